@@ -1,0 +1,137 @@
+/*
+ * onnxhip -- the dense-contraction operators of an ONNX inference graph on one gfx950 GPU.
+ *
+ * The paper's compiler turns an ONNX model into one C-callable entry whose inputs and
+ * outputs mirror the graph's (Section 3, "_dyn_entry_point_main_graph"); tensors are dense
+ * row-major buffers with run-time dimensions (Section 2.2, tensor / memref types), each
+ * operator writes a freshly allocated result (Section 3.1, lowering to krnl), attributes
+ * carry the ONNX defaults (Section 3.2, Listing 6) and output shapes follow from shape
+ * inference (Section 3.4).  This library offers the operators that dominate its two
+ * experiments (Section 4.2: MNIST and ResNet50 -- convolution, pooling, MatMul/Gemm) as
+ * direct calls with the same conventions.
+ *
+ * Conventions for every compute entry point
+ *   - float* / int64_t* tensor arguments are DEVICE pointers (hipMalloc'ed memory of the
+ *     current device); every dims / attribute array is a HOST pointer read before return.
+ *   - Tensors are fp32, dense, row-major, last dimension contiguous; 4-D tensors are NCHW.
+ *   - The caller owns every buffer.  The library never allocates or frees device memory.
+ *   - The output must not overlap any input (ONNX_ERR_ALIAS when the byte ranges intersect).
+ *   - y_dims must equal the inferred output shape (ONNX_ERR_SHAPE otherwise).
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the null stream)
+ *     and the call returns without waiting.  Launch failures are reported as
+ *     ONNX_ERR_DEVICE.
+ *   - All validation happens before anything is enqueued: on any error nothing is written.
+ *   - A zero-sized output returns ONNX_OK without launching.
+ *   - pads are in ONNX order {top, left, bottom, right}.
+ */
+#ifndef ONNXHIP_H
+#define ONNXHIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ONNX_OK = 0,
+    ONNX_ERR_NULL = 1,        /* a required pointer is NULL                                */
+    ONNX_ERR_RANK = 2,        /* a rank outside what the operator accepts                  */
+    ONNX_ERR_SHAPE = 3,       /* dimensions inconsistent with each other or with y_dims    */
+    ONNX_ERR_ATTR = 4,        /* stride/dilation/kernel < 1, pad < 0, pad >= window (pools)*/
+    ONNX_ERR_UNSUPPORTED = 5, /* a valid request this build does not implement             */
+    ONNX_ERR_ALIAS = 6,       /* output overlaps an input                                  */
+    ONNX_ERR_DEVICE = 7       /* the HIP runtime reported an error                         */
+} onnx_status;
+
+typedef enum { ONNX_ACT_NONE = 0, ONNX_ACT_RELU = 1 } onnx_act;
+
+#define ONNX_MAX_RANK 8
+
+/* Message for the most recent non-OK status on the calling thread (static storage). */
+const char* onnx_last_error(void);
+
+/* ---- shape inference (host only; Section 3.4, the shape-inference pass) ------------- */
+
+/* Conv: y = {N, M, OH, OW}, OH = floor((H + pT + pB - ((kH-1)*dH + 1)) / sH) + 1. */
+onnx_status onnx_conv_infer(const int64_t x_dims[4], const int64_t w_dims[4],
+                            const int64_t pads[4], const int64_t strides[2],
+                            const int64_t dilations[2], int64_t group, int64_t y_dims[4]);
+
+/* MaxPool / AveragePool: as Conv per axis; ceil_mode rounds up and drops a last window that
+ * would start beyond the input plus its leading padding. dilations may be NULL (= {1,1}). */
+onnx_status onnx_pool_infer(const int64_t x_dims[4], const int64_t kernel[2],
+                            const int64_t pads[4], const int64_t strides[2],
+                            const int64_t dilations[2], int ceil_mode, int64_t y_dims[4]);
+
+/* MatMul: numpy.matmul shape rules; y_dims must hold max(a_rank, b_rank) entries. */
+onnx_status onnx_matmul_infer(const int64_t* a_dims, int a_rank, const int64_t* b_dims,
+                              int b_rank, int64_t* y_dims, int* y_rank);
+
+/* ---- operators ---------------------------------------------------------------------- */
+
+/*
+ * ONNX Conv, 2-D (Section 4.1 "convolution"; the bulk of ResNet50's time, Section 4.2).
+ *   Y[n,m,oh,ow] = B[m] + sum_{c<C/group, kh, kw}
+ *                    X~[n, g*C/group + c, oh*sH - pT + kh*dH, ow*sW - pL + kw*dW] * W[m,c,kh,kw]
+ * g = m / (M/group), X~ = 0 outside the image, no kernel flip.  Fused epilogue, applied
+ * in this order: + residual[n,m,oh,ow] (NULL = none; same shape as Y), then Relu if
+ * act == ONNX_ACT_RELU.
+ *   X [N,C,H,W]  W [M,C/group,kH,kW]  B [M] or NULL  residual [N,M,OH,OW] or NULL  Y [N,M,OH,OW]
+ * group must divide C and M, w_dims[1]*group == C (ONNX_ERR_SHAPE); strides, dilations >= 1,
+ * pads >= 0 (ONNX_ERR_ATTR).  auto_pad is resolved by the caller into explicit pads.
+ */
+onnx_status onnx_conv(const float* X, const int64_t x_dims[4], const float* W,
+                      const int64_t w_dims[4], const float* B, const int64_t pads[4],
+                      const int64_t strides[2], const int64_t dilations[2], int64_t group,
+                      const float* residual, onnx_act act, float* Y, const int64_t y_dims[4],
+                      void* stream);
+
+/*
+ * ONNX Gemm (Section 3.4: the target of the MatMul+Add rewrite; Section 4.1).
+ *   Y = alpha * op(A) * op(B) + beta * C~,  op(.) = transpose when the flag is non-zero,
+ * op(A) is M x K, op(B) is K x N, C~ is C broadcast to M x N from rank 0 (c_rank = 0, one
+ * element), {N}, {1,N}, {M,1}, {M,N} or {1,1}; C == NULL omits the term.  Relu optional.
+ * a_dims / b_dims are the stored shapes of A and B.
+ */
+onnx_status onnx_gemm(const float* A, const int64_t a_dims[2], const float* B,
+                      const int64_t b_dims[2], const float* C, const int64_t* c_dims, int c_rank,
+                      float alpha, float beta, int transA, int transB, onnx_act act, float* Y,
+                      const int64_t y_dims[2], void* stream);
+
+/*
+ * ONNX MatMul (Section 3.4; MNIST's "matrix multiplication", Section 4.2), numpy.matmul
+ * semantics: a rank-1 A acts as [1,K] and a rank-1 B as [K,1] with the unit dimension
+ * dropped from Y; leading dimensions broadcast right-aligned.  Ranks 1..ONNX_MAX_RANK.
+ */
+onnx_status onnx_matmul(const float* A, const int64_t* a_dims, int a_rank, const float* B,
+                        const int64_t* b_dims, int b_rank, float* Y, const int64_t* y_dims,
+                        int y_rank, void* stream);
+
+/*
+ * ONNX MaxPool, 2-D (Section 4.1 "pooling"; Section 4.2 MNIST "max pooling").
+ * Maximum over the taps inside the image.  Indices (NULL = not wanted) receives, as int64,
+ * the flat row-major position in the whole X tensor of the winning tap; among equal
+ * maxima the first in (kh, kw) scan order wins (storage_order 0).  Pads must be smaller
+ * than the dilated window so that no window is empty (ONNX_ERR_ATTR).
+ */
+onnx_status onnx_maxpool(const float* X, const int64_t x_dims[4], const int64_t kernel[2],
+                         const int64_t pads[4], const int64_t strides[2],
+                         const int64_t dilations[2], int ceil_mode, float* Y, int64_t* Indices,
+                         const int64_t y_dims[4], void* stream);
+
+/*
+ * ONNX AveragePool / GlobalAveragePool, 2-D (Section 4.1 "pooling"; ResNet50's last pool).
+ * Sum of the in-image taps divided by their count (count_include_pad = 0) or by the number
+ * of taps inside the padded image (count_include_pad = 1).  kernel == NULL means global:
+ * window H x W, pads and strides ignored, Y is [N,C,1,1].
+ */
+onnx_status onnx_avgpool(const float* X, const int64_t x_dims[4], const int64_t* kernel,
+                         const int64_t* pads, const int64_t* strides, int ceil_mode,
+                         int count_include_pad, float* Y, const int64_t y_dims[4], void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ONNXHIP_H */

@@ -1,0 +1,170 @@
+"""ctypes binding of libonnxhip.so: same names and argument order as include/onnxhip.h.
+
+Argument marshalling only.  Tensors are torch CUDA tensors (fp32, contiguous); torch supplies
+device memory and the current stream, every operator's arithmetic runs in the library.
+Each compute wrapper allocates the result with torch.empty unless ``out=`` is given.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libonnxhip.so")
+
+ONNX_OK = 0
+ACT_NONE, ACT_RELU = 0, 1
+STATUS_NAMES = {1: "ONNX_ERR_NULL", 2: "ONNX_ERR_RANK", 3: "ONNX_ERR_SHAPE", 4: "ONNX_ERR_ATTR",
+                5: "ONNX_ERR_UNSUPPORTED", 6: "ONNX_ERR_ALIAS", 7: "ONNX_ERR_DEVICE"}
+
+
+class OnnxHipError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("%s: %s" % (STATUS_NAMES.get(status, status), message))
+        self.status = status
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+if not os.path.exists(_LIB_PATH):
+    raise ImportError("libonnxhip.so is not built (%s); run `python -m paper_2008_08272_amd.build` "
+                      "or __graft_entry__.build() first -- there is no fallback path" % _LIB_PATH)
+
+_lib = ctypes.CDLL(_LIB_PATH)
+_i64p = ctypes.POINTER(ctypes.c_int64)
+_vp, _ci, _cf, _c64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_int64
+_lib.onnx_last_error.restype = ctypes.c_char_p
+_lib.onnx_conv_infer.argtypes = [_i64p, _i64p, _i64p, _i64p, _i64p, _c64, _i64p]
+_lib.onnx_pool_infer.argtypes = [_i64p, _i64p, _i64p, _i64p, _i64p, _ci, _i64p]
+_lib.onnx_matmul_infer.argtypes = [_i64p, _ci, _i64p, _ci, _i64p, ctypes.POINTER(_ci)]
+_lib.onnx_conv.argtypes = [_vp, _i64p, _vp, _i64p, _vp, _i64p, _i64p, _i64p, _c64, _vp, _ci, _vp, _i64p, _vp]
+_lib.onnx_gemm.argtypes = [_vp, _i64p, _vp, _i64p, _vp, _i64p, _ci, _cf, _cf, _ci, _ci, _ci, _vp, _i64p, _vp]
+_lib.onnx_matmul.argtypes = [_vp, _i64p, _ci, _vp, _i64p, _ci, _vp, _i64p, _ci, _vp]
+_lib.onnx_maxpool.argtypes = [_vp, _i64p, _i64p, _i64p, _i64p, _i64p, _ci, _vp, _vp, _i64p, _vp]
+_lib.onnx_avgpool.argtypes = [_vp, _i64p, _i64p, _i64p, _i64p, _ci, _ci, _vp, _i64p, _vp]
+for _f in (_lib.onnx_conv_infer, _lib.onnx_pool_infer, _lib.onnx_matmul_infer, _lib.onnx_conv,
+           _lib.onnx_gemm, _lib.onnx_matmul, _lib.onnx_maxpool, _lib.onnx_avgpool):
+    _f.restype = _ci
+
+
+def onnx_last_error():
+    return _lib.onnx_last_error().decode()
+
+
+def _check(st):
+    if st != ONNX_OK:
+        raise OnnxHipError(st, onnx_last_error())
+
+
+def dims(v):
+    v = [int(t) for t in v]
+    return (ctypes.c_int64 * max(len(v), 1))(*v)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _dev(t, name):
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous float32 tensor on the GPU" % name)
+    return t
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def raw():
+    """The loaded ctypes library (for callers that prebuild their argument lists)."""
+    return _lib
+
+
+def onnx_conv_infer(x_dims, w_dims, pads=(0, 0, 0, 0), strides=(1, 1), dilations=(1, 1), group=1):
+    y = (ctypes.c_int64 * 4)()
+    _check(_lib.onnx_conv_infer(dims(x_dims), dims(w_dims), dims(pads), dims(strides), dims(dilations),
+                                int(group), y))
+    return tuple(y)
+
+
+def onnx_pool_infer(x_dims, kernel, pads=(0, 0, 0, 0), strides=(1, 1), dilations=(1, 1), ceil_mode=0):
+    y = (ctypes.c_int64 * 4)()
+    _check(_lib.onnx_pool_infer(dims(x_dims), dims(kernel), dims(pads), dims(strides), dims(dilations),
+                                int(ceil_mode), y))
+    return tuple(y)
+
+
+def onnx_matmul_infer(a_dims, b_dims):
+    y = (ctypes.c_int64 * 16)()
+    r = ctypes.c_int(0)
+    _check(_lib.onnx_matmul_infer(dims(a_dims), len(a_dims), dims(b_dims), len(b_dims), y, ctypes.byref(r)))
+    return tuple(y[i] for i in range(r.value))
+
+
+def onnx_conv(X, W, B=None, pads=(0, 0, 0, 0), strides=(1, 1), dilations=(1, 1), group=1,
+              residual=None, act=ACT_NONE, out=None, stream=None):
+    X, W, B, residual = _dev(X, "X"), _dev(W, "W"), _dev(B, "B"), _dev(residual, "residual")
+    yd = onnx_conv_infer(X.shape, W.shape, pads, strides, dilations, group)
+    Y = torch.empty(yd, dtype=torch.float32, device=X.device) if out is None else _dev(out, "out")
+    _check(_lib.onnx_conv(_ptr(X), dims(X.shape), _ptr(W), dims(W.shape), _ptr(B), dims(pads),
+                          dims(strides), dims(dilations), int(group), _ptr(residual), int(act), _ptr(Y),
+                          dims(Y.shape), _stream(stream)))
+    return Y
+
+
+def onnx_gemm(A, B, C=None, alpha=1.0, beta=1.0, transA=0, transB=0, act=ACT_NONE, out=None, stream=None):
+    A, B, C = _dev(A, "A"), _dev(B, "B"), _dev(C, "C")
+    M = A.shape[1] if transA else A.shape[0]
+    N = B.shape[0] if transB else B.shape[1]
+    Y = torch.empty((M, N), dtype=torch.float32, device=A.device) if out is None else _dev(out, "out")
+    cd, cr = (dims(C.shape), C.dim()) if C is not None else (None, 0)
+    _check(_lib.onnx_gemm(_ptr(A), dims(A.shape), _ptr(B), dims(B.shape), _ptr(C), cd, cr, float(alpha),
+                          float(beta), int(transA), int(transB), int(act), _ptr(Y), dims(Y.shape),
+                          _stream(stream)))
+    return Y
+
+
+def onnx_matmul(A, B, out=None, stream=None):
+    A, B = _dev(A, "A"), _dev(B, "B")
+    yd = onnx_matmul_infer(A.shape, B.shape)
+    Y = torch.empty(yd, dtype=torch.float32, device=A.device) if out is None else _dev(out, "out")
+    _check(_lib.onnx_matmul(_ptr(A), dims(A.shape), A.dim(), _ptr(B), dims(B.shape), B.dim(), _ptr(Y),
+                            dims(Y.shape), Y.dim(), _stream(stream)))
+    return Y
+
+
+def onnx_maxpool(X, kernel, pads=(0, 0, 0, 0), strides=(1, 1), dilations=(1, 1), ceil_mode=0,
+                 want_indices=False, out=None, out_indices=None, stream=None):
+    X = _dev(X, "X")
+    yd = onnx_pool_infer(X.shape, kernel, pads, strides, dilations, ceil_mode)
+    Y = torch.empty(yd, dtype=torch.float32, device=X.device) if out is None else _dev(out, "out")
+    I = out_indices
+    if I is None and want_indices:
+        I = torch.empty(yd, dtype=torch.int64, device=X.device)
+    if I is not None and not (I.is_cuda and I.dtype == torch.int64 and I.is_contiguous()):
+        raise TypeError("indices must be a contiguous int64 tensor on the GPU")
+    _check(_lib.onnx_maxpool(_ptr(X), dims(X.shape), dims(kernel), dims(pads), dims(strides),
+                             dims(dilations), int(ceil_mode), _ptr(Y), _ptr(I), dims(Y.shape),
+                             _stream(stream)))
+    return (Y, I) if I is not None else Y
+
+
+def onnx_avgpool(X, kernel=None, pads=(0, 0, 0, 0), strides=(1, 1), ceil_mode=0, count_include_pad=0,
+                 out=None, stream=None):
+    X = _dev(X, "X")
+    if kernel is None:
+        yd = (X.shape[0], X.shape[1], 1, 1)
+        kp = pp = sp = None
+    else:
+        yd = onnx_pool_infer(X.shape, kernel, pads, strides, (1, 1), ceil_mode)
+        kp, pp, sp = dims(kernel), dims(pads), dims(strides)
+    Y = torch.empty(yd, dtype=torch.float32, device=X.device) if out is None else _dev(out, "out")
+    _check(_lib.onnx_avgpool(_ptr(X), dims(X.shape), kp, pp, sp, int(ceil_mode), int(count_include_pad),
+                             _ptr(Y), dims(Y.shape), _stream(stream)))
+    return Y

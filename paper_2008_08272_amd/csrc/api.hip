@@ -1,0 +1,431 @@
+// C-ABI layer: argument validation, shape inference and kernel selection.
+// Everything here runs on the host; the arithmetic of every operator runs in the kernels.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/onnxhip.h"
+#include "internal.h"
+
+using namespace onnxhip;
+
+namespace {
+
+thread_local char g_err[320] = "";
+
+onnx_status fail(onnx_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+const int64_t kIntMax = 0x7fffffffLL;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// byte ranges [a, a+na) and [b, b+nb) intersect
+inline bool overlaps(const void* a, int64_t na, const void* b, int64_t nb) {
+    if (!a || !b || na <= 0 || nb <= 0) return false;
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + (uintptr_t)nb && b0 < a0 + (uintptr_t)na;
+}
+
+int64_t floordiv(int64_t a, int64_t b) {
+    int64_t q = a / b;
+    if ((a % b != 0) && ((a < 0) != (b < 0))) --q;
+    return q;
+}
+
+// One axis of a sliding window. Returns false when the window exceeds the padded input.
+bool window_extent(int64_t in, int64_t k, int64_t pb, int64_t pe, int64_t s, int64_t d, int ceil_mode,
+                   int64_t* out) {
+    const int64_t eff = (k - 1) * d + 1;
+    const int64_t span = in + pb + pe - eff;
+    if (span < 0) return false;
+    int64_t o;
+    if (ceil_mode) {
+        o = floordiv(span + s - 1, s) + 1;
+        if ((o - 1) * s >= in + pb) --o;     // last window would start past the input: drop it
+    } else {
+        o = floordiv(span, s) + 1;
+    }
+    *out = o;
+    return true;
+}
+
+int pick_tile(int64_t M, int64_t N, int64_t nz) {
+    const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128) * nz;
+    if (M > 64 && N > 64 && t128 >= 192) return TILE_128x128;
+    return TILE_64x64;
+}
+
+void no_batch(ContractionParams& p) {
+    p.nbd = 0;
+    for (int i = 0; i < MAX_BATCH_DIMS; ++i) { p.bdim[i] = 1; p.a_bs[i] = 0; p.b_bs[i] = 0; }
+    p.y_zs = 0;
+    p.bias_zs = 0;
+    p.col_images = 0;
+    p.colP = FastDiv::make(1);
+    p.y_img = 0;
+    p.b_img = 0;
+    memset(&p.ic, 0, sizeof(p.ic));
+    p.ic.kHW = p.ic.kW = p.ic.P = p.ic.OW = FastDiv::make(1);
+}
+
+onnx_status device_status(hipError_t e, const char* what) {
+    if (e == hipSuccess) return ONNX_OK;
+    return fail(ONNX_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* onnx_last_error(void) { return g_err; }
+
+onnx_status onnx_conv_infer(const int64_t x[4], const int64_t w[4], const int64_t pads[4],
+                            const int64_t strides[2], const int64_t dil[2], int64_t group, int64_t y[4]) {
+    if (!x || !w || !pads || !strides || !dil || !y) return fail(ONNX_ERR_NULL, "conv: NULL dims/attribute array");
+    for (int i = 0; i < 4; ++i)
+        if (x[i] < 0 || w[i] < 0) return fail(ONNX_ERR_SHAPE, "conv: negative dimension");
+    if (strides[0] < 1 || strides[1] < 1 || dil[0] < 1 || dil[1] < 1)
+        return fail(ONNX_ERR_ATTR, "conv: strides and dilations must be >= 1");
+    for (int i = 0; i < 4; ++i)
+        if (pads[i] < 0) return fail(ONNX_ERR_ATTR, "conv: pads must be >= 0");
+    if (group < 1) return fail(ONNX_ERR_ATTR, "conv: group must be >= 1");
+    if (w[2] < 1 || w[3] < 1) return fail(ONNX_ERR_SHAPE, "conv: kernel extent must be >= 1");
+    if (x[1] % group || w[0] % group || w[1] * group != x[1])
+        return fail(ONNX_ERR_SHAPE, "conv: group %lld must divide C=%lld and M=%lld, and W dim 1 (%lld) must be C/group",
+                    (long long)group, (long long)x[1], (long long)w[0], (long long)w[1]);
+    int64_t oh, ow;
+    if (!window_extent(x[2], w[2], pads[0], pads[2], strides[0], dil[0], 0, &oh) ||
+        !window_extent(x[3], w[3], pads[1], pads[3], strides[1], dil[1], 0, &ow))
+        return fail(ONNX_ERR_SHAPE, "conv: dilated kernel larger than the padded input");
+    y[0] = x[0]; y[1] = w[0]; y[2] = oh; y[3] = ow;
+    return ONNX_OK;
+}
+
+onnx_status onnx_pool_infer(const int64_t x[4], const int64_t kernel[2], const int64_t pads[4],
+                            const int64_t strides[2], const int64_t dil[2], int ceil_mode, int64_t y[4]) {
+    if (!x || !kernel || !pads || !strides || !y) return fail(ONNX_ERR_NULL, "pool: NULL dims/attribute array");
+    const int64_t d0 = dil ? dil[0] : 1, d1 = dil ? dil[1] : 1;
+    for (int i = 0; i < 4; ++i)
+        if (x[i] < 0) return fail(ONNX_ERR_SHAPE, "pool: negative dimension");
+    if (kernel[0] < 1 || kernel[1] < 1 || strides[0] < 1 || strides[1] < 1 || d0 < 1 || d1 < 1)
+        return fail(ONNX_ERR_ATTR, "pool: kernel, strides and dilations must be >= 1");
+    for (int i = 0; i < 4; ++i)
+        if (pads[i] < 0) return fail(ONNX_ERR_ATTR, "pool: pads must be >= 0");
+    const int64_t e0 = (kernel[0] - 1) * d0 + 1, e1 = (kernel[1] - 1) * d1 + 1;
+    if (pads[0] >= e0 || pads[2] >= e0 || pads[1] >= e1 || pads[3] >= e1)
+        return fail(ONNX_ERR_ATTR, "pool: each pad must be smaller than the (dilated) window");
+    int64_t oh, ow;
+    if (!window_extent(x[2], kernel[0], pads[0], pads[2], strides[0], d0, ceil_mode, &oh) ||
+        !window_extent(x[3], kernel[1], pads[1], pads[3], strides[1], d1, ceil_mode, &ow))
+        return fail(ONNX_ERR_SHAPE, "pool: window larger than the padded input");
+    y[0] = x[0]; y[1] = x[1]; y[2] = oh; y[3] = ow;
+    return ONNX_OK;
+}
+
+onnx_status onnx_matmul_infer(const int64_t* a, int ra, const int64_t* b, int rb, int64_t* y, int* ry) {
+    if (!a || !b || !y || !ry) return fail(ONNX_ERR_NULL, "matmul: NULL dims array");
+    if (ra < 1 || rb < 1 || ra > ONNX_MAX_RANK || rb > ONNX_MAX_RANK)
+        return fail(ONNX_ERR_RANK, "matmul: ranks must be in 1..%d", ONNX_MAX_RANK);
+    for (int i = 0; i < ra; ++i) if (a[i] < 0) return fail(ONNX_ERR_SHAPE, "matmul: negative dimension");
+    for (int i = 0; i < rb; ++i) if (b[i] < 0) return fail(ONNX_ERR_SHAPE, "matmul: negative dimension");
+    const int64_t K = a[ra - 1];
+    const int64_t Kb = rb == 1 ? b[0] : b[rb - 2];
+    if (K != Kb) return fail(ONNX_ERR_SHAPE, "matmul: inner dimensions differ (%lld vs %lld)", (long long)K, (long long)Kb);
+    const int nba = ra >= 2 ? ra - 2 : 0, nbb = rb >= 2 ? rb - 2 : 0;
+    const int nb = nba > nbb ? nba : nbb;
+    int r = 0;
+    for (int t = 0; t < nb; ++t) {
+        const int ia = t - (nb - nba), ib = t - (nb - nbb);
+        const int64_t da = ia >= 0 ? a[ia] : 1, db = ib >= 0 ? b[ib] : 1;
+        if (da != db && da != 1 && db != 1)
+            return fail(ONNX_ERR_SHAPE, "matmul: batch dimensions %lld and %lld do not broadcast", (long long)da, (long long)db);
+        y[r++] = (da == 1) ? db : da;
+    }
+    if (ra >= 2) y[r++] = a[ra - 2];
+    if (rb >= 2) y[r++] = b[rb - 1];
+    *ry = r;
+    return ONNX_OK;
+}
+
+onnx_status onnx_conv(const float* X, const int64_t x_dims[4], const float* W, const int64_t w_dims[4],
+                      const float* B, const int64_t pads[4], const int64_t strides[2],
+                      const int64_t dilations[2], int64_t group, const float* residual, onnx_act act,
+                      float* Y, const int64_t y_dims[4], void* stream) {
+    if (!x_dims || !w_dims || !y_dims) return fail(ONNX_ERR_NULL, "conv: NULL dims array");
+    int64_t yd[4];
+    const onnx_status st = onnx_conv_infer(x_dims, w_dims, pads, strides, dilations, group, yd);
+    if (st != ONNX_OK) return st;
+    for (int i = 0; i < 4; ++i)
+        if (yd[i] != y_dims[i])
+            return fail(ONNX_ERR_SHAPE, "conv: y_dims[%d]=%lld but the inferred extent is %lld", i,
+                        (long long)y_dims[i], (long long)yd[i]);
+    if (act != ONNX_ACT_NONE && act != ONNX_ACT_RELU) return fail(ONNX_ERR_ATTR, "conv: unknown activation");
+    const int64_t N = x_dims[0], C = x_dims[1], H = x_dims[2], Wd = x_dims[3];
+    const int64_t M = w_dims[0], Cg = w_dims[1], kH = w_dims[2], kW = w_dims[3];
+    const int64_t OH = yd[2], OW = yd[3], P = OH * OW;
+    const int64_t ny = N * M * P;
+    if (ny == 0) return ONNX_OK;
+    if (!X || !W || !Y) return fail(ONNX_ERR_NULL, "conv: X, W and Y must not be NULL");
+    const int64_t nx = N * C * H * Wd, nw = M * Cg * kH * kW;
+    if (overlaps(Y, ny * 4, X, nx * 4) || overlaps(Y, ny * 4, W, nw * 4) || overlaps(Y, ny * 4, B, M * 4) ||
+        overlaps(Y, ny * 4, residual, ny * 4))
+        return fail(ONNX_ERR_ALIAS, "conv: Y overlaps an input");
+    const int64_t K = Cg * kH * kW, Mg = M / group, NP = N * P;
+    if (C * H * Wd > kIntMax || M * P > kIntMax || K > kIntMax || pads[0] > kIntMax || pads[1] > kIntMax ||
+        strides[0] > kIntMax || strides[1] > kIntMax || kH * dilations[0] > kIntMax ||
+        kW * dilations[1] > kIntMax || N > kIntMax || group > 32768LL * 65535LL)
+        return fail(ONNX_ERR_UNSUPPORTED, "conv: a single image / filter bank exceeds 2^31 elements");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    WindowGeom g;
+    g.N = (int)N; g.C = (int)C; g.H = (int)H; g.W = (int)Wd; g.OH = (int)OH; g.OW = (int)OW;
+    g.kH = (int)kH; g.kW = (int)kW; g.sH = (int)strides[0]; g.sW = (int)strides[1];
+    g.pT = (int)pads[0]; g.pL = (int)pads[1]; g.pB = (int)pads[2]; g.pR = (int)pads[3];
+    g.dH = (int)dilations[0]; g.dW = (int)dilations[1];
+
+    const bool use_mfma = Mg >= 16 && K >= 8 && NP <= kIntMax;
+    if (!use_mfma)
+        return device_status(launch_conv_direct(X, W, B, residual, Y, g, (int)M, (int)Cg, (int)group,
+                                                act == ONNX_ACT_RELU, s), "conv (direct)");
+
+    ContractionParams p;
+    no_batch(p);
+    p.A = W; p.B = X; p.Y = Y; p.bias = B; p.residual = residual;
+    p.M = (int)Mg; p.N = (int)NP; p.K = (int)K;
+    p.a_ld = K;
+    p.nbd = 1; p.bdim[0] = (int)group; p.a_bs[0] = Mg * K; p.b_bs[0] = Cg * H * Wd;
+    p.y_zs = Mg * P; p.bias_zs = Mg; p.y_rs = P;
+    p.col_images = 1; p.colP = FastDiv::make((uint32_t)P); p.y_img = M * P; p.b_img = C * H * Wd;
+    p.alpha = 1.f; p.beta = 1.f; p.bias_rs = 1; p.bias_cs = 0; p.relu = act == ONNX_ACT_RELU;
+    const bool pointwise = kH == 1 && kW == 1 && strides[0] == 1 && strides[1] == 1 && pads[0] == 0 &&
+                           pads[1] == 0 && pads[2] == 0 && pads[3] == 0;
+    int bkind, vec;
+    const bool a_vec = (K % 4 == 0) && aligned16(W);
+    if (pointwise) {
+        bkind = LOAD_RC;
+        p.b_ld = H * Wd;
+        vec = (a_vec && P % 4 == 0 && aligned16(X)) ? 4 : 1;
+    } else {
+        bkind = LOAD_IM2COL;
+        p.b_ld = 0;
+        vec = a_vec ? 4 : 1;
+        p.ic.C = (int)C; p.ic.H = (int)H; p.ic.W = (int)Wd;
+        p.ic.sH = g.sH; p.ic.sW = g.sW; p.ic.pT = g.pT; p.ic.pL = g.pL; p.ic.dH = g.dH; p.ic.dW = g.dW;
+        p.ic.kHW = FastDiv::make((uint32_t)(kH * kW));
+        p.ic.kW = FastDiv::make((uint32_t)kW);
+        p.ic.P = FastDiv::make((uint32_t)P);
+        p.ic.OW = FastDiv::make((uint32_t)OW);
+        p.ic.image_stride = C * H * Wd;
+    }
+    const int tile = pick_tile(Mg, NP, group);
+    return device_status(launch_contraction(p, LOAD_KC, bkind, vec, tile, (int)group, s), "conv (mfma)");
+}
+
+onnx_status onnx_gemm(const float* A, const int64_t a_dims[2], const float* B, const int64_t b_dims[2],
+                      const float* C, const int64_t* c_dims, int c_rank, float alpha, float beta,
+                      int transA, int transB, onnx_act act, float* Y, const int64_t y_dims[2],
+                      void* stream) {
+    if (!a_dims || !b_dims || !y_dims) return fail(ONNX_ERR_NULL, "gemm: NULL dims array");
+    for (int i = 0; i < 2; ++i)
+        if (a_dims[i] < 0 || b_dims[i] < 0) return fail(ONNX_ERR_SHAPE, "gemm: negative dimension");
+    const int64_t M = transA ? a_dims[1] : a_dims[0], K = transA ? a_dims[0] : a_dims[1];
+    const int64_t Kb = transB ? b_dims[1] : b_dims[0], N = transB ? b_dims[0] : b_dims[1];
+    if (K != Kb) return fail(ONNX_ERR_SHAPE, "gemm: inner dimensions differ (%lld vs %lld)", (long long)K, (long long)Kb);
+    if (y_dims[0] != M || y_dims[1] != N)
+        return fail(ONNX_ERR_SHAPE, "gemm: y_dims is {%lld,%lld} but the result is {%lld,%lld}",
+                    (long long)y_dims[0], (long long)y_dims[1], (long long)M, (long long)N);
+    if (act != ONNX_ACT_NONE && act != ONNX_ACT_RELU) return fail(ONNX_ERR_ATTR, "gemm: unknown activation");
+    int64_t crs = 0, ccs = 0, nc = 0;
+    if (C) {
+        int64_t r = 1, c = 1;
+        if (c_rank < 0 || c_rank > 2) return fail(ONNX_ERR_RANK, "gemm: C must have rank 0, 1 or 2");
+        if (c_rank > 0 && !c_dims) return fail(ONNX_ERR_NULL, "gemm: c_dims is NULL");
+        if (c_rank == 1) c = c_dims[0];
+        if (c_rank == 2) { r = c_dims[0]; c = c_dims[1]; }
+        if (!((r == 1 || r == M) && (c == 1 || c == N)))
+            return fail(ONNX_ERR_SHAPE, "gemm: C {%lld,%lld} does not broadcast to {%lld,%lld}", (long long)r,
+                        (long long)c, (long long)M, (long long)N);
+        crs = (r == 1) ? 0 : c;
+        ccs = (c == 1) ? 0 : 1;
+        nc = r * c;
+    }
+    if (M * N == 0) return ONNX_OK;
+    if (!A || !B || !Y) return fail(ONNX_ERR_NULL, "gemm: A, B and Y must not be NULL");
+    if (overlaps(Y, M * N * 4, A, M * K * 4) || overlaps(Y, M * N * 4, B, K * N * 4) ||
+        overlaps(Y, M * N * 4, C, nc * 4))
+        return fail(ONNX_ERR_ALIAS, "gemm: Y overlaps an input");
+    if (M > kIntMax || N > kIntMax || K > kIntMax) return fail(ONNX_ERR_UNSUPPORTED, "gemm: extent above 2^31-1");
+
+    ContractionParams p;
+    no_batch(p);
+    p.A = A; p.B = B; p.Y = Y; p.bias = C; p.residual = nullptr;
+    p.M = (int)M; p.N = (int)N; p.K = (int)K;
+    p.a_ld = a_dims[1];
+    p.b_ld = b_dims[1];
+    p.y_rs = N;
+    p.alpha = alpha; p.beta = beta; p.bias_rs = crs; p.bias_cs = ccs; p.relu = act == ONNX_ACT_RELU;
+    const int akind = transA ? LOAD_RC : LOAD_KC;
+    const int bkind = transB ? LOAD_KC : LOAD_RC;
+    // 16-byte loads need aligned bases and every row start (and RC row extent) a multiple of 4
+    bool v4 = aligned16(A) && aligned16(B);
+    v4 = v4 && (transA ? (M % 4 == 0) : (K % 4 == 0));
+    v4 = v4 && (transB ? (K % 4 == 0) : (N % 4 == 0));
+    const int tile = pick_tile(M, N, 1);
+    return device_status(launch_contraction(p, akind, bkind, v4 ? 4 : 1, tile, 1, static_cast<hipStream_t>(stream)),
+                         "gemm");
+}
+
+onnx_status onnx_matmul(const float* A, const int64_t* a_dims, int a_rank, const float* B,
+                        const int64_t* b_dims, int b_rank, float* Y, const int64_t* y_dims, int y_rank,
+                        void* stream) {
+    int64_t yd[ONNX_MAX_RANK];
+    int yr = 0;
+    const onnx_status st = onnx_matmul_infer(a_dims, a_rank, b_dims, b_rank, yd, &yr);
+    if (st != ONNX_OK) return st;
+    if (yr != y_rank) return fail(ONNX_ERR_RANK, "matmul: y_rank is %d but the result has rank %d", y_rank, yr);
+    if (yr > 0 && !y_dims) return fail(ONNX_ERR_NULL, "matmul: y_dims is NULL");
+    for (int i = 0; i < yr; ++i)
+        if (yd[i] != y_dims[i])
+            return fail(ONNX_ERR_SHAPE, "matmul: y_dims[%d]=%lld but the inferred extent is %lld", i,
+                        (long long)y_dims[i], (long long)yd[i]);
+    const int64_t M = a_rank >= 2 ? a_dims[a_rank - 2] : 1, K = a_dims[a_rank - 1];
+    const int64_t N = b_rank >= 2 ? b_dims[b_rank - 1] : 1;
+    const int nba = a_rank >= 2 ? a_rank - 2 : 0, nbb = b_rank >= 2 ? b_rank - 2 : 0;
+    const int nb = nba > nbb ? nba : nbb;
+    int64_t nz = 1, na = M * K, nbel = K * N;
+    ContractionParams p;
+    no_batch(p);
+    {
+        int64_t stra = M * K, strb = K * N;
+        for (int t = nb - 1; t >= 0; --t) {
+            const int ia = t - (nb - nba), ib = t - (nb - nbb);
+            const int64_t da = ia >= 0 ? a_dims[ia] : 1, db = ib >= 0 ? b_dims[ib] : 1;
+            const int64_t dy = (da == 1) ? db : da;
+            if (dy > kIntMax) return fail(ONNX_ERR_UNSUPPORTED, "matmul: batch extent above 2^31-1");
+            p.bdim[t] = (int)dy;
+            p.a_bs[t] = (da == 1) ? 0 : stra;
+            p.b_bs[t] = (db == 1) ? 0 : strb;
+            stra *= da; strb *= db;
+            nz *= dy;
+        }
+        na = stra; nbel = strb;
+        p.nbd = nb;
+    }
+    if (nz * M * N == 0) return ONNX_OK;
+    if (!A || !B || !Y) return fail(ONNX_ERR_NULL, "matmul: A, B and Y must not be NULL");
+    const int64_t ny = nz * M * N;
+    if (overlaps(Y, ny * 4, A, na * 4) || overlaps(Y, ny * 4, B, nbel * 4))
+        return fail(ONNX_ERR_ALIAS, "matmul: Y overlaps an input");
+    if (M > kIntMax || N > kIntMax || K > kIntMax) return fail(ONNX_ERR_UNSUPPORTED, "matmul: extent above 2^31-1");
+
+    p.A = A; p.B = B; p.Y = Y; p.bias = nullptr; p.residual = nullptr;
+    int64_t Meff = M;
+    // When B is shared by every batch entry and A's batch is dense, the whole product is one
+    // matrix product with batch*M rows.
+    bool b_shared = true, a_dense = true;
+    {
+        int64_t expect = M * K;
+        for (int t = nb - 1; t >= 0; --t) {
+            if (p.b_bs[t] != 0 && p.bdim[t] != 1) b_shared = false;
+            if (p.bdim[t] != 1 && p.a_bs[t] != expect) a_dense = false;
+            expect *= p.bdim[t];
+        }
+    }
+    if (nz > 1 && b_shared && a_dense && nz * M <= kIntMax) {
+        Meff = nz * M;
+        nz = 1;
+        p.nbd = 0;
+    }
+    if (nz > 32768LL * 65535LL) return fail(ONNX_ERR_UNSUPPORTED, "matmul: too many batch entries");
+    p.M = (int)Meff; p.N = (int)N; p.K = (int)K;
+    p.a_ld = K; p.b_ld = N; p.y_rs = N; p.y_zs = M * N;
+    p.alpha = 1.f; p.beta = 0.f; p.bias_rs = 0; p.bias_cs = 0; p.relu = 0;
+    const bool v4 = aligned16(A) && aligned16(B) && K % 4 == 0 && N % 4 == 0;
+    const int tile = pick_tile(Meff, N, nz);
+    return device_status(launch_contraction(p, LOAD_KC, LOAD_RC, v4 ? 4 : 1, tile, (int)nz,
+                                            static_cast<hipStream_t>(stream)), "matmul");
+}
+
+onnx_status onnx_maxpool(const float* X, const int64_t x_dims[4], const int64_t kernel[2],
+                         const int64_t pads[4], const int64_t strides[2], const int64_t dilations[2],
+                         int ceil_mode, float* Y, int64_t* Indices, const int64_t y_dims[4], void* stream) {
+    if (!x_dims || !y_dims) return fail(ONNX_ERR_NULL, "maxpool: NULL dims array");
+    int64_t yd[4];
+    const onnx_status st = onnx_pool_infer(x_dims, kernel, pads, strides, dilations, ceil_mode, yd);
+    if (st != ONNX_OK) return st;
+    for (int i = 0; i < 4; ++i)
+        if (yd[i] != y_dims[i])
+            return fail(ONNX_ERR_SHAPE, "maxpool: y_dims[%d]=%lld but the inferred extent is %lld", i,
+                        (long long)y_dims[i], (long long)yd[i]);
+    const int64_t ny = yd[0] * yd[1] * yd[2] * yd[3], nx = x_dims[0] * x_dims[1] * x_dims[2] * x_dims[3];
+    if (ny == 0) return ONNX_OK;
+    if (!X || !Y) return fail(ONNX_ERR_NULL, "maxpool: X and Y must not be NULL");
+    if (overlaps(Y, ny * 4, X, nx * 4) || overlaps(Indices, ny * 8, X, nx * 4) || overlaps(Indices, ny * 8, Y, ny * 4))
+        return fail(ONNX_ERR_ALIAS, "maxpool: outputs overlap X or each other");
+    const int64_t d0 = dilations ? dilations[0] : 1, d1 = dilations ? dilations[1] : 1;
+    if (x_dims[2] * x_dims[3] > kIntMax || x_dims[0] > kIntMax || x_dims[1] > kIntMax ||
+        x_dims[1] * yd[2] * yd[3] >= (1LL << 30) || kernel[0] * d0 > kIntMax || kernel[1] * d1 > kIntMax ||
+        strides[0] > kIntMax || strides[1] > kIntMax)
+        return fail(ONNX_ERR_UNSUPPORTED, "maxpool: one image exceeds the 32-bit index range");
+    WindowGeom g;
+    g.N = (int)x_dims[0]; g.C = (int)x_dims[1]; g.H = (int)x_dims[2]; g.W = (int)x_dims[3];
+    g.OH = (int)yd[2]; g.OW = (int)yd[3]; g.kH = (int)kernel[0]; g.kW = (int)kernel[1];
+    g.sH = (int)strides[0]; g.sW = (int)strides[1]; g.pT = (int)pads[0]; g.pL = (int)pads[1];
+    g.pB = (int)pads[2]; g.pR = (int)pads[3]; g.dH = (int)d0; g.dW = (int)d1;
+    return device_status(launch_maxpool(X, Y, Indices, g, static_cast<hipStream_t>(stream)), "maxpool");
+}
+
+onnx_status onnx_avgpool(const float* X, const int64_t x_dims[4], const int64_t* kernel, const int64_t* pads,
+                         const int64_t* strides, int ceil_mode, int count_include_pad, float* Y,
+                         const int64_t y_dims[4], void* stream) {
+    if (!x_dims || !y_dims) return fail(ONNX_ERR_NULL, "avgpool: NULL dims array");
+    for (int i = 0; i < 4; ++i)
+        if (x_dims[i] < 0) return fail(ONNX_ERR_SHAPE, "avgpool: negative dimension");
+    const int64_t nx = x_dims[0] * x_dims[1] * x_dims[2] * x_dims[3];
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!kernel) {
+        if (x_dims[2] * x_dims[3] == 0 && x_dims[0] * x_dims[1] != 0)
+            return fail(ONNX_ERR_SHAPE, "avgpool: global pool over an empty plane");
+        if (y_dims[0] != x_dims[0] || y_dims[1] != x_dims[1] || y_dims[2] != 1 || y_dims[3] != 1)
+            return fail(ONNX_ERR_SHAPE, "avgpool: a global pool yields {N,C,1,1}");
+        const int64_t planes = x_dims[0] * x_dims[1];
+        if (planes == 0) return ONNX_OK;
+        if (!X || !Y) return fail(ONNX_ERR_NULL, "avgpool: X and Y must not be NULL");
+        if (overlaps(Y, planes * 4, X, nx * 4)) return fail(ONNX_ERR_ALIAS, "avgpool: Y overlaps X");
+        if (x_dims[2] * x_dims[3] > kIntMax) return fail(ONNX_ERR_UNSUPPORTED, "avgpool: plane above 2^31-1 elements");
+        return device_status(launch_global_avgpool(X, Y, planes, (int)(x_dims[2] * x_dims[3]), s),
+                             "avgpool (global)");
+    }
+    const int64_t zero4[4] = {0, 0, 0, 0}, one2[2] = {1, 1};
+    if (!pads) pads = zero4;
+    if (!strides) strides = one2;
+    int64_t yd[4];
+    const onnx_status st = onnx_pool_infer(x_dims, kernel, pads, strides, nullptr, ceil_mode, yd);
+    if (st != ONNX_OK) return st;
+    for (int i = 0; i < 4; ++i)
+        if (yd[i] != y_dims[i])
+            return fail(ONNX_ERR_SHAPE, "avgpool: y_dims[%d]=%lld but the inferred extent is %lld", i,
+                        (long long)y_dims[i], (long long)yd[i]);
+    const int64_t ny = yd[0] * yd[1] * yd[2] * yd[3];
+    if (ny == 0) return ONNX_OK;
+    if (!X || !Y) return fail(ONNX_ERR_NULL, "avgpool: X and Y must not be NULL");
+    if (overlaps(Y, ny * 4, X, nx * 4)) return fail(ONNX_ERR_ALIAS, "avgpool: Y overlaps X");
+    if (x_dims[2] * x_dims[3] > kIntMax || x_dims[0] > kIntMax || x_dims[1] > kIntMax ||
+        x_dims[1] * yd[2] * yd[3] >= (1LL << 30) || kernel[0] > kIntMax || kernel[1] > kIntMax ||
+        strides[0] > kIntMax || strides[1] > kIntMax)
+        return fail(ONNX_ERR_UNSUPPORTED, "avgpool: one image exceeds the 32-bit index range");
+    WindowGeom g;
+    g.N = (int)x_dims[0]; g.C = (int)x_dims[1]; g.H = (int)x_dims[2]; g.W = (int)x_dims[3];
+    g.OH = (int)yd[2]; g.OW = (int)yd[3]; g.kH = (int)kernel[0]; g.kW = (int)kernel[1];
+    g.sH = (int)strides[0]; g.sW = (int)strides[1]; g.pT = (int)pads[0]; g.pL = (int)pads[1];
+    g.pB = (int)pads[2]; g.pR = (int)pads[3]; g.dH = 1; g.dW = 1;
+    return device_status(launch_avgpool(X, Y, g, count_include_pad, s), "avgpool");
+}
+
+}  // extern "C"

@@ -1,0 +1,45 @@
+// Instances of the matrix-core contraction kernel and their launcher.
+#include "internal.h"
+
+namespace onnxhip {
+
+template <int BM, int BN, int WM, int WN, int AK, int BKIND, int VEC>
+static hipError_t launch_one(ContractionParams& p, int nz, hipStream_t stream) {
+    p.tiles_m = (p.M + BM - 1) / BM;
+    p.tiles_n = (p.N + BN - 1) / BN;
+    p.nz = nz;
+    const unsigned gz = nz < 32768 ? (unsigned)nz : 32768u;
+    const unsigned gy = ((unsigned)nz + gz - 1) / gz;
+    if ((int64_t)p.tiles_m * p.tiles_n > 0x7fffffffLL || gy > 65535u) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(p.tiles_m * p.tiles_n), gy, gz);
+    hipLaunchKernelGGL((contraction_kernel<BM, BN, WM, WN, AK, BKIND, VEC>), grid, dim3(NTHREADS), 0,
+                       stream, p);
+    return hipGetLastError();
+}
+
+template <int AK, int BKIND, int VEC>
+static hipError_t launch_tile(ContractionParams& p, int tile, int nz, hipStream_t stream) {
+    switch (tile) {
+        case TILE_128x128: return launch_one<128, 128, 2, 2, AK, BKIND, VEC>(p, nz, stream);
+        case TILE_64x64: return launch_one<64, 64, 2, 2, AK, BKIND, VEC>(p, nz, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_contraction(ContractionParams& p, int akind, int bkind, int vec, int tile, int nz,
+                              hipStream_t stream) {
+    if (vec != 1 && vec != 4) return hipErrorInvalidValue;
+#define ONNXHIP_CASE(AK, BKK)                                                    \
+    if (akind == AK && bkind == BKK)                                             \
+        return vec == 4 ? launch_tile<AK, BKK, 4>(p, tile, nz, stream)           \
+                        : launch_tile<AK, BKK, 1>(p, tile, nz, stream);
+    ONNXHIP_CASE(LOAD_KC, LOAD_KC)
+    ONNXHIP_CASE(LOAD_KC, LOAD_RC)
+    ONNXHIP_CASE(LOAD_RC, LOAD_KC)
+    ONNXHIP_CASE(LOAD_RC, LOAD_RC)
+    ONNXHIP_CASE(LOAD_KC, LOAD_IM2COL)
+#undef ONNXHIP_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace onnxhip

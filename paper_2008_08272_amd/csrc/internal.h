@@ -1,0 +1,36 @@
+// Internal launch interface between the C-ABI layer and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "contraction.h"
+
+namespace onnxhip {
+
+enum TileShape { TILE_128x128 = 0, TILE_64x64 = 1, TILE_COUNT };
+
+inline int tile_bm(int t) { return t == TILE_128x128 ? 128 : 64; }
+inline int tile_bn(int t) { return t == TILE_128x128 ? 128 : 64; }
+
+// Fills tiles_m / tiles_n of `p` for the chosen tile and enqueues the kernel instance for
+// (akind, bkind, vec).  nz = number of z-slices (grid.z).
+hipError_t launch_contraction(ContractionParams& p, int akind, int bkind, int vec, int tile,
+                              int nz, hipStream_t stream);
+
+struct WindowGeom {
+    int N, C, H, W, OH, OW;
+    int kH, kW, sH, sW, pT, pL, pB, pR, dH, dW;
+};
+
+// Direct (one thread per output) convolution for shapes the matrix cores cannot use well:
+// depthwise and other tiny-K / tiny-M groups.
+hipError_t launch_conv_direct(const float* X, const float* W, const float* B, const float* residual,
+                              float* Y, const WindowGeom& g, int M, int Cg, int group, int relu,
+                              hipStream_t stream);
+hipError_t launch_maxpool(const float* X, float* Y, int64_t* indices, const WindowGeom& g,
+                          hipStream_t stream);
+hipError_t launch_avgpool(const float* X, float* Y, const WindowGeom& g, int count_include_pad,
+                          hipStream_t stream);
+hipError_t launch_global_avgpool(const float* X, float* Y, int64_t planes, int HW, hipStream_t stream);
+
+}  // namespace onnxhip

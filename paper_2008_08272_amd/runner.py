@@ -1,0 +1,96 @@
+"""Tiny model runner: chains library calls for a workload graph.
+
+The analogue of the single entry function a compiled model exports in the paper (Section 3):
+the graph's constant inputs are uploaded once, every activation buffer is allocated once, and
+``run()`` enqueues one library call per node on one stream with no host synchronisation in
+between.  Reshape is a view of dense row-major data and costs nothing.  All arithmetic
+happens inside the library's kernels; this module only prepares argument lists.
+"""
+import ctypes
+
+import torch
+
+from . import binding as B
+
+
+class GraphRunner:
+    def __init__(self, model, device="cuda:0", keep_all=True):
+        self.device = torch.device(device)
+        self.model = model
+        self.t = {}
+        for k, v in list(model["inputs"].items()) + list(model["weights"].items()):
+            self.t[k] = torch.from_numpy(v).to(self.device).contiguous()
+        self.calls = []
+        self._keepalive = []
+        lib = B.raw()
+        for nd in model["graph"]:
+            op = nd["op"]
+            if op == "conv":
+                x, w = self.t[nd["x"]], self.t[nd["w"]]
+                yd = B.onnx_conv_infer(x.shape, w.shape, nd["pads"], nd["strides"], nd["dilations"], nd["group"])
+                y = self._new(nd["y"], yd)
+                b = self.t[nd["b"]] if nd["b"] else None
+                r = self.t[nd["residual"]] if nd["residual"] else None
+                args = [B._ptr(x), B.dims(x.shape), B._ptr(w), B.dims(w.shape), B._ptr(b), B.dims(nd["pads"]),
+                        B.dims(nd["strides"]), B.dims(nd["dilations"]), int(nd["group"]), B._ptr(r),
+                        B.ACT_RELU if nd["relu"] else B.ACT_NONE, B._ptr(y), B.dims(y.shape), None]
+                self.calls.append((lib.onnx_conv, args))
+            elif op == "maxpool":
+                x = self.t[nd["x"]]
+                yd = B.onnx_pool_infer(x.shape, nd["kernel"], nd["pads"], nd["strides"], nd["dilations"], nd["ceil_mode"])
+                y = self._new(nd["y"], yd)
+                args = [B._ptr(x), B.dims(x.shape), B.dims(nd["kernel"]), B.dims(nd["pads"]), B.dims(nd["strides"]),
+                        B.dims(nd["dilations"]), int(nd["ceil_mode"]), B._ptr(y), None, B.dims(y.shape), None]
+                self.calls.append((lib.onnx_maxpool, args))
+            elif op == "avgpool":
+                x = self.t[nd["x"]]
+                if nd["kernel"] is None:
+                    yd = (x.shape[0], x.shape[1], 1, 1)
+                    kp = pp = sp = None
+                else:
+                    yd = B.onnx_pool_infer(x.shape, nd["kernel"], nd["pads"], nd["strides"], (1, 1), nd["ceil_mode"])
+                    kp, pp, sp = B.dims(nd["kernel"]), B.dims(nd["pads"]), B.dims(nd["strides"])
+                y = self._new(nd["y"], yd)
+                args = [B._ptr(x), B.dims(x.shape), kp, pp, sp, int(nd["ceil_mode"]), int(nd["count_include_pad"]),
+                        B._ptr(y), B.dims(y.shape), None]
+                self.calls.append((lib.onnx_avgpool, args))
+            elif op == "reshape":
+                self.t[nd["y"]] = self.t[nd["x"]].view(nd["shape"])
+            elif op == "gemm":
+                a, b = self.t[nd["a"]], self.t[nd["b"]]
+                c = self.t[nd["c"]] if nd["c"] else None
+                m = a.shape[1] if nd["transA"] else a.shape[0]
+                n = b.shape[0] if nd["transB"] else b.shape[1]
+                y = self._new(nd["y"], (m, n))
+                cd, cr = (B.dims(c.shape), c.dim()) if c is not None else (None, 0)
+                args = [B._ptr(a), B.dims(a.shape), B._ptr(b), B.dims(b.shape), B._ptr(c), cd, cr,
+                        float(nd["alpha"]), float(nd["beta"]), int(nd["transA"]), int(nd["transB"]),
+                        B.ACT_RELU if nd["relu"] else B.ACT_NONE, B._ptr(y), B.dims(y.shape), None]
+                self.calls.append((lib.onnx_gemm, args))
+            elif op == "matmul":
+                a, b = self.t[nd["a"]], self.t[nd["b"]]
+                yd = B.onnx_matmul_infer(a.shape, b.shape)
+                y = self._new(nd["y"], yd)
+                args = [B._ptr(a), B.dims(a.shape), a.dim(), B._ptr(b), B.dims(b.shape), b.dim(), B._ptr(y),
+                        B.dims(y.shape), y.dim(), None]
+                self.calls.append((lib.onnx_matmul, args))
+            else:
+                raise ValueError("unknown node op %r" % (op,))
+        self.output = self.t[model["output"]]
+
+    def _new(self, name, shape):
+        y = torch.empty(tuple(int(s) for s in shape), dtype=torch.float32, device=self.device)
+        self.t[name] = y
+        return y
+
+    def set_input(self, name, array):
+        self.t[name].copy_(torch.from_numpy(array))
+
+    def run(self, stream=None):
+        sp = B._stream(stream)
+        for fn, args in self.calls:
+            args[-1] = sp
+            st = fn(*args)
+            if st != B.ONNX_OK:
+                raise B.OnnxHipError(st, B.onnx_last_error())
+        return self.output

@@ -1,0 +1,129 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, infers shapes like the oracle does, and rejects bad arguments before any
+device work (so these calls are safe without a GPU)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2008_08272_amd import binding
+    return binding
+
+
+def test_library_exports_every_declared_symbol(B):
+    text = open(os.path.join(ROOT, "include", "onnxhip.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(onnx_[a-z_0-9]+)\s*\(", text))
+    assert {"onnx_conv", "onnx_gemm", "onnx_matmul", "onnx_maxpool", "onnx_avgpool", "onnx_conv_infer",
+            "onnx_pool_infer", "onnx_matmul_infer", "onnx_last_error"} <= names
+    lib = ctypes.CDLL(B.lib_path())
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+def test_window_inference_agrees_with_oracle(B):
+    rng = np.random.default_rng(1)
+    for _ in range(300):
+        h, k, s, d = (int(rng.integers(1, 40)), int(rng.integers(1, 6)), int(rng.integers(1, 4)),
+                      int(rng.integers(1, 4)))
+        eff = (k - 1) * d + 1
+        pb, pe = int(rng.integers(0, eff)), int(rng.integers(0, eff))
+        ceil = int(rng.integers(0, 2))
+        want = oracle.window_out(h, k, pb, pe, s, d, ceil)
+        if want < 0:
+            with pytest.raises(B.OnnxHipError):
+                B.onnx_pool_infer((1, 1, h, h), (k, k), (pb, pb, pe, pe), (s, s), (d, d), ceil)
+            continue
+        got = B.onnx_pool_infer((2, 3, h, h), (k, k), (pb, pb, pe, pe), (s, s), (d, d), ceil)
+        assert got == (2, 3, want, want)
+        if not ceil:
+            assert B.onnx_conv_infer((2, 4, h, h), (6, 2, k, k), (pb, pb, pe, pe), (s, s), (d, d), 2) == (2, 6, want, want)
+
+
+def test_matmul_inference_agrees_with_oracle_and_numpy(B):
+    cases = [((5, 4), (4, 6)), ((3, 2, 5, 4), (2, 4, 6)), ((4,), (4, 6)), ((5, 4), (4,)), ((4,), (4,)),
+             ((3, 1, 5, 4), (1, 2, 4, 6)), ((4,), (2, 3, 4, 6)), ((8, 12, 512, 64), (8, 12, 64, 512))]
+    for a, b in cases:
+        assert B.onnx_matmul_infer(a, b) == oracle.matmul_shape(a, b)
+        assert B.onnx_matmul_infer(a, b) == np.matmul(np.zeros(a, np.int8), np.zeros(b, np.int8)).shape
+    for a, b, st in [((3, 4), (5, 6), 3), ((2, 3, 4), (3, 4, 5), 3), ((1,) * 9, (1, 1), 2)]:
+        with pytest.raises(B.OnnxHipError) as e:
+            B.onnx_matmul_infer(a, b)
+        assert e.value.status == st
+
+
+def test_conv_attribute_errors(B):
+    X, W = (1, 4, 5, 5), (6, 2, 3, 3)
+    for kw, st in [(dict(group=3), 3), (dict(group=2, strides=(0, 1)), 4), (dict(group=2, dilations=(1, 0)), 4),
+                   (dict(group=2, pads=(-1, 0, 0, 0)), 4), (dict(group=0), 4)]:
+        with pytest.raises(B.OnnxHipError) as e:
+            B.onnx_conv_infer(X, W, **kw)
+        assert e.value.status == st, kw
+    with pytest.raises(B.OnnxHipError) as e:
+        B.onnx_conv_infer((1, 4, 5, 5), (6, 4, 7, 7))
+    assert e.value.status == 3
+    with pytest.raises(B.OnnxHipError) as e:
+        B.onnx_pool_infer((1, 1, 8, 8), (2, 2), (2, 0, 0, 0), (1, 1))        # a window of padding only
+    assert e.value.status == 4
+
+
+def test_compute_entry_points_validate_before_touching_the_device(B):
+    lib = B.raw()
+    d = B.dims
+    fake = ctypes.c_void_p(4096)      # never dereferenced: every call below fails validation first
+    # NULL tensor
+    st = lib.onnx_gemm(None, d((2, 3)), fake, d((3, 4)), None, None, 0, 1.0, 1.0, 0, 0, 0, fake, d((2, 4)), None)
+    assert st == 1 and "NULL" in B.onnx_last_error()
+    # y_dims mismatch
+    st = lib.onnx_gemm(fake, d((2, 3)), fake, d((3, 4)), None, None, 0, 1.0, 1.0, 0, 0, 0, fake, d((2, 5)), None)
+    assert st == 3
+    # C that does not broadcast
+    st = lib.onnx_gemm(fake, d((2, 3)), fake, d((3, 4)), fake, d((3, 4)), 2, 1.0, 1.0, 0, 0, 0, fake, d((2, 4)), None)
+    assert st == 3
+    # conv: wrong y_dims, bad activation
+    args = [fake, d((1, 4, 8, 8)), fake, d((6, 4, 3, 3)), None, d((1, 1, 1, 1)), d((1, 1)), d((1, 1)), 1, None, 0,
+            fake, d((1, 6, 8, 7)), None]
+    assert lib.onnx_conv(*args) == 3
+    args[12] = d((1, 6, 8, 8)); args[10] = 9
+    assert lib.onnx_conv(*args) == 4
+    # output aliasing an input
+    a = ctypes.c_void_p(1 << 20)
+    st = lib.onnx_matmul(a, d((4, 4)), 2, fake, d((4, 4)), 2, ctypes.c_void_p((1 << 20) + 32), d((4, 4)), 2, None)
+    assert st == 6
+    # pools
+    st = lib.onnx_maxpool(fake, d((1, 1, 8, 8)), d((2, 2)), d((0, 0, 0, 0)), d((2, 2)), d((1, 1)), 0, fake, None,
+                          d((1, 1, 5, 4)), None)
+    assert st == 3
+    st = lib.onnx_avgpool(fake, d((1, 2, 8, 8)), None, None, None, 0, 0, fake, d((1, 2, 2, 1)), None)
+    assert st == 3
+    # matmul rank mismatch of y
+    st = lib.onnx_matmul(fake, d((4, 4)), 2, fake, d((4, 4)), 2, ctypes.c_void_p(1 << 22), d((4, 4, 1)), 3, None)
+    assert st == 2
+
+
+def test_fast_division_constants():
+    """The kernels divide by run-time constants with a multiply-shift; check the host-side
+    constant generation the same way the device code evaluates it."""
+    def make(d):
+        s = d.bit_length() - 1
+        pow2 = (d & (d - 1)) == 0
+        m = 0 if pow2 else ((1 << (32 + s)) // d) + 1
+        assert m < (1 << 32)
+        return m, s, pow2
+
+    rng = np.random.default_rng(2)
+    ds = [1, 2, 3, 5, 7, 9, 25, 49, 147, 196, 784, 3136, 12544, 4608, 2 ** 20, 2 ** 31 - 1, 1000003]
+    for d in ds:
+        m, s, pow2 = make(d)
+        ns = np.concatenate([rng.integers(0, 2 ** 31, 2000), [0, 1, d - 1, d, d + 1, 2 ** 31 - 1]]).astype(np.uint64)
+        q = (ns >> np.uint64(s)) if pow2 else (((ns * np.uint64(m)) >> np.uint64(32)) >> np.uint64(s))
+        assert np.array_equal(q, ns // np.uint64(d)), d

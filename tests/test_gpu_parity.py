@@ -1,0 +1,405 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, same seeded inputs.
+
+Floating outputs: max_i |g_i - r_i| / max(|r_i|, rms(r)) <= 1e-4 against the fp64 oracle, and
+the a-priori component-wise fp32 rounding bound where the oracle supplies the scale.
+MaxPool values and indices, delta-kernel convolutions and small-integer data: bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from util import REL_TOL, rel_err, within_rounding_bound
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2008_08272_amd as p
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return p
+
+
+def dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def announce(*what):
+    print("CASE", *what, flush=True)
+
+
+# ------------------------------------------------------------------------------ Gemm
+
+GEMM_SHAPES = [
+    # M, N, K : several tiles plus ragged tails in every dimension, both tile shapes, vec4 and scalar
+    (1, 1, 1), (3, 5, 7), (64, 64, 16), (65, 63, 17), (200, 150, 70), (130, 257, 129),
+    (256, 384, 64), (300, 520, 36), (1, 1000, 2048), (32, 1000, 2048), (513, 1025, 40),
+    (2048, 1536, 20),
+]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+@pytest.mark.parametrize("transA,transB", [(0, 0), (0, 1), (1, 0), (1, 1)])
+def test_gemm_matches_oracle(lib, M, N, K, transA, transB):
+    announce("gemm", M, N, K, transA, transB)
+    rng = np.random.default_rng([M, N, K, transA, transB])
+    A = rng.uniform(-1, 1, (K, M) if transA else (M, K)).astype(np.float32)
+    B = rng.uniform(-1, 1, (N, K) if transB else (K, N)).astype(np.float32)
+    cshape = [(1, N), (M, 1), (M, N), (N,), (), (1, 1)][(M + N + K + transA) % 6]
+    C = rng.uniform(-1, 1, cshape).astype(np.float32)
+    alpha, beta = 0.75, -1.25
+    relu = bool((M + K) % 2)
+    ref, S = oracle.gemm(A, B, C, alpha, beta, transA, transB, relu=relu, want_scale=True)
+    got = host(lib.onnx_gemm(dev(A), dev(B), dev(C), alpha, beta, transA, transB, act=int(relu)))
+    assert got.shape == ref.shape
+    assert rel_err(got, ref) <= REL_TOL
+    if not relu:
+        assert within_rounding_bound(got, ref, S, K + 2)
+
+
+def test_gemm_no_bias_and_defaults(lib):
+    announce("gemm no bias")
+    rng = np.random.default_rng(3)
+    A = rng.uniform(-1, 1, (70, 90)).astype(np.float32)
+    B = rng.uniform(-1, 1, (90, 50)).astype(np.float32)
+    got = host(lib.onnx_gemm(dev(A), dev(B)))
+    assert rel_err(got, oracle.gemm(A, B)) <= REL_TOL
+
+
+@pytest.mark.parametrize("M,N,K", [(257, 383, 96), (128, 128, 512), (1000, 70, 33)])
+def test_gemm_small_integers_bit_exact(lib, M, N, K):
+    """With inputs in {-4..4} every partial sum is an exactly representable integer, so any
+    summation order gives the same bits: a dropped, duplicated or misplaced k shows up."""
+    announce("gemm integer", M, N, K)
+    rng = np.random.default_rng([M, N, K])
+    A = rng.integers(-4, 5, (M, K)).astype(np.float32)
+    B = rng.integers(-4, 5, (N, K)).astype(np.float32)
+    C = rng.integers(-4, 5, (1, N)).astype(np.float32)
+    ref = oracle.gemm(A, B, C, 1.0, 1.0, 0, 1)
+    got = host(lib.onnx_gemm(dev(A), dev(B), dev(C), 1.0, 1.0, 0, 1))
+    assert np.array_equal(got.astype(np.float64), ref)
+    Bt = np.ascontiguousarray(B.T)
+    got2 = host(lib.onnx_gemm(dev(np.ascontiguousarray(A.T)), dev(Bt), dev(C), 1.0, 1.0, 1, 0))
+    assert np.array_equal(got2.astype(np.float64), ref)
+
+
+def test_gemm_sweep_1024_full(lib):
+    announce("gemm sweep 1024")
+    c = workloads.gemm_case(1024)
+    ref, S = oracle.gemm(c["A"], c["B"], c["C"], 1.0, 1.0, 0, 1, want_scale=True)
+    got = host(lib.onnx_gemm(dev(c["A"]), dev(c["B"]), dev(c["C"]), 1.0, 1.0, 0, 1))
+    assert rel_err(got, ref) <= REL_TOL
+    assert within_rounding_bound(got, ref, S, 1024 + 2)
+
+
+@pytest.mark.parametrize("n", [2048, 4096])
+def test_gemm_sweep_full_size_sampled_rows(lib, n):
+    """Full-size launch as benchmarked; the oracle evaluates a sample of whole rows (a Gemm
+    restricted to some rows of A is the same definition)."""
+    announce("gemm sweep sampled", n)
+    c = workloads.gemm_case(n)
+    got = host(lib.onnx_gemm(dev(c["A"]), dev(c["B"]), dev(c["C"]), 1.0, 1.0, 0, 1))
+    rng = np.random.default_rng(n)
+    rows = np.unique(np.concatenate([[0, 1, 127, 128, n - 1], rng.integers(0, n, 27)]))
+    ref, S = oracle.gemm(c["A"][rows], c["B"], c["C"], 1.0, 1.0, 0, 1, want_scale=True)
+    assert rel_err(got[rows], ref) <= REL_TOL
+    assert within_rounding_bound(got[rows], ref, S, n + 2)
+    # with Relu (the fused epilogue), same launch shape
+    got_r = host(lib.onnx_gemm(dev(c["A"]), dev(c["B"]), dev(c["C"]), 1.0, 1.0, 0, 1, act=1))
+    assert rel_err(got_r[rows], np.maximum(ref, 0)) <= REL_TOL
+
+
+# ------------------------------------------------------------------------------ MatMul
+
+@pytest.mark.parametrize("sa,sb", [
+    ((5, 4), (4, 6)), ((3, 2, 50, 40), (2, 40, 60)), ((2, 70, 33), (3, 1, 33, 65)), ((40,), (40, 6)),
+    ((50, 40), (40,)), ((40,), (40,)), ((3, 1, 5, 4), (1, 2, 4, 6)), ((2, 3, 130, 36), (36, 200)),
+    ((4,), (2, 3, 4, 6)), ((2, 3, 5, 4), (4,)), ((2, 2, 2, 2, 2, 9, 8), (2, 1, 2, 8, 7)),
+])
+def test_matmul_matches_oracle(lib, sa, sb):
+    announce("matmul", sa, sb)
+    rng = np.random.default_rng(len(sa) * 100 + len(sb))
+    A = rng.uniform(-1, 1, sa).astype(np.float32)
+    B = rng.uniform(-1, 1, sb).astype(np.float32)
+    ref = oracle.matmul(A, B)
+    got = host(lib.onnx_matmul(dev(A), dev(B)))
+    assert got.shape == ref.shape
+    assert rel_err(got, ref) <= REL_TOL
+
+
+def test_matmul_attribute_sweep_heads(lib):
+    announce("matmul heads full")
+    c = workloads.attr_sweep_case("matmul_heads")
+    got = host(lib.onnx_matmul(dev(c["A"]), dev(c["B"])))
+    assert got.shape == (8, 12, 512, 512)
+    for (i, j) in [(0, 0), (3, 7), (7, 11)]:
+        ref, S = oracle.matmul(c["A"][i, j], c["B"][i, j], want_scale=True)
+        assert rel_err(got[i, j], ref) <= REL_TOL
+        assert within_rounding_bound(got[i, j], ref, S, 64)
+
+
+def test_matmul_attribute_sweep_projection(lib):
+    announce("matmul proj full")
+    c = workloads.attr_sweep_case("matmul_proj")
+    got = host(lib.onnx_matmul(dev(c["A"]), dev(c["B"])))
+    assert got.shape == (8, 512, 3072)
+    rows = [0, 77, 511]
+    for b in (0, 5, 7):
+        ref, S = oracle.matmul(c["A"][b][rows], c["B"], want_scale=True)
+        assert rel_err(got[b][rows], ref) <= REL_TOL
+        assert within_rounding_bound(got[b][rows], ref, S, 768)
+
+
+# ------------------------------------------------------------------------------ Conv
+
+CONV_CASES = [
+    # N, C, H, W, M, kH, kW, pads, strides, dilations, group      (path the selector takes)
+    (2, 4, 7, 6, 6, 3, 2, (1, 0, 2, 1), (2, 1), (1, 2), 2),          # direct (tiny groups)
+    (1, 1, 28, 28, 8, 5, 5, (2, 2, 2, 2), (1, 1), (1, 1), 1),        # direct (M = 8)
+    (1, 8, 14, 14, 16, 5, 5, (2, 2, 2, 2), (1, 1), (1, 1), 1),       # matrix cores, K = 200
+    (3, 16, 19, 23, 40, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 1),      # ragged tiles, several images per tile
+    (2, 3, 37, 41, 64, 7, 7, (3, 3, 3, 3), (2, 2), (1, 1), 1),       # K = 147 (scalar filter loads)
+    (2, 32, 20, 20, 48, 3, 3, (2, 0, 1, 3), (2, 3), (2, 1), 2),      # asymmetric pads, stride, dilation, 2 groups
+    (2, 64, 12, 12, 96, 1, 1, (0, 0, 0, 0), (1, 1), (1, 1), 1),      # pointwise fast path (16-byte loads)
+    (2, 64, 9, 7, 96, 1, 1, (0, 0, 0, 0), (1, 1), (1, 1), 1),        # pointwise, P = 63 (scalar loads)
+    (2, 64, 12, 12, 96, 1, 1, (0, 0, 0, 0), (2, 2), (1, 1), 1),      # strided 1x1 (projection shortcut)
+    (2, 64, 12, 12, 64, 1, 1, (1, 1, 1, 1), (1, 1), (1, 1), 4),      # padded 1x1 with 4 groups
+    (1, 24, 30, 30, 160, 3, 3, (2, 2, 2, 2), (1, 1), (2, 2), 1),     # dilated, > 128 rows
+    (5, 40, 15, 15, 200, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 1),     # 128x128 tiles with tails
+    (4, 6, 10, 10, 6, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 6),        # depthwise
+    (1, 16, 5, 5, 32, 5, 5, (0, 0, 0, 0), (1, 1), (1, 1), 1),        # output 1x1
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_matches_oracle(lib, case):
+    announce("conv", case)
+    N, C, H, W, M, kH, kW, pads, st, dl, g = case
+    rng = np.random.default_rng(list(case[:7]) + [g])
+    X = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    Wt = rng.uniform(-1, 1, (M, C // g, kH, kW)).astype(np.float32)
+    Bv = rng.uniform(-1, 1, (M,)).astype(np.float32)
+    K = (C // g) * kH * kW
+    ref, S = oracle.conv(X, Wt, Bv, pads, st, dl, g, want_scale=True)
+    got = host(lib.onnx_conv(dev(X), dev(Wt), dev(Bv), pads, st, dl, g))
+    assert got.shape == ref.shape
+    assert rel_err(got, ref) <= REL_TOL
+    assert within_rounding_bound(got, ref, S, K + 1)
+    # fused residual + Relu, and no bias
+    R = rng.uniform(-1, 1, ref.shape).astype(np.float32)
+    ref2 = oracle.conv(X, Wt, None, pads, st, dl, g, residual=R, relu=True)
+    got2 = host(lib.onnx_conv(dev(X), dev(Wt), None, pads, st, dl, g, residual=dev(R), act=1))
+    assert rel_err(got2, ref2) <= REL_TOL
+    assert (got2 >= 0).all()
+
+
+@pytest.mark.parametrize("a,b,dH,dW,pads,st", [
+    (1, 1, 1, 1, (1, 1, 1, 1), (1, 1)), (0, 2, 2, 1, (1, 0, 3, 2), (1, 1)), (2, 0, 1, 2, (0, 2, 1, 4), (2, 3)),
+])
+def test_conv_shifted_delta_kernel_bit_exact(lib, a, b, dH, dW, pads, st):
+    """A filter that is 1 at one tap of the matching input channel copies (shifted, zero-filled,
+    subsampled) input values: one non-zero product per output, so fp32 must reproduce it exactly."""
+    announce("conv delta", a, b, dH, dW, pads, st)
+    rng = np.random.default_rng(6)
+    C = 32
+    X = rng.standard_normal((3, C, 21, 17)).astype(np.float32)
+    Wt = np.zeros((C, C, 3, 3), np.float32)
+    for c in range(C):
+        Wt[c, c, a, b] = 1.0
+    ref = oracle.conv(X, Wt, None, pads, st, (dH, dW))
+    got = host(lib.onnx_conv(dev(X), dev(Wt), None, pads, st, (dH, dW)))
+    assert np.array_equal(got.astype(np.float64), ref)
+
+
+def test_conv_small_integers_bit_exact(lib):
+    announce("conv integer")
+    rng = np.random.default_rng(8)
+    X = rng.integers(-4, 5, (3, 48, 17, 19)).astype(np.float32)
+    Wt = rng.integers(-4, 5, (72, 48, 3, 3)).astype(np.float32)
+    Bv = rng.integers(-4, 5, (72,)).astype(np.float32)
+    for pads, st, dl in [((1, 1, 1, 1), (1, 1), (1, 1)), ((0, 2, 1, 0), (2, 1), (1, 2))]:
+        ref = oracle.conv(X, Wt, Bv, pads, st, dl)
+        got = host(lib.onnx_conv(dev(X), dev(Wt), dev(Bv), pads, st, dl))
+        assert np.array_equal(got.astype(np.float64), ref)
+
+
+def test_conv_attribute_sweep_depthwise_full(lib):
+    announce("conv depthwise full")
+    c = workloads.attr_sweep_case("depthwise")
+    for relu in (False, True):
+        ref = oracle.conv(c["X"], c["W"], c["B"], c["pads"], c["strides"], c["dilations"], c["group"], relu=relu)
+        got = host(lib.onnx_conv(dev(c["X"]), dev(c["W"]), dev(c["B"]), c["pads"], c["strides"],
+                                 c["dilations"], c["group"], act=int(relu)))
+        assert rel_err(got, ref) <= REL_TOL
+
+
+def test_conv_attribute_sweep_dilated_full_launch_sampled_images(lib):
+    """Launch at the full 8x512x28x28 shape; the oracle evaluates two of the images (each image's
+    output depends on that image only)."""
+    announce("conv dilated full")
+    c = workloads.attr_sweep_case("dilated")
+    got = host(lib.onnx_conv(dev(c["X"]), dev(c["W"]), dev(c["B"]), c["pads"], c["strides"], c["dilations"],
+                             c["group"]))
+    assert got.shape == (8, 512, 28, 28)
+    for n in (0, 7):
+        ref, S = oracle.conv(c["X"][n:n + 1], c["W"], c["B"], c["pads"], c["strides"], c["dilations"],
+                             c["group"], want_scale=True)
+        assert rel_err(got[n:n + 1], ref) <= REL_TOL
+        assert within_rounding_bound(got[n:n + 1], ref, S, 4608 + 1)
+
+
+def test_conv_attribute_sweep_pointwise_full(lib):
+    announce("conv pointwise full")
+    c = workloads.attr_sweep_case("pointwise")
+    got = host(lib.onnx_conv(dev(c["X"]), dev(c["W"]), dev(c["B"]), c["pads"], c["strides"], c["dilations"],
+                             c["group"], act=1))
+    sel = [0, 13, 31]
+    ref = oracle.conv(c["X"][sel], c["W"], c["B"], c["pads"], c["strides"], c["dilations"], c["group"], relu=True)
+    assert rel_err(got[sel], ref) <= REL_TOL
+
+
+# ------------------------------------------------------------------------------ pools
+
+POOL_CASES = [
+    (2, 3, 9, 8, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),
+    (1, 2, 10, 7, (2, 3), (0, 1, 0, 1), (2, 1), (1, 1), 0),
+    (2, 2, 11, 11, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 1),
+    (1, 3, 12, 9, (3, 2), (0, 0, 0, 0), (3, 2), (2, 2), 0),
+    (1, 1, 7, 7, (2, 2), (0, 0, 0, 0), (2, 2), (1, 1), 1),
+    (2, 5, 13, 10, (3, 2), (2, 0, 1, 1), (1, 2), (1, 1), 0),
+    (3, 64, 56, 56, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),
+]
+
+
+@pytest.mark.parametrize("case", POOL_CASES)
+def test_maxpool_bit_exact_with_indices(lib, case):
+    announce("maxpool", case)
+    N, C, H, W, k, pads, st, dl, ceil = case
+    rng = np.random.default_rng(31)
+    X = rng.integers(-3, 4, (N, C, H, W)).astype(np.float32)          # many ties
+    X += (rng.random((N, C, H, W)) < 0.5).astype(np.float32) * 0.5
+    ref, iref = oracle.maxpool(X, k, pads, st, dl, ceil)
+    got, igot = lib.onnx_maxpool(dev(X), k, pads, st, dl, ceil, want_indices=True)
+    got, igot = host(got), host(igot)
+    assert np.array_equal(got, ref)
+    assert np.array_equal(igot, iref)
+    only = host(lib.onnx_maxpool(dev(X), k, pads, st, dl, ceil))
+    assert np.array_equal(only, ref)
+
+
+@pytest.mark.parametrize("case", POOL_CASES)
+@pytest.mark.parametrize("cip", [0, 1])
+def test_avgpool_matches_oracle(lib, case, cip):
+    announce("avgpool", case, cip)
+    N, C, H, W, k, pads, st, dl, ceil = case
+    rng = np.random.default_rng(34)
+    X = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    ref = oracle.avgpool(X, k, pads, st, ceil, cip)
+    got = host(lib.onnx_avgpool(dev(X), k, pads, st, ceil, cip))
+    assert rel_err(got, ref) <= REL_TOL
+
+
+@pytest.mark.parametrize("shape", [(2, 5, 7, 7), (3, 130, 1, 1), (1, 3, 20, 33), (32, 2048, 7, 7)])
+def test_global_avgpool_matches_oracle(lib, shape):
+    announce("global avgpool", shape)
+    rng = np.random.default_rng(35)
+    X = rng.standard_normal(shape).astype(np.float32)
+    ref = oracle.avgpool(X, None)
+    got = host(lib.onnx_avgpool(dev(X), None))
+    assert got.shape == ref.shape
+    assert rel_err(got, ref) <= REL_TOL
+
+
+# ------------------------------------------------------------------------------ degenerate sizes and errors
+
+def test_zero_sized_outputs_return_ok(lib):
+    announce("zero sized")
+    z = torch.empty((0, 8), dtype=torch.float32, device="cuda")
+    b = torch.ones((8, 5), dtype=torch.float32, device="cuda")
+    assert tuple(lib.onnx_gemm(z, b).shape) == (0, 5)
+    assert tuple(lib.onnx_matmul(z, b).shape) == (0, 5)
+    x = torch.empty((0, 3, 8, 8), dtype=torch.float32, device="cuda")
+    w = torch.ones((4, 3, 3, 3), dtype=torch.float32, device="cuda")
+    assert tuple(lib.onnx_conv(x, w).shape) == (0, 4, 6, 6)
+    assert tuple(lib.onnx_maxpool(x, (2, 2)).shape) == (0, 3, 7, 7)
+    assert tuple(lib.onnx_avgpool(x, None).shape) == (0, 3, 1, 1)
+    # K = 0: an empty sum plus the bias
+    a = torch.empty((3, 0), dtype=torch.float32, device="cuda")
+    bb = torch.empty((0, 4), dtype=torch.float32, device="cuda")
+    c = torch.full((1, 4), 2.5, dtype=torch.float32, device="cuda")
+    assert np.array_equal(host(lib.onnx_gemm(a, bb, c)), np.full((3, 4), 2.5, np.float32))
+
+
+def test_errors_write_nothing(lib):
+    announce("errors")
+    a = torch.ones((4, 4), dtype=torch.float32, device="cuda")
+    y = torch.full((4, 4), 7.0, dtype=torch.float32, device="cuda")
+    with pytest.raises(lib.OnnxHipError) as e:
+        lib.onnx_gemm(a, a, out=a)                                   # output aliases an input
+    assert e.value.status == 6
+    with pytest.raises(lib.OnnxHipError) as e:
+        lib.onnx_gemm(a, torch.ones((5, 4), dtype=torch.float32, device="cuda"), out=y)
+    assert e.value.status == 3
+    assert np.array_equal(host(y), np.full((4, 4), 7.0, np.float32))
+
+
+# ------------------------------------------------------------------------------ model chains
+
+def _run_chain(lib, model):
+    from paper_2008_08272_amd.runner import GraphRunner
+    r = GraphRunner(model)
+    out = r.run()
+    torch.cuda.synchronize()
+    return r, out.cpu().numpy()
+
+
+def test_small_cnn_chain(lib):
+    announce("small cnn chain")
+    from oracle import chain
+    m = workloads.small_cnn()
+    env, exact = chain.run(m)
+    r, got = _run_chain(lib, m)
+    assert rel_err(got, exact["logits"]) <= REL_TOL
+    for name in ("c1", "p1", "c2", "p2"):
+        assert rel_err(r.t[name].cpu().numpy(), exact[name]) <= REL_TOL, name
+
+
+def test_resnet50_batch1_chain(lib):
+    announce("resnet50 b1 chain")
+    from oracle import chain
+    m = workloads.resnet50(1)
+    env, exact = chain.run(m)
+    r, got = _run_chain(lib, m)
+    worst = 0.0
+    for nd in m["graph"]:
+        if nd["op"] == "reshape":
+            continue
+        e = rel_err(r.t[nd["y"]].cpu().numpy(), exact[nd["y"]])
+        worst = max(worst, e)
+        assert e <= REL_TOL, (nd["y"], e)
+    print("resnet50 b1 worst layer error", worst, flush=True)
+    assert rel_err(got, exact["logits"]) <= REL_TOL
+
+
+def test_resnet50_batch32_chain_sampled_images(lib):
+    """The batch-32 launch shapes; the oracle runs the same graph on two of the 32 images."""
+    announce("resnet50 b32 chain")
+    from oracle import chain
+    m = workloads.resnet50(32)
+    r, got = _run_chain(lib, m)
+    assert got.shape == (32, 1000)
+    for n in (0, 31):
+        sub = dict(m)
+        sub["inputs"] = {"x": m["inputs"]["x"][n:n + 1]}
+        sub["graph"] = [dict(nd, shape=(1, 2048)) if nd["op"] == "reshape" else nd for nd in m["graph"]]
+        env, exact = chain.run(sub, keep=("stem", "pool0", "s1b2c", "s2b3c", "s3b5c", "s4b2c", "gap"))
+        for name, ref in exact.items():
+            e = rel_err(r.t[name][n:n + 1].cpu().numpy(), ref)
+            assert e <= REL_TOL, (n, name, e)
