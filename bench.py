@@ -1,0 +1,171 @@
+"""Throughput of the hot path on one MI355X.
+
+Headline (one JSON line): the ONNX Gemm sweep (M=N=K in {1024, 2048, 4096}, transB=1, 1xN bias,
+alpha=beta=1), fp32, inputs resident in HBM; one step = the three Gemms.  The same line carries
+  roofline      the matrix-core kernel on the 4096 case against the fp32 MFMA peak, from HIP
+                events recorded around that launch inside the timed region;
+  cpu_baseline  the CPU oracle timed on a row sample of the 4096 case on this machine's host cores;
+  details       per-size TFLOP/s, ResNet-50 img/s at batch 32 and 1, attribute-sweep cases.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_FP32_PEAK_TFLOPS = 157.3      # 256 CU x 256 flop/clk x 2.4 GHz
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-details", action="store_true", help="skip the ResNet-50 / attribute-sweep extras")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import workloads
+    import paper_2008_08272_amd as lib
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    def up(a):
+        return torch.from_numpy(a).to(dev)
+
+    # ---- headline: Gemm sweep -------------------------------------------------------------
+    cases = []
+    for n in workloads.GEMM_SWEEP_SIZES:
+        c = workloads.gemm_case(n)
+        A, B, C = up(c["A"]), up(c["B"]), up(c["C"])
+        Y = torch.empty((n, n), dtype=torch.float32, device=dev)
+        cases.append((n, A, B, C, Y, c))
+    flop_step = sum(2.0 * n ** 3 for n in workloads.GEMM_SWEEP_SIZES)
+
+    def step(events=None):
+        for n, A, B, C, Y, _ in cases:
+            if events is not None and n == 4096:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                lib.onnx_gemm(A, B, C, 1.0, 1.0, 0, 1, out=Y)
+                e1.record()
+                events.append((e0, e1))
+            else:
+                lib.onnx_gemm(A, B, C, 1.0, 1.0, 0, 1, out=Y)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = flop_step / (ms_per_step * 1e-3) / 1e12
+    k4096_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))
+    n = 4096
+    flop_4096 = 2.0 * n ** 3
+    bytes_4096 = 4.0 * (n * n + n * n + n + n * n)
+    achieved = flop_4096 / (k4096_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "achieved": round(achieved, 3), "peak": MFMA_FP32_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / MFMA_FP32_PEAK_TFLOPS, 4), "traffic": None,
+                "kernel": "contraction_kernel<128,128,KC,KC,vec4> on Gemm 4096^3",
+                "avg_launch_ms": round(k4096_ms, 4), "algorithmic_flop": flop_4096,
+                "algorithmic_bytes": bytes_4096}
+
+    def time_call(fn, iters=20, warm=3):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    details = {}
+    per_size = {}
+    for n, A, B, C, Y, _ in cases:
+        ms = time_call(lambda: lib.onnx_gemm(A, B, C, 1.0, 1.0, 0, 1, out=Y))
+        tf = 2.0 * n ** 3 / (ms * 1e-3) / 1e12
+        per_size[str(n)] = {"ms": round(ms, 4), "tflops": round(tf, 2), "frac_mfma_peak": round(tf / MFMA_FP32_PEAK_TFLOPS, 4)}
+    details["gemm_sweep"] = per_size
+
+    if not args.no_details:
+        from paper_2008_08272_amd.runner import GraphRunner
+        for batch in (32, 1):
+            m = workloads.resnet50(batch)
+            st = workloads.graph_stats(m)
+            r = GraphRunner(m, dev)
+            ms = time_call(r.run, iters=10 if batch == 32 else 30, warm=3)
+            tf = 2.0 * st["macs"] / (ms * 1e-3) / 1e12
+            details["resnet50_b%d" % batch] = {"ms": round(ms, 4), "img_per_s": round(batch / (ms * 1e-3), 1),
+                                               "tflops": round(tf, 2),
+                                               "frac_mfma_peak": round(tf / MFMA_FP32_PEAK_TFLOPS, 4)}
+            del r
+        for name in workloads.ATTR_SWEEP_CONV:
+            c = workloads.attr_sweep_case(name)
+            X, W, Bv = up(c["X"]), up(c["W"]), up(c["B"])
+            yd = lib.onnx_conv_infer(X.shape, W.shape, c["pads"], c["strides"], c["dilations"], c["group"])
+            Y = torch.empty(yd, dtype=torch.float32, device=dev)
+            ms = time_call(lambda: lib.onnx_conv(X, W, Bv, c["pads"], c["strides"], c["dilations"], c["group"], out=Y))
+            macs = Y.numel() * W.shape[1] * W.shape[2] * W.shape[3]
+            byts = 4.0 * (X.numel() + W.numel() + Y.numel())
+            details["conv_" + name] = {"ms": round(ms, 4), "tflops": round(2.0 * macs / (ms * 1e-3) / 1e12, 3),
+                                       "gbytes_per_s": round(byts / (ms * 1e-3) / 1e9, 1)}
+        for name in workloads.ATTR_SWEEP_MATMUL:
+            c = workloads.attr_sweep_case(name)
+            A, B = up(c["A"]), up(c["B"])
+            Y = torch.empty(lib.onnx_matmul_infer(A.shape, B.shape), dtype=torch.float32, device=dev)
+            ms = time_call(lambda: lib.onnx_matmul(A, B, out=Y))
+            macs = Y.numel() * A.shape[-1]
+            byts = 4.0 * (A.numel() + B.numel() + Y.numel())
+            details[name] = {"ms": round(ms, 4), "tflops": round(2.0 * macs / (ms * 1e-3) / 1e12, 3),
+                             "gbytes_per_s": round(byts / (ms * 1e-3) / 1e9, 1)}
+
+    # ---- CPU oracle beside it (a reported baseline, not the target) ---------------------------
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        oracle.gemm(cases[0][5]["A"][:8], cases[0][5]["B"], cases[0][5]["C"], 1.0, 1.0, 0, 1)   # load the library
+        t0 = time.perf_counter()
+        for _, _, _, _, _, c in cases:
+            oracle.gemm(c["A"], c["B"], c["C"], 1.0, 1.0, 0, 1)
+        dt = time.perf_counter() - t0
+        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        cpu = {"value": round(flop_step / dt / 1e12, 6), "unit": "TFLOP/s", "cores": threads,
+               "kind": "oracle", "seconds": round(dt, 2),
+               "sample": "one whole step (the 1024^3, 2048^3 and 4096^3 Gemms) through the fp64-accumulating "
+                         "C loop nest, OpenMP over output rows"}
+
+    out = {"metric": "ONNX Gemm fp32 throughput on the Gemm sweep (M=N=K in 1024,2048,4096; transB=1, 1xN bias)",
+           "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "gemm_sweep_fp32 (three ONNX Gemm calls per step: 1024^3, 2048^3, 4096^3)",
+                      "flop_per_step": flop_step},
+           "roofline": roofline, "cpu_baseline": cpu, "details": details}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

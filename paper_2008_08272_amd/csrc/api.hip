@@ -256,7 +256,8 @@ onnx_status onnx_gemm(const float* A, const int64_t a_dims[2], const float* B, c
         nc = r * c;
     }
     if (M * N == 0) return ONNX_OK;
-    if (!A || !B || !Y) return fail(ONNX_ERR_NULL, "gemm: A, B and Y must not be NULL");
+    // with K == 0 the sum is empty and A, B are never read (they may be NULL)
+    if (!Y || (K > 0 && (!A || !B))) return fail(ONNX_ERR_NULL, "gemm: A, B and Y must not be NULL");
     if (overlaps(Y, M * N * 4, A, M * K * 4) || overlaps(Y, M * N * 4, B, K * N * 4) ||
         overlaps(Y, M * N * 4, C, nc * 4))
         return fail(ONNX_ERR_ALIAS, "gemm: Y overlaps an input");
@@ -318,7 +319,7 @@ onnx_status onnx_matmul(const float* A, const int64_t* a_dims, int a_rank, const
         p.nbd = nb;
     }
     if (nz * M * N == 0) return ONNX_OK;
-    if (!A || !B || !Y) return fail(ONNX_ERR_NULL, "matmul: A, B and Y must not be NULL");
+    if (!Y || (K > 0 && (!A || !B))) return fail(ONNX_ERR_NULL, "matmul: A, B and Y must not be NULL");
     const int64_t ny = nz * M * N;
     if (overlaps(Y, ny * 4, A, na * 4) || overlaps(Y, ny * 4, B, nbel * 4))
         return fail(ONNX_ERR_ALIAS, "matmul: Y overlaps an input");
