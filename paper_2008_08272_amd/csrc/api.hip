@@ -55,6 +55,12 @@ bool window_extent(int64_t in, int64_t k, int64_t pb, int64_t pe, int64_t s, int
     return true;
 }
 
+// The kernels address each operand tile with 32-bit byte offsets below 2^31 from the tile's
+// first element (tiles have at most 256 rows and walk K in steps of at most 32).
+const int64_t kTileRows = 256, kTileK = 32, kSpan = (1LL << 31) - 64;
+bool kc_fits(int64_t ld, int64_t K) { return (kTileRows * ld + K) * 4 < kSpan; }
+bool rc_fits(int64_t ld, int64_t lead) { return (kTileK * ld + lead) * 4 < kSpan; }
+
 int pick_tile(int64_t M, int64_t N, int64_t nz) {
     const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128) * nz;
     if (M > 64 && N > 64 && t128 >= 192) return TILE_128x128;
@@ -71,7 +77,7 @@ void no_batch(ContractionParams& p) {
     p.y_img = 0;
     p.b_img = 0;
     memset(&p.ic, 0, sizeof(p.ic));
-    p.ic.kHW = p.ic.kW = p.ic.P = p.ic.OW = FastDiv::make(1);
+    p.ic.kHW = p.ic.kW = p.ic.OW = FastDiv::make(1);
 }
 
 onnx_status device_status(hipError_t e, const char* what) {
@@ -189,7 +195,11 @@ onnx_status onnx_conv(const float* X, const int64_t x_dims[4], const float* W, c
     g.pT = (int)pads[0]; g.pL = (int)pads[1]; g.pB = (int)pads[2]; g.pR = (int)pads[3];
     g.dH = (int)dilations[0]; g.dW = (int)dilations[1];
 
-    const bool use_mfma = Mg >= 16 && K >= 8 && NP <= kIntMax;
+    // images one tile of columns can touch, and the span of input they cover
+    const int64_t tile_images = (kTileRows + P - 1) / P + 1;
+    const bool use_mfma = Mg >= 16 && K >= 8 && NP <= kIntMax && kc_fits(K, K) &&
+                          tile_images * C * H * Wd * 4 < kSpan &&
+                          (kTileRows * P + tile_images * M * P) * 4 < kSpan;
     if (!use_mfma)
         return device_status(launch_conv_direct(X, W, B, residual, Y, g, (int)M, (int)Cg, (int)group,
                                                 act == ONNX_ACT_RELU, s), "conv (direct)");
@@ -219,9 +229,8 @@ onnx_status onnx_conv(const float* X, const int64_t x_dims[4], const float* W, c
         p.ic.sH = g.sH; p.ic.sW = g.sW; p.ic.pT = g.pT; p.ic.pL = g.pL; p.ic.dH = g.dH; p.ic.dW = g.dW;
         p.ic.kHW = FastDiv::make((uint32_t)(kH * kW));
         p.ic.kW = FastDiv::make((uint32_t)kW);
-        p.ic.P = FastDiv::make((uint32_t)P);
         p.ic.OW = FastDiv::make((uint32_t)OW);
-        p.ic.image_stride = C * H * Wd;
+        p.ic.image_stride = (int)(C * H * Wd);
     }
     const int tile = pick_tile(Mg, NP, group);
     return device_status(launch_contraction(p, LOAD_KC, bkind, vec, tile, (int)group, s), "conv (mfma)");
@@ -262,6 +271,9 @@ onnx_status onnx_gemm(const float* A, const int64_t a_dims[2], const float* B, c
         overlaps(Y, M * N * 4, C, nc * 4))
         return fail(ONNX_ERR_ALIAS, "gemm: Y overlaps an input");
     if (M > kIntMax || N > kIntMax || K > kIntMax) return fail(ONNX_ERR_UNSUPPORTED, "gemm: extent above 2^31-1");
+    if (!(transA ? rc_fits(M, kTileRows) : kc_fits(K, K)) || !(transB ? kc_fits(K, K) : rc_fits(N, kTileRows)) ||
+        !kc_fits(N, N))
+        return fail(ONNX_ERR_UNSUPPORTED, "gemm: a row of A, B or Y is too long for 32-bit tile offsets");
 
     ContractionParams p;
     no_batch(p);
@@ -324,6 +336,8 @@ onnx_status onnx_matmul(const float* A, const int64_t* a_dims, int a_rank, const
     if (overlaps(Y, ny * 4, A, na * 4) || overlaps(Y, ny * 4, B, nbel * 4))
         return fail(ONNX_ERR_ALIAS, "matmul: Y overlaps an input");
     if (M > kIntMax || N > kIntMax || K > kIntMax) return fail(ONNX_ERR_UNSUPPORTED, "matmul: extent above 2^31-1");
+    if (!kc_fits(K, K) || !rc_fits(N, kTileRows) || !kc_fits(N, N))
+        return fail(ONNX_ERR_UNSUPPORTED, "matmul: a row of A, B or Y is too long for 32-bit tile offsets");
 
     p.A = A; p.B = B; p.Y = Y; p.bias = nullptr; p.residual = nullptr;
     int64_t Meff = M;

@@ -5,21 +5,25 @@
 // convolution is evaluated as the product of the filter matrix [M x Cg*kH*kW] with the
 // never-materialised matrix of input patches [Cg*kH*kW x N*OH*OW]).
 //
-// Work decomposition: a workgroup of 4 wavefronts owns a BM x BN tile of Y and walks K in
-// steps of 16.  Each step stages an A tile and a B tile in LDS (double buffered: global
+// Work decomposition: a workgroup of WM x WN wavefronts owns a BM x BN tile of Y and walks K
+// in steps of BK.  Each step stages an A tile and a B tile in LDS (double buffered: global
 // loads for step t+1 are issued before the MFMAs of step t and written to the other buffer
 // after them, one barrier per step).  Each wavefront owns a (BM/WM) x (BN/WN) sub-tile as
 // a grid of 32x32 accumulators fed by v_mfma_f32_32x32x2_f32.
 //
 // Operand kinds (how a tile is fetched and how it sits in LDS):
 //   KC      k is the contiguous index in memory (Gemm A, Gemm B with transB, conv filters).
-//           LDS holds [row][16+4]; a lane reads 4 consecutive k with one 16-byte read.
+//           LDS holds [row][BK+4]; a lane reads 4 consecutive k with one 16-byte read.
 //   RC      the row (i or j) is the contiguous index (Gemm A with transA, Gemm B, the input
 //           of a 1x1 stride-1 unpadded conv).  LDS holds [k][rows+8]; lanes read along rows.
 //   IM2COL  B only: element (k, j) is gathered from the NCHW input with pads, strides,
 //           dilations and group resolved in the address computation.  LDS as RC.
 // Because both operands of one MFMA must carry the same k, and a KC lane holds 4 consecutive
 // k, the 8 k of a half-step are dealt as  k = 4*(lane/32) + s  to MFMA number s = 0..3.
+//
+// Global loads go through buffer resources (see OOB below): a lane whose element lies
+// outside the operand gets 0 from the hardware range check, so the loop body has no divergent
+// branch and no select, and loads, LDS traffic and MFMAs can be scheduled around each other.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -29,10 +33,8 @@ namespace onnxhip {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int BK = 16;
-constexpr int NTHREADS = 256;
-constexpr int LDK = BK + 4;          // row stride of a KC tile in LDS (floats)
 constexpr int RC_PAD = 8;            // extra floats per k-row of an RC tile
+constexpr int KC_PAD = 4;            // extra floats per row of a KC tile
 constexpr int MAX_BATCH_DIMS = 6;
 constexpr int NUM_XCD = 8;
 
@@ -40,22 +42,24 @@ enum { LOAD_KC = 0, LOAD_RC = 1, LOAD_IM2COL = 2 };
 
 // Unsigned division by a run-time constant d >= 1 for numerators below 2^31:
 // with s = floor(log2 d) and m = floor(2^(32+s)/d) + 1,  n / d == (n*m) >> (32+s).
-// (m would need 33 bits when d is a power of two; those divide by shifting.)
+// (m would need 33 bits when d is a power of two; those divide by shifting, selected with a
+// mask rather than a branch so that the code stays straight-line.)
 struct FastDiv {
-    uint32_t m, s, d, pow2;
+    uint32_t m, s, d, pow2_mask;
     __host__ __device__ static FastDiv make(uint32_t d) {
         FastDiv f;
         f.d = d;
         uint32_t s = 0;
         while ((2u << s) <= d && s < 31) ++s;      // s = floor(log2 d)
         f.s = s;
-        f.pow2 = ((d & (d - 1)) == 0) ? 1u : 0u;
-        f.m = f.pow2 ? 0u : (uint32_t)((((uint64_t)1 << (32 + s)) / d) + 1);
+        const bool pow2 = (d & (d - 1)) == 0;
+        f.pow2_mask = pow2 ? 0xffffffffu : 0u;
+        f.m = pow2 ? 0u : (uint32_t)((((uint64_t)1 << (32 + s)) / d) + 1);
         return f;
     }
     __host__ __device__ inline uint32_t div(uint32_t n) const {
         const uint32_t hi = (uint32_t)(((uint64_t)n * m) >> 32);
-        return pow2 ? (n >> s) : (hi >> s);
+        return ((hi & ~pow2_mask) | (n & pow2_mask)) >> s;
     }
     __host__ __device__ inline void divmod(uint32_t n, uint32_t& q, uint32_t& r) const {
         q = div(n);
@@ -66,8 +70,8 @@ struct FastDiv {
 struct Im2colGeom {
     int C, H, W;             // channels of the whole image, input height and width
     int sH, sW, pT, pL, dH, dW;
-    FastDiv kHW, kW, P, OW;  // divisors: kH*kW, kW, OH*OW, OW
-    int64_t image_stride;    // C*H*W
+    FastDiv kHW, kW, OW;     // divisors: kH*kW, kW, OW
+    int image_stride;        // C*H*W
 };
 
 struct ContractionParams {
@@ -96,104 +100,129 @@ struct ContractionParams {
     Im2colGeom ic;
 };
 
+// Buffer addressing: every operand tile is read through a buffer resource whose base is the
+// tile's first element and whose extent is 2^31 bytes.  Lanes address it with 32-bit byte
+// offsets; a lane whose element does not exist uses offset 2^31, which the hardware range
+// check turns into a returned 0 without touching memory.  The host guarantees that every
+// existing element of a tile lies below 2^31 bytes from the tile's base.
+constexpr uint32_t OOB = 0x80000000u;
+constexpr int RSRC_FLAGS = 0x00020000;          // raw 32-bit data format
+
+__device__ inline __amdgpu_buffer_rsrc_t tile_rsrc(const float* p) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p), 0, (int)OOB, RSRC_FLAGS);
+}
+
 // ------------------------------------------------------------------------------------------
-// Tile loader: global -> registers -> LDS for a ROWS x 16 tile.
-template <int KIND, int VEC, int ROWS>
+// Tile loader: global -> registers -> LDS for a ROWS x BK tile, NT threads.
+template <int KIND, int VEC, int ROWS, int BK, int NT>
 struct TileLoader {
     static constexpr bool kc = (KIND == LOAD_KC);
-    // threads along the fast axis of a pass and rows/k covered per pass
-    static constexpr int FAST = kc ? (BK / VEC) : (ROWS / VEC);
-    static constexpr int SLOW_PER_PASS = NTHREADS / FAST;
+    static constexpr int FAST = kc ? (BK / VEC) : (ROWS / VEC);   // threads along the contiguous axis
+    static constexpr int SLOW_PER_PASS = NT / FAST;               // rows (KC) or k (RC) per pass
     static constexpr int SLOW = kc ? ROWS : BK;
     static constexpr int NLOAD = (SLOW + SLOW_PER_PASS - 1) / SLOW_PER_PASS;
+    static constexpr int LDK = BK + KC_PAD;
     static constexpr int LDR = ROWS + RC_PAD;
     static constexpr int LDS_FLOATS = kc ? ROWS * LDK : BK * LDR;
+    static_assert(NT % FAST == 0, "threads must tile the contiguous axis");
     static_assert(SLOW % SLOW_PER_PASS == 0 || SLOW < SLOW_PER_PASS, "tile/loader mismatch");
 
     float reg[NLOAD * VEC];
-    int fast, slow0;            // this thread's coordinates within a pass
-    bool active;                // false when SLOW < SLOW_PER_PASS leaves the thread idle
-    // KC: per-pass row validity is recomputed (cheap); RC/IM2COL: one column per thread
-    int64_t col_off;            // RC: offset of this thread's first column; IM2COL: image base
+    int fast, slow0;
+    bool active;                 // false when SLOW < SLOW_PER_PASS leaves the thread idle
+    const float* base;           // first element of the tile (RC: at k = 0)
+    __amdgpu_buffer_rsrc_t rsrc; // KC / IM2COL: fixed for the whole K walk
+    int ld, K;
+    // KC: byte offset of each pass's row (OOB when the row does not exist).
+    // RC: byte offset of the thread's column at k = slow0.  IM2COL: element offset of the
+    // column's window origin relative to the tile's first image (may be negative).
+    uint32_t voff[kc ? NLOAD : 1];
     bool col_ok;
-    int ih0, iw0;               // IM2COL: top-left input coordinate of the column's window
-    const float* base;
-    int64_t ld;
-    int rows_total, row0, K;
+    int ih0, iw0;                // IM2COL: input coordinate of the window's first tap
 
-    // `images`: the row index is a column of B that splits into (image, pixel) through cp.colP.
-    __device__ inline void init(const float* p, int64_t ld_, int row0_, int rows_total_, int K_,
+    __device__ inline void init(const float* p, int64_t ld_, int row0, int rows_total, int K_,
                                 bool images, const ContractionParams& cp) {
-        base = p; ld = ld_; row0 = row0_; rows_total = rows_total_; K = K_;
+        ld = (int)ld_; K = K_;
         const int t = threadIdx.x;
         fast = t % FAST;
         slow0 = t / FAST;
         if (FAST % 64 == 0) slow0 = __builtin_amdgcn_readfirstlane(slow0);   // uniform per wavefront
         active = slow0 < SLOW;
-        col_off = 0; col_ok = true; ih0 = 0; iw0 = 0;
-        if (!kc) {
+        ih0 = 0; iw0 = 0; col_ok = true;
+        if (kc) {
+            base = p + (int64_t)row0 * ld_;
+#pragma unroll
+            for (int p_ = 0; p_ < NLOAD; ++p_) {
+                const int slow = slow0 + p_ * SLOW_PER_PASS;
+                const bool ok = active && row0 + slow < rows_total;
+                voff[p_] = ok ? (uint32_t)(slow * ld + fast * VEC) * 4u : OOB;
+            }
+        } else {
             const int j = row0 + fast * VEC;
-            col_ok = j < rows_total;
-            const uint32_t jj = col_ok ? (uint32_t)j : 0u;
+            col_ok = active && j < rows_total;
+            const uint32_t jj = col_ok ? (uint32_t)j : (uint32_t)row0;
             if (KIND == LOAD_RC) {
                 if (images) {
-                    uint32_t n, px;
+                    uint32_t n0_, p0_, n, px;
+                    cp.colP.divmod((uint32_t)row0, n0_, p0_);
                     cp.colP.divmod(jj, n, px);
-                    col_off = (int64_t)n * cp.b_img + px;
+                    base = p + (int64_t)n0_ * cp.b_img;
+                    voff[0] = (uint32_t)((int)(n - n0_) * (int)cp.b_img + (int)px + slow0 * ld) * 4u;
                 } else {
-                    col_off = jj;
+                    base = p + row0;
+                    voff[0] = (uint32_t)((int)(jj - (uint32_t)row0) + slow0 * ld) * 4u;
                 }
             } else {
-                uint32_t n, px, oh, ow;
+                uint32_t n0_, p0_, n, px, oh, ow;
+                cp.colP.divmod((uint32_t)row0, n0_, p0_);
                 cp.colP.divmod(jj, n, px);
                 cp.ic.OW.divmod(px, oh, ow);
                 ih0 = (int)oh * cp.ic.sH - cp.ic.pT;
                 iw0 = (int)ow * cp.ic.sW - cp.ic.pL;
-                col_off = (int64_t)n * cp.ic.image_stride + (int64_t)ih0 * cp.ic.W + iw0;
+                base = p + (int64_t)n0_ * cp.ic.image_stride;
+                voff[0] = (uint32_t)((int)(n - n0_) * cp.ic.image_stride + ih0 * cp.ic.W + iw0);
             }
+        }
+        rsrc = tile_rsrc(base);
+    }
+
+    __device__ inline void load(__amdgpu_buffer_rsrc_t r, uint32_t off, int soff, int p) {
+        if (VEC == 4) {
+            const floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, soff, 0));
+            reg[p * 4 + 0] = v.x; reg[p * 4 + 1] = v.y; reg[p * 4 + 2] = v.z; reg[p * 4 + 3] = v.w;
+        } else {
+            reg[p] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, soff, 0));
         }
     }
 
     // Issue the global loads of the tile whose first k is k0.
     __device__ inline void fetch(int k0, const ContractionParams& cp) {
+        if (kc) {
+            const bool k_ok = k0 + fast * VEC < K;
 #pragma unroll
-        for (int p = 0; p < NLOAD; ++p) {
-            const int slow = slow0 + p * SLOW_PER_PASS;
-            if (kc) {
-                const int row = row0 + slow;
-                const int k = k0 + fast * VEC;
-                const bool ok = active && row < rows_total && k < K;
-                const float* src = base + (int64_t)row * ld + k;
-                if (VEC == 4) {
-                    floatx4 v = {0.f, 0.f, 0.f, 0.f};
-                    if (ok) v = *reinterpret_cast<const floatx4*>(src);
-                    reg[p * 4 + 0] = v.x; reg[p * 4 + 1] = v.y; reg[p * 4 + 2] = v.z; reg[p * 4 + 3] = v.w;
-                } else {
-                    reg[p] = ok ? *src : 0.f;
-                }
-            } else if (KIND == LOAD_RC) {
-                const int k = k0 + slow;
-                const bool ok = active && col_ok && k < K;
-                const float* src = base + col_off + (int64_t)k * ld;
-                if (VEC == 4) {
-                    floatx4 v = {0.f, 0.f, 0.f, 0.f};
-                    if (ok) v = *reinterpret_cast<const floatx4*>(src);
-                    reg[p * 4 + 0] = v.x; reg[p * 4 + 1] = v.y; reg[p * 4 + 2] = v.z; reg[p * 4 + 3] = v.w;
-                } else {
-                    reg[p] = ok ? *src : 0.f;
-                }
-            } else {
+            for (int p = 0; p < NLOAD; ++p) load(rsrc, k_ok ? voff[p] : OOB, k0 * 4, p);
+        } else if (KIND == LOAD_RC) {
+            // the resource is re-based at row k0 so that offsets stay small whatever K is
+            const __amdgpu_buffer_rsrc_t r = tile_rsrc(base + (int64_t)k0 * ld);
+#pragma unroll
+            for (int p = 0; p < NLOAD; ++p) {
+                const bool good = col_ok && (k0 + slow0 + p * SLOW_PER_PASS < K);
+                load(r, good ? voff[0] : OOB, p * SLOW_PER_PASS * ld * 4, p);
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < NLOAD; ++p) {
                 // k -> (c, kh, kw); the same for every lane of a wavefront
-                const uint32_t k = (uint32_t)(k0 + slow);
+                const uint32_t k = (uint32_t)(k0 + slow0 + p * SLOW_PER_PASS);
                 uint32_t c, rem, kh, kw;
                 cp.ic.kHW.divmod(k, c, rem);
                 cp.ic.kW.divmod(rem, kh, kw);
                 const int dh = (int)kh * cp.ic.dH, dw = (int)kw * cp.ic.dW;
                 const int ih = ih0 + dh, iw = iw0 + dw;
-                const bool ok = active && col_ok && (int)k < K && ih >= 0 && ih < cp.ic.H && iw >= 0 &&
-                                iw < cp.ic.W;
-                const int64_t off = col_off + ((int64_t)c * cp.ic.H + dh) * cp.ic.W + dw;
-                reg[p] = ok ? base[off] : 0.f;
+                const bool good = col_ok && (int)k < K && (unsigned)ih < (unsigned)cp.ic.H &&
+                                  (unsigned)iw < (unsigned)cp.ic.W;
+                const int koff = ((int)c * cp.ic.H + dh) * cp.ic.W + dw;
+                load(rsrc, good ? (voff[0] + (uint32_t)koff) * 4u : OOB, 0, p);
             }
         }
     }
@@ -204,22 +233,12 @@ struct TileLoader {
 #pragma unroll
         for (int p = 0; p < NLOAD; ++p) {
             const int slow = slow0 + p * SLOW_PER_PASS;
-            if (kc) {
-                float* dst = lds + slow * LDK + fast * VEC;
-                if (VEC == 4) {
-                    floatx4 v = {reg[p * 4 + 0], reg[p * 4 + 1], reg[p * 4 + 2], reg[p * 4 + 3]};
-                    *reinterpret_cast<floatx4*>(dst) = v;
-                } else {
-                    *dst = reg[p];
-                }
+            float* dst = kc ? lds + slow * LDK + fast * VEC : lds + slow * LDR + fast * VEC;
+            if (VEC == 4) {
+                floatx4 v = {reg[p * 4 + 0], reg[p * 4 + 1], reg[p * 4 + 2], reg[p * 4 + 3]};
+                *reinterpret_cast<floatx4*>(dst) = v;
             } else {
-                float* dst = lds + slow * LDR + fast * VEC;
-                if (VEC == 4) {
-                    floatx4 v = {reg[p * 4 + 0], reg[p * 4 + 1], reg[p * 4 + 2], reg[p * 4 + 3]};
-                    *reinterpret_cast<floatx4*>(dst) = v;
-                } else {
-                    *dst = reg[p];
-                }
+                *dst = reg[p];
             }
         }
     }
@@ -244,23 +263,67 @@ __device__ inline int xcd_contiguous(int bid, int nblocks) {
     return xcd < rem ? xcd * (per + 1) + local : rem * (per + 1) + (xcd - rem) * per + local;
 }
 
-template <int BM, int BN, int WM, int WN, int AKIND, int BKIND, int VEC>
-__global__ __launch_bounds__(NTHREADS) void contraction_kernel(const ContractionParams cp) {
-    static_assert(WM * WN * 64 == NTHREADS, "four wavefronts per workgroup");
+// Epilogue for one 32x32 accumulator block: alpha*acc + beta*bias (+ residual), Relu, store.
+// Accumulator register r holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32.  Y and the
+// residual are addressed through buffer resources based at the tile's first element: `voff`
+// is the lane's byte offset for register 0 (OOB when its column does not exist), the rows
+// of the other registers are reached through the scalar offset, and a row beyond M turns
+// the offset into OOB, which makes the hardware return 0 for the load and drop the store.
+__device__ inline void store_block(const floatx16& acc, int row0, int col, uint32_t voff,
+                                   __amdgpu_buffer_rsrc_t ry, __amdgpu_buffer_rsrc_t rr, bool has_res,
+                                   const float* bz, const ContractionParams& cp) {
+    const int row_stride_bytes = (int)cp.y_rs * 4;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        float add[4];
+        uint32_t off[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int row = row0 + 8 * c + q;
+            off[q] = row < cp.M ? voff : OOB;
+            add[q] = 0.f;
+            if (bz) {
+                const int rr_ = row < cp.M ? row : 0;
+                add[q] = cp.beta * bz[rr_ * cp.bias_rs + col * cp.bias_cs];
+            }
+        }
+        if (has_res) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                add[q] += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                                        rr, (int)off[q], (8 * c + q) * row_stride_bytes, 0));
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            float v = fmaf(cp.alpha, acc[4 * c + q], add[q]);
+            if (cp.relu) v = v > 0.f ? v : 0.f;
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), ry, (int)off[q],
+                                                  (8 * c + q) * row_stride_bytes, 0);
+        }
+    }
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int AKIND, int BKIND, int VEC>
+__global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const ContractionParams cp) {
+    constexpr int NT = 64 * WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN;     // wavefront sub-tile
     constexpr int TM = WTM / 32, TN = WTN / 32;     // 32x32 accumulators per wavefront
     static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "sub-tile of 32x32 blocks");
+    static_assert(BK % 8 == 0, "K step is a multiple of the 8-wide half-step");
     constexpr int BVEC = (BKIND == LOAD_IM2COL) ? 1 : VEC;
-    using ALoader = TileLoader<AKIND, VEC, BM>;
-    using BLoader = TileLoader<BKIND, BVEC, BN>;
+    using ALoader = TileLoader<AKIND, VEC, BM, BK, NT>;
+    using BLoader = TileLoader<BKIND, BVEC, BN, BK, NT>;
 
     __shared__ __attribute__((aligned(16))) float lds_a[2][ALoader::LDS_FLOATS];
     __shared__ __attribute__((aligned(16))) float lds_b[2][BLoader::LDS_FLOATS];
 
-    // ---- which tile, which z-slice
+    const int zslice = blockIdx.y * gridDim.z + blockIdx.z;
+    if (zslice >= cp.nz) return;                    // uniform for the whole workgroup
+
+    // ---- which tile: XCD-contiguous numbering, then sweeps of 8 tile rows
     const int ntiles = cp.tiles_m * cp.tiles_n;
     const int logical = xcd_contiguous(blockIdx.x, ntiles);
-    constexpr int GROUP = 8;                        // tile rows swept together
+    constexpr int GROUP = 8;
     const int per_group = GROUP * cp.tiles_n;
     const int grp = logical / per_group;
     const int first_m = grp * GROUP;
@@ -270,8 +333,6 @@ __global__ __launch_bounds__(NTHREADS) void contraction_kernel(const Contraction
     const int tile_n = in_grp / rows_here;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-    const int zslice = blockIdx.y * gridDim.z + blockIdx.z;
-    if (zslice >= cp.nz) return;                    // uniform for the whole workgroup
     int64_t a_off = 0, b_off = 0;
     {
         int z = zslice;
@@ -282,7 +343,6 @@ __global__ __launch_bounds__(NTHREADS) void contraction_kernel(const Contraction
             b_off += idx * cp.b_bs[d];
         }
     }
-    const int64_t zi = zslice;
 
     ALoader la;
     BLoader lb;
@@ -302,10 +362,12 @@ __global__ __launch_bounds__(NTHREADS) void contraction_kernel(const Contraction
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     const int nk = (cp.K + BK - 1) / BK;
-    la.fetch(0, cp);
-    lb.fetch(0, cp);
-    la.commit(lds_a[0]);
-    lb.commit(lds_b[0]);
+    if (nk > 0) {
+        la.fetch(0, cp);
+        lb.fetch(0, cp);
+        la.commit(lds_a[0]);
+        lb.commit(lds_b[0]);
+    }
     __syncthreads();
 
     for (int kt = 0; kt < nk; ++kt) {
@@ -316,21 +378,26 @@ __global__ __launch_bounds__(NTHREADS) void contraction_kernel(const Contraction
         }
         const float* sa = lds_a[cur];
         const float* sb = lds_b[cur];
+        float fa[BK / 8][TM][4], fb[BK / 8][TN][4];
 #pragma unroll
-        for (int g = 0; g < 2; ++g) {
-            float fa[TM][4], fb[TN][4];
+        for (int g = 0; g < BK / 8; ++g) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) ALoader::frag(sa, wm * WTM + i * 32 + li, g, h, fa[i]);
+            for (int i = 0; i < TM; ++i) ALoader::frag(sa, wm * WTM + i * 32 + li, g, h, fa[g][i]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) BLoader::frag(sb, wn * WTN + j * 32 + li, g, h, fb[j]);
+            for (int j = 0; j < TN; ++j) BLoader::frag(sb, wn * WTN + j * 32 + li, g, h, fb[g][j]);
+        }
+        // keep every LDS read of the step ahead of its MFMAs (the scheduler would otherwise
+        // interleave them one by one and expose the LDS latency before each MFMA group)
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 0; g < BK / 8; ++g)
 #pragma unroll
             for (int s = 0; s < 4; ++s)
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][s], fb[j][s], acc[i][j], 0, 0, 0);
-        }
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[g][i][s], fb[g][j][s], acc[i][j], 0, 0, 0);
         if (kt + 1 < nk) {
             la.commit(lds_a[cur ^ 1]);
             lb.commit(lds_b[cur ^ 1]);
@@ -338,34 +405,38 @@ __global__ __launch_bounds__(NTHREADS) void contraction_kernel(const Contraction
         __syncthreads();
     }
 
-    // ---- epilogue: alpha*acc + beta*bias (+ residual), Relu, store.
-    // Accumulator register r of a 32x32 block holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32.
-    float* yz = cp.Y + zi * cp.y_zs;
-    const float* rz = cp.residual ? cp.residual + zi * cp.y_zs : nullptr;
+    // ---- epilogue
+    const int64_t zi = zslice;
     const float* bz = cp.bias ? cp.bias + zi * cp.bias_zs : nullptr;
+    int64_t tile_off = (int64_t)m0 * cp.y_rs + n0;          // first element of the tile in Y
+    uint32_t img0 = 0;
+    if (cp.col_images) {
+        uint32_t px0;
+        cp.colP.divmod((uint32_t)n0, img0, px0);
+        tile_off = (int64_t)m0 * cp.y_rs + (int64_t)img0 * cp.y_img + px0;
+    }
+    tile_off += zi * cp.y_zs;
+    const __amdgpu_buffer_rsrc_t ry = tile_rsrc(cp.Y + tile_off);
+    const bool has_res = cp.residual != nullptr;
+    const __amdgpu_buffer_rsrc_t rr = tile_rsrc(has_res ? cp.residual + tile_off : cp.Y + tile_off);
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wn * WTN + j * 32 + li;
-        if (col >= cp.N) continue;
-        int64_t coff = col;
+        const int cl = wn * WTN + j * 32 + li;            // column within the tile
+        const int col = n0 + cl;
+        const bool col_ok = col < cp.N;
+        const int cj = col_ok ? col : n0;
+        int crel = cl;                                    // element offset from the tile's first column
         if (cp.col_images) {
-            uint32_t n, px;
-            cp.colP.divmod((uint32_t)col, n, px);
-            coff = (int64_t)n * cp.y_img + px;
+            uint32_t n, px, px0;
+            cp.colP.divmod((uint32_t)cj, n, px);
+            px0 = (uint32_t)n0 - img0 * cp.colP.d;
+            crel = (int)(n - img0) * (int)cp.y_img + (int)px - (int)px0;
         }
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * h + (r % 4);
-                if (row >= cp.M) continue;
-                float v = cp.alpha * acc[i][j][r];
-                if (bz) v += cp.beta * bz[row * cp.bias_rs + col * cp.bias_cs];
-                const int64_t o = (int64_t)row * cp.y_rs + coff;
-                if (rz) v += rz[o];
-                if (cp.relu) v = v > 0.f ? v : 0.f;
-                yz[o] = v;
-            }
+            const int rl = wm * WTM + i * 32 + 4 * h;     // row within the tile of register 0
+            const uint32_t voff = col_ok ? (uint32_t)(rl * (int)cp.y_rs + crel) * 4u : OOB;
+            store_block(acc[i][j], m0 + rl, cj, voff, ry, rr, has_res, bz, cp);
         }
     }
 }

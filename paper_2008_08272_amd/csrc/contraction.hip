@@ -3,7 +3,7 @@
 
 namespace onnxhip {
 
-template <int BM, int BN, int WM, int WN, int AK, int BKIND, int VEC>
+template <int BM, int BN, int BK, int WM, int WN, int AK, int BKIND, int VEC>
 static hipError_t launch_one(ContractionParams& p, int nz, hipStream_t stream) {
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
@@ -12,7 +12,7 @@ static hipError_t launch_one(ContractionParams& p, int nz, hipStream_t stream) {
     const unsigned gy = ((unsigned)nz + gz - 1) / gz;
     if ((int64_t)p.tiles_m * p.tiles_n > 0x7fffffffLL || gy > 65535u) return hipErrorInvalidValue;
     const dim3 grid((unsigned)(p.tiles_m * p.tiles_n), gy, gz);
-    hipLaunchKernelGGL((contraction_kernel<BM, BN, WM, WN, AK, BKIND, VEC>), grid, dim3(NTHREADS), 0,
+    hipLaunchKernelGGL((contraction_kernel<BM, BN, BK, WM, WN, AK, BKIND, VEC>), grid, dim3(64 * WM * WN), 0,
                        stream, p);
     return hipGetLastError();
 }
@@ -20,8 +20,8 @@ static hipError_t launch_one(ContractionParams& p, int nz, hipStream_t stream) {
 template <int AK, int BKIND, int VEC>
 static hipError_t launch_tile(ContractionParams& p, int tile, int nz, hipStream_t stream) {
     switch (tile) {
-        case TILE_128x128: return launch_one<128, 128, 2, 2, AK, BKIND, VEC>(p, nz, stream);
-        case TILE_64x64: return launch_one<64, 64, 2, 2, AK, BKIND, VEC>(p, nz, stream);
+        case TILE_128x128: return launch_one<128, 128, 16, 2, 2, AK, BKIND, VEC>(p, nz, stream);
+        case TILE_64x64: return launch_one<64, 64, 16, 2, 2, AK, BKIND, VEC>(p, nz, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -9,9 +9,6 @@ namespace onnxhip {
 
 enum TileShape { TILE_128x128 = 0, TILE_64x64 = 1, TILE_COUNT };
 
-inline int tile_bm(int t) { return t == TILE_128x128 ? 128 : 64; }
-inline int tile_bn(int t) { return t == TILE_128x128 ? 128 : 64; }
-
 // Fills tiles_m / tiles_n of `p` for the chosen tile and enqueues the kernel instance for
 // (akind, bkind, vec).  nz = number of z-slices (grid.z).
 hipError_t launch_contraction(ContractionParams& p, int akind, int bkind, int vec, int tile,
