@@ -86,7 +86,7 @@ def main():
     achieved = flop_4096 / (k4096_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 3), "peak": MFMA_FP32_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / MFMA_FP32_PEAK_TFLOPS, 4), "traffic": None,
-                "kernel": "contraction_kernel<128,128,KC,KC,vec4> on Gemm 4096^3",
+                "kernel": "contraction_kernel<256,256,16; KC,KC; 16-byte loads> on Gemm 4096^3",
                 "avg_launch_ms": round(k4096_ms, 4), "algorithmic_flop": flop_4096,
                 "algorithmic_bytes": bytes_4096}
 

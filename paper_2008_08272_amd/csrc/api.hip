@@ -61,12 +61,6 @@ const int64_t kTileRows = 256, kTileK = 32, kSpan = (1LL << 31) - 64;
 bool kc_fits(int64_t ld, int64_t K) { return (kTileRows * ld + K) * 4 < kSpan; }
 bool rc_fits(int64_t ld, int64_t lead) { return (kTileK * ld + lead) * 4 < kSpan; }
 
-int pick_tile(int64_t M, int64_t N, int64_t nz) {
-    const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128) * nz;
-    if (M > 64 && N > 64 && t128 >= 192) return TILE_128x128;
-    return TILE_64x64;
-}
-
 void no_batch(ContractionParams& p) {
     p.nbd = 0;
     for (int i = 0; i < MAX_BATCH_DIMS; ++i) { p.bdim[i] = 1; p.a_bs[i] = 0; p.b_bs[i] = 0; }

@@ -197,11 +197,11 @@ struct TileLoader {
 
     // Issue the global loads of the tile whose first k is k0.
     __device__ inline void fetch(int k0, const ContractionParams& cp) {
-        if (kc) {
+        if constexpr (kc) {
             const bool k_ok = k0 + fast * VEC < K;
 #pragma unroll
             for (int p = 0; p < NLOAD; ++p) load(rsrc, k_ok ? voff[p] : OOB, k0 * 4, p);
-        } else if (KIND == LOAD_RC) {
+        } else if constexpr (KIND == LOAD_RC) {
             // the resource is re-based at row k0 so that offsets stay small whatever K is
             const __amdgpu_buffer_rsrc_t r = tile_rsrc(base + (int64_t)k0 * ld);
 #pragma unroll
@@ -210,18 +210,25 @@ struct TileLoader {
                 load(r, good ? voff[0] : OOB, p * SLOW_PER_PASS * ld * 4, p);
             }
         } else {
+            // k -> (c, kh, kw) is the same for every column, so the BK decompositions of this
+            // step are computed once, lane q of each wavefront taking k0 + q; each load then
+            // fetches the one it needs from that lane (its k row is uniform per wavefront).
+            static_assert(FAST % 64 == 0 && BK <= 64, "IM2COL tiles: columns in multiples of 64");
+            const uint32_t kq = (uint32_t)(k0 + (int)(threadIdx.x & (BK - 1)));
+            uint32_t c, rem, kh, kw;
+            cp.ic.kHW.divmod(kq, c, rem);
+            cp.ic.kW.divmod(rem, kh, kw);
+            const int dh_l = (int)kh * cp.ic.dH, dw_l = (int)kw * cp.ic.dW;
+            const int koff_l = (int)kq < K ? ((int)c * cp.ic.H + dh_l) * cp.ic.W + dw_l : -1;
+            const int dhw_l = (dh_l << 16) | dw_l;
 #pragma unroll
             for (int p = 0; p < NLOAD; ++p) {
-                // k -> (c, kh, kw); the same for every lane of a wavefront
-                const uint32_t k = (uint32_t)(k0 + slow0 + p * SLOW_PER_PASS);
-                uint32_t c, rem, kh, kw;
-                cp.ic.kHW.divmod(k, c, rem);
-                cp.ic.kW.divmod(rem, kh, kw);
-                const int dh = (int)kh * cp.ic.dH, dw = (int)kw * cp.ic.dW;
-                const int ih = ih0 + dh, iw = iw0 + dw;
-                const bool good = col_ok && (int)k < K && (unsigned)ih < (unsigned)cp.ic.H &&
+                const int q = slow0 + p * SLOW_PER_PASS;
+                const int koff = __builtin_amdgcn_readlane(koff_l, q);
+                const int dhw = __builtin_amdgcn_readlane(dhw_l, q);
+                const int ih = ih0 + (dhw >> 16), iw = iw0 + (dhw & 0xffff);
+                const bool good = col_ok && koff >= 0 && (unsigned)ih < (unsigned)cp.ic.H &&
                                   (unsigned)iw < (unsigned)cp.ic.W;
-                const int koff = ((int)c * cp.ic.H + dh) * cp.ic.W + dw;
                 load(rsrc, good ? (voff[0] + (uint32_t)koff) * 4u : OOB, 0, p);
             }
         }

@@ -7,7 +7,14 @@
 
 namespace onnxhip {
 
-enum TileShape { TILE_128x128 = 0, TILE_64x64 = 1, TILE_COUNT };
+// Workgroup tiles of the contraction kernel (rows x columns x K step, wavefront grid):
+//   TILE_64   64 x  64 x 32, 2x2 wavefronts  -- small problems, up to 8 workgroups per CU
+//   TILE_128 128 x 128 x 16, 4x2 wavefronts  -- the general case
+//   TILE_256 256 x 256 x 16, 4x4 wavefronts  -- large products, one workgroup per CU
+enum TileShape { TILE_64 = 0, TILE_128 = 1, TILE_256 = 2, TILE_COUNT };
+
+// Picks the tile with the lowest estimated time for an M x N output repeated nz times.
+int pick_tile(int64_t M, int64_t N, int64_t nz);
 
 // Fills tiles_m / tiles_n of `p` for the chosen tile and enqueues the kernel instance for
 // (akind, bkind, vec).  nz = number of z-slices (grid.z).
