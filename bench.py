@@ -30,6 +30,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-details", action="store_true", help="skip the ResNet-50 / attribute-sweep extras")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (a known-size kernel against which "
+                         "hardware byte counters of a profiler run can be scaled)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -47,6 +50,13 @@ def main():
 
     def up(a):
         return torch.from_numpy(a).to(dev)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- headline: Gemm sweep -------------------------------------------------------------
     cases = []

@@ -310,6 +310,72 @@ __device__ inline void store_block(const floatx16& acc, int row0, int col, uint3
     }
 }
 
+// Which tile a workgroup owns: XCD-contiguous numbering, then sweeps of 8 tile rows so that
+// the workgroups running together share A rows and B columns.
+__device__ inline void tile_origin(const ContractionParams& cp, int BM, int BN, int& m0, int& n0) {
+    const int ntiles = cp.tiles_m * cp.tiles_n;
+    const int logical = xcd_contiguous(blockIdx.x, ntiles);
+    constexpr int GROUP = 8;
+    const int per_group = GROUP * cp.tiles_n;
+    const int grp = logical / per_group;
+    const int first_m = grp * GROUP;
+    const int rows_here = min(cp.tiles_m - first_m, GROUP);
+    const int in_grp = logical - grp * per_group;
+    m0 = (first_m + in_grp % rows_here) * BM;
+    n0 = (in_grp / rows_here) * BN;
+}
+
+// Offsets of the z-slice's A and B operands (batch broadcasting / convolution groups).
+__device__ inline void slice_offsets(const ContractionParams& cp, int zslice, int64_t& a_off, int64_t& b_off) {
+    a_off = 0; b_off = 0;
+    int z = zslice;
+    for (int d = cp.nbd - 1; d >= 0; --d) {
+        const int idx = z % cp.bdim[d];
+        z /= cp.bdim[d];
+        a_off += idx * cp.a_bs[d];
+        b_off += idx * cp.b_bs[d];
+    }
+}
+
+// Epilogue of a workgroup tile whose wavefront (wm, wn) holds TM x TN accumulator blocks.
+template <int TM, int TN, int WTM, int WTN>
+__device__ inline void store_tile(const floatx16 (&acc)[TM][TN], int m0, int n0, int zslice, int wm, int wn,
+                                  int li, int h, const ContractionParams& cp) {
+    const int64_t zi = zslice;
+    const float* bz = cp.bias ? cp.bias + zi * cp.bias_zs : nullptr;
+    int64_t tile_off = (int64_t)m0 * cp.y_rs + n0;          // first element of the tile in Y
+    uint32_t img0 = 0;
+    if (cp.col_images) {
+        uint32_t px0;
+        cp.colP.divmod((uint32_t)n0, img0, px0);
+        tile_off = (int64_t)m0 * cp.y_rs + (int64_t)img0 * cp.y_img + px0;
+    }
+    tile_off += zi * cp.y_zs;
+    const __amdgpu_buffer_rsrc_t ry = tile_rsrc(cp.Y + tile_off);
+    const bool has_res = cp.residual != nullptr;
+    const __amdgpu_buffer_rsrc_t rr = tile_rsrc(has_res ? cp.residual + tile_off : cp.Y + tile_off);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int cl = wn * WTN + j * 32 + li;            // column within the tile
+        const int col = n0 + cl;
+        const bool col_ok = col < cp.N;
+        const int cj = col_ok ? col : n0;
+        int crel = cl;                                    // element offset from the tile's first column
+        if (cp.col_images) {
+            uint32_t n, px, px0;
+            cp.colP.divmod((uint32_t)cj, n, px);
+            px0 = (uint32_t)n0 - img0 * cp.colP.d;
+            crel = (int)(n - img0) * (int)cp.y_img + (int)px - (int)px0;
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int rl = wm * WTM + i * 32 + 4 * h;     // row within the tile of register 0
+            const uint32_t voff = col_ok ? (uint32_t)(rl * (int)cp.y_rs + crel) * 4u : OOB;
+            store_block(acc[i][j], m0 + rl, cj, voff, ry, rr, has_res, bz, cp);
+        }
+    }
+}
+
 template <int BM, int BN, int BK, int WM, int WN, int AKIND, int BKIND, int VEC>
 __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const ContractionParams cp) {
     constexpr int NT = 64 * WM * WN;
@@ -327,29 +393,10 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
     const int zslice = blockIdx.y * gridDim.z + blockIdx.z;
     if (zslice >= cp.nz) return;                    // uniform for the whole workgroup
 
-    // ---- which tile: XCD-contiguous numbering, then sweeps of 8 tile rows
-    const int ntiles = cp.tiles_m * cp.tiles_n;
-    const int logical = xcd_contiguous(blockIdx.x, ntiles);
-    constexpr int GROUP = 8;
-    const int per_group = GROUP * cp.tiles_n;
-    const int grp = logical / per_group;
-    const int first_m = grp * GROUP;
-    const int rows_here = min(cp.tiles_m - first_m, GROUP);
-    const int in_grp = logical - grp * per_group;
-    const int tile_m = first_m + in_grp % rows_here;
-    const int tile_n = in_grp / rows_here;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-    int64_t a_off = 0, b_off = 0;
-    {
-        int z = zslice;
-        for (int d = cp.nbd - 1; d >= 0; --d) {
-            const int idx = z % cp.bdim[d];
-            z /= cp.bdim[d];
-            a_off += idx * cp.a_bs[d];
-            b_off += idx * cp.b_bs[d];
-        }
-    }
+    int m0, n0;
+    tile_origin(cp, BM, BN, m0, n0);
+    int64_t a_off, b_off;
+    slice_offsets(cp, zslice, a_off, b_off);
 
     ALoader la;
     BLoader lb;
@@ -412,40 +459,7 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
         __syncthreads();
     }
 
-    // ---- epilogue
-    const int64_t zi = zslice;
-    const float* bz = cp.bias ? cp.bias + zi * cp.bias_zs : nullptr;
-    int64_t tile_off = (int64_t)m0 * cp.y_rs + n0;          // first element of the tile in Y
-    uint32_t img0 = 0;
-    if (cp.col_images) {
-        uint32_t px0;
-        cp.colP.divmod((uint32_t)n0, img0, px0);
-        tile_off = (int64_t)m0 * cp.y_rs + (int64_t)img0 * cp.y_img + px0;
-    }
-    tile_off += zi * cp.y_zs;
-    const __amdgpu_buffer_rsrc_t ry = tile_rsrc(cp.Y + tile_off);
-    const bool has_res = cp.residual != nullptr;
-    const __amdgpu_buffer_rsrc_t rr = tile_rsrc(has_res ? cp.residual + tile_off : cp.Y + tile_off);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int cl = wn * WTN + j * 32 + li;            // column within the tile
-        const int col = n0 + cl;
-        const bool col_ok = col < cp.N;
-        const int cj = col_ok ? col : n0;
-        int crel = cl;                                    // element offset from the tile's first column
-        if (cp.col_images) {
-            uint32_t n, px, px0;
-            cp.colP.divmod((uint32_t)cj, n, px);
-            px0 = (uint32_t)n0 - img0 * cp.colP.d;
-            crel = (int)(n - img0) * (int)cp.y_img + (int)px - (int)px0;
-        }
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int rl = wm * WTM + i * 32 + 4 * h;     // row within the tile of register 0
-            const uint32_t voff = col_ok ? (uint32_t)(rl * (int)cp.y_rs + crel) * 4u : OOB;
-            store_block(acc[i][j], m0 + rl, cj, voff, ry, rr, has_res, bz, cp);
-        }
-    }
+    store_tile<TM, TN, WTM, WTN>(acc, m0, n0, zslice, wm, wn, li, h, cp);
 }
 
 }  // namespace onnxhip
