@@ -226,6 +226,11 @@ onnx_status onnx_conv(const float* X, const int64_t x_dims[4], const float* W, c
         p.ic.OW = FastDiv::make((uint32_t)OW);
         p.ic.image_stride = (int)(C * H * Wd);
     }
+    if (bkind == LOAD_IM2COL && a_vec) {
+        hipError_t e = hipSuccess;
+        if (launch_conv_window(p, (int)kH, (int)kW, (int)OH, (int)OW, (int)Cg, (int)group, s, &e))
+            return device_status(e, "conv (lds patch)");
+    }
     const int tile = pick_tile(Mg, NP, group);
     return device_status(launch_contraction(p, LOAD_KC, bkind, vec, tile, (int)group, s), "conv (mfma)");
 }

@@ -72,6 +72,11 @@ struct Im2colGeom {
     int sH, sW, pT, pL, dH, dW;
     FastDiv kHW, kW, OW;     // divisors: kH*kW, kW, OW
     int image_stride;        // C*H*W
+    // LDS-patch convolution (conv_window.h) only:
+    int OH, Cg;              // output height, input channels per group
+    int E, IPR;              // window extent (kH-1)*dH+1; patch rows of one whole image (OH-1)*sH+E
+    int PC, plane;           // patch columns (OW-1)*sW+(kW-1)*dW+1; floats per channel = patch rows * PC
+    FastDiv OHd, PCd, planed, IPRd;
 };
 
 struct ContractionParams {

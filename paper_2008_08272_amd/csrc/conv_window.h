@@ -1,0 +1,189 @@
+// Convolution with an LDS-resident input patch, on the matrix cores.
+//
+// The generic implicit-GEMM path gathers every (k, pixel) element of the patch matrix from
+// global memory: a KH x KW filter re-reads each input value KH*KW times and pays an address
+// computation per element.  Here a workgroup loads, per step of 4 input channels, the
+// rectangle of input rows and columns its BN output pixels touch (the "patch", zero padding
+// included) into LDS once, and every filter tap reads it from there at lane base + a uniform
+// offset.  Same ONNX Conv semantics (Section 4.1 of the paper lists convolution among the
+// supported operators; Section 4.2's ResNet50 spends nearly all its arithmetic in them).
+//
+// Tiling is the same as in contraction.h (BM output channels x BN consecutive positions of
+// the flattened (image, oh, ow) index), so the epilogue is shared.  The output rows a tile
+// touches may belong to several images; patch rows are laid out image after image:
+//   image a = 0 (the tile's first):  rows for oh = oh0 .. OH-1      start at patch row 0
+//   image a >= 1:                    rows for oh = 0 .. OH-1        start at PS1 + (a-1)*IPR
+// with PS1 = (OH-1-oh0)*sH + E, IPR = (OH-1)*sH + E, E = (KH-1)*dH + 1.  Output row oh of image a
+// reads patch rows start(a) + (oh - first oh of a)*sH + kh*dH, columns ow*sW + kw*dW.
+//
+// K is walked 4 channels at a time.  One MFMA (32x32x2) consumes two k: lanes 0-31 supply
+// channel 2c', lanes 32-63 channel 2c'+1, both at the same tap; A (filters, [row][4*KH*KW+1]
+// in LDS) and B (patch, [channel][patch row][patch col]) use the same dealing.
+#pragma once
+#include "contraction.h"
+
+namespace onnxhip {
+
+constexpr int WIN_CB = 4;      // input channels per K step
+
+template <int BM, int BN, int WM, int WN, int KH, int KW, int MAXPB>
+__global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const ContractionParams cp) {
+    constexpr int NT = 64 * WM * WN;
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int KHW = KH * KW;
+    constexpr int KA = WIN_CB * KHW;            // filter values per row per step (contiguous in W)
+    constexpr int LDA = KA + 1;                 // odd row stride: conflict-free column reads
+    constexpr int NA4 = BM * KA / 4;            // 16-byte loads per A tile
+    constexpr int PA = (NA4 + NT - 1) / NT;
+    static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "sub-tile of 32x32 blocks");
+
+    __shared__ float lds_a[2][BM * LDA];
+    __shared__ float lds_b[2][MAXPB * NT];
+
+    const int zslice = blockIdx.y * gridDim.z + blockIdx.z;
+    if (zslice >= cp.nz) return;
+    int m0, n0;
+    tile_origin(cp, BM, BN, m0, n0);
+    int64_t a_off, b_off;
+    slice_offsets(cp, zslice, a_off, b_off);
+    const Im2colGeom& g = cp.ic;
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int li = lane & 31, h = lane >> 5;
+
+    // ---- geometry of this tile's patch
+    uint32_t q_first, ow_first, img_first, oh0;
+    g.OW.divmod((uint32_t)n0, q_first, ow_first);
+    g.OHd.divmod(q_first, img_first, oh0);
+    const int PS1 = (g.OH - 1 - (int)oh0) * g.sH + g.E;
+    const int n_images = cp.N / (int)cp.colP.d;      // images in the batch
+
+    // ---- filter tile loader: thread -> (row, 16-byte chunk), fixed for the whole K walk
+    const float* a_base = cp.A + a_off + (int64_t)m0 * cp.K;
+    const __amdgpu_buffer_rsrc_t ra = tile_rsrc(a_base);
+    uint32_t voff_a[PA];
+    int dst_a[PA];
+#pragma unroll
+    for (int p = 0; p < PA; ++p) {
+        const int e = t + p * NT;
+        const int row = e / KHW, q = e % KHW;        // KA/4 == KHW chunks per row
+        const bool ok = e < NA4 && m0 + row < cp.M;
+        voff_a[p] = ok ? (uint32_t)(row * cp.K + q * 4) * 4u : OOB;
+        dst_a[p] = (e < NA4 ? row : 0) * LDA + q * 4;
+    }
+    // ---- patch loader: thread -> (channel, patch row, patch col), fixed for the whole K walk
+    const float* b_base = cp.B + b_off + (int64_t)img_first * g.image_stride;
+    const __amdgpu_buffer_rsrc_t rb = tile_rsrc(b_base);
+    const int HW = g.H * g.W;
+    uint32_t voff_b[MAXPB];
+#pragma unroll
+    for (int p = 0; p < MAXPB; ++p) {
+        const uint32_t e = (uint32_t)(t + p * NT);
+        uint32_t c, rem, pr, pc;
+        g.planed.divmod(e, c, rem);
+        g.PCd.divmod(rem, pr, pc);
+        uint32_t a = 0, local = pr;
+        if ((int)pr >= PS1) {
+            g.IPRd.divmod(pr - (uint32_t)PS1, a, local);
+            a += 1;
+        }
+        const int ih = (a == 0 ? (int)oh0 * g.sH : 0) - g.pT + (int)local;
+        const int iw = (int)pc - g.pL;
+        const bool ok = c < (uint32_t)WIN_CB && (int)(img_first + a) < n_images && (unsigned)ih < (unsigned)g.H &&
+                        (unsigned)iw < (unsigned)g.W;
+        voff_b[p] = ok ? (uint32_t)((int)a * g.image_stride + (int)c * HW + ih * g.W + iw) * 4u : OOB;
+    }
+    // ---- where this lane reads its operands for the MFMAs
+    int rd_a[TM], rd_b[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) rd_a[i] = (wm * WTM + i * 32 + li) * LDA + h * KHW;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        int col = n0 + wn * WTN + j * 32 + li;
+        if (col >= cp.N) col = n0;
+        uint32_t q, ow, img, oh;
+        g.OW.divmod((uint32_t)col, q, ow);
+        g.OHd.divmod(q, img, oh);
+        const int a = (int)(img - img_first);
+        const int prow = a == 0 ? ((int)oh - (int)oh0) * g.sH : PS1 + (a - 1) * g.IPR + (int)oh * g.sH;
+        rd_b[j] = prow * g.PC + (int)ow * g.sW + h * g.plane;
+    }
+    int tap_b[KHW];                                  // uniform patch offset of each tap
+#pragma unroll
+    for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < KW; ++kw) tap_b[kh * KW + kw] = kh * g.dH * g.PC + kw * g.dW;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    floatx4 reg_a[PA];
+    float reg_b[MAXPB];
+    const int npb = (WIN_CB * g.plane + NT - 1) / NT;    // patch passes in use (uniform, <= MAXPB)
+
+    auto fetch = [&](int ks) {
+#pragma unroll
+        for (int p = 0; p < PA; ++p)
+            reg_a[p] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(ra, (int)voff_a[p], ks * KA * 4, 0));
+#pragma unroll
+        for (int p = 0; p < MAXPB; ++p)
+            if (p < npb)
+                reg_b[p] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, (int)voff_b[p], ks * WIN_CB * HW * 4, 0));
+    };
+    auto commit = [&](int buf) {
+#pragma unroll
+        for (int p = 0; p < PA; ++p) {
+            if (t + p * NT < NA4) {
+                float* d = lds_a[buf] + dst_a[p];
+                d[0] = reg_a[p].x; d[1] = reg_a[p].y; d[2] = reg_a[p].z; d[3] = reg_a[p].w;
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < MAXPB; ++p)
+            if (p < npb) lds_b[buf][t + p * NT] = reg_b[p];
+    };
+
+    const int nks = g.Cg / WIN_CB;
+    if (nks > 0) {
+        fetch(0);
+        commit(0);
+    }
+    __syncthreads();
+    for (int ks = 0; ks < nks; ++ks) {
+        const int cur = ks & 1;
+        if (ks + 1 < nks) fetch(ks + 1);
+        const float* sa = lds_a[cur];
+        const float* sb = lds_b[cur];
+#pragma unroll
+        for (int cc = 0; cc < WIN_CB / 2; ++cc) {
+            float fa[KHW][TM], fb[KHW][TN];
+#pragma unroll
+            for (int tap = 0; tap < KHW; ++tap) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) fa[tap][i] = sa[rd_a[i] + 2 * cc * KHW + tap];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) fb[tap][j] = sb[rd_b[j] + 2 * cc * g.plane + tap_b[tap]];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int tap = 0; tap < KHW; ++tap)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[tap][i], fb[tap][j], acc[i][j], 0, 0, 0);
+        }
+        if (ks + 1 < nks) commit(cur ^ 1);
+        __syncthreads();
+    }
+    store_tile<TM, TN, WTM, WTN>(acc, m0, n0, zslice, wm, wn, li, h, cp);
+}
+
+}  // namespace onnxhip

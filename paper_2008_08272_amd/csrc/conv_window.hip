@@ -1,0 +1,85 @@
+// Instances of the LDS-patch convolution kernel and their launcher.
+#include "conv_window.h"
+#include "internal.h"
+
+namespace onnxhip {
+
+namespace {
+
+struct WindowConfig {
+    int bm, bn, nt, maxpb;
+    double eff;        // fraction of the MFMA rate the shape sustains on a full chip (measured)
+};
+// Keep in step with the template instances in launch_config below.
+const WindowConfig kConfigs[] = {
+    {64, 64, 256, 8, 0.75},
+    {64, 128, 256, 12, 0.80},
+    {128, 128, 512, 8, 0.85},
+};
+const int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
+
+// Patch rows a tile of `bn` consecutive output positions can need, in the worst case.
+int patch_rows(int bn, int OH, int OW, int sH, int E) {
+    const int nr = bn == 1 ? 1 : (bn - 2) / OW + 2;             // output rows touched
+    int nimg = nr == 1 ? 1 : (nr - 2) / OH + 2;                 // images touched
+    if (nimg > nr) nimg = nr;
+    const int per_image = E > sH ? E : sH;
+    return (nr - nimg) * sH + nimg * per_image;
+}
+
+template <int BM, int BN, int WM, int WN, int KH, int KW, int MAXPB>
+hipError_t launch_instance(ContractionParams& p, int nz, hipStream_t stream) {
+    p.tiles_m = (p.M + BM - 1) / BM;
+    p.tiles_n = (p.N + BN - 1) / BN;
+    p.nz = nz;
+    const unsigned gz = nz < 32768 ? (unsigned)nz : 32768u;
+    const unsigned gy = ((unsigned)nz + gz - 1) / gz;
+    if ((int64_t)p.tiles_m * p.tiles_n > 0x7fffffffLL || gy > 65535u) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((conv_window_kernel<BM, BN, WM, WN, KH, KW, MAXPB>), dim3((unsigned)(p.tiles_m * p.tiles_n), gy, gz),
+                       dim3(64 * WM * WN), 0, stream, p);
+    return hipGetLastError();
+}
+
+template <int KH, int KW>
+hipError_t launch_config(ContractionParams& p, int cfg, int nz, hipStream_t stream) {
+    switch (cfg) {
+        case 0: return launch_instance<64, 64, 2, 2, KH, KW, 8>(p, nz, stream);
+        case 1: return launch_instance<64, 128, 2, 2, KH, KW, 12>(p, nz, stream);
+        case 2: return launch_instance<128, 128, 4, 2, KH, KW, 8>(p, nz, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+bool launch_conv_window(ContractionParams& p, int kH, int kW, int OH, int OW, int Cg, int nz,
+                        hipStream_t stream, hipError_t* status) {
+    if (!(kH == 3 && kW == 3)) return false;
+    if (Cg % WIN_CB != 0) return false;
+    Im2colGeom& g = p.ic;
+    const int E = (kH - 1) * g.dH + 1;
+    const int PC = (OW - 1) * g.sW + (kW - 1) * g.dW + 1;
+    int best = -1, best_plane = 0;
+    double best_cost = 0.0;
+    for (int c = 0; c < kNumConfigs; ++c) {
+        const WindowConfig& k = kConfigs[c];
+        if (OW > k.bn) continue;
+        const int64_t plane = (int64_t)patch_rows(k.bn, OH, OW, g.sH, E) * PC;
+        if (WIN_CB * plane > (int64_t)k.maxpb * k.nt) continue;
+        const double tiles = (double)((p.M + k.bm - 1) / k.bm) * (double)((p.N + k.bn - 1) / k.bn) * nz;
+        double rounds = tiles / 256.0;
+        if (rounds < 1.0) rounds = 1.0;
+        const double cost = rounds * k.bm * k.bn / k.eff;
+        if (best < 0 || cost < best_cost) { best = c; best_cost = cost; best_plane = (int)plane; }
+    }
+    if (best < 0) return false;
+    g.OH = OH; g.Cg = Cg; g.E = E; g.IPR = (OH - 1) * g.sH + E; g.PC = PC; g.plane = best_plane;
+    g.OHd = FastDiv::make((uint32_t)OH);
+    g.PCd = FastDiv::make((uint32_t)PC);
+    g.planed = FastDiv::make((uint32_t)best_plane);
+    g.IPRd = FastDiv::make((uint32_t)g.IPR);
+    *status = launch_config<3, 3>(p, best, nz, stream);
+    return true;
+}
+
+}  // namespace onnxhip

@@ -21,6 +21,13 @@ int pick_tile(int64_t M, int64_t N, int64_t nz);
 hipError_t launch_contraction(ContractionParams& p, int akind, int bkind, int vec, int tile,
                               int nz, hipStream_t stream);
 
+// Convolution through an LDS-resident input patch (conv_window.h).  `p` must be filled as for
+// the IM2COL contraction (A = filters, B = input, ic geometry, K = Cg*kH*kW).  Returns false
+// when no instance fits this shape (the caller then uses the generic path); otherwise
+// enqueues the kernel and stores the launch status in *status.
+bool launch_conv_window(ContractionParams& p, int kH, int kW, int OH, int OW, int Cg, int nz,
+                        hipStream_t stream, hipError_t* status);
+
 struct WindowGeom {
     int N, C, H, W, OH, OW;
     int kH, kW, sH, sW, pT, pL, pB, pR, dH, dW;
