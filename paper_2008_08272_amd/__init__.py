@@ -6,4 +6,4 @@ torch device tensors into that ABI.  There is no CPU or PyTorch fallback: if the
 not been built, importing :mod:`paper_2008_08272_amd.binding` raises.
 """
 from .binding import (OnnxHipError, lib_path, onnx_avgpool, onnx_conv, onnx_conv_infer, onnx_gemm,  # noqa: F401
-                      onnx_last_error, onnx_matmul, onnx_matmul_infer, onnx_maxpool, onnx_pool_infer)
+                      onnx_last_error, onnx_matmul, onnx_set_workspace, onnx_matmul_infer, onnx_maxpool, onnx_pool_infer)

@@ -49,6 +49,25 @@ for _f in (_lib.onnx_conv_infer, _lib.onnx_pool_infer, _lib.onnx_matmul_infer, _
     _f.restype = _ci
 
 
+_lib.onnx_set_workspace.argtypes = [_vp, ctypes.c_size_t]
+_lib.onnx_set_workspace.restype = _ci
+_workspace_tensor = None
+
+
+def onnx_set_workspace(tensor):
+    """Hand a uint8 / float32 CUDA tensor to the library as split-K scratch (None removes it).
+    The binding keeps a reference so the memory outlives the calls that use it."""
+    global _workspace_tensor
+    if tensor is None:
+        _check(_lib.onnx_set_workspace(None, 0))
+        _workspace_tensor = None
+        return
+    if not (tensor.is_cuda and tensor.is_contiguous()):
+        raise TypeError("the workspace must be a contiguous tensor on the GPU")
+    _check(_lib.onnx_set_workspace(ctypes.c_void_p(tensor.data_ptr()), tensor.numel() * tensor.element_size()))
+    _workspace_tensor = tensor
+
+
 def onnx_last_error():
     return _lib.onnx_last_error().decode()
 

@@ -74,6 +74,9 @@ void no_batch(ContractionParams& p) {
     p.ic.kHW = p.ic.kW = p.ic.OW = FastDiv::make(1);
 }
 
+Workspace g_ws = {nullptr, 0, nullptr, 0};
+const int kCounters = 16384;       // arrival counters at the head of the workspace
+
 onnx_status device_status(hipError_t e, const char* what) {
     if (e == hipSuccess) return ONNX_OK;
     return fail(ONNX_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
@@ -81,9 +84,29 @@ onnx_status device_status(hipError_t e, const char* what) {
 
 }  // namespace
 
+namespace onnxhip {
+const Workspace& workspace() { return g_ws; }
+}  // namespace onnxhip
+
 extern "C" {
 
 const char* onnx_last_error(void) { return g_err; }
+
+onnx_status onnx_set_workspace(void* device_ptr, size_t bytes) {
+    g_ws = Workspace{nullptr, 0, nullptr, 0};
+    if (!device_ptr || bytes == 0) return ONNX_OK;
+    const size_t head = (size_t)kCounters * sizeof(int);
+    if ((reinterpret_cast<uintptr_t>(device_ptr) & 255u) != 0)
+        return fail(ONNX_ERR_ATTR, "workspace: the pointer must be 256-byte aligned");
+    if (bytes < head + (1u << 20)) return fail(ONNX_ERR_ATTR, "workspace: at least %zu bytes are needed", head + (1u << 20));
+    const hipError_t e = hipMemset(device_ptr, 0, head);
+    if (e != hipSuccess) return fail(ONNX_ERR_DEVICE, "workspace: %s", hipGetErrorString(e));
+    g_ws.counter = static_cast<int*>(device_ptr);
+    g_ws.counters = kCounters;
+    g_ws.partial = reinterpret_cast<float*>(static_cast<char*>(device_ptr) + head);
+    g_ws.partial_floats = (int64_t)((bytes - head) / sizeof(float));
+    return ONNX_OK;
+}
 
 onnx_status onnx_conv_infer(const int64_t x[4], const int64_t w[4], const int64_t pads[4],
                             const int64_t strides[2], const int64_t dil[2], int64_t group, int64_t y[4]) {

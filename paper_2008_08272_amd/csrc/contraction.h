@@ -101,7 +101,13 @@ struct ContractionParams {
     int64_t bias_rs, bias_cs;
     int relu;
     int tiles_m, tiles_n;
-    int nz;                  // number of z-slices; slice = blockIdx.y * gridDim.z + blockIdx.z
+    int nz;                  // number of z-slices
+    // Split-K: grid.y = ksplit * (z overflow factor).  Workgroup (tile, split) sums its share of
+    // the K steps; with ksplit > 1 it parks the partial tile in ws_partial and the last of a
+    // tile's workgroups to arrive (ws_counter) adds the partials in split order and stores Y.
+    int ksplit;
+    float* ws_partial;
+    int* ws_counter;
     Im2colGeom ic;
 };
 
@@ -381,6 +387,71 @@ __device__ inline void store_tile(const floatx16 (&acc)[TM][TN], int m0, int n0,
     }
 }
 
+// blockIdx.y carries the K split (fast) and the overflow of the z-slice count (slow).
+__device__ inline void slice_and_split(const ContractionParams& cp, int& zslice, int& split) {
+    split = blockIdx.y % cp.ksplit;
+    zslice = (blockIdx.y / cp.ksplit) * gridDim.z + blockIdx.z;
+}
+
+// The K steps [kt0, kt1) of `nk` that split `split` of `ksplit` owns.
+__device__ inline void split_range(int nk, int ksplit, int split, int& kt0, int& kt1) {
+    const int per = (nk + ksplit - 1) / ksplit;
+    kt0 = split * per;
+    kt1 = min(nk, kt0 + per);
+    if (kt0 > kt1) kt0 = kt1;
+}
+
+// End of a workgroup's K walk.  Without split-K: the epilogue.  With split-K: store the
+// partial accumulators (register-major, thread-minor, so every access is coalesced), make
+// them visible device-wide, count arrivals; the workgroup that finds every other split
+// already there re-reads all partials in split order (so the sum does not depend on who
+// arrived last), runs the epilogue and re-arms the counter for the next launch.
+template <int TM, int TN, int WTM, int WTN, int NT>
+__device__ inline void finish_tile(floatx16 (&acc)[TM][TN], int m0, int n0, int zslice, int split, int wm,
+                                   int wn, int li, int h, const ContractionParams& cp) {
+    if (cp.ksplit > 1) {
+        constexpr int TILE = NT * TM * TN * 16;
+        __shared__ int s_last;
+        const int tile_lin = zslice * (cp.tiles_m * cp.tiles_n) + blockIdx.x;
+        float* base = cp.ws_partial + (int64_t)tile_lin * cp.ksplit * TILE;
+        float* mine = base + (int64_t)split * TILE + threadIdx.x;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mine[((i * TN + j) * 16 + r) * NT] = acc[i][j][r];
+        __threadfence();
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const int prev = atomicAdd(cp.ws_counter + tile_lin, 1);
+            const int last = prev == cp.ksplit - 1;
+            if (last) cp.ws_counter[tile_lin] = 0;
+            s_last = last;
+        }
+        __syncthreads();
+        if (!s_last) return;
+        __threadfence();
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        for (int s = 0; s < cp.ksplit; ++s) {
+            const float* src = base + (int64_t)s * TILE + threadIdx.x;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        acc[i][j][r] += __builtin_nontemporal_load(src + ((i * TN + j) * 16 + r) * NT);
+        }
+    }
+    store_tile<TM, TN, WTM, WTN>(acc, m0, n0, zslice, wm, wn, li, h, cp);
+}
+
 template <int BM, int BN, int BK, int WM, int WN, int AKIND, int BKIND, int VEC>
 __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const ContractionParams cp) {
     constexpr int NT = 64 * WM * WN;
@@ -395,7 +466,8 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
     __shared__ __attribute__((aligned(16))) float lds_a[2][ALoader::LDS_FLOATS];
     __shared__ __attribute__((aligned(16))) float lds_b[2][BLoader::LDS_FLOATS];
 
-    const int zslice = blockIdx.y * gridDim.z + blockIdx.z;
+    int zslice, split;
+    slice_and_split(cp, zslice, split);
     if (zslice >= cp.nz) return;                    // uniform for the whole workgroup
 
     int m0, n0;
@@ -420,18 +492,19 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int nk = (cp.K + BK - 1) / BK;
-    if (nk > 0) {
-        la.fetch(0, cp);
-        lb.fetch(0, cp);
+    int kt0, kt1;
+    split_range((cp.K + BK - 1) / BK, cp.ksplit, split, kt0, kt1);
+    if (kt0 < kt1) {
+        la.fetch(kt0 * BK, cp);
+        lb.fetch(kt0 * BK, cp);
         la.commit(lds_a[0]);
         lb.commit(lds_b[0]);
     }
     __syncthreads();
 
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) {
+    for (int kt = kt0; kt < kt1; ++kt) {
+        const int cur = (kt - kt0) & 1;
+        if (kt + 1 < kt1) {
             la.fetch((kt + 1) * BK, cp);
             lb.fetch((kt + 1) * BK, cp);
         }
@@ -457,14 +530,14 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[g][i][s], fb[g][j][s], acc[i][j], 0, 0, 0);
-        if (kt + 1 < nk) {
+        if (kt + 1 < kt1) {
             la.commit(lds_a[cur ^ 1]);
             lb.commit(lds_b[cur ^ 1]);
         }
         __syncthreads();
     }
 
-    store_tile<TM, TN, WTM, WTN>(acc, m0, n0, zslice, wm, wn, li, h, cp);
+    finish_tile<TM, TN, WTM, WTN, NT>(acc, m0, n0, zslice, split, wm, wn, li, h, cp);
 }
 
 }  // namespace onnxhip

@@ -10,8 +10,12 @@ static hipError_t launch_one(ContractionParams& p, int nz, hipStream_t stream) {
     p.nz = nz;
     const unsigned gz = nz < 32768 ? (unsigned)nz : 32768u;
     const unsigned gy = ((unsigned)nz + gz - 1) / gz;
-    if ((int64_t)p.tiles_m * p.tiles_n > 0x7fffffffLL || gy > 65535u) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)(p.tiles_m * p.tiles_n), gy, gz);
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    if (tiles > 0x7fffffffLL || gy > 2047u) return hipErrorInvalidValue;
+    p.ksplit = pick_split(tiles * nz, (p.K + BK - 1) / BK, (int64_t)BM * BN, 6.0);
+    p.ws_partial = workspace().partial;
+    p.ws_counter = workspace().counter;
+    const dim3 grid((unsigned)tiles, gy * (unsigned)p.ksplit, gz);
     hipLaunchKernelGGL((contraction_kernel<BM, BN, BK, WM, WN, AK, BKIND, VEC>), grid, dim3(64 * WM * WN), 0,
                        stream, p);
     return hipGetLastError();
@@ -44,6 +48,21 @@ int pick_tile(int64_t M, int64_t N, int64_t nz) {
         if (rounds < 1.0) rounds = 1.0;
         const double cost = rounds * bm[t] * bm[t] / eff[t];
         if (t == 0 || cost < best_cost) { best = t; best_cost = cost; }
+    }
+    return best;
+}
+
+int pick_split(int64_t tiles, int nk, int64_t tile_elems, double overhead) {
+    const Workspace& w = workspace();
+    if (!w.partial || tiles >= 512 || tiles > w.counters || nk < 4) return 1;
+    int best = 1;
+    double best_cost = 0.0;
+    for (int s = 1; s <= 32 && s * 2 <= nk; ++s) {
+        if (s > 1 && tiles * s * tile_elems > w.partial_floats) break;
+        const double per_cu = (double)((tiles * s + 255) / 256);
+        const double steps = (double)((nk + s - 1) / s) + overhead + (s > 1 ? 0.5 * s + 2.0 : 0.0);
+        const double cost = per_cu * steps;
+        if (s == 1 || cost < best_cost * 0.97) { best = s; best_cost = cost; }
     }
     return best;
 }

@@ -41,7 +41,8 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
     __shared__ float lds_a[2][BM * LDA];
     __shared__ float lds_b[2][MAXPB * NT];
 
-    const int zslice = blockIdx.y * gridDim.z + blockIdx.z;
+    int zslice, split;
+    slice_and_split(cp, zslice, split);
     if (zslice >= cp.nz) return;
     int m0, n0;
     tile_origin(cp, BM, BN, m0, n0);
@@ -150,15 +151,16 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
             if (p < npb) lds_b[buf][t + p * NT] = reg_b[p];
     };
 
-    const int nks = g.Cg / WIN_CB;
-    if (nks > 0) {
-        fetch(0);
+    int ks0, ks1;
+    split_range(g.Cg / WIN_CB, cp.ksplit, split, ks0, ks1);
+    if (ks0 < ks1) {
+        fetch(ks0);
         commit(0);
     }
     __syncthreads();
-    for (int ks = 0; ks < nks; ++ks) {
-        const int cur = ks & 1;
-        if (ks + 1 < nks) fetch(ks + 1);
+    for (int ks = ks0; ks < ks1; ++ks) {
+        const int cur = (ks - ks0) & 1;
+        if (ks + 1 < ks1) fetch(ks + 1);
         const float* sa = lds_a[cur];
         const float* sb = lds_b[cur];
 #pragma unroll
@@ -180,10 +182,10 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
                     for (int j = 0; j < TN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[tap][i], fb[tap][j], acc[i][j], 0, 0, 0);
         }
-        if (ks + 1 < nks) commit(cur ^ 1);
+        if (ks + 1 < ks1) commit(cur ^ 1);
         __syncthreads();
     }
-    store_tile<TM, TN, WTM, WTN>(acc, m0, n0, zslice, wm, wn, li, h, cp);
+    finish_tile<TM, TN, WTM, WTN, NT>(acc, m0, n0, zslice, split, wm, wn, li, h, cp);
 }
 
 }  // namespace onnxhip

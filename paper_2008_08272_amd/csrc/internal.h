@@ -16,6 +16,21 @@ enum TileShape { TILE_64 = 0, TILE_128 = 1, TILE_256 = 2, TILE_COUNT };
 // Picks the tile with the lowest estimated time for an M x N output repeated nz times.
 int pick_tile(int64_t M, int64_t N, int64_t nz);
 
+// Scratch memory for split-K, handed over by the caller through onnx_set_workspace: a block of
+// arrival counters (kept at zero between launches) followed by room for partial tiles.
+struct Workspace {
+    int* counter;
+    int counters;
+    float* partial;
+    int64_t partial_floats;
+};
+const Workspace& workspace();
+
+// How many ways to split the K walk of `tiles` workgroup tiles of `tile_elems` outputs and `nk`
+// K steps each, so that the 256 CUs are evenly loaded; 1 when the workspace cannot hold it.
+// `overhead` is a workgroup's fixed cost (prologue, epilogue) in units of one K step.
+int pick_split(int64_t tiles, int nk, int64_t tile_elems, double overhead);
+
 // Fills tiles_m / tiles_n of `p` for the chosen tile and enqueues the kernel instance for
 // (akind, bkind, vec).  nz = number of z-slices (grid.z).
 hipError_t launch_contraction(ContractionParams& p, int akind, int bkind, int vec, int tile,

@@ -14,9 +14,14 @@ from . import binding as B
 
 
 class GraphRunner:
-    def __init__(self, model, device="cuda:0", keep_all=True):
+    def __init__(self, model, device="cuda:0", workspace_bytes=64 << 20):
         self.device = torch.device(device)
         self.model = model
+        # scratch the library may use to split the K range of products with few output tiles
+        self.workspace = None
+        if workspace_bytes:
+            self.workspace = torch.empty(workspace_bytes, dtype=torch.uint8, device=self.device)
+            B.onnx_set_workspace(self.workspace)
         self.t = {}
         for k, v in list(model["inputs"].items()) + list(model["weights"].items()):
             self.t[k] = torch.from_numpy(v).to(self.device).contiguous()

@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol(B):
     text = open(os.path.join(ROOT, "include", "onnxhip.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(onnx_[a-z_0-9]+)\s*\(", text))
-    assert {"onnx_conv", "onnx_gemm", "onnx_matmul", "onnx_maxpool", "onnx_avgpool", "onnx_conv_infer",
+    assert {"onnx_set_workspace", "onnx_conv", "onnx_gemm", "onnx_matmul", "onnx_maxpool", "onnx_avgpool", "onnx_conv_infer",
             "onnx_pool_infer", "onnx_matmul_infer", "onnx_last_error"} <= names
     lib = ctypes.CDLL(B.lib_path())
     for n in sorted(names):

@@ -22,6 +22,20 @@ def lib():
     return p
 
 
+@pytest.fixture(scope="module", params=["no_workspace", "workspace"], autouse=True)
+def workspace(request, lib):
+    """Every parity case runs twice: without scratch memory (no split-K) and with a 64 MiB
+    workspace (products with few output tiles then split their K range)."""
+    if request.param == "workspace":
+        ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+        lib.onnx_set_workspace(ws)
+    else:
+        lib.onnx_set_workspace(None)
+    yield request.param
+    torch.cuda.synchronize()
+    lib.onnx_set_workspace(None)
+
+
 def dev(a):
     return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
@@ -315,6 +329,37 @@ def test_global_avgpool_matches_oracle(lib, shape):
     got = host(lib.onnx_avgpool(dev(X), None))
     assert got.shape == ref.shape
     assert rel_err(got, ref) <= REL_TOL
+
+
+def test_split_k_shapes_repeatable(lib, workspace):
+    """Few output tiles and a long K: with a workspace the K range is split and partial tiles
+    are reduced by the last workgroup to arrive.  Run each case three times: the arrival
+    counters must re-arm, and the result must not depend on arrival order (bit-identical)."""
+    announce("split-k", workspace)
+    rng = np.random.default_rng(77)
+    for (M, N, K) in [(64, 64, 4096), (100, 130, 2500), (1, 1000, 2048), (32, 1000, 2048), (256, 49, 4608)]:
+        A = rng.uniform(-1, 1, (M, K)).astype(np.float32)
+        B = rng.uniform(-1, 1, (N, K)).astype(np.float32)
+        C = rng.uniform(-1, 1, (1, N)).astype(np.float32)
+        ref, S = oracle.gemm(A, B, C, 1.0, 1.0, 0, 1, relu=False, want_scale=True)
+        a, b, c = dev(A), dev(B), dev(C)
+        outs = [host(lib.onnx_gemm(a, b, c, 1.0, 1.0, 0, 1)) for _ in range(3)]
+        assert rel_err(outs[0], ref) <= REL_TOL
+        assert within_rounding_bound(outs[0], ref, S, K + 2)
+        assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    X = rng.uniform(-1, 1, (1, 512, 7, 7)).astype(np.float32)
+    Wt = rng.uniform(-1, 1, (512, 512, 3, 3)).astype(np.float32)
+    Bv = rng.uniform(-1, 1, (512,)).astype(np.float32)
+    R = rng.uniform(-1, 1, (1, 512, 7, 7)).astype(np.float32)
+    ref = oracle.conv(X, Wt, Bv, (1, 1, 1, 1), residual=R, relu=True)
+    x, w, bv, r = dev(X), dev(Wt), dev(Bv), dev(R)
+    outs = [host(lib.onnx_conv(x, w, bv, (1, 1, 1, 1), residual=r, act=1)) for _ in range(3)]
+    assert rel_err(outs[0], ref) <= REL_TOL
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    X = rng.uniform(-1, 1, (2, 1024, 14, 14)).astype(np.float32)
+    Wt = rng.uniform(-1, 1, (256, 1024, 1, 1)).astype(np.float32)
+    ref = oracle.conv(X, Wt, None)
+    assert rel_err(host(lib.onnx_conv(dev(X), dev(Wt), None)), ref) <= REL_TOL
 
 
 # ------------------------------------------------------------------------------ degenerate sizes and errors
