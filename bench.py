@@ -126,7 +126,11 @@ def main():
             m = workloads.resnet50(batch)
             st = workloads.graph_stats(m)
             r = GraphRunner(m, dev)
-            ms = time_call(r.run, iters=10 if batch == 32 else 30, warm=3)
+            if batch == 1:
+                r.capture()             # launch-bound: one HIP graph launch per forward pass
+                ms = time_call(r.replay, iters=50, warm=3)
+            else:
+                ms = time_call(r.run, iters=10, warm=3)
             tf = 2.0 * st["macs"] / (ms * 1e-3) / 1e12
             details["resnet50_b%d" % batch] = {"ms": round(ms, 4), "img_per_s": round(batch / (ms * 1e-3), 1),
                                                "tflops": round(tf, 2),

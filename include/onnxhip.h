@@ -56,13 +56,13 @@ const char* onnx_last_error(void);
  * Optional scratch memory (Section 3.1 notes that memory management is decided once operators
  * have been lowered to loops over buffers; here the caller decides it).  The library never
  * allocates: when a workspace is set, products whose output has too few tiles to occupy the
- * GPU split their K range over several workgroups that exchange partial tiles through it;
- * without one those products run unsplit.  `device_ptr` is device memory (256-byte aligned,
- * at least 64 KiB + 1 MiB; 64 MiB serves every workload here) that the caller keeps alive and
- * does not touch while calls are in flight.  The call zeroes the first 64 KiB synchronously.
- * All calls share the workspace, so operators that may use it must not run concurrently on
- * different streams.  NULL or 0 bytes removes the workspace.  Results do not depend on it
- * beyond fp32 summation order, and are reproducible run to run for a given workspace size.
+ * GPU split their K range over several workgroups, which park partial tiles in it, and a
+ * second kernel on the same stream adds them and runs the epilogue; without a workspace those
+ * products run unsplit.  `device_ptr` is device memory (256-byte aligned, at least 1 MiB; 64
+ * MiB serves every workload here) that the caller keeps alive and does not touch while calls
+ * are in flight; it needs no initialisation.  All calls share it, so operators that may use it
+ * must not run concurrently on different streams.  NULL or 0 bytes removes the workspace.
+ * Results do not depend on it beyond fp32 summation order and are reproducible run to run.
  */
 onnx_status onnx_set_workspace(void* device_ptr, size_t bytes);
 

@@ -74,8 +74,7 @@ void no_batch(ContractionParams& p) {
     p.ic.kHW = p.ic.kW = p.ic.OW = FastDiv::make(1);
 }
 
-Workspace g_ws = {nullptr, 0, nullptr, 0};
-const int kCounters = 16384;       // arrival counters at the head of the workspace
+Workspace g_ws = {nullptr, 0};
 
 onnx_status device_status(hipError_t e, const char* what) {
     if (e == hipSuccess) return ONNX_OK;
@@ -93,18 +92,13 @@ extern "C" {
 const char* onnx_last_error(void) { return g_err; }
 
 onnx_status onnx_set_workspace(void* device_ptr, size_t bytes) {
-    g_ws = Workspace{nullptr, 0, nullptr, 0};
+    g_ws = Workspace{nullptr, 0};
     if (!device_ptr || bytes == 0) return ONNX_OK;
-    const size_t head = (size_t)kCounters * sizeof(int);
     if ((reinterpret_cast<uintptr_t>(device_ptr) & 255u) != 0)
         return fail(ONNX_ERR_ATTR, "workspace: the pointer must be 256-byte aligned");
-    if (bytes < head + (1u << 20)) return fail(ONNX_ERR_ATTR, "workspace: at least %zu bytes are needed", head + (1u << 20));
-    const hipError_t e = hipMemset(device_ptr, 0, head);
-    if (e != hipSuccess) return fail(ONNX_ERR_DEVICE, "workspace: %s", hipGetErrorString(e));
-    g_ws.counter = static_cast<int*>(device_ptr);
-    g_ws.counters = kCounters;
-    g_ws.partial = reinterpret_cast<float*>(static_cast<char*>(device_ptr) + head);
-    g_ws.partial_floats = (int64_t)((bytes - head) / sizeof(float));
+    if (bytes < (1u << 20)) return fail(ONNX_ERR_ATTR, "workspace: at least 1 MiB is needed");
+    g_ws.partial = static_cast<float*>(device_ptr);
+    g_ws.partial_floats = (int64_t)(bytes / sizeof(float));
     return ONNX_OK;
 }
 

@@ -103,11 +103,10 @@ struct ContractionParams {
     int tiles_m, tiles_n;
     int nz;                  // number of z-slices
     // Split-K: grid.y = ksplit * (z overflow factor).  Workgroup (tile, split) sums its share of
-    // the K steps; with ksplit > 1 it parks the partial tile in ws_partial and the last of a
-    // tile's workgroups to arrive (ws_counter) adds the partials in split order and stores Y.
+    // the K steps; with ksplit > 1 it parks the partial tile in ws_partial and a second kernel
+    // adds the partials in split order and stores Y.
     int ksplit;
     float* ws_partial;
-    int* ws_counter;
     Im2colGeom ic;
 };
 
@@ -401,55 +400,82 @@ __device__ inline void split_range(int nk, int ksplit, int split, int& kt0, int&
     if (kt0 > kt1) kt0 = kt1;
 }
 
-// End of a workgroup's K walk.  Without split-K: the epilogue.  With split-K: store the
-// partial accumulators (register-major, thread-minor, so every access is coalesced), make
-// them visible device-wide, count arrivals; the workgroup that finds every other split
-// already there re-reads all partials in split order (so the sum does not depend on who
-// arrived last), runs the epilogue and re-arms the counter for the next launch.
+// End of a workgroup's K walk.  Without split-K: the epilogue.  With split-K: park the partial
+// accumulators in the workspace (register-major, thread-minor, so every access is
+// coalesced); splitk_finish_kernel, launched right behind on the same stream, adds a tile's
+// partials in split order and runs the epilogue.  Two launches rather than a fence and an
+// arrival counter inside one: the XCDs' L2 caches are only coherent with each other at
+// kernel boundaries, and a device-scope fence per workgroup writes back and invalidates them.
 template <int TM, int TN, int WTM, int WTN, int NT>
 __device__ inline void finish_tile(floatx16 (&acc)[TM][TN], int m0, int n0, int zslice, int split, int wm,
                                    int wn, int li, int h, const ContractionParams& cp) {
     if (cp.ksplit > 1) {
         constexpr int TILE = NT * TM * TN * 16;
-        __shared__ int s_last;
-        const int tile_lin = zslice * (cp.tiles_m * cp.tiles_n) + blockIdx.x;
-        float* base = cp.ws_partial + (int64_t)tile_lin * cp.ksplit * TILE;
-        float* mine = base + (int64_t)split * TILE + threadIdx.x;
+        const int64_t tile_lin = (int64_t)zslice * (cp.tiles_m * cp.tiles_n) + blockIdx.x;
+        float* mine = cp.ws_partial + (tile_lin * cp.ksplit + split) * TILE + threadIdx.x;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) mine[((i * TN + j) * 16 + r) * NT] = acc[i][j][r];
-        __threadfence();
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            const int prev = atomicAdd(cp.ws_counter + tile_lin, 1);
-            const int last = prev == cp.ksplit - 1;
-            if (last) cp.ws_counter[tile_lin] = 0;
-            s_last = last;
-        }
-        __syncthreads();
-        if (!s_last) return;
-        __threadfence();
+        return;
+    }
+    store_tile<TM, TN, WTM, WTN>(acc, m0, n0, zslice, wm, wn, li, h, cp);
+}
+
+// Second half of a split-K product: one workgroup per tile, same thread-to-accumulator
+// mapping as the kernel that produced the partials.
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(64 * WM * WN) void splitk_finish_kernel(const ContractionParams cp) {
+    constexpr int NT = 64 * WM * WN;
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int TILE = NT * TM * TN * 16;
+    const int zslice = blockIdx.y * gridDim.z + blockIdx.z;
+    if (zslice >= cp.nz) return;
+    int m0, n0;
+    tile_origin(cp, BM, BN, m0, n0);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int li = lane & 31, h = lane >> 5;
+    const int64_t tile_lin = (int64_t)zslice * (cp.tiles_m * cp.tiles_n) + blockIdx.x;
+    const float* base = cp.ws_partial + tile_lin * cp.ksplit * TILE + threadIdx.x;
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    for (int s = 0; s < cp.ksplit; ++s) {
+        const float* src = base + (int64_t)s * TILE;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-        for (int s = 0; s < cp.ksplit; ++s) {
-            const float* src = base + (int64_t)s * TILE + threadIdx.x;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        acc[i][j][r] += __builtin_nontemporal_load(src + ((i * TN + j) * 16 + r) * NT);
-        }
+                for (int r = 0; r < 16; ++r) acc[i][j][r] += src[((i * TN + j) * 16 + r) * NT];
     }
     store_tile<TM, TN, WTM, WTN>(acc, m0, n0, zslice, wm, wn, li, h, cp);
+}
+
+// Host side: enqueue `kernel` for the tiles of `p` and, when the K range is split, the
+// finishing kernel behind it.
+template <int BM, int BN, int WM, int WN, typename Kernel>
+inline hipError_t launch_with_split(Kernel kernel, ContractionParams& p, int nz, hipStream_t stream) {
+    const unsigned gz = nz < 32768 ? (unsigned)nz : 32768u;
+    const unsigned gy = ((unsigned)nz + gz - 1) / gz;
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    if (tiles > 0x7fffffffLL || gy > 2047u) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)tiles, gy * (unsigned)p.ksplit, gz), dim3(64 * WM * WN), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && p.ksplit > 1) {
+        hipLaunchKernelGGL((splitk_finish_kernel<BM, BN, WM, WN>), dim3((unsigned)tiles, gy, gz), dim3(64 * WM * WN), 0,
+                           stream, p);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int AKIND, int BKIND, int VEC>

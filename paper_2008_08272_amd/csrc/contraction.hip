@@ -8,17 +8,9 @@ static hipError_t launch_one(ContractionParams& p, int nz, hipStream_t stream) {
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     p.nz = nz;
-    const unsigned gz = nz < 32768 ? (unsigned)nz : 32768u;
-    const unsigned gy = ((unsigned)nz + gz - 1) / gz;
-    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
-    if (tiles > 0x7fffffffLL || gy > 2047u) return hipErrorInvalidValue;
-    p.ksplit = pick_split(tiles * nz, (p.K + BK - 1) / BK, (int64_t)BM * BN, 6.0);
+    p.ksplit = pick_split((int64_t)p.tiles_m * p.tiles_n * nz, (p.K + BK - 1) / BK, (int64_t)BM * BN, 6.0);
     p.ws_partial = workspace().partial;
-    p.ws_counter = workspace().counter;
-    const dim3 grid((unsigned)tiles, gy * (unsigned)p.ksplit, gz);
-    hipLaunchKernelGGL((contraction_kernel<BM, BN, BK, WM, WN, AK, BKIND, VEC>), grid, dim3(64 * WM * WN), 0,
-                       stream, p);
-    return hipGetLastError();
+    return launch_with_split<BM, BN, WM, WN>(contraction_kernel<BM, BN, BK, WM, WN, AK, BKIND, VEC>, p, nz, stream);
 }
 
 template <int AK, int BKIND, int VEC>
@@ -54,13 +46,13 @@ int pick_tile(int64_t M, int64_t N, int64_t nz) {
 
 int pick_split(int64_t tiles, int nk, int64_t tile_elems, double overhead) {
     const Workspace& w = workspace();
-    if (!w.partial || tiles >= 512 || tiles > w.counters || nk < 4) return 1;
+    if (!w.partial || tiles >= 512 || nk < 4) return 1;
     int best = 1;
     double best_cost = 0.0;
     for (int s = 1; s <= 32 && s * 2 <= nk; ++s) {
         if (s > 1 && tiles * s * tile_elems > w.partial_floats) break;
         const double per_cu = (double)((tiles * s + 255) / 256);
-        const double steps = (double)((nk + s - 1) / s) + overhead + (s > 1 ? 0.5 * s + 2.0 : 0.0);
+        const double steps = (double)((nk + s - 1) / s) + overhead + (s > 1 ? 0.25 * s + 6.0 : 0.0);
         const double cost = per_cu * steps;
         if (s == 1 || cost < best_cost * 0.97) { best = s; best_cost = cost; }
     }

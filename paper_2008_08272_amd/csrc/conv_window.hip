@@ -32,16 +32,9 @@ hipError_t launch_instance(ContractionParams& p, int nz, hipStream_t stream) {
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     p.nz = nz;
-    const unsigned gz = nz < 32768 ? (unsigned)nz : 32768u;
-    const unsigned gy = ((unsigned)nz + gz - 1) / gz;
-    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
-    if (tiles > 0x7fffffffLL || gy > 2047u) return hipErrorInvalidValue;
-    p.ksplit = pick_split(tiles * nz, p.ic.Cg / WIN_CB, (int64_t)BM * BN, 4.0);
+    p.ksplit = pick_split((int64_t)p.tiles_m * p.tiles_n * nz, p.ic.Cg / WIN_CB, (int64_t)BM * BN, 4.0);
     p.ws_partial = workspace().partial;
-    p.ws_counter = workspace().counter;
-    hipLaunchKernelGGL((conv_window_kernel<BM, BN, WM, WN, KH, KW, MAXPB>), dim3((unsigned)tiles, gy * (unsigned)p.ksplit, gz),
-                       dim3(64 * WM * WN), 0, stream, p);
-    return hipGetLastError();
+    return launch_with_split<BM, BN, WM, WN>(conv_window_kernel<BM, BN, WM, WN, KH, KW, MAXPB>, p, nz, stream);
 }
 
 template <int KH, int KW>

@@ -16,11 +16,8 @@ enum TileShape { TILE_64 = 0, TILE_128 = 1, TILE_256 = 2, TILE_COUNT };
 // Picks the tile with the lowest estimated time for an M x N output repeated nz times.
 int pick_tile(int64_t M, int64_t N, int64_t nz);
 
-// Scratch memory for split-K, handed over by the caller through onnx_set_workspace: a block of
-// arrival counters (kept at zero between launches) followed by room for partial tiles.
+// Scratch memory for split-K partial tiles, handed over by the caller through onnx_set_workspace.
 struct Workspace {
-    int* counter;
-    int counters;
     float* partial;
     int64_t partial_floats;
 };

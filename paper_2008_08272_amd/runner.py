@@ -91,6 +91,21 @@ class GraphRunner:
     def set_input(self, name, array):
         self.t[name].copy_(torch.from_numpy(array))
 
+    def capture(self):
+        """Record the whole chain into a HIP graph (through torch's stream capture) so that a
+        forward pass is one graph launch instead of one host call per node; worthwhile when
+        the kernels are so short that launching them is the bottleneck (batch 1)."""
+        self.run()
+        torch.cuda.synchronize()
+        self._graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self._graph):
+            self.run()
+        return self
+
+    def replay(self):
+        self._graph.replay()
+        return self.output
+
     def run(self, stream=None):
         sp = B._stream(stream)
         for fn, args in self.calls:

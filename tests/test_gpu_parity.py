@@ -332,9 +332,9 @@ def test_global_avgpool_matches_oracle(lib, shape):
 
 
 def test_split_k_shapes_repeatable(lib, workspace):
-    """Few output tiles and a long K: with a workspace the K range is split and partial tiles
-    are reduced by the last workgroup to arrive.  Run each case three times: the arrival
-    counters must re-arm, and the result must not depend on arrival order (bit-identical)."""
+    """Few output tiles and a long K: with a workspace the K range is split, partial tiles go
+    through the workspace and a second kernel adds them in split order.  Each case runs three
+    times: the result must be bit-identical from run to run."""
     announce("split-k", workspace)
     rng = np.random.default_rng(77)
     for (M, N, K) in [(64, 64, 4096), (100, 130, 2500), (1, 1000, 2048), (32, 1000, 2048), (256, 49, 4608)]:
@@ -430,6 +430,37 @@ def test_resnet50_batch1_chain(lib):
         worst = max(worst, e)
         assert e <= REL_TOL, (nd["y"], e)
     print("resnet50 b1 worst layer error", worst, flush=True)
+    assert rel_err(got, exact["logits"]) <= REL_TOL
+
+
+def test_resnet50_batch1_graph_replay(lib):
+    """The batch-1 chain captured into a HIP graph: every replay, with eager work and
+    synchronisation in between, must reproduce the eager result bit for bit."""
+    announce("resnet50 b1 graph")
+    from paper_2008_08272_amd.runner import GraphRunner
+    m = workloads.resnet50(1)
+    r = GraphRunner(m)
+    eager = r.run().clone()
+    torch.cuda.synchronize()
+    r.capture()
+    rng = np.random.default_rng(5)
+    for i in range(4):
+        r.output.zero_()
+        junk = lib.onnx_gemm(dev(rng.uniform(-1, 1, (70, 90)).astype(np.float32)),
+                             dev(rng.uniform(-1, 1, (90, 50)).astype(np.float32)))
+        torch.cuda.synchronize()
+        out = r.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), i
+        del junk
+    # a new input through the same graph
+    x2 = rng.standard_normal(m["inputs"]["x"].shape).astype(np.float32)
+    r.set_input("x", x2)
+    got = host(r.replay())
+    from oracle import chain
+    m2 = dict(m)
+    m2["inputs"] = {"x": x2}
+    _, exact = chain.run(m2, keep=())
     assert rel_err(got, exact["logits"]) <= REL_TOL
 
 
