@@ -223,7 +223,7 @@ onnx_status onnx_conv(const float* X, const int64_t x_dims[4], const float* W, c
     p.nbd = 1; p.bdim[0] = (int)group; p.a_bs[0] = Mg * K; p.b_bs[0] = Cg * H * Wd;
     p.y_zs = Mg * P; p.bias_zs = Mg; p.y_rs = P;
     p.col_images = 1; p.colP = FastDiv::make((uint32_t)P); p.y_img = M * P; p.b_img = C * H * Wd;
-    p.alpha = 1.f; p.beta = 1.f; p.bias_rs = 1; p.bias_cs = 0; p.relu = act == ONNX_ACT_RELU;
+    p.alpha = 1.f; p.beta = 1.f; p.bias_mode = BIAS_ROW; p.bias_cs = 0; p.relu = act == ONNX_ACT_RELU;
     const bool pointwise = kH == 1 && kW == 1 && strides[0] == 1 && strides[1] == 1 && pads[0] == 0 &&
                            pads[1] == 0 && pads[2] == 0 && pads[3] == 0;
     int bkind, vec;
@@ -298,7 +298,10 @@ onnx_status onnx_gemm(const float* A, const int64_t a_dims[2], const float* B, c
     p.a_ld = a_dims[1];
     p.b_ld = b_dims[1];
     p.y_rs = N;
-    p.alpha = alpha; p.beta = beta; p.bias_rs = crs; p.bias_cs = ccs; p.relu = act == ONNX_ACT_RELU;
+    p.alpha = alpha; p.beta = beta; p.relu = act == ONNX_ACT_RELU;
+    // C broadcast: {M,N} is laid out like Y; {M,1} is one value per row; everything else one per column
+    p.bias_mode = (crs != 0 && ccs != 0) ? BIAS_FULL : (crs != 0 ? BIAS_ROW : BIAS_COL);
+    p.bias_cs = (int)ccs;
     const int akind = transA ? LOAD_RC : LOAD_KC;
     const int bkind = transB ? LOAD_KC : LOAD_RC;
     // 16-byte loads need aligned bases and every row start (and RC row extent) a multiple of 4
@@ -376,7 +379,7 @@ onnx_status onnx_matmul(const float* A, const int64_t* a_dims, int a_rank, const
     if (nz > 32768LL * 65535LL) return fail(ONNX_ERR_UNSUPPORTED, "matmul: too many batch entries");
     p.M = (int)Meff; p.N = (int)N; p.K = (int)K;
     p.a_ld = K; p.b_ld = N; p.y_rs = N; p.y_zs = M * N;
-    p.alpha = 1.f; p.beta = 0.f; p.bias_rs = 0; p.bias_cs = 0; p.relu = 0;
+    p.alpha = 1.f; p.beta = 0.f; p.bias_mode = BIAS_NONE; p.bias_cs = 0; p.relu = 0;
     const bool v4 = aligned16(A) && aligned16(B) && K % 4 == 0 && N % 4 == 0;
     const int tile = pick_tile(Meff, N, nz);
     return device_status(launch_contraction(p, LOAD_KC, LOAD_RC, v4 ? 4 : 1, tile, (int)nz,

@@ -6,9 +6,9 @@
 // never-materialised matrix of input patches [Cg*kH*kW x N*OH*OW]).
 //
 // Work decomposition: a workgroup of WM x WN wavefronts owns a BM x BN tile of Y and walks K
-// in steps of BK.  Each step stages an A tile and a B tile in LDS (double buffered: global
-// loads for step t+1 are issued before the MFMAs of step t and written to the other buffer
-// after them, one barrier per step).  Each wavefront owns a (BM/WM) x (BN/WN) sub-tile as
+// in steps of BK.  Each step stages an A tile and a B tile in LDS (double buffered; global
+// loads run one or two steps ahead of the MFMAs through register staging sets and are
+// written to the other buffer after the current step's MFMAs, one barrier per step).  Each wavefront owns a (BM/WM) x (BN/WN) sub-tile as
 // a grid of 32x32 accumulators fed by v_mfma_f32_32x32x2_f32.
 //
 // Operand kinds (how a tile is fetched and how it sits in LDS):
@@ -39,6 +39,7 @@ constexpr int MAX_BATCH_DIMS = 6;
 constexpr int NUM_XCD = 8;
 
 enum { LOAD_KC = 0, LOAD_RC = 1, LOAD_IM2COL = 2 };
+enum { BIAS_NONE = 0, BIAS_ROW = 1, BIAS_COL = 2, BIAS_FULL = 3 };
 
 // Unsigned division by a run-time constant d >= 1 for numerators below 2^31:
 // with s = floor(log2 d) and m = floor(2^(32+s)/d) + 1,  n / d == (n*m) >> (32+s).
@@ -83,7 +84,7 @@ struct ContractionParams {
     const float* A;
     const float* B;
     float* Y;
-    const float* bias;       // NULL or addressed  bias[z*bias_zs + i*bias_rs + j*bias_cs]
+    const float* bias;       // NULL or the epilogue's additive operand, see bias_mode
     const float* residual;   // NULL or laid out exactly like Y
     int M, N, K;             // extents of one z-slice
     int64_t a_ld, b_ld;      // KC: stride between rows; RC: stride between consecutive k
@@ -98,7 +99,11 @@ struct ContractionParams {
     FastDiv colP;
     int64_t y_img, b_img;
     float alpha, beta;
-    int64_t bias_rs, bias_cs;
+    // How `bias` is laid out against the M x N output: BIAS_ROW one value per row i (conv bias,
+    // Gemm C of shape {M,1}), BIAS_COL one per column j with element stride bias_cs (Gemm C of
+    // shape {N} / {1,N}; stride 0 for a scalar), BIAS_FULL an M x N matrix laid out like Y.
+    int bias_mode;
+    int bias_cs;
     int relu;
     int tiles_m, tiles_n;
     int nz;                  // number of z-slices
@@ -124,7 +129,7 @@ __device__ inline __amdgpu_buffer_rsrc_t tile_rsrc(const float* p) {
 
 // ------------------------------------------------------------------------------------------
 // Tile loader: global -> registers -> LDS for a ROWS x BK tile, NT threads.
-template <int KIND, int VEC, int ROWS, int BK, int NT>
+template <int KIND, int VEC, int ROWS, int BK, int NT, int SETS>
 struct TileLoader {
     static constexpr bool kc = (KIND == LOAD_KC);
     static constexpr int FAST = kc ? (BK / VEC) : (ROWS / VEC);   // threads along the contiguous axis
@@ -137,7 +142,7 @@ struct TileLoader {
     static_assert(NT % FAST == 0, "threads must tile the contiguous axis");
     static_assert(SLOW % SLOW_PER_PASS == 0 || SLOW < SLOW_PER_PASS, "tile/loader mismatch");
 
-    float reg[NLOAD * VEC];
+    float reg[SETS][NLOAD * VEC];   // staging sets: loads run SETS K steps ahead of the MFMAs
     int fast, slow0;
     bool active;                 // false when SLOW < SLOW_PER_PASS leaves the thread idle
     const float* base;           // first element of the tile (RC: at k = 0)
@@ -196,28 +201,30 @@ struct TileLoader {
         rsrc = tile_rsrc(base);
     }
 
+    template <int SET>
     __device__ inline void load(__amdgpu_buffer_rsrc_t r, uint32_t off, int soff, int p) {
         if (VEC == 4) {
             const floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, soff, 0));
-            reg[p * 4 + 0] = v.x; reg[p * 4 + 1] = v.y; reg[p * 4 + 2] = v.z; reg[p * 4 + 3] = v.w;
+            reg[SET][p * 4 + 0] = v.x; reg[SET][p * 4 + 1] = v.y; reg[SET][p * 4 + 2] = v.z; reg[SET][p * 4 + 3] = v.w;
         } else {
-            reg[p] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, soff, 0));
+            reg[SET][p] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, soff, 0));
         }
     }
 
-    // Issue the global loads of the tile whose first k is k0.
+    // Issue the global loads of the tile whose first k is k0 into staging set SET.
+    template <int SET>
     __device__ inline void fetch(int k0, const ContractionParams& cp) {
         if constexpr (kc) {
             const bool k_ok = k0 + fast * VEC < K;
 #pragma unroll
-            for (int p = 0; p < NLOAD; ++p) load(rsrc, k_ok ? voff[p] : OOB, k0 * 4, p);
+            for (int p = 0; p < NLOAD; ++p) load<SET>(rsrc, k_ok ? voff[p] : OOB, k0 * 4, p);
         } else if constexpr (KIND == LOAD_RC) {
             // the resource is re-based at row k0 so that offsets stay small whatever K is
             const __amdgpu_buffer_rsrc_t r = tile_rsrc(base + (int64_t)k0 * ld);
 #pragma unroll
             for (int p = 0; p < NLOAD; ++p) {
                 const bool good = col_ok && (k0 + slow0 + p * SLOW_PER_PASS < K);
-                load(r, good ? voff[0] : OOB, p * SLOW_PER_PASS * ld * 4, p);
+                load<SET>(r, good ? voff[0] : OOB, p * SLOW_PER_PASS * ld * 4, p);
             }
         } else {
             // k -> (c, kh, kw) is the same for every column, so the BK decompositions of this
@@ -239,12 +246,13 @@ struct TileLoader {
                 const int ih = ih0 + (dhw >> 16), iw = iw0 + (dhw & 0xffff);
                 const bool good = col_ok && koff >= 0 && (unsigned)ih < (unsigned)cp.ic.H &&
                                   (unsigned)iw < (unsigned)cp.ic.W;
-                load(rsrc, good ? (voff[0] + (uint32_t)koff) * 4u : OOB, 0, p);
+                load<SET>(rsrc, good ? (voff[0] + (uint32_t)koff) * 4u : OOB, 0, p);
             }
         }
     }
 
-    // Write the fetched tile into an LDS buffer.
+    // Write staging set SET into an LDS buffer.
+    template <int SET>
     __device__ inline void commit(float* lds) const {
         if (!active) return;
 #pragma unroll
@@ -252,10 +260,10 @@ struct TileLoader {
             const int slow = slow0 + p * SLOW_PER_PASS;
             float* dst = kc ? lds + slow * LDK + fast * VEC : lds + slow * LDR + fast * VEC;
             if (VEC == 4) {
-                floatx4 v = {reg[p * 4 + 0], reg[p * 4 + 1], reg[p * 4 + 2], reg[p * 4 + 3]};
+                floatx4 v = {reg[SET][p * 4 + 0], reg[SET][p * 4 + 1], reg[SET][p * 4 + 2], reg[SET][p * 4 + 3]};
                 *reinterpret_cast<floatx4*>(dst) = v;
             } else {
-                *dst = reg[p];
+                *dst = reg[SET][p];
             }
         }
     }
@@ -281,40 +289,59 @@ __device__ inline int xcd_contiguous(int bid, int nblocks) {
 }
 
 // Epilogue for one 32x32 accumulator block: alpha*acc + beta*bias (+ residual), Relu, store.
-// Accumulator register r holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32.  Y and the
-// residual are addressed through buffer resources based at the tile's first element: `voff`
-// is the lane's byte offset for register 0 (OOB when its column does not exist), the rows
-// of the other registers are reached through the scalar offset, and a row beyond M turns
-// the offset into OOB, which makes the hardware return 0 for the load and drop the store.
-__device__ inline void store_block(const floatx16& acc, int row0, int col, uint32_t voff,
-                                   __amdgpu_buffer_rsrc_t ry, __amdgpu_buffer_rsrc_t rr, bool has_res,
-                                   const float* bz, const ContractionParams& cp) {
+// Accumulator register r holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32.  Y, the
+// residual and a full-matrix bias are addressed through buffer resources based at the
+// tile's first element: `voff` is the lane's byte offset for register 0 (OOB when its column
+// does not exist) and the rows of the other registers are reached through the scalar offset.
+// GUARD adds the test for rows beyond M (only tiles on the bottom edge need it): such a row
+// turns the offset into OOB, which makes the hardware return 0 for loads and drop the store.
+struct EpilogueSrc {
+    __amdgpu_buffer_rsrc_t ry, rr, rfull, rrow;   // Y, residual, full-matrix bias, per-row bias
+    bool has_res;
+    int mode;
+    float lo;                                     // 0 with Relu, -inf without
+};
+
+template <bool GUARD>
+__device__ inline void store_block(const floatx16& acc, int row0, float col_bias, uint32_t voff,
+                                   const EpilogueSrc& e, const ContractionParams& cp) {
     const int row_stride_bytes = (int)cp.y_rs * 4;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
         float add[4];
         uint32_t off[4];
+        // four consecutive rows: one 16-byte load fetches their per-row bias
+        floatx4 rb = {0.f, 0.f, 0.f, 0.f};
+        if (e.mode == BIAS_ROW) {
+            if (!GUARD) {
+                rb = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(e.rrow, (row0 + 8 * c) * 4, 0, 0));
+            } else {     // rows may run past M: dword loads, each range-checked on its own
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int row = row0 + 8 * c + q;
-            off[q] = row < cp.M ? voff : OOB;
-            add[q] = 0.f;
-            if (bz) {
-                const int rr_ = row < cp.M ? row : 0;
-                add[q] = cp.beta * bz[rr_ * cp.bias_rs + col * cp.bias_cs];
+                for (int q = 0; q < 4; ++q)
+                    rb[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(e.rrow, (row0 + 8 * c + q) * 4, 0, 0));
             }
         }
-        if (has_res) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            off[q] = (!GUARD || row0 + 8 * c + q < cp.M) ? voff : OOB;
+            add[q] = col_bias + cp.beta * rb[q];
+        }
+        if (e.mode == BIAS_FULL) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                add[q] += cp.beta * __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                        e.rfull, (int)off[q], (8 * c + q) * row_stride_bytes, 0));
+        }
+        if (e.has_res) {
 #pragma unroll
             for (int q = 0; q < 4; ++q)
                 add[q] += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                                        rr, (int)off[q], (8 * c + q) * row_stride_bytes, 0));
+                                                        e.rr, (int)off[q], (8 * c + q) * row_stride_bytes, 0));
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            float v = fmaf(cp.alpha, acc[4 * c + q], add[q]);
-            if (cp.relu) v = v > 0.f ? v : 0.f;
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), ry, (int)off[q],
+            const float v = fmaxf(fmaf(cp.alpha, acc[4 * c + q], add[q]), e.lo);
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), e.ry, (int)off[q],
                                                   (8 * c + q) * row_stride_bytes, 0);
         }
     }
@@ -352,7 +379,6 @@ template <int TM, int TN, int WTM, int WTN>
 __device__ inline void store_tile(const floatx16 (&acc)[TM][TN], int m0, int n0, int zslice, int wm, int wn,
                                   int li, int h, const ContractionParams& cp) {
     const int64_t zi = zslice;
-    const float* bz = cp.bias ? cp.bias + zi * cp.bias_zs : nullptr;
     int64_t tile_off = (int64_t)m0 * cp.y_rs + n0;          // first element of the tile in Y
     uint32_t img0 = 0;
     if (cp.col_images) {
@@ -361,9 +387,17 @@ __device__ inline void store_tile(const floatx16 (&acc)[TM][TN], int m0, int n0,
         tile_off = (int64_t)m0 * cp.y_rs + (int64_t)img0 * cp.y_img + px0;
     }
     tile_off += zi * cp.y_zs;
-    const __amdgpu_buffer_rsrc_t ry = tile_rsrc(cp.Y + tile_off);
-    const bool has_res = cp.residual != nullptr;
-    const __amdgpu_buffer_rsrc_t rr = tile_rsrc(has_res ? cp.residual + tile_off : cp.Y + tile_off);
+    EpilogueSrc e;
+    e.ry = tile_rsrc(cp.Y + tile_off);
+    e.has_res = cp.residual != nullptr;
+    e.rr = tile_rsrc(e.has_res ? cp.residual + tile_off : cp.Y + tile_off);
+    e.mode = cp.bias ? cp.bias_mode : BIAS_NONE;
+    e.rfull = tile_rsrc(e.mode == BIAS_FULL ? cp.bias + tile_off : cp.Y + tile_off);
+    // per-row bias: a resource over exactly the M values of this z-slice, so that rows beyond
+    // M (their stores are dropped anyway) read as 0 instead of running past the array
+    const float* brow = e.mode == BIAS_ROW ? cp.bias + zi * cp.bias_zs : cp.Y;
+    e.rrow = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(brow), 0, cp.M * 4, RSRC_FLAGS);
+    e.lo = cp.relu ? 0.f : -__builtin_inff();
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int cl = wn * WTN + j * 32 + li;            // column within the tile
@@ -377,11 +411,15 @@ __device__ inline void store_tile(const floatx16 (&acc)[TM][TN], int m0, int n0,
             px0 = (uint32_t)n0 - img0 * cp.colP.d;
             crel = (int)(n - img0) * (int)cp.y_img + (int)px - (int)px0;
         }
+        float col_bias = 0.f;
+        if (e.mode == BIAS_COL) col_bias = cp.beta * cp.bias[(int64_t)cj * cp.bias_cs];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int rl = wm * WTM + i * 32 + 4 * h;     // row within the tile of register 0
             const uint32_t voff = col_ok ? (uint32_t)(rl * (int)cp.y_rs + crel) * 4u : OOB;
-            store_block(acc[i][j], m0 + rl, cj, voff, ry, rr, has_res, bz, cp);
+            // the 32 rows of this block all exist unless the block reaches past M (uniform test)
+            if (m0 + wm * WTM + i * 32 + 32 <= cp.M) store_block<false>(acc[i][j], m0 + rl, col_bias, voff, e, cp);
+            else store_block<true>(acc[i][j], m0 + rl, col_bias, voff, e, cp);
         }
     }
 }
@@ -478,16 +516,17 @@ inline hipError_t launch_with_split(Kernel kernel, ContractionParams& p, int nz,
     return e;
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int AKIND, int BKIND, int VEC>
-__global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const ContractionParams cp) {
+template <int BM, int BN, int BK, int WM, int WN, int AKIND, int BKIND, int VEC, int PF>
+__global__ __launch_bounds__(64 * WM * WN, 4) void contraction_kernel(const ContractionParams cp) {
     constexpr int NT = 64 * WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN;     // wavefront sub-tile
     constexpr int TM = WTM / 32, TN = WTN / 32;     // 32x32 accumulators per wavefront
     static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "sub-tile of 32x32 blocks");
     static_assert(BK % 8 == 0, "K step is a multiple of the 8-wide half-step");
     constexpr int BVEC = (BKIND == LOAD_IM2COL) ? 1 : VEC;
-    using ALoader = TileLoader<AKIND, VEC, BM, BK, NT>;
-    using BLoader = TileLoader<BKIND, BVEC, BN, BK, NT>;
+    static_assert(PF == 1 || PF == 2, "prefetch depth");
+    using ALoader = TileLoader<AKIND, VEC, BM, BK, NT, PF>;
+    using BLoader = TileLoader<BKIND, BVEC, BN, BK, NT, PF>;
 
     __shared__ __attribute__((aligned(16))) float lds_a[2][ALoader::LDS_FLOATS];
     __shared__ __attribute__((aligned(16))) float lds_b[2][BLoader::LDS_FLOATS];
@@ -520,22 +559,11 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
 
     int kt0, kt1;
     split_range((cp.K + BK - 1) / BK, cp.ksplit, split, kt0, kt1);
-    if (kt0 < kt1) {
-        la.fetch(kt0 * BK, cp);
-        lb.fetch(kt0 * BK, cp);
-        la.commit(lds_a[0]);
-        lb.commit(lds_b[0]);
-    }
-    __syncthreads();
 
-    for (int kt = kt0; kt < kt1; ++kt) {
-        const int cur = (kt - kt0) & 1;
-        if (kt + 1 < kt1) {
-            la.fetch((kt + 1) * BK, cp);
-            lb.fetch((kt + 1) * BK, cp);
-        }
-        const float* sa = lds_a[cur];
-        const float* sb = lds_b[cur];
+    // MFMAs of one K step from LDS buffer `buf`
+    auto compute = [&](int buf) {
+        const float* sa = lds_a[buf];
+        const float* sb = lds_b[buf];
         float fa[BK / 8][TM][4], fb[BK / 8][TN][4];
 #pragma unroll
         for (int g = 0; g < BK / 8; ++g) {
@@ -556,11 +584,73 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[g][i][s], fb[g][j][s], acc[i][j], 0, 0, 0);
-        if (kt + 1 < kt1) {
-            la.commit(lds_a[cur ^ 1]);
-            lb.commit(lds_b[cur ^ 1]);
+    };
+
+    if constexpr (PF == 1) {
+        // Software pipeline, one K step deep: the loads of step t+1 are issued before the
+        // MFMAs of step t and written to the other LDS buffer after them.
+        if (kt0 < kt1) {
+            la.template fetch<0>(kt0 * BK, cp);
+            lb.template fetch<0>(kt0 * BK, cp);
+            la.template commit<0>(lds_a[0]);
+            lb.template commit<0>(lds_b[0]);
         }
         __syncthreads();
+        for (int kt = kt0; kt < kt1; ++kt) {
+            const int cur = (kt - kt0) & 1;
+            if (kt + 1 < kt1) {
+                la.template fetch<0>((kt + 1) * BK, cp);
+                lb.template fetch<0>((kt + 1) * BK, cp);
+            }
+            compute(cur);
+            if (kt + 1 < kt1) {
+                la.template commit<0>(lds_a[cur ^ 1]);
+                lb.template commit<0>(lds_b[cur ^ 1]);
+            }
+            __syncthreads();
+        }
+    } else {
+        // Two K steps deep: step t is computed from LDS buffer t&1 while the global loads of
+        // steps t+1 (staging set (t+1)&1) and t+2 (issued at the start of step t into the set
+        // that step t's data just left) are in flight.  With at most two steps everything is
+        // requested up front and the workgroup pays one memory round trip.
+        constexpr int S1 = PF - 1;      // second staging set (only instantiated when PF == 2)
+        if (kt0 < kt1) {
+            la.template fetch<0>(kt0 * BK, cp);
+            lb.template fetch<0>(kt0 * BK, cp);
+        }
+        if (kt0 + 1 < kt1) {
+            la.template fetch<S1>((kt0 + 1) * BK, cp);
+            lb.template fetch<S1>((kt0 + 1) * BK, cp);
+        }
+        if (kt0 < kt1) {
+            la.template commit<0>(lds_a[0]);
+            lb.template commit<0>(lds_b[0]);
+        }
+        __syncthreads();
+        for (int kt = kt0; kt < kt1; kt += 2) {
+            if (kt + 2 < kt1) {
+                la.template fetch<0>((kt + 2) * BK, cp);
+                lb.template fetch<0>((kt + 2) * BK, cp);
+            }
+            compute(0);
+            if (kt + 1 < kt1) {
+                la.template commit<S1>(lds_a[1]);
+                lb.template commit<S1>(lds_b[1]);
+            }
+            __syncthreads();
+            if (kt + 1 >= kt1) break;
+            if (kt + 3 < kt1) {
+                la.template fetch<S1>((kt + 3) * BK, cp);
+                lb.template fetch<S1>((kt + 3) * BK, cp);
+            }
+            compute(1);
+            if (kt + 2 < kt1) {
+                la.template commit<0>(lds_a[0]);
+                lb.template commit<0>(lds_b[0]);
+            }
+            __syncthreads();
+        }
     }
 
     finish_tile<TM, TN, WTM, WTN, NT>(acc, m0, n0, zslice, split, wm, wn, li, h, cp);
