@@ -6,9 +6,9 @@
 // never-materialised matrix of input patches [Cg*kH*kW x N*OH*OW]).
 //
 // Work decomposition: a workgroup of WM x WN wavefronts owns a BM x BN tile of Y and walks K
-// in steps of BK.  Each step stages an A tile and a B tile in LDS (double buffered; global
-// loads run one or two steps ahead of the MFMAs through register staging sets and are
-// written to the other buffer after the current step's MFMAs, one barrier per step).  Each wavefront owns a (BM/WM) x (BN/WN) sub-tile as
+// in steps of BK.  Each step stages an A tile and a B tile in LDS (double buffered: global
+// loads for step t+1 are issued before the MFMAs of step t and written to the other buffer
+// after them, one barrier per step).  Each wavefront owns a (BM/WM) x (BN/WN) sub-tile as
 // a grid of 32x32 accumulators fed by v_mfma_f32_32x32x2_f32.
 //
 // Operand kinds (how a tile is fetched and how it sits in LDS):
@@ -129,7 +129,7 @@ __device__ inline __amdgpu_buffer_rsrc_t tile_rsrc(const float* p) {
 
 // ------------------------------------------------------------------------------------------
 // Tile loader: global -> registers -> LDS for a ROWS x BK tile, NT threads.
-template <int KIND, int VEC, int ROWS, int BK, int NT, int SETS>
+template <int KIND, int VEC, int ROWS, int BK, int NT>
 struct TileLoader {
     static constexpr bool kc = (KIND == LOAD_KC);
     static constexpr int FAST = kc ? (BK / VEC) : (ROWS / VEC);   // threads along the contiguous axis
@@ -142,7 +142,7 @@ struct TileLoader {
     static_assert(NT % FAST == 0, "threads must tile the contiguous axis");
     static_assert(SLOW % SLOW_PER_PASS == 0 || SLOW < SLOW_PER_PASS, "tile/loader mismatch");
 
-    float reg[SETS][NLOAD * VEC];   // staging sets: loads run SETS K steps ahead of the MFMAs
+    float reg[NLOAD * VEC];      // staging registers: the next K step's tile on its way to LDS
     int fast, slow0;
     bool active;                 // false when SLOW < SLOW_PER_PASS leaves the thread idle
     const float* base;           // first element of the tile (RC: at k = 0)
@@ -201,30 +201,28 @@ struct TileLoader {
         rsrc = tile_rsrc(base);
     }
 
-    template <int SET>
     __device__ inline void load(__amdgpu_buffer_rsrc_t r, uint32_t off, int soff, int p) {
         if (VEC == 4) {
             const floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, soff, 0));
-            reg[SET][p * 4 + 0] = v.x; reg[SET][p * 4 + 1] = v.y; reg[SET][p * 4 + 2] = v.z; reg[SET][p * 4 + 3] = v.w;
+            reg[p * 4 + 0] = v.x; reg[p * 4 + 1] = v.y; reg[p * 4 + 2] = v.z; reg[p * 4 + 3] = v.w;
         } else {
-            reg[SET][p] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, soff, 0));
+            reg[p] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, soff, 0));
         }
     }
 
-    // Issue the global loads of the tile whose first k is k0 into staging set SET.
-    template <int SET>
+    // Issue the global loads of the tile whose first k is k0.
     __device__ inline void fetch(int k0, const ContractionParams& cp) {
         if constexpr (kc) {
             const bool k_ok = k0 + fast * VEC < K;
 #pragma unroll
-            for (int p = 0; p < NLOAD; ++p) load<SET>(rsrc, k_ok ? voff[p] : OOB, k0 * 4, p);
+            for (int p = 0; p < NLOAD; ++p) load(rsrc, k_ok ? voff[p] : OOB, k0 * 4, p);
         } else if constexpr (KIND == LOAD_RC) {
             // the resource is re-based at row k0 so that offsets stay small whatever K is
             const __amdgpu_buffer_rsrc_t r = tile_rsrc(base + (int64_t)k0 * ld);
 #pragma unroll
             for (int p = 0; p < NLOAD; ++p) {
                 const bool good = col_ok && (k0 + slow0 + p * SLOW_PER_PASS < K);
-                load<SET>(r, good ? voff[0] : OOB, p * SLOW_PER_PASS * ld * 4, p);
+                load(r, good ? voff[0] : OOB, p * SLOW_PER_PASS * ld * 4, p);
             }
         } else {
             // k -> (c, kh, kw) is the same for every column, so the BK decompositions of this
@@ -246,13 +244,12 @@ struct TileLoader {
                 const int ih = ih0 + (dhw >> 16), iw = iw0 + (dhw & 0xffff);
                 const bool good = col_ok && koff >= 0 && (unsigned)ih < (unsigned)cp.ic.H &&
                                   (unsigned)iw < (unsigned)cp.ic.W;
-                load<SET>(rsrc, good ? (voff[0] + (uint32_t)koff) * 4u : OOB, 0, p);
+                load(rsrc, good ? (voff[0] + (uint32_t)koff) * 4u : OOB, 0, p);
             }
         }
     }
 
-    // Write staging set SET into an LDS buffer.
-    template <int SET>
+    // Write the fetched tile into an LDS buffer.
     __device__ inline void commit(float* lds) const {
         if (!active) return;
 #pragma unroll
@@ -260,10 +257,10 @@ struct TileLoader {
             const int slow = slow0 + p * SLOW_PER_PASS;
             float* dst = kc ? lds + slow * LDK + fast * VEC : lds + slow * LDR + fast * VEC;
             if (VEC == 4) {
-                floatx4 v = {reg[SET][p * 4 + 0], reg[SET][p * 4 + 1], reg[SET][p * 4 + 2], reg[SET][p * 4 + 3]};
+                floatx4 v = {reg[p * 4 + 0], reg[p * 4 + 1], reg[p * 4 + 2], reg[p * 4 + 3]};
                 *reinterpret_cast<floatx4*>(dst) = v;
             } else {
-                *dst = reg[SET][p];
+                *dst = reg[p];
             }
         }
     }
@@ -516,17 +513,16 @@ inline hipError_t launch_with_split(Kernel kernel, ContractionParams& p, int nz,
     return e;
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int AKIND, int BKIND, int VEC, int PF>
-__global__ __launch_bounds__(64 * WM * WN, 4) void contraction_kernel(const ContractionParams cp) {
+template <int BM, int BN, int BK, int WM, int WN, int AKIND, int BKIND, int VEC>
+__global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const ContractionParams cp) {
     constexpr int NT = 64 * WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN;     // wavefront sub-tile
     constexpr int TM = WTM / 32, TN = WTN / 32;     // 32x32 accumulators per wavefront
     static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "sub-tile of 32x32 blocks");
     static_assert(BK % 8 == 0, "K step is a multiple of the 8-wide half-step");
     constexpr int BVEC = (BKIND == LOAD_IM2COL) ? 1 : VEC;
-    static_assert(PF == 1 || PF == 2, "prefetch depth");
-    using ALoader = TileLoader<AKIND, VEC, BM, BK, NT, PF>;
-    using BLoader = TileLoader<BKIND, BVEC, BN, BK, NT, PF>;
+    using ALoader = TileLoader<AKIND, VEC, BM, BK, NT>;
+    using BLoader = TileLoader<BKIND, BVEC, BN, BK, NT>;
 
     __shared__ __attribute__((aligned(16))) float lds_a[2][ALoader::LDS_FLOATS];
     __shared__ __attribute__((aligned(16))) float lds_b[2][BLoader::LDS_FLOATS];
@@ -586,71 +582,28 @@ __global__ __launch_bounds__(64 * WM * WN, 4) void contraction_kernel(const Cont
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[g][i][s], fb[g][j][s], acc[i][j], 0, 0, 0);
     };
 
-    if constexpr (PF == 1) {
-        // Software pipeline, one K step deep: the loads of step t+1 are issued before the
-        // MFMAs of step t and written to the other LDS buffer after them.
-        if (kt0 < kt1) {
-            la.template fetch<0>(kt0 * BK, cp);
-            lb.template fetch<0>(kt0 * BK, cp);
-            la.template commit<0>(lds_a[0]);
-            lb.template commit<0>(lds_b[0]);
+    // Software pipeline: the loads of step t+1 are issued before the MFMAs of step t and written
+    // to the other LDS buffer after them.  (Issuing them two steps ahead through a second set
+    // of staging registers was measured and gained nothing.)
+    if (kt0 < kt1) {
+        la.fetch(kt0 * BK, cp);
+        lb.fetch(kt0 * BK, cp);
+        la.commit(lds_a[0]);
+        lb.commit(lds_b[0]);
+    }
+    __syncthreads();
+    for (int kt = kt0; kt < kt1; ++kt) {
+        const int cur = (kt - kt0) & 1;
+        if (kt + 1 < kt1) {
+            la.fetch((kt + 1) * BK, cp);
+            lb.fetch((kt + 1) * BK, cp);
+        }
+        compute(cur);
+        if (kt + 1 < kt1) {
+            la.commit(lds_a[cur ^ 1]);
+            lb.commit(lds_b[cur ^ 1]);
         }
         __syncthreads();
-        for (int kt = kt0; kt < kt1; ++kt) {
-            const int cur = (kt - kt0) & 1;
-            if (kt + 1 < kt1) {
-                la.template fetch<0>((kt + 1) * BK, cp);
-                lb.template fetch<0>((kt + 1) * BK, cp);
-            }
-            compute(cur);
-            if (kt + 1 < kt1) {
-                la.template commit<0>(lds_a[cur ^ 1]);
-                lb.template commit<0>(lds_b[cur ^ 1]);
-            }
-            __syncthreads();
-        }
-    } else {
-        // Two K steps deep: step t is computed from LDS buffer t&1 while the global loads of
-        // steps t+1 (staging set (t+1)&1) and t+2 (issued at the start of step t into the set
-        // that step t's data just left) are in flight.  With at most two steps everything is
-        // requested up front and the workgroup pays one memory round trip.
-        constexpr int S1 = PF - 1;      // second staging set (only instantiated when PF == 2)
-        if (kt0 < kt1) {
-            la.template fetch<0>(kt0 * BK, cp);
-            lb.template fetch<0>(kt0 * BK, cp);
-        }
-        if (kt0 + 1 < kt1) {
-            la.template fetch<S1>((kt0 + 1) * BK, cp);
-            lb.template fetch<S1>((kt0 + 1) * BK, cp);
-        }
-        if (kt0 < kt1) {
-            la.template commit<0>(lds_a[0]);
-            lb.template commit<0>(lds_b[0]);
-        }
-        __syncthreads();
-        for (int kt = kt0; kt < kt1; kt += 2) {
-            if (kt + 2 < kt1) {
-                la.template fetch<0>((kt + 2) * BK, cp);
-                lb.template fetch<0>((kt + 2) * BK, cp);
-            }
-            compute(0);
-            if (kt + 1 < kt1) {
-                la.template commit<S1>(lds_a[1]);
-                lb.template commit<S1>(lds_b[1]);
-            }
-            __syncthreads();
-            if (kt + 1 >= kt1) break;
-            if (kt + 3 < kt1) {
-                la.template fetch<S1>((kt + 3) * BK, cp);
-                lb.template fetch<S1>((kt + 3) * BK, cp);
-            }
-            compute(1);
-            if (kt + 2 < kt1) {
-                la.template commit<0>(lds_a[0]);
-                lb.template commit<0>(lds_b[0]);
-            }
-            __syncthreads();
-        }
     }
 
     finish_tile<TM, TN, WTM, WTN, NT>(acc, m0, n0, zslice, split, wm, wn, li, h, cp);

@@ -3,22 +3,26 @@
 
 namespace onnxhip {
 
-template <int BM, int BN, int BK, int WM, int WN, int PF, int AK, int BKIND, int VEC>
+template <int BM, int BN, int BK, int WM, int WN, int AK, int BKIND, int VEC>
 static hipError_t launch_one(ContractionParams& p, int nz, hipStream_t stream) {
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     p.nz = nz;
     p.ksplit = pick_split((int64_t)p.tiles_m * p.tiles_n * nz, (p.K + BK - 1) / BK, (int64_t)BM * BN, 6.0);
     p.ws_partial = workspace().partial;
-    return launch_with_split<BM, BN, WM, WN>(contraction_kernel<BM, BN, BK, WM, WN, AK, BKIND, VEC, PF>, p, nz, stream);
+    return launch_with_split<BM, BN, WM, WN>(contraction_kernel<BM, BN, BK, WM, WN, AK, BKIND, VEC>, p, nz, stream);
 }
 
 template <int AK, int BKIND, int VEC>
 static hipError_t launch_tile(ContractionParams& p, int tile, int nz, hipStream_t stream) {
     switch (tile) {
-        case TILE_64: return launch_one<64, 64, 32, 2, 2, 2, AK, BKIND, VEC>(p, nz, stream);
-        case TILE_128: return launch_one<128, 128, 16, 4, 2, 2, AK, BKIND, VEC>(p, nz, stream);
-        case TILE_256: return launch_one<256, 256, 16, 4, 4, 1, AK, BKIND, VEC>(p, nz, stream);
+        case TILE_64:
+            // short K: the 16-wide step leaves room for 8 workgroups per CU, which hides the
+            // per-tile prologue and epilogue better; long K: fewer, longer steps
+            if (p.K < 1024) return launch_one<64, 64, 16, 2, 2, AK, BKIND, VEC>(p, nz, stream);
+            return launch_one<64, 64, 32, 2, 2, AK, BKIND, VEC>(p, nz, stream);
+        case TILE_128: return launch_one<128, 128, 16, 4, 2, AK, BKIND, VEC>(p, nz, stream);
+        case TILE_256: return launch_one<256, 256, 16, 4, 4, AK, BKIND, VEC>(p, nz, stream);
         default: return hipErrorInvalidValue;
     }
 }

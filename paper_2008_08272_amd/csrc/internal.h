@@ -8,7 +8,7 @@
 namespace onnxhip {
 
 // Workgroup tiles of the contraction kernel (rows x columns x K step, wavefront grid):
-//   TILE_64   64 x  64 x 32, 2x2 wavefronts  -- small problems, up to 8 workgroups per CU
+//   TILE_64   64 x  64 x 16 (K < 1024) or x 32, 2x2 wavefronts  -- small problems
 //   TILE_128 128 x 128 x 16, 4x2 wavefronts  -- the general case
 //   TILE_256 256 x 256 x 16, 4x4 wavefronts  -- large products, one workgroup per CU
 enum TileShape { TILE_64 = 0, TILE_128 = 1, TILE_256 = 2, TILE_COUNT };

@@ -1,8 +1,9 @@
 // Sliding-window kernels that do not use the matrix cores: direct convolution for depthwise /
 // tiny groups, MaxPool, AveragePool and GlobalAveragePool (Section 4.1 of the paper lists
 // convolution and pooling among the supported operators).  All are bandwidth- or
-// latency-bound: one thread per output element, lanes running along the contiguous output
-// width so that loads and stores of a wavefront fall into few cache lines.
+// latency-bound.  The generic kernels use one thread per output element, lanes running along
+// the contiguous output width; 3x3 convolutions and 2x2 / 3x3 max pools go through the
+// plane-tile kernels further down, which stage the input in LDS.
 #include "internal.h"
 
 namespace onnxhip {
@@ -141,6 +142,176 @@ __global__ __launch_bounds__(256) void global_avgpool_kernel(const float* __rest
     if (lane == 0) Y[plane] = acc / (float)HW;
 }
 
+// ---- plane-tile variants ------------------------------------------------------------------
+// A workgroup owns a strip of output rows of one (image, channel) plane.  It copies the input
+// rows the strip needs into LDS with fully coalesced loads (every input element is read from
+// memory once, padding is materialised in LDS: 0 for convolution, -inf for MaxPool), then each
+// thread produces outputs from LDS, lanes along the output width.  The filter taps of a
+// convolution are uniform for the workgroup and come from scalar loads.
+constexpr int PLANE_LDS_FLOATS = 6144;          // 24 KiB
+constexpr uint32_t kOutOfRange = 0x80000000u;
+
+struct PlaneTiling {
+    int toh, row_tiles;       // output rows per strip, strips per plane
+    int rows_in, lw;          // input rows per strip, LDS row length = W + pL + pR
+    FastDiv lwd, owd, rtd;    // divisors: lw, OW, row_tiles
+};
+
+// Copies input rows [ih_first, ih_first + rows_in) x columns [-pL, W + pR) of one plane into LDS.
+__device__ inline void plane_fill(float* lds, const float* plane, const WindowGeom& g, const PlaneTiling& t,
+                                  int ih_first, float pad) {
+    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(plane), 0,
+                                                                       g.H * g.W * 4, 0x00020000);
+    const int total = t.rows_in * t.lw;
+    for (int e = threadIdx.x; e < total; e += 256) {
+        uint32_t row, x;
+        t.lwd.divmod((uint32_t)e, row, x);
+        const int ih = ih_first + (int)row, iw = (int)x - g.pL;
+        const bool ok = (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
+        const float v = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                            r, ok ? (ih * g.W + iw) * 4 : (int)kOutOfRange, 0, 0));
+        lds[e] = ok ? v : pad;
+    }
+}
+
+template <int KH, int KW>
+__global__ __launch_bounds__(256) void conv_plane_kernel(const float* __restrict__ X,
+                                                         const float* __restrict__ Wt,
+                                                         const float* __restrict__ B,
+                                                         const float* __restrict__ residual,
+                                                         float* __restrict__ Y, WindowGeom g, int M, int Cg,
+                                                         int Mg, int relu, PlaneTiling t) {
+    __shared__ float lds[PLANE_LDS_FLOATS];
+    uint32_t pm, rt;
+    t.rtd.divmod(blockIdx.x, pm, rt);                  // pm = n*M + m
+    const int n = (int)pm / M, m = (int)pm % M;
+    const int grp = m / Mg;
+    const int oh0 = (int)rt * t.toh;
+    const int nrows = min(t.toh, g.OH - oh0);
+    const int ih_first = oh0 * g.sH - g.pT;
+    const int nout = nrows * g.OW;
+    constexpr int MAXO = 12;                           // outputs per thread held in registers
+    float acc[MAXO];
+#pragma unroll
+    for (int i = 0; i < MAXO; ++i) acc[i] = 0.f;
+    const float* wm = Wt + (int64_t)m * Cg * KH * KW;
+    for (int c = 0; c < Cg; ++c) {
+        const float* plane = X + ((int64_t)n * g.C + grp * Cg + c) * g.H * g.W;
+        if (c) __syncthreads();
+        plane_fill(lds, plane, g, t, ih_first, 0.f);
+        float w[KH * KW];                              // uniform: scalar loads
+#pragma unroll
+        for (int i = 0; i < KH * KW; ++i) w[i] = wm[c * KH * KW + i];
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < MAXO; ++i) {
+            const int idx = threadIdx.x + i * 256;
+            if (idx < nout) {
+                uint32_t r, ow;
+                t.owd.divmod((uint32_t)idx, r, ow);
+                const float* p = lds + ((int)r * g.sH) * t.lw + (int)ow * g.sW;
+                float a = acc[i];
+#pragma unroll
+                for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+                    for (int kw = 0; kw < KW; ++kw) a = fmaf(p[kh * g.dH * t.lw + kw * g.dW], w[kh * KW + kw], a);
+                acc[i] = a;
+            }
+        }
+    }
+    const float bias = B ? B[m] : 0.f;
+    const int64_t o0 = ((int64_t)pm * g.OH + oh0) * g.OW;
+#pragma unroll
+    for (int i = 0; i < MAXO; ++i) {
+        const int idx = threadIdx.x + i * 256;
+        if (idx < nout) {
+            float v = acc[i] + bias;
+            if (residual) v += residual[o0 + idx];
+            if (relu) v = v > 0.f ? v : 0.f;
+            Y[o0 + idx] = v;
+        }
+    }
+}
+
+template <int KH, int KW, bool IDX>
+__global__ __launch_bounds__(256) void maxpool_plane_kernel(const float* __restrict__ X, float* __restrict__ Y,
+                                                            int64_t* __restrict__ indices, WindowGeom g,
+                                                            PlaneTiling t) {
+    __shared__ float lds[PLANE_LDS_FLOATS];
+    uint32_t pc, rt;
+    t.rtd.divmod(blockIdx.x, pc, rt);                  // pc = n*C + c
+    const int oh0 = (int)rt * t.toh;
+    const int nrows = min(t.toh, g.OH - oh0);
+    const int ih_first = oh0 * g.sH - g.pT;
+    const int64_t plane_abs = (int64_t)pc * g.H * g.W;
+    plane_fill(lds, X + plane_abs, g, t, ih_first, -__builtin_inff());
+    __syncthreads();
+    const int nout = nrows * g.OW;
+    const int64_t o0 = ((int64_t)pc * g.OH + oh0) * g.OW;
+    for (int idx = threadIdx.x; idx < nout; idx += 256) {
+        uint32_t r, ow;
+        t.owd.divmod((uint32_t)idx, r, ow);
+        const int lr = (int)r * g.sH, lc = (int)ow * g.sW;        // window origin in LDS coordinates
+        const float* p = lds + lr * t.lw + lc;
+        // Padding holds -inf and can never replace the running maximum; the scan starts from
+        // the first tap inside the image so that an all -inf window still reports that tap.
+        // Taps are visited kh outer, kw inner and replace on strict >, i.e. first maximum wins.
+        float best = -__builtin_inff();
+        int bh = 0, bw = 0;
+        if (IDX) {
+            const int ih0 = ih_first + lr, iw0 = lc - g.pL;
+            bh = ih0 < 0 ? (-ih0 + g.dH - 1) / g.dH : 0;
+            bw = iw0 < 0 ? (-iw0 + g.dW - 1) / g.dW : 0;
+        }
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+            for (int kw = 0; kw < KW; ++kw) {
+                const float v = p[kh * g.dH * t.lw + kw * g.dW];
+                if (IDX) {
+                    const bool take = v > best;
+                    bh = take ? kh : bh;
+                    bw = take ? kw : bw;
+                }
+                best = fmaxf(best, v);
+            }
+        Y[o0 + idx] = best;
+        if (IDX) {
+            const int ih = ih_first + lr + bh * g.dH, iw = lc - g.pL + bw * g.dW;
+            indices[o0 + idx] = plane_abs + (int64_t)ih * g.W + iw;
+        }
+    }
+}
+
+// Strip height such that the input rows of a strip fit the LDS tile; false if not even one
+// output row fits or the strip would exceed what a thread holds in registers.
+static inline bool plane_tiling(const WindowGeom& g, int64_t planes, int max_out_per_thread, PlaneTiling& t) {
+    const int64_t lw = (int64_t)g.W + g.pL + g.pR;
+    const int64_t eh = (int64_t)(g.kH - 1) * g.dH + 1, ew = (int64_t)(g.kW - 1) * g.dW + 1;
+    if (lw * eh > PLANE_LDS_FLOATS || g.OW < 1 || g.OH < 1) return false;
+    if ((int64_t)(g.OW - 1) * g.sW + ew > lw) return false;        // windows stay inside the padded row
+    if ((int64_t)g.H * g.W * 4 >= (1LL << 31)) return false;
+    int64_t toh = (PLANE_LDS_FLOATS / lw - eh) / g.sH + 1;
+    if (toh > g.OH) toh = g.OH;
+    if (max_out_per_thread > 0) {
+        const int64_t by_regs = (int64_t)max_out_per_thread * 256 / g.OW;
+        if (by_regs < 1) return false;
+        if (toh > by_regs) toh = by_regs;
+    }
+    // enough strips to occupy the chip when there are few planes
+    while (toh > 1 && planes * ((g.OH + toh - 1) / toh) < 2048) toh = (toh + 1) / 2;
+    t.toh = (int)toh;
+    t.row_tiles = (int)((g.OH + toh - 1) / toh);
+    t.rows_in = (int)((toh - 1) * g.sH + eh);
+    t.lw = (int)lw;
+    if ((int64_t)t.rows_in * lw > PLANE_LDS_FLOATS) return false;
+    if (planes * t.row_tiles > 0x7fffffffLL) return false;
+    t.lwd = FastDiv::make((uint32_t)lw);
+    t.owd = FastDiv::make((uint32_t)g.OW);
+    t.rtd = FastDiv::make((uint32_t)t.row_tiles);
+    return true;
+}
+
 static inline void chunking(int N, uint64_t per_image, int& images_per_chunk, unsigned& chunks,
                             unsigned& blocks) {
     const uint64_t limit = 1ull << 30;
@@ -166,6 +337,14 @@ hipError_t launch_conv_direct(const float* X, const float* W, const float* B, co
     const uint64_t per_image = (uint64_t)M * g.OH * g.OW;
     if (per_image >= (1ull << 30)) return hipErrorInvalidValue;
     int ipc; unsigned chunks, blocks;
+    if (g.kH == 3 && g.kW == 3) {
+        PlaneTiling t;
+        if (plane_tiling(g, (int64_t)g.N * M, 12, t)) {
+            hipLaunchKernelGGL((conv_plane_kernel<3, 3>), dim3((unsigned)((int64_t)g.N * M * t.row_tiles)), dim3(256), 0,
+                               stream, X, W, B, residual, Y, g, M, Cg, M / group, relu, t);
+            return hipGetLastError();
+        }
+    }
     chunking(g.N, per_image, ipc, chunks, blocks);
     hipLaunchKernelGGL(conv_direct_kernel, dim3(blocks, chunks), dim3(256), 0, stream, X, W, B, residual,
                        Y, g, M, Cg, M / group, relu, out_index(g.OW, g.OH, M), (uint32_t)per_image, ipc);
@@ -177,6 +356,17 @@ hipError_t launch_maxpool(const float* X, float* Y, int64_t* indices, const Wind
     const uint64_t per_image = (uint64_t)g.C * g.OH * g.OW;
     if (per_image >= (1ull << 30)) return hipErrorInvalidValue;
     int ipc; unsigned chunks, blocks;
+    const int shape = g.kH != g.kW ? 0 : g.kH == 3 ? 3 : g.kH == 2 ? 2 : 0;
+    PlaneTiling t;
+    if (shape && plane_tiling(g, (int64_t)g.N * g.C, 0, t)) {
+        const dim3 grid((unsigned)((int64_t)g.N * g.C * t.row_tiles)), block(256);
+#define ONNXHIP_POOL(K_)                                                                                          \
+    if (indices) hipLaunchKernelGGL((maxpool_plane_kernel<K_, K_, true>), grid, block, 0, stream, X, Y, indices, g, t); \
+    else hipLaunchKernelGGL((maxpool_plane_kernel<K_, K_, false>), grid, block, 0, stream, X, Y, indices, g, t);
+        if (shape == 3) { ONNXHIP_POOL(3) } else { ONNXHIP_POOL(2) }
+#undef ONNXHIP_POOL
+        return hipGetLastError();
+    }
     chunking(g.N, per_image, ipc, chunks, blocks);
     hipLaunchKernelGGL(maxpool_kernel, dim3(blocks, chunks), dim3(256), 0, stream, X, Y, indices, g,
                        out_index(g.OW, g.OH, g.C), (uint32_t)per_image, ipc);
