@@ -20,13 +20,25 @@
 // channel 2c', lanes 32-63 channel 2c'+1, both at the same tap; A (filters, [row][4*KH*KW+1]
 // in LDS) and B (patch, [channel][patch row][patch col]) use the same dealing.
 #pragma once
+#include <type_traits>
+
 #include "contraction.h"
 
 namespace onnxhip {
 
 constexpr int WIN_CB = 4;      // input channels per K step
 
-template <int BM, int BN, int WM, int WN, int KH, int KW, int MAXPB>
+// NPB = passes of NT threads that cover one step's patch (4 channels x plane values); the
+// launcher picks the smallest instance that fits, so the main loop has no data-dependent
+// branch: every load and LDS store below is unconditional (surplus ones are out-of-range
+// buffer loads, which fetch nothing and return zero).
+//
+// Schedule of one K step (LDS buffer s holds step ks, register set s^1 holds step ks+1, whose
+// loads were issued a whole step ago):
+//   issue global loads of step ks+2 into register set s
+//   read the fragments of channel pair 0; then read pair 1's fragments in between pair 0's MFMAs
+//   store register set s^1 into LDS buffer s^1 in between pair 1's MFMAs; barrier
+template <int BM, int BN, int WM, int WN, int KH, int KW, int NPB>
 __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const ContractionParams cp) {
     constexpr int NT = 64 * WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN;
@@ -36,10 +48,12 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
     constexpr int LDA = KA + 1;                 // odd row stride: conflict-free column reads
     constexpr int NA4 = BM * KA / 4;            // 16-byte loads per A tile
     constexpr int PA = (NA4 + NT - 1) / NT;
+    constexpr int NMFMA = KHW * TM * TN;        // MFMAs per channel pair
+    constexpr int NFRAG = KHW * (TM + TN);      // LDS reads per channel pair
     static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "sub-tile of 32x32 blocks");
 
-    __shared__ float lds_a[2][BM * LDA];
-    __shared__ float lds_b[2][MAXPB * NT];
+    __shared__ float lds_a[2][BM * LDA + 4];    // + a slot that absorbs the stores of surplus threads
+    __shared__ float lds_b[2][NPB * NT];
 
     int zslice, split;
     slice_and_split(cp, zslice, split);
@@ -72,15 +86,15 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
         const int row = e / KHW, q = e % KHW;        // KA/4 == KHW chunks per row
         const bool ok = e < NA4 && m0 + row < cp.M;
         voff_a[p] = ok ? (uint32_t)(row * cp.K + q * 4) * 4u : OOB;
-        dst_a[p] = (e < NA4 ? row : 0) * LDA + q * 4;
+        dst_a[p] = e < NA4 ? row * LDA + q * 4 : BM * LDA;
     }
     // ---- patch loader: thread -> (channel, patch row, patch col), fixed for the whole K walk
     const float* b_base = cp.B + b_off + (int64_t)img_first * g.image_stride;
     const __amdgpu_buffer_rsrc_t rb = tile_rsrc(b_base);
     const int HW = g.H * g.W;
-    uint32_t voff_b[MAXPB];
+    uint32_t voff_b[NPB];
 #pragma unroll
-    for (int p = 0; p < MAXPB; ++p) {
+    for (int p = 0; p < NPB; ++p) {
         const uint32_t e = (uint32_t)(t + p * NT);
         uint32_t c, rem, pr, pc;
         g.planed.divmod(e, c, rem);
@@ -125,65 +139,82 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    floatx4 reg_a[PA];
-    float reg_b[MAXPB];
-    const int npb = (WIN_CB * g.plane + NT - 1) / NT;    // patch passes in use (uniform, <= MAXPB)
-
-    auto fetch = [&](int ks) {
-#pragma unroll
-        for (int p = 0; p < PA; ++p)
-            reg_a[p] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(ra, (int)voff_a[p], ks * KA * 4, 0));
-#pragma unroll
-        for (int p = 0; p < MAXPB; ++p)
-            if (p < npb)
-                reg_b[p] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, (int)voff_b[p], ks * WIN_CB * HW * 4, 0));
-    };
-    auto commit = [&](int buf) {
-#pragma unroll
-        for (int p = 0; p < PA; ++p) {
-            if (t + p * NT < NA4) {
-                float* d = lds_a[buf] + dst_a[p];
-                d[0] = reg_a[p].x; d[1] = reg_a[p].y; d[2] = reg_a[p].z; d[3] = reg_a[p].w;
-            }
-        }
-#pragma unroll
-        for (int p = 0; p < MAXPB; ++p)
-            if (p < npb) lds_b[buf][t + p * NT] = reg_b[p];
-    };
-
     int ks0, ks1;
     split_range(g.Cg / WIN_CB, cp.ksplit, split, ks0, ks1);
-    if (ks0 < ks1) {
-        fetch(ks0);
-        commit(0);
-    }
-    __syncthreads();
-    for (int ks = ks0; ks < ks1; ++ks) {
-        const int cur = (ks - ks0) & 1;
-        if (ks + 1 < ks1) fetch(ks + 1);
-        const float* sa = lds_a[cur];
-        const float* sb = lds_b[cur];
+
+    floatx4 reg_a[2][PA];
+    float reg_b[2][NPB];
+    using Set0 = std::integral_constant<int, 0>;
+    using Set1 = std::integral_constant<int, 1>;
+
+    // Loads of step ks into register set S; a step past the end of the walk loads nothing.
+    auto fetch = [&](int ks, auto S) {
+        constexpr int s = decltype(S)::value;
+        const uint32_t past = ks < ks1 ? 0u : OOB;
 #pragma unroll
-        for (int cc = 0; cc < WIN_CB / 2; ++cc) {
-            float fa[KHW][TM], fb[KHW][TN];
+        for (int p = 0; p < PA; ++p)
+            reg_a[s][p] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(ra, (int)(voff_a[p] | past), ks * KA * 4, 0));
 #pragma unroll
-            for (int tap = 0; tap < KHW; ++tap) {
+        for (int p = 0; p < NPB; ++p)
+            reg_b[s][p] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, (int)(voff_b[p] | past), ks * WIN_CB * HW * 4, 0));
+    };
+    auto commit = [&](int buf, auto S) {
+        constexpr int s = decltype(S)::value;
 #pragma unroll
-                for (int i = 0; i < TM; ++i) fa[tap][i] = sa[rd_a[i] + 2 * cc * KHW + tap];
-#pragma unroll
-                for (int j = 0; j < TN; ++j) fb[tap][j] = sb[rd_b[j] + 2 * cc * g.plane + tap_b[tap]];
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int tap = 0; tap < KHW; ++tap)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[tap][i], fb[tap][j], acc[i][j], 0, 0, 0);
+        for (int p = 0; p < PA; ++p) {
+            float* d = lds_a[buf] + dst_a[p];
+            d[0] = reg_a[s][p].x; d[1] = reg_a[s][p].y; d[2] = reg_a[s][p].z; d[3] = reg_a[s][p].w;
         }
-        if (ks + 1 < ks1) commit(cur ^ 1);
+#pragma unroll
+        for (int p = 0; p < NPB; ++p) lds_b[buf][t + p * NT] = reg_b[s][p];
+    };
+    float fa[2][KHW][TM], fb[2][KHW][TN];
+    auto frags = [&](int f, const float* sa, const float* sb, int cc) {
+#pragma unroll
+        for (int tap = 0; tap < KHW; ++tap) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[f][tap][i] = sa[rd_a[i] + 2 * cc * KHW + tap];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[f][tap][j] = sb[rd_b[j] + 2 * cc * g.plane + tap_b[tap]];
+        }
+    };
+    auto mfmas = [&](int f) {
+#pragma unroll
+        for (int tap = 0; tap < KHW; ++tap)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[f][tap][i], fb[f][tap][j], acc[i][j], 0, 0, 0);
+    };
+    auto step = [&](int ks, auto S, auto SN) {
+        constexpr int s = decltype(S)::value;
+        fetch(ks + 2, S);
+        const float* sa = lds_a[s];
+        const float* sb = lds_b[s];
+        static_assert(WIN_CB == 4, "two channel pairs per step");
+        frags(0, sa, sb, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        frags(1, sa, sb, 1);
+        mfmas(0);
+#pragma unroll
+        for (int q = 0; q < NMFMA; ++q) {            // one MFMA, then its share of pair 1's LDS reads
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, (NFRAG + NMFMA - 1) / NMFMA, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        commit(s ^ 1, SN);                           // past the end this stores zeros nobody reads
+        mfmas(1);
         __syncthreads();
+    };
+
+    fetch(ks0, Set0{});
+    fetch(ks0 + 1, Set1{});
+    commit(0, Set0{});
+    __syncthreads();
+    for (int ks = ks0; ks < ks1; ks += 2) {
+        step(ks, Set0{}, Set1{});
+        if (ks + 1 < ks1) step(ks + 1, Set1{}, Set0{});
     }
     finish_tile<TM, TN, WTM, WTN, NT>(acc, m0, n0, zslice, split, wm, wn, li, h, cp);
 }

@@ -13,8 +13,7 @@ struct WindowConfig {
 // Keep in step with the template instances in launch_config below.
 const WindowConfig kConfigs[] = {
     {64, 64, 256, 8, 0.75},
-    {64, 128, 256, 12, 0.80},
-    {128, 128, 512, 8, 0.85},
+    {128, 128, 512, 8, 0.80},
 };
 const int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 
@@ -27,22 +26,33 @@ int patch_rows(int bn, int OH, int OW, int sH, int E) {
     return (nr - nimg) * sH + nimg * per_image;
 }
 
-template <int BM, int BN, int WM, int WN, int KH, int KW, int MAXPB>
+template <int BM, int BN, int WM, int WN, int KH, int KW, int NPB>
 hipError_t launch_instance(ContractionParams& p, int nz, hipStream_t stream) {
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     p.nz = nz;
     p.ksplit = pick_split((int64_t)p.tiles_m * p.tiles_n * nz, p.ic.Cg / WIN_CB, (int64_t)BM * BN, 4.0);
     p.ws_partial = workspace().partial;
-    return launch_with_split<BM, BN, WM, WN>(conv_window_kernel<BM, BN, WM, WN, KH, KW, MAXPB>, p, nz, stream);
+    return launch_with_split<BM, BN, WM, WN>(conv_window_kernel<BM, BN, WM, WN, KH, KW, NPB>, p, nz, stream);
+}
+
+// npb = passes the patch needs; the instance with the next larger pass count runs it.
+template <int BM, int BN, int WM, int WN, int KH, int KW>
+hipError_t launch_passes(ContractionParams& p, int npb, int nz, hipStream_t stream) {
+    if (npb <= 2) return launch_instance<BM, BN, WM, WN, KH, KW, 2>(p, nz, stream);
+    if (npb <= 3) return launch_instance<BM, BN, WM, WN, KH, KW, 3>(p, nz, stream);
+    if (npb <= 4) return launch_instance<BM, BN, WM, WN, KH, KW, 4>(p, nz, stream);
+    if (npb <= 5) return launch_instance<BM, BN, WM, WN, KH, KW, 5>(p, nz, stream);
+    if (npb <= 6) return launch_instance<BM, BN, WM, WN, KH, KW, 6>(p, nz, stream);
+    if (npb <= 8) return launch_instance<BM, BN, WM, WN, KH, KW, 8>(p, nz, stream);
+    return hipErrorInvalidValue;
 }
 
 template <int KH, int KW>
-hipError_t launch_config(ContractionParams& p, int cfg, int nz, hipStream_t stream) {
+hipError_t launch_config(ContractionParams& p, int cfg, int npb, int nz, hipStream_t stream) {
     switch (cfg) {
-        case 0: return launch_instance<64, 64, 2, 2, KH, KW, 8>(p, nz, stream);
-        case 1: return launch_instance<64, 128, 2, 2, KH, KW, 12>(p, nz, stream);
-        case 2: return launch_instance<128, 128, 4, 2, KH, KW, 8>(p, nz, stream);
+        case 0: return launch_passes<64, 64, 2, 2, KH, KW>(p, npb, nz, stream);
+        case 1: return launch_passes<128, 128, 4, 2, KH, KW>(p, npb, nz, stream);
         default: return hipErrorInvalidValue;
     }
 }
@@ -75,7 +85,8 @@ bool launch_conv_window(ContractionParams& p, int kH, int kW, int OH, int OW, in
     g.PCd = FastDiv::make((uint32_t)PC);
     g.planed = FastDiv::make((uint32_t)best_plane);
     g.IPRd = FastDiv::make((uint32_t)g.IPR);
-    *status = launch_config<3, 3>(p, best, nz, stream);
+    const int npb = (WIN_CB * best_plane + kConfigs[best].nt - 1) / kConfigs[best].nt;
+    *status = launch_config<3, 3>(p, best, npb, nz, stream);
     return true;
 }
 
