@@ -25,6 +25,7 @@
 // outside the operand gets 0 from the hardware range check, so the loop body has no divergent
 // branch and no select, and loads, LDS traffic and MFMAs can be scheduled around each other.
 #pragma once
+#include <type_traits>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -129,7 +130,7 @@ __device__ inline __amdgpu_buffer_rsrc_t tile_rsrc(const float* p) {
 
 // ------------------------------------------------------------------------------------------
 // Tile loader: global -> registers -> LDS for a ROWS x BK tile, NT threads.
-template <int KIND, int VEC, int ROWS, int BK, int NT>
+template <int KIND, int VEC, int ROWS, int BK, int NT, int NSETS = 1>
 struct TileLoader {
     static constexpr bool kc = (KIND == LOAD_KC);
     static constexpr int FAST = kc ? (BK / VEC) : (ROWS / VEC);   // threads along the contiguous axis
@@ -142,7 +143,7 @@ struct TileLoader {
     static_assert(NT % FAST == 0, "threads must tile the contiguous axis");
     static_assert(SLOW % SLOW_PER_PASS == 0 || SLOW < SLOW_PER_PASS, "tile/loader mismatch");
 
-    float reg[NLOAD * VEC];      // staging registers: the next K step's tile on its way to LDS
+    float reg[NSETS][NLOAD * VEC];   // staging registers: tiles of coming K steps on their way to LDS
     int fast, slow0;
     bool active;                 // false when SLOW < SLOW_PER_PASS leaves the thread idle
     const float* base;           // first element of the tile (RC: at k = 0)
@@ -201,28 +202,30 @@ struct TileLoader {
         rsrc = tile_rsrc(base);
     }
 
+    template <int S>
     __device__ inline void load(__amdgpu_buffer_rsrc_t r, uint32_t off, int soff, int p) {
         if (VEC == 4) {
             const floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, soff, 0));
-            reg[p * 4 + 0] = v.x; reg[p * 4 + 1] = v.y; reg[p * 4 + 2] = v.z; reg[p * 4 + 3] = v.w;
+            reg[S][p * 4 + 0] = v.x; reg[S][p * 4 + 1] = v.y; reg[S][p * 4 + 2] = v.z; reg[S][p * 4 + 3] = v.w;
         } else {
-            reg[p] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, soff, 0));
+            reg[S][p] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, soff, 0));
         }
     }
 
-    // Issue the global loads of the tile whose first k is k0.
+    // Issue the global loads of the tile whose first k is k0 into register set S (k0 >= K loads nothing).
+    template <int S>
     __device__ inline void fetch(int k0, const ContractionParams& cp) {
         if constexpr (kc) {
             const bool k_ok = k0 + fast * VEC < K;
 #pragma unroll
-            for (int p = 0; p < NLOAD; ++p) load(rsrc, k_ok ? voff[p] : OOB, k0 * 4, p);
+            for (int p = 0; p < NLOAD; ++p) load<S>(rsrc, k_ok ? voff[p] : OOB, k0 * 4, p);
         } else if constexpr (KIND == LOAD_RC) {
             // the resource is re-based at row k0 so that offsets stay small whatever K is
             const __amdgpu_buffer_rsrc_t r = tile_rsrc(base + (int64_t)k0 * ld);
 #pragma unroll
             for (int p = 0; p < NLOAD; ++p) {
                 const bool good = col_ok && (k0 + slow0 + p * SLOW_PER_PASS < K);
-                load(r, good ? voff[0] : OOB, p * SLOW_PER_PASS * ld * 4, p);
+                load<S>(r, good ? voff[0] : OOB, p * SLOW_PER_PASS * ld * 4, p);
             }
         } else {
             // k -> (c, kh, kw) is the same for every column, so the BK decompositions of this
@@ -244,12 +247,13 @@ struct TileLoader {
                 const int ih = ih0 + (dhw >> 16), iw = iw0 + (dhw & 0xffff);
                 const bool good = col_ok && koff >= 0 && (unsigned)ih < (unsigned)cp.ic.H &&
                                   (unsigned)iw < (unsigned)cp.ic.W;
-                load(rsrc, good ? (voff[0] + (uint32_t)koff) * 4u : OOB, 0, p);
+                load<S>(rsrc, good ? (voff[0] + (uint32_t)koff) * 4u : OOB, 0, p);
             }
         }
     }
 
-    // Write the fetched tile into an LDS buffer.
+    // Write the tile held in register set S into an LDS buffer.
+    template <int S>
     __device__ inline void commit(float* lds) const {
         if (!active) return;
 #pragma unroll
@@ -257,10 +261,10 @@ struct TileLoader {
             const int slow = slow0 + p * SLOW_PER_PASS;
             float* dst = kc ? lds + slow * LDK + fast * VEC : lds + slow * LDR + fast * VEC;
             if (VEC == 4) {
-                floatx4 v = {reg[p * 4 + 0], reg[p * 4 + 1], reg[p * 4 + 2], reg[p * 4 + 3]};
+                floatx4 v = {reg[S][p * 4 + 0], reg[S][p * 4 + 1], reg[S][p * 4 + 2], reg[S][p * 4 + 3]};
                 *reinterpret_cast<floatx4*>(dst) = v;
             } else {
-                *dst = reg[p];
+                *dst = reg[S][p];
             }
         }
     }
@@ -521,8 +525,12 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
     static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "sub-tile of 32x32 blocks");
     static_assert(BK % 8 == 0, "K step is a multiple of the 8-wide half-step");
     constexpr int BVEC = (BKIND == LOAD_IM2COL) ? 1 : VEC;
-    using ALoader = TileLoader<AKIND, VEC, BM, BK, NT>;
-    using BLoader = TileLoader<BKIND, BVEC, BN, BK, NT>;
+    // Steps the global loads run ahead of the MFMAs.  Two hides the memory latency behind a whole
+    // step of MFMAs; one where a step is long anyway (BK = 32: measured 1-2 % faster) or where
+    // the second staging set would not fit in the 128 registers a 1024-thread workgroup has.
+    constexpr int PF = (BK >= 32 || (BM * BN >= 256 * 256 && BKIND == LOAD_IM2COL)) ? 1 : 2;
+    using ALoader = TileLoader<AKIND, VEC, BM, BK, NT, PF>;
+    using BLoader = TileLoader<BKIND, BVEC, BN, BK, NT, PF>;
 
     __shared__ __attribute__((aligned(16))) float lds_a[2][ALoader::LDS_FLOATS];
     __shared__ __attribute__((aligned(16))) float lds_b[2][BLoader::LDS_FLOATS];
@@ -556,54 +564,79 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
     int kt0, kt1;
     split_range((cp.K + BK - 1) / BK, cp.ksplit, split, kt0, kt1);
 
-    // MFMAs of one K step from LDS buffer `buf`
-    auto compute = [&](int buf) {
-        const float* sa = lds_a[buf];
-        const float* sb = lds_b[buf];
-        float fa[BK / 8][TM][4], fb[BK / 8][TN][4];
+    constexpr int G = BK / 8;                       // half-step groups per K step
+    constexpr int NREAD = (TM * (AKIND == LOAD_KC ? 1 : 4)) + (TN * (BKIND == LOAD_KC ? 1 : 4));   // LDS reads per group
+    constexpr int NMFMA = 4 * TM * TN;              // MFMAs per group
+    static_assert(G % 2 == 0, "fragment sets alternate per group");
+    float fa[2][TM][4], fb[2][TN][4];               // fragments of two groups: one in use, one arriving
+    auto frags = [&](int f, int buf, int g) {
 #pragma unroll
-        for (int g = 0; g < BK / 8; ++g) {
+        for (int i = 0; i < TM; ++i) ALoader::frag(lds_a[buf], wm * WTM + i * 32 + li, g, h, fa[f][i]);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) ALoader::frag(sa, wm * WTM + i * 32 + li, g, h, fa[g][i]);
+        for (int j = 0; j < TN; ++j) BLoader::frag(lds_b[buf], wn * WTN + j * 32 + li, g, h, fb[f][j]);
+    };
+    auto mfmas = [&](int f, int s_lo, int s_hi) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) BLoader::frag(sb, wn * WTN + j * 32 + li, g, h, fb[g][j]);
+        for (int s = s_lo; s < s_hi; ++s)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[f][i][s], fb[f][j][s], acc[i][j], 0, 0, 0);
+    };
+    using Par0 = std::integral_constant<int, 0>;
+    using Par1 = std::integral_constant<int, 1>;
+
+    // One K step.  On entry LDS buffer s holds step kt and the fragments of its group 0 are in
+    // fragment set 0; the loads of steps kt+1 .. kt+PF-1 are in flight.
+    //   issue the loads of step kt+PF
+    //   groups 0 .. G-2: MFMAs of group g, the LDS reads of group g+1 in between them
+    //   last group: first half of its MFMAs with the LDS stores of step kt+1 in between;
+    //   barrier; second half with the LDS reads of step kt+1's group 0 in between.
+    auto step = [&](int kt, auto S) {
+        constexpr int s = decltype(S)::value;
+        constexpr int set_in = PF == 2 ? s : 0;         // register set the new loads go to
+        constexpr int set_out = PF == 2 ? (s ^ 1) : 0;  // register set that holds step kt+1
+        la.template fetch<set_in>((kt + PF) * BK, cp);
+        lb.template fetch<set_in>((kt + PF) * BK, cp);
+#pragma unroll
+        for (int g = 0; g + 1 < G; ++g) {
+            frags((g + 1) & 1, s, g + 1);
+            mfmas(g & 1, 0, 4);
+#pragma unroll
+            for (int q = 0; q < NMFMA; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, (NREAD + NMFMA - 1) / NMFMA, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        // keep every LDS read of the step ahead of its MFMAs (the scheduler would otherwise
-        // interleave them one by one and expose the LDS latency before each MFMA group)
+        la.template commit<set_out>(lds_a[s ^ 1]);
+        lb.template commit<set_out>(lds_b[s ^ 1]);
+        mfmas((G - 1) & 1, 0, 2);
+        __syncthreads();
+        frags(0, s ^ 1, 0);
+        mfmas((G - 1) & 1, 2, 4);
+#pragma unroll
+        for (int q = 0; q < NMFMA / 2; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, (NREAD + NMFMA / 2 - 1) / (NMFMA / 2), 0);
+        }
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int g = 0; g < BK / 8; ++g)
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[g][i][s], fb[g][j][s], acc[i][j], 0, 0, 0);
     };
 
-    // Software pipeline: the loads of step t+1 are issued before the MFMAs of step t and written
-    // to the other LDS buffer after them.  (Issuing them two steps ahead through a second set
-    // of staging registers was measured and gained nothing.)
-    if (kt0 < kt1) {
-        la.fetch(kt0 * BK, cp);
-        lb.fetch(kt0 * BK, cp);
-        la.commit(lds_a[0]);
-        lb.commit(lds_b[0]);
+    la.template fetch<0>(kt0 * BK, cp);
+    lb.template fetch<0>(kt0 * BK, cp);
+    if (PF == 2) {
+        la.template fetch<PF - 1>((kt0 + 1) * BK, cp);
+        lb.template fetch<PF - 1>((kt0 + 1) * BK, cp);
     }
+    la.template commit<0>(lds_a[0]);
+    lb.template commit<0>(lds_b[0]);
     __syncthreads();
-    for (int kt = kt0; kt < kt1; ++kt) {
-        const int cur = (kt - kt0) & 1;
-        if (kt + 1 < kt1) {
-            la.fetch((kt + 1) * BK, cp);
-            lb.fetch((kt + 1) * BK, cp);
-        }
-        compute(cur);
-        if (kt + 1 < kt1) {
-            la.commit(lds_a[cur ^ 1]);
-            lb.commit(lds_b[cur ^ 1]);
-        }
-        __syncthreads();
+    frags(0, 0, 0);
+    for (int kt = kt0; kt < kt1; kt += 2) {
+        step(kt, Par0{});
+        if (kt + 1 < kt1) step(kt + 1, Par1{});
     }
 
     finish_tile<TM, TN, WTM, WTN, NT>(acc, m0, n0, zslice, split, wm, wn, li, h, cp);

@@ -18,8 +18,9 @@ static hipError_t launch_tile(ContractionParams& p, int tile, int nz, hipStream_
     switch (tile) {
         case TILE_64:
             // short K: the 16-wide step leaves room for 8 workgroups per CU, which hides the
-            // per-tile prologue and epilogue better; long K: fewer, longer steps
-            if (p.K < 1024) return launch_one<64, 64, 16, 2, 2, AK, BKIND, VEC>(p, nz, stream);
+            // per-tile prologue and epilogue better; long K: fewer, longer steps (measured
+            // crossover between K = 256 and K = 512)
+            if (p.K < 512) return launch_one<64, 64, 16, 2, 2, AK, BKIND, VEC>(p, nz, stream);
             return launch_one<64, 64, 32, 2, 2, AK, BKIND, VEC>(p, nz, stream);
         case TILE_128: return launch_one<128, 128, 16, 4, 2, AK, BKIND, VEC>(p, nz, stream);
         case TILE_256: return launch_one<256, 256, 16, 4, 4, AK, BKIND, VEC>(p, nz, stream);
@@ -29,10 +30,11 @@ static hipError_t launch_tile(ContractionParams& p, int tile, int nz, hipStream_
 
 // Estimated time of each tile shape, in units of (output elements per CU) / efficiency:
 // the workgroups a CU has to run, times the tile area, over the fraction of the MFMA rate
-// that shape sustains when the chip is full (measured on 4096^3: 0.80 / 0.90 / 0.95).
+// that shape sustains when the chip is full (measured on 2048^3 and 4096^3: the 64 tile
+// reaches 0.92, the 128 tile slightly less at mid sizes, the 256 tile 0.94).
 int pick_tile(int64_t M, int64_t N, int64_t nz) {
     static const int bm[TILE_COUNT] = {64, 128, 256};
-    static const double eff[TILE_COUNT] = {0.80, 0.90, 0.95};
+    static const double eff[TILE_COUNT] = {0.92, 0.90, 0.94};
     static const int resident[TILE_COUNT] = {8, 2, 1};    // workgroups that share a CU
     const double cus = 256.0;
     int best = TILE_64;
