@@ -36,8 +36,9 @@ constexpr int WIN_CB = 4;      // input channels per K step
 // Schedule of one K step (LDS buffer s holds step ks, register set s^1 holds step ks+1, whose
 // loads were issued a whole step ago):
 //   issue global loads of step ks+2 into register set s
-//   read the fragments of channel pair 0; then read pair 1's fragments in between pair 0's MFMAs
-//   store register set s^1 into LDS buffer s^1 in between pair 1's MFMAs; barrier
+//   pair 0's MFMAs (fragments read during the previous step), pair 1's LDS reads in between
+//   store register set s^1 into LDS buffer s^1 in between the first half of pair 1's MFMAs
+//   barrier; the second half, with the LDS reads of step ks+1's pair 0 in between
 template <int BM, int BN, int WM, int WN, int KH, int KW, int NPB>
 __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const ContractionParams cp) {
     constexpr int NT = 64 * WM * WN;
@@ -178,25 +179,23 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
             for (int j = 0; j < TN; ++j) fb[f][tap][j] = sb[rd_b[j] + 2 * cc * g.plane + tap_b[tap]];
         }
     };
-    auto mfmas = [&](int f) {
+    auto mfmas = [&](int f, int tap_lo, int tap_hi) {
 #pragma unroll
-        for (int tap = 0; tap < KHW; ++tap)
+        for (int tap = tap_lo; tap < tap_hi; ++tap)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[f][tap][i], fb[f][tap][j], acc[i][j], 0, 0, 0);
     };
+    // On entry LDS buffer s holds step ks and pair 0's fragments (set 0) are already in registers.
     auto step = [&](int ks, auto S, auto SN) {
         constexpr int s = decltype(S)::value;
+        constexpr int HALF = KHW / 2;
         fetch(ks + 2, S);
-        const float* sa = lds_a[s];
-        const float* sb = lds_b[s];
         static_assert(WIN_CB == 4, "two channel pairs per step");
-        frags(0, sa, sb, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        frags(1, sa, sb, 1);
-        mfmas(0);
+        frags(1, lds_a[s], lds_b[s], 1);
+        mfmas(0, 0, KHW);
 #pragma unroll
         for (int q = 0; q < NMFMA; ++q) {            // one MFMA, then its share of pair 1's LDS reads
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -204,14 +203,24 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
         }
         __builtin_amdgcn_sched_barrier(0);
         commit(s ^ 1, SN);                           // past the end this stores zeros nobody reads
-        mfmas(1);
+        mfmas(1, 0, HALF);
         __syncthreads();
+        frags(0, lds_a[s ^ 1], lds_b[s ^ 1], 0);     // next step's pair 0, behind the rest of pair 1
+        mfmas(1, HALF, KHW);
+        constexpr int NREST = (KHW - HALF) * TM * TN;
+#pragma unroll
+        for (int q = 0; q < NREST; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, (NFRAG + NREST - 1) / NREST, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     fetch(ks0, Set0{});
     fetch(ks0 + 1, Set1{});
     commit(0, Set0{});
     __syncthreads();
+    frags(0, lds_a[0], lds_b[0], 0);
     for (int ks = ks0; ks < ks1; ks += 2) {
         step(ks, Set0{}, Set1{});
         if (ks + 1 < ks1) step(ks + 1, Set1{}, Set0{});
