@@ -23,6 +23,25 @@ MFMA_FP32_PEAK_TFLOPS = 157.3      # 256 CU x 256 flop/clk x 2.4 GHz
 HBM_PEAK_GBS = 8000.0
 RAMP_SECONDS = 0.3
 
+# Memory traffic of one Gemm 4096^3 launch from the FETCH_SIZE / WRITE_SIZE counter passes summarised in
+# profiles/gemm4096_hbm_traffic.md (fetch scaled by the 2.000 a plain copy shows, write exact).  The
+# counters sit between the eight L2s and the fabric, so this is L2 fill + write-back traffic (served by
+# the Infinity Cache or HBM).  Reported only while the kernel sources are the ones that were measured.
+TRAFFIC_4096 = {"sources_sha256_16": "945c9ca8139c6826", "bytes_per_launch": (196757.0 * 2.000 + 65536.0) * 1024.0}
+KERNEL_SOURCES = ("paper_2008_08272_amd/csrc/contraction.h", "paper_2008_08272_amd/csrc/contraction.hip")
+
+
+def measured_traffic():
+    import hashlib
+    h = hashlib.sha256()
+    try:
+        for f in KERNEL_SOURCES:
+            with open(os.path.join(ROOT, f), "rb") as fh:
+                h.update(fh.read())
+    except OSError:
+        return None
+    return TRAFFIC_4096["bytes_per_launch"] if h.hexdigest()[:16] == TRAFFIC_4096["sources_sha256_16"] else None
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -103,7 +122,8 @@ def main():
     bytes_4096 = 4.0 * (n * n + n * n + n + n * n)
     achieved = flop_4096 / (k4096_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 3), "peak": MFMA_FP32_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / MFMA_FP32_PEAK_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(achieved / MFMA_FP32_PEAK_TFLOPS, 4), "traffic": measured_traffic(),
+                "traffic_unit": "bytes per launch at the L2/fabric boundary",
                 "kernel": "contraction_kernel<256,256,16; KC,KC; 16-byte loads> on Gemm 4096^3",
                 "avg_launch_ms": round(k4096_ms, 4), "algorithmic_flop": flop_4096,
                 "algorithmic_bytes": bytes_4096}

@@ -6,10 +6,11 @@
 // never-materialised matrix of input patches [Cg*kH*kW x N*OH*OW]).
 //
 // Work decomposition: a workgroup of WM x WN wavefronts owns a BM x BN tile of Y and walks K
-// in steps of BK.  Each step stages an A tile and a B tile in LDS (double buffered: global
-// loads for step t+1 are issued before the MFMAs of step t and written to the other buffer
-// after them, one barrier per step).  Each wavefront owns a (BM/WM) x (BN/WN) sub-tile as
-// a grid of 32x32 accumulators fed by v_mfma_f32_32x32x2_f32.
+// in steps of BK.  Each step stages an A tile and a B tile in LDS (two buffers, one barrier per
+// step; global loads run one or two steps ahead through staging registers, and the LDS reads
+// of the fragments needed next are issued in between the MFMAs of the fragments in use).
+// Each wavefront owns a (BM/WM) x (BN/WN) sub-tile as a grid of 32x32 accumulators fed by
+// v_mfma_f32_32x32x2_f32.
 //
 // Operand kinds (how a tile is fetched and how it sits in LDS):
 //   KC      k is the contiguous index in memory (Gemm A, Gemm B with transB, conv filters).
@@ -25,9 +26,10 @@
 // outside the operand gets 0 from the hardware range check, so the loop body has no divergent
 // branch and no select, and loads, LDS traffic and MFMAs can be scheduled around each other.
 #pragma once
-#include <type_traits>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 namespace onnxhip {
 
