@@ -112,9 +112,15 @@ struct ContractionParams {
     int nz;                  // number of z-slices
     // Split-K: grid.y = ksplit * (z overflow factor).  Workgroup (tile, split) sums its share of
     // the K steps; with ksplit > 1 it parks the partial tile in ws_partial and a second kernel
-    // adds the partials in split order and stores Y.
+    // (splitk_finish_kernel) adds the partials in split order and runs the epilogue.
     int ksplit;
     float* ws_partial;
+    // Tail split (ksplit == 1, nz == 1 only): blocks [0, tail_begin) compute whole tiles; the
+    // remaining tiles_m*tiles_n - tail_begin tiles, which would keep only a few CUs busy at the
+    // end of the launch, are each shared by tail_split blocks that follow in the same grid and
+    // are finished by a splitk_finish_kernel over just those tiles.  tail_begin equals the tile
+    // count when there is no tail.
+    int tail_begin, tail_split;
     Im2colGeom ic;
 };
 
@@ -350,11 +356,17 @@ __device__ inline void store_block(const floatx16& acc, int row0, float col_bias
     }
 }
 
-// Which tile a workgroup owns: XCD-contiguous numbering, then sweeps of 8 tile rows so that
-// the workgroups running together share A rows and B columns.
-__device__ inline void tile_origin(const ContractionParams& cp, int BM, int BN, int& m0, int& n0) {
-    const int ntiles = cp.tiles_m * cp.tiles_n;
-    const int logical = xcd_contiguous(blockIdx.x, ntiles);
+// What a workgroup of a contraction launch computes: the tile at (m0, n0) of z-slice `zslice`,
+// K steps of share `split` out of `ksplit`; with ksplit > 1 its partial tile goes to slot
+// `slot` of the workspace.
+struct TileWork {
+    int m0, n0, zslice, split, ksplit;
+    int64_t slot;
+};
+
+// Logical tile number -> tile origin: tiles are swept 8 tile-rows at a time, column by column,
+// so that consecutive numbers share B columns and stay within a few A row panels.
+__device__ inline void tile_origin(const ContractionParams& cp, int logical, int BM, int BN, int& m0, int& n0) {
     constexpr int GROUP = 8;
     const int per_group = GROUP * cp.tiles_n;
     const int grp = logical / per_group;
@@ -363,6 +375,31 @@ __device__ inline void tile_origin(const ContractionParams& cp, int BM, int BN, 
     const int in_grp = logical - grp * per_group;
     m0 = (first_m + in_grp % rows_here) * BM;
     n0 = (in_grp / rows_here) * BN;
+}
+
+// blockIdx.x below tail_begin: a whole tile (or, with ksplit > 1, share blockIdx.y % ksplit of
+// it; blockIdx.y also carries the overflow of the z-slice count).  From tail_begin on: share
+// t % tail_split of tail tile t / tail_split.  False when the block has nothing to do.
+__device__ inline bool tile_work(const ContractionParams& cp, int BM, int BN, TileWork& w) {
+    const int ntiles = cp.tiles_m * cp.tiles_n;
+    int logical;
+    if ((int)blockIdx.x < cp.tail_begin) {
+        w.ksplit = cp.ksplit;
+        w.split = blockIdx.y % cp.ksplit;
+        w.zslice = (blockIdx.y / cp.ksplit) * gridDim.z + blockIdx.z;
+        logical = xcd_contiguous(blockIdx.x, cp.tail_begin);
+        w.slot = ((int64_t)w.zslice * ntiles + blockIdx.x) * cp.ksplit + w.split;
+    } else {
+        const int t = (int)blockIdx.x - cp.tail_begin;
+        w.ksplit = cp.tail_split;
+        w.split = t % cp.tail_split;
+        w.zslice = 0;
+        logical = cp.tail_begin + t / cp.tail_split;
+        w.slot = t;
+    }
+    if (w.zslice >= cp.nz) return false;
+    tile_origin(cp, logical, BM, BN, w.m0, w.n0);
+    return true;
 }
 
 // Offsets of the z-slice's A and B operands (batch broadcasting / convolution groups).
@@ -427,12 +464,6 @@ __device__ inline void store_tile(const floatx16 (&acc)[TM][TN], int m0, int n0,
     }
 }
 
-// blockIdx.y carries the K split (fast) and the overflow of the z-slice count (slow).
-__device__ inline void slice_and_split(const ContractionParams& cp, int& zslice, int& split) {
-    split = blockIdx.y % cp.ksplit;
-    zslice = (blockIdx.y / cp.ksplit) * gridDim.z + blockIdx.z;
-}
-
 // The K steps [kt0, kt1) of `nk` that split `split` of `ksplit` owns.
 __device__ inline void split_range(int nk, int ksplit, int split, int& kt0, int& kt1) {
     const int per = (nk + ksplit - 1) / ksplit;
@@ -448,12 +479,11 @@ __device__ inline void split_range(int nk, int ksplit, int split, int& kt0, int&
 // arrival counter inside one: the XCDs' L2 caches are only coherent with each other at
 // kernel boundaries, and a device-scope fence per workgroup writes back and invalidates them.
 template <int TM, int TN, int WTM, int WTN, int NT>
-__device__ inline void finish_tile(floatx16 (&acc)[TM][TN], int m0, int n0, int zslice, int split, int wm,
-                                   int wn, int li, int h, const ContractionParams& cp) {
-    if (cp.ksplit > 1) {
+__device__ inline void finish_tile(floatx16 (&acc)[TM][TN], const TileWork& w, int wm, int wn, int li, int h,
+                                   const ContractionParams& cp) {
+    if (w.ksplit > 1) {
         constexpr int TILE = NT * TM * TN * 16;
-        const int64_t tile_lin = (int64_t)zslice * (cp.tiles_m * cp.tiles_n) + blockIdx.x;
-        float* mine = cp.ws_partial + (tile_lin * cp.ksplit + split) * TILE + threadIdx.x;
+        float* mine = cp.ws_partial + w.slot * TILE + threadIdx.x;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -462,26 +492,30 @@ __device__ inline void finish_tile(floatx16 (&acc)[TM][TN], int m0, int n0, int 
                 for (int r = 0; r < 16; ++r) mine[((i * TN + j) * 16 + r) * NT] = acc[i][j][r];
         return;
     }
-    store_tile<TM, TN, WTM, WTN>(acc, m0, n0, zslice, wm, wn, li, h, cp);
+    store_tile<TM, TN, WTM, WTN>(acc, w.m0, w.n0, w.zslice, wm, wn, li, h, cp);
 }
 
 // Second half of a split-K product: one workgroup per tile, same thread-to-accumulator
-// mapping as the kernel that produced the partials.
+// mapping as the kernel that produced the partials.  tail = false: all tiles of a launch
+// with ksplit > 1; tail = true: only the tail tiles of a launch with a tail split.
 template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(64 * WM * WN) void splitk_finish_kernel(const ContractionParams cp) {
+__global__ __launch_bounds__(64 * WM * WN) void splitk_finish_kernel(const ContractionParams cp, const bool tail) {
     constexpr int NT = 64 * WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int TILE = NT * TM * TN * 16;
     const int zslice = blockIdx.y * gridDim.z + blockIdx.z;
     if (zslice >= cp.nz) return;
+    const int ntiles = cp.tiles_m * cp.tiles_n;
+    const int ksplit = tail ? cp.tail_split : cp.ksplit;
+    const int logical = tail ? cp.tail_begin + (int)blockIdx.x : xcd_contiguous(blockIdx.x, ntiles);
+    const int64_t first_slot = tail ? (int64_t)blockIdx.x * ksplit : ((int64_t)zslice * ntiles + blockIdx.x) * ksplit;
     int m0, n0;
-    tile_origin(cp, BM, BN, m0, n0);
+    tile_origin(cp, logical, BM, BN, m0, n0);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, h = lane >> 5;
-    const int64_t tile_lin = (int64_t)zslice * (cp.tiles_m * cp.tiles_n) + blockIdx.x;
-    const float* base = cp.ws_partial + tile_lin * cp.ksplit * TILE + threadIdx.x;
+    const float* base = cp.ws_partial + first_slot * TILE + threadIdx.x;
     floatx16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -489,7 +523,7 @@ __global__ __launch_bounds__(64 * WM * WN) void splitk_finish_kernel(const Contr
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    for (int s = 0; s < cp.ksplit; ++s) {
+    for (int s = 0; s < ksplit; ++s) {
         const float* src = base + (int64_t)s * TILE;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -501,19 +535,52 @@ __global__ __launch_bounds__(64 * WM * WN) void splitk_finish_kernel(const Contr
     store_tile<TM, TN, WTM, WTN>(acc, m0, n0, zslice, wm, wn, li, h, cp);
 }
 
-// Host side: enqueue `kernel` for the tiles of `p` and, when the K range is split, the
-// finishing kernel behind it.
+// Tail split for a launch of `tiles` whole tiles that walk `nk` K steps each: how many tiles
+// to leave to the tail and in how many shares to cut each of them.  A CU keeps several
+// workgroups resident, so the launch ends when the CUs that received one tile more than the
+// rest are done; cutting the surplus tiles into shares that cover all CUs removes most of that
+// last round.  Worth it only when the last round is a sizeable part of the launch and the
+// surplus is small enough that its shares get short.
+struct TailSplit {
+    int tiles, split;
+};
+inline TailSplit pick_tail(int64_t tiles, int nk, int64_t tile_elems, const float* ws, int64_t ws_floats) {
+    TailSplit none = {0, 1};
+    const int cus = 256;
+    if (!ws || tiles <= cus || tiles > 8 * cus || nk < 8) return none;
+    const int r = (int)(tiles % cus);
+    if (r == 0 || r > cus / 2) return none;
+    int s = cus / r;
+    if (s > 16) s = 16;
+    if (s > nk / 4) s = nk / 4;
+    if (s < 2 || (int64_t)r * s * tile_elems > ws_floats) return none;
+    TailSplit t = {r, s};
+    return t;
+}
+
+// Host side: enqueue `kernel` for the tiles of `p` and, when K ranges are split, the finishing
+// kernel behind it.  `nk` = K steps a whole tile walks.
 template <int BM, int BN, int WM, int WN, typename Kernel>
-inline hipError_t launch_with_split(Kernel kernel, ContractionParams& p, int nz, hipStream_t stream) {
+inline hipError_t launch_with_split(Kernel kernel, ContractionParams& p, int nz, int nk, int64_t ws_floats,
+                                    hipStream_t stream) {
     const unsigned gz = nz < 32768 ? (unsigned)nz : 32768u;
     const unsigned gy = ((unsigned)nz + gz - 1) / gz;
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
     if (tiles > 0x7fffffffLL || gy > 2047u) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)tiles, gy * (unsigned)p.ksplit, gz), dim3(64 * WM * WN), 0, stream, p);
+    TailSplit tail = {0, 1};
+    if (p.ksplit == 1 && nz == 1) tail = pick_tail(tiles, nk, (int64_t)BM * BN, p.ws_partial, ws_floats);
+    p.tail_begin = (int)tiles - tail.tiles;
+    p.tail_split = tail.split;
+    const unsigned gx = (unsigned)(p.tail_begin + tail.tiles * tail.split);
+    hipLaunchKernelGGL(kernel, dim3(gx, gy * (unsigned)p.ksplit, gz), dim3(64 * WM * WN), 0, stream, p);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && p.ksplit > 1) {
         hipLaunchKernelGGL((splitk_finish_kernel<BM, BN, WM, WN>), dim3((unsigned)tiles, gy, gz), dim3(64 * WM * WN), 0,
-                           stream, p);
+                           stream, p, false);
+        e = hipGetLastError();
+    } else if (e == hipSuccess && tail.tiles > 0) {
+        hipLaunchKernelGGL((splitk_finish_kernel<BM, BN, WM, WN>), dim3((unsigned)tail.tiles, 1, 1), dim3(64 * WM * WN),
+                           0, stream, p, true);
         e = hipGetLastError();
     }
     return e;
@@ -537,14 +604,11 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
     __shared__ __attribute__((aligned(16))) float lds_a[2][ALoader::LDS_FLOATS];
     __shared__ __attribute__((aligned(16))) float lds_b[2][BLoader::LDS_FLOATS];
 
-    int zslice, split;
-    slice_and_split(cp, zslice, split);
-    if (zslice >= cp.nz) return;                    // uniform for the whole workgroup
-
-    int m0, n0;
-    tile_origin(cp, BM, BN, m0, n0);
+    TileWork w;
+    if (!tile_work(cp, BM, BN, w)) return;          // uniform for the whole workgroup
+    const int m0 = w.m0, n0 = w.n0;
     int64_t a_off, b_off;
-    slice_offsets(cp, zslice, a_off, b_off);
+    slice_offsets(cp, w.zslice, a_off, b_off);
 
     ALoader la;
     BLoader lb;
@@ -564,7 +628,7 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     int kt0, kt1;
-    split_range((cp.K + BK - 1) / BK, cp.ksplit, split, kt0, kt1);
+    split_range((cp.K + BK - 1) / BK, w.ksplit, w.split, kt0, kt1);
 
     constexpr int G = BK / 8;                       // half-step groups per K step
     constexpr int NREAD = (TM * (AKIND == LOAD_KC ? 1 : 4)) + (TN * (BKIND == LOAD_KC ? 1 : 4));   // LDS reads per group
@@ -641,7 +705,7 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
         if (kt + 1 < kt1) step(kt + 1, Par1{});
     }
 
-    finish_tile<TM, TN, WTM, WTN, NT>(acc, m0, n0, zslice, split, wm, wn, li, h, cp);
+    finish_tile<TM, TN, WTM, WTN, NT>(acc, w, wm, wn, li, h, cp);
 }
 
 }  // namespace onnxhip

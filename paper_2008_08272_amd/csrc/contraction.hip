@@ -10,7 +10,8 @@ static hipError_t launch_one(ContractionParams& p, int nz, hipStream_t stream) {
     p.nz = nz;
     p.ksplit = pick_split((int64_t)p.tiles_m * p.tiles_n * nz, (p.K + BK - 1) / BK, (int64_t)BM * BN, 6.0);
     p.ws_partial = workspace().partial;
-    return launch_with_split<BM, BN, WM, WN>(contraction_kernel<BM, BN, BK, WM, WN, AK, BKIND, VEC>, p, nz, stream);
+    return launch_with_split<BM, BN, WM, WN>(contraction_kernel<BM, BN, BK, WM, WN, AK, BKIND, VEC>, p, nz,
+                                             (p.K + BK - 1) / BK, workspace().partial_floats, stream);
 }
 
 template <int AK, int BKIND, int VEC>

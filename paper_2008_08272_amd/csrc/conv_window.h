@@ -56,13 +56,11 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
     __shared__ float lds_a[2][BM * LDA + 4];    // + a slot that absorbs the stores of surplus threads
     __shared__ float lds_b[2][NPB * NT];
 
-    int zslice, split;
-    slice_and_split(cp, zslice, split);
-    if (zslice >= cp.nz) return;
-    int m0, n0;
-    tile_origin(cp, BM, BN, m0, n0);
+    TileWork w;
+    if (!tile_work(cp, BM, BN, w)) return;
+    const int m0 = w.m0, n0 = w.n0;
     int64_t a_off, b_off;
-    slice_offsets(cp, zslice, a_off, b_off);
+    slice_offsets(cp, w.zslice, a_off, b_off);
     const Im2colGeom& g = cp.ic;
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
@@ -141,7 +139,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     int ks0, ks1;
-    split_range(g.Cg / WIN_CB, cp.ksplit, split, ks0, ks1);
+    split_range(g.Cg / WIN_CB, w.ksplit, w.split, ks0, ks1);
 
     floatx4 reg_a[2][PA];
     float reg_b[2][NPB];
@@ -225,7 +223,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
         step(ks, Set0{}, Set1{});
         if (ks + 1 < ks1) step(ks + 1, Set1{}, Set0{});
     }
-    finish_tile<TM, TN, WTM, WTN, NT>(acc, m0, n0, zslice, split, wm, wn, li, h, cp);
+    finish_tile<TM, TN, WTM, WTN, NT>(acc, w, wm, wn, li, h, cp);
 }
 
 }  // namespace onnxhip

@@ -33,7 +33,8 @@ hipError_t launch_instance(ContractionParams& p, int nz, hipStream_t stream) {
     p.nz = nz;
     p.ksplit = pick_split((int64_t)p.tiles_m * p.tiles_n * nz, p.ic.Cg / WIN_CB, (int64_t)BM * BN, 4.0);
     p.ws_partial = workspace().partial;
-    return launch_with_split<BM, BN, WM, WN>(conv_window_kernel<BM, BN, WM, WN, KH, KW, NPB>, p, nz, stream);
+    return launch_with_split<BM, BN, WM, WN>(conv_window_kernel<BM, BN, WM, WN, KH, KW, NPB>, p, nz,
+                                             p.ic.Cg / WIN_CB, workspace().partial_floats, stream);
 }
 
 // npb = passes the patch needs; the instance with the next larger pass count runs it.

@@ -362,6 +362,41 @@ def test_split_k_shapes_repeatable(lib, workspace):
     assert rel_err(host(lib.onnx_conv(dev(X), dev(Wt), None)), ref) <= REL_TOL
 
 
+def test_tail_split_shapes_repeatable(lib, workspace):
+    """Slightly more than a multiple of 256 output tiles: with a workspace the surplus tiles are
+    shared by several workgroups each (their K range cut into shares) inside the same launch and
+    finished by a second kernel; the rest of the tiles is computed as usual.  Results must match
+    the oracle everywhere (whole tiles, shared tiles, ragged edges) and repeat bit for bit."""
+    announce("tail-split", workspace)
+    rng = np.random.default_rng(78)
+    # 64x64 tiles: 17x16 = 272 (16 surplus), 18x16 with ragged edges = 288 (32 surplus), 25x31 = 775 (7 surplus)
+    for (M, N, K, tA, tB) in [(1088, 1024, 256, 0, 1), (1100, 1000, 300, 0, 0), (1600, 1984, 128, 1, 1)]:
+        A = rng.uniform(-1, 1, (K, M) if tA else (M, K)).astype(np.float32)
+        B = rng.uniform(-1, 1, (N, K) if tB else (K, N)).astype(np.float32)
+        C = rng.uniform(-1, 1, (1, N)).astype(np.float32)
+        ref, S = oracle.gemm(A, B, C, 1.0, 1.0, tA, tB, relu=False, want_scale=True)
+        a, b, c = dev(A), dev(B), dev(C)
+        outs = [host(lib.onnx_gemm(a, b, c, 1.0, 1.0, tA, tB)) for _ in range(3)]
+        assert rel_err(outs[0], ref) <= REL_TOL
+        assert within_rounding_bound(outs[0], ref, S, K + 2)
+        assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    # 3x3 convolution through the LDS-patch kernel: 2 x 400 = 800 tiles of 64x64 (32 surplus), bias + residual + Relu
+    X = rng.uniform(-1, 1, (32, 64, 28, 29)).astype(np.float32)
+    Wt = rng.uniform(-1, 1, (128, 64, 3, 3)).astype(np.float32)
+    Bv = rng.uniform(-1, 1, (128,)).astype(np.float32)
+    R = rng.uniform(-1, 1, (32, 128, 28, 29)).astype(np.float32)
+    ref = oracle.conv(X, Wt, Bv, (1, 1, 1, 1), residual=R, relu=True)
+    x, w_, bv, r = dev(X), dev(Wt), dev(Bv), dev(R)
+    outs = [host(lib.onnx_conv(x, w_, bv, (1, 1, 1, 1), residual=r, act=1)) for _ in range(2)]
+    assert rel_err(outs[0], ref) <= REL_TOL
+    assert np.array_equal(outs[0], outs[1])
+    # 1x1 convolution (row-contiguous loader): 4 x 196 = 784 tiles
+    X = rng.uniform(-1, 1, (16, 128, 28, 28)).astype(np.float32)
+    Wt = rng.uniform(-1, 1, (256, 128, 1, 1)).astype(np.float32)
+    ref = oracle.conv(X, Wt, None)
+    assert rel_err(host(lib.onnx_conv(dev(X), dev(Wt), None)), ref) <= REL_TOL
+
+
 # ------------------------------------------------------------------------------ degenerate sizes and errors
 
 def test_zero_sized_outputs_return_ok(lib):
