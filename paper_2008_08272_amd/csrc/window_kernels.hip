@@ -142,6 +142,111 @@ __global__ __launch_bounds__(256) void global_avgpool_kernel(const float* __rest
     if (lane == 0) Y[plane] = acc / (float)HW;
 }
 
+// ---- row-strip variants -------------------------------------------------------------------
+// One wavefront owns R consecutive output rows x 64 consecutive output columns of one (image,
+// channel) plane, one column per lane.  It issues every load the strip needs up front (the
+// ROWS_IN input rows it touches x KW taps per lane: neighbouring lanes and neighbouring taps
+// hit the same cache lines, so memory sees each line once) and then only does arithmetic on
+// registers: nothing waits on LDS or on a barrier, and a CU keeps several hundred independent
+// loads in flight, which is what a bandwidth-bound kernel needs.  Vertical stride and
+// dilation are template arguments so that the input row of every (output row, kh) is a
+// register known at compile time; everything horizontal is plain address arithmetic.
+struct StripMap {
+    FastDiv chunks, strips;   // column chunks per row, strips per plane
+    uint32_t waves;           // planes * strips * chunks
+};
+
+__device__ inline __amdgpu_buffer_rsrc_t plane_rsrc(const float* plane, int HW) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(plane), 0, HW * 4, 0x00020000);
+}
+
+template <int KH, int KW, int S, int D, int R>
+__global__ __launch_bounds__(256) void conv_rows_kernel(const float* __restrict__ X,
+                                                        const float* __restrict__ Wt,
+                                                        const float* __restrict__ B,
+                                                        const float* __restrict__ residual,
+                                                        float* __restrict__ Y, WindowGeom g, int M, int Cg,
+                                                        int Mg, int relu, StripMap sm) {
+    constexpr int ROWS_IN = (R - 1) * S + (KH - 1) * D + 1;
+    constexpr uint32_t OUT = 0x80000000u;             // offset the buffer range check rejects
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * 4u + (threadIdx.x >> 6));
+    if (wave >= sm.waves) return;
+    const int lane = threadIdx.x & 63;
+    uint32_t rest, chunk, pm, strip;
+    sm.chunks.divmod(wave, rest, chunk);
+    sm.strips.divmod(rest, pm, strip);                // pm = n*M + m
+    const int n = (int)pm / M, m = (int)pm % M;
+    const int grp = m / Mg;
+    const int oh0 = (int)strip * R;
+    const int ow = (int)chunk * 64 + lane;
+    const int ih0 = oh0 * S - g.pT;
+    uint32_t voff[KW];
+#pragma unroll
+    for (int kw = 0; kw < KW; ++kw) {
+        const int iw = ow * g.sW - g.pL + kw * g.dW;
+        voff[kw] = (ow < g.OW && (unsigned)iw < (unsigned)g.W) ? (uint32_t)iw * 4u : OUT;
+    }
+    float acc[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) acc[r] = 0.f;
+    const int HW = g.H * g.W;
+    const float* wm = Wt + (int64_t)m * Cg * KH * KW;
+    for (int c = 0; c < Cg; ++c) {
+        const __amdgpu_buffer_rsrc_t rs = plane_rsrc(X + ((int64_t)n * g.C + grp * Cg + c) * HW, HW);
+        float x[ROWS_IN][KW];
+#pragma unroll
+        for (int i = 0; i < ROWS_IN; ++i) {
+            const int ih = ih0 + i;
+            const bool row_ok = (unsigned)ih < (unsigned)g.H;          // uniform
+#pragma unroll
+            for (int kw = 0; kw < KW; ++kw)
+                x[i][kw] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                               rs, (int)(row_ok ? voff[kw] : OUT), row_ok ? ih * g.W * 4 : 0, 0));
+        }
+        float w[KH * KW];                                              // uniform: scalar loads
+#pragma unroll
+        for (int i = 0; i < KH * KW; ++i) w[i] = wm[c * KH * KW + i];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+                for (int kw = 0; kw < KW; ++kw) acc[r] = fmaf(x[r * S + kh * D][kw], w[kh * KW + kw], acc[r]);
+    }
+    if (ow >= g.OW) return;
+    const float bias = B ? B[m] : 0.f;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int oh = oh0 + r;
+        if (oh < g.OH) {
+            const int64_t o = ((int64_t)pm * g.OH + oh) * g.OW + ow;
+            float v = acc[r] + bias;
+            if (residual) v += residual[o];
+            if (relu) v = v > 0.f ? v : 0.f;
+            Y[o] = v;
+        }
+    }
+}
+
+static inline bool strip_map(const WindowGeom& g, int64_t planes, int R, StripMap& sm) {
+    const int64_t chunks = (g.OW + 63) / 64, strips = (g.OH + R - 1) / R;
+    const int64_t waves = planes * strips * chunks;
+    if (g.OW < 1 || g.OH < 1 || (int64_t)g.H * g.W * 4 >= (1LL << 31) || waves >= (1LL << 31)) return false;
+    sm.chunks = FastDiv::make((uint32_t)chunks);
+    sm.strips = FastDiv::make((uint32_t)strips);
+    sm.waves = (uint32_t)waves;
+    return true;
+}
+
+template <int S, int D>
+static hipError_t launch_conv_rows(const float* X, const float* W, const float* B, const float* residual,
+                                   float* Y, const WindowGeom& g, int M, int Cg, int group, int relu,
+                                   const StripMap& sm, hipStream_t stream) {
+    hipLaunchKernelGGL((conv_rows_kernel<3, 3, S, D, 8>), dim3((sm.waves + 3) / 4), dim3(256), 0, stream, X, W, B,
+                       residual, Y, g, M, Cg, M / group, relu, sm);
+    return hipGetLastError();
+}
+
 // ---- plane-tile variants ------------------------------------------------------------------
 // A workgroup owns a strip of output rows of one (image, channel) plane.  It copies the input
 // rows the strip needs into LDS with fully coalesced loads (every input element is read from
@@ -338,6 +443,12 @@ hipError_t launch_conv_direct(const float* X, const float* W, const float* B, co
     if (per_image >= (1ull << 30)) return hipErrorInvalidValue;
     int ipc; unsigned chunks, blocks;
     if (g.kH == 3 && g.kW == 3) {
+        StripMap sm;
+        if (strip_map(g, (int64_t)g.N * M, 8, sm)) {
+            if (g.sH == 1 && g.dH == 1) return launch_conv_rows<1, 1>(X, W, B, residual, Y, g, M, Cg, group, relu, sm, stream);
+            if (g.sH == 2 && g.dH == 1) return launch_conv_rows<2, 1>(X, W, B, residual, Y, g, M, Cg, group, relu, sm, stream);
+            if (g.sH == 1 && g.dH == 2) return launch_conv_rows<1, 2>(X, W, B, residual, Y, g, M, Cg, group, relu, sm, stream);
+        }
         PlaneTiling t;
         if (plane_tiling(g, (int64_t)g.N * M, 12, t)) {
             hipLaunchKernelGGL((conv_plane_kernel<3, 3>), dim3((unsigned)((int64_t)g.N * M * t.row_tiles)), dim3(256), 0,

@@ -189,6 +189,12 @@ CONV_CASES = [
     (5, 40, 15, 15, 200, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 1),     # 128x128 tiles with tails
     (4, 6, 10, 10, 6, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 6),        # depthwise
     (1, 16, 5, 5, 32, 5, 5, (0, 0, 0, 0), (1, 1), (1, 1), 1),        # output 1x1
+    # 3x3 with few channels per group (row-strip kernel: one wavefront per 8 rows x 64 columns)
+    (2, 5, 21, 150, 5, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 5),       # depthwise, 3 column chunks, ragged last strip
+    (2, 6, 23, 70, 12, 3, 3, (0, 2, 1, 0), (2, 2), (1, 1), 3),       # vertical stride 2, 2 channels per group, asymmetric pads
+    (1, 4, 19, 66, 4, 3, 3, (2, 2, 2, 2), (1, 3), (2, 2), 4),        # vertical dilation 2, horizontal stride 3
+    (3, 8, 9, 9, 8, 3, 3, (1, 1, 1, 1), (3, 1), (1, 1), 8),          # vertical stride 3: falls back to the plane kernel
+    (2, 4, 2, 2, 4, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 4),          # plane smaller than the filter
 ]
 
 
