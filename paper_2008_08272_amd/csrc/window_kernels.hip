@@ -228,6 +228,75 @@ __global__ __launch_bounds__(256) void conv_rows_kernel(const float* __restrict_
     }
 }
 
+// MaxPool on the same wavefront-per-strip scheme (vertical dilation 1).  Taps outside the image
+// never take part; taps are visited kh outer, kw inner and a later tap replaces the running
+// maximum only when strictly greater, so Indices reports the first maximum.
+template <int KH, int KW, int S, int R, bool IDX>
+__global__ __launch_bounds__(256) void maxpool_rows_kernel(const float* __restrict__ X, float* __restrict__ Y,
+                                                           int64_t* __restrict__ indices, WindowGeom g,
+                                                           StripMap sm) {
+    constexpr int ROWS_IN = (R - 1) * S + KH;
+    constexpr uint32_t OUT = 0x80000000u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * 4u + (threadIdx.x >> 6));
+    if (wave >= sm.waves) return;
+    const int lane = threadIdx.x & 63;
+    uint32_t rest, chunk, pc, strip;
+    sm.chunks.divmod(wave, rest, chunk);
+    sm.strips.divmod(rest, pc, strip);                // pc = n*C + c
+    const int oh0 = (int)strip * R;
+    const int ow = (int)chunk * 64 + lane;
+    const int ih0 = oh0 * S - g.pT;
+    const int iw0 = ow * g.sW - g.pL;
+    uint32_t voff[KW];
+    bool col_ok[KW];
+#pragma unroll
+    for (int kw = 0; kw < KW; ++kw) {
+        const int iw = iw0 + kw * g.dW;
+        col_ok[kw] = ow < g.OW && (unsigned)iw < (unsigned)g.W;
+        voff[kw] = col_ok[kw] ? (uint32_t)iw * 4u : OUT;
+    }
+    const int HW = g.H * g.W;
+    const int64_t plane_abs = (int64_t)pc * HW;
+    const __amdgpu_buffer_rsrc_t rs = plane_rsrc(X + plane_abs, HW);
+    float x[ROWS_IN][KW];
+#pragma unroll
+    for (int i = 0; i < ROWS_IN; ++i) {
+        const int ih = ih0 + i;
+        const bool row_ok = (unsigned)ih < (unsigned)g.H;              // uniform
+#pragma unroll
+        for (int kw = 0; kw < KW; ++kw)
+            x[i][kw] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                           rs, (int)(row_ok ? voff[kw] : OUT), row_ok ? ih * g.W * 4 : 0, 0));
+    }
+    if (ow >= g.OW) return;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int oh = oh0 + r;
+        if (oh >= g.OH) break;
+        float best = -__builtin_inff();
+        bool found = false;
+        int bh = 0, bw = 0;
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh) {
+            const bool row_ok = (unsigned)(ih0 + r * S + kh) < (unsigned)g.H;
+#pragma unroll
+            for (int kw = 0; kw < KW; ++kw) {
+                const float v = x[r * S + kh][kw];
+                const bool take = row_ok && col_ok[kw] && (!found || v > best);
+                best = take ? v : best;
+                if (IDX) {
+                    bh = take ? kh : bh;
+                    bw = take ? kw : bw;
+                }
+                found = found || take;
+            }
+        }
+        const int64_t o = ((int64_t)pc * g.OH + oh) * g.OW + ow;
+        Y[o] = best;
+        if (IDX) indices[o] = plane_abs + (int64_t)(ih0 + r * S + bh) * g.W + (iw0 + bw * g.dW);
+    }
+}
+
 static inline bool strip_map(const WindowGeom& g, int64_t planes, int R, StripMap& sm) {
     const int64_t chunks = (g.OW + 63) / 64, strips = (g.OH + R - 1) / R;
     const int64_t waves = planes * strips * chunks;
@@ -468,6 +537,16 @@ hipError_t launch_maxpool(const float* X, float* Y, int64_t* indices, const Wind
     if (per_image >= (1ull << 30)) return hipErrorInvalidValue;
     int ipc; unsigned chunks, blocks;
     const int shape = g.kH != g.kW ? 0 : g.kH == 3 ? 3 : g.kH == 2 ? 2 : 0;
+    StripMap sm;
+    if (shape && g.dH == 1 && g.sH == 2 && strip_map(g, (int64_t)g.N * g.C, 4, sm)) {
+        const dim3 grid((sm.waves + 3) / 4), block(256);
+#define ONNXHIP_POOL(K_)                                                                                           \
+    if (indices) hipLaunchKernelGGL((maxpool_rows_kernel<K_, K_, 2, 4, true>), grid, block, 0, stream, X, Y, indices, g, sm); \
+    else hipLaunchKernelGGL((maxpool_rows_kernel<K_, K_, 2, 4, false>), grid, block, 0, stream, X, Y, indices, g, sm);
+        if (shape == 3) { ONNXHIP_POOL(3) } else { ONNXHIP_POOL(2) }
+#undef ONNXHIP_POOL
+        return hipGetLastError();
+    }
     PlaneTiling t;
     if (shape && plane_tiling(g, (int64_t)g.N * g.C, 0, t)) {
         const dim3 grid((unsigned)((int64_t)g.N * g.C * t.row_tiles)), block(256);

@@ -295,6 +295,12 @@ POOL_CASES = [
     (1, 1, 7, 7, (2, 2), (0, 0, 0, 0), (2, 2), (1, 1), 1),
     (2, 5, 13, 10, (3, 2), (2, 0, 1, 1), (1, 2), (1, 1), 0),
     (3, 64, 56, 56, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),
+    # vertical stride 2 (row-strip kernel): several column chunks, ragged strips, ceil_mode, horizontal stride / dilation
+    (2, 3, 37, 300, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),
+    (1, 2, 30, 131, (2, 2), (0, 0, 0, 0), (2, 2), (1, 1), 1),
+    (2, 2, 19, 90, (3, 3), (1, 0, 0, 1), (2, 1), (1, 2), 1),
+    (1, 3, 9, 70, (2, 2), (1, 1, 1, 1), (2, 3), (1, 1), 0),
+    (2, 4, 3, 3, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),
 ]
 
 
