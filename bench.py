@@ -27,7 +27,7 @@ RAMP_SECONDS = 0.3
 # profiles/gemm4096_hbm_traffic.md (fetch scaled by the 2.000 a plain copy shows, write exact).  The
 # counters sit between the eight L2s and the fabric, so this is L2 fill + write-back traffic (served by
 # the Infinity Cache or HBM).  Reported only while the kernel sources are the ones that were measured.
-TRAFFIC_4096 = {"sources_sha256_16": "945c9ca8139c6826", "bytes_per_launch": (196757.0 * 2.000 + 65536.0) * 1024.0}
+TRAFFIC_4096 = {"sources_sha256_16": "9426473eb1333efc", "bytes_per_launch": (196757.0 * 2.000 + 65536.0) * 1024.0}
 KERNEL_SOURCES = ("paper_2008_08272_amd/csrc/contraction.h", "paper_2008_08272_amd/csrc/contraction.hip")
 
 
@@ -43,6 +43,56 @@ def measured_traffic():
     return TRAFFIC_4096["bytes_per_launch"] if h.hexdigest()[:16] == TRAFFIC_4096["sources_sha256_16"] else None
 
 
+def profile_kernels(torch, lib, workloads, dev, with_copy):
+    """The four launches of the counter profiles, each 3 untimed + 5 timed calls."""
+    def up(a):
+        return torch.from_numpy(a).to(dev)
+
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device=dev)
+    lib.onnx_set_workspace(ws)
+    if with_copy:                     # known-size kernel to scale the byte counters with
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    jobs = []
+    c = workloads.gemm_case(4096)
+    A, B, C = up(c["A"]), up(c["B"]), up(c["C"])
+    Y = torch.empty((4096, 4096), dtype=torch.float32, device=dev)
+    jobs.append(("gemm_4096", 2.0 * 4096 ** 3, lambda: lib.onnx_gemm(A, B, C, 1.0, 1.0, 0, 1, out=Y)))
+    g = torch.Generator(device="cpu").manual_seed(workloads.SEED_BASE)
+    X1 = torch.randn(32, 64, 56, 56, generator=g).to(dev)
+    W1 = (torch.randn(64, 64, 3, 3, generator=g) * (2.0 / 576) ** 0.5).to(dev)
+    B1 = torch.zeros(64, device=dev)
+    Y1 = torch.empty(32, 64, 56, 56, device=dev)
+    jobs.append(("conv3x3_32x64x56x56", 2.0 * Y1.numel() * 576,
+                 lambda: lib.onnx_conv(X1, W1, B1, (1, 1, 1, 1), (1, 1), (1, 1), 1, act=1, out=Y1)))
+    for name in ("dilated", "depthwise"):
+        cc = workloads.attr_sweep_case(name)
+        Xc, Wc, Bc = up(cc["X"]), up(cc["W"]), up(cc["B"])
+        yd = lib.onnx_conv_infer(Xc.shape, Wc.shape, cc["pads"], cc["strides"], cc["dilations"], cc["group"])
+        Yc = torch.empty(yd, dtype=torch.float32, device=dev)
+        flop = 2.0 * Yc.numel() * Wc.shape[1] * Wc.shape[2] * Wc.shape[3]
+        jobs.append(("conv_" + name, flop,
+                     lambda Xc=Xc, Wc=Wc, Bc=Bc, cc=cc, Yc=Yc: lib.onnx_conv(
+                         Xc, Wc, Bc, cc["pads"], cc["strides"], cc["dilations"], cc["group"], out=Yc)))
+    out = {}
+    for name, flop, fn in jobs:
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 5
+        out[name] = {"ms": round(ms, 4), "tflops": round(flop / (ms * 1e-3) / 1e12, 2)}
+    print(json.dumps({"profile_kernels": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -53,6 +103,10 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a known-size kernel against which "
                          "hardware byte counters of a profiler run can be scaled)")
+    ap.add_argument("--profile-kernels", action="store_true",
+                    help="run only the four launches whose hardware counters are summarised under profiles/ "
+                         "(Gemm 4096^3, 3x3 conv 32x64x56x56, dilated 3x3 conv, depthwise 3x3 conv), a few "
+                         "times each, print their mean times and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -70,6 +124,10 @@ def main():
 
     def up(a):
         return torch.from_numpy(a).to(dev)
+
+    if args.profile_kernels:
+        profile_kernels(torch, lib, workloads, dev, with_copy=args.copy_calibration)
+        return
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -128,7 +186,9 @@ def main():
                 "avg_launch_ms": round(k4096_ms, 4), "algorithmic_flop": flop_4096,
                 "algorithmic_bytes": bytes_4096}
 
-    def time_call(fn, iters=20, warm=3):
+    def time_call(fn, iters=50, warm=10):
+        """Mean over `iters` back-to-back calls (one event pair around the loop), plus median and
+        minimum of the same number of calls timed one by one (an event pair around each)."""
         t_ramp = time.perf_counter()              # host-side set-up let the clock drop: ramp again
         while time.perf_counter() - t_ramp < RAMP_SECONDS / 2:
             for _ in range(warm):
@@ -139,15 +199,26 @@ def main():
         for _ in range(iters):
             fn()
         e1.record()
+        pairs = []
+        for _ in range(iters):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            pairs.append((a, b))
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / iters
+        each = sorted(a.elapsed_time(b) for a, b in pairs)
+        return e0.elapsed_time(e1) / iters, each[len(each) // 2], each[0]
+
+    def timing(ms3):
+        return {"ms": round(ms3[0], 4), "ms_median": round(ms3[1], 4), "ms_min": round(ms3[2], 4)}
 
     details = {}
     per_size = {}
     for n, A, B, C, Y, _ in cases:
-        ms = time_call(lambda: lib.onnx_gemm(A, B, C, 1.0, 1.0, 0, 1, out=Y))
-        tf = 2.0 * n ** 3 / (ms * 1e-3) / 1e12
-        per_size[str(n)] = {"ms": round(ms, 4), "tflops": round(tf, 2), "frac_mfma_peak": round(tf / MFMA_FP32_PEAK_TFLOPS, 4)}
+        t3 = time_call(lambda: lib.onnx_gemm(A, B, C, 1.0, 1.0, 0, 1, out=Y))
+        tf = 2.0 * n ** 3 / (t3[0] * 1e-3) / 1e12
+        per_size[str(n)] = dict(timing(t3), tflops=round(tf, 2), frac_mfma_peak=round(tf / MFMA_FP32_PEAK_TFLOPS, 4))
     details["gemm_sweep"] = per_size
 
     if not args.no_details:
@@ -158,33 +229,53 @@ def main():
             r = GraphRunner(m, dev)
             if batch == 1:
                 r.capture()             # launch-bound: one HIP graph launch per forward pass
-                ms = time_call(r.replay, iters=50, warm=3)
+                t3 = time_call(r.replay, iters=50, warm=10)
             else:
-                ms = time_call(r.run, iters=10, warm=3)
+                t3 = time_call(r.run, iters=20, warm=5)
+            ms = t3[0]
             tf = 2.0 * st["macs"] / (ms * 1e-3) / 1e12
-            details["resnet50_b%d" % batch] = {"ms": round(ms, 4), "img_per_s": round(batch / (ms * 1e-3), 1),
-                                               "tflops": round(tf, 2),
-                                               "frac_mfma_peak": round(tf / MFMA_FP32_PEAK_TFLOPS, 4)}
+            # per-layer sum of rooflines: each node at the better of the MFMA peak and the HBM peak
+            floor_ms = sum(max(2.0 * mac / (MFMA_FP32_PEAK_TFLOPS * 1e12), nb / (HBM_PEAK_GBS * 1e9))
+                           for _, _, mac, nb in st["per_node"]) * 1e3
+            details["resnet50_b%d" % batch] = dict(timing(t3), img_per_s=round(batch / (ms * 1e-3), 1),
+                                                   tflops=round(tf, 2),
+                                                   frac_mfma_peak=round(tf / MFMA_FP32_PEAK_TFLOPS, 4),
+                                                   sum_of_layer_rooflines_ms=round(floor_ms, 4),
+                                                   frac_of_layer_rooflines=round(floor_ms / ms, 4))
+            if batch == 32:             # the stem's 3x3/2 MaxPool on its own: HBM-bound
+                x = torch.randn(32, 64, 112, 112, device=dev)
+                y = torch.empty(32, 64, 56, 56, device=dev)
+                t3 = time_call(lambda: lib.onnx_maxpool(x, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0, out=y))
+                gb = 4.0 * (x.numel() + y.numel()) / (t3[0] * 1e-3) / 1e9
+                details["maxpool_b32"] = dict(timing(t3), gbytes_per_s=round(gb, 1),
+                                              frac_hbm_peak=round(gb / HBM_PEAK_GBS, 4))
+                del x, y
             del r
         for name in workloads.ATTR_SWEEP_CONV:
             c = workloads.attr_sweep_case(name)
             X, W, Bv = up(c["X"]), up(c["W"]), up(c["B"])
             yd = lib.onnx_conv_infer(X.shape, W.shape, c["pads"], c["strides"], c["dilations"], c["group"])
             Y = torch.empty(yd, dtype=torch.float32, device=dev)
-            ms = time_call(lambda: lib.onnx_conv(X, W, Bv, c["pads"], c["strides"], c["dilations"], c["group"], out=Y))
+            t3 = time_call(lambda: lib.onnx_conv(X, W, Bv, c["pads"], c["strides"], c["dilations"], c["group"], out=Y))
+            ms = t3[0]
             macs = Y.numel() * W.shape[1] * W.shape[2] * W.shape[3]
             byts = 4.0 * (X.numel() + W.numel() + Y.numel())
-            details["conv_" + name] = {"ms": round(ms, 4), "tflops": round(2.0 * macs / (ms * 1e-3) / 1e12, 3),
-                                       "gbytes_per_s": round(byts / (ms * 1e-3) / 1e9, 1)}
+            details["conv_" + name] = dict(timing(t3), tflops=round(2.0 * macs / (ms * 1e-3) / 1e12, 3),
+                                           frac_mfma_peak=round(2.0 * macs / (ms * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS, 4),
+                                           gbytes_per_s=round(byts / (ms * 1e-3) / 1e9, 1),
+                                           frac_hbm_peak=round(byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
         for name in workloads.ATTR_SWEEP_MATMUL:
             c = workloads.attr_sweep_case(name)
             A, B = up(c["A"]), up(c["B"])
             Y = torch.empty(lib.onnx_matmul_infer(A.shape, B.shape), dtype=torch.float32, device=dev)
-            ms = time_call(lambda: lib.onnx_matmul(A, B, out=Y))
+            t3 = time_call(lambda: lib.onnx_matmul(A, B, out=Y))
+            ms = t3[0]
             macs = Y.numel() * A.shape[-1]
             byts = 4.0 * (A.numel() + B.numel() + Y.numel())
-            details[name] = {"ms": round(ms, 4), "tflops": round(2.0 * macs / (ms * 1e-3) / 1e12, 3),
-                             "gbytes_per_s": round(byts / (ms * 1e-3) / 1e9, 1)}
+            details[name] = dict(timing(t3), tflops=round(2.0 * macs / (ms * 1e-3) / 1e12, 3),
+                                 frac_mfma_peak=round(2.0 * macs / (ms * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS, 4),
+                                 gbytes_per_s=round(byts / (ms * 1e-3) / 1e9, 1),
+                                 frac_hbm_peak=round(byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
 
     # ---- CPU oracle beside it (a reported baseline, not the target) ---------------------------
     cpu = None

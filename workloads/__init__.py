@@ -262,5 +262,11 @@ def graph_stats(model):
         else:
             raise ValueError(op)
         macs += mac
-        per_node.append((nd["y"], op, mac))
+        # compulsory bytes of the node: every operand read once, the result written once
+        operands = [nd.get(k) for k in ("x", "w", "b", "residual", "a", "c")]
+        if op == "gemm":
+            operands = [nd["a"], nd["b"], nd.get("c")]
+        nbytes = 0 if op == "reshape" else 4 * (sum(int(np.prod(shapes[k])) for k in operands if k) +
+                                                int(np.prod(shapes[nd["y"]])))
+        per_node.append((nd["y"], op, mac, nbytes))
     return dict(params=params, macs=macs, per_node=per_node, shapes=shapes)
