@@ -1,5 +1,10 @@
 """Runs a workload graph with the CPU oracle (test infrastructure only).
 
+Graphs may be in the fused form the GPU runner executes or in the operator-by-operator form
+an exporter writes (BatchNormalization, Relu, Add, Identity, MatMul as nodes of their own: the
+inputs of the graph-level passes of Section 3.4 of the paper); the latter are evaluated by
+their definitions, so a rewritten graph can be checked against the graph it came from.
+
 Each node is evaluated by the oracle in double precision from fp32 inputs; the
 result is rounded to fp32 once, when it is handed to the next node, as a chain
 of fp32 operators would store it.  ``run`` returns every fp32 activation and the
@@ -8,6 +13,15 @@ un-rounded double result of each node, so a test can compare any layer.
 import numpy as np
 
 from . import avgpool, conv, gemm, matmul, maxpool
+
+
+def batchnorm(x, scale, bias, mean, var, eps):
+    """ONNX BatchNormalization at inference, per channel c of an N x C x ... tensor, in double:
+    y = (x - mean[c]) / sqrt(var[c] + eps) * scale[c] + bias[c]."""
+    x = np.asarray(x, dtype=np.float64)
+    shp = (1, -1) + (1,) * (x.ndim - 2)
+    f = lambda v: np.asarray(v, dtype=np.float64).reshape(shp)
+    return (x - f(mean)) / np.sqrt(f(var) + float(eps)) * f(scale) + f(bias)
 
 
 def run(model, keep=None):
@@ -36,6 +50,15 @@ def run(model, keep=None):
                      nd["transB"], relu=nd["relu"])
         elif op == "matmul":
             y = matmul(env[nd["a"]], env[nd["b"]])
+        elif op == "batchnorm":
+            y = batchnorm(env[nd["x"]], env[nd["scale"]], env[nd["bias"]], env[nd["mean"]],
+                          env[nd["var"]], nd["eps"])
+        elif op == "relu":
+            y = np.maximum(np.asarray(env[nd["x"]], dtype=np.float64), 0.0)
+        elif op == "add":
+            y = np.asarray(env[nd["a"]], dtype=np.float64) + np.asarray(env[nd["b"]], dtype=np.float64)
+        elif op == "identity":
+            y = np.asarray(env[nd["x"]], dtype=np.float64)
         else:
             raise ValueError("unknown node op %r" % (op,))
         if keep is None or nd["y"] in keep or nd["y"] == model["output"]:

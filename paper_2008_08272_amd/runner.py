@@ -17,6 +17,12 @@ class GraphRunner:
     def __init__(self, model, device="cuda:0", workspace_bytes=64 << 20):
         self.device = torch.device(device)
         self.model = model
+        for nd in model["graph"]:                  # refuse before anything is allocated or registered
+            if nd["op"] in ("batchnorm", "relu", "add", "identity"):
+                raise NotImplementedError(
+                    "node %r (%s) has no kernel of its own: run paper_2008_08272_amd.passes.optimize on the "
+                    "graph first; it folds such nodes into the convolution or Gemm that feeds them"
+                    % (nd["y"], nd["op"]))
         # scratch the library may use to split the K range of products with few output tiles
         self.workspace = None
         if workspace_bytes:

@@ -526,3 +526,29 @@ def test_resnet50_batch32_chain_sampled_images(lib):
         for name, ref in exact.items():
             e = rel_err(r.t[name][n:n + 1].cpu().numpy(), ref)
             assert e <= REL_TOL, (n, name, e)
+
+
+# ------------------------------------------------------------------------------ graph passes
+
+def test_unfused_graphs_through_the_passes(lib):
+    """Operator-by-operator graphs (BatchNormalization, Relu, Add, Identity, MatMul + Add as nodes
+    of their own) go through the graph passes and then through the runner; the reference is the
+    oracle evaluating the ORIGINAL graph by the operators' definitions."""
+    announce("passes + runner")
+    from oracle import chain
+    from paper_2008_08272_amd import passes
+    from paper_2008_08272_amd.runner import GraphRunner
+    for raw in (workloads.small_cnn_unfused(), workloads.resnet50_unfused(2, image=96)):
+        with pytest.raises(NotImplementedError):
+            GraphRunner(raw)                     # no kernel for a bare Relu / BatchNorm: fails loudly
+        opt = passes.optimize(raw)
+        _, exact = chain.run(raw)
+        r, got = _run_chain(lib, opt)
+        assert got.shape == exact[raw["output"]].shape
+        assert rel_err(got, exact[raw["output"]]) <= REL_TOL, raw["name"]
+        # every intermediate tensor that survives the rewrite matches the original graph's
+        worst = 0.0
+        for nd in opt["graph"]:
+            if nd["op"] != "reshape" and nd["y"] in exact:
+                worst = max(worst, rel_err(r.t[nd["y"]].cpu().numpy(), exact[nd["y"]]))
+        assert worst <= REL_TOL

@@ -65,6 +65,28 @@ def reshape_node(x, y, shape):
     return dict(op="reshape", x=x, y=y, shape=tuple(shape))
 
 
+# Nodes that only occur in graphs as an exporter would write them, before any graph-level pass
+# (Section 3.4 of the paper: operators are fused and constants folded by rewriting the graph).
+def batchnorm_node(x, scale, bias, mean, var, y, eps):
+    return dict(op="batchnorm", x=x, scale=scale, bias=bias, mean=mean, var=var, y=y, eps=float(eps))
+
+
+def relu_node(x, y):
+    return dict(op="relu", x=x, y=y)
+
+
+def add_node(a, b, y):
+    return dict(op="add", a=a, b=b, y=y)
+
+
+def identity_node(x, y):
+    return dict(op="identity", x=x, y=y)
+
+
+def matmul_node(a, b, y):
+    return dict(op="matmul", a=a, b=b, y=y)
+
+
 # --------------------------------------------------------------------------- config 1
 
 def small_cnn(seed=SEED_BASE + 1):
@@ -89,6 +111,27 @@ def small_cnn(seed=SEED_BASE + 1):
         gemm_node("flat", "wg", "bg", "logits"),
     ]
     return dict(name="small_cnn", inputs=inputs, weights=weights, graph=graph, output="logits")
+
+
+def small_cnn_unfused(seed=SEED_BASE + 1):
+    """The same network and tensors as ``small_cnn`` written operator by operator: Relu as
+    nodes of their own, the classifier as MatMul followed by Add (the pair the paper's
+    MatMul+Add -> Gemm rewrite targets, Section 3.4), and an Identity on the input."""
+    m = small_cnn(seed)
+    graph = [
+        identity_node("x", "x_id"),
+        conv_node("x_id", "w1", "b1", "c1_lin", pads=(2, 2, 2, 2)),
+        relu_node("c1_lin", "c1"),
+        maxpool_node("c1", "p1", (2, 2), strides=(2, 2)),
+        conv_node("p1", "w2", "b2", "c2_lin", pads=(2, 2, 2, 2)),
+        relu_node("c2_lin", "c2"),
+        maxpool_node("c2", "p2", (3, 3), strides=(3, 3)),
+        reshape_node("p2", "flat", (1, 256)),
+        matmul_node("flat", "wg", "mm"),
+        add_node("mm", "bg", "logits"),
+    ]
+    return dict(name="small_cnn_unfused", inputs=m["inputs"], weights=m["weights"], graph=graph,
+                output="logits")
 
 
 # --------------------------------------------------------------------------- config 2
@@ -179,6 +222,40 @@ def resnet50(batch=1, seed=None, keep_raw=False, image=224):
     if keep_raw:
         out["raw"] = raws
     return out
+
+
+def resnet50_unfused(batch=1, seed=None, image=224):
+    """The network of ``resnet50`` as an exporter writes it: every convolution without bias,
+    followed by a BatchNormalization node (fp32 scale, bias, mean, var; eps 1e-5), Relu and the
+    residual Add as nodes of their own.  Same random draws as ``resnet50``; the BatchNorm
+    parameters are stored in fp32, as a model file would hold them."""
+    m = resnet50(batch, seed, keep_raw=True, image=image)
+    weights, graph = {}, []
+    for nd in m["graph"]:
+        if nd["op"] != "conv":
+            graph.append(dict(nd))
+            for k in ("b", "c"):
+                if nd["op"] == "gemm" and nd.get(k):
+                    weights[nd[k]] = m["weights"][nd[k]]
+            continue
+        name, raw = nd["y"], m["raw"][nd["y"]]
+        weights[name + "_w"] = raw["w"]
+        for k in ("gamma", "beta", "mean", "var"):
+            weights[name + "_" + k] = np.asarray(raw[k], dtype=np.float32)
+        graph.append(conv_node(nd["x"], name + "_w", None, name + "_conv", pads=nd["pads"],
+                               strides=nd["strides"], dilations=nd["dilations"], group=nd["group"]))
+        bn_out = name if not (nd["residual"] or nd["relu"]) else name + "_bn"
+        graph.append(batchnorm_node(name + "_conv", name + "_gamma", name + "_beta", name + "_mean",
+                                    name + "_var", bn_out, BN_EPS))
+        cur = bn_out
+        if nd["residual"]:
+            nxt = name if not nd["relu"] else name + "_sum"
+            graph.append(add_node(cur, nd["residual"], nxt))
+            cur = nxt
+        if nd["relu"]:
+            graph.append(relu_node(cur, name))
+    return dict(name="resnet50_unfused_b%d" % batch, inputs=m["inputs"], weights=weights, graph=graph,
+                output=m["output"])
 
 
 # --------------------------------------------------------------------------- config 5
