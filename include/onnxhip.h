@@ -145,6 +145,63 @@ onnx_status onnx_avgpool(const float* X, const int64_t x_dims[4], const int64_t*
                          const int64_t* pads, const int64_t* strides, int ceil_mode,
                          int count_include_pad, float* Y, const int64_t y_dims[4], void* stream);
 
+/*
+ * Element-wise, reduction and softmax operators: the operators the paper walks through next
+ * to the contractions.  Same conventions as above (device tensors, host dims, caller-owned
+ * memory, no overlap of output and inputs, validation before any launch, zero-sized outputs
+ * return ONNX_OK without launching).  Tensors of up to 2^31-1 elements (ONNX_ERR_UNSUPPORTED
+ * beyond), ranks 0..ONNX_MAX_RANK.
+ */
+
+/* Shape of a numpy-style (ONNX "multidirectional") broadcast of two shapes: aligned at the
+ * last axis, each pair of extents equal or one of them 1.  Pure host function. */
+onnx_status onnx_broadcast_infer(const int64_t* a_dims, int a_rank, const int64_t* b_dims, int b_rank,
+                                 int64_t* y_dims, int* y_rank);
+
+/*
+ * ONNX Add (the running example of Section 3: two 3x4x5 tensors added element by element):
+ * Y = A + B with multidirectional broadcasting; y_dims/y_rank must be the broadcast shape.
+ */
+onnx_status onnx_add(const float* A, const int64_t* a_dims, int a_rank, const float* B,
+                     const int64_t* b_dims, int b_rank, float* Y, const int64_t* y_dims, int y_rank,
+                     void* stream);
+
+/* ONNX Relu, y = max(0, x), over `count` elements. */
+onnx_status onnx_relu(const float* X, int64_t count, float* Y, void* stream);
+
+/* ONNX LeakyRelu (its operator definition is the example of Section 3.1): y = x for x >= 0,
+ * alpha * x otherwise; the ONNX default of alpha is 0.01. */
+onnx_status onnx_leakyrelu(const float* X, int64_t count, float alpha, float* Y, void* stream);
+
+/* ONNX Abs, y = |x| (with ReduceSum it makes up ReduceL1: the decomposition of Section 3.4). */
+onnx_status onnx_abs(const float* X, int64_t count, float* Y, void* stream);
+
+/* Output shape of a reduction over `axes` (negative values count from the last axis; naxes = 0
+ * reduces every axis; an axis out of range or listed twice is ONNX_ERR_ATTR): reduced axes keep
+ * extent 1 when keepdims != 0 and disappear otherwise.  Pure host function. */
+onnx_status onnx_reduce_infer(const int64_t* x_dims, int rank, const int64_t* axes, int naxes,
+                              int keepdims, int64_t* y_dims, int* y_rank);
+
+/*
+ * ONNX ReduceSum (Section 3.4): Y = sum of X over the listed axes, shape as onnx_reduce_infer.
+ * Sums are formed in fp32 (64 partial sums per output where the innermost axis is reduced, one
+ * running sum otherwise).  With a workspace set (onnx_set_workspace), a long sum into few
+ * outputs is cut into chunks that run in parallel and are added by a second launch.
+ */
+onnx_status onnx_reducesum(const float* X, const int64_t* x_dims, int rank, const int64_t* axes,
+                           int naxes, int keepdims, float* Y, const int64_t* y_dims, int y_rank,
+                           void* stream);
+
+/*
+ * ONNX Softmax along one axis (negative values count from the last axis):
+ * y_i = exp(x_i - m) / sum_j exp(x_j - m) with m the maximum along the axis.  (The paper leaves
+ * operator semantics to the ONNX standard, Section 3.1; older operator sets flatten the tensor
+ * to 2-D at `axis` instead: for the classifier's [N, classes] logits with axis 1 or -1 both
+ * readings coincide.)  Rank 1..ONNX_MAX_RANK.
+ */
+onnx_status onnx_softmax(const float* X, const int64_t* x_dims, int rank, int axis, float* Y,
+                         void* stream);
+
 #ifdef __cplusplus
 }
 #endif

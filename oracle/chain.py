@@ -13,6 +13,7 @@ un-rounded double result of each node, so a test can compare any layer.
 import numpy as np
 
 from . import avgpool, conv, gemm, matmul, maxpool
+from . import elementwise as ew
 
 
 def batchnorm(x, scale, bias, mean, var, eps):
@@ -54,9 +55,19 @@ def run(model, keep=None):
             y = batchnorm(env[nd["x"]], env[nd["scale"]], env[nd["bias"]], env[nd["mean"]],
                           env[nd["var"]], nd["eps"])
         elif op == "relu":
-            y = np.maximum(np.asarray(env[nd["x"]], dtype=np.float64), 0.0)
+            y = ew.relu(env[nd["x"]])
         elif op == "add":
-            y = np.asarray(env[nd["a"]], dtype=np.float64) + np.asarray(env[nd["b"]], dtype=np.float64)
+            y = ew.add(env[nd["a"]], env[nd["b"]])
+        elif op == "leakyrelu":
+            y = ew.leakyrelu(env[nd["x"]], nd["alpha"])
+        elif op == "abs":
+            y = ew.absolute(env[nd["x"]])
+        elif op == "reducesum":
+            y = ew.reducesum(env[nd["x"]], nd["axes"], nd["keepdims"])
+        elif op == "reducel1":
+            y = ew.reducel1(env[nd["x"]], nd["axes"], nd["keepdims"])
+        elif op == "softmax":
+            y = ew.softmax(env[nd["x"]], nd["axis"])
         elif op == "identity":
             y = np.asarray(env[nd["x"]], dtype=np.float64)
         else:

@@ -48,6 +48,18 @@ for _f in (_lib.onnx_conv_infer, _lib.onnx_pool_infer, _lib.onnx_matmul_infer, _
            _lib.onnx_gemm, _lib.onnx_matmul, _lib.onnx_maxpool, _lib.onnx_avgpool):
     _f.restype = _ci
 
+_ip = ctypes.POINTER(_ci)
+_lib.onnx_broadcast_infer.argtypes = [_i64p, _ci, _i64p, _ci, _i64p, _ip]
+_lib.onnx_reduce_infer.argtypes = [_i64p, _ci, _i64p, _ci, _ci, _i64p, _ip]
+_lib.onnx_add.argtypes = [_vp, _i64p, _ci, _vp, _i64p, _ci, _vp, _i64p, _ci, _vp]
+_lib.onnx_relu.argtypes = [_vp, _c64, _vp, _vp]
+_lib.onnx_leakyrelu.argtypes = [_vp, _c64, _cf, _vp, _vp]
+_lib.onnx_abs.argtypes = [_vp, _c64, _vp, _vp]
+_lib.onnx_reducesum.argtypes = [_vp, _i64p, _ci, _i64p, _ci, _ci, _vp, _i64p, _ci, _vp]
+_lib.onnx_softmax.argtypes = [_vp, _i64p, _ci, _ci, _vp, _vp]
+for _f in (_lib.onnx_broadcast_infer, _lib.onnx_reduce_infer, _lib.onnx_add, _lib.onnx_relu, _lib.onnx_leakyrelu,
+           _lib.onnx_abs, _lib.onnx_reducesum, _lib.onnx_softmax):
+    _f.restype = _ci
 
 _lib.onnx_set_workspace.argtypes = [_vp, ctypes.c_size_t]
 _lib.onnx_set_workspace.restype = _ci
@@ -186,4 +198,68 @@ def onnx_avgpool(X, kernel=None, pads=(0, 0, 0, 0), strides=(1, 1), ceil_mode=0,
     Y = torch.empty(yd, dtype=torch.float32, device=X.device) if out is None else _dev(out, "out")
     _check(_lib.onnx_avgpool(_ptr(X), dims(X.shape), kp, pp, sp, int(ceil_mode), int(count_include_pad),
                              _ptr(Y), dims(Y.shape), _stream(stream)))
+    return Y
+
+
+def onnx_broadcast_infer(a_dims, b_dims):
+    y = (ctypes.c_int64 * 16)()
+    r = ctypes.c_int(0)
+    _check(_lib.onnx_broadcast_infer(dims(a_dims), len(a_dims), dims(b_dims), len(b_dims), y, ctypes.byref(r)))
+    return tuple(y[i] for i in range(r.value))
+
+
+def onnx_reduce_infer(x_dims, axes=None, keepdims=1):
+    axes = [] if axes is None else list(axes)
+    y = (ctypes.c_int64 * 16)()
+    r = ctypes.c_int(0)
+    _check(_lib.onnx_reduce_infer(dims(x_dims), len(x_dims), dims(axes), len(axes), int(keepdims), y, ctypes.byref(r)))
+    return tuple(y[i] for i in range(r.value))
+
+
+def _out(out, shape, like):
+    return torch.empty(tuple(shape), dtype=torch.float32, device=like.device) if out is None else _dev(out, "out")
+
+
+def onnx_add(A, B, out=None, stream=None):
+    A, B = _dev(A, "A"), _dev(B, "B")
+    Y = _out(out, onnx_broadcast_infer(A.shape, B.shape), A)
+    _check(_lib.onnx_add(_ptr(A), dims(A.shape), A.dim(), _ptr(B), dims(B.shape), B.dim(), _ptr(Y), dims(Y.shape),
+                         Y.dim(), _stream(stream)))
+    return Y
+
+
+def onnx_relu(X, out=None, stream=None):
+    X = _dev(X, "X")
+    Y = _out(out, X.shape, X)
+    _check(_lib.onnx_relu(_ptr(X), X.numel(), _ptr(Y), _stream(stream)))
+    return Y
+
+
+def onnx_leakyrelu(X, alpha=0.01, out=None, stream=None):
+    X = _dev(X, "X")
+    Y = _out(out, X.shape, X)
+    _check(_lib.onnx_leakyrelu(_ptr(X), X.numel(), float(alpha), _ptr(Y), _stream(stream)))
+    return Y
+
+
+def onnx_abs(X, out=None, stream=None):
+    X = _dev(X, "X")
+    Y = _out(out, X.shape, X)
+    _check(_lib.onnx_abs(_ptr(X), X.numel(), _ptr(Y), _stream(stream)))
+    return Y
+
+
+def onnx_reducesum(X, axes=None, keepdims=1, out=None, stream=None):
+    X = _dev(X, "X")
+    axes = [] if axes is None else list(axes)
+    Y = _out(out, onnx_reduce_infer(X.shape, axes, keepdims), X)
+    _check(_lib.onnx_reducesum(_ptr(X), dims(X.shape), X.dim(), dims(axes), len(axes), int(keepdims), _ptr(Y),
+                               dims(Y.shape), Y.dim(), _stream(stream)))
+    return Y
+
+
+def onnx_softmax(X, axis=-1, out=None, stream=None):
+    X = _dev(X, "X")
+    Y = _out(out, X.shape, X)
+    _check(_lib.onnx_softmax(_ptr(X), dims(X.shape), X.dim(), int(axis), _ptr(Y), _stream(stream)))
     return Y

@@ -85,6 +85,10 @@ onnx_status device_status(hipError_t e, const char* what) {
 
 namespace onnxhip {
 const Workspace& workspace() { return g_ws; }
+int report_error(int status, const char* message) {
+    snprintf(g_err, sizeof(g_err), "%s", message);
+    return status;
+}
 }  // namespace onnxhip
 
 extern "C" {

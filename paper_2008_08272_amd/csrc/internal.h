@@ -23,6 +23,10 @@ struct Workspace {
 };
 const Workspace& workspace();
 
+// Stores `message` as the calling thread's last error (what onnx_last_error returns) and hands
+// `status` back; for the entry points that live outside the main C-ABI translation unit.
+int report_error(int status, const char* message);
+
 // How many ways to split the K walk of `tiles` workgroup tiles of `tile_elems` outputs and `nk`
 // K steps each, so that the 256 CUs are evenly loaded; 1 when the workspace cannot hold it.
 // `overhead` is a workgroup's fixed cost (prologue, epilogue) in units of one K step.

@@ -7,6 +7,7 @@ runner's graph description (a list of node dicts over named tensors), so that wh
 GPU is one library call per fused operator:
 
     infer_shapes          extents of every tensor (the library's own shape-inference entry points)
+    decompose_reducel1    ReduceL1(x) -> ReduceSum(Abs(x))
     eliminate_identity    Identity(x) -> x
     fold_batchnorm        Conv with constant filters + BatchNormalization with constant
                           parameters -> Conv with rescaled filters and a bias
@@ -14,11 +15,11 @@ GPU is one library call per fused operator:
     fuse_epilogue         Conv/Gemm [+ Add(residual)] [+ Relu] -> one node with the epilogue flags
 
 Every pass takes a model dict and returns a new one; none touches the GPU.  ``optimize`` runs
-them all.  Nodes the runner cannot execute (a Relu or Add that found no producer to fuse
-into, a BatchNormalization on a non-constant input) are left in place and make the runner
-raise: there is no slow path.
+them all.  A Relu or Add that found no producer to fuse into stays a node of its own and runs
+through the library's element-wise kernels; nodes the runner cannot execute (a
+BatchNormalization on a non-constant input, a ReduceL1 that was not decomposed, an Identity)
+make it raise: there is no slow path.
 """
-import copy
 
 import numpy as np
 
@@ -36,6 +37,11 @@ _INPUTS = {
     "relu": ("x",),
     "add": ("a", "b"),
     "identity": ("x",),
+    "leakyrelu": ("x",),
+    "abs": ("x",),
+    "reducesum": ("x",),
+    "reducel1": ("x",),
+    "softmax": ("x",),
 }
 
 
@@ -113,10 +119,12 @@ def infer_shapes(model):
             y = (m, n)
         elif op == "matmul":
             y = B.onnx_matmul_infer(sh[nd["a"]], sh[nd["b"]])
-        elif op in ("batchnorm", "relu", "identity"):
+        elif op in ("batchnorm", "relu", "identity", "leakyrelu", "abs", "softmax"):
             y = sh[nd["x"]]
+        elif op in ("reducesum", "reducel1"):
+            y = B.onnx_reduce_infer(sh[nd["x"]], nd["axes"], nd["keepdims"])
         elif op == "add":
-            y = tuple(np.broadcast_shapes(sh[nd["a"]], sh[nd["b"]]))
+            y = B.onnx_broadcast_infer(sh[nd["a"]], sh[nd["b"]])
         else:
             raise ValueError("unknown node op %r" % (op,))
         sh[nd["y"]] = tuple(int(d) for d in y)
@@ -124,6 +132,23 @@ def infer_shapes(model):
 
 
 # ----------------------------------------------------------------------------- rewrites
+
+def decompose_reducel1(model):
+    """ReduceL1(x, axes, keepdims) -> ReduceSum(Abs(x), axes, keepdims): the operator
+    decomposition the paper gives as its first example of a rewriting pass (Section 3.4), so
+    that only ReduceSum and Abs need kernels."""
+    out = _clone(model)
+    graph = []
+    for nd in out["graph"]:
+        if nd["op"] == "reducel1":
+            tmp = nd["y"] + "_abs"
+            graph.append(dict(op="abs", x=nd["x"], y=tmp))
+            graph.append(dict(op="reducesum", x=tmp, y=nd["y"], axes=nd["axes"], keepdims=nd["keepdims"]))
+        else:
+            graph.append(nd)
+    out["graph"] = graph
+    return out
+
 
 def eliminate_identity(model):
     out = _clone(model)
@@ -235,7 +260,8 @@ def fuse_epilogue(model):
 
 def optimize(model):
     """All passes, in the order that lets each see the patterns the previous one exposed."""
-    m = eliminate_identity(model)
+    m = decompose_reducel1(model)
+    m = eliminate_identity(m)
     m = fold_batchnorm(m)
     m = matmul_add_to_gemm(m)
     m = fuse_epilogue(m)

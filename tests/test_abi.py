@@ -127,3 +127,50 @@ def test_fast_division_constants():
         ns = np.concatenate([rng.integers(0, 2 ** 31, 2000), [0, 1, d - 1, d, d + 1, 2 ** 31 - 1]]).astype(np.uint64)
         q = (ns >> np.uint64(s)) if pow2 else (((ns * np.uint64(m)) >> np.uint64(32)) >> np.uint64(s))
         assert np.array_equal(q, ns // np.uint64(d)), d
+
+
+def test_broadcast_and_reduce_inference(B):
+    rng = np.random.default_rng(2)
+    for _ in range(200):
+        r = int(rng.integers(0, 6))
+        y = [int(rng.integers(1, 5)) for _ in range(r)]
+        a = [d if rng.random() < 0.6 else 1 for d in y][int(rng.integers(0, r + 1)):]
+        b = [d if rng.random() < 0.6 else 1 for d in y][int(rng.integers(0, r + 1)):]
+        assert B.onnx_broadcast_infer(a, b) == np.broadcast_shapes(tuple(a), tuple(b))
+        x = [int(rng.integers(1, 5)) for _ in range(max(r, 1))]
+        k = int(rng.integers(0, len(x) + 1))
+        axes = [int(t) for t in rng.permutation(len(x))[:k]]
+        axes = [t - len(x) if rng.random() < 0.3 else t for t in axes]
+        for keep in (0, 1):
+            want = np.sum(np.zeros(x), axis=tuple(axes) if axes else None, keepdims=bool(keep)).shape
+            assert B.onnx_reduce_infer(x, axes, keep) == want
+    with pytest.raises(B.OnnxHipError) as e:
+        B.onnx_broadcast_infer((2, 3), (4,))
+    assert e.value.status == 3
+    for bad in ([2], [-3], [0, 0], [1, -1]):
+        with pytest.raises(B.OnnxHipError) as e:
+            B.onnx_reduce_infer((3, 4), bad, 1)
+        assert e.value.status == 4
+
+
+def test_elementwise_errors_are_reported_before_touching_the_device(B):
+    lib = B.raw()
+    d = B.dims
+    fake = ctypes.c_void_p(1 << 20)
+    assert lib.onnx_relu(None, 16, fake, None) == 1
+    assert lib.onnx_relu(fake, 16, fake, None) == 6                      # Y overlaps X
+    assert lib.onnx_abs(fake, -1, fake, None) == 3
+    assert lib.onnx_leakyrelu(None, 0, 0.1, None, None) == 0             # nothing to do
+    other = ctypes.c_void_p(1 << 24)
+    assert lib.onnx_add(fake, d((2, 3)), 2, fake, d((3,)), 1, other, d((2, 4)), 2, None) == 3
+    assert lib.onnx_add(fake, d((2, 3)), 2, fake, d((3,)), 1, other, d((2, 3)), 1, None) == 3
+    assert lib.onnx_add(fake, d((2, 3)), 2, fake, d((4,)), 1, other, d((2, 3)), 2, None) == 3
+    assert lib.onnx_add(fake, d((2, 3)), 2, None, d((3,)), 1, other, d((2, 3)), 2, None) == 1
+    assert lib.onnx_add(fake, d((2, 0)), 2, None, d((1,)), 1, None, d((2, 0)), 2, None) == 0
+    assert lib.onnx_reducesum(fake, d((2, 3)), 2, d((1,)), 1, 1, other, d((2,)), 1, None) == 3
+    assert lib.onnx_reducesum(fake, d((2, 3)), 2, d((5,)), 1, 1, other, d((2, 1)), 2, None) == 4
+    assert lib.onnx_reducesum(fake, d((2, 3)), 9, d((1,)), 1, 1, other, d((2, 1)), 2, None) == 2
+    assert lib.onnx_softmax(fake, d((2, 3)), 2, 2, other, None) == 4
+    assert lib.onnx_softmax(fake, d((2, 3)), 0, 0, other, None) == 2
+    assert lib.onnx_softmax(fake, d((2, 3)), 2, 1, fake, None) == 6
+    assert "softmax" in B.onnx_last_error()

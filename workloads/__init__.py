@@ -87,6 +87,24 @@ def matmul_node(a, b, y):
     return dict(op="matmul", a=a, b=b, y=y)
 
 
+def leakyrelu_node(x, y, alpha=0.01):
+    return dict(op="leakyrelu", x=x, y=y, alpha=float(alpha))
+
+
+def abs_node(x, y):
+    return dict(op="abs", x=x, y=y)
+
+
+def reduce_node(kind, x, y, axes=None, keepdims=1):
+    """kind: "reducesum" or "reducel1" (the latter exists only before the decomposition pass)."""
+    return dict(op=kind, x=x, y=y, axes=None if axes is None else tuple(int(a) for a in axes),
+                keepdims=int(keepdims))
+
+
+def softmax_node(x, y, axis=-1):
+    return dict(op="softmax", x=x, y=y, axis=int(axis))
+
+
 # --------------------------------------------------------------------------- config 1
 
 def small_cnn(seed=SEED_BASE + 1):
@@ -132,6 +150,26 @@ def small_cnn_unfused(seed=SEED_BASE + 1):
     ]
     return dict(name="small_cnn_unfused", inputs=m["inputs"], weights=m["weights"], graph=graph,
                 output="logits")
+
+
+def classifier_head(batch=32, classes=1000, features=2048, seed=SEED_BASE + 6):
+    """A classifier tail written operator by operator, exercising the element-wise, reduction
+    and softmax operators: features -> LeakyRelu -> MatMul + Add (-> Gemm) -> Softmax, plus the L1
+    norm of the logits per image (ReduceL1, which the decomposition pass turns into Abs +
+    ReduceSum) and the column sums of the probabilities."""
+    r = _rng(seed, 0)
+    inputs = {"feat": _normal(r, (batch, features), 1.0)}
+    weights = {"w": _normal(r, (features, classes), np.sqrt(1.0 / features)),
+               "b": _normal(r, (classes,), 0.1)}
+    graph = [
+        leakyrelu_node("feat", "act", 0.1),
+        matmul_node("act", "w", "mm"),
+        add_node("mm", "b", "logits"),
+        softmax_node("logits", "prob", axis=1),
+        reduce_node("reducel1", "logits", "l1", axes=(1,), keepdims=0),
+        reduce_node("reducesum", "prob", "colsum", axes=(0,), keepdims=1),
+    ]
+    return dict(name="classifier_head", inputs=inputs, weights=weights, graph=graph, output="prob")
 
 
 # --------------------------------------------------------------------------- config 2
