@@ -242,14 +242,6 @@ def main():
                                                    frac_mfma_peak=round(tf / MFMA_FP32_PEAK_TFLOPS, 4),
                                                    sum_of_layer_rooflines_ms=round(floor_ms, 4),
                                                    frac_of_layer_rooflines=round(floor_ms / ms, 4))
-            if batch == 32:             # the stem's 3x3/2 MaxPool on its own: HBM-bound
-                x = torch.randn(32, 64, 112, 112, device=dev)
-                y = torch.empty(32, 64, 56, 56, device=dev)
-                t3 = time_call(lambda: lib.onnx_maxpool(x, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0, out=y))
-                gb = 4.0 * (x.numel() + y.numel()) / (t3[0] * 1e-3) / 1e9
-                details["maxpool_b32"] = dict(timing(t3), gbytes_per_s=round(gb, 1),
-                                              frac_hbm_peak=round(gb / HBM_PEAK_GBS, 4))
-                del x, y
             del r
         for name in workloads.ATTR_SWEEP_CONV:
             c = workloads.attr_sweep_case(name)
@@ -276,6 +268,78 @@ def main():
                                  frac_mfma_peak=round(2.0 * macs / (ms * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS, 4),
                                  gbytes_per_s=round(byts / (ms * 1e-3) / 1e9, 1),
                                  frac_hbm_peak=round(byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
+
+    if not args.no_details:
+        # Element-wise / reduction / softmax operators and the two HBM-bound window kernels, quoted
+        # against the 8 TB/s HBM peak.  Each call of a case works on the next of several buffer sets
+        # (at least 4, together above 600 MB) so that the 256 MB Infinity Cache cannot serve them.
+        def hbm(name, nbytes, make):
+            nsets = max(4, int(600e6 // nbytes) + 1)
+            sets = [make() for _ in range(nsets)]
+            state = [0]
+
+            def fn():
+                sets[state[0] % nsets]()
+                state[0] += 1
+            t3 = time_call(fn)
+            gb = nbytes / (t3[0] * 1e-3) / 1e9
+            details[name] = dict(timing(t3), gbytes_per_s=round(gb, 1), frac_hbm_peak=round(gb / HBM_PEAK_GBS, 4),
+                                 buffer_sets=nsets)
+            del sets
+
+        shape = (32, 256, 56, 56)                                 # 102.8 MB, ResNet-50's largest activation
+        nb = 4.0 * 32 * 256 * 56 * 56
+
+        def rnd(*sh):
+            return torch.randn(*sh, device=dev)
+
+        def mk_add():
+            a, b, y = rnd(*shape), rnd(*shape), torch.empty(shape, device=dev)
+            return lambda: lib.onnx_add(a, b, out=y)
+
+        def mk_bias():
+            a, b, y = rnd(*shape), rnd(256, 1, 1), torch.empty(shape, device=dev)
+            return lambda: lib.onnx_add(a, b, out=y)
+
+        def mk_relu():
+            a, y = rnd(*shape), torch.empty(shape, device=dev)
+            return lambda: lib.onnx_relu(a, out=y)
+
+        def mk_leaky():
+            a, y = rnd(*shape), torch.empty(shape, device=dev)
+            return lambda: lib.onnx_leakyrelu(a, 0.01, out=y)
+
+        def mk_sum_hw():
+            a, y = rnd(*shape), torch.empty(32, 256, 1, 1, device=dev)
+            return lambda: lib.onnx_reducesum(a, (2, 3), 1, out=y)
+
+        def mk_sum_all():
+            a, y = rnd(*shape), torch.empty((), device=dev)
+            return lambda: lib.onnx_reducesum(a, None, 0, out=y)
+
+        def mk_softmax():
+            a = rnd(8192, 1000)
+            y = torch.empty_like(a)
+            return lambda: lib.onnx_softmax(a, 1, out=y)
+
+        def mk_maxpool():
+            x, y = rnd(32, 64, 112, 112), torch.empty(32, 64, 56, 56, device=dev)
+            return lambda: lib.onnx_maxpool(x, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0, out=y)
+
+        def mk_depthwise():
+            x, w, b = rnd(8, 256, 56, 56), rnd(256, 1, 3, 3), rnd(256)
+            y = torch.empty(8, 256, 56, 56, device=dev)
+            return lambda: lib.onnx_conv(x, w, b, (1, 1, 1, 1), (1, 1), (1, 1), 256, out=y)
+
+        hbm("hbm_add_32x256x56x56", 3 * nb, mk_add)
+        hbm("hbm_add_channel_bias_32x256x56x56", 2 * nb, mk_bias)
+        hbm("hbm_relu_32x256x56x56", 2 * nb, mk_relu)
+        hbm("hbm_leakyrelu_32x256x56x56", 2 * nb, mk_leaky)
+        hbm("hbm_reducesum_32x256x56x56_over_hw", nb, mk_sum_hw)
+        hbm("hbm_reducesum_all_25.7M", nb, mk_sum_all)
+        hbm("hbm_softmax_8192x1000", 8.0 * 8192 * 1000, mk_softmax)
+        hbm("hbm_maxpool_3x3s2_32x64x112x112", 4.0 * (32 * 64 * 112 * 112 + 32 * 64 * 56 * 56), mk_maxpool)
+        hbm("hbm_depthwise_3x3_8x256x56x56", 4.0 * 2 * 8 * 256 * 56 * 56, mk_depthwise)
 
     # ---- CPU oracle beside it (a reported baseline, not the target) ---------------------------
     cpu = None

@@ -180,7 +180,32 @@ __global__ __launch_bounds__(256) void reduce_inner_kernel(const float* __restri
     const uint32_t r0 = chunk * per_chunk;
     const uint32_t r1 = min(m.reduced, r0 + per_chunk);
     float acc = 0.f;
-    if (m.nr == 1) {
+    if (m.nr == 1 && m.rs[0] == 1) {
+        // contiguous run: scalar head up to a 16-byte boundary, 16-byte loads with four
+        // independent partial sums per lane (four loads in flight), scalar tail
+        const float* p = base + r0;
+        const uint32_t n = r1 > r0 ? r1 - r0 : 0u;
+        uint32_t head = (uint32_t)((16u - (uint32_t)(reinterpret_cast<uintptr_t>(p) & 15u)) & 15u) >> 2;
+        if (head > n) head = n;
+        if ((uint32_t)lane < head) acc += p[lane];
+        const floatx4* p4 = reinterpret_cast<const floatx4*>(p + head);
+        const uint32_t n4 = (n - head) >> 2;
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        uint32_t j = lane;
+        for (; j + 192 < n4; j += 256) {
+            const floatx4 v0 = p4[j], v1 = p4[j + 64], v2 = p4[j + 128], v3 = p4[j + 192];
+            a0 += (v0.x + v0.y) + (v0.z + v0.w);
+            a1 += (v1.x + v1.y) + (v1.z + v1.w);
+            a2 += (v2.x + v2.y) + (v2.z + v2.w);
+            a3 += (v3.x + v3.y) + (v3.z + v3.w);
+        }
+        for (; j < n4; j += 64) {
+            const floatx4 v = p4[j];
+            a0 += (v.x + v.y) + (v.z + v.w);
+        }
+        acc += (a0 + a1) + (a2 + a3);
+        for (uint32_t t = head + (n4 << 2) + lane; t < n; t += 64) acc += p[t];
+    } else if (m.nr == 1) {
         for (uint32_t r = r0 + lane; r < r1; r += 64) acc += base[(int64_t)r * m.rs[0]];
     } else {
         for (uint32_t r = r0 + lane; r < r1; r += 64) acc += base[offset_of(r, m.nr, m.rdim, m.rs)];
