@@ -243,6 +243,15 @@ def main():
                                                    sum_of_layer_rooflines_ms=round(floor_ms, 4),
                                                    frac_of_layer_rooflines=round(floor_ms / ms, 4))
             del r
+        # batch sweep through the same runner and kernels (shapes are run-time values: nothing is re-tuned)
+        sweep = {}
+        for batch in (2, 4, 8, 16, 64):
+            m = workloads.resnet50(batch)
+            r = GraphRunner(m, dev)
+            t3 = time_call(r.run, iters=20, warm=5)
+            sweep[str(batch)] = {"ms": round(t3[0], 4), "img_per_s": round(batch / (t3[0] * 1e-3), 1)}
+            del r, m
+        details["resnet50_batch_sweep"] = sweep
         for name in workloads.ATTR_SWEEP_CONV:
             c = workloads.attr_sweep_case(name)
             X, W, Bv = up(c["X"]), up(c["W"]), up(c["B"])
