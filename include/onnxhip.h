@@ -202,6 +202,23 @@ onnx_status onnx_reducesum(const float* X, const int64_t* x_dims, int rank, cons
 onnx_status onnx_softmax(const float* X, const int64_t* x_dims, int rank, int axis, float* Y,
                          void* stream);
 
+/* Element types of the 16-bit entry point below (storage: IEEE binary16, or bfloat16 = the upper
+ * half of a binary32). */
+typedef enum { ONNX_F32 = 0, ONNX_F16 = 1, ONNX_BF16 = 2 } onnx_dtype;
+
+/*
+ * ONNX Gemm on 16-bit floating-point inputs (the operator definitions admit F16 tensors,
+ * Section 3.1): Y = alpha * A * B' + beta * C with A [M,K] and B [N,K] (transA = 0, transB = 1:
+ * both operands K-contiguous; other layouts are ONNX_ERR_UNSUPPORTED in this build) stored as
+ * in_type.  Products are exact and summed in fp32; C (NULL, or fp32 broadcastable to [M,N] as
+ * for onnx_gemm) and the epilogue are fp32; Y is stored as out_type: ONNX_F32, or in_type with
+ * round-to-nearest-even.  K must be a multiple of 8 and A, B 16-byte aligned.
+ */
+onnx_status onnx_gemm_lp(const void* A, const int64_t a_dims[2], const void* B, const int64_t b_dims[2],
+                         const float* C, const int64_t* c_dims, int c_rank, float alpha, float beta,
+                         int transA, int transB, onnx_act act, void* Y, const int64_t y_dims[2],
+                         onnx_dtype in_type, onnx_dtype out_type, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

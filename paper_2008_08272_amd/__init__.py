@@ -9,4 +9,4 @@ not been built, importing :mod:`paper_2008_08272_amd.binding` raises.
 from .binding import (OnnxHipError, lib_path, onnx_avgpool, onnx_conv, onnx_conv_infer, onnx_gemm,  # noqa: F401
                       onnx_last_error, onnx_matmul, onnx_set_workspace, onnx_matmul_infer, onnx_maxpool, onnx_pool_infer,
                       onnx_abs, onnx_add, onnx_broadcast_infer, onnx_leakyrelu, onnx_reduce_infer, onnx_reducesum,
-                      onnx_relu, onnx_softmax)
+                      onnx_relu, onnx_softmax, onnx_gemm_lp)

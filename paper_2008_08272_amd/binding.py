@@ -60,6 +60,9 @@ _lib.onnx_softmax.argtypes = [_vp, _i64p, _ci, _ci, _vp, _vp]
 for _f in (_lib.onnx_broadcast_infer, _lib.onnx_reduce_infer, _lib.onnx_add, _lib.onnx_relu, _lib.onnx_leakyrelu,
            _lib.onnx_abs, _lib.onnx_reducesum, _lib.onnx_softmax):
     _f.restype = _ci
+_lib.onnx_gemm_lp.argtypes = [_vp, _i64p, _vp, _i64p, _vp, _i64p, _ci, _cf, _cf, _ci, _ci, _ci, _vp, _i64p, _ci, _ci, _vp]
+_lib.onnx_gemm_lp.restype = _ci
+F32, F16, BF16 = 0, 1, 2
 
 _lib.onnx_set_workspace.argtypes = [_vp, ctypes.c_size_t]
 _lib.onnx_set_workspace.restype = _ci
@@ -263,3 +266,30 @@ def onnx_softmax(X, axis=-1, out=None, stream=None):
     Y = _out(out, X.shape, X)
     _check(_lib.onnx_softmax(_ptr(X), dims(X.shape), X.dim(), int(axis), _ptr(Y), _stream(stream)))
     return Y
+
+
+_LP_TYPES = {torch.float16: F16, torch.bfloat16: BF16}
+
+
+def onnx_gemm_lp(A, B, C=None, alpha=1.0, beta=1.0, transA=0, transB=1, act=ACT_NONE, out_dtype=None, out=None,
+                 stream=None):
+    """Gemm on float16 / bfloat16 CUDA tensors (A [M,K], B [N,K] with transB=1), fp32 bias C, result in
+    ``out_dtype`` (torch.float32 or the inputs' type; default the inputs' type, as ONNX Gemm does)."""
+    if not (isinstance(A, torch.Tensor) and isinstance(B, torch.Tensor) and A.is_cuda and B.is_cuda and
+            A.dtype == B.dtype and A.dtype in _LP_TYPES and A.is_contiguous() and B.is_contiguous()):
+        raise TypeError("A and B must be contiguous float16 or bfloat16 tensors of one type on the GPU")
+    C = _dev(C, "C")
+    out_dtype = A.dtype if out_dtype is None else out_dtype
+    if out_dtype not in (torch.float32, A.dtype):
+        raise TypeError("out_dtype must be torch.float32 or the inputs' type")
+    m = A.shape[1] if transA else A.shape[0]
+    n = B.shape[0] if transB else B.shape[1]
+    if out is None:
+        out = torch.empty((m, n), dtype=out_dtype, device=A.device)
+    elif not (out.is_cuda and out.dtype == out_dtype and out.is_contiguous()):
+        raise TypeError("out must be a contiguous GPU tensor of out_dtype")
+    cd, cr = (dims(C.shape), C.dim()) if C is not None else (None, 0)
+    _check(_lib.onnx_gemm_lp(_ptr(A), dims(A.shape), _ptr(B), dims(B.shape), _ptr(C), cd, cr, float(alpha), float(beta),
+                             int(transA), int(transB), int(act), _ptr(out), dims(out.shape), _LP_TYPES[A.dtype],
+                             F32 if out_dtype == torch.float32 else _LP_TYPES[A.dtype], _stream(stream)))
+    return out

@@ -1,0 +1,214 @@
+// Gemm on 16-bit inputs (IEEE half or bfloat16) with fp32 accumulation, on the gfx950 matrix cores.
+//
+// The paper's operator definitions admit 16-bit floating-point tensors (Section 3.1: the
+// LeakyRelu definition lists F16 next to F32 and F64).  Here Y = alpha * A * B^T + beta * C for
+// A [M, K] and B [N, K], both K-contiguous and stored as 16-bit values; products are exact in
+// fp32 and the sum is kept in fp32 accumulators (v_mfma_f32_32x32x16_{f16,bf16}: one MFMA
+// consumes 16 k, each lane supplying 8 consecutive k of its row or column).  The bias C and the
+// epilogue arithmetic are fp32; Y is stored as fp32 or rounded to the input type (nearest even).
+//
+// Same decomposition as contraction.h: a workgroup of WM x WN wavefronts owns a BM x BN tile,
+// walks K in steps of BK through two LDS buffers, global loads one step ahead in staging
+// registers, the 16-byte LDS reads of the next 16-k group issued in between the MFMAs of the
+// current one.  LDS rows are [BK + 8] 16-bit values: the 16-byte pad makes the 16-byte reads of
+// 8 neighbouring rows hit disjoint banks.
+#pragma once
+#include "contraction.h"
+
+namespace onnxhip {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+enum { LP_F16 = 1, LP_BF16 = 2 };
+
+template <int DT>
+__device__ inline floatx16 mfma16(const floatx4& a, const floatx4& b, const floatx16& c) {
+    if (DT == LP_BF16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+// fp32 -> 16-bit storage, round to nearest even
+template <int DT>
+__device__ inline uint16_t to_lp(float v) {
+    if (DT == LP_F16) return __builtin_bit_cast(uint16_t, (_Float16)v);
+    const uint32_t u = __builtin_bit_cast(uint32_t, v);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);      // NaN stays NaN
+    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+// K-contiguous tile loader for 16-bit elements: ROWS x BK values, 16-byte chunks of 8.
+template <int ROWS, int BK, int NT>
+struct LpLoader {
+    static constexpr int CPR = BK / 8;                     // chunks per row
+    static constexpr int ROWS_PER_PASS = NT / CPR;
+    static constexpr int NLOAD = (ROWS + ROWS_PER_PASS - 1) / ROWS_PER_PASS;
+    static constexpr int LDB = (BK + 8) * 2;               // bytes per LDS row
+    static constexpr int LDS_BYTES = ROWS * LDB;
+    static_assert(NT % CPR == 0 && ROWS % ROWS_PER_PASS == 0, "tile/loader mismatch");
+
+    floatx4 reg[NLOAD];
+    uint32_t voff[NLOAD];
+    int chunk, row0;
+    int K;
+    __amdgpu_buffer_rsrc_t rsrc;
+
+    __device__ inline void init(const uint16_t* p, int64_t ld, int first_row, int rows_total, int K_) {
+        K = K_;
+        chunk = threadIdx.x % CPR;
+        row0 = threadIdx.x / CPR;
+        const uint16_t* base = p + (int64_t)first_row * ld;
+        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(base), 0, (int)OOB, RSRC_FLAGS);
+#pragma unroll
+        for (int q = 0; q < NLOAD; ++q) {
+            const int row = row0 + q * ROWS_PER_PASS;
+            voff[q] = first_row + row < rows_total ? (uint32_t)(row * (int)ld + chunk * 8) * 2u : OOB;
+        }
+    }
+    // loads of the tile whose first k is k0 (k0 >= K loads nothing)
+    __device__ inline void fetch(int k0) {
+        const bool k_ok = k0 + chunk * 8 < K;
+#pragma unroll
+        for (int q = 0; q < NLOAD; ++q)
+            reg[q] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(k_ok ? voff[q] : OOB), k0 * 2, 0));
+    }
+    __device__ inline void commit(char* lds) const {
+#pragma unroll
+        for (int q = 0; q < NLOAD; ++q)
+            *reinterpret_cast<floatx4*>(lds + (row0 + q * ROWS_PER_PASS) * LDB + chunk * 16) = reg[q];
+    }
+    // the 8 consecutive k this lane feeds for tile-row `row`, 16-k group g, lane half h
+    __device__ static inline floatx4 frag(const char* lds, int row, int g, int h) {
+        return *reinterpret_cast<const floatx4*>(lds + row * LDB + g * 32 + h * 16);
+    }
+};
+
+// Stores a tile as 16-bit values: alpha*acc + beta*bias (none / per column / per row / full
+// fp32 matrix), Relu, rounding, 2-byte buffer stores (dropped by the range check outside Y).
+template <int DT, int TM, int TN, int WTM, int WTN>
+__device__ inline void store_tile_lp(const floatx16 (&acc)[TM][TN], const TileWork& w, int wm, int wn, int li, int h,
+                                     const ContractionParams& cp) {
+    uint16_t* Y = reinterpret_cast<uint16_t*>(cp.Y);
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y + ((int64_t)w.m0 * cp.y_rs + w.n0), 0, (int)OOB, RSRC_FLAGS);
+    const int mode = cp.bias ? cp.bias_mode : BIAS_NONE;
+    const float lo = cp.relu ? 0.f : -__builtin_inff();
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int cl = wn * WTN + j * 32 + li;
+        const int col = w.n0 + cl;
+        const bool col_ok = col < cp.N;
+        const int cj = col_ok ? col : w.n0;
+        const float col_bias = mode == BIAS_COL ? cp.beta * cp.bias[(int64_t)cj * cp.bias_cs] : 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int rl = wm * WTM + i * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+                const int row = w.m0 + rl;
+                const bool ok = col_ok && row < cp.M;
+                float add = col_bias;
+                if (mode == BIAS_ROW) add = cp.beta * cp.bias[ok ? row : 0];
+                if (mode == BIAS_FULL) add = cp.beta * cp.bias[ok ? (int64_t)row * cp.N + col : 0];
+                const float v = fmaxf(fmaf(cp.alpha, acc[i][j][r], add), lo);
+                __builtin_amdgcn_raw_buffer_store_b16((short)to_lp<DT>(v), ry, ok ? (rl * (int)cp.y_rs + cl) * 2 : (int)OOB, 0, 0);
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int DT, bool LP_OUT>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_lp_kernel(const ContractionParams cp) {
+    constexpr int NT = 64 * WM * WN;
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int G = BK / 16;                       // 16-k groups per K step
+    static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0 && BK % 32 == 0, "tile shape");
+    using ALoader = LpLoader<BM, BK, NT>;
+    using BLoader = LpLoader<BN, BK, NT>;
+
+    __shared__ __attribute__((aligned(16))) char lds_a[2][ALoader::LDS_BYTES];
+    __shared__ __attribute__((aligned(16))) char lds_b[2][BLoader::LDS_BYTES];
+
+    TileWork w;
+    if (!tile_work(cp, BM, BN, w)) return;
+    const int m0 = w.m0, n0 = w.n0;
+
+    ALoader la;
+    BLoader lb;
+    la.init(reinterpret_cast<const uint16_t*>(cp.A), cp.a_ld, m0, cp.M, cp.K);
+    lb.init(reinterpret_cast<const uint16_t*>(cp.B), cp.b_ld, n0, cp.N, cp.K);
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int li = lane & 31, h = lane >> 5;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    int kt0, kt1;
+    split_range((cp.K + BK - 1) / BK, w.ksplit, w.split, kt0, kt1);
+
+    floatx4 fa[2][TM], fb[2][TN];                    // fragments of two groups: one in use, one arriving
+    auto frags = [&](int f, int buf, int g) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[f][i] = ALoader::frag(lds_a[buf], wm * WTM + i * 32 + li, g, h);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[f][j] = BLoader::frag(lds_b[buf], wn * WTN + j * 32 + li, g, h);
+    };
+    auto mfmas = [&](int f, int i_lo, int i_hi) {
+#pragma unroll
+        for (int i = i_lo; i < i_hi; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[i][j] = mfma16<DT>(fa[f][i], fb[f][j], acc[i][j]);
+    };
+    constexpr int NREAD = TM + TN, NMFMA = TM * TN;
+    constexpr int HALF = TM > 1 ? TM / 2 : 1;        // rows of accumulator blocks issued before the barrier
+
+    // One K step (see contraction.h): loads of the next step issued first; groups 0 .. G-2 with the
+    // next group's LDS reads in between their MFMAs; the last group split around the barrier,
+    // the LDS stores of the next tile before it, the first reads of the next step after it.
+    auto step = [&](int kt, int s) {
+        la.fetch((kt + 1) * BK);
+        lb.fetch((kt + 1) * BK);
+#pragma unroll
+        for (int g = 0; g + 1 < G; ++g) {
+            frags((g + 1) & 1, s, g + 1);
+            mfmas(g & 1, 0, TM);
+#pragma unroll
+            for (int q = 0; q < NMFMA; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, (NREAD + NMFMA - 1) / NMFMA, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        la.commit(lds_a[s ^ 1]);
+        lb.commit(lds_b[s ^ 1]);
+        mfmas((G - 1) & 1, 0, HALF);
+        __syncthreads();
+        frags(0, s ^ 1, 0);
+        if (HALF < TM) mfmas((G - 1) & 1, HALF, TM);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    la.fetch(kt0 * BK);
+    lb.fetch(kt0 * BK);
+    la.commit(lds_a[0]);
+    lb.commit(lds_b[0]);
+    __syncthreads();
+    frags(0, 0, 0);
+    for (int kt = kt0; kt < kt1; kt += 2) {
+        step(kt, 0);
+        if (kt + 1 < kt1) step(kt + 1, 1);
+    }
+
+    if (LP_OUT && w.ksplit == 1) store_tile_lp<DT, TM, TN, WTM, WTN>(acc, w, wm, wn, li, h, cp);
+    else finish_tile<TM, TN, WTM, WTN, NT>(acc, w, wm, wn, li, h, cp);
+}
+
+}  // namespace onnxhip

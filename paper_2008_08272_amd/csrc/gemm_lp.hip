@@ -1,0 +1,127 @@
+// Gemm on 16-bit inputs: kernel instances, tile choice and the C-ABI entry point.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/onnxhip.h"
+#include "gemm_lp.h"
+#include "internal.h"
+
+using namespace onnxhip;
+
+namespace {
+
+onnx_status fail(onnx_status st, const char* fmt, ...) {
+    char buf[320];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    return static_cast<onnx_status>(report_error(st, buf));
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline bool overlaps(const void* a, int64_t na, const void* b, int64_t nb) {
+    if (!a || !b || na <= 0 || nb <= 0) return false;
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + (uintptr_t)nb && b0 < a0 + (uintptr_t)na;
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int DT, bool LP_OUT>
+hipError_t launch_instance(ContractionParams& p, hipStream_t stream) {
+    p.tiles_m = (p.M + BM - 1) / BM;
+    p.tiles_n = (p.N + BN - 1) / BN;
+    p.nz = 1;
+    p.ksplit = 1;                                    // every tile walks its whole K range
+    p.ws_partial = nullptr;
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    p.tail_begin = (int)tiles;
+    p.tail_split = 1;
+    hipLaunchKernelGGL((gemm_lp_kernel<BM, BN, BK, WM, WN, DT, LP_OUT>), dim3((unsigned)tiles, 1, 1), dim3(64 * WM * WN), 0,
+                       stream, p);
+    return hipGetLastError();
+}
+
+// Tile by the same estimate as the fp32 kernel: workgroups per CU x tile area / efficiency.
+template <int DT, bool LP_OUT>
+hipError_t launch_tile(ContractionParams& p, hipStream_t stream) {
+    const double cus = 256.0;
+    const double t256 = (double)((p.M + 255) / 256) * (double)((p.N + 255) / 256);
+    const double t128 = (double)((p.M + 127) / 128) * (double)((p.N + 127) / 128);
+    const double c256 = (double)(int64_t)((t256 + cus - 1) / cus) * 65536.0 / 1.0;
+    const double c128 = (t128 / cus < 1.0 ? 1.0 : t128 / cus) * 16384.0 / 0.85;
+    if (c256 <= c128) return launch_instance<256, 256, 64, 4, 4, DT, LP_OUT>(p, stream);
+    return launch_instance<128, 128, 64, 2, 2, DT, LP_OUT>(p, stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+onnx_status onnx_gemm_lp(const void* A, const int64_t a_dims[2], const void* B, const int64_t b_dims[2], const float* C,
+                         const int64_t* c_dims, int c_rank, float alpha, float beta, int transA, int transB, onnx_act act,
+                         void* Y, const int64_t y_dims[2], onnx_dtype in_type, onnx_dtype out_type, void* stream) {
+    if (!a_dims || !b_dims || !y_dims) return fail(ONNX_ERR_NULL, "gemm_lp: NULL dims array");
+    if (in_type != ONNX_F16 && in_type != ONNX_BF16) return fail(ONNX_ERR_ATTR, "gemm_lp: in_type must be ONNX_F16 or ONNX_BF16");
+    if (out_type != ONNX_F32 && out_type != in_type) return fail(ONNX_ERR_ATTR, "gemm_lp: out_type must be ONNX_F32 or in_type");
+    if (transA != 0 || transB != 1)
+        return fail(ONNX_ERR_UNSUPPORTED, "gemm_lp: only transA = 0, transB = 1 (both operands K-contiguous) is built");
+    for (int i = 0; i < 2; ++i)
+        if (a_dims[i] < 0 || b_dims[i] < 0) return fail(ONNX_ERR_SHAPE, "gemm_lp: negative dimension");
+    const int64_t M = a_dims[0], K = a_dims[1], N = b_dims[0];
+    if (b_dims[1] != K) return fail(ONNX_ERR_SHAPE, "gemm_lp: inner dimensions differ (%lld vs %lld)", (long long)K, (long long)b_dims[1]);
+    if (y_dims[0] != M || y_dims[1] != N)
+        return fail(ONNX_ERR_SHAPE, "gemm_lp: y_dims is {%lld,%lld} but the result is {%lld,%lld}", (long long)y_dims[0],
+                    (long long)y_dims[1], (long long)M, (long long)N);
+    if (act != ONNX_ACT_NONE && act != ONNX_ACT_RELU) return fail(ONNX_ERR_ATTR, "gemm_lp: unknown activation");
+    int64_t crs = 0, ccs = 0, nc = 0;
+    if (C) {
+        int64_t r = 1, c = 1;
+        if (c_rank < 0 || c_rank > 2) return fail(ONNX_ERR_RANK, "gemm_lp: C must have rank 0, 1 or 2");
+        if (c_rank > 0 && !c_dims) return fail(ONNX_ERR_NULL, "gemm_lp: c_dims is NULL");
+        if (c_rank == 1) c = c_dims[0];
+        if (c_rank == 2) { r = c_dims[0]; c = c_dims[1]; }
+        if (!((r == 1 || r == M) && (c == 1 || c == N)))
+            return fail(ONNX_ERR_SHAPE, "gemm_lp: C {%lld,%lld} does not broadcast to {%lld,%lld}", (long long)r, (long long)c,
+                        (long long)M, (long long)N);
+        crs = (r == 1) ? 0 : c;
+        ccs = (c == 1) ? 0 : 1;
+        nc = r * c;
+    }
+    if (M * N == 0) return ONNX_OK;
+    if (!Y || (K > 0 && (!A || !B))) return fail(ONNX_ERR_NULL, "gemm_lp: A, B and Y must not be NULL");
+    const int64_t ysz = out_type == ONNX_F32 ? 4 : 2;
+    if (overlaps(Y, M * N * ysz, A, M * K * 2) || overlaps(Y, M * N * ysz, B, K * N * 2) || overlaps(Y, M * N * ysz, C, nc * 4))
+        return fail(ONNX_ERR_ALIAS, "gemm_lp: Y overlaps an input");
+    if (M > 0x7fffffffLL || N > 0x7fffffffLL || K > 0x7fffffffLL) return fail(ONNX_ERR_UNSUPPORTED, "gemm_lp: extent above 2^31-1");
+    if (K % 8 != 0 || !aligned16(A) || !aligned16(B))
+        return fail(ONNX_ERR_UNSUPPORTED, "gemm_lp: K must be a multiple of 8 and A, B 16-byte aligned (16-byte loads of 8 values)");
+    // 32-bit tile offsets: 256 rows of an operand or of Y must span less than 2^31 bytes
+    if ((256 * K + K) * 2 >= (1LL << 31) - 64 || (256 * N + N) * 4 >= (1LL << 31) - 64)
+        return fail(ONNX_ERR_UNSUPPORTED, "gemm_lp: a row of A, B or Y is too long for 32-bit tile offsets");
+
+    ContractionParams p;
+    memset(&p, 0, sizeof(p));
+    for (int i = 0; i < MAX_BATCH_DIMS; ++i) p.bdim[i] = 1;
+    p.colP = FastDiv::make(1);
+    p.ic.kHW = p.ic.kW = p.ic.OW = FastDiv::make(1);
+    p.A = static_cast<const float*>(A);
+    p.B = static_cast<const float*>(B);
+    p.Y = static_cast<float*>(Y);
+    p.bias = C;
+    p.M = (int)M; p.N = (int)N; p.K = (int)K;
+    p.a_ld = K; p.b_ld = K; p.y_rs = N;
+    p.alpha = alpha; p.beta = beta; p.relu = act == ONNX_ACT_RELU;
+    p.bias_mode = (crs != 0 && ccs != 0) ? BIAS_FULL : (crs != 0 ? BIAS_ROW : BIAS_COL);
+    p.bias_cs = (int)ccs;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (in_type == ONNX_F16) e = out_type == ONNX_F32 ? launch_tile<LP_F16, false>(p, s) : launch_tile<LP_F16, true>(p, s);
+    else e = out_type == ONNX_F32 ? launch_tile<LP_BF16, false>(p, s) : launch_tile<LP_BF16, true>(p, s);
+    if (e != hipSuccess) return fail(ONNX_ERR_DEVICE, "gemm_lp: %s", hipGetErrorString(e));
+    return ONNX_OK;
+}
+
+}  // extern "C"

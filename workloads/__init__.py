@@ -187,6 +187,38 @@ def gemm_case(n, seed=SEED_BASE + 2, m=None, k=None):
 GEMM_SWEEP_SIZES = (1024, 2048, 4096)
 
 
+def to_bf16_bits(x):
+    """fp32 array -> bfloat16 storage (uint16: the upper half of the binary32 pattern), rounded to
+    nearest even.  Input preparation only."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def from_bf16_bits(b):
+    """bfloat16 storage -> the fp32 values it denotes (exact)."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def gemm_case_16bit(n, kind, seed=SEED_BASE + 7, m=None, k=None):
+    """A [m,k], B [n,k] (used with transB=1) drawn U[-1,1) and rounded to ``kind`` ("f16" or "bf16"),
+    C [1,n] fp32.  Returns the 16-bit storage (uint16 bit patterns) and the fp32 values they
+    denote, which is what a reference has to be computed from."""
+    m = n if m is None else m
+    k = n if k is None else k
+    r = _rng(seed, n)
+    a, b, c = _uniform(r, (m, k)), _uniform(r, (n, k)), _uniform(r, (1, n))
+    if kind == "bf16":
+        ab, bb = to_bf16_bits(a), to_bf16_bits(b)
+        av, bv = from_bf16_bits(ab), from_bf16_bits(bb)
+    elif kind == "f16":
+        ah, bh = a.astype(np.float16), b.astype(np.float16)
+        ab, bb = ah.view(np.uint16), bh.view(np.uint16)
+        av, bv = ah.astype(np.float32), bh.astype(np.float32)
+    else:
+        raise ValueError(kind)
+    return dict(A_bits=ab, B_bits=bb, A=av, B=bv, C=c, kind=kind)
+
+
 # --------------------------------------------------------------------------- configs 3, 4
 
 RESNET50_STAGES = ((64, 3, 1), (128, 4, 2), (256, 6, 2), (512, 3, 2))   # width, blocks, stride
