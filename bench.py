@@ -21,6 +21,7 @@ if ROOT not in sys.path:
 
 MFMA_FP32_PEAK_TFLOPS = 157.3      # 256 CU x 256 flop/clk x 2.4 GHz
 HBM_PEAK_GBS = 8000.0
+MFMA_16BIT_PEAK_TFLOPS = 2500.0    # dense fp16 / bf16
 RAMP_SECONDS = 0.3
 
 # Memory traffic of one Gemm 4096^3 launch from the FETCH_SIZE / WRITE_SIZE counter passes summarised in
@@ -243,6 +244,18 @@ def main():
                                                    sum_of_layer_rooflines_ms=round(floor_ms, 4),
                                                    frac_of_layer_rooflines=round(floor_ms / ms, 4))
             del r
+        # Gemm on 16-bit inputs (fp32 accumulation), against the 2.5 PFLOP/s dense fp16 / bf16 MFMA peak
+        for kind, tdt in (("bf16", torch.bfloat16), ("f16", torch.float16)):
+            for n in (4096, 8192):
+                A16 = torch.randn(n, n, device=dev).to(tdt)
+                B16 = torch.randn(n, n, device=dev).to(tdt)
+                C32 = torch.randn(1, n, device=dev)
+                Y16 = torch.empty(n, n, device=dev, dtype=tdt)
+                t3 = time_call(lambda: lib.onnx_gemm_lp(A16, B16, C32, out=Y16), iters=20, warm=5)
+                tf = 2.0 * n ** 3 / (t3[0] * 1e-3) / 1e12
+                details["gemm_%s_%d" % (kind, n)] = dict(timing(t3), tflops=round(tf, 1),
+                                                         frac_mfma_peak_16bit=round(tf / MFMA_16BIT_PEAK_TFLOPS, 4))
+                del A16, B16, C32, Y16
         # batch sweep through the same runner and kernels (shapes are run-time values: nothing is re-tuned)
         sweep = {}
         for batch in (2, 4, 8, 16, 64):

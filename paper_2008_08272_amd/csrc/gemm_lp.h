@@ -8,9 +8,9 @@
 // epilogue arithmetic are fp32; Y is stored as fp32 or rounded to the input type (nearest even).
 //
 // Same decomposition as contraction.h: a workgroup of WM x WN wavefronts owns a BM x BN tile,
-// walks K in steps of BK through two LDS buffers, global loads one step ahead in staging
-// registers, the 16-byte LDS reads of the next 16-k group issued in between the MFMAs of the
-// current one.  LDS rows are [BK + 8] 16-bit values: the 16-byte pad makes the 16-byte reads of
+// walks K in steps of BK through two LDS buffers, global loads one or two steps ahead in
+// staging registers, the 16-byte LDS reads of the next 16-k group issued in between the MFMAs
+// of the current one.  LDS rows are [BK + 8] 16-bit values: the 16-byte pad makes the 16-byte reads of
 // 8 neighbouring rows hit disjoint banks.
 #pragma once
 #include "contraction.h"
@@ -39,7 +39,7 @@ __device__ inline uint16_t to_lp(float v) {
 }
 
 // K-contiguous tile loader for 16-bit elements: ROWS x BK values, 16-byte chunks of 8.
-template <int ROWS, int BK, int NT>
+template <int ROWS, int BK, int NT, int NSETS>
 struct LpLoader {
     static constexpr int CPR = BK / 8;                     // chunks per row
     static constexpr int ROWS_PER_PASS = NT / CPR;
@@ -48,7 +48,7 @@ struct LpLoader {
     static constexpr int LDS_BYTES = ROWS * LDB;
     static_assert(NT % CPR == 0 && ROWS % ROWS_PER_PASS == 0, "tile/loader mismatch");
 
-    floatx4 reg[NLOAD];
+    floatx4 reg[NSETS][NLOAD];             // staging registers: tiles of coming K steps on their way to LDS
     uint32_t voff[NLOAD];
     int chunk, row0;
     int K;
@@ -66,17 +66,19 @@ struct LpLoader {
             voff[q] = first_row + row < rows_total ? (uint32_t)(row * (int)ld + chunk * 8) * 2u : OOB;
         }
     }
-    // loads of the tile whose first k is k0 (k0 >= K loads nothing)
+    // loads of the tile whose first k is k0 into register set S (k0 >= K loads nothing)
+    template <int S>
     __device__ inline void fetch(int k0) {
         const bool k_ok = k0 + chunk * 8 < K;
 #pragma unroll
         for (int q = 0; q < NLOAD; ++q)
-            reg[q] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(k_ok ? voff[q] : OOB), k0 * 2, 0));
+            reg[S][q] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(k_ok ? voff[q] : OOB), k0 * 2, 0));
     }
+    template <int S>
     __device__ inline void commit(char* lds) const {
 #pragma unroll
         for (int q = 0; q < NLOAD; ++q)
-            *reinterpret_cast<floatx4*>(lds + (row0 + q * ROWS_PER_PASS) * LDB + chunk * 16) = reg[q];
+            *reinterpret_cast<floatx4*>(lds + (row0 + q * ROWS_PER_PASS) * LDB + chunk * 16) = reg[S][q];
     }
     // the 8 consecutive k this lane feeds for tile-row `row`, 16-k group g, lane half h
     __device__ static inline floatx4 frag(const char* lds, int row, int g, int h) {
@@ -117,15 +119,15 @@ __device__ inline void store_tile_lp(const floatx16 (&acc)[TM][TN], const TileWo
     }
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int DT, bool LP_OUT>
+template <int BM, int BN, int BK, int WM, int WN, int DT, bool LP_OUT, int PF>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_lp_kernel(const ContractionParams cp) {
     constexpr int NT = 64 * WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int G = BK / 16;                       // 16-k groups per K step
     static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0 && BK % 32 == 0, "tile shape");
-    using ALoader = LpLoader<BM, BK, NT>;
-    using BLoader = LpLoader<BN, BK, NT>;
+    using ALoader = LpLoader<BM, BK, NT, PF>;
+    using BLoader = LpLoader<BN, BK, NT, PF>;
 
     __shared__ __attribute__((aligned(16))) char lds_a[2][ALoader::LDS_BYTES];
     __shared__ __attribute__((aligned(16))) char lds_b[2][BLoader::LDS_BYTES];
@@ -170,12 +172,16 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_lp_kernel(const Contraction
     constexpr int NREAD = TM + TN, NMFMA = TM * TN;
     constexpr int HALF = TM > 1 ? TM / 2 : 1;        // rows of accumulator blocks issued before the barrier
 
-    // One K step (see contraction.h): loads of the next step issued first; groups 0 .. G-2 with the
+    // One K step (see contraction.h): loads PF steps ahead issued first; groups 0 .. G-2 with the
     // next group's LDS reads in between their MFMAs; the last group split around the barrier,
     // the LDS stores of the next tile before it, the first reads of the next step after it.
-    auto step = [&](int kt, int s) {
-        la.fetch((kt + 1) * BK);
-        lb.fetch((kt + 1) * BK);
+    using Par0 = std::integral_constant<int, 0>;
+    using Par1 = std::integral_constant<int, 1>;
+    auto step = [&](int kt, auto S) {
+        constexpr int s = decltype(S)::value;
+        constexpr int set_in = PF == 2 ? s : 0, set_out = PF == 2 ? (s ^ 1) : 0;
+        la.template fetch<set_in>((kt + PF) * BK);
+        lb.template fetch<set_in>((kt + PF) * BK);
 #pragma unroll
         for (int g = 0; g + 1 < G; ++g) {
             frags((g + 1) & 1, s, g + 1);
@@ -187,8 +193,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_lp_kernel(const Contraction
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        la.commit(lds_a[s ^ 1]);
-        lb.commit(lds_b[s ^ 1]);
+        la.template commit<set_out>(lds_a[s ^ 1]);
+        lb.template commit<set_out>(lds_b[s ^ 1]);
         mfmas((G - 1) & 1, 0, HALF);
         __syncthreads();
         frags(0, s ^ 1, 0);
@@ -196,15 +202,19 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_lp_kernel(const Contraction
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    la.fetch(kt0 * BK);
-    lb.fetch(kt0 * BK);
-    la.commit(lds_a[0]);
-    lb.commit(lds_b[0]);
+    la.template fetch<0>(kt0 * BK);
+    lb.template fetch<0>(kt0 * BK);
+    if (PF == 2) {
+        la.template fetch<PF - 1>((kt0 + 1) * BK);
+        lb.template fetch<PF - 1>((kt0 + 1) * BK);
+    }
+    la.template commit<0>(lds_a[0]);
+    lb.template commit<0>(lds_b[0]);
     __syncthreads();
     frags(0, 0, 0);
     for (int kt = kt0; kt < kt1; kt += 2) {
-        step(kt, 0);
-        if (kt + 1 < kt1) step(kt + 1, 1);
+        step(kt, Par0{});
+        if (kt + 1 < kt1) step(kt + 1, Par1{});
     }
 
     if (LP_OUT && w.ksplit == 1) store_tile_lp<DT, TM, TN, WTM, WTN>(acc, w, wm, wn, li, h, cp);

@@ -28,7 +28,7 @@ inline bool overlaps(const void* a, int64_t na, const void* b, int64_t nb) {
     return a0 < b0 + (uintptr_t)nb && b0 < a0 + (uintptr_t)na;
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int DT, bool LP_OUT>
+template <int BM, int BN, int BK, int WM, int WN, int DT, bool LP_OUT, int PF>
 hipError_t launch_instance(ContractionParams& p, hipStream_t stream) {
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
@@ -39,7 +39,7 @@ hipError_t launch_instance(ContractionParams& p, hipStream_t stream) {
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
     p.tail_begin = (int)tiles;
     p.tail_split = 1;
-    hipLaunchKernelGGL((gemm_lp_kernel<BM, BN, BK, WM, WN, DT, LP_OUT>), dim3((unsigned)tiles, 1, 1), dim3(64 * WM * WN), 0,
+    hipLaunchKernelGGL((gemm_lp_kernel<BM, BN, BK, WM, WN, DT, LP_OUT, PF>), dim3((unsigned)tiles, 1, 1), dim3(64 * WM * WN), 0,
                        stream, p);
     return hipGetLastError();
 }
@@ -52,8 +52,8 @@ hipError_t launch_tile(ContractionParams& p, hipStream_t stream) {
     const double t128 = (double)((p.M + 127) / 128) * (double)((p.N + 127) / 128);
     const double c256 = (double)(int64_t)((t256 + cus - 1) / cus) * 65536.0 / 1.0;
     const double c128 = (t128 / cus < 1.0 ? 1.0 : t128 / cus) * 16384.0 / 0.85;
-    if (c256 <= c128) return launch_instance<256, 256, 64, 4, 4, DT, LP_OUT>(p, stream);
-    return launch_instance<128, 128, 64, 2, 2, DT, LP_OUT>(p, stream);
+    if (c256 <= c128) return launch_instance<256, 256, 64, 2, 4, DT, LP_OUT, 2>(p, stream);
+    return launch_instance<128, 128, 64, 2, 2, DT, LP_OUT, 1>(p, stream);
 }
 
 }  // namespace
