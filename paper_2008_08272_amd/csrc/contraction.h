@@ -515,7 +515,12 @@ __global__ __launch_bounds__(64 * WM * WN) void splitk_finish_kernel(const Contr
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, h = lane >> 5;
-    const float* base = cp.ws_partial + first_slot * TILE + threadIdx.x;
+    // The partial tiles come from other XCDs, i.e. from memory: their latency, not their volume, is
+    // what this kernel waits for.  Four shares are fetched at a time, every load issued before the
+    // first add (a share past the last one is an out-of-range offset that returns 0), and added in
+    // split order.
+    const __amdgpu_buffer_rsrc_t rp = tile_rsrc(cp.ws_partial + first_slot * TILE);
+    constexpr int AHEAD = 4;
     floatx16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -523,14 +528,28 @@ __global__ __launch_bounds__(64 * WM * WN) void splitk_finish_kernel(const Contr
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    for (int s = 0; s < ksplit; ++s) {
-        const float* src = base + (int64_t)s * TILE;
+    for (int s0 = 0; s0 < ksplit; s0 += AHEAD) {
+        float v[AHEAD][TM][TN][16];
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int u = 0; u < AHEAD; ++u) {
+            const uint32_t share = s0 + u < ksplit ? (uint32_t)threadIdx.x * 4u : OOB;
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] += src[((i * TN + j) * 16 + r) * NT];
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        v[u][i][j][r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                            rp, (int)share, ((s0 + u) * TILE + ((i * TN + j) * 16 + r) * NT) * 4, 0));
+        }
+#pragma unroll
+        for (int u = 0; u < AHEAD; ++u)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] += v[u][i][j][r];
     }
     store_tile<TM, TN, WTM, WTN>(acc, m0, n0, zslice, wm, wn, li, h, cp);
 }

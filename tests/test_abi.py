@@ -174,3 +174,27 @@ def test_elementwise_errors_are_reported_before_touching_the_device(B):
     assert lib.onnx_softmax(fake, d((2, 3)), 0, 0, other, None) == 2
     assert lib.onnx_softmax(fake, d((2, 3)), 2, 1, fake, None) == 6
     assert "softmax" in B.onnx_last_error()
+
+
+def test_gemm_16bit_errors_are_reported_before_touching_the_device(B):
+    lib = B.raw()
+    d = B.dims
+    a, b, y = ctypes.c_void_p(1 << 20), ctypes.c_void_p(1 << 22), ctypes.c_void_p(1 << 24)
+    ok = (a, d((16, 16)), b, d((32, 16)), None, None, 0, 1.0, 1.0, 0, 1, 0, y, d((16, 32)))
+    assert lib.onnx_gemm_lp(*ok, 0, 0, None) == 4                       # inputs must be a 16-bit type
+    assert lib.onnx_gemm_lp(*ok, 1, 2, None) == 4                       # output: fp32 or the input type
+    bad = list(ok); bad[10] = 0
+    assert lib.onnx_gemm_lp(*bad, 2, 2, None) == 5                      # transB = 0 is not built
+    bad = list(ok); bad[1] = d((16, 12)); bad[3] = d((32, 12))
+    assert lib.onnx_gemm_lp(*bad, 2, 0, None) == 5                      # K not a multiple of 8
+    bad = list(ok); bad[3] = d((32, 24))
+    assert lib.onnx_gemm_lp(*bad, 2, 0, None) == 3
+    bad = list(ok); bad[13] = d((16, 31))
+    assert lib.onnx_gemm_lp(*bad, 2, 0, None) == 3
+    bad = list(ok); bad[0] = None
+    assert lib.onnx_gemm_lp(*bad, 1, 1, None) == 1
+    bad = list(ok); bad[12] = a
+    assert lib.onnx_gemm_lp(*bad, 1, 1, None) == 6
+    bad = list(ok); bad[0] = ctypes.c_void_p((1 << 20) + 8)
+    assert lib.onnx_gemm_lp(*bad, 1, 1, None) == 5                      # 16-byte alignment
+    assert "gemm_lp" in B.onnx_last_error()
