@@ -256,6 +256,17 @@ def main():
                 details["gemm_%s_%d" % (kind, n)] = dict(timing(t3), tflops=round(tf, 1),
                                                          frac_mfma_peak_16bit=round(tf / MFMA_16BIT_PEAK_TFLOPS, 4))
                 del A16, B16, C32, Y16
+        # LSTM: one Gemm for the input projection of the sequence, then one small Gemm + one cell kernel per step
+        seq, bsz, nin, hid = 64, 32, 512, 512
+        Xl = torch.randn(seq, bsz, nin, device=dev)
+        Wl = torch.randn(1, 4 * hid, nin, device=dev) / nin ** 0.5
+        Rl = torch.randn(1, 4 * hid, hid, device=dev) / hid ** 0.5
+        Bl = torch.randn(1, 8 * hid, device=dev) * 0.1
+        t3 = time_call(lambda: lib.onnx_lstm(Xl, Wl, Rl, Bl), iters=10, warm=3)
+        fl = 2.0 * seq * bsz * 4 * hid * (nin + hid)
+        details["lstm_seq64_b32_512_512"] = dict(timing(t3), tflops=round(fl / (t3[0] * 1e-3) / 1e12, 2),
+                                                 us_per_step=round(t3[0] * 1e3 / seq, 2))
+        del Xl, Wl, Rl, Bl
         # batch sweep through the same runner and kernels (shapes are run-time values: nothing is re-tuned)
         sweep = {}
         for batch in (2, 4, 8, 16, 64):

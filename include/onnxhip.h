@@ -219,6 +219,27 @@ onnx_status onnx_gemm_lp(const void* A, const int64_t a_dims[2], const void* B, 
                          int transA, int transB, onnx_act act, void* Y, const int64_t y_dims[2],
                          onnx_dtype in_type, onnx_dtype out_type, void* stream);
 
+/*
+ * ONNX LSTM (named among the supported operators, Section 4.1), layout 0, default activations
+ * (sigmoid, tanh, tanh), no peepholes, every sequence of full length.  X [seq, batch, input];
+ * W [dirs, 4H, input] and R [dirs, 4H, H] with the gate blocks in the order i, o, f, c;
+ * B NULL or [dirs, 8H] (input biases, then recurrent biases); initial_h / initial_c NULL (zeros)
+ * or [dirs, batch, H]; dirs = 2 for ONNX_LSTM_BIDIRECTIONAL, else 1.  Per step
+ *   i,o,f = sigmoid(x W' + h R' + Wb + Rb),  g = tanh(...),  c = f*c + i*g,  h = o*tanh(c).
+ * Outputs (each may be NULL, not all): Y [seq, dirs, batch, H], Y_h and Y_c [dirs, batch, H].
+ * The products run through the same kernels as onnx_gemm (one Gemm for the input projection of
+ * the whole sequence, one per time step for the recurrence), followed by an element-wise cell
+ * kernel per step.  `scratch` is caller-owned device memory of at least
+ * onnx_lstm_scratch_bytes(...) bytes, 256-byte aligned, contents irrelevant; it must not overlap
+ * any input or output (ONNX_ERR_ALIAS).
+ */
+enum { ONNX_LSTM_FORWARD = 0, ONNX_LSTM_REVERSE = 1, ONNX_LSTM_BIDIRECTIONAL = 2 };
+size_t onnx_lstm_scratch_bytes(const int64_t x_dims[3], int64_t hidden_size, int direction);
+onnx_status onnx_lstm(const float* X, const int64_t x_dims[3], const float* W, const float* R,
+                      const float* B, const float* initial_h, const float* initial_c,
+                      int64_t hidden_size, int direction, float* Y, float* Y_h, float* Y_c,
+                      void* scratch, size_t scratch_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

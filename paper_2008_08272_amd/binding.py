@@ -63,6 +63,11 @@ for _f in (_lib.onnx_broadcast_infer, _lib.onnx_reduce_infer, _lib.onnx_add, _li
 _lib.onnx_gemm_lp.argtypes = [_vp, _i64p, _vp, _i64p, _vp, _i64p, _ci, _cf, _cf, _ci, _ci, _ci, _vp, _i64p, _ci, _ci, _vp]
 _lib.onnx_gemm_lp.restype = _ci
 F32, F16, BF16 = 0, 1, 2
+_lib.onnx_lstm_scratch_bytes.argtypes = [_i64p, _c64, _ci]
+_lib.onnx_lstm_scratch_bytes.restype = ctypes.c_size_t
+_lib.onnx_lstm.argtypes = [_vp, _i64p, _vp, _vp, _vp, _vp, _vp, _c64, _ci, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.onnx_lstm.restype = _ci
+LSTM_DIRECTIONS = {"forward": 0, "reverse": 1, "bidirectional": 2}
 
 _lib.onnx_set_workspace.argtypes = [_vp, ctypes.c_size_t]
 _lib.onnx_set_workspace.restype = _ci
@@ -293,3 +298,28 @@ def onnx_gemm_lp(A, B, C=None, alpha=1.0, beta=1.0, transA=0, transB=1, act=ACT_
                              int(transA), int(transB), int(act), _ptr(out), dims(out.shape), _LP_TYPES[A.dtype],
                              F32 if out_dtype == torch.float32 else _LP_TYPES[A.dtype], _stream(stream)))
     return out
+
+
+def onnx_lstm(X, W, R, B=None, initial_h=None, initial_c=None, direction="forward", stream=None):
+    """ONNX LSTM (layout 0, default activations).  Returns (Y, Y_h, Y_c); the scratch the library
+    needs is allocated here with torch.empty and lives until the call's work has been enqueued
+    (torch keeps the block alive for the stream it was allocated on)."""
+    X, W, R = _dev(X, "X"), _dev(W, "W"), _dev(R, "R")
+    B, initial_h, initial_c = _dev(B, "B"), _dev(initial_h, "initial_h"), _dev(initial_c, "initial_c")
+    d = LSTM_DIRECTIONS[direction]
+    dirs = 2 if d == 2 else 1
+    seq, batch, _ = X.shape
+    H = R.shape[2]
+    if tuple(W.shape) != (dirs, 4 * H, X.shape[2]) or tuple(R.shape) != (dirs, 4 * H, H):
+        raise ValueError("W must be [dirs, 4H, input] and R [dirs, 4H, H]")
+    for t, shape, name in ((B, (dirs, 8 * H), "B"), (initial_h, (dirs, batch, H), "initial_h"), (initial_c, (dirs, batch, H), "initial_c")):
+        if t is not None and tuple(t.shape) != shape:
+            raise ValueError("%s must have shape %r" % (name, shape))
+    Y = torch.empty((seq, dirs, batch, H), dtype=torch.float32, device=X.device)
+    Yh = torch.empty((dirs, batch, H), dtype=torch.float32, device=X.device)
+    Yc = torch.empty((dirs, batch, H), dtype=torch.float32, device=X.device)
+    need = _lib.onnx_lstm_scratch_bytes(dims(X.shape), H, d)
+    scratch = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
+    _check(_lib.onnx_lstm(_ptr(X), dims(X.shape), _ptr(W), _ptr(R), _ptr(B), _ptr(initial_h), _ptr(initial_c), H, d,
+                          _ptr(Y), _ptr(Yh), _ptr(Yc), _ptr(scratch), scratch.numel(), _stream(stream)))
+    return Y, Yh, Yc

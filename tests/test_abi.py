@@ -198,3 +198,23 @@ def test_gemm_16bit_errors_are_reported_before_touching_the_device(B):
     bad = list(ok); bad[0] = ctypes.c_void_p((1 << 20) + 8)
     assert lib.onnx_gemm_lp(*bad, 1, 1, None) == 5                      # 16-byte alignment
     assert "gemm_lp" in B.onnx_last_error()
+
+
+def test_lstm_scratch_size_and_errors(B):
+    lib = B.raw()
+    d = B.dims
+    up = lambda v: (v + 63) // 64 * 64
+    for (seq, batch, H, direction) in [(1, 1, 1, 0), (7, 3, 33, 1), (16, 32, 128, 2)]:
+        per = up(seq * batch * 4 * H) + up(batch * 4 * H) + 3 * up(batch * H) + up(4 * H)
+        assert lib.onnx_lstm_scratch_bytes(d((seq, batch, 5)), H, direction) == 4 * per * (2 if direction == 2 else 1)
+    x, w, r, y, sc = (ctypes.c_void_p(a << 20) for a in (1, 2, 3, 4, 64))
+    args = lambda **kw: [kw.get("x", x), d((3, 2, 4)), w, r, None, None, None, kw.get("H", 2), kw.get("dir", 0), kw.get("y", y), None, None,
+                         kw.get("sc", sc), kw.get("n", 1 << 20), None]
+    assert lib.onnx_lstm(*args(H=0)) == 4
+    assert lib.onnx_lstm(*args(dir=5)) == 4
+    assert lib.onnx_lstm(*args(x=None)) == 1
+    assert lib.onnx_lstm(*args(y=None)) == 1
+    assert lib.onnx_lstm(*args(n=16)) == 1
+    assert lib.onnx_lstm(*args(sc=ctypes.c_void_p((64 << 20) + 64))) == 4
+    assert lib.onnx_lstm(*args(sc=x)) == 6
+    assert "lstm" in B.onnx_last_error()
