@@ -228,14 +228,21 @@ onnx_status onnx_conv(const float* X, const int64_t x_dims[4], const float* W, c
     p.y_zs = Mg * P; p.bias_zs = Mg; p.y_rs = P;
     p.col_images = 1; p.colP = FastDiv::make((uint32_t)P); p.y_img = M * P; p.b_img = C * H * Wd;
     p.alpha = 1.f; p.beta = 1.f; p.bias_mode = BIAS_ROW; p.bias_cs = 0; p.relu = act == ONNX_ACT_RELU;
-    const bool pointwise = kH == 1 && kW == 1 && strides[0] == 1 && strides[1] == 1 && pads[0] == 0 &&
-                           pads[1] == 0 && pads[2] == 0 && pads[3] == 0;
+    const bool unpadded_1x1 = kH == 1 && kW == 1 && pads[0] == 0 && pads[1] == 0 && pads[2] == 0 && pads[3] == 0;
+    const bool pointwise = unpadded_1x1 && strides[0] == 1 && strides[1] == 1;
     int bkind, vec;
     const bool a_vec = (K % 4 == 0) && aligned16(W);
     if (pointwise) {
         bkind = LOAD_RC;
         p.b_ld = H * Wd;
         vec = (a_vec && P % 4 == 0 && aligned16(X)) ? 4 : 1;
+    } else if (unpadded_1x1) {
+        // strided 1x1 (ResNet's projection shortcuts): rows of B are still whole planes apart
+        bkind = LOAD_RCS;
+        p.b_ld = H * Wd;
+        vec = a_vec ? 4 : 1;
+        p.ic.W = (int)Wd; p.ic.sH = g.sH; p.ic.sW = g.sW;
+        p.ic.OW = FastDiv::make((uint32_t)OW);
     } else {
         bkind = LOAD_IM2COL;
         p.b_ld = 0;

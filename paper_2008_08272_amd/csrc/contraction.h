@@ -19,6 +19,10 @@
 //           of a 1x1 stride-1 unpadded conv).  LDS holds [k][rows+8]; lanes read along rows.
 //   IM2COL  B only: element (k, j) is gathered from the NCHW input with pads, strides,
 //           dilations and group resolved in the address computation.  LDS as RC.
+//   RCS     B only: the input of a strided, unpadded 1x1 convolution.  As RC, except that
+//           column j (an output pixel) sits at input pixel (oh*sH, ow*sW), so neighbouring
+//           columns are not neighbours in memory and are fetched one value at a time; a k row
+//           is still one plane further, so no per-element address arithmetic is needed.
 // Because both operands of one MFMA must carry the same k, and a KC lane holds 4 consecutive
 // k, the 8 k of a half-step are dealt as  k = 4*(lane/32) + s  to MFMA number s = 0..3.
 //
@@ -41,7 +45,7 @@ constexpr int KC_PAD = 4;            // extra floats per row of a KC tile
 constexpr int MAX_BATCH_DIMS = 6;
 constexpr int NUM_XCD = 8;
 
-enum { LOAD_KC = 0, LOAD_RC = 1, LOAD_IM2COL = 2 };
+enum { LOAD_KC = 0, LOAD_RC = 1, LOAD_IM2COL = 2, LOAD_RCS = 3 };
 enum { BIAS_NONE = 0, BIAS_ROW = 1, BIAS_COL = 2, BIAS_FULL = 3 };
 
 // Unsigned division by a run-time constant d >= 1 for numerators below 2^31:
@@ -185,11 +189,16 @@ struct TileLoader {
             const int j = row0 + fast * VEC;
             col_ok = active && j < rows_total;
             const uint32_t jj = col_ok ? (uint32_t)j : (uint32_t)row0;
-            if (KIND == LOAD_RC) {
+            if (KIND == LOAD_RC || KIND == LOAD_RCS) {
                 if (images) {
                     uint32_t n0_, p0_, n, px;
                     cp.colP.divmod((uint32_t)row0, n0_, p0_);
                     cp.colP.divmod(jj, n, px);
+                    if (KIND == LOAD_RCS) {               // output pixel -> input pixel of the strided 1x1 window
+                        uint32_t oh, ow;
+                        cp.ic.OW.divmod(px, oh, ow);
+                        px = oh * (uint32_t)(cp.ic.sH * cp.ic.W) + ow * (uint32_t)cp.ic.sW;
+                    }
                     base = p + (int64_t)n0_ * cp.b_img;
                     voff[0] = (uint32_t)((int)(n - n0_) * (int)cp.b_img + (int)px + slow0 * ld) * 4u;
                 } else {
@@ -227,7 +236,7 @@ struct TileLoader {
             const bool k_ok = k0 + fast * VEC < K;
 #pragma unroll
             for (int p = 0; p < NLOAD; ++p) load<S>(rsrc, k_ok ? voff[p] : OOB, k0 * 4, p);
-        } else if constexpr (KIND == LOAD_RC) {
+        } else if constexpr (KIND == LOAD_RC || KIND == LOAD_RCS) {
             // the resource is re-based at row k0 so that offsets stay small whatever K is
             const __amdgpu_buffer_rsrc_t r = tile_rsrc(base + (int64_t)k0 * ld);
 #pragma unroll
@@ -612,7 +621,7 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
     constexpr int TM = WTM / 32, TN = WTN / 32;     // 32x32 accumulators per wavefront
     static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "sub-tile of 32x32 blocks");
     static_assert(BK % 8 == 0, "K step is a multiple of the 8-wide half-step");
-    constexpr int BVEC = (BKIND == LOAD_IM2COL) ? 1 : VEC;
+    constexpr int BVEC = (BKIND == LOAD_IM2COL || BKIND == LOAD_RCS) ? 1 : VEC;
     // Steps the global loads run ahead of the MFMAs.  Two hides the memory latency behind a whole
     // step of MFMAs; one where a step is long anyway (BK = 32: measured 1-2 % faster) or where
     // the second staging set would not fit in the 128 registers a 1024-thread workgroup has.

@@ -78,6 +78,7 @@ hipError_t launch_contraction(ContractionParams& p, int akind, int bkind, int ve
     ONNXHIP_CASE(LOAD_RC, LOAD_KC)
     ONNXHIP_CASE(LOAD_RC, LOAD_RC)
     ONNXHIP_CASE(LOAD_KC, LOAD_IM2COL)
+    ONNXHIP_CASE(LOAD_KC, LOAD_RCS)
 #undef ONNXHIP_CASE
     return hipErrorInvalidValue;
 }

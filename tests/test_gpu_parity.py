@@ -184,6 +184,8 @@ CONV_CASES = [
     (2, 64, 12, 12, 96, 1, 1, (0, 0, 0, 0), (1, 1), (1, 1), 1),      # pointwise fast path (16-byte loads)
     (2, 64, 9, 7, 96, 1, 1, (0, 0, 0, 0), (1, 1), (1, 1), 1),        # pointwise, P = 63 (scalar loads)
     (2, 64, 12, 12, 96, 1, 1, (0, 0, 0, 0), (2, 2), (1, 1), 1),      # strided 1x1 (projection shortcut)
+    (3, 20, 13, 11, 40, 1, 1, (0, 0, 0, 0), (3, 2), (1, 1), 1),      # strided 1x1, unequal strides, odd extents
+    (2, 64, 14, 14, 128, 1, 1, (0, 0, 0, 0), (2, 2), (1, 1), 2),     # strided 1x1 with 2 groups
     (2, 64, 12, 12, 64, 1, 1, (1, 1, 1, 1), (1, 1), (1, 1), 4),      # padded 1x1 with 4 groups
     (1, 24, 30, 30, 160, 3, 3, (2, 2, 2, 2), (1, 1), (2, 2), 1),     # dilated, > 128 rows
     (5, 40, 15, 15, 200, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 1),     # 128x128 tiles with tails
