@@ -4,8 +4,11 @@ Headline (one JSON line): the ONNX Gemm sweep (M=N=K in {1024, 2048, 4096}, tran
 alpha=beta=1), fp32, inputs resident in HBM; one step = the three Gemms.  The same line carries
   roofline      the matrix-core kernel on the 4096 case against the fp32 MFMA peak, from HIP
                 events recorded around that launch inside the timed region;
-  cpu_baseline  the CPU oracle timed on a row sample of the 4096 case on this box's host cores;
-  details       per-size TFLOP/s, ResNet-50 img/s at batch 32 and 1, attribute-sweep cases.
+  cpu_baseline  the CPU oracle timed on one whole step on this box's host cores;
+  details       per-size TFLOP/s; ResNet-50 img/s at batch 32, 1 and a batch sweep, with the per-layer
+                sum of rooflines; the attribute-sweep convolutions and MatMuls; the 16-bit Gemm; LSTM;
+                the HBM-bound operators (element-wise, reductions, softmax, pooling, depthwise
+                convolution) on buffer sets larger than the Infinity Cache.
 """
 import argparse
 import json
@@ -110,7 +113,7 @@ def main():
                          "times each, print their mean times and exit")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+        print("bench.py: this library runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
 

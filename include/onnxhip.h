@@ -40,7 +40,7 @@ typedef enum {
     ONNX_ERR_RANK = 2,        /* a rank outside what the operator accepts                  */
     ONNX_ERR_SHAPE = 3,       /* dimensions inconsistent with each other or with y_dims    */
     ONNX_ERR_ATTR = 4,        /* stride/dilation/kernel < 1, pad < 0, pad >= window (pools)*/
-    ONNX_ERR_UNSUPPORTED = 5, /* a valid request this build does not implement             */
+    ONNX_ERR_UNSUPPORTED = 5, /* a valid request this library does not implement           */
     ONNX_ERR_ALIAS = 6,       /* output overlaps an input                                  */
     ONNX_ERR_DEVICE = 7       /* the HIP runtime reported an error                         */
 } onnx_status;
@@ -209,7 +209,7 @@ typedef enum { ONNX_F32 = 0, ONNX_F16 = 1, ONNX_BF16 = 2 } onnx_dtype;
 /*
  * ONNX Gemm on 16-bit floating-point inputs (the operator definitions admit F16 tensors,
  * Section 3.1): Y = alpha * A * B' + beta * C with A [M,K] and B [N,K] (transA = 0, transB = 1:
- * both operands K-contiguous; other layouts are ONNX_ERR_UNSUPPORTED in this build) stored as
+ * both operands K-contiguous; other layouts are ONNX_ERR_UNSUPPORTED) stored as
  * in_type.  Products are exact and summed in fp32; C (NULL, or fp32 broadcastable to [M,N] as
  * for onnx_gemm) and the epilogue are fp32; Y is stored as out_type: ONNX_F32, or in_type with
  * round-to-nearest-even.  K must be a multiple of 8 and A, B 16-byte aligned.

@@ -20,6 +20,11 @@ entries of ``inputs`` / ``weights`` or to an earlier node's ``y``:
   reshape  x shape y                       (a view of dense row-major data)
   gemm     a b c alpha beta transA transB relu y
   matmul   a b y
+
+Graphs "as an exporter writes them" (the inputs of the graph-level passes) also use
+
+  batchnorm x scale bias mean var eps y      relu x y        add a b y       identity x y
+  leakyrelu x alpha y     abs x y     reducesum / reducel1 x axes keepdims y     softmax x axis y
 """
 import numpy as np
 
