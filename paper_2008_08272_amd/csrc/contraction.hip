@@ -60,7 +60,13 @@ int pick_split(int64_t tiles, int nk, int64_t tile_elems, double overhead) {
         if (s > 1 && tiles * s * tile_elems > w.partial_floats) break;
         const double per_cu = (double)((tiles * s + 255) / 256);
         const double steps = (double)((nk + s - 1) / s) + overhead + (s > 1 ? 0.25 * s + 6.0 : 0.0);
-        const double cost = per_cu * steps;
+        // A CU that holds a single 4-wavefront workgroup keeps its matrix pipes busy less than a
+        // third of the time (every wait of that one wavefront per SIMD is exposed); with several
+        // resident workgroups they fill each other's waits.  Fractions measured on ResNet-50
+        // (batch 1, 8 and 32 all run fastest with these).
+        static const double eff[5] = {1.0, 0.3, 0.5, 0.6, 0.7};
+        const int occ = per_cu < 4.0 ? (int)per_cu : 4;
+        const double cost = per_cu * steps / (tile_elems <= 64 * 64 ? eff[occ] : eff[4]);
         if (s == 1 || cost < best_cost * 0.97) { best = s; best_cost = cost; }
     }
     return best;

@@ -28,7 +28,8 @@ const Workspace& workspace();
 int report_error(int status, const char* message);
 
 // How many ways to split the K walk of `tiles` workgroup tiles of `tile_elems` outputs and `nk`
-// K steps each, so that the 256 CUs are evenly loaded; 1 when the workspace cannot hold it.
+// K steps each, so that the 256 CUs are evenly loaded and hold enough workgroups to overlap each
+// other's waits; 1 when the workspace cannot hold it.
 // `overhead` is a workgroup's fixed cost (prologue, epilogue) in units of one K step.
 int pick_split(int64_t tiles, int nk, int64_t tile_elems, double overhead);
 
