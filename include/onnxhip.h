@@ -57,8 +57,10 @@ const char* onnx_last_error(void);
  * have been lowered to loops over buffers; here the caller decides it).  The library never
  * allocates: when a workspace is set, products whose output has too few tiles to occupy the
  * GPU split their K range over several workgroups, which park partial tiles in it, and a
- * second kernel on the same stream adds them and runs the epilogue; without a workspace those
- * products run unsplit.  `device_ptr` is device memory (256-byte aligned, at least 1 MiB; 64
+ * second kernel on the same stream adds them and runs the epilogue (the same is done for the
+ * few tiles by which a tile count exceeds a multiple of the 256 CUs, and onnx_reducesum uses it
+ * for the chunk sums of a long sum into few outputs); without a workspace those products run
+ * unsplit.  `device_ptr` is device memory (256-byte aligned, at least 1 MiB; 64
  * MiB serves every workload here) that the caller keeps alive and does not touch while calls
  * are in flight; it needs no initialisation.  All calls share it, so operators that may use it
  * must not run concurrently on different streams.  NULL or 0 bytes removes the workspace.
