@@ -231,7 +231,11 @@ __global__ __launch_bounds__(256) void conv_rows_kernel(const float* __restrict_
 // MaxPool on the same wavefront-per-strip scheme (vertical dilation 1).  Taps outside the image
 // never take part; taps are visited kh outer, kw inner and a later tap replaces the running
 // maximum only when strictly greater, so Indices reports the first maximum.
-template <int KH, int KW, int S, int R, bool IDX>
+// PAIR (horizontal stride 2, dilation 1, left pad KW - 2, even W, one column chunk per row): the
+// taps at input columns 2*ow and 2*ow + 1 come from one 8-byte load per lane, which makes the
+// wavefront's load one contiguous 512-byte run instead of three runs of every other element;
+// for KW = 3 the tap at 2*ow - 1 is the left neighbour lane's second value.
+template <int KH, int KW, int S, int R, bool IDX, bool PAIR>
 __global__ __launch_bounds__(256) void maxpool_rows_kernel(const float* __restrict__ X, float* __restrict__ Y,
                                                            int64_t* __restrict__ indices, WindowGeom g,
                                                            StripMap sm) {
@@ -259,14 +263,33 @@ __global__ __launch_bounds__(256) void maxpool_rows_kernel(const float* __restri
     const int64_t plane_abs = (int64_t)pc * HW;
     const __amdgpu_buffer_rsrc_t rs = plane_rsrc(X + plane_abs, HW);
     float x[ROWS_IN][KW];
+    if (PAIR) {
+        typedef float floatx2 __attribute__((ext_vector_type(2)));
+        const uint32_t pair_off = (ow < g.OW && 2 * ow + 1 < g.W) ? (uint32_t)(2 * ow) * 4u : OUT;
+        floatx2 v[ROWS_IN];
 #pragma unroll
-    for (int i = 0; i < ROWS_IN; ++i) {
-        const int ih = ih0 + i;
-        const bool row_ok = (unsigned)ih < (unsigned)g.H;              // uniform
+        for (int i = 0; i < ROWS_IN; ++i) {
+            const int ih = ih0 + i;
+            const bool row_ok = (unsigned)ih < (unsigned)g.H;          // uniform
+            v[i] = __builtin_bit_cast(floatx2, __builtin_amdgcn_raw_buffer_load_b64(
+                       rs, (int)(row_ok ? pair_off : OUT), row_ok ? ih * g.W * 4 : 0, 0));
+        }
 #pragma unroll
-        for (int kw = 0; kw < KW; ++kw)
-            x[i][kw] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                           rs, (int)(row_ok ? voff[kw] : OUT), row_ok ? ih * g.W * 4 : 0, 0));
+        for (int i = 0; i < ROWS_IN; ++i) {
+            x[i][KW - 2] = v[i].x;
+            x[i][KW - 1] = v[i].y;
+            if (KW == 3) x[i][0] = __shfl_up(v[i].y, 1, 64);           // lane 0 has ow = 0: its left tap is padding
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < ROWS_IN; ++i) {
+            const int ih = ih0 + i;
+            const bool row_ok = (unsigned)ih < (unsigned)g.H;          // uniform
+#pragma unroll
+            for (int kw = 0; kw < KW; ++kw)
+                x[i][kw] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                               rs, (int)(row_ok ? voff[kw] : OUT), row_ok ? ih * g.W * 4 : 0, 0));
+        }
     }
     if (ow >= g.OW) return;
 #pragma unroll
@@ -540,10 +563,15 @@ hipError_t launch_maxpool(const float* X, float* Y, int64_t* indices, const Wind
     StripMap sm;
     if (shape && g.dH == 1 && g.sH == 2 && strip_map(g, (int64_t)g.N * g.C, 4, sm)) {
         const dim3 grid((sm.waves + 3) / 4), block(256);
-#define ONNXHIP_POOL(K_)                                                                                           \
-    if (indices) hipLaunchKernelGGL((maxpool_rows_kernel<K_, K_, 2, 4, true>), grid, block, 0, stream, X, Y, indices, g, sm); \
-    else hipLaunchKernelGGL((maxpool_rows_kernel<K_, K_, 2, 4, false>), grid, block, 0, stream, X, Y, indices, g, sm);
-        if (shape == 3) { ONNXHIP_POOL(3) } else { ONNXHIP_POOL(2) }
+        // 8-byte loads of column pairs: every row of every plane starts 8-byte aligned, the pair
+        // (2*ow, 2*ow + 1) holds the window's last two taps, and the lane to the left holds the first
+        const bool pair = g.sW == 2 && g.dW == 1 && g.pL == shape - 2 && g.W % 2 == 0 && g.OW <= 64 &&
+                          (reinterpret_cast<uintptr_t>(X) & 7u) == 0;
+#define ONNXHIP_POOL(K_, P_)                                                                                       \
+    if (indices) hipLaunchKernelGGL((maxpool_rows_kernel<K_, K_, 2, 4, true, P_>), grid, block, 0, stream, X, Y, indices, g, sm); \
+    else hipLaunchKernelGGL((maxpool_rows_kernel<K_, K_, 2, 4, false, P_>), grid, block, 0, stream, X, Y, indices, g, sm);
+        if (shape == 3) { if (pair) { ONNXHIP_POOL(3, true) } else { ONNXHIP_POOL(3, false) } }
+        else { if (pair) { ONNXHIP_POOL(2, true) } else { ONNXHIP_POOL(2, false) } }
 #undef ONNXHIP_POOL
         return hipGetLastError();
     }

@@ -303,6 +303,11 @@ POOL_CASES = [
     (2, 2, 19, 90, (3, 3), (1, 0, 0, 1), (2, 1), (1, 2), 1),
     (1, 3, 9, 70, (2, 2), (1, 1, 1, 1), (2, 3), (1, 1), 0),
     (2, 4, 3, 3, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),
+    # even width, horizontal stride 2, left pad = kernel - 2: the 8-byte paired loads
+    (2, 3, 12, 20, (2, 2), (0, 0, 0, 0), (2, 2), (1, 1), 0),
+    (1, 2, 16, 24, (3, 3), (1, 1, 0, 2), (2, 2), (1, 1), 1),
+    (2, 2, 9, 128, (3, 3), (0, 1, 1, 1), (2, 2), (1, 1), 0),
+    (1, 2, 11, 130, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),        # 65 output columns: two chunks, plain loads
 ]
 
 
