@@ -160,7 +160,10 @@ __device__ inline __amdgpu_buffer_rsrc_t plane_rsrc(const float* plane, int HW) 
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(plane), 0, HW * 4, 0x00020000);
 }
 
-template <int KH, int KW, int S, int D, int R>
+// SHUF (KW = 3, horizontal stride and dilation 1, left pad 1, W <= 64 so that one wavefront spans
+// a row): each lane loads only the input value above its own column; the taps to the left and
+// right are the neighbouring lanes' values (zero outside the image).
+template <int KH, int KW, int S, int D, int R, bool SHUF>
 __global__ __launch_bounds__(256) void conv_rows_kernel(const float* __restrict__ X,
                                                         const float* __restrict__ Wt,
                                                         const float* __restrict__ B,
@@ -194,14 +197,33 @@ __global__ __launch_bounds__(256) void conv_rows_kernel(const float* __restrict_
     for (int c = 0; c < Cg; ++c) {
         const __amdgpu_buffer_rsrc_t rs = plane_rsrc(X + ((int64_t)n * g.C + grp * Cg + c) * HW, HW);
         float x[ROWS_IN][KW];
+        if (SHUF) {
+            const uint32_t centre = ow < g.W ? (uint32_t)ow * 4u : OUT;
+            float v[ROWS_IN];
 #pragma unroll
-        for (int i = 0; i < ROWS_IN; ++i) {
-            const int ih = ih0 + i;
-            const bool row_ok = (unsigned)ih < (unsigned)g.H;          // uniform
+            for (int i = 0; i < ROWS_IN; ++i) {
+                const int ih = ih0 + i;
+                const bool row_ok = (unsigned)ih < (unsigned)g.H;      // uniform
+                v[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                           rs, (int)(row_ok ? centre : OUT), row_ok ? ih * g.W * 4 : 0, 0));
+            }
 #pragma unroll
-            for (int kw = 0; kw < KW; ++kw)
-                x[i][kw] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                               rs, (int)(row_ok ? voff[kw] : OUT), row_ok ? ih * g.W * 4 : 0, 0));
+            for (int i = 0; i < ROWS_IN; ++i) {
+                const float left = __shfl_up(v[i], 1, 64), right = __shfl_down(v[i], 1, 64);
+                x[i][0] = lane > 0 ? left : 0.f;
+                x[i][KW / 2] = v[i];
+                x[i][KW - 1] = lane < 63 ? right : 0.f;                 // lanes at and beyond W loaded zeros
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < ROWS_IN; ++i) {
+                const int ih = ih0 + i;
+                const bool row_ok = (unsigned)ih < (unsigned)g.H;      // uniform
+#pragma unroll
+                for (int kw = 0; kw < KW; ++kw)
+                    x[i][kw] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                   rs, (int)(row_ok ? voff[kw] : OUT), row_ok ? ih * g.W * 4 : 0, 0));
+            }
         }
         float w[KH * KW];                                              // uniform: scalar loads
 #pragma unroll
@@ -334,8 +356,13 @@ template <int S, int D>
 static hipError_t launch_conv_rows(const float* X, const float* W, const float* B, const float* residual,
                                    float* Y, const WindowGeom& g, int M, int Cg, int group, int relu,
                                    const StripMap& sm, hipStream_t stream) {
-    hipLaunchKernelGGL((conv_rows_kernel<3, 3, S, D, 8>), dim3((sm.waves + 3) / 4), dim3(256), 0, stream, X, W, B,
-                       residual, Y, g, M, Cg, M / group, relu, sm);
+    // one load per row instead of three when a wavefront spans the whole row (see SHUF)
+    if (g.sW == 1 && g.dW == 1 && g.pL == 1 && g.W <= 64 && g.OW <= 64)
+        hipLaunchKernelGGL((conv_rows_kernel<3, 3, S, D, 8, true>), dim3((sm.waves + 3) / 4), dim3(256), 0, stream, X, W,
+                           B, residual, Y, g, M, Cg, M / group, relu, sm);
+    else
+        hipLaunchKernelGGL((conv_rows_kernel<3, 3, S, D, 8, false>), dim3((sm.waves + 3) / 4), dim3(256), 0, stream, X,
+                           W, B, residual, Y, g, M, Cg, M / group, relu, sm);
     return hipGetLastError();
 }
 

@@ -197,6 +197,9 @@ CONV_CASES = [
     (1, 4, 19, 66, 4, 3, 3, (2, 2, 2, 2), (1, 3), (2, 2), 4),        # vertical dilation 2, horizontal stride 3
     (3, 8, 9, 9, 8, 3, 3, (1, 1, 1, 1), (3, 1), (1, 1), 8),          # vertical stride 3: falls back to the plane kernel
     (2, 4, 2, 2, 4, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 4),          # plane smaller than the filter
+    (2, 6, 17, 64, 6, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 6),        # full-width rows: neighbour lanes supply the side taps
+    (2, 4, 9, 64, 4, 3, 3, (0, 1, 2, 2), (2, 1), (1, 1), 4),         # 65 output columns: two chunks, plain loads
+    (1, 8, 20, 33, 16, 3, 3, (2, 1, 0, 0), (1, 1), (2, 1), 4),       # right pad 0, vertical dilation 2, 2 channels per group
 ]
 
 
