@@ -562,3 +562,98 @@ def test_unfused_graphs_through_the_passes(lib):
             if nd["op"] != "reshape" and nd["y"] in exact:
                 worst = max(worst, rel_err(r.t[nd["y"]].cpu().numpy(), exact[nd["y"]]))
         assert worst <= REL_TOL
+
+
+# ------------------------------------------------------------------------------ seeded random sweeps
+
+def _random_conv_case(rng):
+    kH, kW = [(1, 1), (3, 3), (3, 3), (3, 3), (5, 5), (2, 3), (7, 7), (1, 3)][int(rng.integers(0, 8))]
+    group = int(rng.choice([1, 1, 1, 2, 4]))
+    cg = int(rng.choice([1, 3, 4, 8, 12, 16, 32]))
+    mg = int(rng.choice([1, 4, 16, 24, 64, 80]))
+    C, M = cg * group, mg * group
+    sH, sW = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+    dH, dW = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+    pads = tuple(int(rng.integers(0, 3)) for _ in range(4))
+    eh, ew = (kH - 1) * dH + 1, (kW - 1) * dW + 1
+    H = int(rng.integers(max(1, eh - pads[0] - pads[2]), 40))
+    W = int(rng.integers(max(1, ew - pads[1] - pads[3]), 40))
+    N = int(rng.integers(1, 5))
+    return (N, C, H, W, M, kH, kW, pads, (sH, sW), (dH, dW), group)
+
+
+def test_conv_random_attribute_sweep(lib):
+    """120 seeded random convolutions over kernel sizes, groups, channel counts, pads, strides and
+    dilations: whatever path the selector takes (matrix cores with the LDS patch, the gather or
+    the row-contiguous loaders, row-strip, plane or direct kernels), the result must match."""
+    rng = np.random.default_rng(20260)
+    for it in range(120):
+        case = _random_conv_case(rng)
+        N, C, H, W, M, kH, kW, pads, st, dl, g = case
+        announce("conv sweep", it, case)
+        X = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+        Wt = rng.uniform(-1, 1, (M, C // g, kH, kW)).astype(np.float32)
+        Bv = rng.uniform(-1, 1, (M,)).astype(np.float32) if it % 3 else None
+        relu = bool(it % 2)
+        ref = oracle.conv(X, Wt, Bv, pads, st, dl, g, relu=relu)
+        R = rng.uniform(-1, 1, ref.shape).astype(np.float32) if it % 4 == 0 else None
+        if R is not None:
+            ref = oracle.conv(X, Wt, Bv, pads, st, dl, g, residual=R, relu=relu)
+        got = host(lib.onnx_conv(dev(X), dev(Wt), dev(Bv), pads, st, dl, g, residual=dev(R), act=int(relu)))
+        assert got.shape == ref.shape, case
+        assert rel_err(got, ref) <= REL_TOL, case
+
+
+def test_gemm_matmul_random_sweep(lib):
+    rng = np.random.default_rng(20261)
+    for it in range(60):
+        M, N, K = (int(rng.integers(1, 400)) for _ in range(3))
+        if it % 5 == 0:
+            K = int(rng.integers(400, 3000))
+        tA, tB = int(rng.integers(0, 2)), int(rng.integers(0, 2))
+        announce("gemm sweep", it, M, N, K, tA, tB)
+        A = rng.uniform(-1, 1, (K, M) if tA else (M, K)).astype(np.float32)
+        B = rng.uniform(-1, 1, (N, K) if tB else (K, N)).astype(np.float32)
+        cshape = [(1, N), (M, 1), (M, N), (N,), None][it % 5]
+        C = rng.uniform(-1, 1, cshape).astype(np.float32) if cshape else None
+        alpha, beta = float(np.float32(rng.uniform(-2, 2))), float(np.float32(rng.uniform(-2, 2)))
+        ref, S = oracle.gemm(A, B, C, alpha, beta, tA, tB, relu=bool(it % 2), want_scale=True)
+        got = host(lib.onnx_gemm(dev(A), dev(B), dev(C), alpha, beta, tA, tB, act=it % 2))
+        assert rel_err(got, ref) <= REL_TOL
+        assert within_rounding_bound(got, ref, S, K + 2)
+    for it in range(20):
+        batch = tuple(int(rng.integers(1, 4)) for _ in range(int(rng.integers(0, 3))))
+        m, n, k = (int(rng.integers(1, 90)) for _ in range(3))
+        sa = tuple(b if rng.random() < 0.7 else 1 for b in batch) + (m, k)
+        sb = tuple(b if rng.random() < 0.7 else 1 for b in batch)[int(rng.integers(0, len(batch) + 1)):] + (k, n)
+        announce("matmul sweep", it, sa, sb)
+        A = rng.uniform(-1, 1, sa).astype(np.float32)
+        B = rng.uniform(-1, 1, sb).astype(np.float32)
+        ref = oracle.matmul(A, B)
+        got = host(lib.onnx_matmul(dev(A), dev(B)))
+        assert got.shape == ref.shape
+        assert rel_err(got, ref) <= REL_TOL
+
+
+def test_pool_random_sweep(lib):
+    rng = np.random.default_rng(20262)
+    for it in range(80):
+        kH, kW = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        sH, sW = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        dH, dW = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+        pads = (int(rng.integers(0, kH)), int(rng.integers(0, kW)), int(rng.integers(0, kH)), int(rng.integers(0, kW)))
+        ceil = int(rng.integers(0, 2))
+        H = int(rng.integers((kH - 1) * dH + 1, 50))
+        W = int(rng.integers((kW - 1) * dW + 1, 140))
+        N, C = int(rng.integers(1, 3)), int(rng.integers(1, 5))
+        announce("pool sweep", it, (N, C, H, W), (kH, kW), pads, (sH, sW), (dH, dW), ceil)
+        X = rng.integers(-4, 5, (N, C, H, W)).astype(np.float32) + (rng.random((N, C, H, W)) < 0.5) * np.float32(0.5)
+        X = X.astype(np.float32)
+        ref, iref = oracle.maxpool(X, (kH, kW), pads, (sH, sW), (dH, dW), ceil)
+        got, igot = lib.onnx_maxpool(dev(X), (kH, kW), pads, (sH, sW), (dH, dW), ceil, want_indices=True)
+        assert np.array_equal(host(got), ref)
+        assert np.array_equal(host(igot), iref)
+        for cip in (0, 1):
+            ra = oracle.avgpool(X, (kH, kW), pads, (sH, sW), ceil, cip)
+            ga = host(lib.onnx_avgpool(dev(X), (kH, kW), pads, (sH, sW), ceil, cip))
+            assert rel_err(ga, ra) <= REL_TOL
