@@ -17,8 +17,9 @@
 // reads patch rows start(a) + (oh - first oh of a)*sH + kh*dH, columns ow*sW + kw*dW.
 //
 // K is walked 4 channels at a time.  One MFMA (32x32x2) consumes two k: lanes 0-31 supply
-// channel 2c', lanes 32-63 channel 2c'+1, both at the same tap; A (filters, [row][4*KH*KW+1]
-// in LDS) and B (patch, [channel][patch row][patch col]) use the same dealing.
+// channel 2c', lanes 32-63 channel 2c'+1, both at the same tap; A (filters, in LDS as
+// [row][channel][taps padded to a multiple of 4], so that a lane fetches its channel's taps
+// with 16-byte reads) and B (patch, [channel][patch row][patch col]) use the same dealing.
 #pragma once
 #include <type_traits>
 
@@ -46,14 +47,15 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
     constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int KHW = KH * KW;
     constexpr int KA = WIN_CB * KHW;            // filter values per row per step (contiguous in W)
-    constexpr int LDA = KA + 1;                 // odd row stride: conflict-free column reads
+    constexpr int CH = (KHW + 3) / 4 * 4;       // floats per (row, channel) in LDS: the taps, padded to 16 bytes
+    constexpr int LDA = WIN_CB * CH + 4;        // row stride: 16-byte fragment reads of 8 neighbouring rows hit disjoint banks
     constexpr int NA4 = BM * KA / 4;            // 16-byte loads per A tile
     constexpr int PA = (NA4 + NT - 1) / NT;
     constexpr int NMFMA = KHW * TM * TN;        // MFMAs per channel pair
-    constexpr int NFRAG = KHW * (TM + TN);      // LDS reads per channel pair
+    constexpr int NFRAG = CH / 4 * TM + KHW * TN;   // LDS reads per channel pair
     static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "sub-tile of 32x32 blocks");
 
-    __shared__ float lds_a[2][BM * LDA + 4];    // + a slot that absorbs the stores of surplus threads
+    __shared__ __attribute__((aligned(16))) float lds_a[2][BM * LDA + 4];   // + a slot that absorbs the stores of surplus threads
     __shared__ float lds_b[2][NPB * NT];
 
     TileWork w;
@@ -78,14 +80,18 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
     const float* a_base = cp.A + a_off + (int64_t)m0 * cp.K;
     const __amdgpu_buffer_rsrc_t ra = tile_rsrc(a_base);
     uint32_t voff_a[PA];
-    int dst_a[PA];
+    int dst_a[PA][4];                               // LDS position of each of a chunk's 4 values
 #pragma unroll
     for (int p = 0; p < PA; ++p) {
         const int e = t + p * NT;
         const int row = e / KHW, q = e % KHW;        // KA/4 == KHW chunks per row
         const bool ok = e < NA4 && m0 + row < cp.M;
         voff_a[p] = ok ? (uint32_t)(row * cp.K + q * 4) * 4u : OOB;
-        dst_a[p] = e < NA4 ? row * LDA + q * 4 : BM * LDA;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int k = q * 4 + j;                     // position in the row's KA = 4 channels x KHW taps
+            dst_a[p][j] = e < NA4 ? row * LDA + (k / KHW) * CH + k % KHW : BM * LDA;
+        }
     }
     // ---- patch loader: thread -> (channel, patch row, patch col), fixed for the whole K walk
     const float* b_base = cp.B + b_off + (int64_t)img_first * g.image_stride;
@@ -112,7 +118,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
     // ---- where this lane reads its operands for the MFMAs
     int rd_a[TM], rd_b[TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) rd_a[i] = (wm * WTM + i * 32 + li) * LDA + h * KHW;
+    for (int i = 0; i < TM; ++i) rd_a[i] = (wm * WTM + i * 32 + li) * LDA + h * CH;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         int col = n0 + wn * WTN + j * 32 + li;
@@ -161,18 +167,24 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
         constexpr int s = decltype(S)::value;
 #pragma unroll
         for (int p = 0; p < PA; ++p) {
-            float* d = lds_a[buf] + dst_a[p];
-            d[0] = reg_a[s][p].x; d[1] = reg_a[s][p].y; d[2] = reg_a[s][p].z; d[3] = reg_a[s][p].w;
+            float* d = lds_a[buf];
+            d[dst_a[p][0]] = reg_a[s][p].x; d[dst_a[p][1]] = reg_a[s][p].y;
+            d[dst_a[p][2]] = reg_a[s][p].z; d[dst_a[p][3]] = reg_a[s][p].w;
         }
 #pragma unroll
         for (int p = 0; p < NPB; ++p) lds_b[buf][t + p * NT] = reg_b[s][p];
     };
-    float fa[2][KHW][TM], fb[2][KHW][TN];
+    float fa[2][CH][TM], fb[2][KHW][TN];
     auto frags = [&](int f, const float* sa, const float* sb, int cc) {
 #pragma unroll
         for (int tap = 0; tap < KHW; ++tap) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) fa[f][tap][i] = sa[rd_a[i] + 2 * cc * KHW + tap];
+            for (int i = 0; i < TM; ++i) {
+                if (tap % 4 == 0) {                      // the lane's channel: CH / 4 reads of 16 bytes
+                    const floatx4 v = *reinterpret_cast<const floatx4*>(sa + rd_a[i] + 2 * cc * CH + tap);
+                    fa[f][tap][i] = v.x; fa[f][tap + 1][i] = v.y; fa[f][tap + 2][i] = v.z; fa[f][tap + 3][i] = v.w;
+                }
+            }
 #pragma unroll
             for (int j = 0; j < TN; ++j) fb[f][tap][j] = sb[rd_b[j] + 2 * cc * g.plane + tap_b[tap]];
         }
