@@ -247,6 +247,14 @@ def main():
                                                    sum_of_layer_rooflines_ms=round(floor_ms, 4),
                                                    frac_of_layer_rooflines=round(floor_ms / ms, 4))
             del r
+        # the MNIST-shaped small CNN (5 calls, 1.6 MFLOP): pure launch latency
+        r = GraphRunner(workloads.small_cnn(), dev)
+        t_eager = time_call(r.run, iters=50, warm=10)
+        r.capture()
+        t_graph = time_call(r.replay, iters=50, warm=10)
+        details["small_cnn_b1"] = {"us_eager": round(t_eager[0] * 1e3, 2), "us_graph": round(t_graph[0] * 1e3, 2),
+                                   "calls": len(r.calls)}
+        del r
         # Gemm on 16-bit inputs (fp32 accumulation), against the 2.5 PFLOP/s dense fp16 / bf16 MFMA peak
         for kind, tdt in (("bf16", torch.bfloat16), ("f16", torch.float16)):
             for n in (4096, 8192):
