@@ -657,3 +657,34 @@ def test_pool_random_sweep(lib):
             ra = oracle.avgpool(X, (kH, kW), pads, (sH, sW), ceil, cip)
             ga = host(lib.onnx_avgpool(dev(X), (kH, kW), pads, (sH, sW), ceil, cip))
             assert rel_err(ga, ra) <= REL_TOL
+
+
+def test_overlapped_graph_matches_single_stream(lib):
+    """The two-stream schedule (projection shortcuts on a side stream, each stream with its own half
+    of the workspace) must give bit for bit what the single-stream run gives, eagerly and as a
+    replayed HIP graph with other work in between the replays."""
+    announce("overlapped runner")
+    from paper_2008_08272_amd.runner import GraphRunner
+    for batch in (1, 3):
+        m = workloads.resnet50(batch)
+        r = GraphRunner(m)
+        ref = r.run().clone()
+        torch.cuda.synchronize()
+        got = r.run_overlapped().clone()
+        torch.cuda.synchronize()
+        assert torch.equal(got, ref)
+        r.capture(overlap=True)
+        for rep in range(3):
+            r.output.zero_()
+            junk = torch.randn(1 << 20, device="cuda").sum()       # unrelated eager work between replays
+            out = r.replay().clone()
+            torch.cuda.synchronize()
+            assert torch.equal(out, ref), (batch, rep)
+            del junk
+        # a new input through the same graph
+        x2 = np.random.default_rng(5).standard_normal(m["inputs"]["x"].shape).astype(np.float32)
+        r.set_input("x", x2)
+        a = r.run().clone()
+        b = r.replay().clone()
+        torch.cuda.synchronize()
+        assert torch.equal(a, b) and not torch.equal(a, ref)
