@@ -399,10 +399,18 @@ def main():
             oracle.gemm(c["A"], c["B"], c["C"], 1.0, 1.0, 0, 1)
         dt = time.perf_counter() - t0
         threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        extra = {}
+        if not args.no_details:              # the same oracle on one ResNet-50 image (8.2 GFLOP), for the img/s figures
+            from oracle import chain
+            m1 = workloads.resnet50(1)
+            t0 = time.perf_counter()
+            chain.run(m1, keep=())
+            extra = {"resnet50_b1_seconds": round(time.perf_counter() - t0, 3)}
         cpu = {"value": round(flop_step / dt / 1e12, 6), "unit": "TFLOP/s", "cores": threads,
                "kind": "oracle", "seconds": round(dt, 2),
                "sample": "one whole step (the 1024^3, 2048^3 and 4096^3 Gemms) through the fp64-accumulating "
                          "C loop nest, OpenMP over output rows"}
+        cpu.update(extra)
 
     out = {"metric": "ONNX Gemm fp32 throughput on the Gemm sweep (M=N=K in 1024,2048,4096; transB=1, 1xN bias)",
            "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
