@@ -6,7 +6,6 @@ the graph's constant inputs are uploaded once, every activation buffer is alloca
 between.  Reshape is a view of dense row-major data and costs nothing.  All arithmetic
 happens inside the library's kernels; this module only prepares argument lists.
 """
-import ctypes
 
 import torch
 
