@@ -53,6 +53,14 @@ typedef enum { ONNX_ACT_NONE = 0, ONNX_ACT_RELU = 1 } onnx_act;
 const char* onnx_last_error(void);
 
 /*
+ * Which kernel instance the calling thread's most recent Conv / Gemm / MatMul launch on the
+ * matrix cores used, as text: family, tile (rows x columns x K step), wavefront grid
+ * (rows x columns x K slices), operand loader kinds and load widths, split factors.  Empty
+ * before the first such launch.  For tests and tuning; static thread-local storage.
+ */
+const char* onnx_last_launch(void);
+
+/*
  * Optional scratch memory (Section 3.1 notes that memory management is decided once operators
  * have been lowered to loops over buffers; here the caller decides it).  The library never
  * allocates: when a workspace is set, products whose output has too few tiles to occupy the
@@ -64,6 +72,9 @@ const char* onnx_last_error(void);
  * MiB serves every workload here) that the caller keeps alive and does not touch while calls
  * are in flight; it needs no initialisation.  All calls share it, so operators that may use it
  * must not run concurrently on different streams.  NULL or 0 bytes removes the workspace.
+ * The setting is process-wide: a call uses the workspace that was set when it was made (setting
+ * and reading are serialised against each other, so host threads never see a torn pointer/size
+ * pair), but two host threads that set different workspaces must order their calls themselves.
  * Results do not depend on it beyond fp32 summation order and are reproducible run to run.
  */
 onnx_status onnx_set_workspace(void* device_ptr, size_t bytes);

@@ -40,6 +40,7 @@ _lib.onnx_conv_infer.argtypes = [_i64p, _i64p, _i64p, _i64p, _i64p, _c64, _i64p]
 _lib.onnx_pool_infer.argtypes = [_i64p, _i64p, _i64p, _i64p, _i64p, _ci, _i64p]
 _lib.onnx_matmul_infer.argtypes = [_i64p, _ci, _i64p, _ci, _i64p, ctypes.POINTER(_ci)]
 _lib.onnx_conv.argtypes = [_vp, _i64p, _vp, _i64p, _vp, _i64p, _i64p, _i64p, _c64, _vp, _ci, _vp, _i64p, _vp]
+_lib.onnx_last_launch.restype = ctypes.c_char_p
 _lib.onnx_gemm.argtypes = [_vp, _i64p, _vp, _i64p, _vp, _i64p, _ci, _cf, _cf, _ci, _ci, _ci, _vp, _i64p, _vp]
 _lib.onnx_matmul.argtypes = [_vp, _i64p, _ci, _vp, _i64p, _ci, _vp, _i64p, _ci, _vp]
 _lib.onnx_maxpool.argtypes = [_vp, _i64p, _i64p, _i64p, _i64p, _i64p, _ci, _vp, _vp, _i64p, _vp]
@@ -90,6 +91,10 @@ def onnx_set_workspace(tensor):
 
 def onnx_last_error():
     return _lib.onnx_last_error().decode()
+
+
+def onnx_last_launch():
+    return _lib.onnx_last_launch().decode()
 
 
 def _check(st):

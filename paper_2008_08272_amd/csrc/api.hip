@@ -4,6 +4,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "../../include/onnxhip.h"
 #include "internal.h"
 
@@ -12,25 +14,12 @@ using namespace onnxhip;
 namespace {
 
 thread_local char g_err[320] = "";
+thread_local LaunchRecord g_launch = {};
+thread_local char g_launch_text[200] = "";
 
-onnx_status fail(onnx_status st, const char* fmt, ...) {
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(g_err, sizeof(g_err), fmt, ap);
-    va_end(ap);
-    return st;
-}
+#define fail(st, ...) static_cast<onnx_status>(fail_with((st), __VA_ARGS__))
 
 const int64_t kIntMax = 0x7fffffffLL;
-
-inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
-// byte ranges [a, a+na) and [b, b+nb) intersect
-inline bool overlaps(const void* a, int64_t na, const void* b, int64_t nb) {
-    if (!a || !b || na <= 0 || nb <= 0) return false;
-    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
-    return a0 < b0 + (uintptr_t)nb && b0 < a0 + (uintptr_t)na;
-}
 
 int64_t floordiv(int64_t a, int64_t b) {
     int64_t q = a / b;
@@ -74,6 +63,10 @@ void no_batch(ContractionParams& p) {
     p.ic.kHW = p.ic.kW = p.ic.OW = FastDiv::make(1);
 }
 
+// What onnx_set_workspace last stored.  Setting it and reading it are serialised, so a call
+// always sees a matching pointer and size; which of two racing settings a call sees is up to
+// the caller to order.
+std::mutex g_ws_mutex;
 Workspace g_ws = {nullptr, 0};
 
 onnx_status device_status(hipError_t e, const char* what) {
@@ -84,18 +77,136 @@ onnx_status device_status(hipError_t e, const char* what) {
 }  // namespace
 
 namespace onnxhip {
-const Workspace& workspace() { return g_ws; }
+Workspace workspace() {
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    return g_ws;
+}
 int report_error(int status, const char* message) {
     snprintf(g_err, sizeof(g_err), "%s", message);
     return status;
 }
+void record_launch(const LaunchRecord& r) { g_launch = r; }
+int fail_with(int status, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return status;
+}
 }  // namespace onnxhip
+
+namespace {
+
+// ONNX Conv with the split-K scratch `caller_ws` (possibly none).
+onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const float* W, const int64_t w_dims[4],
+                                const float* B, const int64_t pads[4], const int64_t strides[2],
+                                const int64_t dilations[2], int64_t group, const float* residual, onnx_act act,
+                                float* Y, const int64_t y_dims[4], const Workspace* caller_ws, void* stream) {
+    if (!x_dims || !w_dims || !y_dims) return fail(ONNX_ERR_NULL, "conv: NULL dims array");
+    int64_t yd[4];
+    const onnx_status st = onnx_conv_infer(x_dims, w_dims, pads, strides, dilations, group, yd);
+    if (st != ONNX_OK) return st;
+    for (int i = 0; i < 4; ++i)
+        if (yd[i] != y_dims[i])
+            return fail(ONNX_ERR_SHAPE, "conv: y_dims[%d]=%lld but the inferred extent is %lld", i,
+                        (long long)y_dims[i], (long long)yd[i]);
+    if (act != ONNX_ACT_NONE && act != ONNX_ACT_RELU) return fail(ONNX_ERR_ATTR, "conv: unknown activation");
+    const int64_t N = x_dims[0], C = x_dims[1], H = x_dims[2], Wd = x_dims[3];
+    const int64_t M = w_dims[0], Cg = w_dims[1], kH = w_dims[2], kW = w_dims[3];
+    const int64_t OH = yd[2], OW = yd[3], P = OH * OW;
+    const int64_t ny = N * M * P;
+    if (ny == 0) return ONNX_OK;
+    if (!X || !W || !Y) return fail(ONNX_ERR_NULL, "conv: X, W and Y must not be NULL");
+    const int64_t nx = N * C * H * Wd, nw = M * Cg * kH * kW;
+    if (overlaps(Y, ny * 4, X, nx * 4) || overlaps(Y, ny * 4, W, nw * 4) || overlaps(Y, ny * 4, B, M * 4) ||
+        overlaps(Y, ny * 4, residual, ny * 4))
+        return fail(ONNX_ERR_ALIAS, "conv: Y overlaps an input");
+    const int64_t K = Cg * kH * kW, Mg = M / group, NP = N * P;
+    if (C * H * Wd > kIntMax || M * P > kIntMax || K > kIntMax || pads[0] > kIntMax || pads[1] > kIntMax ||
+        strides[0] > kIntMax || strides[1] > kIntMax || kH * dilations[0] > kIntMax ||
+        kW * dilations[1] > kIntMax || N > kIntMax || group > 32768LL * 65535LL)
+        return fail(ONNX_ERR_UNSUPPORTED, "conv: a single image / filter bank exceeds 2^31 elements");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Workspace ws = *caller_ws;
+
+    WindowGeom g;
+    g.N = (int)N; g.C = (int)C; g.H = (int)H; g.W = (int)Wd; g.OH = (int)OH; g.OW = (int)OW;
+    g.kH = (int)kH; g.kW = (int)kW; g.sH = (int)strides[0]; g.sW = (int)strides[1];
+    g.pT = (int)pads[0]; g.pL = (int)pads[1]; g.pB = (int)pads[2]; g.pR = (int)pads[3];
+    g.dH = (int)dilations[0]; g.dW = (int)dilations[1];
+
+    // images one tile of columns can touch, and the span of input they cover
+    const int64_t tile_images = (kTileRows + P - 1) / P + 1;
+    const bool use_mfma = Mg >= 16 && K >= 8 && NP <= kIntMax && kc_fits(K, K) &&
+                          tile_images * C * H * Wd * 4 < kSpan &&
+                          (kTileRows * P + tile_images * M * P) * 4 < kSpan;
+    if (!use_mfma)
+        return device_status(launch_conv_direct(X, W, B, residual, Y, g, (int)M, (int)Cg, (int)group,
+                                                act == ONNX_ACT_RELU, s), "conv (direct)");
+
+    ContractionParams p;
+    no_batch(p);
+    p.A = W; p.B = X; p.Y = Y; p.bias = B; p.residual = residual;
+    p.M = (int)Mg; p.N = (int)NP; p.K = (int)K;
+    p.a_ld = K;
+    p.nbd = 1; p.bdim[0] = (int)group; p.a_bs[0] = Mg * K; p.b_bs[0] = Cg * H * Wd;
+    p.y_zs = Mg * P; p.bias_zs = Mg; p.y_rs = P;
+    p.col_images = 1; p.colP = FastDiv::make((uint32_t)P); p.y_img = M * P; p.b_img = C * H * Wd;
+    p.alpha = 1.f; p.beta = 1.f; p.bias_mode = BIAS_ROW; p.bias_cs = 0; p.relu = act == ONNX_ACT_RELU;
+    const bool unpadded_1x1 = kH == 1 && kW == 1 && pads[0] == 0 && pads[1] == 0 && pads[2] == 0 && pads[3] == 0;
+    const bool pointwise = unpadded_1x1 && strides[0] == 1 && strides[1] == 1;
+    int bkind, bvec = 1;
+    // 16-byte loads per operand: the filters when every row starts aligned, the input of a
+    // pointwise convolution when every plane does
+    const bool a_vec = (K % 4 == 0) && aligned16(W);
+    if (pointwise) {
+        bkind = LOAD_RC;
+        p.b_ld = H * Wd;
+        bvec = (P % 4 == 0 && aligned16(X)) ? 4 : 1;
+    } else if (unpadded_1x1) {
+        // strided 1x1 (ResNet's projection shortcuts): rows of B are still whole planes apart
+        bkind = LOAD_RCS;
+        p.b_ld = H * Wd;
+        p.ic.W = (int)Wd; p.ic.sH = g.sH; p.ic.sW = g.sW;
+        p.ic.OW = FastDiv::make((uint32_t)OW);
+    } else {
+        bkind = LOAD_IM2COL;
+        p.b_ld = 0;
+        p.ic.C = (int)C; p.ic.H = (int)H; p.ic.W = (int)Wd;
+        p.ic.sH = g.sH; p.ic.sW = g.sW; p.ic.pT = g.pT; p.ic.pL = g.pL; p.ic.dH = g.dH; p.ic.dW = g.dW;
+        p.ic.kHW = FastDiv::make((uint32_t)(kH * kW));
+        p.ic.kW = FastDiv::make((uint32_t)kW);
+        p.ic.OW = FastDiv::make((uint32_t)OW);
+        p.ic.image_stride = (int)(C * H * Wd);
+    }
+    if (bkind == LOAD_IM2COL && a_vec) {
+        hipError_t e = hipSuccess;
+        if (launch_conv_window(p, (int)kH, (int)kW, (int)OH, (int)OW, (int)Cg, (int)group, ws, s, &e))
+            return device_status(e, "conv (lds patch)");
+    }
+    const int tile = pick_tile(Mg, NP, K, group);
+    return device_status(launch_contraction(p, LOAD_KC, bkind, a_vec ? 4 : 1, bvec, tile, (int)group, ws, s),
+                         "conv (mfma)");
+}
+
+}  // namespace
 
 extern "C" {
 
 const char* onnx_last_error(void) { return g_err; }
 
+const char* onnx_last_launch(void) {
+    static const char* const kinds[] = {"KC", "RC", "IM2COL", "RCS"};
+    const LaunchRecord& r = g_launch;
+    if (!r.family) return "";
+    snprintf(g_launch_text, sizeof(g_launch_text), "%s %dx%dx%d waves %dx%dx%d A=%s/%d B=%s/%d npb=%d ksplit=%d tail=%dx%d",
+             r.family, r.bm, r.bn, r.bk, r.wm, r.wn, r.ks, kinds[r.akind & 3], r.avec, kinds[r.bkind & 3], r.bvec, r.npb,
+             r.ksplit, r.tail_tiles, r.tail_split);
+    return g_launch_text;
+}
+
 onnx_status onnx_set_workspace(void* device_ptr, size_t bytes) {
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
     g_ws = Workspace{nullptr, 0};
     if (!device_ptr || bytes == 0) return ONNX_OK;
     if ((reinterpret_cast<uintptr_t>(device_ptr) & 255u) != 0)
@@ -178,89 +289,9 @@ onnx_status onnx_conv(const float* X, const int64_t x_dims[4], const float* W, c
                       const float* B, const int64_t pads[4], const int64_t strides[2],
                       const int64_t dilations[2], int64_t group, const float* residual, onnx_act act,
                       float* Y, const int64_t y_dims[4], void* stream) {
-    if (!x_dims || !w_dims || !y_dims) return fail(ONNX_ERR_NULL, "conv: NULL dims array");
-    int64_t yd[4];
-    const onnx_status st = onnx_conv_infer(x_dims, w_dims, pads, strides, dilations, group, yd);
-    if (st != ONNX_OK) return st;
-    for (int i = 0; i < 4; ++i)
-        if (yd[i] != y_dims[i])
-            return fail(ONNX_ERR_SHAPE, "conv: y_dims[%d]=%lld but the inferred extent is %lld", i,
-                        (long long)y_dims[i], (long long)yd[i]);
-    if (act != ONNX_ACT_NONE && act != ONNX_ACT_RELU) return fail(ONNX_ERR_ATTR, "conv: unknown activation");
-    const int64_t N = x_dims[0], C = x_dims[1], H = x_dims[2], Wd = x_dims[3];
-    const int64_t M = w_dims[0], Cg = w_dims[1], kH = w_dims[2], kW = w_dims[3];
-    const int64_t OH = yd[2], OW = yd[3], P = OH * OW;
-    const int64_t ny = N * M * P;
-    if (ny == 0) return ONNX_OK;
-    if (!X || !W || !Y) return fail(ONNX_ERR_NULL, "conv: X, W and Y must not be NULL");
-    const int64_t nx = N * C * H * Wd, nw = M * Cg * kH * kW;
-    if (overlaps(Y, ny * 4, X, nx * 4) || overlaps(Y, ny * 4, W, nw * 4) || overlaps(Y, ny * 4, B, M * 4) ||
-        overlaps(Y, ny * 4, residual, ny * 4))
-        return fail(ONNX_ERR_ALIAS, "conv: Y overlaps an input");
-    const int64_t K = Cg * kH * kW, Mg = M / group, NP = N * P;
-    if (C * H * Wd > kIntMax || M * P > kIntMax || K > kIntMax || pads[0] > kIntMax || pads[1] > kIntMax ||
-        strides[0] > kIntMax || strides[1] > kIntMax || kH * dilations[0] > kIntMax ||
-        kW * dilations[1] > kIntMax || N > kIntMax || group > 32768LL * 65535LL)
-        return fail(ONNX_ERR_UNSUPPORTED, "conv: a single image / filter bank exceeds 2^31 elements");
-    hipStream_t s = static_cast<hipStream_t>(stream);
-
-    WindowGeom g;
-    g.N = (int)N; g.C = (int)C; g.H = (int)H; g.W = (int)Wd; g.OH = (int)OH; g.OW = (int)OW;
-    g.kH = (int)kH; g.kW = (int)kW; g.sH = (int)strides[0]; g.sW = (int)strides[1];
-    g.pT = (int)pads[0]; g.pL = (int)pads[1]; g.pB = (int)pads[2]; g.pR = (int)pads[3];
-    g.dH = (int)dilations[0]; g.dW = (int)dilations[1];
-
-    // images one tile of columns can touch, and the span of input they cover
-    const int64_t tile_images = (kTileRows + P - 1) / P + 1;
-    const bool use_mfma = Mg >= 16 && K >= 8 && NP <= kIntMax && kc_fits(K, K) &&
-                          tile_images * C * H * Wd * 4 < kSpan &&
-                          (kTileRows * P + tile_images * M * P) * 4 < kSpan;
-    if (!use_mfma)
-        return device_status(launch_conv_direct(X, W, B, residual, Y, g, (int)M, (int)Cg, (int)group,
-                                                act == ONNX_ACT_RELU, s), "conv (direct)");
-
-    ContractionParams p;
-    no_batch(p);
-    p.A = W; p.B = X; p.Y = Y; p.bias = B; p.residual = residual;
-    p.M = (int)Mg; p.N = (int)NP; p.K = (int)K;
-    p.a_ld = K;
-    p.nbd = 1; p.bdim[0] = (int)group; p.a_bs[0] = Mg * K; p.b_bs[0] = Cg * H * Wd;
-    p.y_zs = Mg * P; p.bias_zs = Mg; p.y_rs = P;
-    p.col_images = 1; p.colP = FastDiv::make((uint32_t)P); p.y_img = M * P; p.b_img = C * H * Wd;
-    p.alpha = 1.f; p.beta = 1.f; p.bias_mode = BIAS_ROW; p.bias_cs = 0; p.relu = act == ONNX_ACT_RELU;
-    const bool unpadded_1x1 = kH == 1 && kW == 1 && pads[0] == 0 && pads[1] == 0 && pads[2] == 0 && pads[3] == 0;
-    const bool pointwise = unpadded_1x1 && strides[0] == 1 && strides[1] == 1;
-    int bkind, vec;
-    const bool a_vec = (K % 4 == 0) && aligned16(W);
-    if (pointwise) {
-        bkind = LOAD_RC;
-        p.b_ld = H * Wd;
-        vec = (a_vec && P % 4 == 0 && aligned16(X)) ? 4 : 1;
-    } else if (unpadded_1x1) {
-        // strided 1x1 (ResNet's projection shortcuts): rows of B are still whole planes apart
-        bkind = LOAD_RCS;
-        p.b_ld = H * Wd;
-        vec = a_vec ? 4 : 1;
-        p.ic.W = (int)Wd; p.ic.sH = g.sH; p.ic.sW = g.sW;
-        p.ic.OW = FastDiv::make((uint32_t)OW);
-    } else {
-        bkind = LOAD_IM2COL;
-        p.b_ld = 0;
-        vec = a_vec ? 4 : 1;
-        p.ic.C = (int)C; p.ic.H = (int)H; p.ic.W = (int)Wd;
-        p.ic.sH = g.sH; p.ic.sW = g.sW; p.ic.pT = g.pT; p.ic.pL = g.pL; p.ic.dH = g.dH; p.ic.dW = g.dW;
-        p.ic.kHW = FastDiv::make((uint32_t)(kH * kW));
-        p.ic.kW = FastDiv::make((uint32_t)kW);
-        p.ic.OW = FastDiv::make((uint32_t)OW);
-        p.ic.image_stride = (int)(C * H * Wd);
-    }
-    if (bkind == LOAD_IM2COL && a_vec) {
-        hipError_t e = hipSuccess;
-        if (launch_conv_window(p, (int)kH, (int)kW, (int)OH, (int)OW, (int)Cg, (int)group, s, &e))
-            return device_status(e, "conv (lds patch)");
-    }
-    const int tile = pick_tile(Mg, NP, group);
-    return device_status(launch_contraction(p, LOAD_KC, bkind, vec, tile, (int)group, s), "conv (mfma)");
+    const Workspace ws = workspace();
+    return conv_with_workspace(X, x_dims, W, w_dims, B, pads, strides, dilations, group, residual, act, Y, y_dims,
+                               &ws, stream);
 }
 
 onnx_status onnx_gemm(const float* A, const int64_t a_dims[2], const float* B, const int64_t b_dims[2],
@@ -315,13 +346,12 @@ onnx_status onnx_gemm(const float* A, const int64_t a_dims[2], const float* B, c
     p.bias_cs = (int)ccs;
     const int akind = transA ? LOAD_RC : LOAD_KC;
     const int bkind = transB ? LOAD_KC : LOAD_RC;
-    // 16-byte loads need aligned bases and every row start (and RC row extent) a multiple of 4
-    bool v4 = aligned16(A) && aligned16(B);
-    v4 = v4 && (transA ? (M % 4 == 0) : (K % 4 == 0));
-    v4 = v4 && (transB ? (K % 4 == 0) : (N % 4 == 0));
-    const int tile = pick_tile(M, N, 1);
-    return device_status(launch_contraction(p, akind, bkind, v4 ? 4 : 1, tile, 1, static_cast<hipStream_t>(stream)),
-                         "gemm");
+    // 16-byte loads of an operand need an aligned base and every row start a multiple of 4
+    const bool a4 = aligned16(A) && a_dims[1] % 4 == 0;
+    const bool b4 = aligned16(B) && b_dims[1] % 4 == 0;
+    const int tile = pick_tile(M, N, K, 1);
+    return device_status(launch_contraction(p, akind, bkind, a4 ? 4 : 1, b4 ? 4 : 1, tile, 1, workspace(),
+                                            static_cast<hipStream_t>(stream)), "gemm");
 }
 
 onnx_status onnx_matmul(const float* A, const int64_t* a_dims, int a_rank, const float* B,
@@ -391,9 +421,9 @@ onnx_status onnx_matmul(const float* A, const int64_t* a_dims, int a_rank, const
     p.M = (int)Meff; p.N = (int)N; p.K = (int)K;
     p.a_ld = K; p.b_ld = N; p.y_rs = N; p.y_zs = M * N;
     p.alpha = 1.f; p.beta = 0.f; p.bias_mode = BIAS_NONE; p.bias_cs = 0; p.relu = 0;
-    const bool v4 = aligned16(A) && aligned16(B) && K % 4 == 0 && N % 4 == 0;
-    const int tile = pick_tile(Meff, N, nz);
-    return device_status(launch_contraction(p, LOAD_KC, LOAD_RC, v4 ? 4 : 1, tile, (int)nz,
+    const bool a4 = aligned16(A) && K % 4 == 0, b4 = aligned16(B) && N % 4 == 0;
+    const int tile = pick_tile(Meff, N, K, nz);
+    return device_status(launch_contraction(p, LOAD_KC, LOAD_RC, a4 ? 4 : 1, b4 ? 4 : 1, tile, (int)nz, workspace(),
                                             static_cast<hipStream_t>(stream)), "matmul");
 }
 

@@ -317,7 +317,7 @@ struct EpilogueSrc {
     __amdgpu_buffer_rsrc_t ry, rr, rfull, rrow;   // Y, residual, full-matrix bias, per-row bias
     bool has_res;
     int mode;
-    float lo;                                     // 0 with Relu, -inf without
+    bool relu;
 };
 
 template <bool GUARD>
@@ -358,7 +358,9 @@ __device__ inline void store_block(const floatx16& acc, int row0, float col_bias
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const float v = fmaxf(fmaf(cp.alpha, acc[4 * c + q], add[q]), e.lo);
+            // Relu as v > 0 ? v : 0 (a NaN becomes 0); without Relu the value is stored as it is
+            const float lin = fmaf(cp.alpha, acc[4 * c + q], add[q]);
+            const float v = e.relu ? fmaxf(lin, 0.f) : lin;
             __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), e.ry, (int)off[q],
                                                   (8 * c + q) * row_stride_bytes, 0);
         }
@@ -446,7 +448,7 @@ __device__ inline void store_tile(const floatx16 (&acc)[TM][TN], int m0, int n0,
     // M (their stores are dropped anyway) read as 0 instead of running past the array
     const float* brow = e.mode == BIAS_ROW ? cp.bias + zi * cp.bias_zs : cp.Y;
     e.rrow = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(brow), 0, cp.M * 4, RSRC_FLAGS);
-    e.lo = cp.relu ? 0.f : -__builtin_inff();
+    e.relu = cp.relu != 0;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int cl = wn * WTN + j * 32 + li;            // column within the tile
@@ -588,7 +590,8 @@ inline TailSplit pick_tail(int64_t tiles, int nk, int64_t tile_elems, const floa
 
 // Host side: enqueue `kernel` for the tiles of `p` and, when K ranges are split, the finishing
 // kernel behind it.  `nk` = K steps a whole tile walks.
-template <int BM, int BN, int WM, int WN, typename Kernel>
+// KS = K slices inside the main kernel's workgroup (it runs 64*WM*WN*KS threads).
+template <int BM, int BN, int WM, int WN, int KS = 1, typename Kernel>
 inline hipError_t launch_with_split(Kernel kernel, ContractionParams& p, int nz, int nk, int64_t ws_floats,
                                     hipStream_t stream) {
     const unsigned gz = nz < 32768 ? (unsigned)nz : 32768u;
@@ -600,7 +603,7 @@ inline hipError_t launch_with_split(Kernel kernel, ContractionParams& p, int nz,
     p.tail_begin = (int)tiles - tail.tiles;
     p.tail_split = tail.split;
     const unsigned gx = (unsigned)(p.tail_begin + tail.tiles * tail.split);
-    hipLaunchKernelGGL(kernel, dim3(gx, gy * (unsigned)p.ksplit, gz), dim3(64 * WM * WN), 0, stream, p);
+    hipLaunchKernelGGL(kernel, dim3(gx, gy * (unsigned)p.ksplit, gz), dim3(64 * WM * WN * KS), 0, stream, p);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && p.ksplit > 1) {
         hipLaunchKernelGGL((splitk_finish_kernel<BM, BN, WM, WN>), dim3((unsigned)tiles, gy, gz), dim3(64 * WM * WN), 0,
@@ -614,23 +617,36 @@ inline hipError_t launch_with_split(Kernel kernel, ContractionParams& p, int nz,
     return e;
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int AKIND, int BKIND, int VEC>
-__global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const ContractionParams cp) {
-    constexpr int NT = 64 * WM * WN;
+// KS > 1 adds K slices inside the workgroup: KS groups of WM x WN wavefronts share the staged
+// tiles, slice ks walking the half-step groups [ks*G/KS, (ks+1)*G/KS) of every K step, and the
+// slices' accumulators are added through LDS before the epilogue.  It doubles the wavefronts
+// per SIMD for outputs with too few tiles to give every CU more than one workgroup, at the
+// same LDS and global traffic per flop.
+template <int BM, int BN, int BK, int WM, int WN, int KS, int AKIND, int BKIND, int AVEC, int BVEC_>
+__global__ __launch_bounds__(64 * WM * WN * KS) void contraction_kernel(const ContractionParams cp) {
+    constexpr int NW = WM * WN;                     // wavefronts of one K slice
+    constexpr int NT = 64 * NW * KS;
     constexpr int WTM = BM / WM, WTN = BN / WN;     // wavefront sub-tile
     constexpr int TM = WTM / 32, TN = WTN / 32;     // 32x32 accumulators per wavefront
     static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "sub-tile of 32x32 blocks");
     static_assert(BK % 8 == 0, "K step is a multiple of the 8-wide half-step");
-    constexpr int BVEC = (BKIND == LOAD_IM2COL || BKIND == LOAD_RCS) ? 1 : VEC;
+    constexpr int BVEC = (BKIND == LOAD_IM2COL || BKIND == LOAD_RCS) ? 1 : BVEC_;
     // Steps the global loads run ahead of the MFMAs.  Two hides the memory latency behind a whole
     // step of MFMAs; one where a step is long anyway (BK = 32: measured 1-2 % faster) or where
     // the second staging set would not fit in the 128 registers a 1024-thread workgroup has.
     constexpr int PF = (BK >= 32 || (BM * BN >= 256 * 256 && BKIND == LOAD_IM2COL)) ? 1 : 2;
-    using ALoader = TileLoader<AKIND, VEC, BM, BK, NT, PF>;
+    using ALoader = TileLoader<AKIND, AVEC, BM, BK, NT, PF>;
     using BLoader = TileLoader<BKIND, BVEC, BN, BK, NT, PF>;
 
-    __shared__ __attribute__((aligned(16))) float lds_a[2][ALoader::LDS_FLOATS];
-    __shared__ __attribute__((aligned(16))) float lds_b[2][BLoader::LDS_FLOATS];
+    // One LDS array: two buffers of the A tile, two of the B tile; the slices' partial
+    // accumulators reuse it once the K walk is over.
+    constexpr int A_FLOATS = ALoader::LDS_FLOATS, B_FLOATS = BLoader::LDS_FLOATS;
+    constexpr int RED_FLOATS = (KS - 1) * NW * TM * TN * 16 * 64;
+    constexpr int LDS_TOTAL = 2 * (A_FLOATS + B_FLOATS) > RED_FLOATS ? 2 * (A_FLOATS + B_FLOATS) : RED_FLOATS;
+    static_assert(A_FLOATS % 4 == 0 && B_FLOATS % 4 == 0, "tiles keep 16-byte alignment");
+    __shared__ __attribute__((aligned(16))) float lds[LDS_TOTAL];
+    auto lds_a = [&](int buf) { return lds + buf * A_FLOATS; };
+    auto lds_b = [&](int buf) { return lds + 2 * A_FLOATS + buf * B_FLOATS; };
 
     TileWork w;
     if (!tile_work(cp, BM, BN, w)) return;          // uniform for the whole workgroup
@@ -643,7 +659,9 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
     la.init(cp.A + a_off, cp.a_ld, m0, cp.M, cp.K, false, cp);
     lb.init(cp.B + b_off, cp.b_ld, n0, cp.N, cp.K, cp.col_images != 0, cp);
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int ks = wave_all / NW, wave = wave_all % NW;
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, h = lane >> 5;
 
@@ -658,16 +676,17 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
     int kt0, kt1;
     split_range((cp.K + BK - 1) / BK, w.ksplit, w.split, kt0, kt1);
 
-    constexpr int G = BK / 8;                       // half-step groups per K step
+    constexpr int G = BK / 8 / KS;                  // half-step groups per K step and slice
+    const int g0 = ks * G;                          // this slice's first group
     constexpr int NREAD = (TM * (AKIND == LOAD_KC ? 1 : 4)) + (TN * (BKIND == LOAD_KC ? 1 : 4));   // LDS reads per group
     constexpr int NMFMA = 4 * TM * TN;              // MFMAs per group
-    static_assert(G % 2 == 0, "fragment sets alternate per group");
+    static_assert((BK / 8) % KS == 0 && G % 2 == 0, "fragment sets alternate per group");
     float fa[2][TM][4], fb[2][TN][4];               // fragments of two groups: one in use, one arriving
     auto frags = [&](int f, int buf, int g) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) ALoader::frag(lds_a[buf], wm * WTM + i * 32 + li, g, h, fa[f][i]);
+        for (int i = 0; i < TM; ++i) ALoader::frag(lds_a(buf), wm * WTM + i * 32 + li, g, h, fa[f][i]);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) BLoader::frag(lds_b[buf], wn * WTN + j * 32 + li, g, h, fb[f][j]);
+        for (int j = 0; j < TN; ++j) BLoader::frag(lds_b(buf), wn * WTN + j * 32 + li, g, h, fb[f][j]);
     };
     auto mfmas = [&](int f, int s_lo, int s_hi) {
 #pragma unroll
@@ -681,12 +700,12 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
     using Par0 = std::integral_constant<int, 0>;
     using Par1 = std::integral_constant<int, 1>;
 
-    // One K step.  On entry LDS buffer s holds step kt and the fragments of its group 0 are in
-    // fragment set 0; the loads of steps kt+1 .. kt+PF-1 are in flight.
+    // One K step.  On entry LDS buffer s holds step kt and the fragments of the slice's first
+    // group are in fragment set 0; the loads of steps kt+1 .. kt+PF-1 are in flight.
     //   issue the loads of step kt+PF
     //   groups 0 .. G-2: MFMAs of group g, the LDS reads of group g+1 in between them
     //   last group: first half of its MFMAs with the LDS stores of step kt+1 in between;
-    //   barrier; second half with the LDS reads of step kt+1's group 0 in between.
+    //   barrier; second half with the LDS reads of step kt+1's first group in between.
     auto step = [&](int kt, auto S) {
         constexpr int s = decltype(S)::value;
         constexpr int set_in = PF == 2 ? s : 0;         // register set the new loads go to
@@ -695,7 +714,7 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
         lb.template fetch<set_in>((kt + PF) * BK, cp);
 #pragma unroll
         for (int g = 0; g + 1 < G; ++g) {
-            frags((g + 1) & 1, s, g + 1);
+            frags((g + 1) & 1, s, g0 + g + 1);
             mfmas(g & 1, 0, 4);
 #pragma unroll
             for (int q = 0; q < NMFMA; ++q) {
@@ -704,11 +723,11 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        la.template commit<set_out>(lds_a[s ^ 1]);
-        lb.template commit<set_out>(lds_b[s ^ 1]);
+        la.template commit<set_out>(lds_a(s ^ 1));
+        lb.template commit<set_out>(lds_b(s ^ 1));
         mfmas((G - 1) & 1, 0, 2);
         __syncthreads();
-        frags(0, s ^ 1, 0);
+        frags(0, s ^ 1, g0);
         mfmas((G - 1) & 1, 2, 4);
 #pragma unroll
         for (int q = 0; q < NMFMA / 2; ++q) {
@@ -724,16 +743,43 @@ __global__ __launch_bounds__(64 * WM * WN) void contraction_kernel(const Contrac
         la.template fetch<PF - 1>((kt0 + 1) * BK, cp);
         lb.template fetch<PF - 1>((kt0 + 1) * BK, cp);
     }
-    la.template commit<0>(lds_a[0]);
-    lb.template commit<0>(lds_b[0]);
+    la.template commit<0>(lds_a(0));
+    lb.template commit<0>(lds_b(0));
     __syncthreads();
-    frags(0, 0, 0);
+    frags(0, 0, g0);
     for (int kt = kt0; kt < kt1; kt += 2) {
         step(kt, Par0{});
         if (kt + 1 < kt1) step(kt + 1, Par1{});
     }
 
-    finish_tile<TM, TN, WTM, WTN, NT>(acc, w, wm, wn, li, h, cp);
+    if constexpr (KS > 1) {
+        // Add the slices' accumulators in slice order: slices 1.. park theirs in LDS (register-major,
+        // lane-minor: conflict-free), slice 0 adds them and goes on to the epilogue alone.
+        constexpr int PER_WAVE = TM * TN * 16 * 64;
+        __syncthreads();                            // every wavefront is done with the staged tiles
+        if (ks > 0) {
+            float* mine = lds + ((ks - 1) * NW + wave) * PER_WAVE + lane;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) mine[((i * TN + j) * 16 + r) * 64] = acc[i][j][r];
+        }
+        __syncthreads();
+        if (ks > 0) return;
+#pragma unroll
+        for (int q = 1; q < KS; ++q) {
+            const float* theirs = lds + ((q - 1) * NW + wave) * PER_WAVE + lane;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] += theirs[((i * TN + j) * 16 + r) * 64];
+        }
+    }
+    finish_tile<TM, TN, WTM, WTN, 64 * NW>(acc, w, wm, wn, li, h, cp);
 }
 
 }  // namespace onnxhip

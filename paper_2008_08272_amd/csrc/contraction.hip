@@ -3,28 +3,33 @@
 
 namespace onnxhip {
 
-template <int BM, int BN, int BK, int WM, int WN, int AK, int BKIND, int VEC>
-static hipError_t launch_one(ContractionParams& p, int nz, hipStream_t stream) {
+template <int BM, int BN, int BK, int WM, int WN, int KS, int AK, int BKIND, int AVEC, int BVEC>
+static hipError_t launch_one(ContractionParams& p, int nz, const Workspace& ws, hipStream_t stream) {
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     p.nz = nz;
-    p.ksplit = pick_split((int64_t)p.tiles_m * p.tiles_n * nz, (p.K + BK - 1) / BK, (int64_t)BM * BN, 6.0);
-    p.ws_partial = workspace().partial;
-    return launch_with_split<BM, BN, WM, WN>(contraction_kernel<BM, BN, BK, WM, WN, AK, BKIND, VEC>, p, nz,
-                                             (p.K + BK - 1) / BK, workspace().partial_floats, stream);
+    p.ksplit = pick_split((int64_t)p.tiles_m * p.tiles_n * nz, (p.K + BK - 1) / BK, (int64_t)BM * BN, 6.0, ws);
+    p.ws_partial = ws.partial;
+    const hipError_t e = launch_with_split<BM, BN, WM, WN, KS>(contraction_kernel<BM, BN, BK, WM, WN, KS, AK, BKIND, AVEC, BVEC>,
+                                                               p, nz, (p.K + BK - 1) / BK, ws.partial_floats, stream);
+    const int ntiles = p.tiles_m * p.tiles_n;
+    record_launch(LaunchRecord{"contraction", BM, BN, BK, WM, WN, KS, AK, BKIND, AVEC, BVEC, 0, p.ksplit,
+                               ntiles - p.tail_begin, p.tail_split});
+    return e;
 }
 
-template <int AK, int BKIND, int VEC>
-static hipError_t launch_tile(ContractionParams& p, int tile, int nz, hipStream_t stream) {
+template <int AK, int BKIND, int AVEC, int BVEC>
+static hipError_t launch_tile(ContractionParams& p, int tile, int nz, const Workspace& ws, hipStream_t stream) {
     switch (tile) {
         case TILE_64:
             // short K: the 16-wide step leaves room for 8 workgroups per CU, which hides the
             // per-tile prologue and epilogue better; long K: fewer, longer steps (measured
             // crossover between K = 256 and K = 512)
-            if (p.K < 512) return launch_one<64, 64, 16, 2, 2, AK, BKIND, VEC>(p, nz, stream);
-            return launch_one<64, 64, 32, 2, 2, AK, BKIND, VEC>(p, nz, stream);
-        case TILE_128: return launch_one<128, 128, 16, 4, 2, AK, BKIND, VEC>(p, nz, stream);
-        case TILE_256: return launch_one<256, 256, 16, 4, 4, AK, BKIND, VEC>(p, nz, stream);
+            if (p.K < 512) return launch_one<64, 64, 16, 2, 2, 1, AK, BKIND, AVEC, BVEC>(p, nz, ws, stream);
+            return launch_one<64, 64, 32, 2, 2, 1, AK, BKIND, AVEC, BVEC>(p, nz, ws, stream);
+        case TILE_64_SLICED: return launch_one<64, 64, 32, 2, 2, 2, AK, BKIND, AVEC, BVEC>(p, nz, ws, stream);
+        case TILE_128: return launch_one<128, 128, 16, 4, 2, 1, AK, BKIND, AVEC, BVEC>(p, nz, ws, stream);
+        case TILE_256: return launch_one<256, 256, 16, 4, 4, 1, AK, BKIND, AVEC, BVEC>(p, nz, ws, stream);
         default: return hipErrorInvalidValue;
     }
 }
@@ -33,14 +38,15 @@ static hipError_t launch_tile(ContractionParams& p, int tile, int nz, hipStream_
 // the workgroups a CU has to run, times the tile area, over the fraction of the MFMA rate
 // that shape sustains when the chip is full (measured on 2048^3 and 4096^3: the 64 tile
 // reaches 0.92, the 128 tile slightly less at mid sizes, the 256 tile 0.94).
-int pick_tile(int64_t M, int64_t N, int64_t nz) {
-    static const int bm[TILE_COUNT] = {64, 128, 256};
-    static const double eff[TILE_COUNT] = {0.92, 0.90, 0.94};
-    static const int resident[TILE_COUNT] = {8, 2, 1};    // workgroups that share a CU
+int pick_tile(int64_t M, int64_t N, int64_t K, int64_t nz) {
+    static const int bm[TILE_COUNT] = {64, 64, 128, 256};
+    static const double eff[TILE_COUNT] = {0.92, 0.92, 0.90, 0.94};
+    static const int resident[TILE_COUNT] = {8, 4, 2, 1};    // workgroups that share a CU
     const double cus = 256.0;
     int best = TILE_64;
     double best_cost = 0.0;
     for (int t = 0; t < TILE_COUNT; ++t) {
+        if (t == TILE_64_SLICED) continue;
         const double tiles = (double)((M + bm[t] - 1) / bm[t]) * (double)((N + bm[t] - 1) / bm[t]) * (double)nz;
         double rounds = tiles / cus;
         if (resident[t] == 1) rounds = (double)(int64_t)((tiles + cus - 1) / cus);
@@ -48,11 +54,17 @@ int pick_tile(int64_t M, int64_t N, int64_t nz) {
         const double cost = rounds * bm[t] * bm[t] / eff[t];
         if (t == 0 || cost < best_cost) { best = t; best_cost = cost; }
     }
+    // Few 64 x 64 tiles and a long K walk: a CU would hold one or two 4-wavefront workgroups,
+    // one wavefront per SIMD with every wait exposed; the sliced form runs 8 wavefronts on the
+    // same tile.
+    if (best == TILE_64) {
+        const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64) * nz;
+        if (tiles <= 2 * 256 && K >= 256) best = TILE_64_SLICED;
+    }
     return best;
 }
 
-int pick_split(int64_t tiles, int nk, int64_t tile_elems, double overhead) {
-    const Workspace& w = workspace();
+int pick_split(int64_t tiles, int nk, int64_t tile_elems, double overhead, const Workspace& w) {
     if (!w.partial || tiles >= 512 || nk < 4) return 1;
     int best = 1;
     double best_cost = 0.0;
@@ -72,20 +84,32 @@ int pick_split(int64_t tiles, int nk, int64_t tile_elems, double overhead) {
     return best;
 }
 
-hipError_t launch_contraction(ContractionParams& p, int akind, int bkind, int vec, int tile, int nz,
-                              hipStream_t stream) {
-    if (vec != 1 && vec != 4) return hipErrorInvalidValue;
-#define ONNXHIP_CASE(AK, BKK)                                                    \
-    if (akind == AK && bkind == BKK)                                             \
-        return vec == 4 ? launch_tile<AK, BKK, 4>(p, tile, nz, stream)           \
-                        : launch_tile<AK, BKK, 1>(p, tile, nz, stream);
+hipError_t launch_contraction(ContractionParams& p, int akind, int bkind, int avec, int bvec, int tile, int nz,
+                              const Workspace& ws, hipStream_t stream) {
+    if ((avec != 1 && avec != 4) || (bvec != 1 && bvec != 4)) return hipErrorInvalidValue;
+    // the gather kinds fetch B one value at a time whatever the caller's alignment
+    if (bkind == LOAD_IM2COL || bkind == LOAD_RCS) bvec = 1;
+    // instances exist for 16-byte loads of both operands, of A only, and of neither
+    if (avec == 1) bvec = 1;
+#define ONNXHIP_CASE(AK, BKK)                                                                          \
+    if (akind == AK && bkind == BKK) {                                                                 \
+        if (avec == 4 && bvec == 4) return launch_tile<AK, BKK, 4, 4>(p, tile, nz, ws, stream);        \
+        if (avec == 4) return launch_tile<AK, BKK, 4, 1>(p, tile, nz, ws, stream);                     \
+        return launch_tile<AK, BKK, 1, 1>(p, tile, nz, ws, stream);                                    \
+    }
+#define ONNXHIP_CASE_GATHER(AK, BKK)                                                                   \
+    if (akind == AK && bkind == BKK) {                                                                 \
+        if (avec == 4) return launch_tile<AK, BKK, 4, 1>(p, tile, nz, ws, stream);                     \
+        return launch_tile<AK, BKK, 1, 1>(p, tile, nz, ws, stream);                                    \
+    }
     ONNXHIP_CASE(LOAD_KC, LOAD_KC)
     ONNXHIP_CASE(LOAD_KC, LOAD_RC)
     ONNXHIP_CASE(LOAD_RC, LOAD_KC)
     ONNXHIP_CASE(LOAD_RC, LOAD_RC)
-    ONNXHIP_CASE(LOAD_KC, LOAD_IM2COL)
-    ONNXHIP_CASE(LOAD_KC, LOAD_RCS)
+    ONNXHIP_CASE_GATHER(LOAD_KC, LOAD_IM2COL)
+    ONNXHIP_CASE_GATHER(LOAD_KC, LOAD_RCS)
 #undef ONNXHIP_CASE
+#undef ONNXHIP_CASE_GATHER
     return hipErrorInvalidValue;
 }
 

@@ -27,33 +27,36 @@ int patch_rows(int bn, int OH, int OW, int sH, int E) {
 }
 
 template <int BM, int BN, int WM, int WN, int KH, int KW, int NPB>
-hipError_t launch_instance(ContractionParams& p, int nz, hipStream_t stream) {
+hipError_t launch_instance(ContractionParams& p, int nz, const Workspace& ws, hipStream_t stream) {
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     p.nz = nz;
-    p.ksplit = pick_split((int64_t)p.tiles_m * p.tiles_n * nz, p.ic.Cg / WIN_CB, (int64_t)BM * BN, 4.0);
-    p.ws_partial = workspace().partial;
-    return launch_with_split<BM, BN, WM, WN>(conv_window_kernel<BM, BN, WM, WN, KH, KW, NPB>, p, nz,
-                                             p.ic.Cg / WIN_CB, workspace().partial_floats, stream);
+    p.ksplit = pick_split((int64_t)p.tiles_m * p.tiles_n * nz, p.ic.Cg / WIN_CB, (int64_t)BM * BN, 4.0, ws);
+    p.ws_partial = ws.partial;
+    const hipError_t e = launch_with_split<BM, BN, WM, WN>(conv_window_kernel<BM, BN, WM, WN, KH, KW, NPB>, p, nz,
+                                                           p.ic.Cg / WIN_CB, ws.partial_floats, stream);
+    record_launch(LaunchRecord{"conv_window", BM, BN, WIN_CB * KH * KW, WM, WN, 1, LOAD_KC, LOAD_IM2COL, 4, 1, NPB, p.ksplit,
+                               p.tiles_m * p.tiles_n - p.tail_begin, p.tail_split});
+    return e;
 }
 
 // npb = passes the patch needs; the instance with the next larger pass count runs it.
 template <int BM, int BN, int WM, int WN, int KH, int KW>
-hipError_t launch_passes(ContractionParams& p, int npb, int nz, hipStream_t stream) {
-    if (npb <= 2) return launch_instance<BM, BN, WM, WN, KH, KW, 2>(p, nz, stream);
-    if (npb <= 3) return launch_instance<BM, BN, WM, WN, KH, KW, 3>(p, nz, stream);
-    if (npb <= 4) return launch_instance<BM, BN, WM, WN, KH, KW, 4>(p, nz, stream);
-    if (npb <= 5) return launch_instance<BM, BN, WM, WN, KH, KW, 5>(p, nz, stream);
-    if (npb <= 6) return launch_instance<BM, BN, WM, WN, KH, KW, 6>(p, nz, stream);
-    if (npb <= 8) return launch_instance<BM, BN, WM, WN, KH, KW, 8>(p, nz, stream);
+hipError_t launch_passes(ContractionParams& p, int npb, int nz, const Workspace& ws, hipStream_t stream) {
+    if (npb <= 2) return launch_instance<BM, BN, WM, WN, KH, KW, 2>(p, nz, ws, stream);
+    if (npb <= 3) return launch_instance<BM, BN, WM, WN, KH, KW, 3>(p, nz, ws, stream);
+    if (npb <= 4) return launch_instance<BM, BN, WM, WN, KH, KW, 4>(p, nz, ws, stream);
+    if (npb <= 5) return launch_instance<BM, BN, WM, WN, KH, KW, 5>(p, nz, ws, stream);
+    if (npb <= 6) return launch_instance<BM, BN, WM, WN, KH, KW, 6>(p, nz, ws, stream);
+    if (npb <= 8) return launch_instance<BM, BN, WM, WN, KH, KW, 8>(p, nz, ws, stream);
     return hipErrorInvalidValue;
 }
 
 template <int KH, int KW>
-hipError_t launch_config(ContractionParams& p, int cfg, int npb, int nz, hipStream_t stream) {
+hipError_t launch_config(ContractionParams& p, int cfg, int npb, int nz, const Workspace& ws, hipStream_t stream) {
     switch (cfg) {
-        case 0: return launch_passes<64, 64, 2, 2, KH, KW>(p, npb, nz, stream);
-        case 1: return launch_passes<128, 128, 4, 2, KH, KW>(p, npb, nz, stream);
+        case 0: return launch_passes<64, 64, 2, 2, KH, KW>(p, npb, nz, ws, stream);
+        case 1: return launch_passes<128, 128, 4, 2, KH, KW>(p, npb, nz, ws, stream);
         default: return hipErrorInvalidValue;
     }
 }
@@ -61,7 +64,7 @@ hipError_t launch_config(ContractionParams& p, int cfg, int npb, int nz, hipStre
 }  // namespace
 
 bool launch_conv_window(ContractionParams& p, int kH, int kW, int OH, int OW, int Cg, int nz,
-                        hipStream_t stream, hipError_t* status) {
+                        const Workspace& ws, hipStream_t stream, hipError_t* status) {
     if (!(kH == 3 && kW == 3)) return false;
     if (Cg % WIN_CB != 0) return false;
     Im2colGeom& g = p.ic;
@@ -87,7 +90,7 @@ bool launch_conv_window(ContractionParams& p, int kH, int kW, int OH, int OW, in
     g.planed = FastDiv::make((uint32_t)best_plane);
     g.IPRd = FastDiv::make((uint32_t)g.IPR);
     const int npb = (WIN_CB * best_plane + kConfigs[best].nt - 1) / kConfigs[best].nt;
-    *status = launch_config<3, 3>(p, best, npb, nz, stream);
+    *status = launch_config<3, 3>(p, best, npb, nz, ws, stream);
     return true;
 }
 

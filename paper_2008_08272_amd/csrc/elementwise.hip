@@ -4,7 +4,6 @@
 // every element once and do next to no arithmetic: they are bound by HBM bandwidth, so the
 // kernels are about coalesced 16-byte accesses and enough independent loads in flight.
 // This file holds the kernels and their C-ABI entry points.
-#include <stdarg.h>
 #include <stdio.h>
 
 #include "../../include/onnxhip.h"
@@ -17,26 +16,11 @@ namespace {
 constexpr int EW_MAX_DIMS = ONNX_MAX_RANK;
 const int64_t kMaxElems = 0x7fffffffLL;
 
-onnx_status fail(onnx_status st, const char* fmt, ...) {
-    char buf[320];
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(buf, sizeof(buf), fmt, ap);
-    va_end(ap);
-    return static_cast<onnx_status>(report_error(st, buf));
-}
+#define fail(st, ...) static_cast<onnx_status>(fail_with((st), __VA_ARGS__))
 
 onnx_status device_status(hipError_t e, const char* what) {
     if (e == hipSuccess) return ONNX_OK;
     return fail(ONNX_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
-}
-
-inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
-inline bool overlaps(const void* a, int64_t na, const void* b, int64_t nb) {
-    if (!a || !b || na <= 0 || nb <= 0) return false;
-    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
-    return a0 < b0 + (uintptr_t)nb && b0 < a0 + (uintptr_t)na;
 }
 
 unsigned blocks_for(int64_t work_items, int per_block = 256, unsigned cap = 256u * 32u) {

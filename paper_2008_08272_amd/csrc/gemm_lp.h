@@ -94,7 +94,7 @@ __device__ inline void store_tile_lp(const floatx16 (&acc)[TM][TN], const TileWo
     uint16_t* Y = reinterpret_cast<uint16_t*>(cp.Y);
     const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y + ((int64_t)w.m0 * cp.y_rs + w.n0), 0, (int)OOB, RSRC_FLAGS);
     const int mode = cp.bias ? cp.bias_mode : BIAS_NONE;
-    const float lo = cp.relu ? 0.f : -__builtin_inff();
+    const bool relu = cp.relu != 0;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int cl = wn * WTN + j * 32 + li;
@@ -112,7 +112,8 @@ __device__ inline void store_tile_lp(const floatx16 (&acc)[TM][TN], const TileWo
                 float add = col_bias;
                 if (mode == BIAS_ROW) add = cp.beta * cp.bias[ok ? row : 0];
                 if (mode == BIAS_FULL) add = cp.beta * cp.bias[ok ? (int64_t)row * cp.N + col : 0];
-                const float v = fmaxf(fmaf(cp.alpha, acc[i][j][r], add), lo);
+                const float lin = fmaf(cp.alpha, acc[i][j][r], add);
+                const float v = relu ? fmaxf(lin, 0.f) : lin;      // no clamp without Relu: a NaN stays a NaN
                 __builtin_amdgcn_raw_buffer_store_b16((short)to_lp<DT>(v), ry, ok ? (rl * (int)cp.y_rs + cl) * 2 : (int)OOB, 0, 0);
             }
         }

@@ -1,5 +1,4 @@
 // Gemm on 16-bit inputs: kernel instances, tile choice and the C-ABI entry point.
-#include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
 
@@ -11,22 +10,7 @@ using namespace onnxhip;
 
 namespace {
 
-onnx_status fail(onnx_status st, const char* fmt, ...) {
-    char buf[320];
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(buf, sizeof(buf), fmt, ap);
-    va_end(ap);
-    return static_cast<onnx_status>(report_error(st, buf));
-}
-
-inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
-inline bool overlaps(const void* a, int64_t na, const void* b, int64_t nb) {
-    if (!a || !b || na <= 0 || nb <= 0) return false;
-    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
-    return a0 < b0 + (uintptr_t)nb && b0 < a0 + (uintptr_t)na;
-}
+#define fail(st, ...) static_cast<onnx_status>(fail_with((st), __VA_ARGS__))
 
 template <int BM, int BN, int BK, int WM, int WN, int DT, bool LP_OUT, int PF>
 hipError_t launch_instance(ContractionParams& p, hipStream_t stream) {
@@ -41,6 +25,7 @@ hipError_t launch_instance(ContractionParams& p, hipStream_t stream) {
     p.tail_split = 1;
     hipLaunchKernelGGL((gemm_lp_kernel<BM, BN, BK, WM, WN, DT, LP_OUT, PF>), dim3((unsigned)tiles, 1, 1), dim3(64 * WM * WN), 0,
                        stream, p);
+    record_launch(LaunchRecord{"gemm_lp", BM, BN, BK, WM, WN, 1, LOAD_KC, LOAD_KC, 8, 8, DT + (LP_OUT ? 2 : 0), 1, 0, 1});
     return hipGetLastError();
 }
 

@@ -8,42 +8,70 @@
 namespace onnxhip {
 
 // Workgroup tiles of the contraction kernel (rows x columns x K step, wavefront grid):
-//   TILE_64   64 x  64 x 16 (K < 1024) or x 32, 2x2 wavefronts  -- small problems
-//   TILE_128 128 x 128 x 16, 4x2 wavefronts  -- the general case
-//   TILE_256 256 x 256 x 16, 4x4 wavefronts  -- large products, one workgroup per CU
-enum TileShape { TILE_64 = 0, TILE_128 = 1, TILE_256 = 2, TILE_COUNT };
+//   TILE_64          64 x  64 x 16 (K < 512) or x 32, 2x2 wavefronts  -- outputs with many tiles
+//   TILE_64_SLICED   64 x  64 x 32, 2x2 wavefronts x 2 K slices      -- few tiles, long K
+//   TILE_128        128 x 128 x 16, 4x2 wavefronts
+//   TILE_256        256 x 256 x 16, 4x4 wavefronts  -- large products, one workgroup per CU
+enum TileShape { TILE_64 = 0, TILE_64_SLICED = 1, TILE_128 = 2, TILE_256 = 3, TILE_COUNT };
 
-// Picks the tile with the lowest estimated time for an M x N output repeated nz times.
-int pick_tile(int64_t M, int64_t N, int64_t nz);
+// Picks the tile with the lowest estimated time for an M x N x K product repeated nz times.
+int pick_tile(int64_t M, int64_t N, int64_t K, int64_t nz);
 
-// Scratch memory for split-K partial tiles, handed over by the caller through onnx_set_workspace.
+// Scratch memory for split-K partial tiles: the buffer handed over through onnx_set_workspace,
+// or the library's own fixed array for the entry point that may not allocate.  Every launcher
+// receives the one its call uses as an argument.
 struct Workspace {
     float* partial;
     int64_t partial_floats;
 };
-const Workspace& workspace();
+// A consistent copy of what onnx_set_workspace last stored.
+Workspace workspace();
 
 // Stores `message` as the calling thread's last error (what onnx_last_error returns) and hands
-// `status` back; for the entry points that live outside the main C-ABI translation unit.
+// `status` back.
 int report_error(int status, const char* message);
+// printf-style form of the same.
+int fail_with(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// byte ranges [a, a+na) and [b, b+nb) intersect
+inline bool overlaps(const void* a, int64_t na, const void* b, int64_t nb) {
+    if (!a || !b || na <= 0 || nb <= 0) return false;
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + (uintptr_t)nb && b0 < a0 + (uintptr_t)na;
+}
+
+// What the calling thread's most recent contraction / LDS-patch / 16-bit Gemm launch was: the
+// kernel family and the template instance.  onnx_last_launch formats it; the tests use it to
+// show that a case reaches the instance it is meant to cover.
+struct LaunchRecord {
+    const char* family;      // "contraction", "conv_window", "gemm_lp"
+    int bm, bn, bk, wm, wn, ks;
+    int akind, bkind, avec, bvec;
+    int npb;                 // conv_window: patch passes; gemm_lp: 1 = fp16, 2 = bf16, +2 when Y is 16-bit
+    int ksplit, tail_tiles, tail_split;
+};
+void record_launch(const LaunchRecord& r);
 
 // How many ways to split the K walk of `tiles` workgroup tiles of `tile_elems` outputs and `nk`
 // K steps each, so that the 256 CUs are evenly loaded and hold enough workgroups to overlap each
 // other's waits; 1 when the workspace cannot hold it.
 // `overhead` is a workgroup's fixed cost (prologue, epilogue) in units of one K step.
-int pick_split(int64_t tiles, int nk, int64_t tile_elems, double overhead);
+int pick_split(int64_t tiles, int nk, int64_t tile_elems, double overhead, const Workspace& ws);
 
 // Fills tiles_m / tiles_n of `p` for the chosen tile and enqueues the kernel instance for
-// (akind, bkind, vec).  nz = number of z-slices (grid.z).
-hipError_t launch_contraction(ContractionParams& p, int akind, int bkind, int vec, int tile,
-                              int nz, hipStream_t stream);
+// (akind, bkind) with 16-byte (vec 4) or 4-byte (vec 1) global loads per operand.
+// nz = number of z-slices (grid.z).
+hipError_t launch_contraction(ContractionParams& p, int akind, int bkind, int avec, int bvec, int tile,
+                              int nz, const Workspace& ws, hipStream_t stream);
 
 // Convolution through an LDS-resident input patch (conv_window.h).  `p` must be filled as for
 // the IM2COL contraction (A = filters, B = input, ic geometry, K = Cg*kH*kW).  Returns false
 // when no instance fits this shape (the caller then uses the generic path); otherwise
 // enqueues the kernel and stores the launch status in *status.
 bool launch_conv_window(ContractionParams& p, int kH, int kW, int OH, int OW, int Cg, int nz,
-                        hipStream_t stream, hipError_t* status);
+                        const Workspace& ws, hipStream_t stream, hipError_t* status);
 
 struct WindowGeom {
     int N, C, H, W, OH, OW;

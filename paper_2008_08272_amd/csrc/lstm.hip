@@ -3,7 +3,6 @@
 // state plus one element-wise cell kernel.  All arithmetic of the products runs in the
 // contraction kernels (through onnx_gemm); this file adds the cell kernel, the bias and state
 // preparation kernels and the sequencing.
-#include <stdarg.h>
 #include <stdio.h>
 
 #include "../../include/onnxhip.h"
@@ -13,20 +12,7 @@ using namespace onnxhip;
 
 namespace {
 
-onnx_status fail(onnx_status st, const char* fmt, ...) {
-    char buf[320];
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(buf, sizeof(buf), fmt, ap);
-    va_end(ap);
-    return static_cast<onnx_status>(report_error(st, buf));
-}
-
-inline bool overlaps(const void* a, int64_t na, const void* b, int64_t nb) {
-    if (!a || !b || na <= 0 || nb <= 0) return false;
-    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
-    return a0 < b0 + (uintptr_t)nb && b0 < a0 + (uintptr_t)na;
-}
+#define fail(st, ...) static_cast<onnx_status>(fail_with((st), __VA_ARGS__))
 
 __device__ inline float sigmoidf(float v) { return 1.0f / (1.0f + expf(-v)); }
 

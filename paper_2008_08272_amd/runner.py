@@ -22,21 +22,17 @@ class GraphRunner:
                     "node %r (%s) has no kernel of its own: run paper_2008_08272_amd.passes.optimize on the "
                     "graph first; it folds, removes or decomposes such nodes" % (nd["y"], nd["op"]))
         # scratch the library may use to split the K range of products with few output tiles
+        # (set as the library's workspace at the start of every run)
         self.workspace = None
         if workspace_bytes:
             self.workspace = torch.empty(workspace_bytes, dtype=torch.uint8, device=self.device)
-            B.onnx_set_workspace(self.workspace)
         self.t = {}
         for k, v in list(model["inputs"].items()) + list(model["weights"].items()):
             self.t[k] = torch.from_numpy(v).to(self.device).contiguous()
         self.calls = []
-        self.io = []                 # per call: (names of the tensors it reads, name of the tensor it writes)
-        self._alias = {}             # a Reshape result is a view: dependencies go to the tensor behind it
-        self._keepalive = []
         lib = B.raw()
         for nd in model["graph"]:
             op = nd["op"]
-            ncalls = len(self.calls)
             if op == "conv":
                 x, w = self.t[nd["x"]], self.t[nd["w"]]
                 yd = B.onnx_conv_infer(x.shape, w.shape, nd["pads"], nd["strides"], nd["dilations"], nd["group"])
@@ -113,13 +109,7 @@ class GraphRunner:
                 self.calls.append((lib.onnx_softmax, [B._ptr(x), B.dims(x.shape), x.dim(), int(nd["axis"]), B._ptr(y), None]))
             else:
                 raise ValueError("unknown node op %r" % (op,))
-            reads = [self._alias.get(nd[f], nd[f]) for f in ("x", "w", "b", "residual", "a", "c") if nd.get(f)]
-            if op == "reshape":
-                self._alias[nd["y"]] = self._alias.get(nd["x"], nd["x"])
-            elif len(self.calls) > ncalls:
-                self.io.append((reads, nd["y"]))
         self.output = self.t[model["output"]]
-        self._side = None
 
     def _new(self, name, shape):
         y = torch.empty(tuple(int(s) for s in shape), dtype=torch.float32, device=self.device)
@@ -129,72 +119,25 @@ class GraphRunner:
     def set_input(self, name, array):
         self.t[name].copy_(torch.from_numpy(array))
 
-    def capture(self, overlap=False):
+    def capture(self):
         """Record the whole chain into a HIP graph (through torch's stream capture) so that a
         forward pass is one graph launch instead of one host call per node; worthwhile when
-        the kernels are so short that launching them is the bottleneck (batch 1).  With
-        ``overlap`` independent branches of the graph are recorded on a second stream, so the
-        HIP graph lets them run side by side (see run_overlapped); measured on ResNet-50 this
-        only pays from batch 4 on (0.98 vs 1.02 ms), at batch 1 and 2 the cross-stream
-        dependencies cost more than the overlap gains (0.79 vs 0.75 ms), hence off by default."""
-        runner = self.run_overlapped if overlap else self.run
-        runner()
+        the kernels are so short that launching them is the bottleneck (batch 1)."""
+        self.run()
         torch.cuda.synchronize()
         self._graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(self._graph):
-            runner()
+            self.run()
         return self
-
-    def run_overlapped(self):
-        """Like run(), on two streams: a node that does not read the result of the node before it
-        (ResNet's projection shortcut next to the block's first two convolutions) goes to a side
-        stream and runs while the main stream continues; events carry the true dependencies.
-        At small batch each kernel fills only part of the GPU, so the branches overlap.  Each
-        stream's calls get their own half of the workspace (the library uses whichever workspace is
-        set when a call is made), so concurrent split-K products do not share scratch memory."""
-        main = torch.cuda.current_stream()
-        if self._side is None:
-            self._side = torch.cuda.Stream(device=self.device)
-        side = self._side
-        halves = None
-        if self.workspace is not None:
-            half = (self.workspace.numel() // 2) // 256 * 256
-            halves = {main: self.workspace[:half], side: self.workspace[half:2 * half]}
-        done = {}                    # tensor name -> (stream that produced it, event recorded behind the producer)
-        prev_main = None
-        pending_side = []
-        for (fn, args), (reads, y) in zip(self.calls, self.io):
-            on_side = prev_main is not None and prev_main not in reads
-            st_ = side if on_side else main
-            for name in reads:
-                if name in done and done[name][0] is not st_:
-                    st_.wait_event(done[name][1])
-            if on_side and not any(name in done for name in reads):
-                st_.wait_stream(main)            # reads only graph inputs: still has to join the capture
-            if halves is not None:
-                B.onnx_set_workspace(halves[st_])
-            args[-1] = B._stream(st_)
-            rc = fn(*args)
-            if rc != B.ONNX_OK:
-                raise B.OnnxHipError(rc, B.onnx_last_error())
-            ev = torch.cuda.Event()
-            ev.record(st_)
-            done[y] = (st_, ev)
-            if on_side:
-                pending_side.append(ev)
-            else:
-                prev_main = y
-        for ev in pending_side:                  # join: the main stream ends behind everything
-            main.wait_event(ev)
-        if self.workspace is not None:
-            B.onnx_set_workspace(self.workspace)
-        return self.output
 
     def replay(self):
         self._graph.replay()
         return self.output
 
     def run(self, stream=None):
+        # The library's workspace is one process-wide setting: point it at this runner's buffer
+        # (or clear it) before enqueuing, so that runners never inherit each other's scratch.
+        B.onnx_set_workspace(self.workspace)
         sp = B._stream(stream)
         for fn, args in self.calls:
             args[-1] = sp

@@ -218,3 +218,10 @@ def test_lstm_scratch_size_and_errors(B):
     assert lib.onnx_lstm(*args(sc=ctypes.c_void_p((64 << 20) + 64))) == 4
     assert lib.onnx_lstm(*args(sc=x)) == 6
     assert "lstm" in B.onnx_last_error()
+
+
+def test_workspace_setting_checks_its_arguments(B):
+    lib = B.raw()
+    assert lib.onnx_set_workspace(ctypes.c_void_p(1 << 20), 1 << 19) == 4         # below 1 MiB
+    assert lib.onnx_set_workspace(ctypes.c_void_p((1 << 20) + 64), 1 << 20) == 4  # not 256-byte aligned
+    assert lib.onnx_set_workspace(None, 0) == 0

@@ -49,6 +49,17 @@ def announce(*what):
     print("CASE", *what, flush=True)
 
 
+_ORACLE_CACHE = {}
+
+
+def cached(key, fn):
+    """Every case runs with and without a workspace; the oracle's result for a large case is
+    computed once and kept for the second pass."""
+    if key not in _ORACLE_CACHE:
+        _ORACLE_CACHE[key] = fn()
+    return _ORACLE_CACHE[key]
+
+
 # ------------------------------------------------------------------------------ Gemm
 
 GEMM_SHAPES = [
@@ -114,20 +125,20 @@ def test_gemm_sweep_1024_full(lib):
 
 
 @pytest.mark.parametrize("n", [2048, 4096])
-def test_gemm_sweep_full_size_sampled_rows(lib, n):
-    """Full-size launch as benchmarked; the oracle evaluates a sample of whole rows (a Gemm
-    restricted to some rows of A is the same definition)."""
-    announce("gemm sweep sampled", n)
+def test_gemm_sweep_full_size_whole_output(lib, n):
+    """The launches the benchmark times (4096: the 256 x 256 tile, one workgroup per CU), every
+    output element compared with the oracle, without and with the fused Relu."""
+    announce("gemm sweep full", n)
     c = workloads.gemm_case(n)
-    got = host(lib.onnx_gemm(dev(c["A"]), dev(c["B"]), dev(c["C"]), 1.0, 1.0, 0, 1))
-    rng = np.random.default_rng(n)
-    rows = np.unique(np.concatenate([[0, 1, 127, 128, n - 1], rng.integers(0, n, 27)]))
-    ref, S = oracle.gemm(c["A"][rows], c["B"], c["C"], 1.0, 1.0, 0, 1, want_scale=True)
-    assert rel_err(got[rows], ref) <= REL_TOL
-    assert within_rounding_bound(got[rows], ref, S, n + 2)
-    # with Relu (the fused epilogue), same launch shape
-    got_r = host(lib.onnx_gemm(dev(c["A"]), dev(c["B"]), dev(c["C"]), 1.0, 1.0, 0, 1, act=1))
-    assert rel_err(got_r[rows], np.maximum(ref, 0)) <= REL_TOL
+    ref, S = cached(("gemm_sweep", n), lambda: oracle.gemm(c["A"], c["B"], c["C"], 1.0, 1.0, 0, 1, want_scale=True))
+    a, b, cc = dev(c["A"]), dev(c["B"]), dev(c["C"])
+    got = host(lib.onnx_gemm(a, b, cc, 1.0, 1.0, 0, 1))
+    if n == 4096:
+        assert lib.onnx_last_launch().startswith("contraction 256x256x16 waves 4x4x1 A=KC/4 B=KC/4"), lib.onnx_last_launch()
+    assert rel_err(got, ref) <= REL_TOL
+    assert within_rounding_bound(got, ref, S, n + 2)
+    got_r = host(lib.onnx_gemm(a, b, cc, 1.0, 1.0, 0, 1, act=1))
+    assert rel_err(got_r, np.maximum(ref, 0)) <= REL_TOL
 
 
 # ------------------------------------------------------------------------------ MatMul
@@ -149,26 +160,25 @@ def test_matmul_matches_oracle(lib, sa, sb):
 
 
 def test_matmul_attribute_sweep_heads(lib):
+    """[8,12,512,64] x [8,12,64,512]: all 96 products compared."""
     announce("matmul heads full")
     c = workloads.attr_sweep_case("matmul_heads")
+    ref, S = cached("matmul_heads", lambda: oracle.matmul(c["A"], c["B"], want_scale=True))
     got = host(lib.onnx_matmul(dev(c["A"]), dev(c["B"])))
     assert got.shape == (8, 12, 512, 512)
-    for (i, j) in [(0, 0), (3, 7), (7, 11)]:
-        ref, S = oracle.matmul(c["A"][i, j], c["B"][i, j], want_scale=True)
-        assert rel_err(got[i, j], ref) <= REL_TOL
-        assert within_rounding_bound(got[i, j], ref, S, 64)
+    assert rel_err(got, ref) <= REL_TOL
+    assert within_rounding_bound(got, ref, S, 64)
 
 
 def test_matmul_attribute_sweep_projection(lib):
+    """[8,512,768] x [768,3072]: the whole [8,512,3072] result compared."""
     announce("matmul proj full")
     c = workloads.attr_sweep_case("matmul_proj")
+    ref, S = cached("matmul_proj", lambda: oracle.matmul(c["A"], c["B"], want_scale=True))
     got = host(lib.onnx_matmul(dev(c["A"]), dev(c["B"])))
     assert got.shape == (8, 512, 3072)
-    rows = [0, 77, 511]
-    for b in (0, 5, 7):
-        ref, S = oracle.matmul(c["A"][b][rows], c["B"], want_scale=True)
-        assert rel_err(got[b][rows], ref) <= REL_TOL
-        assert within_rounding_bound(got[b][rows], ref, S, 768)
+    assert rel_err(got, ref) <= REL_TOL
+    assert within_rounding_bound(got, ref, S, 768)
 
 
 # ------------------------------------------------------------------------------ Conv
@@ -265,29 +275,64 @@ def test_conv_attribute_sweep_depthwise_full(lib):
         assert rel_err(got, ref) <= REL_TOL
 
 
-def test_conv_attribute_sweep_dilated_full_launch_sampled_images(lib):
-    """Launch at the full 8x512x28x28 shape; the oracle evaluates two of the images (each image's
-    output depends on that image only)."""
+def test_conv_attribute_sweep_dilated_full(lib):
+    """8x512x28x28, 3x3, dilation 2, pad 2: all 8 images compared."""
     announce("conv dilated full")
     c = workloads.attr_sweep_case("dilated")
+    ref, S = cached("dilated", lambda: oracle.conv(c["X"], c["W"], c["B"], c["pads"], c["strides"], c["dilations"],
+                                                   c["group"], want_scale=True))
     got = host(lib.onnx_conv(dev(c["X"]), dev(c["W"]), dev(c["B"]), c["pads"], c["strides"], c["dilations"],
                              c["group"]))
     assert got.shape == (8, 512, 28, 28)
-    for n in (0, 7):
-        ref, S = oracle.conv(c["X"][n:n + 1], c["W"], c["B"], c["pads"], c["strides"], c["dilations"],
-                             c["group"], want_scale=True)
-        assert rel_err(got[n:n + 1], ref) <= REL_TOL
-        assert within_rounding_bound(got[n:n + 1], ref, S, 4608 + 1)
+    assert rel_err(got, ref) <= REL_TOL
+    assert within_rounding_bound(got, ref, S, 4608 + 1)
 
 
 def test_conv_attribute_sweep_pointwise_full(lib):
+    """32x1024x14x14 -> 256 channels, 1x1: all 32 images compared."""
     announce("conv pointwise full")
     c = workloads.attr_sweep_case("pointwise")
+    ref = cached("pointwise", lambda: oracle.conv(c["X"], c["W"], c["B"], c["pads"], c["strides"], c["dilations"],
+                                                  c["group"], relu=True))
     got = host(lib.onnx_conv(dev(c["X"]), dev(c["W"]), dev(c["B"]), c["pads"], c["strides"], c["dilations"],
                              c["group"], act=1))
-    sel = [0, 13, 31]
-    ref = oracle.conv(c["X"][sel], c["W"], c["B"], c["pads"], c["strides"], c["dilations"], c["group"], relu=True)
-    assert rel_err(got[sel], ref) <= REL_TOL
+    assert rel_err(got, ref) <= REL_TOL
+
+
+def test_nan_and_inf_propagate_alike_on_every_conv_path(lib):
+    """A NaN or an infinity in the input reaches the output the same way whichever kernel the shape
+    selects: without Relu the affected outputs are NaN / inf, with Relu a NaN becomes 0 (the
+    v > 0 ? v : 0 of the definition) and +inf stays +inf."""
+    announce("nan/inf propagation")
+    rng = np.random.default_rng(99)
+    shapes = [
+        ((2, 16, 12, 12), (32, 16, 3, 3), (1, 1, 1, 1), 1),      # LDS-patch kernel
+        ((2, 16, 12, 12), (32, 16, 1, 1), (0, 0, 0, 0), 1),      # contraction kernel
+        ((2, 6, 12, 12), (32, 6, 5, 5), (2, 2, 2, 2), 1),        # gather loader
+        ((2, 8, 12, 12), (8, 1, 3, 3), (1, 1, 1, 1), 8),         # row-strip (depthwise)
+        ((2, 8, 12, 12), (8, 1, 5, 5), (2, 2, 2, 2), 8),         # direct
+    ]
+    for xs, ws_, pads, g in shapes:
+        X = rng.uniform(0.5, 1, xs).astype(np.float32)
+        Wt = rng.uniform(0.5, 1, ws_).astype(np.float32)
+        X[0, 0, 5, 5] = np.nan
+        X[1, 1, 6, 6] = np.inf
+        for relu in (False, True):
+            ref = oracle.conv(X, Wt, None, pads, (1, 1), (1, 1), g, relu=relu)
+            got = host(lib.onnx_conv(dev(X), dev(Wt), None, pads, (1, 1), (1, 1), g, act=int(relu)))
+            assert np.array_equal(np.isnan(got), np.isnan(ref)), (xs, ws_, relu)
+            assert np.array_equal(np.isinf(got), np.isinf(ref)), (xs, ws_, relu)
+            fin = np.isfinite(ref)
+            assert rel_err(np.where(fin, got, 0), np.where(fin, ref, 0)) <= REL_TOL
+    # Gemm (contraction epilogue, every split configuration of the fixture)
+    A = rng.uniform(0.5, 1, (70, 300)).astype(np.float32)
+    B = rng.uniform(0.5, 1, (300, 90)).astype(np.float32)
+    A[3, 7] = np.nan
+    A[9, 1] = -np.inf
+    for relu in (False, True):
+        ref = oracle.gemm(A, B, None, 1.0, 1.0, 0, 0, relu=relu)
+        got = host(lib.onnx_gemm(dev(A), dev(B), act=int(relu)))
+        assert np.array_equal(np.isnan(got), np.isnan(ref)) and np.array_equal(np.isinf(got), np.isinf(ref)), relu
 
 
 # ------------------------------------------------------------------------------ pools
@@ -328,6 +373,20 @@ def test_maxpool_bit_exact_with_indices(lib, case):
     assert np.array_equal(igot, iref)
     only = host(lib.onnx_maxpool(dev(X), k, pads, st, dl, ceil))
     assert np.array_equal(only, ref)
+
+
+def test_maxpool_resnet_stem_shape_values_and_indices(lib):
+    """32x64x112x112, 3x3 / stride 2 / pad 1 (the pool behind ResNet-50's stem at batch 32, the
+    shape the benchmark times): every value and every int64 index, bit for bit."""
+    announce("maxpool 32x64x112x112")
+    rng = np.random.default_rng(41)
+    X = rng.integers(-6, 7, (32, 64, 112, 112)).astype(np.float32)      # ties in most windows
+    X += (rng.random(X.shape) < 0.3).astype(np.float32) * 0.25
+    ref, iref = cached("maxpool_stem", lambda: oracle.maxpool(X, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0))
+    got, igot = lib.onnx_maxpool(dev(X), (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0, want_indices=True)
+    assert np.array_equal(host(got), ref)
+    assert np.array_equal(host(igot), iref)
+    assert np.array_equal(host(lib.onnx_maxpool(dev(X), (3, 3), (1, 1, 1, 1), (2, 2))), ref)
 
 
 @pytest.mark.parametrize("case", POOL_CASES)
@@ -454,31 +513,32 @@ def test_errors_write_nothing(lib):
 
 # ------------------------------------------------------------------------------ model chains
 
-def _run_chain(lib, model):
+def _run_chain(lib, model, workspace="workspace"):
+    """The runner sets its own workspace at the start of a run: none or 64 MiB, following the fixture."""
     from paper_2008_08272_amd.runner import GraphRunner
-    r = GraphRunner(model)
+    r = GraphRunner(model, workspace_bytes=(64 << 20) if workspace == "workspace" else 0)
     out = r.run()
     torch.cuda.synchronize()
     return r, out.cpu().numpy()
 
 
-def test_small_cnn_chain(lib):
+def test_small_cnn_chain(lib, workspace):
     announce("small cnn chain")
     from oracle import chain
     m = workloads.small_cnn()
     env, exact = chain.run(m)
-    r, got = _run_chain(lib, m)
+    r, got = _run_chain(lib, m, workspace)
     assert rel_err(got, exact["logits"]) <= REL_TOL
     for name in ("c1", "p1", "c2", "p2"):
         assert rel_err(r.t[name].cpu().numpy(), exact[name]) <= REL_TOL, name
 
 
-def test_resnet50_batch1_chain(lib):
+def test_resnet50_batch1_chain(lib, workspace):
     announce("resnet50 b1 chain")
     from oracle import chain
     m = workloads.resnet50(1)
     env, exact = chain.run(m)
-    r, got = _run_chain(lib, m)
+    r, got = _run_chain(lib, m, workspace)
     worst = 0.0
     for nd in m["graph"]:
         if nd["op"] == "reshape":
@@ -521,26 +581,36 @@ def test_resnet50_batch1_graph_replay(lib):
     assert rel_err(got, exact["logits"]) <= REL_TOL
 
 
-def test_resnet50_batch32_chain_sampled_images(lib):
-    """The batch-32 launch shapes; the oracle runs the same graph on two of the 32 images."""
+def test_resnet50_batch32_chain_every_image_every_layer(lib, workspace):
+    """The batch-32 launch shapes the benchmark times.  The oracle runs the same graph image by
+    image (an image's activations depend on that image only) and every activation of every one of
+    the 32 images is compared, layer by layer."""
     announce("resnet50 b32 chain")
     from oracle import chain
     m = workloads.resnet50(32)
-    r, got = _run_chain(lib, m)
+    r, got = _run_chain(lib, m, workspace)
     assert got.shape == (32, 1000)
-    for n in (0, 31):
-        sub = dict(m)
-        sub["inputs"] = {"x": m["inputs"]["x"][n:n + 1]}
-        sub["graph"] = [dict(nd, shape=(1, 2048)) if nd["op"] == "reshape" else nd for nd in m["graph"]]
-        env, exact = chain.run(sub, keep=("stem", "pool0", "s1b2c", "s2b3c", "s3b5c", "s4b2c", "gap"))
-        for name, ref in exact.items():
-            e = rel_err(r.t[name][n:n + 1].cpu().numpy(), ref)
+    layers = [nd["y"] for nd in m["graph"] if nd["op"] != "reshape"]
+    acts = {name: r.t[name].cpu().numpy() for name in layers}
+    worst = 0.0
+    for n in range(32):
+        def one_image(n=n):
+            sub = dict(m)
+            sub["inputs"] = {"x": m["inputs"]["x"][n:n + 1]}
+            sub["graph"] = [dict(nd, shape=(1, 2048)) if nd["op"] == "reshape" else nd for nd in m["graph"]]
+            return {k: np.asarray(v, dtype=np.float32) for k, v in chain.run(sub)[1].items()}
+        # kept for the second workspace configuration as fp32 (2^-24 relative: far below the tolerance)
+        exact = cached(("resnet50_b32", n), one_image)
+        for name in layers:
+            e = rel_err(acts[name][n:n + 1], exact[name])
+            worst = max(worst, e)
             assert e <= REL_TOL, (n, name, e)
+    print("resnet50 b32 worst layer error", worst, flush=True)
 
 
 # ------------------------------------------------------------------------------ graph passes
 
-def test_unfused_graphs_through_the_passes(lib):
+def test_unfused_graphs_through_the_passes(lib, workspace):
     """Operator-by-operator graphs (BatchNormalization, Relu, Add, Identity, MatMul + Add as nodes
     of their own) go through the graph passes and then through the runner; the reference is the
     oracle evaluating the ORIGINAL graph by the operators' definitions."""
@@ -553,7 +623,7 @@ def test_unfused_graphs_through_the_passes(lib):
             GraphRunner(raw)                     # no kernel for a bare Relu / BatchNorm: fails loudly
         opt = passes.optimize(raw)
         _, exact = chain.run(raw)
-        r, got = _run_chain(lib, opt)
+        r, got = _run_chain(lib, opt, workspace)
         assert got.shape == exact[raw["output"]].shape
         assert rel_err(got, exact[raw["output"]]) <= REL_TOL, raw["name"]
         # every intermediate tensor that survives the rewrite matches the original graph's
@@ -659,32 +729,92 @@ def test_pool_random_sweep(lib):
             assert rel_err(ga, ra) <= REL_TOL
 
 
-def test_overlapped_graph_matches_single_stream(lib):
-    """The two-stream schedule (projection shortcuts on a side stream, each stream with its own half
-    of the workspace) must give bit for bit what the single-stream run gives, eagerly and as a
-    replayed HIP graph with other work in between the replays."""
-    announce("overlapped runner")
-    from paper_2008_08272_amd.runner import GraphRunner
-    for batch in (1, 3):
-        m = workloads.resnet50(batch)
-        r = GraphRunner(m)
-        ref = r.run().clone()
-        torch.cuda.synchronize()
-        got = r.run_overlapped().clone()
-        torch.cuda.synchronize()
-        assert torch.equal(got, ref)
-        r.capture(overlap=True)
-        for rep in range(3):
-            r.output.zero_()
-            junk = torch.randn(1 << 20, device="cuda").sum()       # unrelated eager work between replays
-            out = r.replay().clone()
-            torch.cuda.synchronize()
-            assert torch.equal(out, ref), (batch, rep)
-            del junk
-        # a new input through the same graph
-        x2 = np.random.default_rng(5).standard_normal(m["inputs"]["x"].shape).astype(np.float32)
-        r.set_input("x", x2)
-        a = r.run().clone()
-        b = r.replay().clone()
-        torch.cuda.synchronize()
-        assert torch.equal(a, b) and not torch.equal(a, ref)
+# ------------------------------------------------------------------------------ every kernel instance
+
+def _offset_dev(a, misalign):
+    """The array on the GPU; with `misalign` its first element sits 4 bytes past a 16-byte boundary
+    (a view into a larger buffer), which rules out 16-byte loads of that operand."""
+    if not misalign:
+        return dev(a)
+    buf = torch.empty(a.size + 1, dtype=torch.float32, device="cuda")
+    view = buf[1:].view(a.shape)
+    view.copy_(torch.from_numpy(np.ascontiguousarray(a)))
+    assert view.data_ptr() % 16 == 4
+    return view
+
+
+# tile class -> (M, N, K) that makes the selector take it, and the instance it names
+GEMM_TILE_CLASSES = {
+    "64x64x16": ((132, 200, 72), "64x64x16 waves 2x2x1"),
+    "64x64x32": ((1500, 1504, 512), "64x64x32 waves 2x2x1"),
+    "64x64x32 sliced": ((200, 152, 300), "64x64x32 waves 2x2x2"),
+    "256x256x16": ((4096, 4096, 40), "256x256x16 waves 4x4x1"),
+}
+
+
+@pytest.mark.parametrize("loads", ["16B/16B", "16B/4B", "4B/4B"])
+@pytest.mark.parametrize("transA,transB", [(0, 1), (0, 0), (1, 1), (1, 0)])
+@pytest.mark.parametrize("tile", list(GEMM_TILE_CLASSES))
+def test_every_gemm_instance(lib, tile, transA, transB, loads):
+    """One case per compiled instance of the contraction kernel that Gemm can reach: tile shape x
+    operand layouts x load widths.  The launch record names the instance that ran; the whole
+    output is compared with the oracle."""
+    (M, N, K), inst = GEMM_TILE_CLASSES[tile]
+    announce("gemm instance", tile, transA, transB, loads)
+    rng = np.random.default_rng([M, N, K, transA, transB])
+    A = rng.uniform(-1, 1, (K, M) if transA else (M, K)).astype(np.float32)
+    B = rng.uniform(-1, 1, (N, K) if transB else (K, N)).astype(np.float32)
+    C = rng.uniform(-1, 1, (1, N)).astype(np.float32)
+    ref, S = cached(("gemm_inst", tile, transA, transB),
+                    lambda: oracle.gemm(A, B, C, 1.0, 1.0, transA, transB, want_scale=True))
+    a = _offset_dev(A, loads == "4B/4B")
+    b = _offset_dev(B, loads != "16B/16B")
+    got = host(lib.onnx_gemm(a, b, dev(C), 1.0, 1.0, transA, transB))
+    av, bv = {"16B/16B": (4, 4), "16B/4B": (4, 1), "4B/4B": (1, 1)}[loads]
+    want = "contraction %s A=%s/%d B=%s/%d " % (inst, "RC" if transA else "KC", av, "KC" if transB else "RC", bv)
+    assert lib.onnx_last_launch().startswith(want), (lib.onnx_last_launch(), want)
+    assert rel_err(got, ref) <= REL_TOL
+    assert within_rounding_bound(got, ref, S, K + 2)
+
+
+CONV_INSTANCE_CASES = [
+    # name, X shape, W shape, pads, strides, expected instance prefix
+    ("im2col 64x64x16 16B", (1, 8, 14, 14), (16, 8, 5, 5), (2, 2, 2, 2), (1, 1), "64x64x16 waves 2x2x1 A=KC/4 B=IM2COL/1"),
+    ("im2col 64x64x16 4B", (2, 3, 37, 41), (64, 3, 7, 7), (3, 3, 3, 3), (2, 2), "64x64x16 waves 2x2x1 A=KC/1 B=IM2COL/1"),
+    ("im2col 64x64x32 16B", (16, 24, 48, 48), (64, 24, 5, 5), (2, 2, 2, 2), (1, 1), "64x64x32 waves 2x2x1 A=KC/4 B=IM2COL/1"),
+    ("im2col 64x64x32 4B", (16, 25, 48, 48), (64, 25, 5, 5), (2, 2, 2, 2), (1, 1), "64x64x32 waves 2x2x1 A=KC/1 B=IM2COL/1"),
+    ("im2col sliced 16B", (2, 24, 20, 20), (64, 24, 5, 5), (2, 2, 2, 2), (1, 1), "64x64x32 waves 2x2x2 A=KC/4 B=IM2COL/1"),
+    ("im2col sliced 4B", (2, 25, 20, 20), (64, 25, 5, 5), (2, 2, 2, 2), (1, 1), "64x64x32 waves 2x2x2 A=KC/1 B=IM2COL/1"),
+    ("im2col 256x256x16 16B", (8, 4, 64, 64), (512, 4, 5, 5), (2, 2, 2, 2), (1, 1), "256x256x16 waves 4x4x1 A=KC/4 B=IM2COL/1"),
+    ("im2col 256x256x16 4B", (8, 6, 64, 64), (512, 6, 3, 3), (1, 1, 1, 1), (1, 1), "256x256x16 waves 4x4x1 A=KC/1 B=IM2COL/1"),
+    ("rcs 64x64x16 16B", (2, 64, 12, 12), (96, 64, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x16 waves 2x2x1 A=KC/4 B=RCS/1"),
+    ("rcs 64x64x16 4B", (2, 18, 13, 11), (40, 18, 1, 1), (0, 0, 0, 0), (3, 2), "64x64x16 waves 2x2x1 A=KC/1 B=RCS/1"),
+    ("rcs 64x64x32 16B", (9, 512, 64, 64), (256, 512, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x32 waves 2x2x1 A=KC/4 B=RCS/1"),
+    ("rcs 64x64x32 4B", (9, 514, 64, 64), (256, 514, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x32 waves 2x2x1 A=KC/1 B=RCS/1"),
+    ("rcs sliced 16B", (2, 512, 14, 14), (128, 512, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x32 waves 2x2x2 A=KC/4 B=RCS/1"),
+    ("rcs sliced 4B", (2, 510, 14, 14), (128, 510, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x32 waves 2x2x2 A=KC/1 B=RCS/1"),
+    ("rcs 256x256x16 16B", (8, 16, 128, 128), (512, 16, 1, 1), (0, 0, 0, 0), (2, 2), "256x256x16 waves 4x4x1 A=KC/4 B=RCS/1"),
+    ("rcs 256x256x16 4B", (8, 18, 128, 128), (512, 18, 1, 1), (0, 0, 0, 0), (2, 2), "256x256x16 waves 4x4x1 A=KC/1 B=RCS/1"),
+    # pointwise convolutions: the row-contiguous loader with images as column blocks
+    ("pointwise 16B/16B", (2, 64, 12, 12), (96, 64, 1, 1), (0, 0, 0, 0), (1, 1), "64x64x16 waves 2x2x1 A=KC/4 B=RC/4"),
+    ("pointwise 16B/4B (P = 49)", (32, 512, 7, 7), (2048, 512, 1, 1), (0, 0, 0, 0), (1, 1), "64x64x32 waves 2x2x1 A=KC/4 B=RC/1"),
+    ("pointwise 256x256x16", (32, 64, 32, 32), (512, 64, 1, 1), (0, 0, 0, 0), (1, 1), "256x256x16 waves 4x4x1 A=KC/4 B=RC/4"),
+]
+
+
+@pytest.mark.parametrize("case", CONV_INSTANCE_CASES, ids=[c[0] for c in CONV_INSTANCE_CASES])
+def test_every_conv_contraction_instance(lib, case):
+    """The instances of the contraction kernel only convolutions reach (gather loader, strided 1x1
+    loader, image-blocked row-contiguous loader), each tile shape and filter load width once."""
+    name, xs, ws_, pads, st, inst = case
+    announce("conv instance", name)
+    rng = np.random.default_rng([len(name)] + list(xs))
+    X = rng.uniform(-1, 1, xs).astype(np.float32)
+    Wt = rng.uniform(-1, 1, ws_).astype(np.float32)
+    Bv = rng.uniform(-1, 1, (ws_[0],)).astype(np.float32)
+    K = ws_[1] * ws_[2] * ws_[3]
+    ref, S = cached(("conv_inst", name), lambda: oracle.conv(X, Wt, Bv, pads, st, (1, 1), 1, want_scale=True))
+    got = host(lib.onnx_conv(dev(X), dev(Wt), dev(Bv), pads, st, (1, 1), 1))
+    assert lib.onnx_last_launch().startswith("contraction " + inst), (lib.onnx_last_launch(), inst)
+    assert rel_err(got, ref) <= REL_TOL
+    assert within_rounding_bound(got, ref, S, K + 1)

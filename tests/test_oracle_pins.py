@@ -438,3 +438,24 @@ def test_small_cnn_chain_shapes_and_values():
     t = F.max_pool2d(t, 3, 3).reshape(1, 256)
     ref = (t @ w["wg"] + w["bg"]).numpy()
     np.testing.assert_allclose(exact["logits"], ref, rtol=1e-12, atol=1e-12)
+
+
+def test_bf16_input_encoding_matches_torch_and_the_format_definition():
+    """The generator's fp32 -> bfloat16 encoding (input preparation for the 16-bit Gemm cases, also
+    used to state the expected rounding of 16-bit results) against an independent library routine
+    (torch's conversion) and against the format's definition: the upper 16 bits of the binary32
+    pattern, round to nearest, ties to even."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(16)
+    x = np.concatenate([rng.standard_normal(20000) * 10.0 ** rng.integers(-20, 20, 20000),
+                        [0.0, -0.0, 1.0, -1.0, 65504.0, 3.0e38, 1e-40, np.inf, -np.inf]]).astype(np.float32)
+    bits = workloads.to_bf16_bits(x)
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(bits, want)
+    assert np.array_equal(workloads.from_bf16_bits(bits), torch.from_numpy(x).to(torch.bfloat16).float().numpy())
+    # ties: a pattern exactly half way between two bfloat16 values goes to the one with an even last bit
+    half = np.array([0x3F808000, 0x3F818000, 0x3F800001 | 0x8000, 0x3F807FFF], dtype=np.uint32).view(np.float32)
+    assert list(workloads.to_bf16_bits(half)) == [0x3F80, 0x3F82, 0x3F81, 0x3F80]
+    # decoding is exact: every bfloat16 pattern round-trips
+    allb = np.arange(0x0000, 0x7F80, dtype=np.uint16)
+    assert np.array_equal(workloads.to_bf16_bits(workloads.from_bf16_bits(allb)), allb)
