@@ -116,6 +116,26 @@ onnx_status onnx_conv(const float* X, const int64_t x_dims[4], const float* W,
                       void* stream);
 
 /*
+ * onnx_conv for callers that cannot allocate or hand over device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, result and
+ * errors as onnx_conv.  The split-K scratch that onnx_conv takes from onnx_set_workspace is here a
+ * fixed array of ONNX_CONV_FIXED_SCRATCH_BYTES inside the library's device image (every GPU the
+ * library runs on holds its copy until the process ends); the workspace set by
+ * onnx_set_workspace is neither used nor changed.  The call allocates and frees nothing.
+ * Outputs of more than ONNX_CONV_FIXED_SCRATCH_MAX_OUTPUTS elements are refused with
+ * ONNX_ERR_UNSUPPORTED (larger convolutions fill the GPU without split-K: use onnx_conv).
+ * The array needs no initialisation (every partial tile is written before it is read), and all
+ * calls on one GPU share it: calls that overlap in time on one GPU, on whatever streams, race.
+ */
+#define ONNX_CONV_FIXED_SCRATCH_BYTES (16u << 20)
+#define ONNX_CONV_FIXED_SCRATCH_MAX_OUTPUTS (1 << 21)
+onnx_status onnx_conv_fixed_scratch(const float* X, const int64_t x_dims[4], const float* W,
+                                    const int64_t w_dims[4], const float* B, const int64_t pads[4],
+                                    const int64_t strides[2], const int64_t dilations[2],
+                                    int64_t group, const float* residual, onnx_act act, float* Y,
+                                    const int64_t y_dims[4], void* stream);
+
+/*
  * ONNX Gemm (Section 3.4: the target of the MatMul+Add rewrite; Section 4.1).
  *   Y = alpha * op(A) * op(B) + beta * C~,  op(.) = transpose when the flag is non-zero,
  * op(A) is M x K, op(B) is K x N, C~ is C broadcast to M x N from rank 0 (c_rank = 0, one

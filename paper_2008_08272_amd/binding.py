@@ -40,7 +40,11 @@ _lib.onnx_conv_infer.argtypes = [_i64p, _i64p, _i64p, _i64p, _i64p, _c64, _i64p]
 _lib.onnx_pool_infer.argtypes = [_i64p, _i64p, _i64p, _i64p, _i64p, _ci, _i64p]
 _lib.onnx_matmul_infer.argtypes = [_i64p, _ci, _i64p, _ci, _i64p, ctypes.POINTER(_ci)]
 _lib.onnx_conv.argtypes = [_vp, _i64p, _vp, _i64p, _vp, _i64p, _i64p, _i64p, _c64, _vp, _ci, _vp, _i64p, _vp]
+_lib.onnx_conv_fixed_scratch.argtypes = _lib.onnx_conv.argtypes
+_lib.onnx_conv_fixed_scratch.restype = _ci
 _lib.onnx_last_launch.restype = ctypes.c_char_p
+CONV_FIXED_SCRATCH_BYTES = 16 << 20
+CONV_FIXED_SCRATCH_MAX_OUTPUTS = 1 << 21
 _lib.onnx_gemm.argtypes = [_vp, _i64p, _vp, _i64p, _vp, _i64p, _ci, _cf, _cf, _ci, _ci, _ci, _vp, _i64p, _vp]
 _lib.onnx_matmul.argtypes = [_vp, _i64p, _ci, _vp, _i64p, _ci, _vp, _i64p, _ci, _vp]
 _lib.onnx_maxpool.argtypes = [_vp, _i64p, _i64p, _i64p, _i64p, _i64p, _ci, _vp, _vp, _i64p, _vp]
@@ -159,6 +163,19 @@ def onnx_conv(X, W, B=None, pads=(0, 0, 0, 0), strides=(1, 1), dilations=(1, 1),
     _check(_lib.onnx_conv(_ptr(X), dims(X.shape), _ptr(W), dims(W.shape), _ptr(B), dims(pads),
                           dims(strides), dims(dilations), int(group), _ptr(residual), int(act), _ptr(Y),
                           dims(Y.shape), _stream(stream)))
+    return Y
+
+
+def onnx_conv_fixed_scratch(X, W, B=None, pads=(0, 0, 0, 0), strides=(1, 1), dilations=(1, 1), group=1,
+                            residual=None, act=ACT_NONE, out=None, stream=None):
+    """onnx_conv with the library's fixed split-K scratch.  The library call itself allocates nothing;
+    pass ``out=`` to keep this wrapper from allocating the result."""
+    X, W, B, residual = _dev(X, "X"), _dev(W, "W"), _dev(B, "B"), _dev(residual, "residual")
+    yd = onnx_conv_infer(X.shape, W.shape, pads, strides, dilations, group)
+    Y = torch.empty(yd, dtype=torch.float32, device=X.device) if out is None else _dev(out, "out")
+    _check(_lib.onnx_conv_fixed_scratch(_ptr(X), dims(X.shape), _ptr(W), dims(W.shape), _ptr(B), dims(pads),
+                                        dims(strides), dims(dilations), int(group), _ptr(residual), int(act),
+                                        _ptr(Y), dims(Y.shape), _stream(stream)))
     return Y
 
 

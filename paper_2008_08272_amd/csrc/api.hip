@@ -95,13 +95,51 @@ int fail_with(int status, const char* fmt, ...) {
 }
 }  // namespace onnxhip
 
+// ---- the entry point that may not allocate: its split-K scratch is this fixed array -----------
 namespace {
 
-// ONNX Conv with the split-K scratch `caller_ws` (possibly none).
+constexpr int64_t kFixedScratchFloats = (int64_t)ONNX_CONV_FIXED_SCRATCH_BYTES / 4;
+static __device__ __align__(256) float scratch[kFixedScratchFloats];
+
+// Every GPU holds its own copy of `scratch` at its own address; in host code the array's name is
+// only a handle for hipGetSymbolAddress.  The address is looked up once per device, with that
+// device current, and kept here.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices] = {};
+
+onnx_status fixed_scratch(Workspace* out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(ONNX_ERR_DEVICE, "conv (fixed scratch): hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(ONNX_ERR_UNSUPPORTED, "conv (fixed scratch): device ordinal %d outside 0..%d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(ONNX_ERR_DEVICE, "conv (fixed scratch): hipGetSymbolAddress: %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = static_cast<float*>(ptr);
+    }
+    out->partial = g_scratch_ptr[dev];
+    out->partial_floats = kFixedScratchFloats;
+    return ONNX_OK;
+}
+
+}  // namespace
+
+namespace {
+
+// ONNX Conv with the split-K scratch `caller_ws` (possibly none), or, when that is NULL, with
+// the library's fixed array, whose address is looked up once the arguments have passed
+// validation.  max_outputs > 0 caps the number of output elements (the fixed-scratch entry
+// point's limit).
 onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const float* W, const int64_t w_dims[4],
                                 const float* B, const int64_t pads[4], const int64_t strides[2],
                                 const int64_t dilations[2], int64_t group, const float* residual, onnx_act act,
-                                float* Y, const int64_t y_dims[4], const Workspace* caller_ws, void* stream) {
+                                float* Y, const int64_t y_dims[4], const Workspace* caller_ws, int64_t max_outputs,
+                                void* stream) {
     if (!x_dims || !w_dims || !y_dims) return fail(ONNX_ERR_NULL, "conv: NULL dims array");
     int64_t yd[4];
     const onnx_status st = onnx_conv_infer(x_dims, w_dims, pads, strides, dilations, group, yd);
@@ -116,6 +154,9 @@ onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const f
     const int64_t OH = yd[2], OW = yd[3], P = OH * OW;
     const int64_t ny = N * M * P;
     if (ny == 0) return ONNX_OK;
+    if (max_outputs > 0 && ny > max_outputs)
+        return fail(ONNX_ERR_UNSUPPORTED, "conv: %lld output elements exceed the %lld this entry point's fixed scratch is "
+                    "sized for; use onnx_conv with onnx_set_workspace", (long long)ny, (long long)max_outputs);
     if (!X || !W || !Y) return fail(ONNX_ERR_NULL, "conv: X, W and Y must not be NULL");
     const int64_t nx = N * C * H * Wd, nw = M * Cg * kH * kW;
     if (overlaps(Y, ny * 4, X, nx * 4) || overlaps(Y, ny * 4, W, nw * 4) || overlaps(Y, ny * 4, B, M * 4) ||
@@ -127,7 +168,13 @@ onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const f
         kW * dilations[1] > kIntMax || N > kIntMax || group > 32768LL * 65535LL)
         return fail(ONNX_ERR_UNSUPPORTED, "conv: a single image / filter bank exceeds 2^31 elements");
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const Workspace ws = *caller_ws;
+    Workspace ws = {nullptr, 0};
+    if (caller_ws) {
+        ws = *caller_ws;
+    } else {
+        const onnx_status sst = fixed_scratch(&ws);
+        if (sst != ONNX_OK) return sst;
+    }
 
     WindowGeom g;
     g.N = (int)N; g.C = (int)C; g.H = (int)H; g.W = (int)Wd; g.OH = (int)OH; g.OW = (int)OW;
@@ -291,7 +338,15 @@ onnx_status onnx_conv(const float* X, const int64_t x_dims[4], const float* W, c
                       float* Y, const int64_t y_dims[4], void* stream) {
     const Workspace ws = workspace();
     return conv_with_workspace(X, x_dims, W, w_dims, B, pads, strides, dilations, group, residual, act, Y, y_dims,
-                               &ws, stream);
+                               &ws, 0, stream);
+}
+
+onnx_status onnx_conv_fixed_scratch(const float* X, const int64_t x_dims[4], const float* W, const int64_t w_dims[4],
+                                    const float* B, const int64_t pads[4], const int64_t strides[2],
+                                    const int64_t dilations[2], int64_t group, const float* residual, onnx_act act,
+                                    float* Y, const int64_t y_dims[4], void* stream) {
+    return conv_with_workspace(X, x_dims, W, w_dims, B, pads, strides, dilations, group, residual, act, Y, y_dims,
+                               nullptr, ONNX_CONV_FIXED_SCRATCH_MAX_OUTPUTS, stream);
 }
 
 onnx_status onnx_gemm(const float* A, const int64_t a_dims[2], const float* B, const int64_t b_dims[2],

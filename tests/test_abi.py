@@ -220,6 +220,29 @@ def test_lstm_scratch_size_and_errors(B):
     assert "lstm" in B.onnx_last_error()
 
 
+def test_fixed_scratch_conv_validates_like_conv_and_enforces_its_maximum(B):
+    """The entry point that may not allocate checks its arguments like onnx_conv, before it looks
+    up its scratch array or touches the device, and refuses outputs above its stated maximum."""
+    lib = B.raw()
+    d = B.dims
+    fake = ctypes.c_void_p(4096)
+    args = [fake, d((1, 4, 8, 8)), fake, d((6, 4, 3, 3)), None, d((1, 1, 1, 1)), d((1, 1)), d((1, 1)), 1, None, 0,
+            fake, d((1, 6, 8, 7)), None]
+    assert lib.onnx_conv_fixed_scratch(*args) == 3
+    args[12] = d((1, 6, 8, 8)); args[10] = 9
+    assert lib.onnx_conv_fixed_scratch(*args) == 4
+    args[10] = 0; args[0] = None
+    assert lib.onnx_conv_fixed_scratch(*args) == 1
+    # one output element above the maximum
+    m = B.CONV_FIXED_SCRATCH_MAX_OUTPUTS // (64 * 64) + 1
+    big = [fake, d((1, 4, 64, 64)), fake, d((m, 4, 1, 1)), None, d((0, 0, 0, 0)), d((1, 1)), d((1, 1)), 1, None, 0,
+           ctypes.c_void_p(1 << 30), d((1, m, 64, 64)), None]
+    assert lib.onnx_conv_fixed_scratch(*big) == 5 and "exceed" in B.onnx_last_error()
+    text = open(os.path.join(ROOT, "include", "onnxhip.h")).read()
+    assert "#define ONNX_CONV_FIXED_SCRATCH_BYTES (16u << 20)" in text and B.CONV_FIXED_SCRATCH_BYTES == 16 << 20
+    assert "#define ONNX_CONV_FIXED_SCRATCH_MAX_OUTPUTS (1 << 21)" in text and B.CONV_FIXED_SCRATCH_MAX_OUTPUTS == 1 << 21
+
+
 def test_workspace_setting_checks_its_arguments(B):
     lib = B.raw()
     assert lib.onnx_set_workspace(ctypes.c_void_p(1 << 20), 1 << 19) == 4         # below 1 MiB
