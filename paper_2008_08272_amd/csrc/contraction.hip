@@ -28,7 +28,7 @@ static hipError_t launch_tile(ContractionParams& p, int tile, int nz, const Work
             if (p.K < 512) return launch_one<64, 64, 16, 2, 2, 1, AK, BKIND, AVEC, BVEC>(p, nz, ws, stream);
             return launch_one<64, 64, 32, 2, 2, 1, AK, BKIND, AVEC, BVEC>(p, nz, ws, stream);
         case TILE_64_SLICED: return launch_one<64, 64, 32, 2, 2, 2, AK, BKIND, AVEC, BVEC>(p, nz, ws, stream);
-        case TILE_128: return launch_one<128, 128, 16, 4, 2, 1, AK, BKIND, AVEC, BVEC>(p, nz, ws, stream);
+        case TILE_128: return launch_one<128, 128, 16, 4, 4, 1, AK, BKIND, AVEC, BVEC>(p, nz, ws, stream);
         case TILE_256: return launch_one<256, 256, 16, 4, 4, 1, AK, BKIND, AVEC, BVEC>(p, nz, ws, stream);
         default: return hipErrorInvalidValue;
     }
@@ -36,12 +36,14 @@ static hipError_t launch_tile(ContractionParams& p, int tile, int nz, const Work
 
 // Estimated time of each tile shape, in units of (output elements per CU) / efficiency:
 // the workgroups a CU has to run, times the tile area, over the fraction of the MFMA rate
-// that shape sustains when the chip is full (measured on 2048^3 and 4096^3: the 64 tile
-// reaches 0.92, the 128 tile slightly less at mid sizes, the 256 tile 0.94).
+// that shape sustains when the chip is full.  The 16-wavefront shapes (128 and 256) run one
+// workgroup per CU at a time, so their tile count is rounded up to whole rounds of 256: they
+// win exactly where that rounding is cheap (2048^2 outputs = 256 tiles of 128: measured 130
+// against 123 TFLOP/s for the 64 tile; 4096^2 = 256 tiles of 256: 147 against 144 and 130).
 int pick_tile(int64_t M, int64_t N, int64_t K, int64_t nz) {
     static const int bm[TILE_COUNT] = {64, 64, 128, 256};
-    static const double eff[TILE_COUNT] = {0.92, 0.92, 0.90, 0.94};
-    static const int resident[TILE_COUNT] = {8, 4, 2, 1};    // workgroups that share a CU
+    static const double eff[TILE_COUNT] = {0.92, 0.92, 0.93, 0.94};
+    static const int resident[TILE_COUNT] = {8, 4, 1, 1};    // workgroups that share a CU
     const double cus = 256.0;
     int best = TILE_64;
     double best_cost = 0.0;

@@ -10,7 +10,7 @@ namespace onnxhip {
 // Workgroup tiles of the contraction kernel (rows x columns x K step, wavefront grid):
 //   TILE_64          64 x  64 x 16 (K < 512) or x 32, 2x2 wavefronts  -- outputs with many tiles
 //   TILE_64_SLICED   64 x  64 x 32, 2x2 wavefronts x 2 K slices      -- few tiles, long K
-//   TILE_128        128 x 128 x 16, 4x2 wavefronts
+//   TILE_128        128 x 128 x 16, 4x4 wavefronts  -- outputs of about 256 or 512 such tiles
 //   TILE_256        256 x 256 x 16, 4x4 wavefronts  -- large products, one workgroup per CU
 enum TileShape { TILE_64 = 0, TILE_64_SLICED = 1, TILE_128 = 2, TILE_256 = 3, TILE_COUNT };
 

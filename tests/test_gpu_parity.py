@@ -748,6 +748,7 @@ GEMM_TILE_CLASSES = {
     "64x64x16": ((132, 200, 72), "64x64x16 waves 2x2x1"),
     "64x64x32": ((1500, 1504, 512), "64x64x32 waves 2x2x1"),
     "64x64x32 sliced": ((200, 152, 300), "64x64x32 waves 2x2x2"),
+    "128x128x16": ((2048, 2048, 40), "128x128x16 waves 4x4x1"),
     "256x256x16": ((4096, 4096, 40), "256x256x16 waves 4x4x1"),
 }
 
@@ -785,6 +786,8 @@ CONV_INSTANCE_CASES = [
     ("im2col 64x64x32 4B", (16, 25, 48, 48), (64, 25, 5, 5), (2, 2, 2, 2), (1, 1), "64x64x32 waves 2x2x1 A=KC/1 B=IM2COL/1"),
     ("im2col sliced 16B", (2, 24, 20, 20), (64, 24, 5, 5), (2, 2, 2, 2), (1, 1), "64x64x32 waves 2x2x2 A=KC/4 B=IM2COL/1"),
     ("im2col sliced 4B", (2, 25, 20, 20), (64, 25, 5, 5), (2, 2, 2, 2), (1, 1), "64x64x32 waves 2x2x2 A=KC/1 B=IM2COL/1"),
+    ("im2col 128x128x16 16B", (2, 4, 64, 64), (512, 4, 5, 5), (2, 2, 2, 2), (1, 1), "128x128x16 waves 4x4x1 A=KC/4 B=IM2COL/1"),
+    ("im2col 128x128x16 4B", (2, 6, 64, 64), (512, 6, 3, 3), (1, 1, 1, 1), (1, 1), "128x128x16 waves 4x4x1 A=KC/1 B=IM2COL/1"),
     ("im2col 256x256x16 16B", (8, 4, 64, 64), (512, 4, 5, 5), (2, 2, 2, 2), (1, 1), "256x256x16 waves 4x4x1 A=KC/4 B=IM2COL/1"),
     ("im2col 256x256x16 4B", (8, 6, 64, 64), (512, 6, 3, 3), (1, 1, 1, 1), (1, 1), "256x256x16 waves 4x4x1 A=KC/1 B=IM2COL/1"),
     ("rcs 64x64x16 16B", (2, 64, 12, 12), (96, 64, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x16 waves 2x2x1 A=KC/4 B=RCS/1"),
@@ -793,11 +796,14 @@ CONV_INSTANCE_CASES = [
     ("rcs 64x64x32 4B", (9, 514, 64, 64), (256, 514, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x32 waves 2x2x1 A=KC/1 B=RCS/1"),
     ("rcs sliced 16B", (2, 512, 14, 14), (128, 512, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x32 waves 2x2x2 A=KC/4 B=RCS/1"),
     ("rcs sliced 4B", (2, 510, 14, 14), (128, 510, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x32 waves 2x2x2 A=KC/1 B=RCS/1"),
+    ("rcs 128x128x16 16B", (2, 16, 128, 128), (512, 16, 1, 1), (0, 0, 0, 0), (2, 2), "128x128x16 waves 4x4x1 A=KC/4 B=RCS/1"),
+    ("rcs 128x128x16 4B", (2, 18, 128, 128), (512, 18, 1, 1), (0, 0, 0, 0), (2, 2), "128x128x16 waves 4x4x1 A=KC/1 B=RCS/1"),
     ("rcs 256x256x16 16B", (8, 16, 128, 128), (512, 16, 1, 1), (0, 0, 0, 0), (2, 2), "256x256x16 waves 4x4x1 A=KC/4 B=RCS/1"),
     ("rcs 256x256x16 4B", (8, 18, 128, 128), (512, 18, 1, 1), (0, 0, 0, 0), (2, 2), "256x256x16 waves 4x4x1 A=KC/1 B=RCS/1"),
     # pointwise convolutions: the row-contiguous loader with images as column blocks
     ("pointwise 16B/16B", (2, 64, 12, 12), (96, 64, 1, 1), (0, 0, 0, 0), (1, 1), "64x64x16 waves 2x2x1 A=KC/4 B=RC/4"),
     ("pointwise 16B/4B (P = 49)", (32, 512, 7, 7), (2048, 512, 1, 1), (0, 0, 0, 0), (1, 1), "64x64x32 waves 2x2x1 A=KC/4 B=RC/1"),
+    ("pointwise 128x128x16", (8, 64, 32, 32), (512, 64, 1, 1), (0, 0, 0, 0), (1, 1), "128x128x16 waves 4x4x1 A=KC/4 B=RC/4"),
     ("pointwise 256x256x16", (32, 64, 32, 32), (512, 64, 1, 1), (0, 0, 0, 0), (1, 1), "256x256x16 waves 4x4x1 A=KC/4 B=RC/4"),
 ]
 
