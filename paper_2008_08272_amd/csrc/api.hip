@@ -182,6 +182,12 @@ onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const f
     g.pT = (int)pads[0]; g.pL = (int)pads[1]; g.pB = (int)pads[2]; g.pR = (int)pads[3];
     g.dH = (int)dilations[0]; g.dW = (int)dilations[1];
 
+    if (group == 1) {
+        hipError_t e = hipSuccess;
+        if (launch_conv_resident(X, W, B, residual, Y, g, (int)M, (int)Cg, act == ONNX_ACT_RELU, s, &e))
+            return device_status(e, "conv (resident filters)");
+    }
+
     // images one tile of columns can touch, and the span of input they cover
     const int64_t tile_images = (kTileRows + P - 1) / P + 1;
     const bool use_mfma = Mg >= 16 && K >= 8 && NP <= kIntMax && kc_fits(K, K) &&

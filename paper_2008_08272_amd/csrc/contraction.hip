@@ -49,6 +49,9 @@ int pick_tile(int64_t M, int64_t N, int64_t K, int64_t nz) {
     double best_cost = 0.0;
     for (int t = 0; t < TILE_COUNT; ++t) {
         if (t == TILE_64_SLICED) continue;
+        // 16 wavefronts on a 128 x 128 tile pay off on a long K walk only (96 products of
+        // 512 x 512 x 64 ran at 60 instead of 75 TFLOP/s with it)
+        if (t == TILE_128 && K < 512) continue;
         const double tiles = (double)((M + bm[t] - 1) / bm[t]) * (double)((N + bm[t] - 1) / bm[t]) * (double)nz;
         double rounds = tiles / cus;
         if (resident[t] == 1) rounds = (double)(int64_t)((tiles + cus - 1) / cus);

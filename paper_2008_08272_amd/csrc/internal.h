@@ -78,6 +78,13 @@ struct WindowGeom {
     int kH, kW, sH, sW, pT, pL, pB, pR, dH, dW;
 };
 
+// Convolution with the filters held in registers by persistent workgroups (conv_resident.hip):
+// few input channels, large window (the 7x7 stride-2 stem of ResNet50).  group must be 1.
+// Returns false when no instance fits this shape; otherwise enqueues and stores the launch
+// status in *status.
+bool launch_conv_resident(const float* X, const float* W, const float* B, const float* residual, float* Y,
+                          const WindowGeom& g, int M, int Cg, int relu, hipStream_t stream, hipError_t* status);
+
 // Direct (one thread per output) convolution for shapes the matrix cores cannot use well:
 // depthwise and other tiny-K / tiny-M groups.
 hipError_t launch_conv_direct(const float* X, const float* W, const float* B, const float* residual,

@@ -235,6 +235,42 @@ def test_conv_matches_oracle(lib, case):
     assert (got2 >= 0).all()
 
 
+RESIDENT_CASES = [
+    # N, H, W, M, pads: 7x7 stride-2 convolutions of 3-channel images (the filters stay in registers)
+    (2, 37, 41, 64, (3, 3, 3, 3)),          # ragged tiles in both directions
+    (1, 224, 224, 64, (3, 3, 3, 3)),        # ResNet-50's stem: 14 x 7 whole tiles per image
+    (3, 64, 50, 96, (0, 2, 5, 1)),          # asymmetric pads, 96 filters: the second filter block is half empty
+    (2, 23, 130, 130, (6, 6, 6, 6)),        # pads as large as they may be, three filter blocks, one row of tiles
+    (5, 7, 7, 32, (0, 0, 0, 0)),            # a single output position per image
+]
+
+
+@pytest.mark.parametrize("case", RESIDENT_CASES)
+def test_conv_resident_filters_matches_oracle(lib, case):
+    N, H, W, M, pads = case
+    announce("conv resident", case)
+    rng = np.random.default_rng([N, H, W, M])
+    X = rng.uniform(-1, 1, (N, 3, H, W)).astype(np.float32)
+    Wt = rng.uniform(-1, 1, (M, 3, 7, 7)).astype(np.float32)
+    Bv = rng.uniform(-1, 1, (M,)).astype(np.float32)
+    ref, S = oracle.conv(X, Wt, Bv, pads, (2, 2), (1, 1), 1, want_scale=True)
+    got = host(lib.onnx_conv(dev(X), dev(Wt), dev(Bv), pads, (2, 2), (1, 1), 1))
+    assert lib.onnx_last_launch().startswith("conv_resident 64x128x147"), lib.onnx_last_launch()
+    assert got.shape == ref.shape
+    assert rel_err(got, ref) <= REL_TOL
+    assert within_rounding_bound(got, ref, S, 147 + 1)
+    R = rng.uniform(-1, 1, ref.shape).astype(np.float32)
+    ref2 = oracle.conv(X, Wt, None, pads, (2, 2), (1, 1), 1, residual=R, relu=True)
+    got2 = host(lib.onnx_conv(dev(X), dev(Wt), None, pads, (2, 2), (1, 1), 1, residual=dev(R), act=1))
+    assert rel_err(got2, ref2) <= REL_TOL
+    # small integers: every partial sum exact, so the bits must agree whatever the order of the k pairs
+    Xi = rng.integers(-4, 5, X.shape).astype(np.float32)
+    Wi = rng.integers(-4, 5, Wt.shape).astype(np.float32)
+    refi = oracle.conv(Xi, Wi, None, pads, (2, 2), (1, 1), 1)
+    goti = host(lib.onnx_conv(dev(Xi), dev(Wi), None, pads, (2, 2), (1, 1), 1))
+    assert np.array_equal(goti.astype(np.float64), refi)
+
+
 @pytest.mark.parametrize("a,b,dH,dW,pads,st", [
     (1, 1, 1, 1, (1, 1, 1, 1), (1, 1)), (0, 2, 2, 1, (1, 0, 3, 2), (1, 1)), (2, 0, 1, 2, (0, 2, 1, 4), (2, 3)),
 ])
@@ -311,6 +347,7 @@ def test_nan_and_inf_propagate_alike_on_every_conv_path(lib):
         ((2, 6, 12, 12), (32, 6, 5, 5), (2, 2, 2, 2), 1),        # gather loader
         ((2, 8, 12, 12), (8, 1, 3, 3), (1, 1, 1, 1), 8),         # row-strip (depthwise)
         ((2, 8, 12, 12), (8, 1, 5, 5), (2, 2, 2, 2), 8),         # direct
+        ((2, 3, 20, 20), (32, 3, 7, 7), (3, 3, 3, 3), 1),        # filters resident in registers (stride 2)
     ]
     for xs, ws_, pads, g in shapes:
         X = rng.uniform(0.5, 1, xs).astype(np.float32)
@@ -318,8 +355,9 @@ def test_nan_and_inf_propagate_alike_on_every_conv_path(lib):
         X[0, 0, 5, 5] = np.nan
         X[1, 1, 6, 6] = np.inf
         for relu in (False, True):
-            ref = oracle.conv(X, Wt, None, pads, (1, 1), (1, 1), g, relu=relu)
-            got = host(lib.onnx_conv(dev(X), dev(Wt), None, pads, (1, 1), (1, 1), g, act=int(relu)))
+            st = (2, 2) if ws_[2] == 7 else (1, 1)
+            ref = oracle.conv(X, Wt, None, pads, st, (1, 1), g, relu=relu)
+            got = host(lib.onnx_conv(dev(X), dev(Wt), None, pads, st, (1, 1), g, act=int(relu)))
             assert np.array_equal(np.isnan(got), np.isnan(ref)), (xs, ws_, relu)
             assert np.array_equal(np.isinf(got), np.isinf(ref)), (xs, ws_, relu)
             fin = np.isfinite(ref)
@@ -748,7 +786,7 @@ GEMM_TILE_CLASSES = {
     "64x64x16": ((132, 200, 72), "64x64x16 waves 2x2x1"),
     "64x64x32": ((1500, 1504, 512), "64x64x32 waves 2x2x1"),
     "64x64x32 sliced": ((200, 152, 300), "64x64x32 waves 2x2x2"),
-    "128x128x16": ((2048, 2048, 40), "128x128x16 waves 4x4x1"),
+    "128x128x16": ((2048, 2048, 512), "128x128x16 waves 4x4x1"),
     "256x256x16": ((4096, 4096, 40), "256x256x16 waves 4x4x1"),
 }
 
@@ -781,13 +819,13 @@ def test_every_gemm_instance(lib, tile, transA, transB, loads):
 CONV_INSTANCE_CASES = [
     # name, X shape, W shape, pads, strides, expected instance prefix
     ("im2col 64x64x16 16B", (1, 8, 14, 14), (16, 8, 5, 5), (2, 2, 2, 2), (1, 1), "64x64x16 waves 2x2x1 A=KC/4 B=IM2COL/1"),
-    ("im2col 64x64x16 4B", (2, 3, 37, 41), (64, 3, 7, 7), (3, 3, 3, 3), (2, 2), "64x64x16 waves 2x2x1 A=KC/1 B=IM2COL/1"),
+    ("im2col 64x64x16 4B", (2, 3, 37, 41), (64, 3, 5, 5), (2, 2, 2, 2), (2, 2), "64x64x16 waves 2x2x1 A=KC/1 B=IM2COL/1"),
     ("im2col 64x64x32 16B", (16, 24, 48, 48), (64, 24, 5, 5), (2, 2, 2, 2), (1, 1), "64x64x32 waves 2x2x1 A=KC/4 B=IM2COL/1"),
     ("im2col 64x64x32 4B", (16, 25, 48, 48), (64, 25, 5, 5), (2, 2, 2, 2), (1, 1), "64x64x32 waves 2x2x1 A=KC/1 B=IM2COL/1"),
     ("im2col sliced 16B", (2, 24, 20, 20), (64, 24, 5, 5), (2, 2, 2, 2), (1, 1), "64x64x32 waves 2x2x2 A=KC/4 B=IM2COL/1"),
     ("im2col sliced 4B", (2, 25, 20, 20), (64, 25, 5, 5), (2, 2, 2, 2), (1, 1), "64x64x32 waves 2x2x2 A=KC/1 B=IM2COL/1"),
-    ("im2col 128x128x16 16B", (2, 4, 64, 64), (512, 4, 5, 5), (2, 2, 2, 2), (1, 1), "128x128x16 waves 4x4x1 A=KC/4 B=IM2COL/1"),
-    ("im2col 128x128x16 4B", (2, 6, 64, 64), (512, 6, 3, 3), (1, 1, 1, 1), (1, 1), "128x128x16 waves 4x4x1 A=KC/1 B=IM2COL/1"),
+    ("im2col 128x128x16 16B", (2, 24, 64, 64), (512, 24, 5, 5), (2, 2, 2, 2), (1, 1), "128x128x16 waves 4x4x1 A=KC/4 B=IM2COL/1"),
+    ("im2col 128x128x16 4B", (2, 21, 64, 64), (512, 21, 5, 5), (2, 2, 2, 2), (1, 1), "128x128x16 waves 4x4x1 A=KC/1 B=IM2COL/1"),
     ("im2col 256x256x16 16B", (8, 4, 64, 64), (512, 4, 5, 5), (2, 2, 2, 2), (1, 1), "256x256x16 waves 4x4x1 A=KC/4 B=IM2COL/1"),
     ("im2col 256x256x16 4B", (8, 6, 64, 64), (512, 6, 3, 3), (1, 1, 1, 1), (1, 1), "256x256x16 waves 4x4x1 A=KC/1 B=IM2COL/1"),
     ("rcs 64x64x16 16B", (2, 64, 12, 12), (96, 64, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x16 waves 2x2x1 A=KC/4 B=RCS/1"),
@@ -796,14 +834,14 @@ CONV_INSTANCE_CASES = [
     ("rcs 64x64x32 4B", (9, 514, 64, 64), (256, 514, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x32 waves 2x2x1 A=KC/1 B=RCS/1"),
     ("rcs sliced 16B", (2, 512, 14, 14), (128, 512, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x32 waves 2x2x2 A=KC/4 B=RCS/1"),
     ("rcs sliced 4B", (2, 510, 14, 14), (128, 510, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x32 waves 2x2x2 A=KC/1 B=RCS/1"),
-    ("rcs 128x128x16 16B", (2, 16, 128, 128), (512, 16, 1, 1), (0, 0, 0, 0), (2, 2), "128x128x16 waves 4x4x1 A=KC/4 B=RCS/1"),
-    ("rcs 128x128x16 4B", (2, 18, 128, 128), (512, 18, 1, 1), (0, 0, 0, 0), (2, 2), "128x128x16 waves 4x4x1 A=KC/1 B=RCS/1"),
+    ("rcs 128x128x16 16B", (2, 512, 128, 128), (512, 512, 1, 1), (0, 0, 0, 0), (2, 2), "128x128x16 waves 4x4x1 A=KC/4 B=RCS/1"),
+    ("rcs 128x128x16 4B", (2, 514, 128, 128), (512, 514, 1, 1), (0, 0, 0, 0), (2, 2), "128x128x16 waves 4x4x1 A=KC/1 B=RCS/1"),
     ("rcs 256x256x16 16B", (8, 16, 128, 128), (512, 16, 1, 1), (0, 0, 0, 0), (2, 2), "256x256x16 waves 4x4x1 A=KC/4 B=RCS/1"),
     ("rcs 256x256x16 4B", (8, 18, 128, 128), (512, 18, 1, 1), (0, 0, 0, 0), (2, 2), "256x256x16 waves 4x4x1 A=KC/1 B=RCS/1"),
     # pointwise convolutions: the row-contiguous loader with images as column blocks
     ("pointwise 16B/16B", (2, 64, 12, 12), (96, 64, 1, 1), (0, 0, 0, 0), (1, 1), "64x64x16 waves 2x2x1 A=KC/4 B=RC/4"),
     ("pointwise 16B/4B (P = 49)", (32, 512, 7, 7), (2048, 512, 1, 1), (0, 0, 0, 0), (1, 1), "64x64x32 waves 2x2x1 A=KC/4 B=RC/1"),
-    ("pointwise 128x128x16", (8, 64, 32, 32), (512, 64, 1, 1), (0, 0, 0, 0), (1, 1), "128x128x16 waves 4x4x1 A=KC/4 B=RC/4"),
+    ("pointwise 128x128x16", (8, 512, 32, 32), (512, 512, 1, 1), (0, 0, 0, 0), (1, 1), "128x128x16 waves 4x4x1 A=KC/4 B=RC/4"),
     ("pointwise 256x256x16", (32, 64, 32, 32), (512, 64, 1, 1), (0, 0, 0, 0), (1, 1), "256x256x16 waves 4x4x1 A=KC/4 B=RC/4"),
 ]
 
