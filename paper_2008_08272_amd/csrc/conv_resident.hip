@@ -159,9 +159,37 @@ __global__ __launch_bounds__(512, 2) void conv_resident_kernel(const ResidentPar
         }
     };
 
-    const __amdgpu_buffer_rsrc_t rbias = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(cp.bias ? cp.bias : cp.W), 0, cp.bias ? cp.M * 4 : 0, RSRC_FLAGS);
+    // the bias of the 16 filter rows this lane's accumulator registers hold: the same for every tile
+    float bias_r[16];
+    {
+        const __amdgpu_buffer_rsrc_t rbias = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(cp.bias ? cp.bias : cp.W), 0, cp.bias ? cp.M * 4 : 0, RSRC_FLAGS);
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            bias_r[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rbias, (m0 + 8 * (r / 4) + 4 * h + r % 4) * 4, 0, 0));
+    }
     const bool has_res = cp.residual != nullptr;
     const bool relu = cp.relu != 0;
+
+    // Epilogue of one tile: bias, residual, Relu, store.
+    auto epilogue = [&](int tile, const floatx16& acc) {
+        const int n = tile / per_image, rem = tile - n * per_image;
+        const int ty = rem / cp.tiles_x, tx = rem - ty * cp.tiles_x;
+        const int oh = ty * S::TH + pos_r, ow = tx * S::TW + pos_c;
+        const bool pos_ok = oh < cp.OH && ow < cp.OW;
+        const int64_t img = (int64_t)n * cp.M * P;
+        const __amdgpu_buffer_rsrc_t ry = tile_rsrc(cp.Y + img);
+        const __amdgpu_buffer_rsrc_t rr = tile_rsrc(has_res ? cp.residual + img : cp.Y + img);
+        const int pix = oh * cp.OW + ow;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = m0 + 8 * (r / 4) + 4 * h + r % 4;   // accumulator register r holds this row
+            const int off = (pos_ok && m < cp.M) ? (m * P + pix) * 4 : (int)OOB;
+            float v = acc[r] + bias_r[r];
+            if (has_res) v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rr, off, 0, 0));
+            if (relu) v = fmaxf(v, 0.f);
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), ry, off, 0, 0);
+        }
+    };
 
     int tile = blockIdx.x;
     if (tile >= cp.total_tiles) return;                 // uniform per workgroup
@@ -183,38 +211,22 @@ __global__ __launch_bounds__(512, 2) void conv_resident_kernel(const ResidentPar
         const float* src = lds[buf];
 #pragma unroll
         for (int p = 0; p < AHEAD && p < NP; ++p) fb[p % RING] = src[bb[T.kind[p]] + S::loff(T.k0[p])];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             if (p + AHEAD < NP) fb[(p + AHEAD) % RING] = src[bb[T.kind[p + AHEAD]] + S::loff(T.k0[p + AHEAD])];
             if (p % 2 == 0) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[p], fb[p % RING], acc, 0, 0, 0);
             else acc_odd = __builtin_amdgcn_mfma_f32_32x32x2f32(a[p], fb[p % RING], acc_odd, 0, 0, 0);
+            // keep the read AHEAD pairs in front of its MFMA: left alone, the scheduler sinks every
+            // read to just before its use and each MFMA then waits out a whole LDS round trip
+            __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] += acc_odd[r];
 
         if (more) commit(lds[buf ^ 1]);
         __syncthreads();
-
-        // ---- epilogue of this tile: bias, residual, Relu, store
-        {
-            const int n = tile / per_image, rem = tile - n * per_image;
-            const int ty = rem / cp.tiles_x, tx = rem - ty * cp.tiles_x;
-            const int oh = ty * S::TH + pos_r, ow = tx * S::TW + pos_c;
-            const bool pos_ok = oh < cp.OH && ow < cp.OW;
-            const int64_t img = (int64_t)n * cp.M * P;
-            const __amdgpu_buffer_rsrc_t ry = tile_rsrc(cp.Y + img);
-            const __amdgpu_buffer_rsrc_t rr = tile_rsrc(has_res ? cp.residual + img : cp.Y + img);
-            const int pix = oh * cp.OW + ow;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = m0 + 8 * (r / 4) + 4 * h + r % 4;   // accumulator register r holds this row
-                const int off = (pos_ok && m < cp.M) ? (m * P + pix) * 4 : (int)OOB;
-                float v = acc[r] + __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rbias, m * 4, 0, 0));
-                if (has_res) v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rr, off, 0, 0));
-                if (relu) v = fmaxf(v, 0.f);
-                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), ry, off, 0, 0);
-            }
-        }
+        epilogue(tile, acc);
         if (!more) break;
         tile = next;
         buf ^= 1;
