@@ -9,6 +9,8 @@ GPU is one library call per fused operator:
     infer_shapes          extents of every tensor (the library's own shape-inference entry points)
     decompose_reducel1    ReduceL1(x) -> ReduceSum(Abs(x))
     eliminate_identity    Identity(x) -> x
+    propagate_constants   element-wise operators on constants only are evaluated now; Adds that mix
+                          constants and activations are normalised so that the constants meet
     fold_batchnorm        Conv with constant filters + BatchNormalization with constant
                           parameters -> Conv with rescaled filters and a bias
     matmul_add_to_gemm    Add(MatMul(A, B), C) -> Gemm(A, B, C)
@@ -190,6 +192,113 @@ def fold_batchnorm(model):
     return _drop_unused_weights(out)
 
 
+def _fold_constant_nodes(out):
+    """Evaluates Add / Relu / Abs / LeakyRelu / Identity / Reshape nodes whose inputs are all
+    constants (fp32, one rounding per operator, as the kernels would) and makes their results
+    constants of the graph."""
+    w = out["weights"]
+    changed = False
+    for nd in list(out["graph"]):
+        op = nd["op"]
+        if op not in ("add", "relu", "abs", "leakyrelu", "identity", "reshape"):
+            continue
+        ins = [nd[f] for f in _INPUTS[op] if nd.get(f)]
+        if not ins or any(t not in w for t in ins) or nd["y"] == out["output"]:
+            continue
+        if op == "add":
+            v = w[nd["a"]] + w[nd["b"]]
+        elif op == "relu":
+            v = np.where(w[nd["x"]] > 0, w[nd["x"]], np.float32(0))
+        elif op == "abs":
+            v = np.abs(w[nd["x"]])
+        elif op == "leakyrelu":
+            v = np.where(w[nd["x"]] >= 0, w[nd["x"]], np.float32(nd["alpha"]) * w[nd["x"]])
+        elif op == "reshape":
+            v = np.reshape(w[nd["x"]], nd["shape"])
+        else:
+            v = w[nd["x"]]
+        w[nd["y"]] = np.ascontiguousarray(v, dtype=np.float32)
+        out["graph"].remove(nd)
+        changed = True
+    return changed
+
+
+def propagate_constants(model):
+    """Constant propagation (Section 3.4).  An operator all of whose inputs are constants is
+    evaluated here and removed (element-wise operators and Reshape; BatchNormalization on a
+    convolution is fold_batchnorm's business).  Adds that mix constants c and activations x, y
+    are normalised with the paper's rules, which move the constants outwards until they meet:
+        c + x               ->  x + c
+        (x + c1) + c2       ->  x + (c1 + c2)
+        (x + c) + y         ->  (x + y) + c
+        x + (y + c)         ->  (x + y) + c
+        (x + c1) + (y + c2) ->  (x + y) + (c1 + c2)
+    An inner Add is only taken apart when nothing else reads its result.  The sum of two
+    constants is formed in fp32 like any Add, so the rewritten graph differs from the original
+    by the rounding of a reassociated fp32 sum, not more."""
+    out = _clone(model)
+    w = out["weights"]
+    counter = [0]
+
+    def fresh(stem):
+        counter[0] += 1
+        return "%s_cp%d" % (stem, counter[0])
+
+    changed = True
+    while changed:
+        changed = _fold_constant_nodes(out)
+        uses, prod = _uses(out), _producers(out)
+
+        def const_add(name):
+            """(x, c) when `name` is the single-use result of Add(x, c) with c constant, x not."""
+            if name not in prod or uses.get(name, 0) != 1:
+                return None
+            nd = out["graph"][prod[name]]
+            if nd["op"] == "add" and nd["b"] in w and nd["a"] not in w:
+                return nd
+            return None
+
+        for nd in out["graph"]:
+            if nd["op"] != "add":
+                continue
+            a, b = nd["a"], nd["b"]
+            if a in w and b not in w:                                  # c + x -> x + c
+                nd["a"], nd["b"] = b, a
+                changed = True
+                break
+            if a in w:
+                continue                                               # both constant: folded above
+            ia, ib = const_add(a), (None if b in w else const_add(b))
+            if b in w and ia is not None:                              # (x + c1) + c2 -> x + (c1 + c2)
+                c = fresh("c")
+                w[c] = np.ascontiguousarray(w[ia["b"]] + w[b], dtype=np.float32)
+                nd["a"], nd["b"] = ia["a"], c
+                out["graph"].remove(ia)
+                changed = True
+                break
+            if b in w:
+                continue
+            if ia is not None and ib is not None:                      # (x + c1) + (y + c2) -> (x + y) + (c1 + c2)
+                c, t = fresh("c"), fresh(nd["y"])
+                w[c] = np.ascontiguousarray(w[ia["b"]] + w[ib["b"]], dtype=np.float32)
+                i = out["graph"].index(nd)
+                out["graph"][i:i + 1] = [dict(op="add", a=ia["a"], b=ib["a"], y=t), dict(op="add", a=t, b=c, y=nd["y"])]
+                out["graph"].remove(ia)
+                out["graph"].remove(ib)
+                changed = True
+                break
+            inner, other = (ia, b) if ia is not None else (ib, a)
+            if inner is not None:                                      # (x + c) + y  /  x + (y + c) -> (x + y) + c
+                t = fresh(nd["y"])
+                first, second = (inner["a"], other) if inner is ia else (other, inner["a"])
+                i = out["graph"].index(nd)
+                out["graph"][i:i + 1] = [dict(op="add", a=first, b=second, y=t), dict(op="add", a=t, b=inner["b"], y=nd["y"])]
+                out["graph"].remove(inner)
+                changed = True
+                break
+    return _drop_unused_weights(out)
+
+
 def matmul_add_to_gemm(model):
     """Add(MatMul(A, B), C) with 2-D A and B, the product used only by the Add, and C
     broadcastable to the product's shape, becomes Gemm(A, B, C) with alpha = beta = 1 (the
@@ -262,6 +371,7 @@ def optimize(model):
     """All passes, in the order that lets each see the patterns the previous one exposed."""
     m = decompose_reducel1(model)
     m = eliminate_identity(m)
+    m = propagate_constants(m)
     m = fold_batchnorm(m)
     m = matmul_add_to_gemm(m)
     m = fuse_epilogue(m)

@@ -672,6 +672,22 @@ def test_unfused_graphs_through_the_passes(lib, workspace):
         assert worst <= REL_TOL
 
 
+def test_constant_propagation_graph_on_the_gpu(lib, workspace):
+    """Chained Adds of constants (the paper's normalisation rules, Section 3.4): the rewritten graph
+    runs on the GPU, the reference is the oracle on the graph as written."""
+    announce("constant propagation + runner")
+    from oracle import chain
+    from paper_2008_08272_amd import passes
+    raw = workloads.constant_adds()
+    _, exact = chain.run(raw)
+    opt = passes.optimize(raw)
+    assert sum(nd["op"] == "add" for nd in opt["graph"]) == 4
+    r, got = _run_chain(lib, opt, workspace)
+    assert rel_err(got, exact["out"]) <= REL_TOL
+    _, got_raw = _run_chain(lib, raw, workspace)           # the unrewritten graph runs too, operator by operator
+    assert rel_err(got_raw, exact["out"]) <= REL_TOL
+
+
 # ------------------------------------------------------------------------------ seeded random sweeps
 
 def _random_conv_case(rng):

@@ -145,3 +145,62 @@ def test_infer_shapes_matches_the_oracle_chain():
     bad["graph"][7] = workloads.reshape_node("p2", "flat", (1, 255))
     with pytest.raises(ValueError):
         passes.infer_shapes(bad)
+
+
+def test_constant_propagation_normalises_adds_and_folds_constants():
+    """Section 3.4's Add normalisation rules: after the pass every constant of the chain has met
+    in one constant, operators on constants only are gone, and the graph computes the same
+    function (up to the rounding of the reassociated fp32 sums)."""
+    raw = workloads.constant_adds()
+    assert ops(raw) == collections.Counter(add=9, relu=2)
+    opt = passes.propagate_constants(raw)
+    assert ops(opt) == collections.Counter(add=4, relu=1)
+    consts = [nd for nd in opt["graph"] if nd["op"] == "add" and nd["b"] in opt["weights"]]
+    assert len(consts) == 1 and consts[0]["y"] == "out" and len(opt["weights"]) == 1
+    assert not any(nd["op"] == "add" and nd["a"] in opt["weights"] for nd in opt["graph"])
+    # the merged constant is the sum of all constants of the original chain, broadcast
+    w = raw["weights"]
+    k2 = np.maximum(w["c5"].astype(np.float64) + w["c6"], 0)
+    want = w["c1"].astype(np.float64) + w["c2"] + k2 + w["c3"] + w["c4"]
+    got = opt["weights"][consts[0]["b"]]
+    assert got.dtype == np.float32 and got.shape == want.shape
+    assert np.abs(got - want).max() <= 8 * 2.0 ** -24 * np.abs(want).max()
+    _, e_raw = oracle.chain.run(raw)
+    _, e_opt = oracle.chain.run(opt)
+    assert rel_err(e_opt["out"], e_raw["out"]) <= 1e-6
+    assert ops(raw) == collections.Counter(add=9, relu=2)          # the input graph is left untouched
+
+
+@pytest.mark.parametrize("rule", ["c+x", "(x+c1)+c2", "(x+c)+y", "x+(y+c)", "(x+c1)+(y+c2)", "shared inner"])
+def test_each_add_normalisation_rule(rule):
+    rng = np.random.default_rng(11)
+    x, y = rng.standard_normal((2, 3, 4)).astype(np.float32), rng.standard_normal((2, 3, 4)).astype(np.float32)
+    c1, c2 = rng.standard_normal((3, 1)).astype(np.float32), rng.standard_normal((4,)).astype(np.float32)
+    A = workloads.add_node
+    graphs = {
+        "c+x": [A("c1", "x", "out")],
+        "(x+c1)+c2": [A("x", "c1", "t"), A("t", "c2", "out")],
+        "(x+c)+y": [A("x", "c1", "t"), A("t", "y", "out")],
+        "x+(y+c)": [A("y", "c1", "t"), A("x", "t", "out")],
+        "(x+c1)+(y+c2)": [A("x", "c1", "t"), A("y", "c2", "u"), A("t", "u", "out")],
+        "shared inner": [A("x", "c1", "t"), A("t", "c2", "u"), A("t", "u", "out")],     # t has two readers: it stays
+    }
+    raw = dict(name=rule, inputs={"x": x, "y": y}, weights={"c1": c1, "c2": c2}, graph=graphs[rule], output="out")
+    opt = passes.propagate_constants(raw)
+    g = opt["graph"]
+    if rule == "c+x":
+        assert [(n["a"], n["b"]) for n in g] == [("x", "c1")]
+    elif rule == "(x+c1)+c2":
+        assert len(g) == 1 and g[0]["a"] == "x" and np.array_equal(opt["weights"][g[0]["b"]], c1 + c2)
+    elif rule in ("(x+c)+y", "x+(y+c)"):
+        assert len(g) == 2 and {g[0]["a"], g[0]["b"]} == {"x", "y"} and (g[1]["a"], g[1]["b"]) == (g[0]["y"], "c1")
+    elif rule == "(x+c1)+(y+c2)":
+        assert len(g) == 2 and (g[0]["a"], g[0]["b"]) == ("x", "y") and np.array_equal(opt["weights"][g[1]["b"]], c1 + c2)
+    else:
+        # t = x + c1 is read twice and is left alone; u = t + c2 is read once: t + (t + c2) -> (t + t) + c2
+        assert len(g) == 3 and (g[0]["a"], g[0]["b"], g[0]["y"]) == ("x", "c1", "t")
+        assert (g[1]["a"], g[1]["b"]) == ("t", "t") and (g[2]["a"], g[2]["b"], g[2]["y"]) == (g[1]["y"], "c2", "out")
+    _, e_raw = oracle.chain.run(raw)
+    _, e_opt = oracle.chain.run(opt)
+    assert rel_err(e_opt["out"], e_raw["out"]) <= 1e-6
+    assert passes.infer_shapes(opt)["out"] == passes.infer_shapes(raw)["out"]

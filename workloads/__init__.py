@@ -177,6 +177,32 @@ def classifier_head(batch=32, classes=1000, features=2048, seed=SEED_BASE + 6):
     return dict(name="classifier_head", inputs=inputs, weights=weights, graph=graph, output="prob")
 
 
+def constant_adds(batch=4, channels=16, hw=12, seed=SEED_BASE + 8):
+    """A graph with chained Adds of constants around two activations, every shape of the paper's
+    Add normalisation rules (Section 3.4, constant propagation) once, plus an Add and a Relu of
+    constants only:  x, y = Relu(x)  ->  c1 + x,  (x + c1) + c2,  (x + c) + y,  x + (y + c),
+    (x + c1) + (y + c2), with per-channel, scalar and full-tensor constants."""
+    r = _rng(seed, 0)
+    inputs = {"x": _normal(r, (batch, channels, hw, hw), 1.0)}
+    weights = {"c1": _normal(r, (1, channels, 1, 1), 1.0), "c2": _normal(r, (1, channels, 1, 1), 1.0),
+               "c3": _normal(r, (), 1.0).reshape(()), "c4": _normal(r, (channels, hw, hw), 1.0),
+               "c5": _normal(r, (1, channels, 1, 1), 1.0), "c6": _normal(r, (hw,), 1.0)}
+    graph = [
+        relu_node("x", "y"),
+        add_node("c1", "x", "t1"),            # c + x
+        add_node("t1", "c2", "t2"),           # (x + c1) + c2
+        add_node("t2", "y", "t3"),            # (x + c) + y
+        add_node("c5", "c6", "k1"),           # constants only
+        relu_node("k1", "k2"),                # constants only
+        add_node("y", "k2", "t4"),            # y + c
+        add_node("t3", "t4", "t5"),           # (u + c) + (y + c')
+        add_node("x", "c3", "t6"),            # x + c
+        add_node("t5", "t6", "t7"),           # u + (x + c)
+        add_node("t7", "c4", "out"),
+    ]
+    return dict(name="constant_adds", inputs=inputs, weights=weights, graph=graph, output="out")
+
+
 # --------------------------------------------------------------------------- config 2
 
 def gemm_case(n, seed=SEED_BASE + 2, m=None, k=None):
