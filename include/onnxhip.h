@@ -241,16 +241,39 @@ typedef enum { ONNX_F32 = 0, ONNX_F16 = 1, ONNX_BF16 = 2 } onnx_dtype;
 
 /*
  * ONNX Gemm on 16-bit floating-point inputs (the operator definitions admit F16 tensors,
- * Section 3.1): Y = alpha * A * B' + beta * C with A [M,K] and B [N,K] (transA = 0, transB = 1:
- * both operands K-contiguous; other layouts are ONNX_ERR_UNSUPPORTED) stored as
- * in_type.  Products are exact and summed in fp32; C (NULL, or fp32 broadcastable to [M,N] as
- * for onnx_gemm) and the epilogue are fp32; Y is stored as out_type: ONNX_F32, or in_type with
- * round-to-nearest-even.  K must be a multiple of 8 and A, B 16-byte aligned.
+ * Section 3.1): Y = alpha * op(A) * op(B) + beta * C with A and B stored as in_type, every
+ * transA / transB combination, any K.  Products are exact and summed in fp32; C (NULL, or fp32
+ * broadcastable to [M,N] as for onnx_gemm) and the epilogue are fp32; Y is stored as out_type:
+ * ONNX_F32, or in_type with round-to-nearest-even.  The tuned kernel takes transA = 0,
+ * transB = 1 (both operands K-contiguous) with K a multiple of 8 and A, B 16-byte aligned;
+ * every other case runs through a general, slower kernel that transposes operands on their way
+ * into LDS.
  */
 onnx_status onnx_gemm_lp(const void* A, const int64_t a_dims[2], const void* B, const int64_t b_dims[2],
                          const float* C, const int64_t* c_dims, int c_rank, float alpha, float beta,
                          int transA, int transB, onnx_act act, void* Y, const int64_t y_dims[2],
                          onnx_dtype in_type, onnx_dtype out_type, void* stream);
+
+/*
+ * ONNX MatMul on 16-bit inputs: numpy.matmul semantics as onnx_matmul, A and B stored as in_type,
+ * fp32 accumulation, Y stored as out_type (ONNX_F32 or in_type, rounded to nearest even).
+ */
+onnx_status onnx_matmul_lp(const void* A, const int64_t* a_dims, int a_rank, const void* B,
+                           const int64_t* b_dims, int b_rank, void* Y, const int64_t* y_dims, int y_rank,
+                           onnx_dtype in_type, onnx_dtype out_type, void* stream);
+
+/*
+ * ONNX Conv on 16-bit inputs: the semantics, attributes and errors of onnx_conv; X and W stored
+ * as in_type, the bias B in fp32 ([M] or NULL), fp32 accumulation, Y and the optional residual
+ * stored as out_type (ONNX_F32 or in_type, rounded to nearest even).  Every shape runs through
+ * one general kernel (the pointwise case reads the input row-contiguously, the others gather
+ * it); no workspace is used.
+ */
+onnx_status onnx_conv_lp(const void* X, const int64_t x_dims[4], const void* W, const int64_t w_dims[4],
+                         const float* B, const int64_t pads[4], const int64_t strides[2],
+                         const int64_t dilations[2], int64_t group, const void* residual, onnx_act act,
+                         void* Y, const int64_t y_dims[4], onnx_dtype in_type, onnx_dtype out_type,
+                         void* stream);
 
 /*
  * ONNX LSTM (named among the supported operators, Section 4.1), layout 0, default activations

@@ -68,6 +68,10 @@ for _f in (_lib.onnx_broadcast_infer, _lib.onnx_reduce_infer, _lib.onnx_add, _li
 _lib.onnx_gemm_lp.argtypes = [_vp, _i64p, _vp, _i64p, _vp, _i64p, _ci, _cf, _cf, _ci, _ci, _ci, _vp, _i64p, _ci, _ci, _vp]
 _lib.onnx_gemm_lp.restype = _ci
 F32, F16, BF16 = 0, 1, 2
+_lib.onnx_matmul_lp.argtypes = [_vp, _i64p, _ci, _vp, _i64p, _ci, _vp, _i64p, _ci, _ci, _ci, _vp]
+_lib.onnx_matmul_lp.restype = _ci
+_lib.onnx_conv_lp.argtypes = [_vp, _i64p, _vp, _i64p, _vp, _i64p, _i64p, _i64p, _c64, _vp, _ci, _vp, _i64p, _ci, _ci, _vp]
+_lib.onnx_conv_lp.restype = _ci
 _lib.onnx_lstm_scratch_bytes.argtypes = [_i64p, _c64, _ci]
 _lib.onnx_lstm_scratch_bytes.restype = ctypes.c_size_t
 _lib.onnx_lstm.argtypes = [_vp, _i64p, _vp, _vp, _vp, _vp, _vp, _c64, _ci, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
@@ -320,6 +324,52 @@ def onnx_gemm_lp(A, B, C=None, alpha=1.0, beta=1.0, transA=0, transB=1, act=ACT_
                              int(transA), int(transB), int(act), _ptr(out), dims(out.shape), _LP_TYPES[A.dtype],
                              F32 if out_dtype == torch.float32 else _LP_TYPES[A.dtype], _stream(stream)))
     return out
+
+
+def _lp(t, name, like=None):
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype in _LP_TYPES and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous float16 or bfloat16 tensor on the GPU" % name)
+    if like is not None and t.dtype != like.dtype:
+        raise TypeError("%s must have the type of the other 16-bit operands" % name)
+    return t
+
+
+def _lp_out(out, shape, out_dtype, like):
+    out_dtype = like.dtype if out_dtype is None else out_dtype
+    if out_dtype not in (torch.float32, like.dtype):
+        raise TypeError("out_dtype must be torch.float32 or the inputs' type")
+    if out is None:
+        out = torch.empty(tuple(shape), dtype=out_dtype, device=like.device)
+    elif not (out.is_cuda and out.dtype == out_dtype and out.is_contiguous()):
+        raise TypeError("out must be a contiguous GPU tensor of out_dtype")
+    return out, (F32 if out_dtype == torch.float32 else _LP_TYPES[like.dtype])
+
+
+def onnx_matmul_lp(A, B, out_dtype=None, out=None, stream=None):
+    """MatMul on float16 / bfloat16 CUDA tensors, result in ``out_dtype`` (default: the inputs' type)."""
+    A = _lp(A, "A")
+    B = _lp(B, "B", A)
+    Y, ot = _lp_out(out, onnx_matmul_infer(A.shape, B.shape), out_dtype, A)
+    _check(_lib.onnx_matmul_lp(_ptr(A), dims(A.shape), A.dim(), _ptr(B), dims(B.shape), B.dim(), _ptr(Y), dims(Y.shape),
+                               Y.dim(), _LP_TYPES[A.dtype], ot, _stream(stream)))
+    return Y
+
+
+def onnx_conv_lp(X, W, B=None, pads=(0, 0, 0, 0), strides=(1, 1), dilations=(1, 1), group=1, residual=None,
+                 act=ACT_NONE, out_dtype=None, out=None, stream=None):
+    """Conv on float16 / bfloat16 CUDA tensors X, W; fp32 bias B; result (and residual) in ``out_dtype``."""
+    X = _lp(X, "X")
+    W = _lp(W, "W", X)
+    B = _dev(B, "B")
+    Y, ot = _lp_out(out, onnx_conv_infer(X.shape, W.shape, pads, strides, dilations, group), out_dtype, X)
+    if residual is not None and not (residual.is_cuda and residual.dtype == Y.dtype and residual.is_contiguous()):
+        raise TypeError("residual must be a contiguous GPU tensor of the result's type")
+    _check(_lib.onnx_conv_lp(_ptr(X), dims(X.shape), _ptr(W), dims(W.shape), _ptr(B), dims(pads), dims(strides),
+                             dims(dilations), int(group), _ptr(residual), int(act), _ptr(Y), dims(Y.shape),
+                             _LP_TYPES[X.dtype], ot, _stream(stream)))
+    return Y
 
 
 def onnx_lstm(X, W, R, B=None, initial_h=None, initial_c=None, direction="forward", stream=None):

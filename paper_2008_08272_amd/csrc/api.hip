@@ -139,7 +139,7 @@ onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const f
                                 const float* B, const int64_t pads[4], const int64_t strides[2],
                                 const int64_t dilations[2], int64_t group, const float* residual, onnx_act act,
                                 float* Y, const int64_t y_dims[4], const Workspace* caller_ws, int64_t max_outputs,
-                                void* stream) {
+                                void* stream, onnx_dtype in_type = ONNX_F32, onnx_dtype out_type = ONNX_F32) {
     if (!x_dims || !w_dims || !y_dims) return fail(ONNX_ERR_NULL, "conv: NULL dims array");
     int64_t yd[4];
     const onnx_status st = onnx_conv_infer(x_dims, w_dims, pads, strides, dilations, group, yd);
@@ -159,8 +159,9 @@ onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const f
                     "sized for; use onnx_conv with onnx_set_workspace", (long long)ny, (long long)max_outputs);
     if (!X || !W || !Y) return fail(ONNX_ERR_NULL, "conv: X, W and Y must not be NULL");
     const int64_t nx = N * C * H * Wd, nw = M * Cg * kH * kW;
-    if (overlaps(Y, ny * 4, X, nx * 4) || overlaps(Y, ny * 4, W, nw * 4) || overlaps(Y, ny * 4, B, M * 4) ||
-        overlaps(Y, ny * 4, residual, ny * 4))
+    const int64_t esz = in_type == ONNX_F32 ? 4 : 2, ysz = out_type == ONNX_F32 ? 4 : 2;     // bytes per element
+    if (overlaps(Y, ny * ysz, X, nx * esz) || overlaps(Y, ny * ysz, W, nw * esz) || overlaps(Y, ny * ysz, B, M * 4) ||
+        overlaps(Y, ny * ysz, residual, ny * ysz))
         return fail(ONNX_ERR_ALIAS, "conv: Y overlaps an input");
     const int64_t K = Cg * kH * kW, Mg = M / group, NP = N * P;
     if (C * H * Wd > kIntMax || M * P > kIntMax || K > kIntMax || pads[0] > kIntMax || pads[1] > kIntMax ||
@@ -181,6 +182,33 @@ onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const f
     g.kH = (int)kH; g.kW = (int)kW; g.sH = (int)strides[0]; g.sW = (int)strides[1];
     g.pT = (int)pads[0]; g.pL = (int)pads[1]; g.pB = (int)pads[2]; g.pR = (int)pads[3];
     g.dH = (int)dilations[0]; g.dW = (int)dilations[1];
+
+    if (in_type != ONNX_F32) {
+        // 16-bit tensors: one general kernel; the pointwise case reads the input as a row-contiguous
+        // matrix per image, everything else gathers it
+        if (NP > kIntMax || group > 32768LL * 65535LL)
+            return fail(ONNX_ERR_UNSUPPORTED, "conv (16-bit): more than 2^31-1 output positions");
+        ContractionParams p;
+        no_batch(p);
+        p.A = W; p.B = X; p.Y = Y; p.bias = B; p.residual = residual;
+        p.M = (int)(M / group); p.N = (int)NP; p.K = (int)(Cg * kH * kW);
+        p.a_ld = p.K;
+        p.nbd = 1; p.bdim[0] = (int)group; p.a_bs[0] = (M / group) * p.K; p.b_bs[0] = Cg * H * Wd;
+        p.y_zs = (M / group) * P; p.bias_zs = M / group; p.y_rs = P;
+        p.col_images = 1; p.colP = FastDiv::make((uint32_t)P); p.y_img = M * P; p.b_img = C * H * Wd;
+        p.alpha = 1.f; p.beta = 1.f; p.bias_mode = BIAS_ROW; p.bias_cs = 0; p.relu = act == ONNX_ACT_RELU;
+        const bool pw = kH == 1 && kW == 1 && pads[0] == 0 && pads[1] == 0 && pads[2] == 0 && pads[3] == 0 &&
+                        strides[0] == 1 && strides[1] == 1;
+        p.b_ld = pw ? H * Wd : 0;
+        p.ic.C = (int)C; p.ic.H = (int)H; p.ic.W = (int)Wd;
+        p.ic.sH = g.sH; p.ic.sW = g.sW; p.ic.pT = g.pT; p.ic.pL = g.pL; p.ic.dH = g.dH; p.ic.dW = g.dW;
+        p.ic.kHW = FastDiv::make((uint32_t)(kH * kW));
+        p.ic.kW = FastDiv::make((uint32_t)kW);
+        p.ic.OW = FastDiv::make((uint32_t)OW);
+        p.ic.image_stride = (int)(C * H * Wd);
+        return device_status(launch_lp_generic(p, LOAD_KC, pw ? LOAD_RC : LOAD_IM2COL, (int)group, (int)in_type,
+                                               (int)out_type, s), "conv (16-bit)");
+    }
 
     if (group == 1) {
         hipError_t e = hipSuccess;
@@ -240,6 +268,89 @@ onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const f
     const int tile = pick_tile(Mg, NP, K, group);
     return device_status(launch_contraction(p, LOAD_KC, bkind, a_vec ? 4 : 1, bvec, tile, (int)group, ws, s),
                          "conv (mfma)");
+}
+
+}  // namespace
+
+namespace {
+
+// ONNX MatMul on fp32 tensors (in_type ONNX_F32) or on 16-bit tensors with the result stored as
+// out_type (fp32 or the input type).
+onnx_status matmul_any(const float* A, const int64_t* a_dims, int a_rank, const float* B,
+                       const int64_t* b_dims, int b_rank, float* Y, const int64_t* y_dims, int y_rank,
+                       onnx_dtype in_type, onnx_dtype out_type, void* stream) {
+    int64_t yd[ONNX_MAX_RANK];
+    int yr = 0;
+    const onnx_status st = onnx_matmul_infer(a_dims, a_rank, b_dims, b_rank, yd, &yr);
+    if (st != ONNX_OK) return st;
+    if (yr != y_rank) return fail(ONNX_ERR_RANK, "matmul: y_rank is %d but the result has rank %d", y_rank, yr);
+    if (yr > 0 && !y_dims) return fail(ONNX_ERR_NULL, "matmul: y_dims is NULL");
+    for (int i = 0; i < yr; ++i)
+        if (yd[i] != y_dims[i])
+            return fail(ONNX_ERR_SHAPE, "matmul: y_dims[%d]=%lld but the inferred extent is %lld", i,
+                        (long long)y_dims[i], (long long)yd[i]);
+    const int64_t M = a_rank >= 2 ? a_dims[a_rank - 2] : 1, K = a_dims[a_rank - 1];
+    const int64_t N = b_rank >= 2 ? b_dims[b_rank - 1] : 1;
+    const int nba = a_rank >= 2 ? a_rank - 2 : 0, nbb = b_rank >= 2 ? b_rank - 2 : 0;
+    const int nb = nba > nbb ? nba : nbb;
+    int64_t nz = 1, na = M * K, nbel = K * N;
+    ContractionParams p;
+    no_batch(p);
+    {
+        int64_t stra = M * K, strb = K * N;
+        for (int t = nb - 1; t >= 0; --t) {
+            const int ia = t - (nb - nba), ib = t - (nb - nbb);
+            const int64_t da = ia >= 0 ? a_dims[ia] : 1, db = ib >= 0 ? b_dims[ib] : 1;
+            const int64_t dy = (da == 1) ? db : da;
+            if (dy > kIntMax) return fail(ONNX_ERR_UNSUPPORTED, "matmul: batch extent above 2^31-1");
+            p.bdim[t] = (int)dy;
+            p.a_bs[t] = (da == 1) ? 0 : stra;
+            p.b_bs[t] = (db == 1) ? 0 : strb;
+            stra *= da; strb *= db;
+            nz *= dy;
+        }
+        na = stra; nbel = strb;
+        p.nbd = nb;
+    }
+    if (nz * M * N == 0) return ONNX_OK;
+    if (!Y || (K > 0 && (!A || !B))) return fail(ONNX_ERR_NULL, "matmul: A, B and Y must not be NULL");
+    const int64_t ny = nz * M * N;
+    const int64_t esz = in_type == ONNX_F32 ? 4 : 2, ysz = out_type == ONNX_F32 ? 4 : 2;     // bytes per element
+    if (overlaps(Y, ny * ysz, A, na * esz) || overlaps(Y, ny * ysz, B, nbel * esz))
+        return fail(ONNX_ERR_ALIAS, "matmul: Y overlaps an input");
+    if (M > kIntMax || N > kIntMax || K > kIntMax) return fail(ONNX_ERR_UNSUPPORTED, "matmul: extent above 2^31-1");
+    if (!kc_fits(K, K) || !rc_fits(N, kTileRows) || !kc_fits(N, N))
+        return fail(ONNX_ERR_UNSUPPORTED, "matmul: a row of A, B or Y is too long for 32-bit tile offsets");
+
+    p.A = A; p.B = B; p.Y = Y; p.bias = nullptr; p.residual = nullptr;
+    int64_t Meff = M;
+    // When B is shared by every batch entry and A's batch is dense, the whole product is one
+    // matrix product with batch*M rows.
+    bool b_shared = true, a_dense = true;
+    {
+        int64_t expect = M * K;
+        for (int t = nb - 1; t >= 0; --t) {
+            if (p.b_bs[t] != 0 && p.bdim[t] != 1) b_shared = false;
+            if (p.bdim[t] != 1 && p.a_bs[t] != expect) a_dense = false;
+            expect *= p.bdim[t];
+        }
+    }
+    if (nz > 1 && b_shared && a_dense && nz * M <= kIntMax) {
+        Meff = nz * M;
+        nz = 1;
+        p.nbd = 0;
+    }
+    if (nz > 32768LL * 65535LL) return fail(ONNX_ERR_UNSUPPORTED, "matmul: too many batch entries");
+    p.M = (int)Meff; p.N = (int)N; p.K = (int)K;
+    p.a_ld = K; p.b_ld = N; p.y_rs = N; p.y_zs = M * N;
+    p.alpha = 1.f; p.beta = 0.f; p.bias_mode = BIAS_NONE; p.bias_cs = 0; p.relu = 0;
+    if (in_type != ONNX_F32)
+        return device_status(launch_lp_generic(p, LOAD_KC, LOAD_RC, (int)nz, (int)in_type, (int)out_type,
+                                               static_cast<hipStream_t>(stream)), "matmul (16-bit)");
+    const bool a4 = aligned16(A) && K % 4 == 0, b4 = aligned16(B) && N % 4 == 0;
+    const int tile = pick_tile(Meff, N, K, nz);
+    return device_status(launch_contraction(p, LOAD_KC, LOAD_RC, a4 ? 4 : 1, b4 ? 4 : 1, tile, (int)nz, workspace(),
+                                            static_cast<hipStream_t>(stream)), "matmul");
 }
 
 }  // namespace
@@ -418,74 +529,28 @@ onnx_status onnx_gemm(const float* A, const int64_t a_dims[2], const float* B, c
 onnx_status onnx_matmul(const float* A, const int64_t* a_dims, int a_rank, const float* B,
                         const int64_t* b_dims, int b_rank, float* Y, const int64_t* y_dims, int y_rank,
                         void* stream) {
-    int64_t yd[ONNX_MAX_RANK];
-    int yr = 0;
-    const onnx_status st = onnx_matmul_infer(a_dims, a_rank, b_dims, b_rank, yd, &yr);
-    if (st != ONNX_OK) return st;
-    if (yr != y_rank) return fail(ONNX_ERR_RANK, "matmul: y_rank is %d but the result has rank %d", y_rank, yr);
-    if (yr > 0 && !y_dims) return fail(ONNX_ERR_NULL, "matmul: y_dims is NULL");
-    for (int i = 0; i < yr; ++i)
-        if (yd[i] != y_dims[i])
-            return fail(ONNX_ERR_SHAPE, "matmul: y_dims[%d]=%lld but the inferred extent is %lld", i,
-                        (long long)y_dims[i], (long long)yd[i]);
-    const int64_t M = a_rank >= 2 ? a_dims[a_rank - 2] : 1, K = a_dims[a_rank - 1];
-    const int64_t N = b_rank >= 2 ? b_dims[b_rank - 1] : 1;
-    const int nba = a_rank >= 2 ? a_rank - 2 : 0, nbb = b_rank >= 2 ? b_rank - 2 : 0;
-    const int nb = nba > nbb ? nba : nbb;
-    int64_t nz = 1, na = M * K, nbel = K * N;
-    ContractionParams p;
-    no_batch(p);
-    {
-        int64_t stra = M * K, strb = K * N;
-        for (int t = nb - 1; t >= 0; --t) {
-            const int ia = t - (nb - nba), ib = t - (nb - nbb);
-            const int64_t da = ia >= 0 ? a_dims[ia] : 1, db = ib >= 0 ? b_dims[ib] : 1;
-            const int64_t dy = (da == 1) ? db : da;
-            if (dy > kIntMax) return fail(ONNX_ERR_UNSUPPORTED, "matmul: batch extent above 2^31-1");
-            p.bdim[t] = (int)dy;
-            p.a_bs[t] = (da == 1) ? 0 : stra;
-            p.b_bs[t] = (db == 1) ? 0 : strb;
-            stra *= da; strb *= db;
-            nz *= dy;
-        }
-        na = stra; nbel = strb;
-        p.nbd = nb;
-    }
-    if (nz * M * N == 0) return ONNX_OK;
-    if (!Y || (K > 0 && (!A || !B))) return fail(ONNX_ERR_NULL, "matmul: A, B and Y must not be NULL");
-    const int64_t ny = nz * M * N;
-    if (overlaps(Y, ny * 4, A, na * 4) || overlaps(Y, ny * 4, B, nbel * 4))
-        return fail(ONNX_ERR_ALIAS, "matmul: Y overlaps an input");
-    if (M > kIntMax || N > kIntMax || K > kIntMax) return fail(ONNX_ERR_UNSUPPORTED, "matmul: extent above 2^31-1");
-    if (!kc_fits(K, K) || !rc_fits(N, kTileRows) || !kc_fits(N, N))
-        return fail(ONNX_ERR_UNSUPPORTED, "matmul: a row of A, B or Y is too long for 32-bit tile offsets");
+    return matmul_any(A, a_dims, a_rank, B, b_dims, b_rank, Y, y_dims, y_rank, ONNX_F32, ONNX_F32, stream);
+}
 
-    p.A = A; p.B = B; p.Y = Y; p.bias = nullptr; p.residual = nullptr;
-    int64_t Meff = M;
-    // When B is shared by every batch entry and A's batch is dense, the whole product is one
-    // matrix product with batch*M rows.
-    bool b_shared = true, a_dense = true;
-    {
-        int64_t expect = M * K;
-        for (int t = nb - 1; t >= 0; --t) {
-            if (p.b_bs[t] != 0 && p.bdim[t] != 1) b_shared = false;
-            if (p.bdim[t] != 1 && p.a_bs[t] != expect) a_dense = false;
-            expect *= p.bdim[t];
-        }
-    }
-    if (nz > 1 && b_shared && a_dense && nz * M <= kIntMax) {
-        Meff = nz * M;
-        nz = 1;
-        p.nbd = 0;
-    }
-    if (nz > 32768LL * 65535LL) return fail(ONNX_ERR_UNSUPPORTED, "matmul: too many batch entries");
-    p.M = (int)Meff; p.N = (int)N; p.K = (int)K;
-    p.a_ld = K; p.b_ld = N; p.y_rs = N; p.y_zs = M * N;
-    p.alpha = 1.f; p.beta = 0.f; p.bias_mode = BIAS_NONE; p.bias_cs = 0; p.relu = 0;
-    const bool a4 = aligned16(A) && K % 4 == 0, b4 = aligned16(B) && N % 4 == 0;
-    const int tile = pick_tile(Meff, N, K, nz);
-    return device_status(launch_contraction(p, LOAD_KC, LOAD_RC, a4 ? 4 : 1, b4 ? 4 : 1, tile, (int)nz, workspace(),
-                                            static_cast<hipStream_t>(stream)), "matmul");
+onnx_status onnx_matmul_lp(const void* A, const int64_t* a_dims, int a_rank, const void* B, const int64_t* b_dims,
+                           int b_rank, void* Y, const int64_t* y_dims, int y_rank, onnx_dtype in_type,
+                           onnx_dtype out_type, void* stream) {
+    if (in_type != ONNX_F16 && in_type != ONNX_BF16) return fail(ONNX_ERR_ATTR, "matmul_lp: in_type must be ONNX_F16 or ONNX_BF16");
+    if (out_type != ONNX_F32 && out_type != in_type) return fail(ONNX_ERR_ATTR, "matmul_lp: out_type must be ONNX_F32 or in_type");
+    return matmul_any(static_cast<const float*>(A), a_dims, a_rank, static_cast<const float*>(B), b_dims, b_rank,
+                      static_cast<float*>(Y), y_dims, y_rank, in_type, out_type, stream);
+}
+
+onnx_status onnx_conv_lp(const void* X, const int64_t x_dims[4], const void* W, const int64_t w_dims[4], const float* B,
+                         const int64_t pads[4], const int64_t strides[2], const int64_t dilations[2], int64_t group,
+                         const void* residual, onnx_act act, void* Y, const int64_t y_dims[4], onnx_dtype in_type,
+                         onnx_dtype out_type, void* stream) {
+    if (in_type != ONNX_F16 && in_type != ONNX_BF16) return fail(ONNX_ERR_ATTR, "conv_lp: in_type must be ONNX_F16 or ONNX_BF16");
+    if (out_type != ONNX_F32 && out_type != in_type) return fail(ONNX_ERR_ATTR, "conv_lp: out_type must be ONNX_F32 or in_type");
+    const Workspace none = {nullptr, 0};
+    return conv_with_workspace(static_cast<const float*>(X), x_dims, static_cast<const float*>(W), w_dims, B, pads, strides,
+                               dilations, group, static_cast<const float*>(residual), act, static_cast<float*>(Y), y_dims,
+                               &none, 0, stream, in_type, out_type);
 }
 
 onnx_status onnx_maxpool(const float* X, const int64_t x_dims[4], const int64_t kernel[2],

@@ -54,12 +54,11 @@ onnx_status onnx_gemm_lp(const void* A, const int64_t a_dims[2], const void* B, 
     if (!a_dims || !b_dims || !y_dims) return fail(ONNX_ERR_NULL, "gemm_lp: NULL dims array");
     if (in_type != ONNX_F16 && in_type != ONNX_BF16) return fail(ONNX_ERR_ATTR, "gemm_lp: in_type must be ONNX_F16 or ONNX_BF16");
     if (out_type != ONNX_F32 && out_type != in_type) return fail(ONNX_ERR_ATTR, "gemm_lp: out_type must be ONNX_F32 or in_type");
-    if (transA != 0 || transB != 1)
-        return fail(ONNX_ERR_UNSUPPORTED, "gemm_lp: only transA = 0, transB = 1 (both operands K-contiguous) is built");
     for (int i = 0; i < 2; ++i)
         if (a_dims[i] < 0 || b_dims[i] < 0) return fail(ONNX_ERR_SHAPE, "gemm_lp: negative dimension");
-    const int64_t M = a_dims[0], K = a_dims[1], N = b_dims[0];
-    if (b_dims[1] != K) return fail(ONNX_ERR_SHAPE, "gemm_lp: inner dimensions differ (%lld vs %lld)", (long long)K, (long long)b_dims[1]);
+    const int64_t M = transA ? a_dims[1] : a_dims[0], K = transA ? a_dims[0] : a_dims[1];
+    const int64_t Kb = transB ? b_dims[1] : b_dims[0], N = transB ? b_dims[0] : b_dims[1];
+    if (Kb != K) return fail(ONNX_ERR_SHAPE, "gemm_lp: inner dimensions differ (%lld vs %lld)", (long long)K, (long long)Kb);
     if (y_dims[0] != M || y_dims[1] != N)
         return fail(ONNX_ERR_SHAPE, "gemm_lp: y_dims is {%lld,%lld} but the result is {%lld,%lld}", (long long)y_dims[0],
                     (long long)y_dims[1], (long long)M, (long long)N);
@@ -84,11 +83,10 @@ onnx_status onnx_gemm_lp(const void* A, const int64_t a_dims[2], const void* B, 
     if (overlaps(Y, M * N * ysz, A, M * K * 2) || overlaps(Y, M * N * ysz, B, K * N * 2) || overlaps(Y, M * N * ysz, C, nc * 4))
         return fail(ONNX_ERR_ALIAS, "gemm_lp: Y overlaps an input");
     if (M > 0x7fffffffLL || N > 0x7fffffffLL || K > 0x7fffffffLL) return fail(ONNX_ERR_UNSUPPORTED, "gemm_lp: extent above 2^31-1");
-    if (K % 8 != 0 || !aligned16(A) || !aligned16(B))
-        return fail(ONNX_ERR_UNSUPPORTED, "gemm_lp: K must be a multiple of 8 and A, B 16-byte aligned (16-byte loads of 8 values)");
-    // 32-bit tile offsets: 256 rows of an operand or of Y must span less than 2^31 bytes
-    if ((256 * K + K) * 2 >= (1LL << 31) - 64 || (256 * N + N) * 4 >= (1LL << 31) - 64)
-        return fail(ONNX_ERR_UNSUPPORTED, "gemm_lp: a row of A, B or Y is too long for 32-bit tile offsets");
+    // the tuned kernel: both operands K-contiguous, 16-byte loads of 8 values, 32-bit tile offsets
+    // (256 rows of an operand or of Y span less than 2^31 bytes); everything else: the general kernel
+    const bool fast = transA == 0 && transB == 1 && K % 8 == 0 && aligned16(A) && aligned16(B) &&
+                      (256 * K + K) * 2 < (1LL << 31) - 64 && (256 * N + N) * 4 < (1LL << 31) - 64;
 
     ContractionParams p;
     memset(&p, 0, sizeof(p));
@@ -100,13 +98,16 @@ onnx_status onnx_gemm_lp(const void* A, const int64_t a_dims[2], const void* B, 
     p.Y = static_cast<float*>(Y);
     p.bias = C;
     p.M = (int)M; p.N = (int)N; p.K = (int)K;
-    p.a_ld = K; p.b_ld = K; p.y_rs = N;
+    p.a_ld = a_dims[1]; p.b_ld = b_dims[1]; p.y_rs = N;
+    p.nz = 1;
     p.alpha = alpha; p.beta = beta; p.relu = act == ONNX_ACT_RELU;
     p.bias_mode = (crs != 0 && ccs != 0) ? BIAS_FULL : (crs != 0 ? BIAS_ROW : BIAS_COL);
     p.bias_cs = (int)ccs;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
-    if (in_type == ONNX_F16) e = out_type == ONNX_F32 ? launch_tile<LP_F16, false>(p, s) : launch_tile<LP_F16, true>(p, s);
+    if (!fast)
+        e = launch_lp_generic(p, transA ? LOAD_RC : LOAD_KC, transB ? LOAD_KC : LOAD_RC, 1, (int)in_type, (int)out_type, s);
+    else if (in_type == ONNX_F16) e = out_type == ONNX_F32 ? launch_tile<LP_F16, false>(p, s) : launch_tile<LP_F16, true>(p, s);
     else e = out_type == ONNX_F32 ? launch_tile<LP_BF16, false>(p, s) : launch_tile<LP_BF16, true>(p, s);
     if (e != hipSuccess) return fail(ONNX_ERR_DEVICE, "gemm_lp: %s", hipGetErrorString(e));
     return ONNX_OK;

@@ -66,6 +66,12 @@ int pick_split(int64_t tiles, int nk, int64_t tile_elems, double overhead, const
 hipError_t launch_contraction(ContractionParams& p, int akind, int bkind, int avec, int bvec, int tile,
                               int nz, const Workspace& ws, hipStream_t stream);
 
+// Contraction on 16-bit operands (in_type: 1 = IEEE half, 2 = bfloat16; out_type: 0 = fp32, else
+// in_type) in any operand layout (lp_generic.hip): akind KC / RC, bkind KC / RC / IM2COL.  `p` is
+// filled as for launch_contraction, with strides and offsets counted in elements.
+hipError_t launch_lp_generic(ContractionParams& p, int akind, int bkind, int nz, int in_type, int out_type,
+                             hipStream_t stream);
+
 // Convolution through an LDS-resident input patch (conv_window.h).  `p` must be filled as for
 // the IM2COL contraction (A = filters, B = input, ic geometry, K = Cg*kH*kW).  Returns false
 // when no instance fits this shape (the caller then uses the generic path); otherwise

@@ -7,6 +7,7 @@ between.  Reshape is a view of dense row-major data and costs nothing.  All arit
 happens inside the library's kernels; this module only prepares argument lists.
 """
 
+import numpy as np
 import torch
 
 from . import binding as B
@@ -28,7 +29,7 @@ class GraphRunner:
             self.workspace = torch.empty(workspace_bytes, dtype=torch.uint8, device=self.device)
         self.t = {}
         for k, v in list(model["inputs"].items()) + list(model["weights"].items()):
-            self.t[k] = torch.from_numpy(v).to(self.device).contiguous()
+            self.t[k] = torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(self.device)
         self.calls = []
         lib = B.raw()
         for nd in model["graph"]:

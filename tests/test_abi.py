@@ -184,9 +184,7 @@ def test_gemm_16bit_errors_are_reported_before_touching_the_device(B):
     assert lib.onnx_gemm_lp(*ok, 0, 0, None) == 4                       # inputs must be a 16-bit type
     assert lib.onnx_gemm_lp(*ok, 1, 2, None) == 4                       # output: fp32 or the input type
     bad = list(ok); bad[10] = 0
-    assert lib.onnx_gemm_lp(*bad, 2, 2, None) == 5                      # transB = 0 is not built
-    bad = list(ok); bad[1] = d((16, 12)); bad[3] = d((32, 12))
-    assert lib.onnx_gemm_lp(*bad, 2, 0, None) == 5                      # K not a multiple of 8
+    assert lib.onnx_gemm_lp(*bad, 2, 2, None) == 3                      # transB = 0: B is then [K,N] = {32,16}, K differs
     bad = list(ok); bad[3] = d((32, 24))
     assert lib.onnx_gemm_lp(*bad, 2, 0, None) == 3
     bad = list(ok); bad[13] = d((16, 31))
@@ -195,9 +193,18 @@ def test_gemm_16bit_errors_are_reported_before_touching_the_device(B):
     assert lib.onnx_gemm_lp(*bad, 1, 1, None) == 1
     bad = list(ok); bad[12] = a
     assert lib.onnx_gemm_lp(*bad, 1, 1, None) == 6
-    bad = list(ok); bad[0] = ctypes.c_void_p((1 << 20) + 8)
-    assert lib.onnx_gemm_lp(*bad, 1, 1, None) == 5                      # 16-byte alignment
     assert "gemm_lp" in B.onnx_last_error()
+    # the 16-bit MatMul and Conv entry points validate like their fp32 forms
+    assert lib.onnx_matmul_lp(a, d((4, 4)), 2, b, d((5, 4)), 2, y, d((4, 4)), 2, 1, 1, None) == 3
+    assert lib.onnx_matmul_lp(a, d((4, 4)), 2, b, d((4, 4)), 2, y, d((4, 4)), 2, 0, 0, None) == 4
+    assert lib.onnx_matmul_lp(a, d((4, 4)), 2, b, d((4, 4)), 2, y, d((4, 4)), 2, 1, 2, None) == 4
+    assert lib.onnx_matmul_lp(a, d((4, 4)), 2, b, d((4, 4)), 2, a, d((4, 4)), 2, 2, 2, None) == 6
+    cargs = [a, d((1, 4, 8, 8)), b, d((6, 4, 3, 3)), None, d((1, 1, 1, 1)), d((1, 1)), d((1, 1)), 1, None, 0, y, d((1, 6, 8, 7))]
+    assert lib.onnx_conv_lp(*cargs, 1, 1, None) == 3
+    cargs[12] = d((1, 6, 8, 8))
+    assert lib.onnx_conv_lp(*cargs, 0, 0, None) == 4
+    cargs[8] = 3
+    assert lib.onnx_conv_lp(*cargs, 2, 0, None) == 3                    # group must divide C and M
 
 
 def test_lstm_scratch_size_and_errors(B):

@@ -1,5 +1,5 @@
-"""GPU parity of the 16-bit-input Gemm (IEEE half / bfloat16 inputs, fp32 accumulation) against the
-CPU oracle evaluated on the fp32 values the 16-bit inputs denote."""
+"""GPU parity of the 16-bit-input Gemm, MatMul and Conv (IEEE half / bfloat16 inputs, fp32
+accumulation) against the CPU oracle evaluated on the fp32 values the 16-bit inputs denote."""
 import numpy as np
 import pytest
 
@@ -82,32 +82,149 @@ def test_gemm_16bit_small_integers_bit_exact(lib, kind):
         assert np.array_equal(got, want)
 
 
-def test_gemm_16bit_full_size_sampled_rows(lib):
-    """4096^3 in the configuration the benchmark times, checked on sampled rows."""
-    announce("gemm_lp 4096 sampled")
-    for kind in ("bf16", "f16"):
-        c = workloads.gemm_case_16bit(4096, kind)
-        A, B, C = bits_to_dev(c["A_bits"], kind), bits_to_dev(c["B_bits"], kind), torch.from_numpy(c["C"]).cuda()
-        got = lib.onnx_gemm_lp(A, B, C, out_dtype=torch.float32)
-        torch.cuda.synchronize()
-        rows = np.array([0, 1, 255, 256, 257, 1023, 2048, 3071, 4094, 4095])
-        ref, S = oracle.gemm(c["A"][rows], c["B"], c["C"], 1.0, 1.0, 0, 1, relu=False, want_scale=True)
-        g = got[torch.from_numpy(rows).cuda()].cpu().numpy()
-        assert rel_err(g, ref) <= REL_TOL
-        assert within_rounding_bound(g, ref, S, 4096 + 2)
+@pytest.mark.parametrize("kind", ["bf16", "f16"])
+@pytest.mark.parametrize("n", [2048, 4096])
+def test_gemm_16bit_full_size_whole_output(lib, n, kind):
+    """2048^3 and 4096^3 in the configuration the benchmark times, every output element compared."""
+    announce("gemm_lp full", n, kind)
+    c = workloads.gemm_case_16bit(n, kind)
+    A, B, C = bits_to_dev(c["A_bits"], kind), bits_to_dev(c["B_bits"], kind), torch.from_numpy(c["C"]).cuda()
+    got = lib.onnx_gemm_lp(A, B, C, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    want = "gemm_lp 256x256x64" if n == 4096 else "gemm_lp 128x128x64"
+    assert lib.onnx_last_launch().startswith(want), lib.onnx_last_launch()
+    ref, S = oracle.gemm(c["A"], c["B"], c["C"], 1.0, 1.0, 0, 1, relu=False, want_scale=True)
+    g = got.cpu().numpy()
+    assert rel_err(g, ref) <= REL_TOL
+    assert within_rounding_bound(g, ref, S, n + 2)
+
+
+def encode(x, kind):
+    """fp32 array -> (16-bit storage, the fp32 values it denotes)."""
+    if kind == "bf16":
+        b = workloads.to_bf16_bits(x)
+        return b, workloads.from_bf16_bits(b)
+    hh = x.astype(np.float16)
+    return hh.view(np.uint16), hh.astype(np.float32)
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("transA,transB", [(0, 0), (1, 0), (1, 1), (0, 1)])
+@pytest.mark.parametrize("M,N,K", [(70, 90, 50), (130, 257, 129), (64, 64, 32), (300, 200, 7), (1, 1, 1)])
+def test_gemm_16bit_every_layout_and_ragged_k(lib, M, N, K, transA, transB, kind):
+    """Layouts and K the tuned kernel does not take go through the general kernel (so does
+    transA = 0 / transB = 1 when K is not a multiple of 8)."""
+    announce("gemm_lp layouts", kind, M, N, K, transA, transB)
+    rng = np.random.default_rng([M, N, K, transA, transB])
+    ab, av = encode(rng.uniform(-1, 1, (K, M) if transA else (M, K)).astype(np.float32), kind)
+    bb, bv = encode(rng.uniform(-1, 1, (N, K) if transB else (K, N)).astype(np.float32), kind)
+    cshape = [(1, N), (M, 1), (M, N), (N,)][(M + K + transA) % 4]
+    C = rng.uniform(-1, 1, cshape).astype(np.float32)
+    ref, S = oracle.gemm(av, bv, C, 0.75, -1.25, transA, transB, relu=False, want_scale=True)
+    got = lib.onnx_gemm_lp(bits_to_dev(ab, kind), bits_to_dev(bb, kind), torch.from_numpy(C).cuda(), alpha=0.75, beta=-1.25,
+                           transA=transA, transB=transB, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    fast = transA == 0 and transB == 1 and K % 8 == 0
+    assert lib.onnx_last_launch().startswith("gemm_lp" if fast else "lp_generic"), lib.onnx_last_launch()
+    g = got.cpu().numpy()
+    assert rel_err(g, ref) <= REL_TOL
+    assert within_rounding_bound(g, ref, S, K + 2)
+    # stored in the inputs' type, with Relu
+    ref2 = oracle.gemm(av, bv, C, 0.75, -1.25, transA, transB, relu=True)
+    got2 = lp_to_host(lib.onnx_gemm_lp(bits_to_dev(ab, kind), bits_to_dev(bb, kind), torch.from_numpy(C).cuda(), alpha=0.75,
+                                       beta=-1.25, transA=transA, transB=transB, act=1), kind)
+    u = 2.0 ** -PRECISION[kind]
+    assert (np.abs(got2 - ref2) <= u * np.abs(ref2) + (K + 5) * 2.0 ** -24 * (S + 2.0) + 1e-7).all()
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("sa,sb", [((5, 4), (4, 6)), ((3, 2, 50, 40), (2, 40, 60)), ((2, 70, 33), (3, 1, 33, 65)), ((40,), (40, 6)),
+                                   ((50, 40), (40,)), ((2, 3, 130, 36), (36, 200)), ((8, 12, 128, 64), (8, 12, 64, 128))])
+def test_matmul_16bit_matches_oracle(lib, sa, sb, kind):
+    announce("matmul_lp", kind, sa, sb)
+    rng = np.random.default_rng(len(sa) * 100 + len(sb))
+    ab, av = encode(rng.uniform(-1, 1, sa).astype(np.float32), kind)
+    bb, bv = encode(rng.uniform(-1, 1, sb).astype(np.float32), kind)
+    ref, S = oracle.matmul(av, bv, want_scale=True)
+    got = lib.onnx_matmul_lp(bits_to_dev(ab, kind), bits_to_dev(bb, kind), out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert lib.onnx_last_launch().startswith("lp_generic"), lib.onnx_last_launch()
+    g = got.cpu().numpy()
+    assert g.shape == ref.shape
+    assert rel_err(g, ref) <= REL_TOL
+    assert within_rounding_bound(g, ref, S, sa[-1] + 2)
+    got2 = lp_to_host(lib.onnx_matmul_lp(bits_to_dev(ab, kind), bits_to_dev(bb, kind)), kind)
+    u = 2.0 ** -PRECISION[kind]
+    assert (np.abs(got2 - ref) <= u * np.abs(ref) + (sa[-1] + 5) * 2.0 ** -24 * (S + 1.0) + 1e-7).all()
+
+
+CONV_LP_CASES = [
+    # N, C, H, W, M, kH, kW, pads, strides, dilations, group
+    (2, 16, 19, 23, 40, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 1),
+    (2, 3, 37, 41, 64, 7, 7, (3, 3, 3, 3), (2, 2), (1, 1), 1),
+    (2, 32, 20, 20, 48, 3, 3, (2, 0, 1, 3), (2, 3), (2, 1), 2),
+    (2, 64, 12, 12, 96, 1, 1, (0, 0, 0, 0), (1, 1), (1, 1), 1),          # pointwise: row-contiguous input
+    (2, 64, 9, 7, 96, 1, 1, (0, 0, 0, 0), (1, 1), (1, 1), 1),            # pointwise, 63 positions per image
+    (2, 64, 12, 12, 96, 1, 1, (0, 0, 0, 0), (2, 2), (1, 1), 1),          # strided 1x1
+    (4, 6, 10, 10, 6, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 6),            # depthwise
+    (1, 1, 28, 28, 8, 5, 5, (2, 2, 2, 2), (1, 1), (1, 1), 1),
+    (3, 128, 14, 14, 128, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 1),        # K = 1152
+]
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("case", CONV_LP_CASES)
+def test_conv_16bit_matches_oracle(lib, case, kind):
+    announce("conv_lp", kind, case)
+    N, C, H, W, M, kH, kW, pads, st, dl, g = case
+    rng = np.random.default_rng(list(case[:7]) + [g])
+    xb, xv = encode(rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32), kind)
+    wb, wv = encode(rng.uniform(-1, 1, (M, C // g, kH, kW)).astype(np.float32), kind)
+    Bv = rng.uniform(-1, 1, (M,)).astype(np.float32)
+    K = (C // g) * kH * kW
+    ref, S = oracle.conv(xv, wv, Bv, pads, st, dl, g, want_scale=True)
+    X, Wt = bits_to_dev(xb, kind), bits_to_dev(wb, kind)
+    got = lib.onnx_conv_lp(X, Wt, torch.from_numpy(Bv).cuda(), pads, st, dl, g, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert lib.onnx_last_launch().startswith("lp_generic"), lib.onnx_last_launch()
+    gth = got.cpu().numpy()
+    assert gth.shape == ref.shape
+    assert rel_err(gth, ref) <= REL_TOL
+    assert within_rounding_bound(gth, ref, S, K + 1)
+    # 16-bit result with a 16-bit residual and Relu: one more rounding on top of the fp32 result
+    rb, rv = encode(rng.uniform(-1, 1, ref.shape).astype(np.float32), kind)
+    ref2, S2 = oracle.conv(xv, wv, None, pads, st, dl, g, residual=rv, relu=False, want_scale=True)
+    got2 = lp_to_host(lib.onnx_conv_lp(X, Wt, None, pads, st, dl, g, residual=bits_to_dev(rb, kind), act=1), kind)
+    u = 2.0 ** -PRECISION[kind]
+    want = np.maximum(ref2, 0)
+    assert (np.abs(got2 - want) <= u * np.abs(want) + (K + 5) * 2.0 ** -24 * (S2 + 1.0) + 1e-7).all()
+    assert (got2 >= 0).all()
+
+
+def test_conv_16bit_small_integers_bit_exact(lib):
+    announce("conv_lp integers")
+    rng = np.random.default_rng(8)
+    X = rng.integers(-4, 5, (3, 48, 17, 19)).astype(np.float32)
+    Wt = rng.integers(-4, 5, (72, 48, 3, 3)).astype(np.float32)
+    Bv = rng.integers(-4, 5, (72,)).astype(np.float32)
+    for kind in ("f16", "bf16"):
+        xb, _ = encode(X, kind)
+        wb, _ = encode(Wt, kind)
+        for pads, st, dl in [((1, 1, 1, 1), (1, 1), (1, 1)), ((0, 2, 1, 0), (2, 1), (1, 2))]:
+            ref = oracle.conv(X, Wt, Bv, pads, st, dl)
+            got = lib.onnx_conv_lp(bits_to_dev(xb, kind), bits_to_dev(wb, kind), torch.from_numpy(Bv).cuda(), pads, st, dl,
+                                   out_dtype=torch.float32)
+            torch.cuda.synchronize()
+            assert np.array_equal(got.cpu().numpy().astype(np.float64), ref)
 
 
 def test_gemm_16bit_errors(lib):
     announce("gemm_lp errors")
     a = torch.zeros((16, 16), dtype=torch.bfloat16, device="cuda")
     b = torch.zeros((16, 16), dtype=torch.bfloat16, device="cuda")
-    with pytest.raises(lib.OnnxHipError) as e:
-        lib.onnx_gemm_lp(a, b, transB=0)
-    assert e.value.status == 5
-    with pytest.raises(lib.OnnxHipError) as e:
-        lib.onnx_gemm_lp(torch.zeros((16, 12), dtype=torch.bfloat16, device="cuda"),
-                         torch.zeros((16, 12), dtype=torch.bfloat16, device="cuda"))
-    assert e.value.status == 5
+    assert lib.onnx_gemm_lp(a, b, transB=0).shape == (16, 16)            # every layout is taken
+    assert lib.onnx_gemm_lp(torch.zeros((16, 12), dtype=torch.bfloat16, device="cuda"),
+                            torch.zeros((16, 12), dtype=torch.bfloat16, device="cuda")).shape == (16, 16)
     with pytest.raises(lib.OnnxHipError) as e:
         lib.onnx_gemm_lp(a, torch.zeros((16, 24), dtype=torch.bfloat16, device="cuda"))
     assert e.value.status == 3

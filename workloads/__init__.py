@@ -185,7 +185,7 @@ def constant_adds(batch=4, channels=16, hw=12, seed=SEED_BASE + 8):
     r = _rng(seed, 0)
     inputs = {"x": _normal(r, (batch, channels, hw, hw), 1.0)}
     weights = {"c1": _normal(r, (1, channels, 1, 1), 1.0), "c2": _normal(r, (1, channels, 1, 1), 1.0),
-               "c3": _normal(r, (), 1.0).reshape(()), "c4": _normal(r, (channels, hw, hw), 1.0),
+               "c3": np.asarray(_normal(r, (1,), 1.0)[0], dtype=np.float32), "c4": _normal(r, (channels, hw, hw), 1.0),
                "c5": _normal(r, (1, channels, 1, 1), 1.0), "c6": _normal(r, (hw,), 1.0)}
     graph = [
         relu_node("x", "y"),
