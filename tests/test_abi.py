@@ -221,7 +221,8 @@ def test_lstm_scratch_size_and_errors(B):
     assert lib.onnx_lstm(*args(dir=5)) == 4
     assert lib.onnx_lstm(*args(x=None)) == 1
     assert lib.onnx_lstm(*args(y=None)) == 1
-    assert lib.onnx_lstm(*args(n=16)) == 1
+    assert lib.onnx_lstm(*args(n=16)) == 4                              # too little scratch: an argument error
+    assert lib.onnx_lstm(*args(sc=None)) == 1
     assert lib.onnx_lstm(*args(sc=ctypes.c_void_p((64 << 20) + 64))) == 4
     assert lib.onnx_lstm(*args(sc=x)) == 6
     assert "lstm" in B.onnx_last_error()

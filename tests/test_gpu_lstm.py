@@ -33,6 +33,9 @@ CASES = [
     (16, 32, 64, 128, "forward", True, True),
     (12, 8, 96, 64, "bidirectional", True, True),
     (24, 64, 256, 256, "reverse", False, True),
+    (6, 40, 20, 70, "bidirectional", True, True),    # two batch blocks, hidden size neither a multiple of 8 nor of 4
+    (4, 33, 16, 520, "forward", True, False),        # k range of a wavefront longer than two load blocks, ragged last block
+    (64, 32, 512, 512, "forward", True, True),       # the benchmarked shape
 ]
 
 
@@ -78,12 +81,21 @@ def test_lstm_errors_and_degenerate(lib):
     assert Y.abs().max().item() == 0.0 and Yc.abs().max().item() == 0.0
     with pytest.raises(ValueError):
         lib.onnx_lstm(X, torch.zeros((1, 8, 5), device="cuda"), R)
+    # an empty sequence: the final states are the initial ones (zeros when none are given)
+    h0 = torch.rand((1, 2, 2), device="cuda")
+    c0 = torch.rand((1, 2, 2), device="cuda")
+    Y0, Yh0, Yc0 = lib.onnx_lstm(torch.zeros((0, 2, 4), device="cuda"), W, R, initial_h=h0, initial_c=c0)
+    torch.cuda.synchronize()
+    assert Y0.shape == (0, 1, 2, 2) and torch.equal(Yh0, h0) and torch.equal(Yc0, c0)
+    _, Yh1, Yc1 = lib.onnx_lstm(torch.zeros((0, 2, 4), device="cuda"), W, R)
+    torch.cuda.synchronize()
+    assert Yh1.abs().max().item() == 0.0 and Yc1.abs().max().item() == 0.0
     import ctypes
     raw = __import__("paper_2008_08272_amd.binding", fromlist=["x"]).raw()
     d = __import__("paper_2008_08272_amd.binding", fromlist=["x"]).dims
     p = lambda t: ctypes.c_void_p(t.data_ptr())
     small = torch.empty(256, dtype=torch.uint8, device="cuda")
     st = raw.onnx_lstm(p(X), d(X.shape), p(W), p(R), None, None, None, 2, 0, p(Y), None, None, p(small), small.numel(), None)
-    assert st == 1                                    # scratch too small
+    assert st == 4                                    # scratch too small
     st = raw.onnx_lstm(p(X), d(X.shape), p(W), p(R), None, None, None, 2, 3, p(Y), None, None, p(small), small.numel(), None)
     assert st == 4                                    # unknown direction
