@@ -31,7 +31,7 @@ RAMP_SECONDS = 0.3
 # profiles/gemm4096_hbm_traffic.md (fetch scaled by the 2.000 a plain copy shows, write exact).  The
 # counters sit between the eight L2s and the fabric, so this is L2 fill + write-back traffic (served by
 # the Infinity Cache or HBM).  Reported only while the kernel sources are the ones that were measured.
-TRAFFIC_4096 = {"sources_sha256_16": "258358ecea877f3d", "bytes_per_launch": (196761.0 * 2.000 + 65536.0) * 1024.0}
+TRAFFIC_4096 = {"sources_sha256_16": "74b42c99491b62df", "bytes_per_launch": (196765.5 * 2.000 + 65536.0) * 1024.0}
 KERNEL_SOURCES = ("paper_2008_08272_amd/csrc/contraction.h", "paper_2008_08272_amd/csrc/contraction.hip")
 
 
@@ -267,7 +267,34 @@ def main():
                 details["gemm_%s_%d" % (kind, n)] = dict(timing(t3), tflops=round(tf, 1),
                                                          frac_mfma_peak_16bit=round(tf / MFMA_16BIT_PEAK_TFLOPS, 4))
                 del A16, B16, C32, Y16
-        # LSTM: one Gemm for the input projection of the sequence, then one small Gemm + one cell kernel per step
+        # 16-bit MatMul and Conv through the general transposing kernel (any layout; not the tuned Gemm path)
+        A16 = torch.randn(8, 512, 768, device=dev).to(torch.bfloat16)
+        B16 = torch.randn(768, 3072, device=dev).to(torch.bfloat16)
+        Y16 = torch.empty(8, 512, 3072, device=dev, dtype=torch.bfloat16)
+        t3 = time_call(lambda: lib.onnx_matmul_lp(A16, B16, out=Y16), iters=20, warm=5)
+        details["matmul_bf16_proj_8x512x768_x_768x3072"] = dict(timing(t3), tflops=round(2.0 * 8 * 512 * 768 * 3072 / (t3[0] * 1e-3) / 1e12, 1))
+        del A16, B16, Y16
+        for cname, xs, ws_, pads in (("conv_bf16_3x3_32x128x28x28", (32, 128, 28, 28), (128, 128, 3, 3), (1, 1, 1, 1)),
+                                     ("conv_bf16_1x1_32x1024x14x14", (32, 1024, 14, 14), (256, 1024, 1, 1), (0, 0, 0, 0))):
+            X16 = torch.randn(*xs, device=dev).to(torch.bfloat16)
+            W16 = (torch.randn(*ws_, device=dev) * 0.05).to(torch.bfloat16)
+            yd = lib.onnx_conv_infer(xs, ws_, pads)
+            Y16 = torch.empty(yd, device=dev, dtype=torch.bfloat16)
+            t3 = time_call(lambda: lib.onnx_conv_lp(X16, W16, None, pads, act=1, out=Y16), iters=20, warm=5)
+            fl = 2.0 * Y16.numel() * ws_[1] * ws_[2] * ws_[3]
+            details[cname] = dict(timing(t3), tflops=round(fl / (t3[0] * 1e-3) / 1e12, 1))
+            del X16, W16, Y16
+        # ResNet-50's stem alone at batch 32 (7x7 stride 2, 3 -> 64 channels: the resident-filter kernel)
+        Xs = torch.randn(32, 3, 224, 224, device=dev)
+        Ws = torch.randn(64, 3, 7, 7, device=dev) * 0.1
+        Bs = torch.randn(64, device=dev)
+        Ys = torch.empty(32, 64, 112, 112, device=dev)
+        t3 = time_call(lambda: lib.onnx_conv(Xs, Ws, Bs, (3, 3, 3, 3), (2, 2), act=1, out=Ys), iters=30, warm=5)
+        fl = 2.0 * Ys.numel() * 147
+        details["conv_stem_7x7s2_32x3x224x224"] = dict(timing(t3), tflops=round(fl / (t3[0] * 1e-3) / 1e12, 2),
+                                                       frac_mfma_peak=round(fl / (t3[0] * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS, 4))
+        del Xs, Ws, Bs, Ys
+        # LSTM: one Gemm for the input projection of the sequence, then one fused launch per time step
         seq, bsz, nin, hid = 64, 32, 512, 512
         Xl = torch.randn(seq, bsz, nin, device=dev)
         Wl = torch.randn(1, 4 * hid, nin, device=dev) / nin ** 0.5
