@@ -247,14 +247,29 @@ def main():
                                                    sum_of_layer_rooflines_ms=round(floor_ms, 4),
                                                    frac_of_layer_rooflines=round(floor_ms / ms, 4))
             del r
-        # the MNIST-shaped small CNN (5 calls, 1.6 MFLOP): pure launch latency
-        r = GraphRunner(workloads.small_cnn(), dev)
+        # the MNIST-shaped small CNN (1.6 MFLOP): one call per node (5 launches: pure launch latency) and the
+        # whole model as one launch (onnx_chain: weights and activations in LDS), at batch 1 and one workgroup
+        # per image at batch 64
+        r = GraphRunner(workloads.small_cnn(), dev, fuse_chain=False)
         t_eager = time_call(r.run, iters=50, warm=10)
         r.capture()
         t_graph = time_call(r.replay, iters=50, warm=10)
-        details["small_cnn_b1"] = {"us_eager": round(t_eager[0] * 1e3, 2), "us_graph": round(t_graph[0] * 1e3, 2),
-                                   "calls": len(r.calls)}
+        calls = len(r.calls)
         del r
+        r = GraphRunner(workloads.small_cnn(), dev)
+        assert r.chain is not None
+        t_chain = time_call(r.run, iters=200, warm=20)
+        del r
+        m64 = workloads.small_cnn()
+        m64["inputs"] = {"x": np.random.default_rng(7).uniform(0, 1, (64, 1, 28, 28)).astype(np.float32)}
+        m64["graph"] = [dict(nd, shape=(64, 256)) if nd["op"] == "reshape" else nd for nd in m64["graph"]]
+        r = GraphRunner(m64, dev)
+        assert r.chain is not None
+        t_chain64 = time_call(r.run, iters=200, warm=20)
+        del r
+        details["small_cnn_b1"] = {"us_per_node_calls": round(t_eager[0] * 1e3, 2), "us_per_node_graph": round(t_graph[0] * 1e3, 2),
+                                   "calls": calls, "us_one_launch": round(t_chain[0] * 1e3, 2),
+                                   "us_one_launch_batch64": round(t_chain64[0] * 1e3, 2)}
         # Gemm on 16-bit inputs (fp32 accumulation), against the 2.5 PFLOP/s dense fp16 / bf16 MFMA peak
         for kind, tdt in (("bf16", torch.bfloat16), ("f16", torch.float16)):
             for n in (4096, 8192):

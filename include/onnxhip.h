@@ -283,9 +283,9 @@ onnx_status onnx_conv_lp(const void* X, const int64_t x_dims[4], const void* W, 
  * or [dirs, batch, H]; dirs = 2 for ONNX_LSTM_BIDIRECTIONAL, else 1.  Per step
  *   i,o,f = sigmoid(x W' + h R' + Wb + Rb),  g = tanh(...),  c = f*c + i*g,  h = o*tanh(c).
  * Outputs (each may be NULL, not all): Y [seq, dirs, batch, H], Y_h and Y_c [dirs, batch, H].
- * The products run through the same kernels as onnx_gemm (one Gemm for the input projection of
- * the whole sequence, one per time step for the recurrence), followed by an element-wise cell
- * kernel per step.  `scratch` is caller-owned device memory of at least
+ * The input projection of the whole sequence runs through the same kernel as onnx_gemm; every
+ * time step is then one launch that multiplies h by R' on the matrix cores and applies the gates
+ * (both directions of a bidirectional LSTM in the same launch).  `scratch` is caller-owned device memory of at least
  * onnx_lstm_scratch_bytes(...) bytes, 256-byte aligned, contents irrelevant; it must not overlap
  * any input or output (ONNX_ERR_ALIAS).
  */
@@ -295,6 +295,55 @@ onnx_status onnx_lstm(const float* X, const int64_t x_dims[3], const float* W, c
                       const float* B, const float* initial_h, const float* initial_c,
                       int64_t hidden_size, int direction, float* Y, float* Y_h, float* Y_c,
                       void* scratch, size_t scratch_bytes, void* stream);
+
+/*
+ * A whole small model as one launch (Section 3: the compiler emits one entry function per
+ * model; Section 4.2: the MNIST network, two convolutions with Relu, two max pools and a matrix
+ * product with bias).  `ops` (host memory) is a linear chain of 1..ONNX_CHAIN_MAX_OPS operators;
+ * the first consumes X [N,C,H,W], each other one the result of its predecessor; a Gemm consumes
+ * its input flattened to [1, C*H*W] per image (the Reshape / Flatten in front of it is implied).
+ * One workgroup runs the whole chain for one image with all weights and every activation in LDS:
+ * nothing but X, the weights and the requested results touches device memory.
+ *   ONNX_CHAIN_CONV     onnx_conv with group 1: W [outputs, C, kernel[0], kernel[1]], B NULL or
+ *                       [outputs]; pads, strides, dilations, act as there
+ *   ONNX_CHAIN_MAXPOOL  onnx_maxpool without Indices: kernel, pads, strides, dilations, ceil_mode
+ *   ONNX_CHAIN_AVGPOOL  onnx_avgpool: kernel, pads, strides, ceil_mode, count_include_pad;
+ *                       kernel {0,0} means global
+ *   ONNX_CHAIN_GEMM     Y = alpha * x * op(W) + beta * B, x the flattened input [1,K], W [K,outputs]
+ *                       (transB = 0) or [outputs,K], B NULL or [outputs]; act as for onnx_gemm
+ * Each operator's Y is NULL (the result stays on chip) or device memory for the result of every
+ * image, [N, ...] in the shape the matching *_infer call gives; the last operator's Y is
+ * required.  Limits (ONNX_ERR_UNSUPPORTED beyond them): every activation, counted with the
+ * zero padding of the Conv that consumes it, has at most ONNX_CHAIN_MAX_ACTIVATION floats per
+ * image; all weights and biases together at most ONNX_CHAIN_MAX_WEIGHTS floats (a Conv's filter
+ * rows count as C*kH*kW rounded up to a multiple of 16, plus 4); a Conv's C*kH*kW at most
+ * ONNX_CHAIN_MAX_CONV_K.
+ * Attribute and shape errors are those of the single operators.  Everything is validated before
+ * the launch; nothing is allocated; Y buffers must not overlap X or the weights.
+ */
+#define ONNX_CHAIN_MAX_OPS 8
+#define ONNX_CHAIN_MAX_ACTIVATION 10240
+#define ONNX_CHAIN_MAX_WEIGHTS 14336
+#define ONNX_CHAIN_MAX_CONV_K 2048
+typedef enum { ONNX_CHAIN_CONV = 0, ONNX_CHAIN_MAXPOOL = 1, ONNX_CHAIN_AVGPOOL = 2, ONNX_CHAIN_GEMM = 3 } onnx_chain_kind;
+typedef struct {
+    int32_t kind;               /* onnx_chain_kind */
+    int32_t act;                /* onnx_act, Conv and Gemm */
+    int64_t outputs;            /* Conv: output channels; Gemm: columns of the result */
+    int64_t kernel[2];
+    int64_t pads[4];
+    int64_t strides[2];
+    int64_t dilations[2];
+    int32_t ceil_mode;
+    int32_t count_include_pad;
+    int32_t transB;
+    float alpha, beta;
+    const float* W;             /* device */
+    const float* B;             /* device or NULL */
+    float* Y;                   /* device or NULL */
+} onnx_chain_op;
+onnx_status onnx_chain(const onnx_chain_op* ops, int n_ops, const float* X, const int64_t x_dims[4],
+                       void* stream);
 
 #ifdef __cplusplus
 }

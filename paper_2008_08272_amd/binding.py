@@ -13,6 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libonnxhip.so")
 
 ONNX_OK = 0
+ONNX_ERR_UNSUPPORTED = 5
 ACT_NONE, ACT_RELU = 0, 1
 STATUS_NAMES = {1: "ONNX_ERR_NULL", 2: "ONNX_ERR_RANK", 3: "ONNX_ERR_SHAPE", 4: "ONNX_ERR_ATTR",
                 5: "ONNX_ERR_UNSUPPORTED", 6: "ONNX_ERR_ALIAS", 7: "ONNX_ERR_DEVICE"}
@@ -78,6 +79,19 @@ _lib.onnx_lstm.argtypes = [_vp, _i64p, _vp, _vp, _vp, _vp, _vp, _c64, _ci, _vp, 
 _lib.onnx_lstm.restype = _ci
 LSTM_DIRECTIONS = {"forward": 0, "reverse": 1, "bidirectional": 2}
 
+
+
+class ChainOp(ctypes.Structure):
+    """onnx_chain_op of include/onnxhip.h."""
+    _fields_ = [("kind", ctypes.c_int32), ("act", ctypes.c_int32), ("outputs", ctypes.c_int64),
+                ("kernel", ctypes.c_int64 * 2), ("pads", ctypes.c_int64 * 4), ("strides", ctypes.c_int64 * 2),
+                ("dilations", ctypes.c_int64 * 2), ("ceil_mode", ctypes.c_int32),
+                ("count_include_pad", ctypes.c_int32), ("transB", ctypes.c_int32), ("alpha", ctypes.c_float),
+                ("beta", ctypes.c_float), ("W", ctypes.c_void_p), ("B", ctypes.c_void_p), ("Y", ctypes.c_void_p)]
+
+
+_lib.onnx_chain.argtypes = [ctypes.POINTER(ChainOp), _ci, _vp, _i64p, _vp]
+_lib.onnx_chain.restype = _ci
 _lib.onnx_set_workspace.argtypes = [_vp, ctypes.c_size_t]
 _lib.onnx_set_workspace.restype = _ci
 _workspace_tensor = None
@@ -395,3 +409,85 @@ def onnx_lstm(X, W, R, B=None, initial_h=None, initial_c=None, direction="forwar
     _check(_lib.onnx_lstm(_ptr(X), dims(X.shape), _ptr(W), _ptr(R), _ptr(B), _ptr(initial_h), _ptr(initial_c), H, d,
                           _ptr(Y), _ptr(Yh), _ptr(Yc), _ptr(scratch), scratch.numel(), _stream(stream)))
     return Y, Yh, Yc
+
+
+CHAIN_KINDS = {"conv": 0, "maxpool": 1, "avgpool": 2, "gemm": 3}
+CHAIN_MAX_OPS = 8
+CHAIN_MAX_ACTIVATION = 10240
+CHAIN_MAX_WEIGHTS = 14336
+CHAIN_MAX_CONV_K = 2048
+
+
+def chain_shapes(x_dims, ops):
+    """Result shape of every operator of a chain (host only; the library's *_infer calls)."""
+    d = tuple(int(v) for v in x_dims)
+    shapes = []
+    for o in ops:
+        kind = o["op"]
+        if kind == "conv":
+            w = o["W"].shape
+            d = onnx_conv_infer(d, (w[0], d[1], w[2], w[3]), o.get("pads", (0, 0, 0, 0)), o.get("strides", (1, 1)),
+                                o.get("dilations", (1, 1)), 1)
+        elif kind == "maxpool":
+            d = onnx_pool_infer(d, o["kernel"], o.get("pads", (0, 0, 0, 0)), o.get("strides", (1, 1)),
+                                o.get("dilations", (1, 1)), o.get("ceil_mode", 0))
+        elif kind == "avgpool":
+            if o.get("kernel") is None:
+                d = (d[0], d[1], 1, 1)
+            else:
+                d = onnx_pool_infer(d, o["kernel"], o.get("pads", (0, 0, 0, 0)), o.get("strides", (1, 1)), (1, 1),
+                                    o.get("ceil_mode", 0))
+        elif kind == "gemm":
+            w = o["W"].shape
+            d = (d[0], int(w[0] if o.get("transB", 0) else w[1]), 1, 1)
+        else:
+            raise ValueError("unknown chain operator %r" % kind)
+        shapes.append(tuple(d))
+    return shapes
+
+
+def onnx_chain_args(X, ops, keep=False, outs=None):
+    """Marshals a chain into the C structures: returns (array of onnx_chain_op, result tensors).
+    ``ops`` is a list of dicts: {"op": "conv", "W", "B", "pads", "strides", "dilations", "act"},
+    {"op": "maxpool", "kernel", "pads", "strides", "dilations", "ceil_mode"}, {"op": "avgpool",
+    "kernel" (None = global), "pads", "strides", "ceil_mode", "count_include_pad"}, {"op": "gemm",
+    "W", "B", "transB", "alpha", "beta", "act"}.  With ``keep`` every operator's result is
+    written to device memory, otherwise only the last one's; a Gemm's result is [N, outputs]."""
+    X = _dev(X, "X")
+    shapes = chain_shapes(X.shape, ops)
+    arr = (ChainOp * max(len(ops), 1))()
+    results = []
+    for i, (o, shp) in enumerate(zip(ops, shapes)):
+        c = arr[i]
+        c.kind = CHAIN_KINDS[o["op"]]
+        c.act = int(o.get("act", ACT_NONE))
+        W, B = _dev(o.get("W"), "W"), _dev(o.get("B"), "B")
+        c.outputs = shp[1] if o["op"] in ("conv", "gemm") else 0
+        k = o.get("kernel") if o["op"] != "conv" else W.shape[2:]
+        c.kernel[0], c.kernel[1] = (0, 0) if k is None else (int(k[0]), int(k[1]))
+        for j, v in enumerate(o.get("pads", (0, 0, 0, 0))): c.pads[j] = int(v)
+        for j, v in enumerate(o.get("strides", (1, 1))): c.strides[j] = int(v)
+        for j, v in enumerate(o.get("dilations", (1, 1))): c.dilations[j] = int(v)
+        c.ceil_mode = int(o.get("ceil_mode", 0))
+        c.count_include_pad = int(o.get("count_include_pad", 0))
+        c.transB = int(o.get("transB", 0))
+        c.alpha, c.beta = float(o.get("alpha", 1.0)), float(o.get("beta", 1.0))
+        c.W = None if W is None else W.data_ptr()
+        c.B = None if B is None else B.data_ptr()
+        y = None
+        if keep or i == len(ops) - 1:
+            out_shape = (shp[0], shp[1]) if o["op"] == "gemm" else shp
+            y = outs[i] if outs is not None and outs[i] is not None else torch.empty(out_shape, dtype=torch.float32, device=X.device)
+            y = _dev(y, "out")
+        c.Y = None if y is None else y.data_ptr()
+        results.append(y)
+    return arr, results
+
+
+def onnx_chain(X, ops, keep=False, outs=None, stream=None):
+    """A linear chain of Conv / MaxPool / AveragePool / Gemm operators in one launch (see
+    onnx_chain_args for ``ops``).  Returns the last result, or with ``keep`` the list of all."""
+    X = _dev(X, "X")
+    arr, results = onnx_chain_args(X, ops, keep, outs)
+    _check(_lib.onnx_chain(arr, len(ops), _ptr(X), dims(X.shape), _stream(stream)))
+    return results if keep else results[-1]

@@ -3,8 +3,11 @@
 The analogue of the single entry function a compiled model exports in the paper (Section 3):
 the graph's constant inputs are uploaded once, every activation buffer is allocated once, and
 ``run()`` enqueues one library call per node on one stream with no host synchronisation in
-between.  Reshape is a view of dense row-major data and costs nothing.  All arithmetic
-happens inside the library's kernels; this module only prepares argument lists.
+between.  Reshape is a view of dense row-major data and costs nothing.  A model that is one
+linear chain of Conv / pool / Gemm nodes small enough for the library's single-launch chain
+(``onnx_chain``: every activation and all weights in LDS) is run through that one call
+instead.  All arithmetic happens inside the library's kernels; this module only prepares
+argument lists.
 """
 
 import numpy as np
@@ -14,7 +17,10 @@ from . import binding as B
 
 
 class GraphRunner:
-    def __init__(self, model, device="cuda:0", workspace_bytes=64 << 20):
+    def __init__(self, model, device="cuda:0", workspace_bytes=64 << 20, fuse_chain=True, keep_intermediates=False):
+        """fuse_chain: use the single-launch chain when the model qualifies.  keep_intermediates:
+        have the chain write every node's result to device memory too (for layer-by-layer checks;
+        the per-node path always does)."""
         self.device = torch.device(device)
         self.model = model
         for nd in model["graph"]:                  # refuse before anything is allocated or registered
@@ -111,6 +117,70 @@ class GraphRunner:
             else:
                 raise ValueError("unknown node op %r" % (op,))
         self.output = self.t[model["output"]]
+        self.chain = self._build_chain(keep_intermediates) if fuse_chain else None
+
+    def _build_chain(self, keep):
+        """The model as arguments of one onnx_chain call, or None when it is not a linear chain
+        of operators that call takes or the library finds it too large."""
+        g = [nd for nd in self.model["graph"]]
+        if not g or len(self.model["inputs"]) != 1:
+            return None
+        cur = next(iter(self.model["inputs"]))
+        if self.t[cur].dim() != 4:
+            return None
+        ops, outs = [], []
+        for i, nd in enumerate(g):
+            op = nd["op"]
+            if op == "reshape":
+                x = self.t[nd["x"]]
+                nxt = g[i + 1] if i + 1 < len(g) else None
+                if nd["x"] != cur or nxt is None or nxt["op"] != "gemm" or tuple(nd["shape"]) != (x.shape[0], x.numel() // max(x.shape[0], 1)):
+                    return None
+                cur = nd["y"]
+                continue
+            if op == "conv":
+                if nd["x"] != cur or nd["group"] != 1 or nd["residual"]:
+                    return None
+                ops.append(dict(op="conv", W=self.t[nd["w"]], B=self.t[nd["b"]] if nd["b"] else None, pads=nd["pads"],
+                                strides=nd["strides"], dilations=nd["dilations"], act=B.ACT_RELU if nd["relu"] else B.ACT_NONE))
+            elif op == "maxpool":
+                if nd["x"] != cur:
+                    return None
+                ops.append(dict(op="maxpool", kernel=nd["kernel"], pads=nd["pads"], strides=nd["strides"],
+                                dilations=nd["dilations"], ceil_mode=nd["ceil_mode"]))
+            elif op == "avgpool":
+                if nd["x"] != cur:
+                    return None
+                ops.append(dict(op="avgpool", kernel=nd["kernel"], pads=nd["pads"], strides=nd["strides"],
+                                ceil_mode=nd["ceil_mode"], count_include_pad=nd["count_include_pad"]))
+            elif op == "gemm":
+                a, w = self.t[nd["a"]], self.t[nd["b"]]
+                c = self.t[nd["c"]] if nd["c"] else None
+                n = w.shape[0] if nd["transB"] else w.shape[1]
+                if nd["a"] != cur or nd["transA"] or (a.dim() == 4 and a.shape[2] * a.shape[3] != 1):
+                    return None
+                if c is not None and tuple(c.shape) not in ((n,), (1, n)):
+                    return None
+                ops.append(dict(op="gemm", W=w, B=c, transB=nd["transB"], alpha=nd["alpha"], beta=nd["beta"],
+                                act=B.ACT_RELU if nd["relu"] else B.ACT_NONE))
+            else:
+                return None
+            outs.append(self.t[nd["y"]])
+            cur = nd["y"]
+        if cur != self.model["output"] or not ops or len(ops) > B.CHAIN_MAX_OPS:
+            return None
+        x = self.t[next(iter(self.model["inputs"]))]
+        arr, results = B.onnx_chain_args(x, ops, keep=keep, outs=outs)
+        args = [arr, len(ops), B._ptr(x), B.dims(x.shape), None]
+        # the library validates the sizes against what fits on chip; one untimed call finds out
+        args[-1] = B._stream(None)
+        st = B.raw().onnx_chain(*args)
+        if st == B.ONNX_ERR_UNSUPPORTED:
+            return None
+        if st != B.ONNX_OK:
+            raise B.OnnxHipError(st, B.onnx_last_error())
+        self._chain_keepalive = (ops, results)
+        return (B.raw().onnx_chain, args)
 
     def _new(self, name, shape):
         y = torch.empty(tuple(int(s) for s in shape), dtype=torch.float32, device=self.device)
@@ -140,7 +210,7 @@ class GraphRunner:
         # (or clear it) before enqueuing, so that runners never inherit each other's scratch.
         B.onnx_set_workspace(self.workspace)
         sp = B._stream(stream)
-        for fn, args in self.calls:
+        for fn, args in ([self.chain] if self.chain else self.calls):
             args[-1] = sp
             st = fn(*args)
             if st != B.ONNX_OK:

@@ -256,3 +256,58 @@ def test_workspace_setting_checks_its_arguments(B):
     assert lib.onnx_set_workspace(ctypes.c_void_p(1 << 20), 1 << 19) == 4         # below 1 MiB
     assert lib.onnx_set_workspace(ctypes.c_void_p((1 << 20) + 64), 1 << 20) == 4  # not 256-byte aligned
     assert lib.onnx_set_workspace(None, 0) == 0
+
+
+def test_chain_validates_before_touching_the_device(B):
+    """onnx_chain walks the whole chain on the host (shapes, attributes, what fits in LDS) before it
+    launches anything: every refusal below returns without device work."""
+    lib = B.raw()
+    fake = 4096
+
+    def op(kind, **kw):
+        c = B.ChainOp()
+        c.kind = B.CHAIN_KINDS[kind]
+        c.strides[0] = c.strides[1] = 1
+        c.dilations[0] = c.dilations[1] = 1
+        c.alpha = c.beta = 1.0
+        for k, v in kw.items():
+            if k in ("kernel", "pads", "strides", "dilations"):
+                for i, x in enumerate(v):
+                    getattr(c, k)[i] = x
+            else:
+                setattr(c, k, v)
+        return c
+
+    def call(ops, x_dims, X=fake):
+        arr = (B.ChainOp * max(len(ops), 1))(*ops)
+        return lib.onnx_chain(arr, len(ops), ctypes.c_void_p(X) if X else None, B.dims(x_dims), None)
+
+    conv = lambda **kw: op("conv", **dict(dict(outputs=4, kernel=(3, 3), pads=(1, 1, 1, 1), W=fake, Y=fake), **kw))
+    assert lib.onnx_chain(None, 1, ctypes.c_void_p(fake), B.dims((1, 1, 8, 8)), None) == 1
+    assert call([], (1, 1, 8, 8)) == 5 and "operators" in B.onnx_last_error()
+    assert call([conv()] * 9, (1, 1, 8, 8)) == 5
+    assert call([conv()], (1, 1, 8, 8), X=None) == 1
+    assert call([conv(W=None)], (1, 1, 8, 8)) == 1
+    assert call([conv(Y=None)], (1, 1, 8, 8)) == 1 and "last" in B.onnx_last_error()
+    assert call([conv(strides=(0, 1))], (1, 1, 8, 8)) == 4
+    assert call([conv(pads=(1, 1, -1, 1))], (1, 1, 8, 8)) == 4
+    assert call([conv(kernel=(9, 9), pads=(0, 0, 0, 0))], (1, 1, 8, 8)) == 3          # window larger than the image
+    assert call([conv(act=7)], (1, 1, 8, 8)) == 4
+    assert call([op("gemm", outputs=0, W=fake, Y=fake)], (1, 4, 1, 1)) == 4
+    assert call([op("maxpool", kernel=(2, 2), pads=(2, 0, 0, 0), Y=fake)], (1, 1, 8, 8)) == 4   # pad >= window
+    c = op("conv", outputs=4, kernel=(3, 3), W=fake, Y=fake)
+    c.kind = 9
+    assert call([c], (1, 1, 8, 8)) == 4
+    # the limits of what stays on chip
+    assert call([op("maxpool", kernel=(2, 2), strides=(2, 2), Y=fake)], (1, 3, 64, 64)) == 5
+    assert call([conv(outputs=2), op("maxpool", kernel=(2, 2), Y=fake)], (1, 1, 80, 80)) == 5            # the Conv's result
+    assert call([conv(outputs=4, kernel=(7, 7), pads=(3, 3, 3, 3))], (1, 8, 30, 30)) == 5                 # input + padding
+    assert call([conv(outputs=64)], (1, 64, 8, 8)) == 5 and "weights" in B.onnx_last_error()
+    assert call([conv(outputs=2)], (1, 240, 4, 4)) == 5 and "2160" in B.onnx_last_error()
+    # an empty batch is not an error and launches nothing
+    assert call([conv()], (0, 1, 8, 8)) == 0
+    text = open(os.path.join(ROOT, "include", "onnxhip.h")).read()
+    for name, value in (("MAX_OPS", B.CHAIN_MAX_OPS), ("MAX_ACTIVATION", B.CHAIN_MAX_ACTIVATION),
+                        ("MAX_WEIGHTS", B.CHAIN_MAX_WEIGHTS), ("MAX_CONV_K", B.CHAIN_MAX_CONV_K)):
+        assert "#define ONNX_CHAIN_%s %d" % (name, value) in text
+    assert ctypes.sizeof(B.ChainOp) == 144

@@ -554,7 +554,7 @@ def test_errors_write_nothing(lib):
 def _run_chain(lib, model, workspace="workspace"):
     """The runner sets its own workspace at the start of a run: none or 64 MiB, following the fixture."""
     from paper_2008_08272_amd.runner import GraphRunner
-    r = GraphRunner(model, workspace_bytes=(64 << 20) if workspace == "workspace" else 0)
+    r = GraphRunner(model, workspace_bytes=(64 << 20) if workspace == "workspace" else 0, keep_intermediates=True)
     out = r.run()
     torch.cuda.synchronize()
     return r, out.cpu().numpy()
