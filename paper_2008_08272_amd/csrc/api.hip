@@ -265,7 +265,7 @@ onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const f
         if (launch_conv_window(p, (int)kH, (int)kW, (int)OH, (int)OW, (int)Cg, (int)group, ws, s, &e))
             return device_status(e, "conv (lds patch)");
     }
-    const int tile = pick_tile(Mg, NP, K, group);
+    const int tile = pick_tile(Mg, NP, K, group, bkind != LOAD_IM2COL);
     return device_status(launch_contraction(p, LOAD_KC, bkind, a_vec ? 4 : 1, bvec, tile, (int)group, ws, s),
                          "conv (mfma)");
 }

@@ -30,6 +30,10 @@ static hipError_t launch_tile(ContractionParams& p, int tile, int nz, const Work
         case TILE_64_SLICED: return launch_one<64, 64, 32, 2, 2, 2, AK, BKIND, AVEC, BVEC>(p, nz, ws, stream);
         case TILE_128: return launch_one<128, 128, 16, 4, 4, 1, AK, BKIND, AVEC, BVEC>(p, nz, ws, stream);
         case TILE_256: return launch_one<256, 256, 16, 4, 4, 1, AK, BKIND, AVEC, BVEC>(p, nz, ws, stream);
+        case TILE_32_SLICED:
+            // the gather loader works on 64 columns at a time: no 32-wide form
+            if constexpr (BKIND == LOAD_IM2COL) return launch_one<64, 64, 32, 2, 2, 2, AK, BKIND, AVEC, BVEC>(p, nz, ws, stream);
+            else return launch_one<32, 32, 64, 1, 1, 4, AK, BKIND, AVEC, BVEC>(p, nz, ws, stream);
         default: return hipErrorInvalidValue;
     }
 }
@@ -40,15 +44,15 @@ static hipError_t launch_tile(ContractionParams& p, int tile, int nz, const Work
 // workgroup per CU at a time, so their tile count is rounded up to whole rounds of 256: they
 // win exactly where that rounding is cheap (2048^2 outputs = 256 tiles of 128: measured 130
 // against 123 TFLOP/s for the 64 tile; 4096^2 = 256 tiles of 256: 147 against 144 and 130).
-int pick_tile(int64_t M, int64_t N, int64_t K, int64_t nz) {
-    static const int bm[TILE_COUNT] = {64, 64, 128, 256};
-    static const double eff[TILE_COUNT] = {0.92, 0.92, 0.93, 0.94};
-    static const int resident[TILE_COUNT] = {8, 4, 1, 1};    // workgroups that share a CU
+int pick_tile(int64_t M, int64_t N, int64_t K, int64_t nz, bool narrow_ok) {
+    static const int bm[TILE_COUNT] = {64, 64, 128, 256, 32};
+    static const double eff[TILE_COUNT] = {0.92, 0.92, 0.93, 0.94, 0.5};
+    static const int resident[TILE_COUNT] = {8, 4, 1, 1, 8};    // workgroups that share a CU
     const double cus = 256.0;
     int best = TILE_64;
     double best_cost = 0.0;
     for (int t = 0; t < TILE_COUNT; ++t) {
-        if (t == TILE_64_SLICED) continue;
+        if (t == TILE_64_SLICED || t == TILE_32_SLICED) continue;
         // 16 wavefronts on a 128 x 128 tile pay off on a long K walk only (96 products of
         // 512 x 512 x 64 ran at 60 instead of 75 TFLOP/s with it)
         if (t == TILE_128 && K < 512) continue;
@@ -65,6 +69,11 @@ int pick_tile(int64_t M, int64_t N, int64_t K, int64_t nz) {
     if (best == TILE_64) {
         const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64) * nz;
         if (tiles <= 2 * 256 && K >= 256) best = TILE_64_SLICED;
+        // Fewer tiles than half the CUs (batch-1 layers): a quarter of the tile with four K slices
+        // gives four times the workgroups, each with a quarter of the K walk, and usually makes
+        // the split-K finishing launch unnecessary (ResNet-50 at batch 1: 8-12 us per layer
+        // instead of 10-14).
+        if (narrow_ok && tiles <= 128 && K >= 128) best = TILE_32_SLICED;
     }
     return best;
 }

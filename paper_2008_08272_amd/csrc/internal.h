@@ -12,10 +12,12 @@ namespace onnxhip {
 //   TILE_64_SLICED   64 x  64 x 32, 2x2 wavefronts x 2 K slices      -- few tiles, long K
 //   TILE_128        128 x 128 x 16, 4x4 wavefronts  -- outputs of about 256 or 512 such tiles
 //   TILE_256        256 x 256 x 16, 4x4 wavefronts  -- large products, one workgroup per CU
-enum TileShape { TILE_64 = 0, TILE_64_SLICED = 1, TILE_128 = 2, TILE_256 = 3, TILE_COUNT };
+//   TILE_32_SLICED   32 x  32 x 64, 1 wavefront x 4 K slices          -- very few outputs (batch 1), long K
+enum TileShape { TILE_64 = 0, TILE_64_SLICED = 1, TILE_128 = 2, TILE_256 = 3, TILE_32_SLICED = 4, TILE_COUNT };
 
 // Picks the tile with the lowest estimated time for an M x N x K product repeated nz times.
-int pick_tile(int64_t M, int64_t N, int64_t K, int64_t nz);
+// `narrow_ok`: the operand loaders of this call exist for the 32-wide tile (all but the gather loader).
+int pick_tile(int64_t M, int64_t N, int64_t K, int64_t nz, bool narrow_ok = true);
 
 // Scratch memory for split-K partial tiles: the buffer handed over through onnx_set_workspace,
 // or the library's own fixed array for the entry point that may not allocate.  Every launcher

@@ -801,7 +801,8 @@ def _offset_dev(a, misalign):
 GEMM_TILE_CLASSES = {
     "64x64x16": ((132, 200, 72), "64x64x16 waves 2x2x1"),
     "64x64x32": ((1500, 1504, 512), "64x64x32 waves 2x2x1"),
-    "64x64x32 sliced": ((200, 152, 300), "64x64x32 waves 2x2x2"),
+    "64x64x32 sliced": ((800, 900, 300), "64x64x32 waves 2x2x2"),
+    "32x32x64 sliced": ((200, 152, 300), "32x32x64 waves 1x1x4"),
     "128x128x16": ((2048, 2048, 512), "128x128x16 waves 4x4x1"),
     "256x256x16": ((4096, 4096, 40), "256x256x16 waves 4x4x1"),
 }
@@ -848,8 +849,10 @@ CONV_INSTANCE_CASES = [
     ("rcs 64x64x16 4B", (2, 18, 13, 11), (40, 18, 1, 1), (0, 0, 0, 0), (3, 2), "64x64x16 waves 2x2x1 A=KC/1 B=RCS/1"),
     ("rcs 64x64x32 16B", (9, 512, 64, 64), (256, 512, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x32 waves 2x2x1 A=KC/4 B=RCS/1"),
     ("rcs 64x64x32 4B", (9, 514, 64, 64), (256, 514, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x32 waves 2x2x1 A=KC/1 B=RCS/1"),
-    ("rcs sliced 16B", (2, 512, 14, 14), (128, 512, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x32 waves 2x2x2 A=KC/4 B=RCS/1"),
-    ("rcs sliced 4B", (2, 510, 14, 14), (128, 510, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x32 waves 2x2x2 A=KC/1 B=RCS/1"),
+    ("rcs sliced 16B", (8, 512, 56, 56), (128, 512, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x32 waves 2x2x2 A=KC/4 B=RCS/1"),
+    ("rcs sliced 4B", (8, 510, 56, 56), (128, 510, 1, 1), (0, 0, 0, 0), (2, 2), "64x64x32 waves 2x2x2 A=KC/1 B=RCS/1"),
+    ("rcs 32x32x64 sliced 16B", (2, 512, 14, 14), (128, 512, 1, 1), (0, 0, 0, 0), (2, 2), "32x32x64 waves 1x1x4 A=KC/4 B=RCS/1"),
+    ("rcs 32x32x64 sliced 4B", (2, 510, 14, 14), (128, 510, 1, 1), (0, 0, 0, 0), (2, 2), "32x32x64 waves 1x1x4 A=KC/1 B=RCS/1"),
     ("rcs 128x128x16 16B", (2, 512, 128, 128), (512, 512, 1, 1), (0, 0, 0, 0), (2, 2), "128x128x16 waves 4x4x1 A=KC/4 B=RCS/1"),
     ("rcs 128x128x16 4B", (2, 514, 128, 128), (512, 514, 1, 1), (0, 0, 0, 0), (2, 2), "128x128x16 waves 4x4x1 A=KC/1 B=RCS/1"),
     ("rcs 256x256x16 16B", (8, 16, 128, 128), (512, 16, 1, 1), (0, 0, 0, 0), (2, 2), "256x256x16 waves 4x4x1 A=KC/4 B=RCS/1"),
@@ -857,6 +860,8 @@ CONV_INSTANCE_CASES = [
     # pointwise convolutions: the row-contiguous loader with images as column blocks
     ("pointwise 16B/16B", (2, 64, 12, 12), (96, 64, 1, 1), (0, 0, 0, 0), (1, 1), "64x64x16 waves 2x2x1 A=KC/4 B=RC/4"),
     ("pointwise 16B/4B (P = 49)", (32, 512, 7, 7), (2048, 512, 1, 1), (0, 0, 0, 0), (1, 1), "64x64x32 waves 2x2x1 A=KC/4 B=RC/1"),
+    ("pointwise 32x32x64 sliced (P = 49)", (1, 512, 7, 7), (2048, 512, 1, 1), (0, 0, 0, 0), (1, 1), "32x32x64 waves 1x1x4 A=KC/4 B=RC/1"),
+    ("pointwise 32x32x64 sliced", (1, 256, 14, 14), (1024, 256, 1, 1), (0, 0, 0, 0), (1, 1), "32x32x64 waves 1x1x4 A=KC/4 B=RC/4"),
     ("pointwise 128x128x16", (8, 512, 32, 32), (512, 512, 1, 1), (0, 0, 0, 0), (1, 1), "128x128x16 waves 4x4x1 A=KC/4 B=RC/4"),
     ("pointwise 256x256x16", (32, 64, 32, 32), (512, 64, 1, 1), (0, 0, 0, 0), (1, 1), "256x256x16 waves 4x4x1 A=KC/4 B=RC/4"),
 ]

@@ -27,10 +27,10 @@ def test_fixed_scratch_conv_two_calls_in_a_row():
     lib = B.raw()
     rng = np.random.default_rng(2008)
     # few output tiles and a long K walk, so that both calls split K through the scratch:
-    # 3x3 on 2x256x14x14 (LDS-patch kernel), then the smaller 1x1 on 1x512x7x7 (contraction kernel)
+    # 3x3 on 2x256x14x14 (LDS-patch kernel), then the smaller 1x1 on 1x1536x7x7 (contraction kernel)
     cases = [
         ((2, 256, 14, 14), (256, 256, 3, 3), (1, 1, 1, 1), (1, 1), (1, 1), 1, True),
-        ((1, 512, 7, 7), (128, 512, 1, 1), (0, 0, 0, 0), (1, 1), (1, 1), 1, False),
+        ((1, 1536, 7, 7), (128, 1536, 1, 1), (0, 0, 0, 0), (1, 1), (1, 1), 1, False),
     ]
     same_size_ws = torch.empty(B.CONV_FIXED_SCRATCH_BYTES, dtype=torch.uint8, device="cuda")
     for i, (xs, ws_, pads, st, dl, g, with_res) in enumerate(cases):
