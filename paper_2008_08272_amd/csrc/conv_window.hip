@@ -12,7 +12,7 @@ struct WindowConfig {
 };
 // Keep in step with the template instances in launch_config below.
 const WindowConfig kConfigs[] = {
-    {64, 64, 256, 8, 0.75},
+    {64, 64, 256, 9, 0.75},
     {128, 128, 512, 8, 0.80},
 };
 const int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
@@ -49,6 +49,11 @@ hipError_t launch_passes(ContractionParams& p, int npb, int nz, const Workspace&
     if (npb <= 5) return launch_instance<BM, BN, WM, WN, KH, KW, 5>(p, nz, ws, stream);
     if (npb <= 6) return launch_instance<BM, BN, WM, WN, KH, KW, 6>(p, nz, ws, stream);
     if (npb <= 8) return launch_instance<BM, BN, WM, WN, KH, KW, 8>(p, nz, ws, stream);
+    // nine passes: the stride-2 3x3 convolution of a 56 x 56 plane (ResNet50's first down-sampling block)
+    // needs 2052 patch floats per channel block on the 64 x 64 tile, four more than eight passes hold
+    if constexpr (BM == 64) {
+        if (npb <= 9) return launch_instance<BM, BN, WM, WN, KH, KW, 9>(p, nz, ws, stream);
+    }
     return hipErrorInvalidValue;
 }
 
@@ -80,7 +85,11 @@ bool launch_conv_window(ContractionParams& p, int kH, int kW, int OH, int OW, in
         const double tiles = (double)((p.M + k.bm - 1) / k.bm) * (double)((p.N + k.bn - 1) / k.bn) * nz;
         double rounds = tiles / 256.0;
         if (rounds < 1.0) rounds = 1.0;
-        const double cost = rounds * k.bm * k.bn / k.eff;
+        // the nine-pass instance keeps three instead of four wavefronts per SIMD: on a full chip it ran
+        // the 56 -> 28 stride-2 layer at 73 TFLOP/s where the 128 x 128 tile reaches 82; with few tiles
+        // (batch 1: 18 against 29 us) it is the better one
+        const double eff = WIN_CB * plane > (int64_t)8 * k.nt ? 0.55 : k.eff;
+        const double cost = rounds * k.bm * k.bn / eff;
         if (best < 0 || cost < best_cost) { best = c; best_cost = cost; best_plane = (int)plane; }
     }
     if (best < 0) return false;
