@@ -39,7 +39,7 @@ struct ChainCopy {
     int count, chunk0;       // chunk0: index of this tensor's first 64-float chunk in the whole list
     int dst, pitch, plane;
     int per_image;           // src advances by count per image (the input tensor)
-    int mode;                // 0: stored contiguously, 1: rows of one plane, 2: rows and planes
+    int mode;                // 0: stored contiguously, 1: rows of one plane, 2: rows and planes, 3: transposed (element x of row r at dst + x*pitch + r)
     FastDiv row, rows;
 };
 
@@ -54,6 +54,7 @@ struct ChainOp {
     int w_off, b_off;                              // LDS offsets of weights and bias (b_off < 0: no bias)
     int transB, cip;
     int interior;                                  // pools: every window lies inside the input
+    int direct;                                    // Conv: at most 8 output channels and a short K: one thread per position
     float alpha, beta;
     float* Y;                                      // NULL or [images][M][OH][OW]
     int y_img;
@@ -192,6 +193,48 @@ __device__ inline void conv_items(const ConvSite& c, int wave, int lane, int til
     }
 }
 
+// A Conv with at most 8 output channels and a short reduction: the matrix-core path would leave half
+// of every MFMA empty and spend its time in set-up and epilogue.  One thread per output position
+// instead: per k one input value, the k-th column of the filter matrix (stored [k][8] in LDS: two
+// 16-byte reads that every lane shares) and 8 FMAs.
+__device__ inline void conv_direct8(const ConvSite& c, int t) {
+    for (int pos = t; pos < c.P; pos += CHAIN_THREADS) {
+        uint32_t oh, ow;
+        c.dOW.divmod((uint32_t)pos, oh, ow);
+        const float* bp = c.in + (int)oh * c.sH * c.in_pitch + (int)ow * c.sW;
+        float acc[8];
+#pragma unroll
+        for (int m = 0; m < 8; ++m) acc[m] = 0.f;
+        auto tap = [&](int k, int off) {
+            const float x = bp[off];
+            const floatx4v w0 = *reinterpret_cast<const floatx4v*>(c.w + 8 * k);
+            const floatx4v w1 = *reinterpret_cast<const floatx4v*>(c.w + 8 * k + 4);
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                acc[m] = fmaf(w0[m], x, acc[m]);
+                acc[4 + m] = fmaf(w1[m], x, acc[4 + m]);
+            }
+        };
+        int k = 0;
+        for (; k + 4 <= c.K; k += 4) {
+            const intx4v off = *reinterpret_cast<const intx4v*>(c.koff + k);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) tap(k + u, off[u]);
+        }
+        for (; k < c.K; ++k) tap(k, c.koff[k]);
+        float* o = c.out + c.out_off + (int)oh * c.out_pitch + (int)ow;
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            if (m < c.M) {
+                float v = acc[m] + (c.bias ? c.bias[m] : 0.f);
+                if (c.relu) v = fmaxf(v, 0.f);
+                o[m * c.out_plane] = v;
+                if (c.yimg) c.yimg[m * c.P + pos] = v;
+            }
+        }
+    }
+}
+
 __device__ inline int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
 // Sum of a value over the 64 lanes, the same in every lane, without LDS traffic: rotations inside
@@ -255,7 +298,7 @@ __global__ __launch_bounds__(CHAIN_THREADS) void chain_kernel(const ChainParams)
                         c.row.divmod((uint32_t)e, r, x);
                         h = r;
                         if (mode == 2) c.rows.divmod(r, pl, h);
-                        d[u] = c.dst + (int)pl * c.plane + (int)h * c.pitch + (int)x;
+                        d[u] = mode == 3 ? c.dst + (int)x * c.pitch + (int)r : c.dst + (int)pl * c.plane + (int)h * c.pitch + (int)x;
                     }
                 }
             }
@@ -305,7 +348,8 @@ __global__ __launch_bounds__(CHAIN_THREADS) void chain_kernel(const ChainParams)
             const ConvSite cs{in, out, yimg, arena + w_off, b_off >= 0 ? arena + b_off : nullptr, koff, dOW,
                               M, P, K, Kp, sH, sW, in_pitch, out_off, out_plane, out_pitch, relu};
             // position tiles per item: as many as still leave an item for every wavefront
-            if (tiles_p * mblocks >= 4 * CHAIN_WAVES - 15) conv_items<4>(cs, wave, lane, tiles_p, mblocks);
+            if (uni(op.direct)) conv_direct8(cs, t);
+            else if (tiles_p * mblocks >= 4 * CHAIN_WAVES - 15) conv_items<4>(cs, wave, lane, tiles_p, mblocks);
             else if (tiles_p * mblocks >= 2 * CHAIN_WAVES - 7) conv_items<2>(cs, wave, lane, tiles_p, mblocks);
             else conv_items<1>(cs, wave, lane, tiles_p, mblocks);
         } else if (kind == ONNX_CHAIN_MAXPOOL || kind == ONNX_CHAIN_AVGPOOL) {
@@ -454,7 +498,7 @@ extern "C" onnx_status onnx_chain(const onnx_chain_op* ops, int n_ops, const flo
         op.in_pitch = (int)(dims[3] + lay[1] + lay[3]);
         op.in_plane = (int)((dims[2] + lay[0] + lay[2]) * op.in_pitch);
         op.in_off = (int)(lay[0] * op.in_pitch + lay[1]);
-        op.w_off = 0; op.b_off = -1; op.K = 0; op.Kp = 0; op.transB = 0; op.cip = 0; op.interior = 0; op.alpha = 1.f; op.beta = 1.f;
+        op.w_off = 0; op.b_off = -1; op.K = 0; op.Kp = 0; op.transB = 0; op.cip = 0; op.interior = 0; op.direct = 0; op.alpha = 1.f; op.beta = 1.f;
         op.kH = op.kW = op.sH = op.sW = op.dH = op.dW = 1; op.pT = op.pL = op.pB = op.pR = 0;
         int64_t yd[4] = {images, 0, 1, 1};
         if (s.kind == ONNX_CHAIN_CONV) {
@@ -474,8 +518,17 @@ extern "C" onnx_status onnx_chain(const onnx_chain_op* ops, int n_ops, const flo
             op.dH = (int)s.dilations[0]; op.dW = (int)s.dilations[1];
             op.pT = (int)s.pads[0]; op.pL = (int)s.pads[1]; op.pB = (int)s.pads[2]; op.pR = (int)s.pads[3];
             op.w_off = (int)arena;
-            if (arena + s.outputs * op.Kp <= ARENA_MAX)
-                add_copy(s.W, s.outputs * K, 2 * ACT_MAX + arena, K, op.Kp, s.outputs, 0, 0);
+            // few output channels, short K: the one-thread-per-position form, filters stored [k][8]
+            // (when that takes no more LDS than the rows would)
+            op.direct = s.outputs <= 8 && K <= 256 && 8 * K <= s.outputs * op.Kp;
+            if (arena + s.outputs * op.Kp <= ARENA_MAX) {
+                if (op.direct) {
+                    add_copy(s.W, s.outputs * K, 2 * ACT_MAX + arena, K, 8, s.outputs, 0, 0);
+                    p.copies[p.n_copies - 1].mode = 3;
+                } else {
+                    add_copy(s.W, s.outputs * K, 2 * ACT_MAX + arena, K, op.Kp, s.outputs, 0, 0);
+                }
+            }
             arena += s.outputs * op.Kp;
         } else if (s.kind == ONNX_CHAIN_MAXPOOL || s.kind == ONNX_CHAIN_AVGPOOL) {
             const bool global = s.kind == ONNX_CHAIN_AVGPOOL && s.kernel[0] == 0 && s.kernel[1] == 0;

@@ -129,6 +129,13 @@ def chain_cases():
         dict(op="conv", W=_rand(rng, (6, 128, 4, 4), 0.05), B=_rand(rng, (6,)), act=1),
         dict(op="maxpool", kernel=(2, 2), strides=(1, 1), pads=(1, 1, 1, 1)),
         dict(op="gemm", W=_rand(rng, (6 * 6 * 8, 3)), B=None)])
+    # at most 8 output channels and a short K: the one-thread-per-position Conv, with strides, pads and dilation,
+    # feeding a padded Conv on the matrix cores
+    cases["direct_conv"] = ((3, 2, 23, 19), [
+        dict(op="conv", W=_rand(rng, (7, 2, 3, 3)), B=_rand(rng, (7,)), pads=(2, 0, 1, 3), strides=(2, 3), dilations=(1, 2), act=1),
+        dict(op="conv", W=_rand(rng, (8, 7, 2, 2), 0.4), B=None, pads=(1, 1, 0, 0)),
+        dict(op="conv", W=_rand(rng, (12, 8, 3, 3), 0.3), B=_rand(rng, (12,)), pads=(1, 1, 1, 1), act=1),
+        dict(op="avgpool", kernel=None)])
     # a single operator of each kind
     cases["one_conv"] = ((1, 4, 9, 9), [dict(op="conv", W=_rand(rng, (3, 4, 3, 3)), B=None, pads=(1, 1, 1, 1))])
     cases["one_pool"] = ((4, 6, 11, 13), [dict(op="maxpool", kernel=(3, 3), strides=(2, 2), pads=(1, 1, 1, 1), ceil_mode=1)])
