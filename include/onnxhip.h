@@ -319,7 +319,8 @@ onnx_status onnx_lstm(const float* X, const int64_t x_dims[3], const float* W, c
  * rows count as C*kH*kW rounded up to a multiple of 16, plus 4); a Conv's C*kH*kW at most
  * ONNX_CHAIN_MAX_CONV_K.
  * Attribute and shape errors are those of the single operators.  Everything is validated before
- * the launch; nothing is allocated; Y buffers must not overlap X or the weights.
+ * the launch; nothing is allocated; a Y buffer that overlaps X, a weight, a bias or another Y is refused
+ * (ONNX_ERR_ALIAS).
  */
 #define ONNX_CHAIN_MAX_OPS 8
 #define ONNX_CHAIN_MAX_ACTIVATION 10240

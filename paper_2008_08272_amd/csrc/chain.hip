@@ -590,6 +590,19 @@ extern "C" onnx_status onnx_chain(const onnx_chain_op* ops, int n_ops, const flo
     }
     if (images > 0x7fffffffLL) return fail(ONNX_ERR_UNSUPPORTED, "chain: more than 2^31-1 images");
     if (empty) return ONNX_OK;
+    // no result may overlap the input, a weight, a bias or another result
+    const int64_t x_bytes = images * x_dims[1] * x_dims[2] * x_dims[3] * 4;
+    for (int o = 0; o < n_ops; ++o) {
+        if (!p.ops[o].Y) continue;
+        const int64_t y_bytes = images * p.ops[o].y_img * 4;
+        if (overlaps(p.ops[o].Y, y_bytes, X, x_bytes)) return fail(ONNX_ERR_ALIAS, "chain: the result of op %d overlaps X", o);
+        for (int c = 1; c < p.n_copies; ++c)
+            if (overlaps(p.ops[o].Y, y_bytes, p.copies[c].src, (int64_t)p.copies[c].count * 4))
+                return fail(ONNX_ERR_ALIAS, "chain: the result of op %d overlaps a weight or bias", o);
+        for (int q = 0; q < o; ++q)
+            if (p.ops[q].Y && overlaps(p.ops[o].Y, y_bytes, p.ops[q].Y, images * p.ops[q].y_img * 4))
+                return fail(ONNX_ERR_ALIAS, "chain: the results of ops %d and %d overlap", q, o);
+    }
     p.total_chunks = (int)chunks;
     hipLaunchKernelGGL(chain_kernel, dim3((unsigned)images), dim3(CHAIN_THREADS), 0, static_cast<hipStream_t>(stream), p);
     const hipError_t e = hipGetLastError();

@@ -304,6 +304,10 @@ def test_chain_validates_before_touching_the_device(B):
     assert call([conv(outputs=4, kernel=(7, 7), pads=(3, 3, 3, 3))], (1, 8, 30, 30)) == 5                 # input + padding
     assert call([conv(outputs=64)], (1, 64, 8, 8)) == 5 and "weights" in B.onnx_last_error()
     assert call([conv(outputs=2)], (1, 240, 4, 4)) == 5 and "2160" in B.onnx_last_error()
+    # results that overlap the input, a weight or each other
+    assert call([conv(Y=fake + 64)], (1, 1, 8, 8)) == 6
+    assert call([conv(W=1 << 20, Y=(1 << 20) + 16)], (1, 1, 8, 8)) == 6
+    assert call([conv(Y=1 << 21), op("maxpool", kernel=(2, 2), Y=(1 << 21) + 256)], (1, 1, 8, 8)) == 6
     # an empty batch is not an error and launches nothing
     assert call([conv()], (0, 1, 8, 8)) == 0
     text = open(os.path.join(ROOT, "include", "onnxhip.h")).read()
