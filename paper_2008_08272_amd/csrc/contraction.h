@@ -632,9 +632,11 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void contraction_kernel(const Co
     static_assert(BK % 8 == 0, "K step is a multiple of the 8-wide half-step");
     constexpr int BVEC = (BKIND == LOAD_IM2COL || BKIND == LOAD_RCS) ? 1 : BVEC_;
     // Steps the global loads run ahead of the MFMAs.  Two hides the memory latency behind a whole
-    // step of MFMAs; one where a step is long anyway (BK = 32: measured 1-2 % faster) or where
-    // the second staging set would not fit in the 128 registers a 1024-thread workgroup has.
-    constexpr int PF = (BK >= 32 || (BM * BN >= 256 * 256 && BKIND == LOAD_IM2COL)) ? 1 : 2;
+    // step of MFMAs; one where a step is long anyway (BK = 32 without K slices: measured 1-2 %
+    // faster; with K slices a step is half or a quarter as long and two is 2-7 % faster, 20 % on a
+    // 200-tile layer with K = 2048) or where the second staging set would not fit in the 128
+    // registers a 1024-thread workgroup has.
+    constexpr int PF = ((BK >= 32 && KS == 1) || (BM * BN >= 256 * 256 && BKIND == LOAD_IM2COL)) ? 1 : 2;
     using ALoader = TileLoader<AKIND, AVEC, BM, BK, NT, PF>;
     using BLoader = TileLoader<BKIND, BVEC, BN, BK, NT, PF>;
 
