@@ -244,9 +244,10 @@ typedef enum { ONNX_F32 = 0, ONNX_F16 = 1, ONNX_BF16 = 2 } onnx_dtype;
  * Section 3.1): Y = alpha * op(A) * op(B) + beta * C with A and B stored as in_type, every
  * transA / transB combination, any K.  Products are exact and summed in fp32; C (NULL, or fp32
  * broadcastable to [M,N] as for onnx_gemm) and the epilogue are fp32; Y is stored as out_type:
- * ONNX_F32, or in_type with round-to-nearest-even.  The tuned kernel takes transA = 0,
- * transB = 1 (both operands K-contiguous) with K a multiple of 8 and A, B 16-byte aligned;
- * every other case runs through a general, slower kernel that transposes operands on their way
+ * ONNX_F32, or in_type with round-to-nearest-even.  The tuned kernel takes transA = 0 with K a
+ * multiple of 8 and A 16-byte aligned, and B either K-contiguous (transB = 1, 16-byte aligned)
+ * or row-contiguous (transB = 0, N a multiple of 4, 8-byte aligned); every other case runs
+ * through a general, slower kernel that transposes operands element by element on their way
  * into LDS.
  */
 onnx_status onnx_gemm_lp(const void* A, const int64_t a_dims[2], const void* B, const int64_t b_dims[2],
@@ -256,7 +257,9 @@ onnx_status onnx_gemm_lp(const void* A, const int64_t a_dims[2], const void* B, 
 
 /*
  * ONNX MatMul on 16-bit inputs: numpy.matmul semantics as onnx_matmul, A and B stored as in_type,
- * fp32 accumulation, Y stored as out_type (ONNX_F32 or in_type, rounded to nearest even).
+ * fp32 accumulation, Y stored as out_type (ONNX_F32 or in_type, rounded to nearest even).  The
+ * tuned kernel takes K a multiple of 8 and N a multiple of 4 with aligned operands, as for
+ * onnx_gemm_lp with transB = 0; other shapes run through the general kernel.
  */
 onnx_status onnx_matmul_lp(const void* A, const int64_t* a_dims, int a_rank, const void* B,
                            const int64_t* b_dims, int b_rank, void* Y, const int64_t* y_dims, int y_rank,
@@ -265,9 +268,11 @@ onnx_status onnx_matmul_lp(const void* A, const int64_t* a_dims, int a_rank, con
 /*
  * ONNX Conv on 16-bit inputs: the semantics, attributes and errors of onnx_conv; X and W stored
  * as in_type, the bias B in fp32 ([M] or NULL), fp32 accumulation, Y and the optional residual
- * stored as out_type (ONNX_F32 or in_type, rounded to nearest even).  Every shape runs through
- * one general kernel (the pointwise case reads the input row-contiguously, the others gather
- * it); no workspace is used.
+ * stored as out_type (ONNX_F32 or in_type, rounded to nearest even).  A 1x1 convolution with
+ * stride 1 and no padding whose C/group is a multiple of 8 and whose H*W is a multiple of 4 runs
+ * through the tuned kernel of onnx_gemm_lp (the input of an image is a row-contiguous
+ * [C][H*W] matrix); every other shape runs through one general kernel that gathers the input
+ * element by element.  No workspace is used.
  */
 onnx_status onnx_conv_lp(const void* X, const int64_t x_dims[4], const void* W, const int64_t w_dims[4],
                          const float* B, const int64_t pads[4], const int64_t strides[2],

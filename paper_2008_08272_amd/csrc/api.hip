@@ -206,6 +206,9 @@ onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const f
         p.ic.kW = FastDiv::make((uint32_t)kW);
         p.ic.OW = FastDiv::make((uint32_t)OW);
         p.ic.image_stride = (int)(C * H * Wd);
+        const int bvec = pw ? lp_tuned_fits(p, LOAD_KC, LOAD_RC, (int)group) : 0;
+        if (bvec)
+            return device_status(launch_lp_tuned(p, LOAD_RC, bvec, (int)group, (int)in_type, (int)out_type, s), "conv (16-bit)");
         return device_status(launch_lp_generic(p, LOAD_KC, pw ? LOAD_RC : LOAD_IM2COL, (int)group, (int)in_type,
                                                (int)out_type, s), "conv (16-bit)");
     }
@@ -344,9 +347,14 @@ onnx_status matmul_any(const float* A, const int64_t* a_dims, int a_rank, const 
     p.M = (int)Meff; p.N = (int)N; p.K = (int)K;
     p.a_ld = K; p.b_ld = N; p.y_rs = N; p.y_zs = M * N;
     p.alpha = 1.f; p.beta = 0.f; p.bias_mode = BIAS_NONE; p.bias_cs = 0; p.relu = 0;
-    if (in_type != ONNX_F32)
+    if (in_type != ONNX_F32) {
+        const int bvec = lp_tuned_fits(p, LOAD_KC, LOAD_RC, (int)nz);
+        if (bvec)
+            return device_status(launch_lp_tuned(p, LOAD_RC, bvec, (int)nz, (int)in_type, (int)out_type,
+                                                 static_cast<hipStream_t>(stream)), "matmul (16-bit)");
         return device_status(launch_lp_generic(p, LOAD_KC, LOAD_RC, (int)nz, (int)in_type, (int)out_type,
                                                static_cast<hipStream_t>(stream)), "matmul (16-bit)");
+    }
     const bool a4 = aligned16(A) && K % 4 == 0, b4 = aligned16(B) && N % 4 == 0;
     const int tile = pick_tile(Meff, N, K, nz);
     return device_status(launch_contraction(p, LOAD_KC, LOAD_RC, a4 ? 4 : 1, b4 ? 4 : 1, tile, (int)nz, workspace(),

@@ -1,11 +1,15 @@
-// Gemm on 16-bit inputs (IEEE half or bfloat16) with fp32 accumulation, on the gfx950 matrix cores.
+// Contractions on 16-bit inputs (IEEE half or bfloat16) with fp32 accumulation, on the gfx950
+// matrix cores: the tuned kernel behind onnx_gemm_lp, onnx_matmul_lp and the 1x1 case of
+// onnx_conv_lp.
 //
 // The paper's operator definitions admit 16-bit floating-point tensors (Section 3.1: the
-// LeakyRelu definition lists F16 next to F32 and F64).  Here Y = alpha * A * B^T + beta * C for
-// A [M, K] and B [N, K], both K-contiguous and stored as 16-bit values; products are exact in
-// fp32 and the sum is kept in fp32 accumulators (v_mfma_f32_32x32x16_{f16,bf16}: one MFMA
-// consumes 16 k, each lane supplying 8 consecutive k of its row or column).  The bias C and the
-// epilogue arithmetic are fp32; Y is stored as fp32 or rounded to the input type (nearest even).
+// LeakyRelu definition lists F16 next to F32 and F64).  Here Y = alpha * A * B + beta * C per
+// z-slice for A [M, K], K-contiguous, and B either [N, K] (K-contiguous: Gemm with transB) or
+// [K, N] (row-contiguous: Gemm without transB, MatMul, the input of a 1x1 stride-1 convolution),
+// both stored as 16-bit values; products are exact in fp32 and the sum is kept in fp32
+// accumulators (v_mfma_f32_32x32x16_{f16,bf16}: one MFMA consumes 16 k, each lane supplying 8
+// consecutive k of its row or column).  The bias C and the epilogue arithmetic are fp32; Y is
+// stored as fp32 or rounded to the input type (nearest even).
 //
 // Same decomposition as contraction.h: a workgroup of WM x WN wavefronts owns a BM x BN tile,
 // walks K in steps of BK through two LDS buffers, global loads one or two steps ahead in
@@ -22,6 +26,16 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 enum { LP_F16 = 1, LP_BF16 = 2 };
 
+// Values that are the same in every lane but were computed by vector instructions (the integer
+// divisions of the z-slice decomposition are) and end up in a buffer resource: taken into scalar
+// registers here, once, instead of by a loop around every load and store that uses them.
+__device__ inline int scalar(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ inline int64_t scalar(int64_t v) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
 template <int DT>
 __device__ inline floatx16 mfma16(const floatx4& a, const floatx4& b, const floatx16& c) {
     if (DT == LP_BF16)
@@ -34,8 +48,8 @@ template <int DT>
 __device__ inline uint16_t to_lp(float v) {
     if (DT == LP_F16) return __builtin_bit_cast(uint16_t, (_Float16)v);
     const uint32_t u = __builtin_bit_cast(uint32_t, v);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);      // NaN stays NaN
-    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+    const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    return (uint16_t)((u & 0x7fffffffu) > 0x7f800000u ? (u >> 16) | 0x40u : rounded);      // NaN stays NaN
 }
 
 // K-contiguous tile loader for 16-bit elements: ROWS x BK values, 16-byte chunks of 8.
@@ -86,14 +100,120 @@ struct LpLoader {
     }
 };
 
+// Row-contiguous tile loader for 16-bit elements: the operand is stored [k][row] (rows next to each
+// other in memory, `ld` elements between consecutive k), but the MFMA wants 8 consecutive k of one
+// row from every lane.  A thread therefore fetches the same VEC rows of two consecutive k (two
+// loads of VEC * 2 bytes), interleaves them in registers into (k, k+1) pairs and stores those: LDS
+// holds [k pair][row] as 4-byte pairs, and a lane's 8 k of a 16-k group are four 4-byte reads, the
+// lanes of a wavefront on consecutive banks.  The k order inside a group is the same as the
+// K-contiguous loader's, so the two kinds can be mixed in one MFMA.
+template <int ROWS, int BK, int NT, int NSETS, int VEC>
+struct LpRowLoader {
+    static constexpr int CPR = ROWS / VEC;                 // chunks of VEC rows per k
+    static constexpr int KPP = NT / CPR;                   // k pairs per pass
+    static constexpr int NTASK = (BK / 2) / KPP;           // (chunk, k pair) tasks per thread and K step
+    // pairs of one k pair row; (ROWS + 8) * 4 = 32 mod 64 dwords, so the two lane halves of a
+    // fragment read (4 k pairs apart) use disjoint banks
+    static constexpr int LDP = (ROWS + 8) * 4;             // bytes per k pair
+    static constexpr int LDS_BYTES = (BK / 2) * LDP;
+    static_assert(VEC == 8 || VEC == 4, "chunks of 16 or 8 bytes");
+    static_assert(NT % CPR == 0 && (BK / 2) % KPP == 0 && NTASK >= 1, "tile/loader mismatch");
+    typedef uint32_t chunk_t __attribute__((ext_vector_type(VEC / 2)));
+
+    chunk_t reg[NSETS][NTASK][2];          // [k, k+1] of each task
+    const uint16_t* base;                  // column 0 of the tile (its first image), k = 0
+    uint32_t vbase;                        // byte offset of (this thread's first k pair, its chunk), or OOB
+    int k_first, dst0;                     // first k of that pair; where its (k, k+1) pairs go in an LDS buffer
+    int K, ld;
+
+    __device__ inline void init(const uint16_t* p, int64_t ld_, int first_col, int cols_total, int K_,
+                                const ContractionParams& cp) {
+        K = K_; ld = (int)ld_;
+        const int chunk = threadIdx.x % CPR, kp0 = threadIdx.x / CPR;
+        k_first = 2 * kp0;
+        dst0 = kp0 * LDP + chunk * VEC * 4;
+        const int j = first_col + chunk * VEC;
+        const bool ok = j < cols_total;                    // chunks never straddle the end: cols_total % VEC == 0
+        int col_off = chunk * VEC;
+        base = p + first_col;
+        if (cp.col_images) {                               // column j is pixel j % P of image j / P
+            uint32_t n0, p0, n, px;
+            cp.colP.divmod((uint32_t)first_col, n0, p0);
+            cp.colP.divmod((uint32_t)(ok ? j : first_col), n, px);
+            n0 = (uint32_t)scalar((int)n0);
+            base = p + (int64_t)n0 * cp.b_img;
+            col_off = (int)(n - n0) * (int)cp.b_img + (int)px;
+        }
+        vbase = ok ? (uint32_t)(col_off + 2 * kp0 * ld) * 2u : OOB;
+    }
+    template <int S>
+    __device__ inline void fetch(int k0) {
+        // the resource is re-based at row k0 so that offsets stay small whatever K is
+        const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(base + (int64_t)k0 * ld), 0, (int)OOB, RSRC_FLAGS);
+#pragma unroll
+        for (int q = 0; q < NTASK; ++q) {
+            const int k = k0 + k_first + 2 * q * KPP;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int off = (int)(k + u < K ? vbase + (uint32_t)(u * ld * 2) : OOB);
+                const int soff = 2 * q * KPP * ld * 2;
+                if constexpr (VEC == 8) reg[S][q][u] = __builtin_bit_cast(chunk_t, __builtin_amdgcn_raw_buffer_load_b128(r, off, soff, 0));
+                else reg[S][q][u] = __builtin_bit_cast(chunk_t, __builtin_amdgcn_raw_buffer_load_b64(r, off, soff, 0));
+            }
+        }
+    }
+    template <int S>
+    __device__ inline void commit(char* lds) const {
+#pragma unroll
+        for (int q = 0; q < NTASK; ++q) {
+            uint32_t out[VEC];
+#pragma unroll
+            for (int j = 0; j < VEC / 2; ++j) {
+                const uint32_t lo = reg[S][q][0][j], hi = reg[S][q][1][j];      // rows 2j, 2j+1 of k and of k+1
+                out[2 * j] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);        // row 2j:   (k, k+1)
+                out[2 * j + 1] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);    // row 2j+1: (k, k+1)
+            }
+            char* dst = lds + dst0 + q * KPP * LDP;
+#pragma unroll
+            for (int j = 0; j < VEC / 4; ++j) {
+                const floatx4 v = {__builtin_bit_cast(float, out[4 * j]), __builtin_bit_cast(float, out[4 * j + 1]),
+                                   __builtin_bit_cast(float, out[4 * j + 2]), __builtin_bit_cast(float, out[4 * j + 3])};
+                *reinterpret_cast<floatx4*>(dst + 16 * j) = v;
+            }
+        }
+    }
+    // the 8 consecutive k this lane feeds for tile-row `row`, 16-k group g, lane half h
+    __device__ static inline floatx4 frag(const char* lds, int row, int g, int h) {
+        floatx4 v;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const float*>(lds + (g * 8 + h * 4 + q) * LDP + row * 4);
+        return v;
+    }
+};
+
 // Stores a tile as 16-bit values: alpha*acc + beta*bias (none / per column / per row / full
-// fp32 matrix), Relu, rounding, 2-byte buffer stores (dropped by the range check outside Y).
-template <int DT, int TM, int TN, int WTM, int WTN>
-__device__ inline void store_tile_lp(const floatx16 (&acc)[TM][TN], const TileWork& w, int wm, int wn, int li, int h,
-                                     const ContractionParams& cp) {
+// fp32 matrix) (+ a 16-bit residual laid out like Y), Relu, rounding, 2-byte buffer stores
+// (dropped by the range check outside Y).  Columns are plain columns of Y, or, for a convolution,
+// (image, pixel) pairs as in store_tile.
+template <int DT, int TM, int TN, int WTM, int WTN, bool HAS_RES>
+__device__ __forceinline__ void store_tile_lp_as(const floatx16 (&acc)[TM][TN], const TileWork& w, int wm, int wn, int li, int h,
+                                        const ContractionParams& cp) {
+    const int64_t zi = w.zslice;
+    int64_t tile_off = (int64_t)w.m0 * cp.y_rs + w.n0;
+    uint32_t img0 = 0, px0 = 0;
+    if (cp.col_images) {
+        cp.colP.divmod((uint32_t)w.n0, img0, px0);
+        tile_off = (int64_t)w.m0 * cp.y_rs + (int64_t)img0 * cp.y_img + px0;
+    }
+    tile_off = scalar(tile_off + zi * cp.y_zs);
+    img0 = (uint32_t)scalar((int)img0);
+    px0 = (uint32_t)scalar((int)px0);
     uint16_t* Y = reinterpret_cast<uint16_t*>(cp.Y);
-    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y + ((int64_t)w.m0 * cp.y_rs + w.n0), 0, (int)OOB, RSRC_FLAGS);
+    const uint16_t* R = reinterpret_cast<const uint16_t*>(cp.residual);
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y + tile_off, 0, (int)OOB, RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(HAS_RES ? R + tile_off : Y + tile_off), 0, (int)OOB, RSRC_FLAGS);
     const int mode = cp.bias ? cp.bias_mode : BIAS_NONE;
+    const float* bias = cp.bias ? cp.bias + zi * cp.bias_zs : nullptr;
     const bool relu = cp.relu != 0;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -101,7 +221,13 @@ __device__ inline void store_tile_lp(const floatx16 (&acc)[TM][TN], const TileWo
         const int col = w.n0 + cl;
         const bool col_ok = col < cp.N;
         const int cj = col_ok ? col : w.n0;
-        const float col_bias = mode == BIAS_COL ? cp.beta * cp.bias[(int64_t)cj * cp.bias_cs] : 0.f;
+        int crel = cl;
+        if (cp.col_images) {
+            uint32_t n, px;
+            cp.colP.divmod((uint32_t)cj, n, px);
+            crel = (int)(n - img0) * (int)cp.y_img + (int)px - (int)px0;
+        }
+        const float col_bias = mode == BIAS_COL ? cp.beta * bias[(int64_t)cj * cp.bias_cs] : 0.f;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -109,38 +235,63 @@ __device__ inline void store_tile_lp(const floatx16 (&acc)[TM][TN], const TileWo
                 const int rl = wm * WTM + i * 32 + 8 * (r / 4) + 4 * h + (r % 4);
                 const int row = w.m0 + rl;
                 const bool ok = col_ok && row < cp.M;
+                const int off = ok ? (rl * (int)cp.y_rs + crel) * 2 : (int)OOB;
                 float add = col_bias;
-                if (mode == BIAS_ROW) add = cp.beta * cp.bias[ok ? row : 0];
-                if (mode == BIAS_FULL) add = cp.beta * cp.bias[ok ? (int64_t)row * cp.N + col : 0];
+                if (mode == BIAS_ROW) add = cp.beta * bias[ok ? row : 0];
+                if (mode == BIAS_FULL) add = cp.beta * bias[ok ? (int64_t)row * cp.N + col : 0];
+                if constexpr (HAS_RES) {
+                    const uint16_t rv = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rr, off, 0, 0);
+                    add += DT == LP_F16 ? (float)__builtin_bit_cast(_Float16, rv) : __builtin_bit_cast(float, (uint32_t)rv << 16);
+                }
                 const float lin = fmaf(cp.alpha, acc[i][j][r], add);
                 const float v = relu ? fmaxf(lin, 0.f) : lin;      // no clamp without Relu: a NaN stays a NaN
-                __builtin_amdgcn_raw_buffer_store_b16((short)to_lp<DT>(v), ry, ok ? (rl * (int)cp.y_rs + cl) * 2 : (int)OOB, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b16((short)to_lp<DT>(v), ry, off, 0, 0);
             }
+            // one accumulator block at a time: with up to 8 blocks live, loads hoisted across blocks spill
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int DT, bool LP_OUT, int PF>
+template <int DT, int TM, int TN, int WTM, int WTN>
+__device__ __forceinline__ void store_tile_lp(const floatx16 (&acc)[TM][TN], const TileWork& w, int wm, int wn, int li, int h,
+                                     const ContractionParams& cp) {
+    // two copies of the epilogue rather than a test per element; both must be inlined: a call would
+    // pass the accumulators through memory
+    if (cp.residual) store_tile_lp_as<DT, TM, TN, WTM, WTN, true>(acc, w, wm, wn, li, h, cp);
+    else store_tile_lp_as<DT, TM, TN, WTM, WTN, false>(acc, w, wm, wn, li, h, cp);
+}
+
+// BKIND: LOAD_KC (B stored [N][K], 16-byte chunks of 8 k) or LOAD_RC (B stored [K][N], chunks of
+// BVEC columns).
+template <int BM, int BN, int BK, int WM, int WN, int DT, bool LP_OUT, int PF, int BKIND, int BVEC>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_lp_kernel(const ContractionParams cp) {
     constexpr int NT = 64 * WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int G = BK / 16;                       // 16-k groups per K step
     static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0 && BK % 32 == 0, "tile shape");
+    static_assert(BKIND == LOAD_KC || BKIND == LOAD_RC, "B is K-contiguous or row-contiguous");
     using ALoader = LpLoader<BM, BK, NT, PF>;
-    using BLoader = LpLoader<BN, BK, NT, PF>;
+    using BLoader = std::conditional_t<BKIND == LOAD_KC, LpLoader<BN, BK, NT, PF>, LpRowLoader<BN, BK, NT, PF, BVEC>>;
 
     __shared__ __attribute__((aligned(16))) char lds_a[2][ALoader::LDS_BYTES];
     __shared__ __attribute__((aligned(16))) char lds_b[2][BLoader::LDS_BYTES];
 
     TileWork w;
     if (!tile_work(cp, BM, BN, w)) return;
+    w.m0 = scalar(w.m0); w.n0 = scalar(w.n0); w.zslice = scalar(w.zslice);
     const int m0 = w.m0, n0 = w.n0;
+    int64_t a_off, b_off;
+    slice_offsets(cp, w.zslice, a_off, b_off);
+    a_off = scalar(a_off);
+    b_off = scalar(b_off);
 
     ALoader la;
     BLoader lb;
-    la.init(reinterpret_cast<const uint16_t*>(cp.A), cp.a_ld, m0, cp.M, cp.K);
-    lb.init(reinterpret_cast<const uint16_t*>(cp.B), cp.b_ld, n0, cp.N, cp.K);
+    la.init(reinterpret_cast<const uint16_t*>(cp.A) + a_off, cp.a_ld, m0, cp.M, cp.K);
+    if constexpr (BKIND == LOAD_KC) lb.init(reinterpret_cast<const uint16_t*>(cp.B) + b_off, cp.b_ld, n0, cp.N, cp.K);
+    else lb.init(reinterpret_cast<const uint16_t*>(cp.B) + b_off, cp.b_ld, n0, cp.N, cp.K, cp);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -156,6 +307,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_lp_kernel(const Contraction
 
     int kt0, kt1;
     split_range((cp.K + BK - 1) / BK, w.ksplit, w.split, kt0, kt1);
+    kt0 = scalar(kt0); kt1 = scalar(kt1);
 
     floatx4 fa[2][TM], fb[2][TN];                    // fragments of two groups: one in use, one arriving
     auto frags = [&](int f, int buf, int g) {
@@ -170,7 +322,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_lp_kernel(const Contraction
 #pragma unroll
             for (int j = 0; j < TN; ++j) acc[i][j] = mfma16<DT>(fa[f][i], fb[f][j], acc[i][j]);
     };
-    constexpr int NREAD = TM + TN, NMFMA = TM * TN;
+    constexpr int NREAD = TM + TN * (BKIND == LOAD_KC ? 1 : 4), NMFMA = TM * TN;
     constexpr int HALF = TM > 1 ? TM / 2 : 1;        // rows of accumulator blocks issued before the barrier
 
     // One K step (see contraction.h): loads PF steps ahead issued first; groups 0 .. G-2 with the
@@ -218,7 +370,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_lp_kernel(const Contraction
         if (kt + 1 < kt1) step(kt + 1, Par1{});
     }
 
-    if (LP_OUT && w.ksplit == 1) store_tile_lp<DT, TM, TN, WTM, WTN>(acc, w, wm, wn, li, h, cp);
+    // (the launcher never splits K for this kernel, so a 16-bit result has no partial-sum form)
+    if constexpr (LP_OUT) store_tile_lp<DT, TM, TN, WTM, WTN>(acc, w, wm, wn, li, h, cp);
     else finish_tile<TM, TN, WTM, WTN, NT>(acc, w, wm, wn, li, h, cp);
 }
 

@@ -12,39 +12,86 @@ namespace {
 
 #define fail(st, ...) static_cast<onnx_status>(fail_with((st), __VA_ARGS__))
 
-template <int BM, int BN, int BK, int WM, int WN, int DT, bool LP_OUT, int PF>
-hipError_t launch_instance(ContractionParams& p, hipStream_t stream) {
+template <int BM, int BN, int BK, int WM, int WN, int DT, bool LP_OUT, int PF, int BKIND, int BVEC>
+hipError_t launch_instance(ContractionParams& p, int nz, hipStream_t stream) {
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
-    p.nz = 1;
+    p.nz = nz;
     p.ksplit = 1;                                    // every tile walks its whole K range
     p.ws_partial = nullptr;
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
-    if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    const unsigned gz = nz < 32768 ? (unsigned)nz : 32768u;
+    const unsigned gy = ((unsigned)nz + gz - 1) / gz;
+    if (tiles > 0x7fffffffLL || gy > 65535u) return hipErrorInvalidValue;
     p.tail_begin = (int)tiles;
     p.tail_split = 1;
-    hipLaunchKernelGGL((gemm_lp_kernel<BM, BN, BK, WM, WN, DT, LP_OUT, PF>), dim3((unsigned)tiles, 1, 1), dim3(64 * WM * WN), 0,
-                       stream, p);
-    record_launch(LaunchRecord{"gemm_lp", BM, BN, BK, WM, WN, 1, LOAD_KC, LOAD_KC, 8, 8, DT + (LP_OUT ? 2 : 0), 1, 0, 1});
+    hipLaunchKernelGGL((gemm_lp_kernel<BM, BN, BK, WM, WN, DT, LP_OUT, PF, BKIND, BVEC>), dim3((unsigned)tiles, gy, gz),
+                       dim3(64 * WM * WN), 0, stream, p);
+    record_launch(LaunchRecord{"gemm_lp", BM, BN, BK, WM, WN, 1, LOAD_KC, BKIND, 8, BVEC, DT + (LP_OUT ? 2 : 0), 1, 0, 1});
     return hipGetLastError();
 }
 
 // Tile by the same estimate as the fp32 kernel: workgroups per CU x tile area / efficiency.
-template <int DT, bool LP_OUT>
-hipError_t launch_tile(ContractionParams& p, hipStream_t stream) {
+template <int DT, bool LP_OUT, int BKIND, int BVEC>
+hipError_t launch_tile(ContractionParams& p, int nz, hipStream_t stream) {
     const double cus = 256.0;
-    const double t256 = (double)((p.M + 255) / 256) * (double)((p.N + 255) / 256);
-    const double t128 = (double)((p.M + 127) / 128) * (double)((p.N + 127) / 128);
+    const double t256 = (double)((p.M + 255) / 256) * (double)((p.N + 255) / 256) * nz;
+    const double t128 = (double)((p.M + 127) / 128) * (double)((p.N + 127) / 128) * nz;
     const double c256 = (double)(int64_t)((t256 + cus - 1) / cus) * 65536.0 / 1.0;
     const double c128 = (t128 / cus < 1.0 ? 1.0 : t128 / cus) * 16384.0 / 0.85;
-    if (c256 <= c128) return launch_instance<256, 256, 64, 2, 4, DT, LP_OUT, 2>(p, stream);
+    if (c256 <= c128) return launch_instance<256, 256, 64, 2, 4, DT, LP_OUT, 2, BKIND, BVEC>(p, nz, stream);
     // fewer 128 x 128 tiles than half the CUs: 64 x 64 tiles spread the product over the chip (measured
     // 1024^3: 213 vs 121 TFLOP/s; from 2048^3 on the larger tile wins)
-    if (t128 < cus / 2) return launch_instance<64, 64, 64, 2, 2, DT, LP_OUT, 2>(p, stream);
-    return launch_instance<128, 128, 64, 2, 2, DT, LP_OUT, 1>(p, stream);
+    if (t128 < cus / 2) return launch_instance<64, 64, 64, 2, 2, DT, LP_OUT, 2, BKIND, BVEC>(p, nz, stream);
+    return launch_instance<128, 128, 64, 2, 2, DT, LP_OUT, 1, BKIND, BVEC>(p, nz, stream);
+}
+
+template <int BKIND, int BVEC>
+hipError_t launch_types(ContractionParams& p, int nz, int in_type, int out_type, hipStream_t s) {
+    if (in_type == LP_F16) return out_type == 0 ? launch_tile<LP_F16, false, BKIND, BVEC>(p, nz, s) : launch_tile<LP_F16, true, BKIND, BVEC>(p, nz, s);
+    return out_type == 0 ? launch_tile<LP_BF16, false, BKIND, BVEC>(p, nz, s) : launch_tile<LP_BF16, true, BKIND, BVEC>(p, nz, s);
+}
+
+bool multiple_of(const int64_t* v, int n, int64_t m) {
+    for (int i = 0; i < n; ++i)
+        if (v[i] % m) return false;
+    return true;
 }
 
 }  // namespace
+
+namespace onnxhip {
+
+int lp_tuned_fits(const ContractionParams& p, int akind, int bkind, int nz) {
+    const int64_t span = (1LL << 31) - 64, rows = 256, bk = 64;
+    if (akind != LOAD_KC || (bkind != LOAD_KC && bkind != LOAD_RC) || nz < 1 || nz > 32768LL * 65535LL) return 0;
+    // A: 16-byte chunks of 8 k, also at the start of every z-slice; 32-bit offsets inside a 256-row tile
+    if (p.K % 8 || p.a_ld % 8 || !aligned16(p.A) || !multiple_of(p.a_bs, p.nbd, 8) || (rows * p.a_ld + p.K) * 2 >= span) return 0;
+    // Y (and a residual laid out like it): 32-bit offsets inside a tile, which for a convolution
+    // spans the images its columns belong to
+    const int64_t P = p.col_images ? (int64_t)p.colP.d : 0;
+    const int64_t tile_images = p.col_images ? (rows + P - 1) / P + 1 : 0;
+    if ((rows * p.y_rs + (p.col_images ? tile_images * p.y_img : rows)) * 4 >= span) return 0;
+    if (bkind == LOAD_KC)
+        return (p.b_ld % 8 == 0 && aligned16(p.B) && multiple_of(p.b_bs, p.nbd, 8) && (rows * p.b_ld + p.K) * 2 < span) ? 8 : 0;
+    // B row-contiguous: chunks of 8 or 4 columns that never straddle the end of a k row or of an image
+    if ((bk * p.b_ld + (p.col_images ? tile_images * p.b_img : rows)) * 2 >= span) return 0;
+    for (int vec = 8; vec >= 4; vec /= 2) {
+        const bool ok = p.N % vec == 0 && p.b_ld % vec == 0 && (reinterpret_cast<uintptr_t>(p.B) % (2 * vec)) == 0 &&
+                        multiple_of(p.b_bs, p.nbd, vec) && (!p.col_images || (P % vec == 0 && p.b_img % vec == 0));
+        if (ok) return vec;
+    }
+    return 0;
+}
+
+hipError_t launch_lp_tuned(ContractionParams& p, int bkind, int bvec, int nz, int in_type, int out_type, hipStream_t stream) {
+    if (bkind == LOAD_KC) return launch_types<LOAD_KC, 8>(p, nz, in_type, out_type, stream);
+    if (bvec == 8) return launch_types<LOAD_RC, 8>(p, nz, in_type, out_type, stream);
+    if (bvec == 4) return launch_types<LOAD_RC, 4>(p, nz, in_type, out_type, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace onnxhip
 
 extern "C" {
 
@@ -83,11 +130,6 @@ onnx_status onnx_gemm_lp(const void* A, const int64_t a_dims[2], const void* B, 
     if (overlaps(Y, M * N * ysz, A, M * K * 2) || overlaps(Y, M * N * ysz, B, K * N * 2) || overlaps(Y, M * N * ysz, C, nc * 4))
         return fail(ONNX_ERR_ALIAS, "gemm_lp: Y overlaps an input");
     if (M > 0x7fffffffLL || N > 0x7fffffffLL || K > 0x7fffffffLL) return fail(ONNX_ERR_UNSUPPORTED, "gemm_lp: extent above 2^31-1");
-    // the tuned kernel: both operands K-contiguous, 16-byte loads of 8 values, 32-bit tile offsets
-    // (256 rows of an operand or of Y span less than 2^31 bytes); everything else: the general kernel
-    const bool fast = transA == 0 && transB == 1 && K % 8 == 0 && aligned16(A) && aligned16(B) &&
-                      (256 * K + K) * 2 < (1LL << 31) - 64 && (256 * N + N) * 4 < (1LL << 31) - 64;
-
     ContractionParams p;
     memset(&p, 0, sizeof(p));
     for (int i = 0; i < MAX_BATCH_DIMS; ++i) p.bdim[i] = 1;
@@ -104,11 +146,11 @@ onnx_status onnx_gemm_lp(const void* A, const int64_t a_dims[2], const void* B, 
     p.bias_mode = (crs != 0 && ccs != 0) ? BIAS_FULL : (crs != 0 ? BIAS_ROW : BIAS_COL);
     p.bias_cs = (int)ccs;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e;
-    if (!fast)
-        e = launch_lp_generic(p, transA ? LOAD_RC : LOAD_KC, transB ? LOAD_KC : LOAD_RC, 1, (int)in_type, (int)out_type, s);
-    else if (in_type == ONNX_F16) e = out_type == ONNX_F32 ? launch_tile<LP_F16, false>(p, s) : launch_tile<LP_F16, true>(p, s);
-    else e = out_type == ONNX_F32 ? launch_tile<LP_BF16, false>(p, s) : launch_tile<LP_BF16, true>(p, s);
+    // the tuned kernel: A K-contiguous, 16-byte loads, 32-bit tile offsets; everything else: the general kernel
+    const int akind = transA ? LOAD_RC : LOAD_KC, bkind = transB ? LOAD_KC : LOAD_RC;
+    const int bvec = lp_tuned_fits(p, akind, bkind, 1);
+    const hipError_t e = bvec ? launch_lp_tuned(p, bkind, bvec, 1, (int)in_type, (int)out_type, s)
+                              : launch_lp_generic(p, akind, bkind, 1, (int)in_type, (int)out_type, s);
     if (e != hipSuccess) return fail(ONNX_ERR_DEVICE, "gemm_lp: %s", hipGetErrorString(e));
     return ONNX_OK;
 }

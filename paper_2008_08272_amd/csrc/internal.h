@@ -74,6 +74,14 @@ hipError_t launch_contraction(ContractionParams& p, int akind, int bkind, int av
 hipError_t launch_lp_generic(ContractionParams& p, int akind, int bkind, int nz, int in_type, int out_type,
                              hipStream_t stream);
 
+// The tuned 16-bit kernel (gemm_lp.h): A K-contiguous, B K-contiguous or row-contiguous, wide
+// loads.  lp_tuned_fits returns 0 when `p` (filled as for launch_lp_generic) does not meet its
+// alignment and 32-bit-offset conditions, else the chunk width for B (8, or 4 for a
+// row-contiguous B whose rows are only 8-byte aligned) to pass on to launch_lp_tuned.
+int lp_tuned_fits(const ContractionParams& p, int akind, int bkind, int nz);
+hipError_t launch_lp_tuned(ContractionParams& p, int bkind, int bvec, int nz, int in_type, int out_type,
+                           hipStream_t stream);
+
 // Convolution through an LDS-resident input patch (conv_window.h).  `p` must be filled as for
 // the IM2COL contraction (A = filters, B = input, ic geometry, K = Cg*kH*kW).  Returns false
 // when no instance fits this shape (the caller then uses the generic path); otherwise

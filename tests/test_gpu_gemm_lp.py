@@ -97,6 +97,34 @@ def test_gemm_16bit_full_size_whole_output(lib, n, kind):
     g = got.cpu().numpy()
     assert rel_err(g, ref) <= REL_TOL
     assert within_rounding_bound(g, ref, S, n + 2)
+    # the same launch with the result stored in the inputs' type
+    got2 = lp_to_host(lib.onnx_gemm_lp(A, B, C), kind)
+    assert lib.onnx_last_launch().startswith(want), lib.onnx_last_launch()
+    u = 2.0 ** -PRECISION[kind]
+    assert (np.abs(got2 - ref) <= u * np.abs(ref) + (n + 5) * 2.0 ** -24 * (S + 2.0) + 1e-7).all()
+
+
+@pytest.mark.parametrize("kind", ["bf16", "f16"])
+def test_matmul_16bit_large_whole_output(lib, kind):
+    """B stored [K][N]: the 256 x 256 and 128 x 128 tiles with the row-contiguous loader in chunks of 8 and
+    of 4 columns, every output element compared (4096 x 768 x 3072 is the shape the benchmark times)."""
+    for (M, K, N, want, chunk) in ((4096, 512, 4096, "gemm_lp 256x256x64", 8), (4096, 768, 3072, "gemm_lp 128x128x64", 8),
+                                   (4096, 136, 3844, "gemm_lp 256x256x64", 4), (2048, 136, 2052, "gemm_lp 128x128x64", 4)):
+        announce("matmul_lp large", kind, M, K, N)
+        rng = np.random.default_rng([M, K, N])
+        ab, av = encode(rng.uniform(-1, 1, (M, K)).astype(np.float32), kind)
+        bb, bv = encode(rng.uniform(-1, 1, (K, N)).astype(np.float32), kind)
+        got = lib.onnx_matmul_lp(bits_to_dev(ab, kind), bits_to_dev(bb, kind), out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        launch = lib.onnx_last_launch()
+        assert launch.startswith(want) and "B=RC/%d" % chunk in launch, launch
+        ref, S = oracle.matmul(av, bv, want_scale=True)
+        g = got.cpu().numpy()
+        assert rel_err(g, ref) <= REL_TOL
+        assert within_rounding_bound(g, ref, S, K + 2)
+        got2 = lp_to_host(lib.onnx_matmul_lp(bits_to_dev(ab, kind), bits_to_dev(bb, kind)), kind)
+        u = 2.0 ** -PRECISION[kind]
+        assert (np.abs(got2 - ref) <= u * np.abs(ref) + (K + 5) * 2.0 ** -24 * (S + 1.0) + 1e-7).all()
 
 
 def encode(x, kind):
@@ -110,10 +138,12 @@ def encode(x, kind):
 
 @pytest.mark.parametrize("kind", ["f16", "bf16"])
 @pytest.mark.parametrize("transA,transB", [(0, 0), (1, 0), (1, 1), (0, 1)])
-@pytest.mark.parametrize("M,N,K", [(70, 90, 50), (130, 257, 129), (64, 64, 32), (300, 200, 7), (1, 1, 1)])
+@pytest.mark.parametrize("M,N,K", [(70, 90, 50), (130, 257, 129), (64, 64, 32), (300, 200, 7), (1, 1, 1), (130, 264, 136),
+                                   (70, 92, 48), (257, 200, 64)])
 def test_gemm_16bit_every_layout_and_ragged_k(lib, M, N, K, transA, transB, kind):
-    """Layouts and K the tuned kernel does not take go through the general kernel (so does
-    transA = 0 / transB = 1 when K is not a multiple of 8)."""
+    """The tuned kernel takes transA = 0 with K a multiple of 8 and B either K-contiguous (transB = 1)
+    or row-contiguous with N a multiple of 4 (chunks of 8 columns when N is a multiple of 8, else
+    of 4); every other layout, K and N goes through the general kernel."""
     announce("gemm_lp layouts", kind, M, N, K, transA, transB)
     rng = np.random.default_rng([M, N, K, transA, transB])
     ab, av = encode(rng.uniform(-1, 1, (K, M) if transA else (M, K)).astype(np.float32), kind)
@@ -124,8 +154,11 @@ def test_gemm_16bit_every_layout_and_ragged_k(lib, M, N, K, transA, transB, kind
     got = lib.onnx_gemm_lp(bits_to_dev(ab, kind), bits_to_dev(bb, kind), torch.from_numpy(C).cuda(), alpha=0.75, beta=-1.25,
                            transA=transA, transB=transB, out_dtype=torch.float32)
     torch.cuda.synchronize()
-    fast = transA == 0 and transB == 1 and K % 8 == 0
-    assert lib.onnx_last_launch().startswith("gemm_lp" if fast else "lp_generic"), lib.onnx_last_launch()
+    fast = transA == 0 and K % 8 == 0 and (transB == 1 or N % 4 == 0)
+    launch = lib.onnx_last_launch()
+    assert launch.startswith("gemm_lp" if fast else "lp_generic"), launch
+    if fast:
+        assert ("B=KC/8" if transB else "B=RC/%d" % (8 if N % 8 == 0 else 4)) in launch, launch
     g = got.cpu().numpy()
     assert rel_err(g, ref) <= REL_TOL
     assert within_rounding_bound(g, ref, S, K + 2)
@@ -139,7 +172,8 @@ def test_gemm_16bit_every_layout_and_ragged_k(lib, M, N, K, transA, transB, kind
 
 @pytest.mark.parametrize("kind", ["f16", "bf16"])
 @pytest.mark.parametrize("sa,sb", [((5, 4), (4, 6)), ((3, 2, 50, 40), (2, 40, 60)), ((2, 70, 33), (3, 1, 33, 65)), ((40,), (40, 6)),
-                                   ((50, 40), (40,)), ((2, 3, 130, 36), (36, 200)), ((8, 12, 128, 64), (8, 12, 64, 128))])
+                                   ((50, 40), (40,)), ((2, 3, 130, 36), (36, 200)), ((8, 12, 128, 64), (8, 12, 64, 128)),
+                                   ((4, 130, 72), (72, 264)), ((2, 3, 100, 64), (3, 64, 136)), ((2, 300, 48), (2, 48, 140))])
 def test_matmul_16bit_matches_oracle(lib, sa, sb, kind):
     announce("matmul_lp", kind, sa, sb)
     rng = np.random.default_rng(len(sa) * 100 + len(sb))
@@ -148,7 +182,13 @@ def test_matmul_16bit_matches_oracle(lib, sa, sb, kind):
     ref, S = oracle.matmul(av, bv, want_scale=True)
     got = lib.onnx_matmul_lp(bits_to_dev(ab, kind), bits_to_dev(bb, kind), out_dtype=torch.float32)
     torch.cuda.synchronize()
-    assert lib.onnx_last_launch().startswith("lp_generic"), lib.onnx_last_launch()
+    # the tuned kernel takes K a multiple of 8 with N a multiple of 4 (batch entries then start aligned)
+    n_cols = sb[-1] if len(sb) > 1 else 1
+    fast = len(sa) > 1 and sa[-1] % 8 == 0 and n_cols % 4 == 0
+    launch = lib.onnx_last_launch()
+    assert launch.startswith("gemm_lp" if fast else "lp_generic"), launch
+    if fast:
+        assert "B=RC/%d" % (8 if n_cols % 8 == 0 else 4) in launch, launch
     g = got.cpu().numpy()
     assert g.shape == ref.shape
     assert rel_err(g, ref) <= REL_TOL
@@ -163,8 +203,12 @@ CONV_LP_CASES = [
     (2, 16, 19, 23, 40, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 1),
     (2, 3, 37, 41, 64, 7, 7, (3, 3, 3, 3), (2, 2), (1, 1), 1),
     (2, 32, 20, 20, 48, 3, 3, (2, 0, 1, 3), (2, 3), (2, 1), 2),
-    (2, 64, 12, 12, 96, 1, 1, (0, 0, 0, 0), (1, 1), (1, 1), 1),          # pointwise: row-contiguous input
-    (2, 64, 9, 7, 96, 1, 1, (0, 0, 0, 0), (1, 1), (1, 1), 1),            # pointwise, 63 positions per image
+    (2, 64, 12, 12, 96, 1, 1, (0, 0, 0, 0), (1, 1), (1, 1), 1),          # pointwise: row-contiguous input, chunks of 8 positions
+    (2, 64, 9, 7, 96, 1, 1, (0, 0, 0, 0), (1, 1), (1, 1), 1),            # pointwise, 63 positions per image: general kernel
+    (5, 72, 14, 14, 200, 1, 1, (0, 0, 0, 0), (1, 1), (1, 1), 1),         # pointwise, 196 positions: chunks of 4, tiles span images
+    (3, 64, 12, 12, 96, 1, 1, (0, 0, 0, 0), (1, 1), (1, 1), 2),          # pointwise with two groups
+    (2, 36, 12, 12, 96, 1, 1, (0, 0, 0, 0), (1, 1), (1, 1), 1),          # pointwise, K = 36: general kernel
+    (8, 64, 28, 28, 512, 1, 1, (0, 0, 0, 0), (1, 1), (1, 1), 1),         # pointwise, 196 tiles of 128 x 128
     (2, 64, 12, 12, 96, 1, 1, (0, 0, 0, 0), (2, 2), (1, 1), 1),          # strided 1x1
     (4, 6, 10, 10, 6, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 6),            # depthwise
     (1, 1, 28, 28, 8, 5, 5, (2, 2, 2, 2), (1, 1), (1, 1), 1),
@@ -186,7 +230,12 @@ def test_conv_16bit_matches_oracle(lib, case, kind):
     X, Wt = bits_to_dev(xb, kind), bits_to_dev(wb, kind)
     got = lib.onnx_conv_lp(X, Wt, torch.from_numpy(Bv).cuda(), pads, st, dl, g, out_dtype=torch.float32)
     torch.cuda.synchronize()
-    assert lib.onnx_last_launch().startswith("lp_generic"), lib.onnx_last_launch()
+    # 1x1, stride 1, no padding, K a multiple of 8 and 4 | H*W: the tuned kernel on the input as a [C][H*W] matrix
+    fast = kH == 1 and kW == 1 and st == (1, 1) and pads == (0, 0, 0, 0) and K % 8 == 0 and (H * W) % 4 == 0
+    launch = lib.onnx_last_launch()
+    assert launch.startswith("gemm_lp" if fast else "lp_generic"), launch
+    if fast:
+        assert "B=RC/%d" % (8 if (H * W) % 8 == 0 else 4) in launch, launch
     gth = got.cpu().numpy()
     assert gth.shape == ref.shape
     assert rel_err(gth, ref) <= REL_TOL
