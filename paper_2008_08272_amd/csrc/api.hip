@@ -184,8 +184,9 @@ onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const f
     g.dH = (int)dilations[0]; g.dW = (int)dilations[1];
 
     if (in_type != ONNX_F32) {
-        // 16-bit tensors: one general kernel; the pointwise case reads the input as a row-contiguous
-        // matrix per image, everything else gathers it
+        // 16-bit tensors: the pointwise case reads the input as a row-contiguous [C][H*W] matrix per
+        // image (through the tuned kernel when its alignment conditions hold), everything else
+        // gathers it element by element in the general kernel
         if (NP > kIntMax || group > 32768LL * 65535LL)
             return fail(ONNX_ERR_UNSUPPORTED, "conv (16-bit): more than 2^31-1 output positions");
         ContractionParams p;

@@ -1,5 +1,8 @@
-// Contractions on 16-bit inputs in any operand layout: the kernel behind onnx_matmul_lp,
-// onnx_conv_lp and the layouts of onnx_gemm_lp that its K-contiguous fast kernel does not take.
+// Contractions on 16-bit inputs in any operand layout: the kernel behind the cases of onnx_gemm_lp,
+// onnx_matmul_lp and onnx_conv_lp that the tuned kernel (gemm_lp.h) does not take: a transposed A,
+// K not a multiple of 8, rows of a row-contiguous B that are not a multiple of 4 long, unaligned
+// operands, and every convolution whose input has to be gathered (anything but 1x1 / stride 1 /
+// no padding).
 // The paper's operator definitions admit 16-bit floating-point tensors (Section 3.1); Conv,
 // MatMul and Gemm keep their ONNX semantics, products are exact in fp32 and summed in fp32
 // accumulators (v_mfma_f32_32x32x16_{f16,bf16}).
@@ -11,7 +14,7 @@
 // memory (rows for a row-contiguous operand and for the gathered convolution input, k
 // otherwise) and stores them into LDS as [row][k], where a lane's 8 k are one 16-byte read.
 // Tile 64 x 64 x 32, four wavefronts of 32 x 32, one LDS buffer, no split-K: a plain, general
-// path; the tuned one is gemm_lp.h.
+// path.
 #include "gemm_lp.h"
 #include "internal.h"
 
