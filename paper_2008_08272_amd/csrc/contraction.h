@@ -320,12 +320,13 @@ struct EpilogueSrc {
     bool relu;
 };
 
-template <bool GUARD>
+// C0, C1: the groups of four accumulator registers (eight rows apart) to store, all four by default.
+template <bool GUARD, int C0 = 0, int C1 = 4>
 __device__ inline void store_block(const floatx16& acc, int row0, float col_bias, uint32_t voff,
                                    const EpilogueSrc& e, const ContractionParams& cp) {
     const int row_stride_bytes = (int)cp.y_rs * 4;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int c = C0; c < C1; ++c) {
         float add[4];
         uint32_t off[4];
         // four consecutive rows: one 16-byte load fetches their per-row bias
@@ -426,7 +427,7 @@ __device__ inline void slice_offsets(const ContractionParams& cp, int zslice, in
 }
 
 // Epilogue of a workgroup tile whose wavefront (wm, wn) holds TM x TN accumulator blocks.
-template <int TM, int TN, int WTM, int WTN>
+template <int TM, int TN, int WTM, int WTN, int C0 = 0, int C1 = 4>
 __device__ inline void store_tile(const floatx16 (&acc)[TM][TN], int m0, int n0, int zslice, int wm, int wn,
                                   int li, int h, const ContractionParams& cp) {
     const int64_t zi = zslice;
@@ -469,8 +470,8 @@ __device__ inline void store_tile(const floatx16 (&acc)[TM][TN], int m0, int n0,
             const int rl = wm * WTM + i * 32 + 4 * h;     // row within the tile of register 0
             const uint32_t voff = col_ok ? (uint32_t)(rl * (int)cp.y_rs + crel) * 4u : OOB;
             // the 32 rows of this block all exist unless the block reaches past M (uniform test)
-            if (m0 + wm * WTM + i * 32 + 32 <= cp.M) store_block<false>(acc[i][j], m0 + rl, col_bias, voff, e, cp);
-            else store_block<true>(acc[i][j], m0 + rl, col_bias, voff, e, cp);
+            if (m0 + wm * WTM + i * 32 + 32 <= cp.M) store_block<false, C0, C1>(acc[i][j], m0 + rl, col_bias, voff, e, cp);
+            else store_block<true, C0, C1>(acc[i][j], m0 + rl, col_bias, voff, e, cp);
         }
     }
 }
@@ -506,32 +507,23 @@ __device__ inline void finish_tile(floatx16 (&acc)[TM][TN], const TileWork& w, i
     store_tile<TM, TN, WTM, WTN>(acc, w.m0, w.n0, w.zslice, wm, wn, li, h, cp);
 }
 
-// Second half of a split-K product: one workgroup per tile, same thread-to-accumulator
-// mapping as the kernel that produced the partials.  tail = false: all tiles of a launch
-// with ksplit > 1; tail = true: only the tail tiles of a launch with a tail split.
-template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(64 * WM * WN) void splitk_finish_kernel(const ContractionParams cp, const bool tail) {
-    constexpr int NT = 64 * WM * WN;
-    constexpr int WTM = BM / WM, WTN = BN / WN;
-    constexpr int TM = WTM / 32, TN = WTN / 32;
+// Second half of a split-K product: same thread-to-accumulator mapping as the kernel that
+// produced the partials.  tail = false: all tiles of a launch with ksplit > 1; tail = true: only
+// the tail tiles of a launch with a tail split.  SL = 1: one workgroup per tile.  SL = 4: four
+// workgroups per tile, each adding and storing one group of four accumulator registers per
+// 32 x 32 block (launches with few tiles: a workgroup then waits for a quarter of the partial
+// sums, all of its loads in flight at once, and four times as many CUs pull them in).
+//
+// The partial tiles come from other XCDs, i.e. from memory: their latency, not their volume, is
+// what this kernel waits for.  AHEAD shares are fetched at a time, every load issued before the
+// first add (a share past the last one is an out-of-range offset that returns 0), and added in
+// split order.
+template <int TM, int TN, int WTM, int WTN, int NT, int C0, int C1>
+__device__ inline void finish_registers(const ContractionParams& cp, const __amdgpu_buffer_rsrc_t rp, int ksplit, int m0,
+                                        int n0, int zslice, int wm, int wn, int li, int h) {
     constexpr int TILE = NT * TM * TN * 16;
-    const int zslice = blockIdx.y * gridDim.z + blockIdx.z;
-    if (zslice >= cp.nz) return;
-    const int ntiles = cp.tiles_m * cp.tiles_n;
-    const int ksplit = tail ? cp.tail_split : cp.ksplit;
-    const int logical = tail ? cp.tail_begin + (int)blockIdx.x : xcd_contiguous(blockIdx.x, ntiles);
-    const int64_t first_slot = tail ? (int64_t)blockIdx.x * ksplit : ((int64_t)zslice * ntiles + blockIdx.x) * ksplit;
-    int m0, n0;
-    tile_origin(cp, logical, BM, BN, m0, n0);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave / WN, wn = wave % WN;
-    const int li = lane & 31, h = lane >> 5;
-    // The partial tiles come from other XCDs, i.e. from memory: their latency, not their volume, is
-    // what this kernel waits for.  Four shares are fetched at a time, every load issued before the
-    // first add (a share past the last one is an out-of-range offset that returns 0), and added in
-    // split order.
-    const __amdgpu_buffer_rsrc_t rp = tile_rsrc(cp.ws_partial + first_slot * TILE);
-    constexpr int AHEAD = 4;
+    constexpr int NREG = 4 * (C1 - C0);                               // registers per block this workgroup owns
+    constexpr int AHEAD = 64 / (TM * TN * NREG) >= 16 ? 16 : (64 / (TM * TN * NREG) >= 4 ? 64 / (TM * TN * NREG) : 4);
     floatx16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -540,7 +532,7 @@ __global__ __launch_bounds__(64 * WM * WN) void splitk_finish_kernel(const Contr
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     for (int s0 = 0; s0 < ksplit; s0 += AHEAD) {
-        float v[AHEAD][TM][TN][16];
+        float v[AHEAD][TM][TN][NREG];
 #pragma unroll
         for (int u = 0; u < AHEAD; ++u) {
             const uint32_t share = s0 + u < ksplit ? (uint32_t)threadIdx.x * 4u : OOB;
@@ -549,9 +541,9 @@ __global__ __launch_bounds__(64 * WM * WN) void splitk_finish_kernel(const Contr
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
+                    for (int r = 0; r < NREG; ++r)
                         v[u][i][j][r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                            rp, (int)share, ((s0 + u) * TILE + ((i * TN + j) * 16 + r) * NT) * 4, 0));
+                                            rp, (int)share, ((s0 + u) * TILE + ((i * TN + j) * 16 + 4 * C0 + r) * NT) * 4, 0));
         }
 #pragma unroll
         for (int u = 0; u < AHEAD; ++u)
@@ -560,9 +552,41 @@ __global__ __launch_bounds__(64 * WM * WN) void splitk_finish_kernel(const Contr
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[i][j][r] += v[u][i][j][r];
+                    for (int r = 0; r < NREG; ++r) acc[i][j][4 * C0 + r] += v[u][i][j][r];
     }
-    store_tile<TM, TN, WTM, WTN>(acc, m0, n0, zslice, wm, wn, li, h, cp);
+    store_tile<TM, TN, WTM, WTN, C0, C1>(acc, m0, n0, zslice, wm, wn, li, h, cp);
+}
+
+template <int BM, int BN, int WM, int WN, int SL>
+__global__ __launch_bounds__(64 * WM * WN) void splitk_finish_kernel(const ContractionParams cp, const bool tail) {
+    constexpr int NT = 64 * WM * WN;
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int TILE = NT * TM * TN * 16;
+    static_assert(SL == 1 || SL == 4, "whole blocks or single register groups");
+    const int zslice = blockIdx.y * gridDim.z + blockIdx.z;
+    if (zslice >= cp.nz) return;
+    const int ntiles = cp.tiles_m * cp.tiles_n;
+    const int ksplit = tail ? cp.tail_split : cp.ksplit;
+    const int tile_index = (int)blockIdx.x / SL, part = (int)blockIdx.x % SL;
+    const int logical = tail ? cp.tail_begin + tile_index : xcd_contiguous(tile_index, ntiles);
+    const int64_t first_slot = tail ? (int64_t)tile_index * ksplit : ((int64_t)zslice * ntiles + tile_index) * ksplit;
+    int m0, n0;
+    tile_origin(cp, logical, BM, BN, m0, n0);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int li = lane & 31, h = lane >> 5;
+    const __amdgpu_buffer_rsrc_t rp = tile_rsrc(cp.ws_partial + first_slot * TILE);
+    if constexpr (SL == 1) {
+        finish_registers<TM, TN, WTM, WTN, NT, 0, 4>(cp, rp, ksplit, m0, n0, zslice, wm, wn, li, h);
+    } else {
+        switch (part) {                                  // uniform for the workgroup
+            case 0: finish_registers<TM, TN, WTM, WTN, NT, 0, 1>(cp, rp, ksplit, m0, n0, zslice, wm, wn, li, h); break;
+            case 1: finish_registers<TM, TN, WTM, WTN, NT, 1, 2>(cp, rp, ksplit, m0, n0, zslice, wm, wn, li, h); break;
+            case 2: finish_registers<TM, TN, WTM, WTN, NT, 2, 3>(cp, rp, ksplit, m0, n0, zslice, wm, wn, li, h); break;
+            default: finish_registers<TM, TN, WTM, WTN, NT, 3, 4>(cp, rp, ksplit, m0, n0, zslice, wm, wn, li, h); break;
+        }
+    }
 }
 
 // Tail split for a launch of `tiles` whole tiles that walk `nk` K steps each: how many tiles
@@ -588,6 +612,8 @@ inline TailSplit pick_tail(int64_t tiles, int nk, int64_t tile_elems, const floa
     return t;
 }
 
+constexpr int64_t kFinishSliceTiles = 128;     // up to this many tiles the finishing kernel runs four workgroups per tile
+
 // Host side: enqueue `kernel` for the tiles of `p` and, when K ranges are split, the finishing
 // kernel behind it.  `nk` = K steps a whole tile walks.
 // KS = K slices inside the main kernel's workgroup (it runs 64*WM*WN*KS threads).
@@ -605,13 +631,22 @@ inline hipError_t launch_with_split(Kernel kernel, ContractionParams& p, int nz,
     const unsigned gx = (unsigned)(p.tail_begin + tail.tiles * tail.split);
     hipLaunchKernelGGL(kernel, dim3(gx, gy * (unsigned)p.ksplit, gz), dim3(64 * WM * WN * KS), 0, stream, p);
     hipError_t e = hipGetLastError();
+    // few tiles to finish: four workgroups per tile, a group of accumulator registers each
     if (e == hipSuccess && p.ksplit > 1) {
-        hipLaunchKernelGGL((splitk_finish_kernel<BM, BN, WM, WN>), dim3((unsigned)tiles, gy, gz), dim3(64 * WM * WN), 0,
-                           stream, p, false);
+        if (tiles * nz <= kFinishSliceTiles)
+            hipLaunchKernelGGL((splitk_finish_kernel<BM, BN, WM, WN, 4>), dim3((unsigned)tiles * 4u, gy, gz), dim3(64 * WM * WN),
+                               0, stream, p, false);
+        else
+            hipLaunchKernelGGL((splitk_finish_kernel<BM, BN, WM, WN, 1>), dim3((unsigned)tiles, gy, gz), dim3(64 * WM * WN), 0,
+                               stream, p, false);
         e = hipGetLastError();
     } else if (e == hipSuccess && tail.tiles > 0) {
-        hipLaunchKernelGGL((splitk_finish_kernel<BM, BN, WM, WN>), dim3((unsigned)tail.tiles, 1, 1), dim3(64 * WM * WN),
-                           0, stream, p, true);
+        if (tail.tiles <= kFinishSliceTiles)
+            hipLaunchKernelGGL((splitk_finish_kernel<BM, BN, WM, WN, 4>), dim3((unsigned)tail.tiles * 4u, 1, 1),
+                               dim3(64 * WM * WN), 0, stream, p, true);
+        else
+            hipLaunchKernelGGL((splitk_finish_kernel<BM, BN, WM, WN, 1>), dim3((unsigned)tail.tiles, 1, 1), dim3(64 * WM * WN),
+                               0, stream, p, true);
         e = hipGetLastError();
     }
     return e;
