@@ -198,6 +198,37 @@ def test_matmul_16bit_matches_oracle(lib, sa, sb, kind):
     assert (np.abs(got2 - ref) <= u * np.abs(ref) + (sa[-1] + 5) * 2.0 ** -24 * (S + 1.0) + 1e-7).all()
 
 
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+def test_gemm_16bit_misaligned_operands(lib, kind):
+    """Operands that do not start on a 16-byte boundary: the tuned kernel is taken only as far as its wide
+    loads allow (B [K][N] 8 bytes off: chunks of 4 columns; A or a K-contiguous B off: the general kernel)."""
+    announce("gemm_lp misaligned", kind)
+    M, N, K = 96, 136, 72
+    rng = np.random.default_rng(77)
+    ab, av = encode(rng.uniform(-1, 1, (M, K)).astype(np.float32), kind)
+    b0, b0v = encode(rng.uniform(-1, 1, (K, N)).astype(np.float32), kind)       # transB = 0
+    b1, b1v = encode(rng.uniform(-1, 1, (N, K)).astype(np.float32), kind)       # transB = 1
+
+    def shifted(bits, elems):
+        flat = torch.zeros(bits.size + 16, dtype=torch.int16, device="cuda")
+        flat[elems:elems + bits.size] = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16).ravel()).cuda()
+        t = flat[elems:elems + bits.size].view(bits.shape).view(TORCH_T[kind])
+        assert t.data_ptr() % 16 == (2 * elems) % 16
+        return t
+
+    for a_shift, b_shift, transB, want in ((0, 4, 0, "B=RC/4"), (0, 1, 0, "lp_generic"), (1, 0, 0, "lp_generic"), (0, 4, 1, "lp_generic"),
+                                           (0, 0, 0, "B=RC/8"), (0, 0, 1, "B=KC/8")):
+        A = shifted(ab, a_shift)
+        Bt = shifted(b1 if transB else b0, b_shift)
+        ref, S = oracle.gemm(av, b1v if transB else b0v, None, 1.0, 1.0, 0, transB, relu=False, want_scale=True)
+        got = lib.onnx_gemm_lp(A, Bt, None, transA=0, transB=transB, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        assert want in lib.onnx_last_launch(), (a_shift, b_shift, transB, lib.onnx_last_launch())
+        g = got.cpu().numpy()
+        assert rel_err(g, ref) <= REL_TOL
+        assert within_rounding_bound(g, ref, S, K + 2)
+
+
 CONV_LP_CASES = [
     # N, C, H, W, M, kH, kW, pads, strides, dilations, group
     (2, 16, 19, 23, 40, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 1),
