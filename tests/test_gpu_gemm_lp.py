@@ -229,6 +229,53 @@ def test_gemm_16bit_misaligned_operands(lib, kind):
         assert within_rounding_bound(g, ref, S, K + 2)
 
 
+def test_16bit_tuned_kernel_random_sweep(lib):
+    """Seeded random shapes through the row-contiguous loader of the tuned kernel: MatMul with batch
+    broadcasting and 1x1 convolutions whose tiles span many small images, both types, both output types."""
+    rng = np.random.default_rng(20080827)
+    for it in range(36):
+        kind = ("f16", "bf16")[it % 2]
+        u = 2.0 ** -PRECISION[kind]
+        if it % 3 != 2:
+            M = int(rng.integers(1, 200)); K = 8 * int(rng.integers(1, 30)); N = 4 * int(rng.integers(1, 60))
+            batch = [(), (3,), (2, 2)][int(rng.integers(0, 3))]
+            sa = batch + (M, K)
+            sb = [(K, N), batch + (K, N), batch[-1:] + (K, N)][int(rng.integers(0, 3))]
+            announce("lp sweep matmul", it, kind, sa, sb)
+            ab, av = encode(rng.uniform(-1, 1, sa).astype(np.float32), kind)
+            bb, bv = encode(rng.uniform(-1, 1, sb).astype(np.float32), kind)
+            ref, S = oracle.matmul(av, bv, want_scale=True)
+            got = lib.onnx_matmul_lp(bits_to_dev(ab, kind), bits_to_dev(bb, kind), out_dtype=torch.float32)
+            torch.cuda.synchronize()
+            assert lib.onnx_last_launch().startswith("gemm_lp") and "B=RC/" in lib.onnx_last_launch(), lib.onnx_last_launch()
+            g = got.cpu().numpy()
+            assert g.shape == ref.shape and rel_err(g, ref) <= REL_TOL and within_rounding_bound(g, ref, S, K + 2)
+            got2 = lp_to_host(lib.onnx_matmul_lp(bits_to_dev(ab, kind), bits_to_dev(bb, kind)), kind)
+            assert (np.abs(got2 - ref) <= u * np.abs(ref) + (K + 5) * 2.0 ** -24 * (S + 1.0) + 1e-7).all()
+        else:
+            n = int(rng.integers(1, 40)); g_ = (1, 1, 2, 4)[int(rng.integers(0, 4))]
+            C = 8 * g_ * int(rng.integers(1, 12)); Mo = g_ * int(rng.integers(1, 50))
+            H, W = [(2, 2), (4, 4), (2, 6), (6, 6), (3, 4), (10, 10), (8, 5)][int(rng.integers(0, 7))]
+            announce("lp sweep conv1x1", it, kind, n, C, H, W, Mo, g_)
+            xb, xv = encode(rng.uniform(-1, 1, (n, C, H, W)).astype(np.float32), kind)
+            wb, wv = encode(rng.uniform(-1, 1, (Mo, C // g_, 1, 1)).astype(np.float32), kind)
+            Bv = rng.uniform(-1, 1, (Mo,)).astype(np.float32)
+            rb, rv = encode(rng.uniform(-1, 1, (n, Mo, H, W)).astype(np.float32), kind)
+            z4, o2 = (0, 0, 0, 0), (1, 1)
+            ref, S = oracle.conv(xv, wv, Bv, z4, o2, o2, g_, want_scale=True)
+            X, Wt = bits_to_dev(xb, kind), bits_to_dev(wb, kind)
+            got = lib.onnx_conv_lp(X, Wt, torch.from_numpy(Bv).cuda(), z4, o2, o2, g_, out_dtype=torch.float32)
+            torch.cuda.synchronize()
+            assert lib.onnx_last_launch().startswith("gemm_lp") and "B=RC/" in lib.onnx_last_launch(), lib.onnx_last_launch()
+            gth = got.cpu().numpy()
+            K = C // g_
+            assert rel_err(gth, ref) <= REL_TOL and within_rounding_bound(gth, ref, S, K + 1)
+            ref2, S2 = oracle.conv(xv, wv, Bv, z4, o2, o2, g_, residual=rv, relu=False, want_scale=True)
+            got2 = lp_to_host(lib.onnx_conv_lp(X, Wt, torch.from_numpy(Bv).cuda(), z4, o2, o2, g_, residual=bits_to_dev(rb, kind), act=1), kind)
+            want = np.maximum(ref2, 0)
+            assert (np.abs(got2 - want) <= u * np.abs(want) + (K + 5) * 2.0 ** -24 * (S2 + 1.0) + 1e-7).all()
+
+
 CONV_LP_CASES = [
     # N, C, H, W, M, kH, kW, pads, strides, dilations, group
     (2, 16, 19, 23, 40, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 1),
