@@ -191,13 +191,31 @@ struct LpRowLoader {
     }
 };
 
+// The value a 16-bit storage word denotes.
+template <int DT>
+__device__ inline float from_lp(uint32_t bits16) {
+    return DT == LP_F16 ? (float)__builtin_bit_cast(_Float16, (uint16_t)bits16) : __builtin_bit_cast(float, bits16 << 16);
+}
+
+// What the lane next door (lane ^ 1) holds.
+__device__ inline uint32_t neighbour(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1 /* quad_perm: 1, 0, 3, 2 */, 0xf, 0xf, false);
+}
+
 // Stores a tile as 16-bit values: alpha*acc + beta*bias (none / per column / per row / full
-// fp32 matrix) (+ a 16-bit residual laid out like Y), Relu, rounding, 2-byte buffer stores
-// (dropped by the range check outside Y).  Columns are plain columns of Y, or, for a convolution,
-// (image, pixel) pairs as in store_tile.
-template <int DT, int TM, int TN, int WTM, int WTN, bool HAS_RES>
+// fp32 matrix) (+ a 16-bit residual laid out like Y), Relu, rounding.  Columns are plain columns
+// of Y, or, for a convolution, (image, pixel) pairs as in store_tile.  Stores outside Y are dropped
+// by the range check of the buffer resource.
+//
+// A lane holds one column of sixteen rows.  PAIRS = false: 2-byte stores (and residual loads), one
+// per element.  PAIRS = true (every row of Y starts on a 4-byte boundary and has an even number
+// of elements): two lanes next to each other, which hold columns c and c + 1 of the same rows,
+// trade values so that the even lane stores both columns of one row and the odd lane both columns
+// of the next row as one 4-byte word each: half as many stores, twice as wide, and the residual is
+// fetched the same way.
+template <int DT, int TM, int TN, int WTM, int WTN, bool HAS_RES, bool PAIRS>
 __device__ __forceinline__ void store_tile_lp_as(const floatx16 (&acc)[TM][TN], const TileWork& w, int wm, int wn, int li, int h,
-                                        const ContractionParams& cp) {
+                                                 const ContractionParams& cp) {
     const int64_t zi = w.zslice;
     int64_t tile_off = (int64_t)w.m0 * cp.y_rs + w.n0;
     uint32_t img0 = 0, px0 = 0;
@@ -214,38 +232,99 @@ __device__ __forceinline__ void store_tile_lp_as(const floatx16 (&acc)[TM][TN], 
     const __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(HAS_RES ? R + tile_off : Y + tile_off), 0, (int)OOB, RSRC_FLAGS);
     const int mode = cp.bias ? cp.bias_mode : BIAS_NONE;
     const float* bias = cp.bias ? cp.bias + zi * cp.bias_zs : nullptr;
+    // per-row bias through a resource over exactly the M values of this z-slice: rows beyond M read as 0
+    const __amdgpu_buffer_rsrc_t rrow = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(mode == BIAS_ROW ? bias : reinterpret_cast<const float*>(Y)), 0,
+                                                                          mode == BIAS_ROW ? cp.M * 4 : 0, RSRC_FLAGS);
     const bool relu = cp.relu != 0;
+    const bool odd = (li & 1) != 0;
+    // what depends on the column only
+    int crel[TN], colv[TN];
+    bool col_ok[TN];
+    float col_bias[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int cl = wn * WTN + j * 32 + li;
-        const int col = w.n0 + cl;
-        const bool col_ok = col < cp.N;
-        const int cj = col_ok ? col : w.n0;
-        int crel = cl;
+        colv[j] = w.n0 + cl;
+        col_ok[j] = colv[j] < cp.N;
+        const int cj = col_ok[j] ? colv[j] : w.n0;
+        crel[j] = cl;
         if (cp.col_images) {
             uint32_t n, px;
             cp.colP.divmod((uint32_t)cj, n, px);
-            crel = (int)(n - img0) * (int)cp.y_img + (int)px - (int)px0;
+            crel[j] = (int)(n - img0) * (int)cp.y_img + (int)px - (int)px0;
         }
-        const float col_bias = mode == BIAS_COL ? cp.beta * bias[(int64_t)cj * cp.bias_cs] : 0.f;
+        col_bias[j] = mode == BIAS_COL ? cp.beta * bias[(int64_t)cj * cp.bias_cs] : 0.f;
+    }
+    auto finish = [&](float a, float add) {
+        const float lin = fmaf(cp.alpha, a, add);
+        return relu ? fmaxf(lin, 0.f) : lin;                    // no clamp without Relu: a NaN stays a NaN
+    };
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i) {
+        // the bias of the 16 rows this lane's registers of block row i hold: register r is row
+        // rl0 + 8*(r/4) + r%4; four consecutive rows are one 16-byte load where the block lies inside M
+        const int rl0 = wm * WTM + i * 32 + 4 * h;
+        float row_bias[16];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int rl = wm * WTM + i * 32 + 8 * (r / 4) + 4 * h + (r % 4);
-                const int row = w.m0 + rl;
-                const bool ok = col_ok && row < cp.M;
-                const int off = ok ? (rl * (int)cp.y_rs + crel) * 2 : (int)OOB;
-                float add = col_bias;
-                if (mode == BIAS_ROW) add = cp.beta * bias[ok ? row : 0];
-                if (mode == BIAS_FULL) add = cp.beta * bias[ok ? (int64_t)row * cp.N + col : 0];
-                if constexpr (HAS_RES) {
-                    const uint16_t rv = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rr, off, 0, 0);
-                    add += DT == LP_F16 ? (float)__builtin_bit_cast(_Float16, rv) : __builtin_bit_cast(float, (uint32_t)rv << 16);
+        for (int r = 0; r < 16; ++r) row_bias[r] = 0.f;
+        if (mode == BIAS_ROW) {
+            if (w.m0 + wm * WTM + i * 32 + 32 <= cp.M) {         // uniform for the wavefront
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rrow, (w.m0 + rl0 + 8 * c) * 4, 0, 0));
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) row_bias[4 * c + q] = cp.beta * v[q];
                 }
-                const float lin = fmaf(cp.alpha, acc[i][j][r], add);
-                const float v = relu ? fmaxf(lin, 0.f) : lin;      // no clamp without Relu: a NaN stays a NaN
-                __builtin_amdgcn_raw_buffer_store_b16((short)to_lp<DT>(v), ry, off, 0, 0);
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    row_bias[r] = cp.beta * __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rrow, (w.m0 + rl0 + 8 * (r / 4) + r % 4) * 4, 0, 0));
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            auto bias_of = [&](bool ok, int r, int row) {
+                float add = col_bias[j] + row_bias[r];
+                if (mode == BIAS_FULL) add = cp.beta * bias[ok ? (int64_t)row * cp.N + colv[j] : 0];
+                return add;
+            };
+            if constexpr (!PAIRS) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int rl = rl0 + 8 * (r / 4) + (r % 4);
+                    const int row = w.m0 + rl;
+                    const bool ok = col_ok[j] && row < cp.M;
+                    const int off = ok ? (rl * (int)cp.y_rs + crel[j]) * 2 : (int)OOB;
+                    float add = bias_of(ok, r, row);
+                    if constexpr (HAS_RES) add += from_lp<DT>((uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rr, off, 0, 0));
+                    __builtin_amdgcn_raw_buffer_store_b16((short)to_lp<DT>(finish(acc[i][j][r], add)), ry, off, 0, 0);
+                }
+            } else {
+                // registers 2q and 2q + 1 hold rows rl and rl + 1 of this lane's column; the even lane
+                // of a pair writes (and reads the residual of) row rl, the odd lane row rl + 1, columns
+                // c and c + 1 each (N is even, so both columns exist or neither does)
+                const int crel_pair = crel[j] - (odd ? 1 : 0);
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const int r0 = 2 * q;
+                    const int rl = rl0 + 8 * (r0 / 4) + (r0 % 4);
+                    const int row = w.m0 + rl;
+                    const bool ok0 = col_ok[j] && row < cp.M, ok1 = col_ok[j] && row + 1 < cp.M;
+                    const int my_rl = rl + (odd ? 1 : 0);
+                    const int off = (odd ? ok1 : ok0) ? (my_rl * (int)cp.y_rs + crel_pair) * 2 : (int)OOB;
+                    float add0 = bias_of(ok0, r0, row), add1 = bias_of(ok1, r0 + 1, row + 1);
+                    if constexpr (HAS_RES) {
+                        const uint32_t mine = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rr, off, 0, 0);
+                        const uint32_t theirs = neighbour(mine);
+                        // even lane: its word is (row rl: c, c+1), the odd lane's (row rl+1: c, c+1)
+                        add0 += from_lp<DT>(odd ? theirs >> 16 : mine & 0xffffu);
+                        add1 += from_lp<DT>(odd ? mine >> 16 : theirs & 0xffffu);
+                    }
+                    const uint32_t c0 = to_lp<DT>(finish(acc[i][j][r0], add0)), c1 = to_lp<DT>(finish(acc[i][j][r0 + 1], add1));
+                    const uint32_t s0 = neighbour(c0), s1 = neighbour(c1);
+                    const uint32_t lo = odd ? s1 : c0, hi = odd ? c1 : s0;
+                    __builtin_amdgcn_raw_buffer_store_b32((int)(lo | (hi << 16)), ry, off, 0, 0);
+                }
             }
             // one accumulator block at a time: with up to 8 blocks live, loads hoisted across blocks spill
             __builtin_amdgcn_sched_barrier(0);
@@ -255,11 +334,19 @@ __device__ __forceinline__ void store_tile_lp_as(const floatx16 (&acc)[TM][TN], 
 
 template <int DT, int TM, int TN, int WTM, int WTN>
 __device__ __forceinline__ void store_tile_lp(const floatx16 (&acc)[TM][TN], const TileWork& w, int wm, int wn, int li, int h,
-                                     const ContractionParams& cp) {
-    // two copies of the epilogue rather than a test per element; both must be inlined: a call would
-    // pass the accumulators through memory
-    if (cp.residual) store_tile_lp_as<DT, TM, TN, WTM, WTN, true>(acc, w, wm, wn, li, h, cp);
-    else store_tile_lp_as<DT, TM, TN, WTM, WTN, false>(acc, w, wm, wn, li, h, cp);
+                                              const ContractionParams& cp) {
+    // Copies of the epilogue rather than tests per element; all must be inlined: a call would pass the
+    // accumulators through memory.  Pairs need every (row, even column) of Y and of the residual on a
+    // 4-byte boundary and both columns of a pair in the same row or image.
+    const bool even_strides = ((cp.N | cp.y_rs | cp.y_zs | (cp.col_images ? (int64_t)cp.colP.d | cp.y_img : 0)) & 1) == 0;
+    const bool pairs = even_strides && (reinterpret_cast<uintptr_t>(cp.Y) & 3u) == 0 && (reinterpret_cast<uintptr_t>(cp.residual) & 3u) == 0;
+    if (cp.residual) {
+        if (pairs) store_tile_lp_as<DT, TM, TN, WTM, WTN, true, true>(acc, w, wm, wn, li, h, cp);
+        else store_tile_lp_as<DT, TM, TN, WTM, WTN, true, false>(acc, w, wm, wn, li, h, cp);
+    } else {
+        if (pairs) store_tile_lp_as<DT, TM, TN, WTM, WTN, false, true>(acc, w, wm, wn, li, h, cp);
+        else store_tile_lp_as<DT, TM, TN, WTM, WTN, false, false>(acc, w, wm, wn, li, h, cp);
+    }
 }
 
 // BKIND: LOAD_KC (B stored [N][K], 16-byte chunks of 8 k) or LOAD_RC (B stored [K][N], chunks of

@@ -39,7 +39,9 @@ hipError_t launch_tile(ContractionParams& p, int nz, hipStream_t stream) {
     const double t128 = (double)((p.M + 127) / 128) * (double)((p.N + 127) / 128) * nz;
     const double c256 = (double)(int64_t)((t256 + cus - 1) / cus) * 65536.0 / 1.0;
     const double c128 = (t128 / cus < 1.0 ? 1.0 : t128 / cus) * 16384.0 / 0.85;
-    if (c256 <= c128) return launch_instance<256, 256, 64, 2, 4, DT, LP_OUT, 2, BKIND, BVEC>(p, nz, stream);
+    // (loads two steps ahead for a K-contiguous B; the row-contiguous loader's pairing needs the registers of
+    // the second staging set: with it the kernel spills inside its main loop)
+    if (c256 <= c128) return launch_instance<256, 256, 64, 2, 4, DT, LP_OUT, BKIND == LOAD_KC ? 2 : 1, BKIND, BVEC>(p, nz, stream);
     // fewer 128 x 128 tiles than half the CUs: 64 x 64 tiles spread the product over the chip (measured
     // 1024^3: 213 vs 121 TFLOP/s; from 2048^3 on the larger tile wins)
     if (t128 < cus / 2) return launch_instance<64, 64, 64, 2, 2, DT, LP_OUT, 2, BKIND, BVEC>(p, nz, stream);
