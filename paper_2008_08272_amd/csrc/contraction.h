@@ -298,6 +298,19 @@ struct TileLoader {
     }
 };
 
+// Values that are the same in every lane but were computed by vector instructions (the integer
+// divisions of the tile and z-slice decompositions are) and end up in a buffer resource or a
+// scalar offset: taken into scalar registers here, once.  Left to itself the compiler usually
+// does the same (it does in every instance of contraction_kernel), but in some instances of the
+// LDS-patch and 16-bit kernels it kept them in vector registers and wrapped every buffer access
+// that used them in a loop over the distinct values; those kernels call this.
+__device__ inline int scalar(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ inline int64_t scalar(int64_t v) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
 // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous run of logical
 // tile numbers so that tiles sharing A rows / B columns meet in the same L2.
 __device__ inline int xcd_contiguous(int bid, int nblocks) {

@@ -60,9 +60,11 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
 
     TileWork w;
     if (!tile_work(cp, BM, BN, w)) return;
+    w.m0 = scalar(w.m0); w.n0 = scalar(w.n0); w.zslice = scalar(w.zslice);
     const int m0 = w.m0, n0 = w.n0;
     int64_t a_off, b_off;
     slice_offsets(cp, w.zslice, a_off, b_off);
+    a_off = scalar(a_off); b_off = scalar(b_off);
     const Im2colGeom& g = cp.ic;
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
@@ -73,6 +75,8 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
     uint32_t q_first, ow_first, img_first, oh0;
     g.OW.divmod((uint32_t)n0, q_first, ow_first);
     g.OHd.divmod(q_first, img_first, oh0);
+    img_first = (uint32_t)scalar((int)img_first);
+    oh0 = (uint32_t)scalar((int)oh0);
     const int PS1 = (g.OH - 1 - (int)oh0) * g.sH + g.E;
     const int n_images = cp.N / (int)cp.colP.d;      // images in the batch
 
@@ -146,6 +150,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_kernel(const Contrac
 
     int ks0, ks1;
     split_range(g.Cg / WIN_CB, w.ksplit, w.split, ks0, ks1);
+    ks0 = scalar(ks0); ks1 = scalar(ks1);
 
     floatx4 reg_a[2][PA];
     float reg_b[2][NPB];

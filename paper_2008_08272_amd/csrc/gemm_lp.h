@@ -26,16 +26,6 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 enum { LP_F16 = 1, LP_BF16 = 2 };
 
-// Values that are the same in every lane but were computed by vector instructions (the integer
-// divisions of the z-slice decomposition are) and end up in a buffer resource: taken into scalar
-// registers here, once, instead of by a loop around every load and store that uses them.
-__device__ inline int scalar(int v) { return __builtin_amdgcn_readfirstlane(v); }
-__device__ inline int64_t scalar(int64_t v) {
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
-    return (int64_t)(((uint64_t)hi << 32) | lo);
-}
-
 template <int DT>
 __device__ inline floatx16 mfma16(const floatx4& a, const floatx4& b, const floatx16& c) {
     if (DT == LP_BF16)
