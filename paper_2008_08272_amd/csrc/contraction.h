@@ -630,7 +630,9 @@ constexpr int64_t kFinishSliceTiles = 128;     // up to this many tiles the fini
 // Host side: enqueue `kernel` for the tiles of `p` and, when K ranges are split, the finishing
 // kernel behind it.  `nk` = K steps a whole tile walks.
 // KS = K slices inside the main kernel's workgroup (it runs 64*WM*WN*KS threads).
-template <int BM, int BN, int WM, int WN, int KS = 1, typename Kernel>
+// SPLIT = false: a tile shape that is only ever chosen for outputs that fill whole rounds of the
+// CUs (the caller passes ksplit = 1): no tail either, and no finishing kernel is instantiated.
+template <int BM, int BN, int WM, int WN, int KS = 1, bool SPLIT = true, typename Kernel>
 inline hipError_t launch_with_split(Kernel kernel, ContractionParams& p, int nz, int nk, int64_t ws_floats,
                                     hipStream_t stream) {
     const unsigned gz = nz < 32768 ? (unsigned)nz : 32768u;
@@ -638,14 +640,15 @@ inline hipError_t launch_with_split(Kernel kernel, ContractionParams& p, int nz,
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
     if (tiles > 0x7fffffffLL || gy > 2047u) return hipErrorInvalidValue;
     TailSplit tail = {0, 1};
-    if (p.ksplit == 1 && nz == 1) tail = pick_tail(tiles, nk, (int64_t)BM * BN, p.ws_partial, ws_floats);
+    if (SPLIT && p.ksplit == 1 && nz == 1) tail = pick_tail(tiles, nk, (int64_t)BM * BN, p.ws_partial, ws_floats);
     p.tail_begin = (int)tiles - tail.tiles;
     p.tail_split = tail.split;
     const unsigned gx = (unsigned)(p.tail_begin + tail.tiles * tail.split);
     hipLaunchKernelGGL(kernel, dim3(gx, gy * (unsigned)p.ksplit, gz), dim3(64 * WM * WN * KS), 0, stream, p);
     hipError_t e = hipGetLastError();
+    if constexpr (!SPLIT) return p.ksplit == 1 ? e : hipErrorInvalidValue;
     // few tiles to finish: four workgroups per tile, a group of accumulator registers each
-    if (e == hipSuccess && p.ksplit > 1) {
+    else if (e == hipSuccess && p.ksplit > 1) {
         if (tiles * nz <= kFinishSliceTiles)
             hipLaunchKernelGGL((splitk_finish_kernel<BM, BN, WM, WN, 4>), dim3((unsigned)tiles * 4u, gy, gz), dim3(64 * WM * WN),
                                0, stream, p, false);

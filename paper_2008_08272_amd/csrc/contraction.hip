@@ -8,10 +8,13 @@ static hipError_t launch_one(ContractionParams& p, int nz, const Workspace& ws, 
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     p.nz = nz;
-    p.ksplit = pick_split((int64_t)p.tiles_m * p.tiles_n * nz, (p.K + BK - 1) / BK, (int64_t)BM * BN, 6.0, ws);
+    // The 16-wavefront tiles are chosen only where their tile count fills whole rounds of the 256 CUs
+    // (pick_tile), which is exactly where neither a K split nor a tail split pays: they never split.
+    constexpr bool kMaySplit = BM * BN < 128 * 128;
+    p.ksplit = kMaySplit ? pick_split((int64_t)p.tiles_m * p.tiles_n * nz, (p.K + BK - 1) / BK, (int64_t)BM * BN, 6.0, ws) : 1;
     p.ws_partial = ws.partial;
-    const hipError_t e = launch_with_split<BM, BN, WM, WN, KS>(contraction_kernel<BM, BN, BK, WM, WN, KS, AK, BKIND, AVEC, BVEC>,
-                                                               p, nz, (p.K + BK - 1) / BK, ws.partial_floats, stream);
+    const hipError_t e = launch_with_split<BM, BN, WM, WN, KS, kMaySplit>(
+        contraction_kernel<BM, BN, BK, WM, WN, KS, AK, BKIND, AVEC, BVEC>, p, nz, (p.K + BK - 1) / BK, ws.partial_floats, stream);
     const int ntiles = p.tiles_m * p.tiles_n;
     record_launch(LaunchRecord{"contraction", BM, BN, BK, WM, WN, KS, AK, BKIND, AVEC, BVEC, 0, p.ksplit,
                                ntiles - p.tail_begin, p.tail_split});

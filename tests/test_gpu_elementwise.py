@@ -82,7 +82,10 @@ def test_unary_bit_exact(lib, n):
     # a view that is not 16-byte aligned takes the scalar path
     if n > 8:
         sub = xd[1:]
-        assert np.array_equal(host(lib.onnx_relu(sub.contiguous() if not sub.is_contiguous() else sub)), ew.relu(x[1:]).astype(np.float32))
+        assert sub.is_contiguous() and sub.data_ptr() % 16 == 4
+        assert np.array_equal(host(lib.onnx_relu(sub)), ew.relu(x[1:]).astype(np.float32))
+        assert np.array_equal(host(lib.onnx_abs(sub)), ew.absolute(x[1:]).astype(np.float32))
+        assert np.array_equal(host(lib.onnx_leakyrelu(sub, 0.2)), ew.leakyrelu(x[1:], 0.2).astype(np.float32))
 
 
 REDUCE_CASES = [

@@ -203,6 +203,7 @@ CONV_CASES = [
     (1, 16, 5, 5, 32, 5, 5, (0, 0, 0, 0), (1, 1), (1, 1), 1),        # output 1x1
     # 3x3 with few channels per group (row-strip kernel: one wavefront per 8 rows x 64 columns)
     (2, 5, 21, 150, 5, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 5),       # depthwise, 3 column chunks, ragged last strip
+    (2, 6, 21, 40, 6, 3, 3, (1, 1, 1, 1), (2, 1), (1, 1), 6),        # depthwise, vertical stride 2, a row per wavefront: one load per row
     (2, 6, 23, 70, 12, 3, 3, (0, 2, 1, 0), (2, 2), (1, 1), 3),       # vertical stride 2, 2 channels per group, asymmetric pads
     (1, 4, 19, 66, 4, 3, 3, (2, 2, 2, 2), (1, 3), (2, 2), 4),        # vertical dilation 2, horizontal stride 3
     (3, 8, 9, 9, 8, 3, 3, (1, 1, 1, 1), (3, 1), (1, 1), 8),          # vertical stride 3: falls back to the plane kernel
@@ -394,6 +395,7 @@ POOL_CASES = [
     (1, 2, 16, 24, (3, 3), (1, 1, 0, 2), (2, 2), (1, 1), 1),
     (2, 2, 9, 128, (3, 3), (0, 1, 1, 1), (2, 2), (1, 1), 0),
     (1, 2, 11, 130, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),        # 65 output columns: two chunks, plain loads
+    (2, 3, 9, 10, (2, 2), (0, 0, 0, 0), (1, 1), (1, 1), 0),          # 2x2 window, stride 1: the plane-strip kernel
 ]
 
 
@@ -865,6 +867,40 @@ CONV_INSTANCE_CASES = [
     ("pointwise 128x128x16", (8, 512, 32, 32), (512, 512, 1, 1), (0, 0, 0, 0), (1, 1), "128x128x16 waves 4x4x1 A=KC/4 B=RC/4"),
     ("pointwise 256x256x16", (32, 64, 32, 32), (512, 64, 1, 1), (0, 0, 0, 0), (1, 1), "256x256x16 waves 4x4x1 A=KC/4 B=RC/4"),
 ]
+
+
+CONV_WINDOW_INSTANCE_CASES = [
+    # name, X shape, output channels, pad = dilation, stride, expected instance, and what the split looks like with a workspace
+    ("64x64 2 passes", (30, 16, 16, 4), 64, 1, 1, "64x64x36 waves 2x2x1 A=KC/4 B=IM2COL/1 npb=2", None),
+    ("128x128 2 passes", (500, 16, 8, 8), 128, 1, 1, "128x128x36 waves 4x2x1 A=KC/4 B=IM2COL/1 npb=2", None),
+    ("128x128 3 passes", (500, 16, 8, 8), 128, 2, 1, "128x128x36 waves 4x2x1 A=KC/4 B=IM2COL/1 npb=3", None),
+    ("128x128 4 passes", (500, 16, 8, 8), 128, 3, 1, "128x128x36 waves 4x2x1 A=KC/4 B=IM2COL/1 npb=4", None),
+    ("128x128 5 passes", (500, 16, 16, 16), 128, 1, 2, "128x128x36 waves 4x2x1 A=KC/4 B=IM2COL/1 npb=5", None),
+    ("128x128 6 passes", (2000, 16, 8, 8), 128, 1, 2, "128x128x36 waves 4x2x1 A=KC/4 B=IM2COL/1 npb=6", None),
+    ("128x128 tail split", (25, 64, 28, 28), 256, 1, 1, "128x128x36 waves 4x2x1 A=KC/4 B=IM2COL/1 npb=3", "ksplit=1 tail=52x4"),
+    ("128x128 split K", (25, 256, 28, 28), 256, 1, 1, "128x128x36 waves 4x2x1 A=KC/4 B=IM2COL/1 npb=3", "ksplit=2 tail=0x1"),
+]
+
+
+@pytest.mark.parametrize("case", CONV_WINDOW_INSTANCE_CASES, ids=[c[0] for c in CONV_WINDOW_INSTANCE_CASES])
+def test_every_conv_window_instance(lib, workspace, case):
+    """The pass counts of the LDS-patch kernel that no other test selects (tiny planes: a tile then spans many
+    images; dilated and strided patches), and the 128 x 128 tile with a tail split and with a K split, whose
+    finishing kernels run one and four workgroups per tile."""
+    name, xs, m, d, st, inst, split = case
+    announce("conv window instance", name)
+    rng = np.random.default_rng([len(name)] + list(xs))
+    X = rng.uniform(-1, 1, xs).astype(np.float32)
+    Wt = rng.uniform(-1, 1, (m, xs[1], 3, 3)).astype(np.float32)
+    Bv = rng.uniform(-1, 1, (m,)).astype(np.float32)
+    K = xs[1] * 9
+    ref, S = cached(("conv_window_inst", name), lambda: oracle.conv(X, Wt, Bv, (d, d, d, d), (st, st), (d, d), 1, want_scale=True))
+    got = host(lib.onnx_conv(dev(X), dev(Wt), dev(Bv), (d, d, d, d), (st, st), (d, d), 1))
+    launch = lib.onnx_last_launch()
+    assert launch.startswith("conv_window " + inst), (launch, inst)
+    assert launch.endswith(split if split and workspace == "workspace" else "ksplit=1 tail=0x1"), launch
+    assert rel_err(got, ref) <= REL_TOL
+    assert within_rounding_bound(got, ref, S, K + 1)
 
 
 @pytest.mark.parametrize("case", CONV_INSTANCE_CASES, ids=[c[0] for c in CONV_INSTANCE_CASES])
