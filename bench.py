@@ -31,7 +31,7 @@ RAMP_SECONDS = 0.3
 # profiles/gemm4096_hbm_traffic.md (fetch scaled by the 2.000 a plain copy shows, write exact).  The
 # counters sit between the eight L2s and the fabric, so this is L2 fill + write-back traffic (served by
 # the Infinity Cache or HBM).  Reported only while the kernel sources are the ones that were measured.
-TRAFFIC_4096 = {"sources_sha256_16": "08d1a45b7bb0d034", "bytes_per_launch": (196763.6 * 2.000 + 65536.0) * 1024.0}
+TRAFFIC_4096 = {"sources_sha256_16": "6d9478fbf125c623", "bytes_per_launch": (196763.6 * 2.000 + 65536.0) * 1024.0}
 KERNEL_SOURCES = ("paper_2008_08272_amd/csrc/contraction.h", "paper_2008_08272_amd/csrc/contraction.hip")
 
 
