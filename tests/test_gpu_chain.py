@@ -154,6 +154,72 @@ def test_chain_attribute_cases(lib, name):
     run_and_compare(lib, _rand(rng, shape), ops)
 
 
+def random_chain(rng):
+    """A random chain of up to 6 operators on a small image; None when shape inference refuses it."""
+    import paper_2008_08272_amd as lib
+    n, c, h, w = int(rng.integers(1, 5)), int(rng.integers(1, 7)), int(rng.integers(5, 25)), int(rng.integers(5, 25))
+    shape = (n, c, h, w)
+    ops = []
+    cur = shape
+    for _ in range(int(rng.integers(1, 7))):
+        flat = cur[2] == 1 and cur[3] == 1
+        kind = "gemm" if (flat and ops) or rng.random() < 0.15 else ("conv", "conv", "maxpool", "avgpool")[int(rng.integers(0, 4))]
+        pick = lambda lo, hi: int(rng.integers(lo, hi + 1))
+        if kind == "gemm":
+            k = cur[1] * cur[2] * cur[3]
+            outs = pick(1, 40)
+            tb = pick(0, 1)
+            op = dict(op="gemm", W=_rand(rng, (outs, k) if tb else (k, outs), 0.3), B=_rand(rng, (outs,)) if pick(0, 1) else None,
+                      transB=tb, alpha=float(rng.uniform(-1.5, 1.5)), beta=float(rng.uniform(-1.5, 1.5)), act=pick(0, 1))
+        elif kind == "conv":
+            m, kh, kw = pick(1, 24), pick(1, 4), pick(1, 4)
+            op = dict(op="conv", W=_rand(rng, (m, cur[1], kh, kw), 0.4), B=_rand(rng, (m,)) if pick(0, 1) else None,
+                      pads=tuple(pick(0, 2) for _ in range(4)), strides=(pick(1, 2), pick(1, 2)), dilations=(pick(1, 2), pick(1, 2)),
+                      act=pick(0, 1))
+        elif kind == "maxpool":
+            kh, kw = pick(1, 3), pick(1, 3)
+            op = dict(op="maxpool", kernel=(kh, kw), strides=(pick(1, 3), pick(1, 3)), dilations=(pick(1, 2), pick(1, 2)),
+                      pads=(pick(0, (kh - 1) // 2), pick(0, (kw - 1) // 2), pick(0, (kh - 1) // 2), pick(0, (kw - 1) // 2)), ceil_mode=pick(0, 1))
+        else:
+            if rng.random() < 0.2:
+                op = dict(op="avgpool", kernel=None)
+            else:
+                kh, kw = pick(1, 3), pick(1, 3)
+                op = dict(op="avgpool", kernel=(kh, kw), strides=(pick(1, 3), pick(1, 3)),
+                          pads=(pick(0, (kh - 1) // 2), pick(0, (kw - 1) // 2), pick(0, (kh - 1) // 2), pick(0, (kw - 1) // 2)),
+                          ceil_mode=pick(0, 1), count_include_pad=pick(0, 1))
+        try:
+            cur = lib.chain_shapes(cur, [op])[0]
+        except lib.OnnxHipError:
+            return None
+        if min(cur) < 1:
+            return None
+        ops.append(op)
+    return shape, ops
+
+
+def test_chain_random_sweep(lib):
+    """Seeded random chains (every operator kind, random attributes, both Conv forms, every layer compared);
+    chains that do not fit the kernel's LDS budget must be refused with ONNX_ERR_UNSUPPORTED and are skipped."""
+    rng = np.random.default_rng(20080827)
+    ran = refused = 0
+    while ran < 40:
+        c = random_chain(rng)
+        if c is None:
+            continue
+        shape, ops = c
+        print("CASE chain sweep", ran, shape, [(o["op"], tuple(o["W"].shape) if "W" in o else o.get("kernel")) for o in ops], flush=True)
+        X = _rand(rng, shape)
+        try:
+            run_and_compare(lib, X, ops)
+        except lib.OnnxHipError as e:
+            assert e.status == 5, (e.status, str(e))
+            refused += 1
+            assert refused < 200
+            continue
+        ran += 1
+
+
 def test_chain_small_integers_bit_exact(lib):
     """Integer-valued inputs and weights: every product and partial sum is exact in fp32, so the
     result must equal the oracle's bit for bit whatever the order of the K steps."""
