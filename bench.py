@@ -111,9 +111,9 @@ def main():
                     help="run only the four launches whose hardware counters are summarised under profiles/ "
                          "(Gemm 4096^3, 3x3 conv 32x64x56x56, dilated 3x3 conv, depthwise 3x3 conv), a few "
                          "times each, print their mean times and exit")
-    ap.add_argument("--profile-resnet", action="store_true",
-                    help="run only ResNet-50 at batch 32 (3 untimed + 10 timed passes), print the mean time and exit: "
-                         "the run behind the per-kernel trace under profiles/")
+    ap.add_argument("--profile-resnet", type=int, nargs="?", const=32, default=0, metavar="BATCH",
+                    help="run only ResNet-50 at the given batch (default 32; 3 untimed + 10 timed passes, one call per "
+                         "node), print the mean time and exit: the run behind the per-kernel traces under profiles/")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -137,7 +137,7 @@ def main():
         return
     if args.profile_resnet:
         from paper_2008_08272_amd.runner import GraphRunner
-        r = GraphRunner(workloads.resnet50(32), dev)
+        r = GraphRunner(workloads.resnet50(args.profile_resnet), dev)
         for _ in range(3):
             r.run()
         torch.cuda.synchronize()
@@ -147,7 +147,7 @@ def main():
             r.run()
         e1.record()
         torch.cuda.synchronize()
-        print(json.dumps({"profile_resnet": {"batch": 32, "ms": round(e0.elapsed_time(e1) / 10, 4)}}))
+        print(json.dumps({"profile_resnet": {"batch": args.profile_resnet, "ms": round(e0.elapsed_time(e1) / 10, 4)}}))
         return
 
     if args.copy_calibration:
