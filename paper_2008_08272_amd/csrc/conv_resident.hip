@@ -257,6 +257,12 @@ bool launch_conv_resident(const float* X, const float* W, const float* B, const 
                           const WindowGeom& g, int M, int Cg, int relu, hipStream_t stream, hipError_t* status) {
     const bool stem = g.kH == 7 && g.kW == 7 && Cg == 3 && g.C == 3 && g.sH == 2 && g.sW == 2 && g.dH == 1 && g.dW == 1;
     if (!stem) return false;
+    // Every workgroup first loads its 64 filters into registers; that only pays once a workgroup has a few tiles
+    // to run them over.  With fewer than two tiles per CU (batch 1 to 4 at 224x224: 12 us against 17.5 us at
+    // batch 1, level at batch 4) the gathering contraction kernel is the faster one.
+    using Stem = ResidentShape<7, 7, 3, 2, 2>;
+    const int64_t stem_tiles = (int64_t)g.N * ((g.OW + Stem::TW - 1) / Stem::TW) * ((g.OH + Stem::TH - 1) / Stem::TH);
+    if (stem_tiles * ((M + 63) / 64) < 2 * 256) return false;
     // 32-bit byte offsets inside one image of X and of Y, and inside W
     if ((int64_t)g.C * g.H * g.W * 4 >= (1LL << 31) || (int64_t)(M + 64) * g.OH * g.OW * 4 >= (1LL << 31) ||
         (int64_t)(M + 64) * Cg * g.kH * g.kW * 4 >= (1LL << 31))

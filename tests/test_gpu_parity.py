@@ -237,18 +237,22 @@ def test_conv_matches_oracle(lib, case):
 
 
 RESIDENT_CASES = [
-    # N, H, W, M, pads: 7x7 stride-2 convolutions of 3-channel images (the filters stay in registers)
-    (2, 37, 41, 64, (3, 3, 3, 3)),          # ragged tiles in both directions
-    (1, 224, 224, 64, (3, 3, 3, 3)),        # ResNet-50's stem: 14 x 7 whole tiles per image
-    (3, 64, 50, 96, (0, 2, 5, 1)),          # asymmetric pads, 96 filters: the second filter block is half empty
-    (2, 23, 130, 130, (6, 6, 6, 6)),        # pads as large as they may be, three filter blocks, one row of tiles
-    (5, 7, 7, 32, (0, 0, 0, 0)),            # a single output position per image
+    # N, H, W, M, pads, resident: 7x7 stride-2 convolutions of 3-channel images.  With two or more 8x16 output tiles
+    # per CU and filter block the filters stay in registers; below that the gathering contraction kernel runs.
+    (90, 37, 41, 64, (3, 3, 3, 3), True),         # ragged tiles in both directions
+    (6, 224, 224, 64, (3, 3, 3, 3), True),        # ResNet-50's stem: 14 x 7 whole tiles per image
+    (32, 64, 50, 96, (0, 2, 5, 1), True),         # asymmetric pads, 96 filters: the second filter block is half empty
+    (18, 23, 130, 130, (6, 6, 6, 6), True),       # pads as large as they may be, three filter blocks, two rows of tiles
+    (512, 7, 7, 32, (0, 0, 0, 0), True),          # a single output position per image
+    (1, 224, 224, 64, (3, 3, 3, 3), False),       # the stem at batch 1: 98 tiles
+    (5, 224, 224, 64, (3, 3, 3, 3), False),       # 490 tiles: the last batch below the switch
+    (2, 37, 41, 64, (3, 3, 3, 3), False),
 ]
 
 
 @pytest.mark.parametrize("case", RESIDENT_CASES)
 def test_conv_resident_filters_matches_oracle(lib, case):
-    N, H, W, M, pads = case
+    N, H, W, M, pads, resident = case
     announce("conv resident", case)
     rng = np.random.default_rng([N, H, W, M])
     X = rng.uniform(-1, 1, (N, 3, H, W)).astype(np.float32)
@@ -256,7 +260,7 @@ def test_conv_resident_filters_matches_oracle(lib, case):
     Bv = rng.uniform(-1, 1, (M,)).astype(np.float32)
     ref, S = oracle.conv(X, Wt, Bv, pads, (2, 2), (1, 1), 1, want_scale=True)
     got = host(lib.onnx_conv(dev(X), dev(Wt), dev(Bv), pads, (2, 2), (1, 1), 1))
-    assert lib.onnx_last_launch().startswith("conv_resident 64x128x147"), lib.onnx_last_launch()
+    assert lib.onnx_last_launch().startswith("conv_resident 64x128x147" if resident else "contraction "), lib.onnx_last_launch()
     assert got.shape == ref.shape
     assert rel_err(got, ref) <= REL_TOL
     assert within_rounding_bound(got, ref, S, 147 + 1)
@@ -348,7 +352,8 @@ def test_nan_and_inf_propagate_alike_on_every_conv_path(lib):
         ((2, 6, 12, 12), (32, 6, 5, 5), (2, 2, 2, 2), 1),        # gather loader
         ((2, 8, 12, 12), (8, 1, 3, 3), (1, 1, 1, 1), 8),         # row-strip (depthwise)
         ((2, 8, 12, 12), (8, 1, 5, 5), (2, 2, 2, 2), 8),         # direct
-        ((2, 3, 20, 20), (32, 3, 7, 7), (3, 3, 3, 3), 1),        # filters resident in registers (stride 2)
+        ((2, 3, 20, 20), (32, 3, 7, 7), (3, 3, 3, 3), 1),        # gather loader, 7x7 stride 2
+        ((256, 3, 20, 20), (32, 3, 7, 7), (3, 3, 3, 3), 1),      # filters resident in registers (stride 2)
     ]
     for xs, ws_, pads, g in shapes:
         X = rng.uniform(0.5, 1, xs).astype(np.float32)
