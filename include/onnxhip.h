@@ -271,8 +271,13 @@ onnx_status onnx_matmul_lp(const void* A, const int64_t* a_dims, int a_rank, con
  * stored as out_type (ONNX_F32 or in_type, rounded to nearest even).  A 1x1 convolution with
  * stride 1 and no padding whose C/group is a multiple of 8 and whose H*W is a multiple of 4 runs
  * through the tuned kernel of onnx_gemm_lp (the input of an image is a row-contiguous
- * [C][H*W] matrix); every other shape runs through one general kernel that gathers the input
- * element by element.  No workspace is used.
+ * [C][H*W] matrix).  A 3x3 convolution (any stride, dilation and padding) whose C/group is a
+ * multiple of 16 runs through a kernel that stages the input patch of a tile in LDS, provided
+ * the workspace of onnx_set_workspace can hold a rewritten copy of the filter bank
+ * (M * C/group * 9 16-bit values; a small kernel ahead of the convolution writes it on every
+ * call, so calls that share the workspace on different streams race, as for split-K).  Every
+ * other shape runs through one general kernel that gathers the input element by element and
+ * uses no workspace.
  */
 onnx_status onnx_conv_lp(const void* X, const int64_t x_dims[4], const void* W, const int64_t w_dims[4],
                          const float* B, const int64_t pads[4], const int64_t strides[2],

@@ -210,6 +210,12 @@ onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const f
         const int bvec = pw ? lp_tuned_fits(p, LOAD_KC, LOAD_RC, (int)group) : 0;
         if (bvec)
             return device_status(launch_lp_tuned(p, LOAD_RC, bvec, (int)group, (int)in_type, (int)out_type, s), "conv (16-bit)");
+        if (!pw) {
+            hipError_t e = hipSuccess;
+            if (launch_conv_window_lp(p, (int)kH, (int)kW, (int)OH, (int)OW, (int)Cg, (int)group, (int)in_type, (int)out_type, ws,
+                                      s, &e))
+                return device_status(e, "conv (16-bit, lds patch)");
+        }
         return device_status(launch_lp_generic(p, LOAD_KC, pw ? LOAD_RC : LOAD_IM2COL, (int)group, (int)in_type,
                                                (int)out_type, s), "conv (16-bit)");
     }
@@ -556,10 +562,10 @@ onnx_status onnx_conv_lp(const void* X, const int64_t x_dims[4], const void* W, 
                          onnx_dtype out_type, void* stream) {
     if (in_type != ONNX_F16 && in_type != ONNX_BF16) return fail(ONNX_ERR_ATTR, "conv_lp: in_type must be ONNX_F16 or ONNX_BF16");
     if (out_type != ONNX_F32 && out_type != in_type) return fail(ONNX_ERR_ATTR, "conv_lp: out_type must be ONNX_F32 or in_type");
-    const Workspace none = {nullptr, 0};
+    const Workspace ws = workspace();      // the tuned 3x3 kernel keeps its rewritten filter bank there
     return conv_with_workspace(static_cast<const float*>(X), x_dims, static_cast<const float*>(W), w_dims, B, pads, strides,
                                dilations, group, static_cast<const float*>(residual), act, static_cast<float*>(Y), y_dims,
-                               &none, 0, stream, in_type, out_type);
+                               &ws, 0, stream, in_type, out_type);
 }
 
 onnx_status onnx_maxpool(const float* X, const int64_t x_dims[4], const int64_t kernel[2],

@@ -89,6 +89,12 @@ hipError_t launch_lp_tuned(ContractionParams& p, int bkind, int bvec, int nz, in
 bool launch_conv_window(ContractionParams& p, int kH, int kW, int OH, int OW, int Cg, int nz,
                         const Workspace& ws, hipStream_t stream, hipError_t* status);
 
+// The same for 16-bit tensors (conv_window_lp.hip): 3x3 windows, input channels per group a multiple
+// of 16, and a workspace that holds a rewritten copy of the filter bank (p.M * nz * Cg * 9 16-bit
+// values).  in_type / out_type as for launch_lp_generic.
+bool launch_conv_window_lp(ContractionParams& p, int kH, int kW, int OH, int OW, int Cg, int nz, int in_type, int out_type,
+                           const Workspace& ws, hipStream_t stream, hipError_t* status);
+
 struct WindowGeom {
     int N, C, H, W, OH, OW;
     int kH, kW, sH, sW, pT, pL, pB, pR, dH, dW;

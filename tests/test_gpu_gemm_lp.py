@@ -328,6 +328,99 @@ def test_conv_16bit_matches_oracle(lib, case, kind):
     assert (got2 >= 0).all()
 
 
+CONV3X3_LP_CASES = [
+    # N, C, H, W, M, pads, strides, dilations, group, expected "tile B=IM2COL/columns-per-unit npb"
+    (2, 16, 7, 7, 40, (1, 1, 1, 1), (2, 1), (1, 1), 1, "64x64x144 1 2"),          # odd row length: one column per unit
+    (2, 16, 7, 7, 40, (1, 1, 1, 1), (2, 1), (1, 3), 1, "64x64x144 1 4"),
+    (2, 16, 7, 7, 40, (1, 1, 1, 1), (2, 2), (1, 3), 1, "64x64x144 1 8"),
+    (2, 16, 12, 12, 40, (1, 1, 1, 1), (2, 1), (1, 1), 1, "64x64x144 2 1"),        # even row length: pairs of columns
+    (2, 16, 14, 14, 40, (1, 1, 1, 1), (2, 2), (1, 3), 1, "64x64x144 2 2"),
+    (2, 16, 12, 12, 40, (1, 1, 1, 1), (2, 2), (1, 3), 1, "64x64x144 2 4"),
+    (3, 64, 19, 23, 72, (2, 0, 1, 3), (1, 1), (1, 1), 2, "64x64x144 1 2"),        # two groups, asymmetric pads, ragged M and N
+    (3, 64, 18, 22, 72, (0, 2, 1, 1), (1, 2), (2, 1), 2, "64x64x144 2 2"),        # even left pad: no column shift
+    (5, 32, 28, 28, 200, (1, 1, 1, 1), (1, 1), (1, 1), 1, "64x64x144 2 1"),       # tiles that span images
+    (3, 128, 14, 14, 128, (1, 1, 1, 1), (1, 1), (1, 1), 1, "64x64x144 2 1"),      # K = 1152: eight steps
+    (40, 16, 30, 31, 128, (1, 1, 1, 1), (1, 1), (1, 3), 1, "128x128x144 1 4"),    # enough tiles for the 128 x 128 tile
+    (40, 16, 25, 51, 128, (1, 1, 1, 1), (2, 1), (2, 2), 1, "128x128x144 1 8"),
+    (210, 16, 7, 7, 256, (1, 1, 1, 1), (1, 1), (1, 1), 1, "128x128x144 1 2"),
+    (160, 16, 10, 10, 256, (0, 0, 0, 0), (1, 1), (1, 1), 1, "128x128x144 2 1"),
+    (40, 16, 20, 20, 256, (1, 1, 1, 1), (1, 1), (1, 3), 1, "128x128x144 2 2"),
+    (40, 16, 24, 50, 128, (1, 1, 1, 1), (2, 1), (2, 2), 1, "128x128x144 2 4"),
+]
+
+
+@pytest.fixture
+def lp_workspace(lib):
+    ws = torch.empty(16 << 20, dtype=torch.uint8, device="cuda")
+    lib.onnx_set_workspace(ws)
+    try:
+        yield ws
+    finally:
+        torch.cuda.synchronize()
+        lib.onnx_set_workspace(None)
+
+
+@pytest.mark.parametrize("case", CONV3X3_LP_CASES)
+def test_conv3x3_16bit_lds_patch_matches_oracle(lib, lp_workspace, case):
+    """With a workspace (it holds the rewritten filter bank) 3x3 convolutions whose channel count per group is
+    a multiple of 16 run the LDS-patch kernel: every instance, against the oracle."""
+    N, C, H, W, M, pads, st, dl, g, expect = case
+    kind = ("f16", "bf16")[(N + H + M) % 2]
+    announce("conv_lp 3x3", kind, case)
+    rng = np.random.default_rng([N, C, H, W, M, g])
+    xb, xv = encode(rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32), kind)
+    wb, wv = encode(rng.uniform(-1, 1, (M, C // g, 3, 3)).astype(np.float32), kind)
+    Bv = rng.uniform(-1, 1, (M,)).astype(np.float32)
+    K = (C // g) * 9
+    ref, S = oracle.conv(xv, wv, Bv, pads, st, dl, g, want_scale=True)
+    X, Wt = bits_to_dev(xb, kind), bits_to_dev(wb, kind)
+    got = lib.onnx_conv_lp(X, Wt, torch.from_numpy(Bv).cuda(), pads, st, dl, g, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    tile, cols, npb = expect.split()
+    launch = lib.onnx_last_launch()
+    assert launch.startswith("conv_window_lp " + tile) and "B=IM2COL/%s npb=%s " % (cols, npb) in launch, launch
+    gth = got.cpu().numpy()
+    assert gth.shape == ref.shape
+    assert rel_err(gth, ref) <= REL_TOL
+    assert within_rounding_bound(gth, ref, S, K + 1)
+    # 16-bit result with a 16-bit residual and Relu: one more rounding on top of the fp32 result
+    rb, rv = encode(rng.uniform(-1, 1, ref.shape).astype(np.float32), kind)
+    ref2, S2 = oracle.conv(xv, wv, None, pads, st, dl, g, residual=rv, relu=False, want_scale=True)
+    got2 = lp_to_host(lib.onnx_conv_lp(X, Wt, None, pads, st, dl, g, residual=bits_to_dev(rb, kind), act=1), kind)
+    assert lib.onnx_last_launch().startswith("conv_window_lp " + tile)
+    u = 2.0 ** -PRECISION[kind]
+    want = np.maximum(ref2, 0)
+    assert (np.abs(got2 - want) <= u * np.abs(want) + (K + 5) * 2.0 ** -24 * (S2 + 1.0) + 1e-7).all()
+    assert (got2 >= 0).all()
+    # small integers: every product and partial sum exact, so the bits must agree
+    Xi = rng.integers(-4, 5, (N, C, H, W)).astype(np.float32)
+    Wi = rng.integers(-4, 5, (M, C // g, 3, 3)).astype(np.float32)
+    refi = oracle.conv(Xi, Wi, None, pads, st, dl, g)
+    goti = lib.onnx_conv_lp(bits_to_dev(encode(Xi, kind)[0], kind), bits_to_dev(encode(Wi, kind)[0], kind), None, pads, st, dl, g,
+                            out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert np.array_equal(goti.cpu().numpy().astype(np.float64), refi)
+
+
+def test_conv3x3_16bit_workspace_too_small_or_channels_not_16(lib, lp_workspace):
+    """The LDS-patch kernel needs room for the rewritten filter bank and 16 | channels per group; otherwise the
+    general kernel runs, with the same result up to summation order."""
+    announce("conv_lp 3x3 fallbacks")
+    rng = np.random.default_rng(77)
+    for C, M in ((24, 32), (64, 1024 * 16)):
+        N, H, W = (2, 10, 10) if C == 24 else (1, 4, 4)
+        xb, xv = encode(rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32), "bf16")
+        wb, wv = encode(rng.uniform(-1, 1, (M, C, 3, 3)).astype(np.float32), "bf16")
+        ref, S = oracle.conv(xv, wv, None, (1, 1, 1, 1), (1, 1), (1, 1), 1, want_scale=True)
+        got = lib.onnx_conv_lp(bits_to_dev(xb, "bf16"), bits_to_dev(wb, "bf16"), None, (1, 1, 1, 1), (1, 1), (1, 1), 1,
+                               out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        # 24 channels; 16384 x 64 x 9 values = 18 MiB of filters against a 16 MiB workspace
+        assert lib.onnx_last_launch().startswith("lp_generic"), lib.onnx_last_launch()
+        gth = got.cpu().numpy()
+        assert rel_err(gth, ref) <= REL_TOL and within_rounding_bound(gth, ref, S, C * 9 + 1)
+
+
 def test_conv_16bit_small_integers_bit_exact(lib):
     announce("conv_lp integers")
     rng = np.random.default_rng(8)
