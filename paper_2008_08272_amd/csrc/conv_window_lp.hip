@@ -280,11 +280,14 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_lp_kernel(const Cont
 
 struct WindowLpConfig {
     int bm, bn, nt, max_units;
+    int resident;      // workgroups all CUs hold at once (LDS-limited)
+    double weight;     // time of one workgroup relative to the 64 x 64 tile's
 };
-// Keep in step with the template instances in launch_config below.
+// Keep in step with the template instances in launch_config below.  Measured on ResNet-50's 3x3 layers at batch 32
+// (bf16): a 128 x 128 workgroup of eight wavefronts takes 1.1-1.45 times as long as a 64 x 64 one of four.
 const WindowLpConfig kConfigs[] = {
-    {64, 64, 256, 8},
-    {128, 128, 256, 8},
+    {64, 64, 256, 8, 512, 1.0},
+    {128, 128, 512, 4, 256, 1.4},
 };
 const int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 
@@ -316,12 +319,16 @@ hipError_t launch_units(ContractionParams& p, bool pair, int npu, int nz, hipStr
     if (pair) {
         if (npu <= 2) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, true, 1>(p, nz, stream);
         if (npu <= 4) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, true, 2>(p, nz, stream);
-        if (npu <= 8) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, true, 4>(p, nz, stream);
+        if constexpr (WM * WN <= 4) {
+            if (npu <= 8) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, true, 4>(p, nz, stream);
+        }
         return hipErrorInvalidValue;
     }
     if (npu <= 2) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, false, 2>(p, nz, stream);
     if (npu <= 4) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, false, 4>(p, nz, stream);
-    if (npu <= 8) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, false, 8>(p, nz, stream);
+    if constexpr (WM * WN <= 4) {
+        if (npu <= 8) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, false, 8>(p, nz, stream);
+    }
     return hipErrorInvalidValue;
 }
 
@@ -329,7 +336,7 @@ template <int DT, bool LP_OUT>
 hipError_t launch_config(ContractionParams& p, int cfg, bool pair, int npu, int nz, hipStream_t stream) {
     switch (cfg) {
         case 0: return launch_units<64, 64, 2, 2, DT, LP_OUT>(p, pair, npu, nz, stream);
-        case 1: return launch_units<128, 128, 2, 2, DT, LP_OUT>(p, pair, npu, nz, stream);
+        case 1: return launch_units<128, 128, 2, 4, DT, LP_OUT>(p, pair, npu, nz, stream);
         default: return hipErrorInvalidValue;
     }
 }
@@ -343,7 +350,7 @@ bool launch_conv_window_lp(ContractionParams& p, int kH, int kW, int OH, int OW,
     const int64_t filter_values = (int64_t)p.M * nz * Cg * LPW_TAPS;
     if (!ws.partial || filter_values * 2 > ws.partial_floats * 4) return false;
     // 32-bit byte offsets from a tile's first image: the input of the images one tile touches, and their output
-    const int64_t P = (int64_t)OH * OW, tile_images = (128 + P - 1) / P + 1, span = (1LL << 31) - 64;
+    const int64_t P = (int64_t)OH * OW, tile_images = (256 + P - 1) / P + 1, span = (1LL << 31) - 64;
     if (tile_images * p.ic.image_stride * 2 >= span || (256 * P + tile_images * p.y_img) * 4 >= span || (int64_t)256 * p.K * 2 >= span)
         return false;
     Im2colGeom& g = p.ic;
@@ -361,9 +368,11 @@ bool launch_conv_window_lp(ContractionParams& p, int kH, int kW, int OH, int OW,
         const int64_t plane = (int64_t)patch_rows(k.bn, OH, OW, g.sH, E) * PC;
         if (2 * plane > (int64_t)k.max_units * k.nt) continue;
         const double tiles = (double)((p.M + k.bm - 1) / k.bm) * (double)((p.N + k.bn - 1) / k.bn) * nz;
-        double rounds = tiles / 256.0;
+        double rounds = tiles / k.resident;
         if (rounds < 1.0) rounds = 1.0;
-        const double cost = rounds * k.bm * k.bn / (k.bm >= 128 ? 1.0 : 0.6);
+        // every pass over the patch units beyond the first adds loads and LDS stores to each K step
+        const int64_t passes = (2 * plane + k.nt - 1) / k.nt;
+        const double cost = rounds * k.weight * (1.0 + 0.25 * (double)(passes - 1));
         if (best < 0 || cost < best_cost) { best = c; best_cost = cost; best_plane = (int)plane; }
     }
     if (best < 0) return false;

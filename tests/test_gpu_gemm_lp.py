@@ -340,12 +340,13 @@ CONV3X3_LP_CASES = [
     (3, 64, 18, 22, 72, (0, 2, 1, 1), (1, 2), (2, 1), 2, "64x64x144 2 2"),        # even left pad: no column shift
     (5, 32, 28, 28, 200, (1, 1, 1, 1), (1, 1), (1, 1), 1, "64x64x144 2 1"),       # tiles that span images
     (3, 128, 14, 14, 128, (1, 1, 1, 1), (1, 1), (1, 1), 1, "64x64x144 2 1"),      # K = 1152: eight steps
-    (40, 16, 30, 31, 128, (1, 1, 1, 1), (1, 1), (1, 3), 1, "128x128x144 1 4"),    # enough tiles for the 128 x 128 tile
-    (40, 16, 25, 51, 128, (1, 1, 1, 1), (2, 1), (2, 2), 1, "128x128x144 1 8"),
-    (210, 16, 7, 7, 256, (1, 1, 1, 1), (1, 1), (1, 1), 1, "128x128x144 1 2"),
+    (40, 16, 30, 31, 128, (1, 1, 1, 1), (1, 1), (1, 3), 1, "128x128x144 1 2"),    # enough tiles for the 128 x 128 tile
+    (40, 16, 25, 51, 128, (1, 1, 1, 1), (2, 1), (2, 2), 1, "128x128x144 1 4"),
+    (210, 16, 7, 7, 256, (1, 1, 1, 1), (1, 1), (1, 1), 1, "128x128x144 1 2"),     # tiles that span three or four images
     (160, 16, 10, 10, 256, (0, 0, 0, 0), (1, 1), (1, 1), 1, "128x128x144 2 1"),
-    (40, 16, 20, 20, 256, (1, 1, 1, 1), (1, 1), (1, 3), 1, "128x128x144 2 2"),
-    (40, 16, 24, 50, 128, (1, 1, 1, 1), (2, 1), (2, 2), 1, "128x128x144 2 4"),
+    (40, 16, 20, 20, 256, (1, 1, 1, 1), (1, 1), (1, 3), 1, "128x128x144 2 1"),
+    (40, 16, 24, 50, 128, (1, 1, 1, 1), (2, 1), (2, 2), 1, "128x128x144 2 2"),
+    (70, 32, 14, 14, 300, (1, 1, 1, 1), (1, 1), (1, 1), 2, "128x128x144 2 1"),    # two groups of 150 filters: a ragged second row of tiles
 ]
 
 
