@@ -299,7 +299,7 @@ def main():
                 details["gemm_%s_%d" % (kind, n)] = dict(timing(t3), tflops=round(tf, 1),
                                                          frac_mfma_peak_16bit=round(tf / MFMA_16BIT_PEAK_TFLOPS, 4))
                 del A16, B16, C32, Y16
-        # 16-bit MatMul and Conv through the general transposing kernel (any layout; not the tuned Gemm path)
+        # 16-bit MatMul and Conv (row-contiguous B through the tuned Gemm kernel; the 3x3 through the LDS-patch kernel)
         A16 = torch.randn(8, 512, 768, device=dev).to(torch.bfloat16)
         B16 = torch.randn(768, 3072, device=dev).to(torch.bfloat16)
         Y16 = torch.empty(8, 512, 3072, device=dev, dtype=torch.bfloat16)
