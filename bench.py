@@ -97,6 +97,47 @@ def profile_kernels(torch, lib, workloads, dev, with_copy):
     print(json.dumps({"profile_kernels": out}))
 
 
+CONV_LP_SHAPES = (
+    # name, N, C, H, W, M, stride, dilation: ResNet-50's 3x3 layers at batch 32, a dilated and a large one
+    ("56x56_64", 32, 64, 56, 56, 64, 1, 1),
+    ("28x28_128", 32, 128, 28, 28, 128, 1, 1),
+    ("14x14_256", 32, 256, 14, 14, 256, 1, 1),
+    ("7x7_512", 32, 512, 7, 7, 512, 1, 1),
+    ("56x56_128_stride2", 32, 128, 56, 56, 128, 2, 1),
+    ("64x64_256_dilation2", 8, 256, 64, 64, 256, 1, 2),
+    ("56x56_256_batch64", 64, 256, 56, 56, 256, 1, 1),
+)
+
+
+def profile_conv_lp(torch, lib, dev):
+    """3x3 convolutions on bf16 tensors (bf16 result, Relu), each 3 untimed + 5 timed calls."""
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device=dev)
+    lib.onnx_set_workspace(ws)
+    g = torch.Generator(device="cpu").manual_seed(11)
+    out = {}
+    for name, n, c, h, w, m, st, dl in CONV_LP_SHAPES:
+        X = torch.randn(n, c, h, w, generator=g).to(dev).to(torch.bfloat16)
+        W = (torch.randn(m, c, 3, 3, generator=g) * (2.0 / (9 * c)) ** 0.5).to(dev).to(torch.bfloat16)
+        Bv = torch.zeros(m, device=dev)
+        pads, strides, dil = (dl, dl, dl, dl), (st, st), (dl, dl)
+        Y = torch.empty(lib.onnx_conv_infer(X.shape, W.shape, pads, strides, dil), dtype=torch.bfloat16, device=dev)
+        fn = lambda: lib.onnx_conv_lp(X, W, Bv, pads, strides, dil, 1, act=1, out=Y)
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 5
+        out[name] = {"ms": round(ms, 4), "tflops": round(2.0 * Y.numel() * 9 * c / (ms * 1e-3) / 1e12, 1),
+                     "launch": lib.onnx_last_launch()}
+        del X, W, Y
+    print(json.dumps({"profile_conv_lp": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -111,6 +152,9 @@ def main():
                     help="run only the four launches whose hardware counters are summarised under profiles/ "
                          "(Gemm 4096^3, 3x3 conv 32x64x56x56, dilated 3x3 conv, depthwise 3x3 conv), a few "
                          "times each, print their mean times and exit")
+    ap.add_argument("--profile-conv-lp", action="store_true",
+                    help="run only the 3x3 convolutions on bf16 tensors whose kernel trace and counters are summarised "
+                         "under profiles/, a few times each, print their mean times and exit")
     ap.add_argument("--profile-resnet", type=int, nargs="?", const=32, default=0, metavar="BATCH",
                     help="run only ResNet-50 at the given batch (default 32; 3 untimed + 10 timed passes, one call per "
                          "node), print the mean time and exit: the run behind the per-kernel traces under profiles/")
@@ -134,6 +178,9 @@ def main():
 
     if args.profile_kernels:
         profile_kernels(torch, lib, workloads, dev, with_copy=args.copy_calibration)
+        return
+    if args.profile_conv_lp:
+        profile_conv_lp(torch, lib, dev)
         return
     if args.profile_resnet:
         from paper_2008_08272_amd.runner import GraphRunner
