@@ -31,7 +31,8 @@ constexpr int LPW_KA = LPW_CB * LPW_TAPS;     // filter values per row per step:
 constexpr int LPW_CPR = LPW_KA / 8;           // 16-byte chunks per row per step: chunk q = tap * 2 + channel half
 constexpr int LPW_LDA = LPW_KA * 2 + 16;      // bytes per LDS row: 16-byte reads of 16 neighbouring rows hit disjoint banks
 
-// W [rows][Cg][9] -> P [rows][Cg/16][9][16], one 16-byte chunk of P per thread.
+// W [rows][Cg][9] -> P [rows][Cg/16][9][16], one 16-byte chunk of P per thread.  (A thread per 288-byte
+// row block with 16-byte loads and the pairing done in registers was slower: 5-10 us against 2.5-7, too few threads.)
 __global__ __launch_bounds__(256) void lp_filter_taps_kernel(const uint16_t* __restrict__ W, uint16_t* __restrict__ P,
                                                             int64_t chunks, int Cg) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;

@@ -411,6 +411,33 @@ def test_conv3x3_16bit_lds_patch_matches_oracle(lib, lp_workspace, case, kind):
     assert np.array_equal(goti.cpu().numpy().astype(np.float64), refi)
 
 
+def test_conv3x3_16bit_lds_patch_operands_off_alignment(lib, lp_workspace):
+    """X two bytes off a 4-byte boundary: single-column loads although the rows have even length.  W at any
+    2-byte offset: the filter bank is rewritten with 2-byte loads.  Same results."""
+    announce("conv_lp 3x3 misaligned")
+    rng = np.random.default_rng(5)
+    N, C, H, W, M = 3, 32, 12, 12, 72
+    pads, st, dl = (1, 1, 1, 1), (1, 1), (1, 1)
+    for kind in ("f16", "bf16"):
+        xb, xv = encode(rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32), kind)
+        wb, wv = encode(rng.uniform(-1, 1, (M, C, 3, 3)).astype(np.float32), kind)
+        ref, S = oracle.conv(xv, wv, None, pads, st, dl, 1, want_scale=True)
+        for x_off, w_off, cols in ((1, 0, 1), (0, 1, 2), (1, 3, 1), (2, 8, 2)):
+            def shifted(bits, off):
+                flat = bits_to_dev(bits, kind).reshape(-1)
+                buf = torch.empty(flat.numel() + 16, dtype=flat.dtype, device="cuda")
+                buf[off:off + flat.numel()].copy_(flat)
+                return buf[off:off + flat.numel()].view(bits.shape)
+            X, Wt = shifted(xb, x_off), shifted(wb, w_off)
+            assert X.data_ptr() % 4 == (2 * x_off) % 4 and Wt.data_ptr() % 16 == (2 * w_off) % 16
+            got = lib.onnx_conv_lp(X, Wt, None, pads, st, dl, 1, out_dtype=torch.float32)
+            torch.cuda.synchronize()
+            launch = lib.onnx_last_launch()
+            assert launch.startswith("conv_window_lp 64x64x144") and "B=IM2COL/%d " % cols in launch, launch
+            gth = got.cpu().numpy()
+            assert rel_err(gth, ref) <= REL_TOL and within_rounding_bound(gth, ref, S, C * 9 + 1)
+
+
 def test_conv3x3_16bit_workspace_too_small_or_channels_not_16(lib, lp_workspace):
     """The LDS-patch kernel needs room for the rewritten filter bank and 16 | channels per group; otherwise the
     general kernel runs, with the same result up to summation order."""
