@@ -275,7 +275,12 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_lp_kernel(const Cont
         if (ks + 1 < ks1) step(ks + 1, Set1{}, Set0{});
     }
     // (the launcher never splits K for this kernel)
-    if constexpr (LP_OUT) store_tile_lp<DT, TM, TN, WTM, WTN>(acc, w, wm, wn, li, h, cp);
+    if constexpr (LP_OUT) {
+        static_assert(WM * WN * lp_strip_bytes<WTN>() <= 2 * (BM * LPW_LDA + 16), "the strips of the epilogue fit in the filter buffers");
+        __syncthreads();                             // every wavefront is done reading the operand buffers
+        store_tile_lp<DT, TM, TN, WTM, WTN>(acc, w, wm, wn, li, h, cp,
+                                            reinterpret_cast<float*>(&lds_a[0][0] + wave * lp_strip_bytes<WTN>()));
+    }
     else finish_tile<TM, TN, WTM, WTN, NT>(acc, w, wm, wn, li, h, cp);
 }
 

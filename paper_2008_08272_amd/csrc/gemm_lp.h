@@ -23,6 +23,7 @@ namespace onnxhip {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 
 enum { LP_F16 = 1, LP_BF16 = 2 };
 
@@ -322,9 +323,143 @@ __device__ __forceinline__ void store_tile_lp_as(const floatx16 (&acc)[TM][TN], 
     }
 }
 
+// The same epilogue with whole rows: a wavefront passes each 32-row strip of its WTM x WTN sub-tile
+// through a piece of LDS of its own (`strip`, 32 x (WTN + 4) floats; no barrier, the wavefront
+// reads back what it wrote), after which a lane owns CW = 8 (or 4) consecutive columns of one row:
+// one 16-byte (8-byte) load of the residual, one such store, WTN / CW lanes next to each other
+// covering a row of the sub-tile (128 contiguous bytes for a sub-tile 64 columns wide) instead of
+// 4-byte words scattered over four rows.  Same arithmetic as store_tile_lp_as, in the same order except with a per-column bias.  Needs every group of 8
+// columns that starts at a multiple of 8 to be contiguous in Y and 16-byte aligned (see
+// store_tile_lp), and a bias that is per row or per column with unit stride.
+template <int DT, int TM, int TN, int WTM, int WTN, bool HAS_RES, int CW>
+__device__ __forceinline__ void store_tile_lp_rows(const floatx16 (&acc)[TM][TN], const TileWork& w, int wm, int wn, int lane,
+                                                   const ContractionParams& cp, float* strip) {
+    constexpr int PITCH = WTN + 4;            // floats: the 16-byte reads of two neighbouring rows hit disjoint banks
+    constexpr int CPR = WTN / CW;             // chunks of CW columns per row
+    typedef uint32_t chunk_t __attribute__((ext_vector_type(CW / 2)));
+    static_assert(CW == 8 || CW == 4, "16-byte or 8-byte chunks");
+    constexpr int RPP = 64 / CPR;             // rows per pass of the wavefront
+    static_assert(WTN % 32 == 0 && 32 % RPP == 0, "strip shape");
+    const int li = lane & 31, h = lane >> 5;
+    const int64_t zi = w.zslice;
+    int64_t tile_off = (int64_t)w.m0 * cp.y_rs + w.n0;
+    uint32_t img0 = 0, px0 = 0;
+    if (cp.col_images) {
+        cp.colP.divmod((uint32_t)w.n0, img0, px0);
+        tile_off = (int64_t)w.m0 * cp.y_rs + (int64_t)img0 * cp.y_img + px0;
+    }
+    tile_off = scalar(tile_off + zi * cp.y_zs);
+    img0 = (uint32_t)scalar((int)img0);
+    px0 = (uint32_t)scalar((int)px0);
+    uint16_t* Y = reinterpret_cast<uint16_t*>(cp.Y);
+    const uint16_t* R = reinterpret_cast<const uint16_t*>(cp.residual);
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(Y + tile_off, 0, (int)OOB, RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(HAS_RES ? R + tile_off : Y + tile_off), 0, (int)OOB, RSRC_FLAGS);
+    const int mode = cp.bias ? cp.bias_mode : BIAS_NONE;
+    const float* bias = cp.bias ? cp.bias + zi * cp.bias_zs : nullptr;
+    const __amdgpu_buffer_rsrc_t rrow = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(mode == BIAS_ROW ? bias : reinterpret_cast<const float*>(Y)), 0,
+                                                                          mode == BIAS_ROW ? cp.M * 4 : 0, RSRC_FLAGS);
+    const bool relu = cp.relu != 0;
+    // this lane's chunk of 8 columns, the same in every pass
+    const int cc = lane % CPR, rsub = lane / CPR;
+    const int cl = wn * WTN + cc * CW;
+    const int col = w.n0 + cl;
+    const bool col_ok = col < cp.N;           // N is a multiple of CW: all columns of the chunk exist or none
+    int crel = cl;
+    if (cp.col_images) {
+        uint32_t n, px;
+        cp.colP.divmod((uint32_t)(col_ok ? col : w.n0), n, px);
+        crel = (int)(n - img0) * (int)cp.y_img + (int)px - (int)px0;
+    }
+    // A per-column bias is added on the way into the strip, where a lane holds one column per block (one value
+    // per block instead of eight per lane afterwards): alpha * acc + bias is rounded there and the residual added
+    // to it, where the other bias kinds add bias and residual first.
+    const bool colmode = mode == BIAS_COL;
+    float col_bias[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int c = w.n0 + wn * WTN + j * 32 + li;
+        col_bias[j] = (colmode && c < cp.N) ? cp.beta * bias[c] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        constexpr int NPASS = 32 / RPP;
+        // what the passes of this strip need from memory, all requested before the strip goes through LDS
+        int off[NPASS];
+        float row_bias[NPASS];
+        chunk_t res[NPASS];
+#pragma unroll
+        for (int pass = 0; pass < NPASS; ++pass) {
+            const int row_in_tile = wm * WTM + i * 32 + pass * RPP + rsub;
+            const int row = w.m0 + row_in_tile;
+            off[pass] = (col_ok && row < cp.M) ? (row_in_tile * (int)cp.y_rs + crel) * 2 : (int)OOB;
+            row_bias[pass] = 0.f;
+            if (mode == BIAS_ROW) row_bias[pass] = cp.beta * __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rrow, row * 4, 0, 0));
+            if constexpr (HAS_RES) {
+                if constexpr (CW == 8) res[pass] = __builtin_bit_cast(chunk_t, __builtin_amdgcn_raw_buffer_load_b128(rr, off[pass], 0, 0));
+                else res[pass] = __builtin_bit_cast(chunk_t, __builtin_amdgcn_raw_buffer_load_b64(rr, off[pass], 0, 0));
+            }
+        }
+        // register r of block (i, j) is row 4h + 8*(r/4) + r%4, column j*32 + li of the strip
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                strip[(4 * h + 8 * (r / 4) + (r % 4)) * PITCH + j * 32 + li] = colmode ? fmaf(cp.alpha, acc[i][j][r], col_bias[j]) : acc[i][j][r];
+#pragma unroll
+        for (int pass = 0; pass < NPASS; ++pass) {
+            const int rl = pass * RPP + rsub;
+            float a[CW];
+#pragma unroll
+            for (int q = 0; q < CW / 4; ++q) {
+                const floatx4 v = *reinterpret_cast<const floatx4*>(strip + rl * PITCH + cc * CW + 4 * q);
+                a[4 * q] = v.x; a[4 * q + 1] = v.y; a[4 * q + 2] = v.z; a[4 * q + 3] = v.w;
+            }
+            chunk_t out;
+#pragma unroll
+            for (int k = 0; k < CW / 2; ++k) {
+                float add0 = row_bias[pass], add1 = row_bias[pass];
+                if constexpr (HAS_RES) {
+                    add0 += from_lp<DT>(res[pass][k] & 0xffffu);
+                    add1 += from_lp<DT>(res[pass][k] >> 16);
+                }
+                const float l0 = colmode ? a[2 * k] + add0 : fmaf(cp.alpha, a[2 * k], add0);
+                const float l1 = colmode ? a[2 * k + 1] + add1 : fmaf(cp.alpha, a[2 * k + 1], add1);
+                const uint32_t c0 = to_lp<DT>(relu ? fmaxf(l0, 0.f) : l0), c1 = to_lp<DT>(relu ? fmaxf(l1, 0.f) : l1);
+                out[k] = c0 | (c1 << 16);
+            }
+            if constexpr (CW == 8) __builtin_amdgcn_raw_buffer_store_b128(out, ry, off[pass], 0, 0);
+            else __builtin_amdgcn_raw_buffer_store_b64(out, ry, off[pass], 0, 0);
+        }
+        // one strip at a time: loads hoisted across strips would keep their registers live through the whole epilogue
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// LDS bytes a wavefront's strip takes in store_tile_lp_rows.
+template <int WTN>
+constexpr int lp_strip_bytes() { return 32 * (WTN + 4) * 4; }
+
+// `strip`: this wavefront's lp_strip_bytes<WTN>() of LDS that nothing else uses any more (the caller
+// has passed a barrier behind the last read of its operand buffers), or nullptr.
 template <int DT, int TM, int TN, int WTM, int WTN>
 __device__ __forceinline__ void store_tile_lp(const floatx16 (&acc)[TM][TN], const TileWork& w, int wm, int wn, int li, int h,
-                                              const ContractionParams& cp) {
+                                              const ContractionParams& cp, float* strip = nullptr) {
+    // whole rows: every aligned group of 8 (or 4) columns contiguous in Y (and the residual) and on a 16-byte (8-byte) boundary
+    const int64_t strides = cp.N | cp.y_rs | cp.y_zs | (cp.col_images ? (int64_t)cp.colP.d | cp.y_img : 0);
+    const uintptr_t bases = reinterpret_cast<uintptr_t>(cp.Y) | reinterpret_cast<uintptr_t>(cp.residual);
+    const int bmode = cp.bias ? cp.bias_mode : BIAS_NONE;
+    const bool rows_ok = strip != nullptr && bmode != BIAS_FULL && (bmode != BIAS_COL || cp.bias_cs == 1);
+    if (rows_ok && (strides & 7) == 0 && (bases & 15u) == 0) {
+        if (cp.residual) store_tile_lp_rows<DT, TM, TN, WTM, WTN, true, 8>(acc, w, wm, wn, li + 32 * h, cp, strip);
+        else store_tile_lp_rows<DT, TM, TN, WTM, WTN, false, 8>(acc, w, wm, wn, li + 32 * h, cp, strip);
+        return;
+    }
+    if (rows_ok && (strides & 3) == 0 && (bases & 7u) == 0) {
+        if (cp.residual) store_tile_lp_rows<DT, TM, TN, WTM, WTN, true, 4>(acc, w, wm, wn, li + 32 * h, cp, strip);
+        else store_tile_lp_rows<DT, TM, TN, WTM, WTN, false, 4>(acc, w, wm, wn, li + 32 * h, cp, strip);
+        return;
+    }
     // Copies of the epilogue rather than tests per element; all must be inlined: a call would pass the
     // accumulators through memory.  Pairs need every (row, even column) of Y and of the residual on a
     // 4-byte boundary and both columns of a pair in the same row or image.
@@ -448,8 +583,14 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_lp_kernel(const Contraction
     }
 
     // (the launcher never splits K for this kernel, so a 16-bit result has no partial-sum form)
-    if constexpr (LP_OUT) store_tile_lp<DT, TM, TN, WTM, WTN>(acc, w, wm, wn, li, h, cp);
-    else finish_tile<TM, TN, WTM, WTN, NT>(acc, w, wm, wn, li, h, cp);
+    if constexpr (LP_OUT) {
+        static_assert(WM * WN * lp_strip_bytes<WTN>() <= 2 * ALoader::LDS_BYTES, "the strips of the epilogue fit in A's buffers");
+        __syncthreads();                             // every wavefront is done reading the operand buffers
+        store_tile_lp<DT, TM, TN, WTM, WTN>(acc, w, wm, wn, li, h, cp,
+                                            reinterpret_cast<float*>(&lds_a[0][0] + wave * lp_strip_bytes<WTN>()));
+    } else {
+        finish_tile<TM, TN, WTM, WTN, NT>(acc, w, wm, wn, li, h, cp);
+    }
 }
 
 }  // namespace onnxhip
