@@ -311,6 +311,14 @@ def main():
                                                    sum_of_layer_rooflines_ms=round(floor_ms, 4),
                                                    frac_of_layer_rooflines=round(floor_ms / ms, 4))
             del r
+        # the same network on bf16 tensors (weights and activations in bf16, fp32 accumulation, fp32 logits)
+        m = workloads.resnet50(32)
+        st = workloads.graph_stats(m)
+        r = GraphRunner(m, dev, dtype=torch.bfloat16)
+        t3 = time_call(r.run, iters=20, warm=5)
+        details["resnet50_b32_bf16"] = dict(timing(t3), img_per_s=round(32 / (t3[0] * 1e-3), 1),
+                                            tflops=round(2.0 * st["macs"] / (t3[0] * 1e-3) / 1e12, 2))
+        del r
         # the MNIST-shaped small CNN (1.6 MFLOP): one call per node (5 launches: pure launch latency) and the
         # whole model as one launch (onnx_chain: weights and activations in LDS), at batch 1 and one workgroup
         # per image at batch 64

@@ -286,6 +286,23 @@ onnx_status onnx_conv_lp(const void* X, const int64_t x_dims[4], const void* W, 
                          void* stream);
 
 /*
+ * ONNX MaxPool and AveragePool / GlobalAveragePool on 16-bit tensors (type ONNX_F16 or
+ * ONNX_BF16 for X and Y alike): what lies between the 16-bit convolutions of a network whose
+ * activations stay in the 16-bit type.  Semantics, attributes, limits and errors of
+ * onnx_maxpool (without Indices) and onnx_avgpool.  The maximum is stored with the bits of the
+ * winning input; an average is summed in fp32 in scan order, divided, and rounded to the type
+ * once (nearest even).  At most 2^31-1 output elements.
+ */
+onnx_status onnx_maxpool_lp(const void* X, const int64_t x_dims[4], const int64_t kernel[2],
+                            const int64_t pads[4], const int64_t strides[2],
+                            const int64_t dilations[2], int ceil_mode, void* Y,
+                            const int64_t y_dims[4], onnx_dtype type, void* stream);
+onnx_status onnx_avgpool_lp(const void* X, const int64_t x_dims[4], const int64_t* kernel,
+                            const int64_t* pads, const int64_t* strides, int ceil_mode,
+                            int count_include_pad, void* Y, const int64_t y_dims[4],
+                            onnx_dtype type, void* stream);
+
+/*
  * ONNX LSTM (named among the supported operators, Section 4.1), layout 0, default activations
  * (sigmoid, tanh, tanh), no peepholes, every sequence of full length.  X [seq, batch, input];
  * W [dirs, 4H, input] and R [dirs, 4H, H] with the gate blocks in the order i, o, f, c;

@@ -50,8 +50,11 @@ _lib.onnx_gemm.argtypes = [_vp, _i64p, _vp, _i64p, _vp, _i64p, _ci, _cf, _cf, _c
 _lib.onnx_matmul.argtypes = [_vp, _i64p, _ci, _vp, _i64p, _ci, _vp, _i64p, _ci, _vp]
 _lib.onnx_maxpool.argtypes = [_vp, _i64p, _i64p, _i64p, _i64p, _i64p, _ci, _vp, _vp, _i64p, _vp]
 _lib.onnx_avgpool.argtypes = [_vp, _i64p, _i64p, _i64p, _i64p, _ci, _ci, _vp, _i64p, _vp]
+_lib.onnx_maxpool_lp.argtypes = [_vp, _i64p, _i64p, _i64p, _i64p, _i64p, _ci, _vp, _i64p, _ci, _vp]
+_lib.onnx_avgpool_lp.argtypes = [_vp, _i64p, _i64p, _i64p, _i64p, _ci, _ci, _vp, _i64p, _ci, _vp]
 for _f in (_lib.onnx_conv_infer, _lib.onnx_pool_infer, _lib.onnx_matmul_infer, _lib.onnx_conv,
-           _lib.onnx_gemm, _lib.onnx_matmul, _lib.onnx_maxpool, _lib.onnx_avgpool):
+           _lib.onnx_gemm, _lib.onnx_matmul, _lib.onnx_maxpool, _lib.onnx_avgpool, _lib.onnx_maxpool_lp,
+           _lib.onnx_avgpool_lp):
     _f.restype = _ci
 
 _ip = ctypes.POINTER(_ci)
@@ -383,6 +386,31 @@ def onnx_conv_lp(X, W, B=None, pads=(0, 0, 0, 0), strides=(1, 1), dilations=(1, 
     _check(_lib.onnx_conv_lp(_ptr(X), dims(X.shape), _ptr(W), dims(W.shape), _ptr(B), dims(pads), dims(strides),
                              dims(dilations), int(group), _ptr(residual), int(act), _ptr(Y), dims(Y.shape),
                              _LP_TYPES[X.dtype], ot, _stream(stream)))
+    return Y
+
+
+def onnx_maxpool_lp(X, kernel, pads=(0, 0, 0, 0), strides=(1, 1), dilations=(1, 1), ceil_mode=0, out=None, stream=None):
+    """MaxPool on a float16 / bfloat16 CUDA tensor; the result has the same type."""
+    X = _lp(X, "X")
+    Y, _ = _lp_out(out, onnx_pool_infer(X.shape, kernel, pads, strides, dilations, ceil_mode), X.dtype, X)
+    _check(_lib.onnx_maxpool_lp(_ptr(X), dims(X.shape), dims(kernel), dims(pads), dims(strides), dims(dilations),
+                                int(ceil_mode), _ptr(Y), dims(Y.shape), _LP_TYPES[X.dtype], _stream(stream)))
+    return Y
+
+
+def onnx_avgpool_lp(X, kernel=None, pads=(0, 0, 0, 0), strides=(1, 1), ceil_mode=0, count_include_pad=0, out=None,
+                    stream=None):
+    """AveragePool (kernel=None: GlobalAveragePool) on a float16 / bfloat16 CUDA tensor; the result has the same type."""
+    X = _lp(X, "X")
+    if kernel is None:
+        yd = (X.shape[0], X.shape[1], 1, 1)
+        kp = pp = sp = None
+    else:
+        yd = onnx_pool_infer(X.shape, kernel, pads, strides, (1, 1), ceil_mode)
+        kp, pp, sp = dims(kernel), dims(pads), dims(strides)
+    Y, _ = _lp_out(out, yd, X.dtype, X)
+    _check(_lib.onnx_avgpool_lp(_ptr(X), dims(X.shape), kp, pp, sp, int(ceil_mode), int(count_include_pad),
+                                _ptr(Y), dims(Y.shape), _LP_TYPES[X.dtype], _stream(stream)))
     return Y
 
 

@@ -568,10 +568,16 @@ onnx_status onnx_conv_lp(const void* X, const int64_t x_dims[4], const void* W, 
                                &ws, 0, stream, in_type, out_type);
 }
 
-onnx_status onnx_maxpool(const float* X, const int64_t x_dims[4], const int64_t kernel[2],
-                         const int64_t pads[4], const int64_t strides[2], const int64_t dilations[2],
-                         int ceil_mode, float* Y, int64_t* Indices, const int64_t y_dims[4], void* stream) {
+}  // extern "C"
+
+namespace {
+
+// ONNX MaxPool on fp32 tensors (type ONNX_F32, optional Indices) or on 16-bit tensors (no Indices).
+onnx_status maxpool_any(const void* X, const int64_t x_dims[4], const int64_t kernel[2],
+                        const int64_t pads[4], const int64_t strides[2], const int64_t dilations[2],
+                        int ceil_mode, void* Y, int64_t* Indices, const int64_t y_dims[4], onnx_dtype type, void* stream) {
     if (!x_dims || !y_dims) return fail(ONNX_ERR_NULL, "maxpool: NULL dims array");
+    const int64_t esz = type == ONNX_F32 ? 4 : 2;
     int64_t yd[4];
     const onnx_status st = onnx_pool_infer(x_dims, kernel, pads, strides, dilations, ceil_mode, yd);
     if (st != ONNX_OK) return st;
@@ -582,7 +588,7 @@ onnx_status onnx_maxpool(const float* X, const int64_t x_dims[4], const int64_t 
     const int64_t ny = yd[0] * yd[1] * yd[2] * yd[3], nx = x_dims[0] * x_dims[1] * x_dims[2] * x_dims[3];
     if (ny == 0) return ONNX_OK;
     if (!X || !Y) return fail(ONNX_ERR_NULL, "maxpool: X and Y must not be NULL");
-    if (overlaps(Y, ny * 4, X, nx * 4) || overlaps(Indices, ny * 8, X, nx * 4) || overlaps(Indices, ny * 8, Y, ny * 4))
+    if (overlaps(Y, ny * esz, X, nx * esz) || overlaps(Indices, ny * 8, X, nx * esz) || overlaps(Indices, ny * 8, Y, ny * esz))
         return fail(ONNX_ERR_ALIAS, "maxpool: outputs overlap X or each other");
     const int64_t d0 = dilations ? dilations[0] : 1, d1 = dilations ? dilations[1] : 1;
     if (x_dims[2] * x_dims[3] > kIntMax || x_dims[0] > kIntMax || x_dims[1] > kIntMax ||
@@ -594,13 +600,20 @@ onnx_status onnx_maxpool(const float* X, const int64_t x_dims[4], const int64_t 
     g.OH = (int)yd[2]; g.OW = (int)yd[3]; g.kH = (int)kernel[0]; g.kW = (int)kernel[1];
     g.sH = (int)strides[0]; g.sW = (int)strides[1]; g.pT = (int)pads[0]; g.pL = (int)pads[1];
     g.pB = (int)pads[2]; g.pR = (int)pads[3]; g.dH = (int)d0; g.dW = (int)d1;
-    return device_status(launch_maxpool(X, Y, Indices, g, static_cast<hipStream_t>(stream)), "maxpool");
+    if (type != ONNX_F32) {
+        if (ny > kIntMax) return fail(ONNX_ERR_UNSUPPORTED, "maxpool (16-bit): more than 2^31-1 output elements");
+        return device_status(launch_maxpool_lp(X, Y, g, (int)type, static_cast<hipStream_t>(stream)), "maxpool (16-bit)");
+    }
+    return device_status(launch_maxpool(static_cast<const float*>(X), static_cast<float*>(Y), Indices, g,
+                                        static_cast<hipStream_t>(stream)), "maxpool");
 }
 
-onnx_status onnx_avgpool(const float* X, const int64_t x_dims[4], const int64_t* kernel, const int64_t* pads,
-                         const int64_t* strides, int ceil_mode, int count_include_pad, float* Y,
-                         const int64_t y_dims[4], void* stream) {
+// ONNX AveragePool / GlobalAveragePool on fp32 or 16-bit tensors.
+onnx_status avgpool_any(const void* X, const int64_t x_dims[4], const int64_t* kernel, const int64_t* pads,
+                        const int64_t* strides, int ceil_mode, int count_include_pad, void* Y,
+                        const int64_t y_dims[4], onnx_dtype type, void* stream) {
     if (!x_dims || !y_dims) return fail(ONNX_ERR_NULL, "avgpool: NULL dims array");
+    const int64_t esz = type == ONNX_F32 ? 4 : 2;
     for (int i = 0; i < 4; ++i)
         if (x_dims[i] < 0) return fail(ONNX_ERR_SHAPE, "avgpool: negative dimension");
     const int64_t nx = x_dims[0] * x_dims[1] * x_dims[2] * x_dims[3];
@@ -613,10 +626,13 @@ onnx_status onnx_avgpool(const float* X, const int64_t x_dims[4], const int64_t*
         const int64_t planes = x_dims[0] * x_dims[1];
         if (planes == 0) return ONNX_OK;
         if (!X || !Y) return fail(ONNX_ERR_NULL, "avgpool: X and Y must not be NULL");
-        if (overlaps(Y, planes * 4, X, nx * 4)) return fail(ONNX_ERR_ALIAS, "avgpool: Y overlaps X");
+        if (overlaps(Y, planes * esz, X, nx * esz)) return fail(ONNX_ERR_ALIAS, "avgpool: Y overlaps X");
         if (x_dims[2] * x_dims[3] > kIntMax) return fail(ONNX_ERR_UNSUPPORTED, "avgpool: plane above 2^31-1 elements");
-        return device_status(launch_global_avgpool(X, Y, planes, (int)(x_dims[2] * x_dims[3]), s),
-                             "avgpool (global)");
+        if (type != ONNX_F32)
+            return device_status(launch_global_avgpool_lp(X, Y, planes, (int)(x_dims[2] * x_dims[3]), (int)type, s),
+                                 "avgpool (global, 16-bit)");
+        return device_status(launch_global_avgpool(static_cast<const float*>(X), static_cast<float*>(Y), planes,
+                                                   (int)(x_dims[2] * x_dims[3]), s), "avgpool (global)");
     }
     const int64_t zero4[4] = {0, 0, 0, 0}, one2[2] = {1, 1};
     if (!pads) pads = zero4;
@@ -631,7 +647,7 @@ onnx_status onnx_avgpool(const float* X, const int64_t x_dims[4], const int64_t*
     const int64_t ny = yd[0] * yd[1] * yd[2] * yd[3];
     if (ny == 0) return ONNX_OK;
     if (!X || !Y) return fail(ONNX_ERR_NULL, "avgpool: X and Y must not be NULL");
-    if (overlaps(Y, ny * 4, X, nx * 4)) return fail(ONNX_ERR_ALIAS, "avgpool: Y overlaps X");
+    if (overlaps(Y, ny * esz, X, nx * esz)) return fail(ONNX_ERR_ALIAS, "avgpool: Y overlaps X");
     if (x_dims[2] * x_dims[3] > kIntMax || x_dims[0] > kIntMax || x_dims[1] > kIntMax ||
         x_dims[1] * yd[2] * yd[3] >= (1LL << 30) || kernel[0] > kIntMax || kernel[1] > kIntMax ||
         strides[0] > kIntMax || strides[1] > kIntMax)
@@ -641,7 +657,41 @@ onnx_status onnx_avgpool(const float* X, const int64_t x_dims[4], const int64_t*
     g.OH = (int)yd[2]; g.OW = (int)yd[3]; g.kH = (int)kernel[0]; g.kW = (int)kernel[1];
     g.sH = (int)strides[0]; g.sW = (int)strides[1]; g.pT = (int)pads[0]; g.pL = (int)pads[1];
     g.pB = (int)pads[2]; g.pR = (int)pads[3]; g.dH = 1; g.dW = 1;
-    return device_status(launch_avgpool(X, Y, g, count_include_pad, s), "avgpool");
+    if (type != ONNX_F32) {
+        if (ny > kIntMax) return fail(ONNX_ERR_UNSUPPORTED, "avgpool (16-bit): more than 2^31-1 output elements");
+        return device_status(launch_avgpool_lp(X, Y, g, count_include_pad, (int)type, s), "avgpool (16-bit)");
+    }
+    return device_status(launch_avgpool(static_cast<const float*>(X), static_cast<float*>(Y), g, count_include_pad, s), "avgpool");
+}
+
+}  // namespace
+
+extern "C" {
+
+onnx_status onnx_maxpool(const float* X, const int64_t x_dims[4], const int64_t kernel[2],
+                         const int64_t pads[4], const int64_t strides[2], const int64_t dilations[2],
+                         int ceil_mode, float* Y, int64_t* Indices, const int64_t y_dims[4], void* stream) {
+    return maxpool_any(X, x_dims, kernel, pads, strides, dilations, ceil_mode, Y, Indices, y_dims, ONNX_F32, stream);
+}
+
+onnx_status onnx_avgpool(const float* X, const int64_t x_dims[4], const int64_t* kernel, const int64_t* pads,
+                         const int64_t* strides, int ceil_mode, int count_include_pad, float* Y,
+                         const int64_t y_dims[4], void* stream) {
+    return avgpool_any(X, x_dims, kernel, pads, strides, ceil_mode, count_include_pad, Y, y_dims, ONNX_F32, stream);
+}
+
+onnx_status onnx_maxpool_lp(const void* X, const int64_t x_dims[4], const int64_t kernel[2],
+                            const int64_t pads[4], const int64_t strides[2], const int64_t dilations[2],
+                            int ceil_mode, void* Y, const int64_t y_dims[4], onnx_dtype type, void* stream) {
+    if (type != ONNX_F16 && type != ONNX_BF16) return fail(ONNX_ERR_ATTR, "maxpool_lp: type must be ONNX_F16 or ONNX_BF16");
+    return maxpool_any(X, x_dims, kernel, pads, strides, dilations, ceil_mode, Y, nullptr, y_dims, type, stream);
+}
+
+onnx_status onnx_avgpool_lp(const void* X, const int64_t x_dims[4], const int64_t* kernel, const int64_t* pads,
+                            const int64_t* strides, int ceil_mode, int count_include_pad, void* Y,
+                            const int64_t y_dims[4], onnx_dtype type, void* stream) {
+    if (type != ONNX_F16 && type != ONNX_BF16) return fail(ONNX_ERR_ATTR, "avgpool_lp: type must be ONNX_F16 or ONNX_BF16");
+    return avgpool_any(X, x_dims, kernel, pads, strides, ceil_mode, count_include_pad, Y, y_dims, type, stream);
 }
 
 }  // extern "C"

@@ -117,5 +117,9 @@ hipError_t launch_maxpool(const float* X, float* Y, int64_t* indices, const Wind
 hipError_t launch_avgpool(const float* X, float* Y, const WindowGeom& g, int count_include_pad,
                           hipStream_t stream);
 hipError_t launch_global_avgpool(const float* X, float* Y, int64_t planes, int HW, hipStream_t stream);
+// The pools on 16-bit tensors (window_lp.hip); `type` is ONNX_F16 / ONNX_BF16, N*C*OH*OW < 2^31.
+hipError_t launch_maxpool_lp(const void* X, void* Y, const WindowGeom& g, int type, hipStream_t stream);
+hipError_t launch_avgpool_lp(const void* X, void* Y, const WindowGeom& g, int count_include_pad, int type, hipStream_t stream);
+hipError_t launch_global_avgpool_lp(const void* X, void* Y, int64_t planes, int HW, int type, hipStream_t stream);
 
 }  // namespace onnxhip

@@ -1,0 +1,125 @@
+// MaxPool / AveragePool / GlobalAveragePool on 16-bit tensors (IEEE half or bfloat16): what a
+// network whose contractions run on 16-bit inputs (gemm_lp.h, conv_window_lp.hip) needs between
+// them so that its activations never leave the 16-bit type.  Same ONNX semantics as the fp32
+// pools (Section 4.1 of the paper lists pooling among the supported operators): the maximum is
+// one of the inputs and is stored with its bits unchanged; an average is summed in fp32 in scan
+// order, divided, and rounded to the type once.  Bandwidth-bound and small next to the
+// convolutions: one thread per output element (one wavefront per plane for the global average).
+#include "gemm_lp.h"
+#include "internal.h"
+
+namespace onnxhip {
+
+namespace {
+
+struct PoolIndex {
+    FastDiv OW, OH;
+};
+
+template <int DT>
+__global__ __launch_bounds__(256) void maxpool_lp_kernel(const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, WindowGeom g,
+                                                        PoolIndex d, uint32_t total) {
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= total) return;
+    uint32_t q, ow, plane, oh;
+    d.OW.divmod(idx, q, ow);
+    d.OH.divmod(q, plane, oh);
+    const int ih0 = (int)oh * g.sH - g.pT, iw0 = (int)ow * g.sW - g.pL;
+    const uint16_t* xc = X + (int64_t)plane * g.H * g.W;
+    // scan kh outer, kw inner; a later tap wins only when strictly greater (first maximum)
+    bool found = false;
+    float best = 0.f;
+    uint16_t best_bits = 0;
+    for (int kh = 0; kh < g.kH; ++kh) {
+        const int ih = ih0 + kh * g.dH;
+        if (ih < 0 || ih >= g.H) continue;
+        for (int kw = 0; kw < g.kW; ++kw) {
+            const int iw = iw0 + kw * g.dW;
+            if (iw < 0 || iw >= g.W) continue;
+            const uint16_t bits = xc[ih * g.W + iw];
+            const float v = from_lp<DT>(bits);
+            if (!found || v > best) { best = v; best_bits = bits; found = true; }
+        }
+    }
+    Y[idx] = best_bits;
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void avgpool_lp_kernel(const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, WindowGeom g,
+                                                        int count_include_pad, PoolIndex d, uint32_t total) {
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= total) return;
+    uint32_t q, ow, plane, oh;
+    d.OW.divmod(idx, q, ow);
+    d.OH.divmod(q, plane, oh);
+    const int ih0 = (int)oh * g.sH - g.pT, iw0 = (int)ow * g.sW - g.pL;
+    const uint16_t* xc = X + (int64_t)plane * g.H * g.W;
+    float acc = 0.f;
+    int cnt = 0, cnt_padded = 0;
+    for (int kh = 0; kh < g.kH; ++kh) {
+        const int ih = ih0 + kh;
+        if (ih >= g.H + g.pB) continue;
+        for (int kw = 0; kw < g.kW; ++kw) {
+            const int iw = iw0 + kw;
+            if (iw >= g.W + g.pR) continue;
+            ++cnt_padded;
+            if (ih < 0 || ih >= g.H || iw < 0 || iw >= g.W) continue;
+            acc += from_lp<DT>(xc[ih * g.W + iw]);
+            ++cnt;
+        }
+    }
+    Y[idx] = to_lp<DT>(acc / (float)(count_include_pad ? cnt_padded : cnt));
+}
+
+// One wavefront per (n, c) plane: lanes stride over the H*W contiguous values, the partial sums
+// meet in a butterfly of cross-lane moves, lane 0 stores the mean.
+template <int DT>
+__global__ __launch_bounds__(256) void global_avgpool_lp_kernel(const uint16_t* __restrict__ X, uint16_t* __restrict__ Y,
+                                                               int64_t planes, int HW) {
+    const int lane = threadIdx.x & 63;
+    const int64_t plane = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (plane >= planes) return;
+    const uint16_t* xp = X + plane * HW;
+    float acc = 0.f;
+    for (int i = lane; i < HW; i += 64) acc += from_lp<DT>(xp[i]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if (lane == 0) Y[plane] = to_lp<DT>(acc / (float)HW);
+}
+
+}  // namespace
+
+// X, Y: 16-bit tensors of `type` (LP_F16 / LP_BF16).  The caller has checked that N*C*OH*OW < 2^31.
+hipError_t launch_maxpool_lp(const void* X, void* Y, const WindowGeom& g, int type, hipStream_t stream) {
+    const uint32_t total = (uint32_t)((int64_t)g.N * g.C * g.OH * g.OW);
+    const PoolIndex d = {FastDiv::make((uint32_t)g.OW), FastDiv::make((uint32_t)g.OH)};
+    const dim3 grid((total + 255u) / 256u), block(256);
+    const uint16_t* x = static_cast<const uint16_t*>(X);
+    uint16_t* y = static_cast<uint16_t*>(Y);
+    if (type == LP_BF16) hipLaunchKernelGGL(maxpool_lp_kernel<LP_BF16>, grid, block, 0, stream, x, y, g, d, total);
+    else hipLaunchKernelGGL(maxpool_lp_kernel<LP_F16>, grid, block, 0, stream, x, y, g, d, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_avgpool_lp(const void* X, void* Y, const WindowGeom& g, int count_include_pad, int type, hipStream_t stream) {
+    const uint32_t total = (uint32_t)((int64_t)g.N * g.C * g.OH * g.OW);
+    const PoolIndex d = {FastDiv::make((uint32_t)g.OW), FastDiv::make((uint32_t)g.OH)};
+    const dim3 grid((total + 255u) / 256u), block(256);
+    const uint16_t* x = static_cast<const uint16_t*>(X);
+    uint16_t* y = static_cast<uint16_t*>(Y);
+    if (type == LP_BF16) hipLaunchKernelGGL(avgpool_lp_kernel<LP_BF16>, grid, block, 0, stream, x, y, g, count_include_pad, d, total);
+    else hipLaunchKernelGGL(avgpool_lp_kernel<LP_F16>, grid, block, 0, stream, x, y, g, count_include_pad, d, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_global_avgpool_lp(const void* X, void* Y, int64_t planes, int HW, int type, hipStream_t stream) {
+    const int64_t blocks = (planes + 3) / 4;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const uint16_t* x = static_cast<const uint16_t*>(X);
+    uint16_t* y = static_cast<uint16_t*>(Y);
+    if (type == LP_BF16) hipLaunchKernelGGL(global_avgpool_lp_kernel<LP_BF16>, dim3((unsigned)blocks), dim3(256), 0, stream, x, y, planes, HW);
+    else hipLaunchKernelGGL(global_avgpool_lp_kernel<LP_F16>, dim3((unsigned)blocks), dim3(256), 0, stream, x, y, planes, HW);
+    return hipGetLastError();
+}
+
+}  // namespace onnxhip

@@ -8,6 +8,12 @@ linear chain of Conv / pool / Gemm nodes small enough for the library's single-l
 (``onnx_chain``: every activation and all weights in LDS) is run through that one call
 instead.  All arithmetic happens inside the library's kernels; this module only prepares
 argument lists.
+
+With ``dtype=torch.float16`` or ``torch.bfloat16`` a graph of Conv / MaxPool / AveragePool / Reshape /
+Gemm / MatMul nodes runs on 16-bit tensors (the operator definitions admit them, Section 3.1):
+inputs and weights are rounded to the type once, on upload, the biases stay fp32, every
+activation is stored in the type (fp32 accumulation inside each operator), and the node that
+produces the model's output stores fp32.
 """
 
 import numpy as np
@@ -17,12 +23,17 @@ from . import binding as B
 
 
 class GraphRunner:
-    def __init__(self, model, device="cuda:0", workspace_bytes=64 << 20, fuse_chain=True, keep_intermediates=False):
+    def __init__(self, model, device="cuda:0", workspace_bytes=64 << 20, fuse_chain=True, keep_intermediates=False,
+                 dtype=None):
         """fuse_chain: use the single-launch chain when the model qualifies.  keep_intermediates:
         have the chain write every node's result to device memory too (for layer-by-layer checks;
-        the per-node path always does)."""
+        the per-node path always does).  dtype: None (fp32) or the 16-bit type to run in."""
         self.device = torch.device(device)
         self.model = model
+        self.dtype = None if dtype in (None, torch.float32) else dtype
+        if self.dtype is not None:
+            self._init_lp(workspace_bytes)
+            return
         for nd in model["graph"]:                  # refuse before anything is allocated or registered
             if nd["op"] in ("batchnorm", "identity", "reducel1"):
                 raise NotImplementedError(
@@ -119,6 +130,86 @@ class GraphRunner:
         self.output = self.t[model["output"]]
         self.chain = self._build_chain(keep_intermediates) if fuse_chain else None
 
+    def _init_lp(self, workspace_bytes):
+        """The 16-bit form of the graph: the same nodes through the library's 16-bit entry points."""
+        model, dt = self.model, self.dtype
+        if dt not in (torch.float16, torch.bfloat16):
+            raise TypeError("dtype must be torch.float32, torch.float16 or torch.bfloat16")
+        code = B.F16 if dt == torch.float16 else B.BF16
+        fp32_names = set()                         # the additive operands, which the 16-bit operators take in fp32
+        for nd in model["graph"]:
+            if nd["op"] not in ("conv", "maxpool", "avgpool", "reshape", "gemm", "matmul"):
+                raise NotImplementedError("node %r (%s): the 16-bit runner takes Conv, MaxPool, AveragePool, Reshape, Gemm "
+                                          "and MatMul nodes" % (nd["y"], nd["op"]))
+            if nd["op"] == "conv" and nd["b"]:
+                fp32_names.add(nd["b"])
+            if nd["op"] == "gemm" and nd["c"]:
+                fp32_names.add(nd["c"])
+        self.workspace = torch.empty(workspace_bytes, dtype=torch.uint8, device=self.device) if workspace_bytes else None
+        self.t = {}
+        for k, v in list(model["inputs"].items()) + list(model["weights"].items()):
+            t = torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(self.device)
+            self.t[k] = t if k in fp32_names else t.to(dt)
+        self.calls = []
+        self.chain = None
+        lib = B.raw()
+        for nd in model["graph"]:
+            op = nd["op"]
+            last = nd["y"] == model["output"]
+            ydt, ycode = (torch.float32, B.F32) if last and op in ("conv", "gemm", "matmul") else (dt, code)
+            if op == "conv":
+                x, w = self.t[nd["x"]], self.t[nd["w"]]
+                yd = B.onnx_conv_infer(x.shape, w.shape, nd["pads"], nd["strides"], nd["dilations"], nd["group"])
+                y = self._new(nd["y"], yd, ydt)
+                b = self.t[nd["b"]] if nd["b"] else None
+                r = self.t[nd["residual"]] if nd["residual"] else None
+                if r is not None and r.dtype != ydt:
+                    raise NotImplementedError("node %r: a residual must have the type of the result" % (nd["y"],))
+                args = [B._ptr(x), B.dims(x.shape), B._ptr(w), B.dims(w.shape), B._ptr(b), B.dims(nd["pads"]),
+                        B.dims(nd["strides"]), B.dims(nd["dilations"]), int(nd["group"]), B._ptr(r),
+                        B.ACT_RELU if nd["relu"] else B.ACT_NONE, B._ptr(y), B.dims(y.shape), code, ycode, None]
+                self.calls.append((lib.onnx_conv_lp, args))
+            elif op == "maxpool":
+                x = self.t[nd["x"]]
+                yd = B.onnx_pool_infer(x.shape, nd["kernel"], nd["pads"], nd["strides"], nd["dilations"], nd["ceil_mode"])
+                y = self._new(nd["y"], yd, dt)
+                args = [B._ptr(x), B.dims(x.shape), B.dims(nd["kernel"]), B.dims(nd["pads"]), B.dims(nd["strides"]),
+                        B.dims(nd["dilations"]), int(nd["ceil_mode"]), B._ptr(y), B.dims(y.shape), code, None]
+                self.calls.append((lib.onnx_maxpool_lp, args))
+            elif op == "avgpool":
+                x = self.t[nd["x"]]
+                if nd["kernel"] is None:
+                    yd = (x.shape[0], x.shape[1], 1, 1)
+                    kp = pp = sp = None
+                else:
+                    yd = B.onnx_pool_infer(x.shape, nd["kernel"], nd["pads"], nd["strides"], (1, 1), nd["ceil_mode"])
+                    kp, pp, sp = B.dims(nd["kernel"]), B.dims(nd["pads"]), B.dims(nd["strides"])
+                y = self._new(nd["y"], yd, dt)
+                args = [B._ptr(x), B.dims(x.shape), kp, pp, sp, int(nd["ceil_mode"]), int(nd["count_include_pad"]),
+                        B._ptr(y), B.dims(y.shape), code, None]
+                self.calls.append((lib.onnx_avgpool_lp, args))
+            elif op == "reshape":
+                self.t[nd["y"]] = self.t[nd["x"]].view(nd["shape"])
+            elif op == "gemm":
+                a, b = self.t[nd["a"]], self.t[nd["b"]]
+                c = self.t[nd["c"]] if nd["c"] else None
+                m = a.shape[1] if nd["transA"] else a.shape[0]
+                n = b.shape[0] if nd["transB"] else b.shape[1]
+                y = self._new(nd["y"], (m, n), ydt)
+                cd, cr = (B.dims(c.shape), c.dim()) if c is not None else (None, 0)
+                args = [B._ptr(a), B.dims(a.shape), B._ptr(b), B.dims(b.shape), B._ptr(c), cd, cr,
+                        float(nd["alpha"]), float(nd["beta"]), int(nd["transA"]), int(nd["transB"]),
+                        B.ACT_RELU if nd["relu"] else B.ACT_NONE, B._ptr(y), B.dims(y.shape), code, ycode, None]
+                self.calls.append((lib.onnx_gemm_lp, args))
+            else:                                  # matmul
+                a, b = self.t[nd["a"]], self.t[nd["b"]]
+                yd = B.onnx_matmul_infer(a.shape, b.shape)
+                y = self._new(nd["y"], yd, ydt)
+                args = [B._ptr(a), B.dims(a.shape), a.dim(), B._ptr(b), B.dims(b.shape), b.dim(), B._ptr(y),
+                        B.dims(y.shape), y.dim(), code, ycode, None]
+                self.calls.append((lib.onnx_matmul_lp, args))
+        self.output = self.t[model["output"]]
+
     def _build_chain(self, keep):
         """The model as arguments of one onnx_chain call, or None when it is not a linear chain
         of operators that call takes or the library finds it too large."""
@@ -182,13 +273,13 @@ class GraphRunner:
         self._chain_keepalive = (ops, results)
         return (B.raw().onnx_chain, args)
 
-    def _new(self, name, shape):
-        y = torch.empty(tuple(int(s) for s in shape), dtype=torch.float32, device=self.device)
+    def _new(self, name, shape, dtype=torch.float32):
+        y = torch.empty(tuple(int(s) for s in shape), dtype=dtype, device=self.device)
         self.t[name] = y
         return y
 
     def set_input(self, name, array):
-        self.t[name].copy_(torch.from_numpy(array))
+        self.t[name].copy_(torch.from_numpy(array))        # rounds to the tensor's type (nearest even)
 
     def capture(self):
         """Record the whole chain into a HIP graph (through torch's stream capture) so that a

@@ -474,6 +474,122 @@ def test_conv_16bit_small_integers_bit_exact(lib):
             assert np.array_equal(got.cpu().numpy().astype(np.float64), ref)
 
 
+POOL_LP_CASES = [
+    # N, C, H, W, kernel, pads, strides, dilations, ceil_mode
+    (2, 3, 9, 8, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),
+    (1, 2, 10, 7, (2, 3), (0, 1, 0, 1), (2, 1), (1, 1), 0),
+    (2, 2, 11, 11, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 1),
+    (1, 3, 12, 9, (3, 2), (0, 0, 0, 0), (3, 2), (2, 2), 0),
+    (2, 5, 13, 10, (3, 2), (2, 0, 1, 1), (1, 2), (1, 1), 0),
+    (3, 64, 56, 56, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),
+    (4, 1, 1, 1, (1, 1), (0, 0, 0, 0), (1, 1), (1, 1), 0),
+    (0, 3, 8, 8, (2, 2), (0, 0, 0, 0), (2, 2), (1, 1), 0),
+]
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("case", POOL_LP_CASES)
+def test_pools_16bit_match_oracle(lib, case, kind):
+    """MaxPool on 16-bit tensors returns one of its inputs: bit-exact against the oracle on the values the bits
+    denote.  AveragePool sums in fp32 and rounds once: within one rounding of the type of the oracle's fp64 mean."""
+    N, C, H, W, k, pads, st, dl, ceil = case
+    announce("pool_lp", kind, case)
+    rng = np.random.default_rng([N, C, H, W, k[0], k[1]])
+    xb, xv = encode(rng.uniform(-2, 2, (N, C, H, W)).astype(np.float32), kind)
+    X = bits_to_dev(xb, kind) if N else torch.empty((0, C, H, W), dtype=TORCH_T[kind], device="cuda")
+    got = lib.onnx_maxpool_lp(X, k, pads, st, dl, ceil)
+    assert got.dtype == TORCH_T[kind]
+    if N == 0:
+        assert got.shape[0] == 0
+        return
+    ref = oracle.maxpool(xv, k, pads, st, dl, ceil, want_indices=False)
+    assert np.array_equal(lp_to_host(got, kind), ref)
+    u = 2.0 ** -PRECISION[kind]
+    if dl == (1, 1):
+        for cip in (0, 1):
+            want = oracle.avgpool(xv, k, pads, st, ceil, cip)
+            g = lp_to_host(lib.onnx_avgpool_lp(X, k, pads, st, ceil, cip), kind)
+            assert g.shape == want.shape
+            # one rounding to the type plus the fp32 sum of at most k0*k1 values of magnitude <= 2
+            assert (np.abs(g - want) <= u * np.abs(want) + k[0] * k[1] * 2.0 ** -22).all()
+    want = oracle.avgpool(xv, None)
+    g = lp_to_host(lib.onnx_avgpool_lp(X), kind)
+    assert g.shape == (N, C, 1, 1)
+    assert (np.abs(g - want) <= u * np.abs(want) + H * W * 2.0 ** -22).all()
+
+
+def test_pools_16bit_errors(lib):
+    announce("pool_lp errors")
+    import ctypes
+    B = lib
+    x = torch.zeros((1, 1, 4, 4), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(TypeError):
+        lib.onnx_maxpool_lp(torch.zeros((1, 1, 4, 4), device="cuda"), (2, 2))
+    with pytest.raises(lib.OnnxHipError):
+        lib.onnx_maxpool_lp(x, (2, 2), pads=(2, 2, 2, 2))           # pads as large as the window
+    with pytest.raises(lib.OnnxHipError):
+        lib.onnx_avgpool_lp(x, (5, 5))                              # window larger than the image
+    y = torch.zeros((1, 1, 2, 2), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(lib.OnnxHipError):
+        lib.onnx_maxpool_lp(x, (2, 2), out=y)                       # y_dims do not match the inferred shape
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+def test_resnet50_16bit_every_layer_from_its_own_inputs(lib, kind):
+    """ResNet-50 through the runner in a 16-bit type (batch 2: tiles span both images).  Every node is checked as
+    an operator: the oracle gets the very tensors the node read on the GPU (16-bit activations and weights decoded,
+    fp32 biases) and the node's result must lie within the operator's budget of the fp64 value: exact for MaxPool,
+    one rounding of the type plus the fp32 accumulation bound otherwise.  The fp32 logits are also compared with
+    the fp32 network's, as a sanity bound on what 54 roundings of the activations add up to."""
+    announce("resnet50 16-bit", kind)
+    from paper_2008_08272_amd.runner import GraphRunner
+    from oracle import chain
+    m = workloads.resnet50(2)
+    r = GraphRunner(m, dtype=TORCH_T[kind])
+    out = r.run()
+    torch.cuda.synchronize()
+    assert out.dtype == torch.float32 and out.shape == (2, 1000)
+    u = 2.0 ** -PRECISION[kind]
+    val = lambda name: r.t[name].float().cpu().numpy()
+    tuned3x3 = 0
+    for nd in m["graph"]:
+        op = nd["op"]
+        if op == "reshape":
+            continue
+        got = val(nd["y"]).astype(np.float64)
+        last = nd["y"] == m["output"]
+        ulp = 0.0 if last else u
+        if op == "conv":
+            x, w = val(nd["x"]), val(nd["w"])
+            res = val(nd["residual"]) if nd["residual"] else None
+            ref, S = oracle.conv(x, w, val(nd["b"]) if nd["b"] else None, nd["pads"], nd["strides"], nd["dilations"], nd["group"],
+                                 residual=res, relu=False, want_scale=True)
+            if nd["relu"]:
+                ref = np.maximum(ref, 0)
+            K = w.shape[1] * w.shape[2] * w.shape[3]
+            bound = ulp * np.abs(ref) + (K + 5) * 2.0 ** -24 * (S + 1.0) + 1e-7
+        elif op == "gemm":
+            a, b = val(nd["a"]), val(nd["b"])
+            ref, S = oracle.gemm(a, b, val(nd["c"]) if nd["c"] else None, nd["alpha"], nd["beta"], nd["transA"], nd["transB"],
+                                 relu=nd["relu"], want_scale=True)
+            bound = ulp * np.abs(ref) + (a.shape[1] + 5) * 2.0 ** -24 * (S + 1.0) + 1e-7
+        elif op == "maxpool":
+            ref = oracle.maxpool(val(nd["x"]), nd["kernel"], nd["pads"], nd["strides"], nd["dilations"], nd["ceil_mode"],
+                                 want_indices=False).astype(np.float64)
+            bound = np.zeros_like(ref)
+        else:
+            assert op == "avgpool"
+            x = val(nd["x"])
+            ref = oracle.avgpool(x, nd["kernel"], nd["pads"], nd["strides"], nd["ceil_mode"], nd["count_include_pad"])
+            bound = u * np.abs(ref) + x.shape[2] * x.shape[3] * 2.0 ** -22 * np.abs(x).max()
+        assert got.shape == ref.shape, nd["y"]
+        assert (np.abs(got - ref) <= bound).all(), (nd["y"], op, float(np.abs(got - ref).max()))
+    _, exact = chain.run(m, keep=())
+    e = rel_err(out.cpu().numpy(), exact["logits"])
+    print("resnet50 %s logits against the fp32 network: %.4f" % (kind, e), flush=True)
+    assert e <= (0.1 if kind == "bf16" else 0.02)
+
+
 def test_gemm_16bit_errors(lib):
     announce("gemm_lp errors")
     a = torch.zeros((16, 16), dtype=torch.bfloat16, device="cuda")
