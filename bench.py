@@ -158,6 +158,7 @@ def main():
     ap.add_argument("--profile-resnet", type=int, nargs="?", const=32, default=0, metavar="BATCH",
                     help="run only ResNet-50 at the given batch (default 32; 3 untimed + 10 timed passes, one call per "
                          "node), print the mean time and exit: the run behind the per-kernel traces under profiles/")
+    ap.add_argument("--profile-bf16", action="store_true", help="with --profile-resnet: run the network on bf16 tensors")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -184,7 +185,7 @@ def main():
         return
     if args.profile_resnet:
         from paper_2008_08272_amd.runner import GraphRunner
-        r = GraphRunner(workloads.resnet50(args.profile_resnet), dev)
+        r = GraphRunner(workloads.resnet50(args.profile_resnet), dev, dtype=torch.bfloat16 if args.profile_bf16 else None)
         for _ in range(3):
             r.run()
         torch.cuda.synchronize()
@@ -194,7 +195,8 @@ def main():
             r.run()
         e1.record()
         torch.cuda.synchronize()
-        print(json.dumps({"profile_resnet": {"batch": args.profile_resnet, "ms": round(e0.elapsed_time(e1) / 10, 4)}}))
+        print(json.dumps({"profile_resnet": {"batch": args.profile_resnet, "dtype": "bf16" if args.profile_bf16 else "f32",
+                                             "ms": round(e0.elapsed_time(e1) / 10, 4)}}))
         return
 
     if args.copy_calibration:

@@ -198,16 +198,40 @@ onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const f
         p.y_zs = (M / group) * P; p.bias_zs = M / group; p.y_rs = P;
         p.col_images = 1; p.colP = FastDiv::make((uint32_t)P); p.y_img = M * P; p.b_img = C * H * Wd;
         p.alpha = 1.f; p.beta = 1.f; p.bias_mode = BIAS_ROW; p.bias_cs = 0; p.relu = act == ONNX_ACT_RELU;
-        const bool pw = kH == 1 && kW == 1 && pads[0] == 0 && pads[1] == 0 && pads[2] == 0 && pads[3] == 0 &&
-                        strides[0] == 1 && strides[1] == 1;
-        p.b_ld = pw ? H * Wd : 0;
+        const bool unpadded_1x1 = kH == 1 && kW == 1 && pads[0] == 0 && pads[1] == 0 && pads[2] == 0 && pads[3] == 0;
+        bool pw = unpadded_1x1 && strides[0] == 1 && strides[1] == 1;
         p.ic.C = (int)C; p.ic.H = (int)H; p.ic.W = (int)Wd;
         p.ic.sH = g.sH; p.ic.sW = g.sW; p.ic.pT = g.pT; p.ic.pL = g.pL; p.ic.dH = g.dH; p.ic.dW = g.dW;
         p.ic.kHW = FastDiv::make((uint32_t)(kH * kW));
         p.ic.kW = FastDiv::make((uint32_t)kW);
         p.ic.OW = FastDiv::make((uint32_t)OW);
         p.ic.image_stride = (int)(C * H * Wd);
-        const int bvec = pw ? lp_tuned_fits(p, LOAD_KC, LOAD_RC, (int)group) : 0;
+        // Layout passes through the workspace (lp_layout.hip) for 1x1 convolutions the tuned kernel cannot read
+        // as they are: first the positions a strided one reads, then, if the planes still have no aligned
+        // chunks of columns, one K-contiguous row per position.
+        char* ws_free = reinterpret_cast<char*>(ws.partial);
+        int64_t ws_bytes = ws.partial ? ws.partial_floats * 4 : 0;
+        const int64_t copy_bytes = ((N * C * P * 2 + 255) / 256) * 256;
+        if (unpadded_1x1 && !pw && K % 8 == 0 && copy_bytes <= ws_bytes && N * C * P <= kIntMax) {
+            const hipError_t e = launch_lp_subsample(X, ws_free, N * C, (int)H, (int)Wd, (int)OH, (int)OW, g.sH, g.sW, s);
+            if (e != hipSuccess) return device_status(e, "conv (16-bit, subsample)");
+            p.B = reinterpret_cast<const float*>(ws_free);
+            ws_free += copy_bytes; ws_bytes -= copy_bytes;
+            p.b_bs[0] = Cg * P; p.b_img = C * P;
+            p.ic.H = (int)OH; p.ic.W = (int)OW; p.ic.sH = 1; p.ic.sW = 1; p.ic.image_stride = (int)(C * P);
+            pw = true;
+        }
+        p.b_ld = pw ? P : 0;
+        int bvec = pw ? lp_tuned_fits(p, LOAD_KC, LOAD_RC, (int)group) : 0;
+        if (pw && !bvec && K % 8 == 0 && copy_bytes <= ws_bytes && N <= 65535) {
+            const hipError_t e = launch_lp_planes_to_rows(p.B, ws_free, (int)N, (int)C, (int)P, s);
+            if (e != hipSuccess) return device_status(e, "conv (16-bit, planes to rows)");
+            ContractionParams q = p;                 // B as an [N*P][C] K-contiguous matrix; Y keeps its (image, position) columns
+            q.B = reinterpret_cast<const float*>(ws_free);
+            q.b_ld = C; q.b_bs[0] = Cg; q.b_img = 0;
+            if (lp_tuned_fits(q, LOAD_KC, LOAD_KC, (int)group))
+                return device_status(launch_lp_tuned(q, LOAD_KC, 8, (int)group, (int)in_type, (int)out_type, s), "conv (16-bit)");
+        }
         if (bvec)
             return device_status(launch_lp_tuned(p, LOAD_RC, bvec, (int)group, (int)in_type, (int)out_type, s), "conv (16-bit)");
         if (!pw) {

@@ -95,6 +95,12 @@ bool launch_conv_window(ContractionParams& p, int kH, int kW, int OH, int OW, in
 bool launch_conv_window_lp(ContractionParams& p, int kH, int kW, int OH, int OW, int Cg, int nz, int in_type, int out_type,
                            const Workspace& ws, hipStream_t stream, hipError_t* status);
 
+// Layout passes ahead of a 1x1 convolution on 16-bit tensors (lp_layout.hip): the positions a strided
+// convolution reads, copied into a dense [planes][OH][OW] tensor, and [N][C][P] rewritten as [N][P][C].
+hipError_t launch_lp_subsample(const void* X, void* Xs, int64_t planes, int H, int W, int OH, int OW, int sH, int sW,
+                               hipStream_t stream);
+hipError_t launch_lp_planes_to_rows(const void* X, void* Xt, int N, int C, int P, hipStream_t stream);
+
 struct WindowGeom {
     int N, C, H, W, OH, OW;
     int kH, kW, sH, sW, pT, pL, pB, pR, dH, dW;

@@ -438,6 +438,55 @@ def test_conv3x3_16bit_lds_patch_operands_off_alignment(lib, lp_workspace):
             assert rel_err(gth, ref) <= REL_TOL and within_rounding_bound(gth, ref, S, C * 9 + 1)
 
 
+CONV1X1_LAYOUT_CASES = [
+    # N, C, H, W, M, strides, group, expected B loader of the tuned kernel
+    (3, 64, 12, 12, 96, (2, 2), 1, "B=RC/4"),       # strided: the 6 x 6 positions it reads are copied, then chunks of 4 columns
+    (2, 32, 17, 16, 40, (1, 2), 1, "B=RC/8"),       # stride along the row only: 17 x 8 positions, chunks of 8
+    (5, 64, 14, 14, 200, (2, 2), 2, "B=KC/8"),      # strided into 7 x 7 = 49 positions: copied, then one row per position; two groups
+    (4, 128, 7, 7, 130, (1, 1), 1, "B=KC/8"),       # pointwise on 49 positions per image
+    (2, 72, 9, 7, 96, (1, 1), 3, "B=KC/8"),         # 63 positions, three groups of 24 channels
+    (33, 256, 7, 7, 512, (1, 1), 1, "B=KC/8"),      # several 128 x 128 tiles, each spanning three images
+    (3, 24, 13, 11, 20, (3, 2), 1, "B=KC/8"),       # strided into 5 x 6 = 30 positions
+]
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("case", CONV1X1_LAYOUT_CASES)
+def test_conv1x1_16bit_through_layout_passes(lib, lp_workspace, case, kind):
+    """With a workspace, 1x1 convolutions the tuned kernel cannot read in place go through it after a layout pass:
+    strided ones on a dense copy of the positions they read, planes without aligned column chunks as one
+    K-contiguous row per position."""
+    N, C, H, W, M, st, g, loader = case
+    announce("conv_lp 1x1 layouts", kind, case)
+    rng = np.random.default_rng([N, C, H, W, M, g])
+    xb, xv = encode(rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32), kind)
+    wb, wv = encode(rng.uniform(-1, 1, (M, C // g, 1, 1)).astype(np.float32), kind)
+    Bv = rng.uniform(-1, 1, (M,)).astype(np.float32)
+    z4, o2 = (0, 0, 0, 0), (1, 1)
+    K = C // g
+    ref, S = oracle.conv(xv, wv, Bv, z4, st, o2, g, want_scale=True)
+    X, Wt = bits_to_dev(xb, kind), bits_to_dev(wb, kind)
+    got = lib.onnx_conv_lp(X, Wt, torch.from_numpy(Bv).cuda(), z4, st, o2, g, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    launch = lib.onnx_last_launch()
+    assert launch.startswith("gemm_lp") and loader in launch, launch
+    gth = got.cpu().numpy()
+    assert gth.shape == ref.shape
+    assert rel_err(gth, ref) <= REL_TOL and within_rounding_bound(gth, ref, S, K + 1)
+    rb, rv = encode(rng.uniform(-1, 1, ref.shape).astype(np.float32), kind)
+    ref2, S2 = oracle.conv(xv, wv, None, z4, st, o2, g, residual=rv, relu=False, want_scale=True)
+    got2 = lp_to_host(lib.onnx_conv_lp(X, Wt, None, z4, st, o2, g, residual=bits_to_dev(rb, kind), act=1), kind)
+    u = 2.0 ** -PRECISION[kind]
+    want = np.maximum(ref2, 0)
+    assert (np.abs(got2 - want) <= u * np.abs(want) + (K + 5) * 2.0 ** -24 * (S2 + 1.0) + 1e-7).all()
+    Xi = rng.integers(-4, 5, (N, C, H, W)).astype(np.float32)
+    Wi = rng.integers(-4, 5, (M, C // g, 1, 1)).astype(np.float32)
+    goti = lib.onnx_conv_lp(bits_to_dev(encode(Xi, kind)[0], kind), bits_to_dev(encode(Wi, kind)[0], kind), None, z4, st, o2, g,
+                            out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert np.array_equal(goti.cpu().numpy().astype(np.float64), oracle.conv(Xi, Wi, None, z4, st, o2, g))
+
+
 def test_conv3x3_16bit_workspace_too_small_or_channels_not_16(lib, lp_workspace):
     """The LDS-patch kernel needs room for the rewritten filter bank and 16 | channels per group; otherwise the
     general kernel runs, with the same result up to summation order."""
