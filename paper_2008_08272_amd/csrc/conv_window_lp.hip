@@ -290,10 +290,12 @@ struct WindowLpConfig {
     double weight;     // time of one workgroup relative to the 64 x 64 tile's
 };
 // Keep in step with the template instances in launch_config below.  Measured on ResNet-50's 3x3 layers at batch 32
-// (bf16): a 128 x 128 workgroup of eight wavefronts takes 1.1-1.45 times as long as a 64 x 64 one of four.
+// (bf16): a 128 x 128 workgroup of eight wavefronts takes 1.1-1.45 times as long as a 64 x 64 one of four, a
+// 64 x 128 one of four (for layers with 64 filters or fewer: twice the positions per filter tile) 1.5 times.
 const WindowLpConfig kConfigs[] = {
     {64, 64, 256, 8, 512, 1.0},
     {128, 128, 512, 4, 256, 1.4},
+    {64, 128, 256, 8, 512, 1.5},
 };
 const int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 
@@ -343,6 +345,7 @@ hipError_t launch_config(ContractionParams& p, int cfg, bool pair, int npu, int 
     switch (cfg) {
         case 0: return launch_units<64, 64, 2, 2, DT, LP_OUT>(p, pair, npu, nz, stream);
         case 1: return launch_units<128, 128, 2, 4, DT, LP_OUT>(p, pair, npu, nz, stream);
+        case 2: return launch_units<64, 128, 2, 2, DT, LP_OUT>(p, pair, npu, nz, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -346,7 +346,12 @@ CONV3X3_LP_CASES = [
     (160, 16, 10, 10, 256, (0, 0, 0, 0), (1, 1), (1, 1), 1, "128x128x144 2 1"),
     (40, 16, 20, 20, 256, (1, 1, 1, 1), (1, 1), (1, 3), 1, "128x128x144 2 1"),
     (40, 16, 24, 50, 128, (1, 1, 1, 1), (2, 1), (2, 2), 1, "128x128x144 2 2"),
-    (70, 32, 14, 14, 300, (1, 1, 1, 1), (1, 1), (1, 1), 2, "128x128x144 2 1"),    # two groups of 150 filters: a ragged second row of tiles
+    (70, 32, 14, 14, 300, (1, 1, 1, 1), (1, 1), (1, 1), 2, "64x128x144 2 2"),     # two groups of 150 filters: a ragged third row of tiles
+    (700, 16, 9, 9, 40, (1, 1, 1, 1), (1, 1), (1, 1), 1, "64x128x144 1 2"),       # few filters, many positions: the 64 x 128 tile
+    (80, 16, 30, 31, 40, (1, 1, 1, 1), (1, 1), (1, 1), 1, "64x128x144 1 4"),
+    (80, 16, 25, 51, 40, (1, 1, 1, 1), (1, 1), (2, 2), 1, "64x128x144 1 8"),
+    (1200, 16, 10, 10, 40, (0, 0, 0, 0), (1, 1), (1, 1), 1, "64x128x144 2 1"),
+    (80, 16, 24, 50, 40, (1, 1, 1, 1), (1, 1), (2, 2), 1, "64x128x144 2 4"),
 ]
 
 
