@@ -286,6 +286,24 @@ onnx_status onnx_conv_lp(const void* X, const int64_t x_dims[4], const void* W, 
                          void* stream);
 
 /*
+ * The 3x3 case of onnx_conv_lp for filters that do not change between calls (inference): the
+ * LDS-patch kernel reads the filter bank in tap order, [M][C/group / 16][9 taps][16 channels],
+ * and onnx_conv_lp rewrites W into that order in the workspace on every call.
+ * onnx_conv_lp_filter_taps does the rewriting once, into `packed` (device memory of the size of
+ * W, 16-byte aligned, caller-owned); onnx_conv_lp_taps is onnx_conv_lp with `packed` in place of
+ * W (w_dims still the ONNX shape [M, C/group, 3, 3]) and uses no workspace.  Both need 3x3
+ * windows and C/group a multiple of 16; onnx_conv_lp_taps returns ONNX_ERR_UNSUPPORTED, before
+ * any launch, for shapes whose input patch does not fit the kernel (the caller then uses
+ * onnx_conv_lp with W).
+ */
+onnx_status onnx_conv_lp_filter_taps(const void* W, const int64_t w_dims[4], void* packed, void* stream);
+onnx_status onnx_conv_lp_taps(const void* X, const int64_t x_dims[4], const void* packed, const int64_t w_dims[4],
+                              const float* B, const int64_t pads[4], const int64_t strides[2],
+                              const int64_t dilations[2], int64_t group, const void* residual,
+                              onnx_act act, void* Y, const int64_t y_dims[4], onnx_dtype in_type,
+                              onnx_dtype out_type, void* stream);
+
+/*
  * ONNX MaxPool and AveragePool / GlobalAveragePool on 16-bit tensors (type ONNX_F16 or
  * ONNX_BF16 for X and Y alike): what lies between the 16-bit convolutions of a network whose
  * activations stay in the 16-bit type.  Semantics, attributes, limits and errors of

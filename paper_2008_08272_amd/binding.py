@@ -76,6 +76,10 @@ _lib.onnx_matmul_lp.argtypes = [_vp, _i64p, _ci, _vp, _i64p, _ci, _vp, _i64p, _c
 _lib.onnx_matmul_lp.restype = _ci
 _lib.onnx_conv_lp.argtypes = [_vp, _i64p, _vp, _i64p, _vp, _i64p, _i64p, _i64p, _c64, _vp, _ci, _vp, _i64p, _ci, _ci, _vp]
 _lib.onnx_conv_lp.restype = _ci
+_lib.onnx_conv_lp_taps.argtypes = _lib.onnx_conv_lp.argtypes
+_lib.onnx_conv_lp_taps.restype = _ci
+_lib.onnx_conv_lp_filter_taps.argtypes = [_vp, _i64p, _vp, _vp]
+_lib.onnx_conv_lp_filter_taps.restype = _ci
 _lib.onnx_lstm_scratch_bytes.argtypes = [_i64p, _c64, _ci]
 _lib.onnx_lstm_scratch_bytes.restype = ctypes.c_size_t
 _lib.onnx_lstm.argtypes = [_vp, _i64p, _vp, _vp, _vp, _vp, _vp, _c64, _ci, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
@@ -386,6 +390,29 @@ def onnx_conv_lp(X, W, B=None, pads=(0, 0, 0, 0), strides=(1, 1), dilations=(1, 
     _check(_lib.onnx_conv_lp(_ptr(X), dims(X.shape), _ptr(W), dims(W.shape), _ptr(B), dims(pads), dims(strides),
                              dims(dilations), int(group), _ptr(residual), int(act), _ptr(Y), dims(Y.shape),
                              _LP_TYPES[X.dtype], ot, _stream(stream)))
+    return Y
+
+
+def onnx_conv_lp_filter_taps(W, stream=None):
+    """A 3x3 filter bank [M, C/group, 3, 3] (C/group a multiple of 16) rewritten into the tap order onnx_conv_lp_taps reads."""
+    W = _lp(W, "W")
+    packed = torch.empty_like(W)
+    _check(_lib.onnx_conv_lp_filter_taps(_ptr(W), dims(W.shape), _ptr(packed), _stream(stream)))
+    return packed
+
+
+def onnx_conv_lp_taps(X, packed, B=None, pads=(0, 0, 0, 0), strides=(1, 1), dilations=(1, 1), group=1, residual=None,
+                      act=ACT_NONE, out_dtype=None, out=None, stream=None):
+    """onnx_conv_lp for a 3x3 filter bank rewritten by onnx_conv_lp_filter_taps (it keeps W's shape); no workspace."""
+    X = _lp(X, "X")
+    packed = _lp(packed, "packed", X)
+    B = _dev(B, "B")
+    Y, ot = _lp_out(out, onnx_conv_infer(X.shape, packed.shape, pads, strides, dilations, group), out_dtype, X)
+    if residual is not None and not (residual.is_cuda and residual.dtype == Y.dtype and residual.is_contiguous()):
+        raise TypeError("residual must be a contiguous GPU tensor of the result's type")
+    _check(_lib.onnx_conv_lp_taps(_ptr(X), dims(X.shape), _ptr(packed), dims(packed.shape), _ptr(B), dims(pads), dims(strides),
+                                  dims(dilations), int(group), _ptr(residual), int(act), _ptr(Y), dims(Y.shape),
+                                  _LP_TYPES[X.dtype], ot, _stream(stream)))
     return Y
 
 

@@ -139,7 +139,8 @@ onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const f
                                 const float* B, const int64_t pads[4], const int64_t strides[2],
                                 const int64_t dilations[2], int64_t group, const float* residual, onnx_act act,
                                 float* Y, const int64_t y_dims[4], const Workspace* caller_ws, int64_t max_outputs,
-                                void* stream, onnx_dtype in_type = ONNX_F32, onnx_dtype out_type = ONNX_F32) {
+                                void* stream, onnx_dtype in_type = ONNX_F32, onnx_dtype out_type = ONNX_F32,
+                                bool filters_in_tap_order = false) {
     if (!x_dims || !w_dims || !y_dims) return fail(ONNX_ERR_NULL, "conv: NULL dims array");
     int64_t yd[4];
     const onnx_status st = onnx_conv_infer(x_dims, w_dims, pads, strides, dilations, group, yd);
@@ -236,10 +237,13 @@ onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const f
             return device_status(launch_lp_tuned(p, LOAD_RC, bvec, (int)group, (int)in_type, (int)out_type, s), "conv (16-bit)");
         if (!pw) {
             hipError_t e = hipSuccess;
-            if (launch_conv_window_lp(p, (int)kH, (int)kW, (int)OH, (int)OW, (int)Cg, (int)group, (int)in_type, (int)out_type, ws,
-                                      s, &e))
+            if (launch_conv_window_lp(p, (int)kH, (int)kW, (int)OH, (int)OW, (int)Cg, (int)group, (int)in_type, (int)out_type,
+                                      filters_in_tap_order, ws, s, &e))
                 return device_status(e, "conv (16-bit, lds patch)");
         }
+        if (filters_in_tap_order)
+            return fail(ONNX_ERR_UNSUPPORTED, "conv_lp_taps: only 3x3 convolutions with a multiple of 16 channels per group whose "
+                        "patch fits the LDS-patch kernel take filters in tap order; use onnx_conv_lp");
         return device_status(launch_lp_generic(p, LOAD_KC, pw ? LOAD_RC : LOAD_IM2COL, (int)group, (int)in_type,
                                                (int)out_type, s), "conv (16-bit)");
     }
@@ -578,6 +582,35 @@ onnx_status onnx_matmul_lp(const void* A, const int64_t* a_dims, int a_rank, con
     if (out_type != ONNX_F32 && out_type != in_type) return fail(ONNX_ERR_ATTR, "matmul_lp: out_type must be ONNX_F32 or in_type");
     return matmul_any(static_cast<const float*>(A), a_dims, a_rank, static_cast<const float*>(B), b_dims, b_rank,
                       static_cast<float*>(Y), y_dims, y_rank, in_type, out_type, stream);
+}
+
+onnx_status onnx_conv_lp_filter_taps(const void* W, const int64_t w_dims[4], void* packed, void* stream) {
+    if (!w_dims) return fail(ONNX_ERR_NULL, "conv_lp_filter_taps: NULL dims array");
+    for (int i = 0; i < 4; ++i)
+        if (w_dims[i] < 0) return fail(ONNX_ERR_SHAPE, "conv_lp_filter_taps: negative dimension");
+    if (w_dims[2] != 3 || w_dims[3] != 3 || w_dims[1] % 16 != 0 || w_dims[1] > kIntMax)
+        return fail(ONNX_ERR_UNSUPPORTED, "conv_lp_filter_taps: W must be [M, C/group, 3, 3] with C/group a multiple of 16");
+    const int64_t n = w_dims[0] * w_dims[1] * 9;
+    if (n == 0) return ONNX_OK;
+    if (!W || !packed) return fail(ONNX_ERR_NULL, "conv_lp_filter_taps: W and packed must not be NULL");
+    if ((reinterpret_cast<uintptr_t>(packed) & 15u) != 0) return fail(ONNX_ERR_ATTR, "conv_lp_filter_taps: packed must be 16-byte aligned");
+    if (overlaps(packed, n * 2, W, n * 2)) return fail(ONNX_ERR_ALIAS, "conv_lp_filter_taps: packed overlaps W");
+    return device_status(launch_lp_filter_taps(W, packed, w_dims[0], (int)w_dims[1], static_cast<hipStream_t>(stream)),
+                         "conv_lp_filter_taps");
+}
+
+onnx_status onnx_conv_lp_taps(const void* X, const int64_t x_dims[4], const void* packed, const int64_t w_dims[4], const float* B,
+                              const int64_t pads[4], const int64_t strides[2], const int64_t dilations[2], int64_t group,
+                              const void* residual, onnx_act act, void* Y, const int64_t y_dims[4], onnx_dtype in_type,
+                              onnx_dtype out_type, void* stream) {
+    if (in_type != ONNX_F16 && in_type != ONNX_BF16) return fail(ONNX_ERR_ATTR, "conv_lp_taps: in_type must be ONNX_F16 or ONNX_BF16");
+    if (out_type != ONNX_F32 && out_type != in_type) return fail(ONNX_ERR_ATTR, "conv_lp_taps: out_type must be ONNX_F32 or in_type");
+    if (packed && (reinterpret_cast<uintptr_t>(packed) & 15u) != 0)
+        return fail(ONNX_ERR_ATTR, "conv_lp_taps: the rewritten filter bank must be 16-byte aligned");
+    const Workspace none = {nullptr, 0};
+    return conv_with_workspace(static_cast<const float*>(X), x_dims, static_cast<const float*>(packed), w_dims, B, pads, strides,
+                               dilations, group, static_cast<const float*>(residual), act, static_cast<float*>(Y), y_dims,
+                               &none, 0, stream, in_type, out_type, true);
 }
 
 onnx_status onnx_conv_lp(const void* X, const int64_t x_dims[4], const void* W, const int64_t w_dims[4], const float* B,

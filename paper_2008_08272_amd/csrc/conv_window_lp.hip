@@ -352,12 +352,22 @@ hipError_t launch_config(ContractionParams& p, int cfg, bool pair, int npu, int 
 
 }  // namespace
 
+hipError_t launch_lp_filter_taps(const void* W, void* packed, int64_t rows, int Cg, hipStream_t stream) {
+    const int64_t chunks = rows * Cg * LPW_TAPS / 8;
+    if (Cg % LPW_CB != 0 || (chunks + 255) / 256 > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (chunks == 0) return hipSuccess;
+    hipLaunchKernelGGL(lp_filter_taps_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, stream,
+                       static_cast<const uint16_t*>(W), static_cast<uint16_t*>(packed), chunks, Cg);
+    return hipGetLastError();
+}
+
 bool launch_conv_window_lp(ContractionParams& p, int kH, int kW, int OH, int OW, int Cg, int nz, int in_type, int out_type,
-                           const Workspace& ws, hipStream_t stream, hipError_t* status) {
+                           bool filters_in_tap_order, const Workspace& ws, hipStream_t stream, hipError_t* status) {
     if (!(kH == 3 && kW == 3) || Cg % LPW_CB != 0) return false;
-    // the rewritten filter bank lives in the workspace
+    // the rewritten filter bank lives in the workspace, unless the caller hands it over rewritten
     const int64_t filter_values = (int64_t)p.M * nz * Cg * LPW_TAPS;
-    if (!ws.partial || filter_values * 2 > ws.partial_floats * 4) return false;
+    if (!filters_in_tap_order && (!ws.partial || filter_values * 2 > ws.partial_floats * 4)) return false;
+    if ((reinterpret_cast<uintptr_t>(p.A) & 15u) != 0 && filters_in_tap_order) return false;
     // 32-bit byte offsets from a tile's first image: the input of the images one tile touches, and their output
     const int64_t P = (int64_t)OH * OW, tile_images = (256 + P - 1) / P + 1, span = (1LL << 31) - 64;
     if (tile_images * p.ic.image_stride * 2 >= span || (256 * P + tile_images * p.y_img) * 4 >= span || (int64_t)256 * p.K * 2 >= span)
@@ -391,13 +401,11 @@ bool launch_conv_window_lp(ContractionParams& p, int kH, int kW, int OH, int OW,
     g.planed = FastDiv::make((uint32_t)(pair ? best_plane / 2 : best_plane));
     g.IPRd = FastDiv::make((uint32_t)g.IPR);
 
-    uint16_t* packed = reinterpret_cast<uint16_t*>(ws.partial);
-    const int64_t chunks = filter_values / 8;
-    hipLaunchKernelGGL(lp_filter_taps_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, stream,
-                       reinterpret_cast<const uint16_t*>(p.A), packed, chunks, Cg);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) { *status = e; return true; }
-    p.A = reinterpret_cast<const float*>(packed);
+    if (!filters_in_tap_order) {
+        const hipError_t e = launch_lp_filter_taps(p.A, ws.partial, (int64_t)p.M * nz, Cg, stream);
+        if (e != hipSuccess) { *status = e; return true; }
+        p.A = ws.partial;
+    }
 
     const int npu = (2 * best_plane + kConfigs[best].nt - 1) / kConfigs[best].nt;
     const bool lp_out = out_type != 0;

@@ -90,10 +90,13 @@ bool launch_conv_window(ContractionParams& p, int kH, int kW, int OH, int OW, in
                         const Workspace& ws, hipStream_t stream, hipError_t* status);
 
 // The same for 16-bit tensors (conv_window_lp.hip): 3x3 windows, input channels per group a multiple
-// of 16, and a workspace that holds a rewritten copy of the filter bank (p.M * nz * Cg * 9 16-bit
-// values).  in_type / out_type as for launch_lp_generic.
+// of 16, and either a workspace that holds a rewritten copy of the filter bank (p.M * nz * Cg * 9
+// 16-bit values) or p.A already rewritten by launch_lp_filter_taps (filters_in_tap_order; 16-byte
+// aligned).  in_type / out_type as for launch_lp_generic.
 bool launch_conv_window_lp(ContractionParams& p, int kH, int kW, int OH, int OW, int Cg, int nz, int in_type, int out_type,
-                           const Workspace& ws, hipStream_t stream, hipError_t* status);
+                           bool filters_in_tap_order, const Workspace& ws, hipStream_t stream, hipError_t* status);
+// W [rows][Cg][3][3] -> packed [rows][Cg/16][9][16] (16-bit values; Cg a multiple of 16).
+hipError_t launch_lp_filter_taps(const void* W, void* packed, int64_t rows, int Cg, hipStream_t stream);
 
 // Layout passes ahead of a 1x1 convolution on 16-bit tensors (lp_layout.hip): the positions a strided
 // convolution reads, copied into a dense [planes][OH][OW] tensor, and [N][C][P] rewritten as [N][P][C].

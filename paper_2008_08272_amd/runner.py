@@ -168,7 +168,20 @@ class GraphRunner:
                 args = [B._ptr(x), B.dims(x.shape), B._ptr(w), B.dims(w.shape), B._ptr(b), B.dims(nd["pads"]),
                         B.dims(nd["strides"]), B.dims(nd["dilations"]), int(nd["group"]), B._ptr(r),
                         B.ACT_RELU if nd["relu"] else B.ACT_NONE, B._ptr(y), B.dims(y.shape), code, ycode, None]
-                self.calls.append((lib.onnx_conv_lp, args))
+                fn = lib.onnx_conv_lp
+                if tuple(w.shape[2:]) == (3, 3) and w.shape[1] % 16 == 0:
+                    # the weights are constants: rewrite the filter bank into the 3x3 kernel's tap order once, here,
+                    # instead of on every call; one untimed call finds out whether the kernel takes this shape
+                    taps = B.onnx_conv_lp_filter_taps(w)
+                    trial = list(args)
+                    trial[2], trial[-1] = B._ptr(taps), B._stream(None)
+                    st = lib.onnx_conv_lp_taps(*trial)
+                    if st == B.ONNX_OK:
+                        self.t[nd["w"] + ".taps"] = taps
+                        args[2], fn = B._ptr(taps), lib.onnx_conv_lp_taps
+                    elif st != B.ONNX_ERR_UNSUPPORTED:
+                        raise B.OnnxHipError(st, B.onnx_last_error())
+                self.calls.append((fn, args))
             elif op == "maxpool":
                 x = self.t[nd["x"]]
                 yd = B.onnx_pool_infer(x.shape, nd["kernel"], nd["pads"], nd["strides"], nd["dilations"], nd["ceil_mode"])

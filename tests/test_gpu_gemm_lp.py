@@ -492,6 +492,46 @@ def test_conv1x1_16bit_through_layout_passes(lib, lp_workspace, case, kind):
     assert np.array_equal(goti.cpu().numpy().astype(np.float64), oracle.conv(Xi, Wi, None, z4, st, o2, g))
 
 
+def test_conv3x3_16bit_filters_rewritten_once(lib):
+    """onnx_conv_lp_filter_taps + onnx_conv_lp_taps: the filter bank rewritten once, no workspace; bit for bit the
+    result of onnx_conv_lp with a workspace (same kernel, same operands), and within the budget of the oracle."""
+    announce("conv_lp taps")
+    rng = np.random.default_rng(21)
+    for kind in ("f16", "bf16"):
+        for (N, C, H, W, M, pads, st, dl, g) in [(3, 64, 19, 23, 72, (2, 0, 1, 3), (1, 1), (1, 1), 2), (40, 16, 20, 20, 256, (1, 1, 1, 1), (1, 1), (1, 3), 1),
+                                                 (2, 32, 14, 14, 40, (1, 1, 1, 1), (2, 2), (1, 1), 1)]:
+            xb, xv = encode(rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32), kind)
+            wb, wv = encode(rng.uniform(-1, 1, (M, C // g, 3, 3)).astype(np.float32), kind)
+            Bv = rng.uniform(-1, 1, (M,)).astype(np.float32)
+            X, Wt, Bd = bits_to_dev(xb, kind), bits_to_dev(wb, kind), torch.from_numpy(Bv).cuda()
+            taps = lib.onnx_conv_lp_filter_taps(Wt)
+            got = lib.onnx_conv_lp_taps(X, taps, Bd, pads, st, dl, g, act=1)
+            torch.cuda.synchronize()
+            assert lib.onnx_last_launch().startswith("conv_window_lp"), lib.onnx_last_launch()
+            ws = torch.empty(16 << 20, dtype=torch.uint8, device="cuda")
+            lib.onnx_set_workspace(ws)
+            try:
+                same = lib.onnx_conv_lp(X, Wt, Bd, pads, st, dl, g, act=1)
+                torch.cuda.synchronize()
+            finally:
+                lib.onnx_set_workspace(None)
+            assert torch.equal(got.view(torch.int16), same.view(torch.int16))
+            ref, S = oracle.conv(xv, wv, Bv, pads, st, dl, g, relu=False, want_scale=True)
+            want = np.maximum(ref, 0)
+            u = 2.0 ** -PRECISION[kind]
+            assert (np.abs(lp_to_host(got, kind) - want) <= u * np.abs(want) + (C // g * 9 + 5) * 2.0 ** -24 * (S + 1.0) + 1e-7).all()
+    # shapes the kernel does not take are refused before any launch
+    x = torch.zeros((1, 16, 300, 300), dtype=torch.bfloat16, device="cuda")            # rows longer than the widest tile
+    w = torch.zeros((8, 16, 3, 3), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(lib.OnnxHipError) as e:
+        lib.onnx_conv_lp_taps(x, lib.onnx_conv_lp_filter_taps(w), None, (1, 1, 1, 1))
+    assert e.value.status == 5
+    with pytest.raises(lib.OnnxHipError):
+        lib.onnx_conv_lp_filter_taps(torch.zeros((8, 24, 3, 3), dtype=torch.bfloat16, device="cuda"))
+    with pytest.raises(lib.OnnxHipError):
+        lib.onnx_conv_lp_filter_taps(torch.zeros((8, 16, 5, 5), dtype=torch.bfloat16, device="cuda"))
+
+
 def test_conv3x3_16bit_workspace_too_small_or_channels_not_16(lib, lp_workspace):
     """The LDS-patch kernel needs room for the rewritten filter bank and 16 | channels per group; otherwise the
     general kernel runs, with the same result up to summation order."""
