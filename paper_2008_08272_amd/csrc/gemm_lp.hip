@@ -39,12 +39,16 @@ hipError_t launch_tile(ContractionParams& p, int nz, hipStream_t stream) {
     const double t128 = (double)((p.M + 127) / 128) * (double)((p.N + 127) / 128) * nz;
     const double c256 = (double)(int64_t)((t256 + cus - 1) / cus) * 65536.0 / 1.0;
     const double c128 = (t128 / cus < 1.0 ? 1.0 : t128 / cus) * 16384.0 / 0.85;
+    // at most 64 rows: a larger tile would be half empty (ResNet-50's 1x1 layers with 64 filters at batch 32: 18.6 -> 12.4
+    // and 25.6 -> 18.4 us)
+    if (p.M <= 64) return launch_instance<64, 64, 64, 2, 2, DT, LP_OUT, 2, BKIND, BVEC>(p, nz, stream);
     // (loads two steps ahead for a K-contiguous B; the row-contiguous loader's pairing needs the registers of
     // the second staging set: with it the kernel spills inside its main loop)
     if (c256 <= c128) return launch_instance<256, 256, 64, 2, 4, DT, LP_OUT, BKIND == LOAD_KC ? 2 : 1, BKIND, BVEC>(p, nz, stream);
-    // fewer 128 x 128 tiles than half the CUs: 64 x 64 tiles spread the product over the chip (measured
-    // 1024^3: 213 vs 121 TFLOP/s; from 2048^3 on the larger tile wins)
-    if (t128 < cus / 2) return launch_instance<64, 64, 64, 2, 2, DT, LP_OUT, 2, BKIND, BVEC>(p, nz, stream);
+    // fewer 128 x 128 tiles than half the CUs (than all CUs when K is short): 64 x 64 tiles spread the product
+    // over the chip (measured 1024^3: 213 vs 121 TFLOP/s; from 2048^3 on the larger tile wins; 2048 x 1568 x 512:
+    // 21.8 vs 33.6 us)
+    if (t128 < cus / 2 || (t128 < cus && p.K <= 512)) return launch_instance<64, 64, 64, 2, 2, DT, LP_OUT, 2, BKIND, BVEC>(p, nz, stream);
     return launch_instance<128, 128, 64, 2, 2, DT, LP_OUT, 1, BKIND, BVEC>(p, nz, stream);
 }
 
