@@ -321,6 +321,11 @@ def main():
         details["resnet50_b32_bf16"] = dict(timing(t3), img_per_s=round(32 / (t3[0] * 1e-3), 1),
                                             tflops=round(2.0 * st["macs"] / (t3[0] * 1e-3) / 1e12, 2))
         del r
+        r = GraphRunner(workloads.resnet50(1), dev, dtype=torch.bfloat16)
+        r.capture()
+        t3 = time_call(r.replay, iters=50, warm=10)
+        details["resnet50_b1_bf16"] = dict(timing(t3), img_per_s=round(1 / (t3[0] * 1e-3), 1))
+        del r
         # the MNIST-shaped small CNN (1.6 MFLOP): one call per node (5 launches: pure launch latency) and the
         # whole model as one launch (onnx_chain: weights and activations in LDS), at batch 1 and one workgroup
         # per image at batch 64
