@@ -607,10 +607,10 @@ onnx_status onnx_conv_lp_taps(const void* X, const int64_t x_dims[4], const void
     if (out_type != ONNX_F32 && out_type != in_type) return fail(ONNX_ERR_ATTR, "conv_lp_taps: out_type must be ONNX_F32 or in_type");
     if (packed && (reinterpret_cast<uintptr_t>(packed) & 15u) != 0)
         return fail(ONNX_ERR_ATTR, "conv_lp_taps: the rewritten filter bank must be 16-byte aligned");
-    const Workspace none = {nullptr, 0};
+    const Workspace ws = workspace();      // only for split-K shares, when the output has few tiles
     return conv_with_workspace(static_cast<const float*>(X), x_dims, static_cast<const float*>(packed), w_dims, B, pads, strides,
                                dilations, group, static_cast<const float*>(residual), act, static_cast<float*>(Y), y_dims,
-                               &none, 0, stream, in_type, out_type, true);
+                               &ws, 0, stream, in_type, out_type, true);
 }
 
 onnx_status onnx_conv_lp(const void* X, const int64_t x_dims[4], const void* W, const int64_t w_dims[4], const float* B,

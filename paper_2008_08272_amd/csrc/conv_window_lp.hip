@@ -162,7 +162,9 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_lp_kernel(const Cont
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int ks1 = scalar(g.Cg / LPW_CB);
+    int ks0, ks1;                                   // the K steps this workgroup walks (all of them unless K is split)
+    split_range(g.Cg / LPW_CB, w.ksplit, w.split, ks0, ks1);
+    ks0 = scalar(ks0); ks1 = scalar(ks1);
     const int chan_bytes = scalar(HW * 2);
 
     floatx4 reg_a[2][PA];
@@ -265,16 +267,28 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_lp_kernel(const Cont
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    fetch(0, Set0{});
-    fetch(1, Set1{});
+    fetch(ks0, Set0{});
+    fetch(ks0 + 1, Set1{});
     commit(0, Set0{});
     __syncthreads();
     frags(0, lds_a[0], lds_b[0], 0);
-    for (int ks = 0; ks < ks1; ks += 2) {
+    for (int ks = ks0; ks < ks1; ks += 2) {
         step(ks, Set0{}, Set1{});
         if (ks + 1 < ks1) step(ks + 1, Set1{}, Set0{});
     }
-    // (the launcher never splits K for this kernel)
+    // With K split over several workgroups the partial tile is parked in the workspace (register-major,
+    // thread-minor, as finish_tile does) and window_lp_finish_kernel adds the shares and runs the epilogue.
+    if (w.ksplit > 1) {
+        constexpr int TILE = NT * TM * TN * 16;
+        float* mine = cp.ws_partial + w.slot * TILE + threadIdx.x;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mine[((i * TN + j) * 16 + r) * NT] = acc[i][j][r];
+        return;
+    }
     if constexpr (LP_OUT) {
         static_assert(WM * WN * lp_strip_bytes<WTN>() <= 2 * (BM * LPW_LDA + 16), "the strips of the epilogue fit in the filter buffers");
         __syncthreads();                             // every wavefront is done reading the operand buffers
@@ -282,6 +296,59 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_lp_kernel(const Cont
                                             reinterpret_cast<float*>(&lds_a[0][0] + wave * lp_strip_bytes<WTN>()));
     }
     else finish_tile<TM, TN, WTM, WTN, NT>(acc, w, wm, wn, li, h, cp);
+}
+
+// Second half of a convolution whose K range was split: the thread-to-accumulator mapping of the
+// kernel above; the shares of a tile are added in split order (four requested at a time, a share
+// past the last one being an out-of-range offset that returns 0), then the same epilogues.
+template <int BM, int BN, int WM, int WN, int DT, bool LP_OUT>
+__global__ __launch_bounds__(64 * WM * WN) void window_lp_finish_kernel(const ContractionParams cp) {
+    constexpr int NT = 64 * WM * WN;
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int TILE = NT * TM * TN * 16;
+    constexpr int AHEAD = 4;
+    TileWork w;
+    w.zslice = blockIdx.y * gridDim.z + blockIdx.z;
+    if (w.zslice >= cp.nz) return;
+    const int ntiles = cp.tiles_m * cp.tiles_n;
+    w.ksplit = 1; w.split = 0; w.slot = 0;
+    tile_origin(cp, xcd_contiguous(blockIdx.x, ntiles), BM, BN, w.m0, w.n0);
+    w.m0 = scalar(w.m0); w.n0 = scalar(w.n0); w.zslice = scalar(w.zslice);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int li = lane & 31, h = lane >> 5;
+    const int64_t first_slot = ((int64_t)w.zslice * ntiles + blockIdx.x) * cp.ksplit;
+    const __amdgpu_buffer_rsrc_t rp = tile_rsrc(cp.ws_partial + first_slot * TILE);
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            for (int s0 = 0; s0 < cp.ksplit; s0 += AHEAD) {
+                float v[AHEAD][16];
+#pragma unroll
+                for (int u = 0; u < AHEAD; ++u) {
+                    const uint32_t share = s0 + u < cp.ksplit ? (uint32_t)threadIdx.x * 4u : OOB;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        v[u][r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                      rp, (int)share, ((s0 + u) * TILE + ((i * TN + j) * 16 + r) * NT) * 4, 0));
+                }
+#pragma unroll
+                for (int u = 0; u < AHEAD; ++u)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] += v[u][r];
+            }
+        }
+    if constexpr (LP_OUT) store_tile_lp<DT, TM, TN, WTM, WTN>(acc, w, wm, wn, li, h, cp);
+    else store_tile<TM, TN, WTM, WTN>(acc, w.m0, w.n0, w.zslice, wm, wn, li, h, cp);
 }
 
 struct WindowLpConfig {
@@ -308,44 +375,69 @@ int patch_rows(int bn, int OH, int OW, int sH, int E) {
     return (nr - nimg) * sH + nimg * per_image;
 }
 
+// The workspace a launch may park split-K shares in (what is left of the caller's behind the rewritten
+// filter bank, if that lives there too).
+struct SplitSpace {
+    float* partial;
+    int64_t floats;
+};
+
 template <int BM, int BN, int WM, int WN, int DT, bool LP_OUT, bool PAIR, int NPU>
-hipError_t launch_instance(ContractionParams& p, int nz, hipStream_t stream) {
+hipError_t launch_instance(ContractionParams& p, int nz, const SplitSpace& space, hipStream_t stream) {
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     p.nz = nz;
-    p.ksplit = 1;
-    p.ws_partial = nullptr;
-    const hipError_t e = launch_with_split<BM, BN, WM, WN, 1, false>(conv_window_lp_kernel<BM, BN, WM, WN, DT, LP_OUT, PAIR, NPU>, p, nz,
-                                                                     p.ic.Cg / LPW_CB, 0, stream);
-    record_launch(LaunchRecord{"conv_window_lp", BM, BN, LPW_KA, WM, WN, 1, LOAD_KC, LOAD_IM2COL, 8, PAIR ? 2 : 1, NPU, 1, 0, 1});
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    const Workspace ws = {space.partial, space.floats};
+    // few tiles (small batches, the 7 x 7 layers): split the channel steps over several workgroups per tile.  The
+    // 64 x 128 tile is only ever chosen for more tiles than a split pays for: it has no finishing kernel.
+    constexpr bool kMaySplit = BM == BN;
+    p.ksplit = kMaySplit ? pick_split(tiles * nz, p.ic.Cg / LPW_CB, (int64_t)BM * BN, 4.0, ws) : 1;
+    p.ws_partial = space.partial;
+    p.tail_begin = (int)tiles;
+    p.tail_split = 1;
+    const unsigned gz = nz < 32768 ? (unsigned)nz : 32768u;
+    const unsigned gy = ((unsigned)nz + gz - 1) / gz;
+    if (tiles > 0x7fffffffLL || gy * (unsigned)p.ksplit > 65535u) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((conv_window_lp_kernel<BM, BN, WM, WN, DT, LP_OUT, PAIR, NPU>), dim3((unsigned)tiles, gy * (unsigned)p.ksplit, gz),
+                       dim3(64 * WM * WN), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if constexpr (kMaySplit) {
+        if (e == hipSuccess && p.ksplit > 1) {
+            hipLaunchKernelGGL((window_lp_finish_kernel<BM, BN, WM, WN, DT, LP_OUT>), dim3((unsigned)tiles, gy, gz), dim3(64 * WM * WN), 0,
+                               stream, p);
+            e = hipGetLastError();
+        }
+    }
+    record_launch(LaunchRecord{"conv_window_lp", BM, BN, LPW_KA, WM, WN, 1, LOAD_KC, LOAD_IM2COL, 8, PAIR ? 2 : 1, NPU, p.ksplit, 0, 1});
     return e;
 }
 
 // npu = passes over the single-position units; a pair unit covers two of them.
 template <int BM, int BN, int WM, int WN, int DT, bool LP_OUT>
-hipError_t launch_units(ContractionParams& p, bool pair, int npu, int nz, hipStream_t stream) {
+hipError_t launch_units(ContractionParams& p, bool pair, int npu, int nz, const SplitSpace& space, hipStream_t stream) {
     if (pair) {
-        if (npu <= 2) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, true, 1>(p, nz, stream);
-        if (npu <= 4) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, true, 2>(p, nz, stream);
+        if (npu <= 2) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, true, 1>(p, nz, space, stream);
+        if (npu <= 4) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, true, 2>(p, nz, space, stream);
         if constexpr (WM * WN <= 4) {
-            if (npu <= 8) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, true, 4>(p, nz, stream);
+            if (npu <= 8) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, true, 4>(p, nz, space, stream);
         }
         return hipErrorInvalidValue;
     }
-    if (npu <= 2) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, false, 2>(p, nz, stream);
-    if (npu <= 4) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, false, 4>(p, nz, stream);
+    if (npu <= 2) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, false, 2>(p, nz, space, stream);
+    if (npu <= 4) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, false, 4>(p, nz, space, stream);
     if constexpr (WM * WN <= 4) {
-        if (npu <= 8) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, false, 8>(p, nz, stream);
+        if (npu <= 8) return launch_instance<BM, BN, WM, WN, DT, LP_OUT, false, 8>(p, nz, space, stream);
     }
     return hipErrorInvalidValue;
 }
 
 template <int DT, bool LP_OUT>
-hipError_t launch_config(ContractionParams& p, int cfg, bool pair, int npu, int nz, hipStream_t stream) {
+hipError_t launch_config(ContractionParams& p, int cfg, bool pair, int npu, int nz, const SplitSpace& space, hipStream_t stream) {
     switch (cfg) {
-        case 0: return launch_units<64, 64, 2, 2, DT, LP_OUT>(p, pair, npu, nz, stream);
-        case 1: return launch_units<128, 128, 2, 4, DT, LP_OUT>(p, pair, npu, nz, stream);
-        case 2: return launch_units<64, 128, 2, 2, DT, LP_OUT>(p, pair, npu, nz, stream);
+        case 0: return launch_units<64, 64, 2, 2, DT, LP_OUT>(p, pair, npu, nz, space, stream);
+        case 1: return launch_units<128, 128, 2, 4, DT, LP_OUT>(p, pair, npu, nz, space, stream);
+        case 2: return launch_units<64, 128, 2, 2, DT, LP_OUT>(p, pair, npu, nz, space, stream);
         default: return hipErrorInvalidValue;
     }
 }
@@ -401,16 +493,20 @@ bool launch_conv_window_lp(ContractionParams& p, int kH, int kW, int OH, int OW,
     g.planed = FastDiv::make((uint32_t)(pair ? best_plane / 2 : best_plane));
     g.IPRd = FastDiv::make((uint32_t)g.IPR);
 
+    SplitSpace space = {ws.partial, ws.partial ? ws.partial_floats : 0};
     if (!filters_in_tap_order) {
         const hipError_t e = launch_lp_filter_taps(p.A, ws.partial, (int64_t)p.M * nz, Cg, stream);
         if (e != hipSuccess) { *status = e; return true; }
         p.A = ws.partial;
+        const int64_t used = (filter_values * 2 + 255) / 256 * 64;          // floats, a multiple of 256 bytes
+        space.partial += used;
+        space.floats -= used;
     }
 
     const int npu = (2 * best_plane + kConfigs[best].nt - 1) / kConfigs[best].nt;
     const bool lp_out = out_type != 0;
-    if (in_type == LP_BF16) *status = lp_out ? launch_config<LP_BF16, true>(p, best, pair, npu, nz, stream) : launch_config<LP_BF16, false>(p, best, pair, npu, nz, stream);
-    else *status = lp_out ? launch_config<LP_F16, true>(p, best, pair, npu, nz, stream) : launch_config<LP_F16, false>(p, best, pair, npu, nz, stream);
+    if (in_type == LP_BF16) *status = lp_out ? launch_config<LP_BF16, true>(p, best, pair, npu, nz, space, stream) : launch_config<LP_BF16, false>(p, best, pair, npu, nz, space, stream);
+    else *status = lp_out ? launch_config<LP_F16, true>(p, best, pair, npu, nz, space, stream) : launch_config<LP_F16, false>(p, best, pair, npu, nz, space, stream);
     return true;
 }
 

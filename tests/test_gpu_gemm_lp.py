@@ -347,6 +347,8 @@ CONV3X3_LP_CASES = [
     (40, 16, 20, 20, 256, (1, 1, 1, 1), (1, 1), (1, 3), 1, "128x128x144 2 1"),
     (40, 16, 24, 50, 128, (1, 1, 1, 1), (2, 1), (2, 2), 1, "128x128x144 2 2"),
     (70, 32, 14, 14, 300, (1, 1, 1, 1), (1, 1), (1, 1), 2, "64x128x144 2 2"),     # two groups of 150 filters: a ragged third row of tiles
+    (2, 512, 7, 7, 72, (1, 1, 1, 1), (1, 1), (1, 1), 1, "64x64x144 1 2 split"),   # 4 tiles, 32 channel steps: K split, finishing kernel
+    (1, 256, 50, 100, 128, (1, 1, 1, 1), (1, 1), (1, 1), 1, "128x128x144 2 2 split"),  # rows wider than 64: 40 tiles of 128 x 128, K split
     (700, 16, 9, 9, 40, (1, 1, 1, 1), (1, 1), (1, 1), 1, "64x128x144 1 2"),       # few filters, many positions: the 64 x 128 tile
     (80, 16, 30, 31, 40, (1, 1, 1, 1), (1, 1), (1, 1), 1, "64x128x144 1 4"),
     (80, 16, 25, 51, 40, (1, 1, 1, 1), (1, 1), (2, 2), 1, "64x128x144 1 8"),
@@ -390,9 +392,10 @@ def test_conv3x3_16bit_lds_patch_matches_oracle(lib, lp_workspace, case, kind):
     X, Wt = bits_to_dev(xb, kind), bits_to_dev(wb, kind)
     got = lib.onnx_conv_lp(X, Wt, torch.from_numpy(Bv).cuda(), pads, st, dl, g, out_dtype=torch.float32)
     torch.cuda.synchronize()
-    tile, cols, npb = expect.split()
+    tile, cols, npb = expect.split()[:3]
     launch = lib.onnx_last_launch()
     assert launch.startswith("conv_window_lp " + tile) and "B=IM2COL/%s npb=%s " % (cols, npb) in launch, launch
+    assert ("ksplit=1 " not in launch) == expect.endswith("split"), launch
     gth = got.cpu().numpy()
     assert gth.shape == ref.shape
     assert rel_err(gth, ref) <= REL_TOL
