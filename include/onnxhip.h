@@ -291,7 +291,8 @@ onnx_status onnx_conv_lp(const void* X, const int64_t x_dims[4], const void* W, 
  * and onnx_conv_lp rewrites W into that order in the workspace on every call.
  * onnx_conv_lp_filter_taps does the rewriting once, into `packed` (device memory of the size of
  * W, 16-byte aligned, caller-owned); onnx_conv_lp_taps is onnx_conv_lp with `packed` in place of
- * W (w_dims still the ONNX shape [M, C/group, 3, 3]) and uses no workspace.  Both need 3x3
+ * W (w_dims still the ONNX shape [M, C/group, 3, 3]); it needs no workspace and uses one only
+ * to split K when the output has few tiles.  Both need 3x3
  * windows and C/group a multiple of 16; onnx_conv_lp_taps returns ONNX_ERR_UNSUPPORTED, before
  * any launch, for shapes whose input patch does not fit the kernel (the caller then uses
  * onnx_conv_lp with W).

@@ -403,7 +403,7 @@ def onnx_conv_lp_filter_taps(W, stream=None):
 
 def onnx_conv_lp_taps(X, packed, B=None, pads=(0, 0, 0, 0), strides=(1, 1), dilations=(1, 1), group=1, residual=None,
                       act=ACT_NONE, out_dtype=None, out=None, stream=None):
-    """onnx_conv_lp for a 3x3 filter bank rewritten by onnx_conv_lp_filter_taps (it keeps W's shape); no workspace."""
+    """onnx_conv_lp for a 3x3 filter bank rewritten by onnx_conv_lp_filter_taps (it keeps W's shape); needs no workspace."""
     X = _lp(X, "X")
     packed = _lp(packed, "packed", X)
     B = _dev(B, "B")
