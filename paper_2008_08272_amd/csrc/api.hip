@@ -231,10 +231,14 @@ onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const f
             q.B = reinterpret_cast<const float*>(ws_free);
             q.b_ld = C; q.b_bs[0] = Cg; q.b_img = 0;
             if (lp_tuned_fits(q, LOAD_KC, LOAD_KC, (int)group))
-                return device_status(launch_lp_tuned(q, LOAD_KC, 8, (int)group, (int)in_type, (int)out_type, s), "conv (16-bit)");
+                return device_status(launch_lp_tuned(q, LOAD_KC, 8, (int)group, (int)in_type, (int)out_type,
+                                                     Workspace{reinterpret_cast<float*>(ws_free + copy_bytes), (ws_bytes - copy_bytes) / 4}, s),
+                                     "conv (16-bit)");
         }
         if (bvec)
-            return device_status(launch_lp_tuned(p, LOAD_RC, bvec, (int)group, (int)in_type, (int)out_type, s), "conv (16-bit)");
+            return device_status(launch_lp_tuned(p, LOAD_RC, bvec, (int)group, (int)in_type, (int)out_type,
+                                                 Workspace{ws_bytes > 0 ? reinterpret_cast<float*>(ws_free) : nullptr, ws_bytes / 4}, s),
+                                 "conv (16-bit)");
         if (!pw) {
             hipError_t e = hipSuccess;
             if (launch_conv_window_lp(p, (int)kH, (int)kW, (int)OH, (int)OW, (int)Cg, (int)group, (int)in_type, (int)out_type,
@@ -385,7 +389,7 @@ onnx_status matmul_any(const float* A, const int64_t* a_dims, int a_rank, const 
     if (in_type != ONNX_F32) {
         const int bvec = lp_tuned_fits(p, LOAD_KC, LOAD_RC, (int)nz);
         if (bvec)
-            return device_status(launch_lp_tuned(p, LOAD_RC, bvec, (int)nz, (int)in_type, (int)out_type,
+            return device_status(launch_lp_tuned(p, LOAD_RC, bvec, (int)nz, (int)in_type, (int)out_type, workspace(),
                                                  static_cast<hipStream_t>(stream)), "matmul (16-bit)");
         return device_status(launch_lp_generic(p, LOAD_KC, LOAD_RC, (int)nz, (int)in_type, (int)out_type,
                                                static_cast<hipStream_t>(stream)), "matmul (16-bit)");

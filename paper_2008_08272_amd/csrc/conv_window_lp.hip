@@ -277,17 +277,12 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_lp_kernel(const Cont
         if (ks + 1 < ks1) step(ks + 1, Set1{}, Set0{});
     }
     // With K split over several workgroups the partial tile is parked in the workspace (register-major,
-    // thread-minor, as finish_tile does) and window_lp_finish_kernel adds the shares and runs the epilogue.
-    if (w.ksplit > 1) {
-        constexpr int TILE = NT * TM * TN * 16;
-        float* mine = cp.ws_partial + w.slot * TILE + threadIdx.x;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mine[((i * TN + j) * 16 + r) * NT] = acc[i][j][r];
-        return;
+    // thread-minor, as finish_tile does) and lp_finish_kernel adds the shares and runs the epilogue.
+    if constexpr (BM == BN) {                        // (the 64 x 128 tile is never launched with a split)
+        if (w.ksplit > 1) {
+            park_partial_tile<TM, TN, NT>(acc, w, cp);
+            return;
+        }
     }
     if constexpr (LP_OUT) {
         static_assert(WM * WN * lp_strip_bytes<WTN>() <= 2 * (BM * LPW_LDA + 16), "the strips of the epilogue fit in the filter buffers");
@@ -296,59 +291,6 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_window_lp_kernel(const Cont
                                             reinterpret_cast<float*>(&lds_a[0][0] + wave * lp_strip_bytes<WTN>()));
     }
     else finish_tile<TM, TN, WTM, WTN, NT>(acc, w, wm, wn, li, h, cp);
-}
-
-// Second half of a convolution whose K range was split: the thread-to-accumulator mapping of the
-// kernel above; the shares of a tile are added in split order (four requested at a time, a share
-// past the last one being an out-of-range offset that returns 0), then the same epilogues.
-template <int BM, int BN, int WM, int WN, int DT, bool LP_OUT>
-__global__ __launch_bounds__(64 * WM * WN) void window_lp_finish_kernel(const ContractionParams cp) {
-    constexpr int NT = 64 * WM * WN;
-    constexpr int WTM = BM / WM, WTN = BN / WN;
-    constexpr int TM = WTM / 32, TN = WTN / 32;
-    constexpr int TILE = NT * TM * TN * 16;
-    constexpr int AHEAD = 4;
-    TileWork w;
-    w.zslice = blockIdx.y * gridDim.z + blockIdx.z;
-    if (w.zslice >= cp.nz) return;
-    const int ntiles = cp.tiles_m * cp.tiles_n;
-    w.ksplit = 1; w.split = 0; w.slot = 0;
-    tile_origin(cp, xcd_contiguous(blockIdx.x, ntiles), BM, BN, w.m0, w.n0);
-    w.m0 = scalar(w.m0); w.n0 = scalar(w.n0); w.zslice = scalar(w.zslice);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave / WN, wn = wave % WN;
-    const int li = lane & 31, h = lane >> 5;
-    const int64_t first_slot = ((int64_t)w.zslice * ntiles + blockIdx.x) * cp.ksplit;
-    const __amdgpu_buffer_rsrc_t rp = tile_rsrc(cp.ws_partial + first_slot * TILE);
-    floatx16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            for (int s0 = 0; s0 < cp.ksplit; s0 += AHEAD) {
-                float v[AHEAD][16];
-#pragma unroll
-                for (int u = 0; u < AHEAD; ++u) {
-                    const uint32_t share = s0 + u < cp.ksplit ? (uint32_t)threadIdx.x * 4u : OOB;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        v[u][r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                      rp, (int)share, ((s0 + u) * TILE + ((i * TN + j) * 16 + r) * NT) * 4, 0));
-                }
-#pragma unroll
-                for (int u = 0; u < AHEAD; ++u)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[i][j][r] += v[u][r];
-            }
-        }
-    if constexpr (LP_OUT) store_tile_lp<DT, TM, TN, WTM, WTN>(acc, w, wm, wn, li, h, cp);
-    else store_tile<TM, TN, WTM, WTN>(acc, w.m0, w.n0, w.zslice, wm, wn, li, h, cp);
 }
 
 struct WindowLpConfig {
@@ -404,7 +346,7 @@ hipError_t launch_instance(ContractionParams& p, int nz, const SplitSpace& space
     hipError_t e = hipGetLastError();
     if constexpr (kMaySplit) {
         if (e == hipSuccess && p.ksplit > 1) {
-            hipLaunchKernelGGL((window_lp_finish_kernel<BM, BN, WM, WN, DT, LP_OUT>), dim3((unsigned)tiles, gy, gz), dim3(64 * WM * WN), 0,
+            hipLaunchKernelGGL((lp_finish_kernel<BM, BN, WM, WN, DT, LP_OUT>), dim3((unsigned)tiles, gy, gz), dim3(64 * WM * WN), 0,
                                stream, p);
             e = hipGetLastError();
         }

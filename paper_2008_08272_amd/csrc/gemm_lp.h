@@ -474,6 +474,73 @@ __device__ __forceinline__ void store_tile_lp(const floatx16 (&acc)[TM][TN], con
     }
 }
 
+// A workgroup's share of a tile whose K range is split: parked in the workspace, register-major and
+// thread-minor (every access coalesced), for lp_finish_kernel.
+template <int TM, int TN, int NT>
+__device__ __forceinline__ void park_partial_tile(const floatx16 (&acc)[TM][TN], const TileWork& w, const ContractionParams& cp) {
+    constexpr int TILE = NT * TM * TN * 16;
+    float* mine = cp.ws_partial + w.slot * TILE + threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mine[((i * TN + j) * 16 + r) * NT] = acc[i][j][r];
+}
+
+// Second half of a product whose K range was split over several workgroups per tile (park_partial_tile
+// below): the thread-to-accumulator mapping of the kernel that parked the shares; the shares of a tile are added in split order (four requested at a time, a share
+// past the last one being an out-of-range offset that returns 0), then the same epilogues.
+template <int BM, int BN, int WM, int WN, int DT, bool LP_OUT>
+__global__ __launch_bounds__(64 * WM * WN) void lp_finish_kernel(const ContractionParams cp) {
+    constexpr int NT = 64 * WM * WN;
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int TILE = NT * TM * TN * 16;
+    constexpr int AHEAD = 4;
+    TileWork w;
+    w.zslice = blockIdx.y * gridDim.z + blockIdx.z;
+    if (w.zslice >= cp.nz) return;
+    const int ntiles = cp.tiles_m * cp.tiles_n;
+    w.ksplit = 1; w.split = 0; w.slot = 0;
+    tile_origin(cp, xcd_contiguous(blockIdx.x, ntiles), BM, BN, w.m0, w.n0);
+    w.m0 = scalar(w.m0); w.n0 = scalar(w.n0); w.zslice = scalar(w.zslice);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int li = lane & 31, h = lane >> 5;
+    const int64_t first_slot = ((int64_t)w.zslice * ntiles + blockIdx.x) * cp.ksplit;
+    const __amdgpu_buffer_rsrc_t rp = tile_rsrc(cp.ws_partial + first_slot * TILE);
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            for (int s0 = 0; s0 < cp.ksplit; s0 += AHEAD) {
+                float v[AHEAD][16];
+#pragma unroll
+                for (int u = 0; u < AHEAD; ++u) {
+                    const uint32_t share = s0 + u < cp.ksplit ? (uint32_t)threadIdx.x * 4u : OOB;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        v[u][r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                      rp, (int)share, ((s0 + u) * TILE + ((i * TN + j) * 16 + r) * NT) * 4, 0));
+                }
+#pragma unroll
+                for (int u = 0; u < AHEAD; ++u)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] += v[u][r];
+            }
+        }
+    if constexpr (LP_OUT) store_tile_lp<DT, TM, TN, WTM, WTN>(acc, w, wm, wn, li, h, cp);
+    else store_tile<TM, TN, WTM, WTN>(acc, w.m0, w.n0, w.zslice, wm, wn, li, h, cp);
+}
+
 // BKIND: LOAD_KC (B stored [N][K], 16-byte chunks of 8 k) or LOAD_RC (B stored [K][N], chunks of
 // BVEC columns).
 template <int BM, int BN, int BK, int WM, int WN, int DT, bool LP_OUT, int PF, int BKIND, int BVEC>
@@ -582,7 +649,14 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_lp_kernel(const Contraction
         if (kt + 1 < kt1) step(kt + 1, Par1{});
     }
 
-    // (the launcher never splits K for this kernel, so a 16-bit result has no partial-sum form)
+    // K split over several workgroups (only the 64 x 64 tile is ever launched that way; in the larger instances the
+    // parking code alone cost the registers of their second workgroup per CU): lp_finish_kernel does the rest
+    if constexpr (BM == 64 && BN == 64) {
+        if (w.ksplit > 1) {
+            park_partial_tile<TM, TN, NT>(acc, w, cp);
+            return;
+        }
+    }
     if constexpr (LP_OUT) {
         static_assert(WM * WN * lp_strip_bytes<WTN>() <= 2 * ALoader::LDS_BYTES, "the strips of the epilogue fit in A's buffers");
         __syncthreads();                             // every wavefront is done reading the operand buffers

@@ -13,27 +13,39 @@ namespace {
 #define fail(st, ...) static_cast<onnx_status>(fail_with((st), __VA_ARGS__))
 
 template <int BM, int BN, int BK, int WM, int WN, int DT, bool LP_OUT, int PF, int BKIND, int BVEC>
-hipError_t launch_instance(ContractionParams& p, int nz, hipStream_t stream) {
+hipError_t launch_instance(ContractionParams& p, int nz, const Workspace& ws, hipStream_t stream) {
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     p.nz = nz;
-    p.ksplit = 1;                                    // every tile walks its whole K range
-    p.ws_partial = nullptr;
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    // The 64 x 64 tile is the one chosen for outputs with few tiles: with a workspace its K range may be split over
+    // several workgroups per tile (lp_finish_kernel adds the shares); the larger tiles walk their whole K range.
+    // Only outputs that leave half the CUs idle: with more tiles than that the shares and the finishing kernel (whose
+    // 16-bit epilogue has no LDS strip) cost more than they save (ResNet-50 in bf16 at batch 32: 1.78 against 1.51 ms).
+    constexpr bool kMaySplit = BM == 64;
+    p.ksplit = kMaySplit && tiles * nz <= 128 ? pick_split(tiles * nz, (p.K + BK - 1) / BK, (int64_t)BM * BN, 4.0, ws) : 1;
+    p.ws_partial = ws.partial;
     const unsigned gz = nz < 32768 ? (unsigned)nz : 32768u;
     const unsigned gy = ((unsigned)nz + gz - 1) / gz;
-    if (tiles > 0x7fffffffLL || gy > 65535u) return hipErrorInvalidValue;
+    if (tiles > 0x7fffffffLL || gy * (unsigned)p.ksplit > 65535u) return hipErrorInvalidValue;
     p.tail_begin = (int)tiles;
     p.tail_split = 1;
-    hipLaunchKernelGGL((gemm_lp_kernel<BM, BN, BK, WM, WN, DT, LP_OUT, PF, BKIND, BVEC>), dim3((unsigned)tiles, gy, gz),
+    hipLaunchKernelGGL((gemm_lp_kernel<BM, BN, BK, WM, WN, DT, LP_OUT, PF, BKIND, BVEC>), dim3((unsigned)tiles, gy * (unsigned)p.ksplit, gz),
                        dim3(64 * WM * WN), 0, stream, p);
-    record_launch(LaunchRecord{"gemm_lp", BM, BN, BK, WM, WN, 1, LOAD_KC, BKIND, 8, BVEC, DT + (LP_OUT ? 2 : 0), 1, 0, 1});
-    return hipGetLastError();
+    hipError_t e = hipGetLastError();
+    if constexpr (kMaySplit) {
+        if (e == hipSuccess && p.ksplit > 1) {
+            hipLaunchKernelGGL((lp_finish_kernel<BM, BN, WM, WN, DT, LP_OUT>), dim3((unsigned)tiles, gy, gz), dim3(64 * WM * WN), 0, stream, p);
+            e = hipGetLastError();
+        }
+    }
+    record_launch(LaunchRecord{"gemm_lp", BM, BN, BK, WM, WN, 1, LOAD_KC, BKIND, 8, BVEC, DT + (LP_OUT ? 2 : 0), p.ksplit, 0, 1});
+    return e;
 }
 
 // Tile by the same estimate as the fp32 kernel: workgroups per CU x tile area / efficiency.
 template <int DT, bool LP_OUT, int BKIND, int BVEC>
-hipError_t launch_tile(ContractionParams& p, int nz, hipStream_t stream) {
+hipError_t launch_tile(ContractionParams& p, int nz, const Workspace& ws, hipStream_t stream) {
     const double cus = 256.0;
     const double t256 = (double)((p.M + 255) / 256) * (double)((p.N + 255) / 256) * nz;
     const double t128 = (double)((p.M + 127) / 128) * (double)((p.N + 127) / 128) * nz;
@@ -41,21 +53,21 @@ hipError_t launch_tile(ContractionParams& p, int nz, hipStream_t stream) {
     const double c128 = (t128 / cus < 1.0 ? 1.0 : t128 / cus) * 16384.0 / 0.85;
     // at most 64 rows: a larger tile would be half empty (ResNet-50's 1x1 layers with 64 filters at batch 32: 18.6 -> 12.4
     // and 25.6 -> 18.4 us)
-    if (p.M <= 64) return launch_instance<64, 64, 64, 2, 2, DT, LP_OUT, 2, BKIND, BVEC>(p, nz, stream);
+    if (p.M <= 64) return launch_instance<64, 64, 64, 2, 2, DT, LP_OUT, 2, BKIND, BVEC>(p, nz, ws, stream);
     // (loads two steps ahead for a K-contiguous B; the row-contiguous loader's pairing needs the registers of
     // the second staging set: with it the kernel spills inside its main loop)
-    if (c256 <= c128) return launch_instance<256, 256, 64, 2, 4, DT, LP_OUT, BKIND == LOAD_KC ? 2 : 1, BKIND, BVEC>(p, nz, stream);
+    if (c256 <= c128) return launch_instance<256, 256, 64, 2, 4, DT, LP_OUT, BKIND == LOAD_KC ? 2 : 1, BKIND, BVEC>(p, nz, ws, stream);
     // fewer 128 x 128 tiles than half the CUs (than all CUs when K is short): 64 x 64 tiles spread the product
     // over the chip (measured 1024^3: 213 vs 121 TFLOP/s; from 2048^3 on the larger tile wins; 2048 x 1568 x 512:
     // 21.8 vs 33.6 us)
-    if (t128 < cus / 2 || (t128 < cus && p.K <= 512)) return launch_instance<64, 64, 64, 2, 2, DT, LP_OUT, 2, BKIND, BVEC>(p, nz, stream);
-    return launch_instance<128, 128, 64, 2, 2, DT, LP_OUT, 1, BKIND, BVEC>(p, nz, stream);
+    if (t128 < cus / 2 || (t128 < cus && p.K <= 512)) return launch_instance<64, 64, 64, 2, 2, DT, LP_OUT, 2, BKIND, BVEC>(p, nz, ws, stream);
+    return launch_instance<128, 128, 64, 2, 2, DT, LP_OUT, 1, BKIND, BVEC>(p, nz, ws, stream);
 }
 
 template <int BKIND, int BVEC>
-hipError_t launch_types(ContractionParams& p, int nz, int in_type, int out_type, hipStream_t s) {
-    if (in_type == LP_F16) return out_type == 0 ? launch_tile<LP_F16, false, BKIND, BVEC>(p, nz, s) : launch_tile<LP_F16, true, BKIND, BVEC>(p, nz, s);
-    return out_type == 0 ? launch_tile<LP_BF16, false, BKIND, BVEC>(p, nz, s) : launch_tile<LP_BF16, true, BKIND, BVEC>(p, nz, s);
+hipError_t launch_types(ContractionParams& p, int nz, int in_type, int out_type, const Workspace& ws, hipStream_t s) {
+    if (in_type == LP_F16) return out_type == 0 ? launch_tile<LP_F16, false, BKIND, BVEC>(p, nz, ws, s) : launch_tile<LP_F16, true, BKIND, BVEC>(p, nz, ws, s);
+    return out_type == 0 ? launch_tile<LP_BF16, false, BKIND, BVEC>(p, nz, ws, s) : launch_tile<LP_BF16, true, BKIND, BVEC>(p, nz, ws, s);
 }
 
 bool multiple_of(const int64_t* v, int n, int64_t m) {
@@ -90,10 +102,11 @@ int lp_tuned_fits(const ContractionParams& p, int akind, int bkind, int nz) {
     return 0;
 }
 
-hipError_t launch_lp_tuned(ContractionParams& p, int bkind, int bvec, int nz, int in_type, int out_type, hipStream_t stream) {
-    if (bkind == LOAD_KC) return launch_types<LOAD_KC, 8>(p, nz, in_type, out_type, stream);
-    if (bvec == 8) return launch_types<LOAD_RC, 8>(p, nz, in_type, out_type, stream);
-    if (bvec == 4) return launch_types<LOAD_RC, 4>(p, nz, in_type, out_type, stream);
+hipError_t launch_lp_tuned(ContractionParams& p, int bkind, int bvec, int nz, int in_type, int out_type, const Workspace& ws,
+                           hipStream_t stream) {
+    if (bkind == LOAD_KC) return launch_types<LOAD_KC, 8>(p, nz, in_type, out_type, ws, stream);
+    if (bvec == 8) return launch_types<LOAD_RC, 8>(p, nz, in_type, out_type, ws, stream);
+    if (bvec == 4) return launch_types<LOAD_RC, 4>(p, nz, in_type, out_type, ws, stream);
     return hipErrorInvalidValue;
 }
 
@@ -155,7 +168,7 @@ onnx_status onnx_gemm_lp(const void* A, const int64_t a_dims[2], const void* B, 
     // the tuned kernel: A K-contiguous, 16-byte loads, 32-bit tile offsets; everything else: the general kernel
     const int akind = transA ? LOAD_RC : LOAD_KC, bkind = transB ? LOAD_KC : LOAD_RC;
     const int bvec = lp_tuned_fits(p, akind, bkind, 1);
-    const hipError_t e = bvec ? launch_lp_tuned(p, bkind, bvec, 1, (int)in_type, (int)out_type, s)
+    const hipError_t e = bvec ? launch_lp_tuned(p, bkind, bvec, 1, (int)in_type, (int)out_type, workspace(), s)
                               : launch_lp_generic(p, akind, bkind, 1, (int)in_type, (int)out_type, s);
     if (e != hipSuccess) return fail(ONNX_ERR_DEVICE, "gemm_lp: %s", hipGetErrorString(e));
     return ONNX_OK;

@@ -77,9 +77,10 @@ hipError_t launch_lp_generic(ContractionParams& p, int akind, int bkind, int nz,
 // The tuned 16-bit kernel (gemm_lp.h): A K-contiguous, B K-contiguous or row-contiguous, wide
 // loads.  lp_tuned_fits returns 0 when `p` (filled as for launch_lp_generic) does not meet its
 // alignment and 32-bit-offset conditions, else the chunk width for B (8, or 4 for a
-// row-contiguous B whose rows are only 8-byte aligned) to pass on to launch_lp_tuned.
+// row-contiguous B whose rows are only 8-byte aligned) to pass on to launch_lp_tuned.  `ws`: where
+// the shares of a split K range may be parked (outputs with few tiles), or {nullptr, 0}.
 int lp_tuned_fits(const ContractionParams& p, int akind, int bkind, int nz);
-hipError_t launch_lp_tuned(ContractionParams& p, int bkind, int bvec, int nz, int in_type, int out_type,
+hipError_t launch_lp_tuned(ContractionParams& p, int bkind, int bvec, int nz, int in_type, int out_type, const Workspace& ws,
                            hipStream_t stream);
 
 // Convolution through an LDS-resident input patch (conv_window.h).  `p` must be filled as for

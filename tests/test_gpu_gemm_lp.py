@@ -535,6 +535,49 @@ def test_conv3x3_16bit_filters_rewritten_once(lib):
         lib.onnx_conv_lp_filter_taps(torch.zeros((8, 16, 5, 5), dtype=torch.bfloat16, device="cuda"))
 
 
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+def test_16bit_split_k_with_a_workspace(lib, lp_workspace, kind):
+    """Few tiles and a long K: with a workspace the 64 x 64 tile of the tuned kernel splits its K range over several
+    workgroups per tile and a finishing kernel adds the shares; Gemm (both B layouts), MatMul and a 1x1 convolution,
+    fp32 and 16-bit results."""
+    announce("lp split k", kind)
+    rng = np.random.default_rng(31)
+    u = 2.0 ** -PRECISION[kind]
+    for (M, N, K, transB) in [(64, 64, 4096, 1), (130, 70, 2048, 1), (200, 136, 1024, 0), (33, 260, 1536, 0)]:
+        ab, av = encode(rng.uniform(-1, 1, (M, K)).astype(np.float32), kind)
+        bb, bv = encode(rng.uniform(-1, 1, (N, K) if transB else (K, N)).astype(np.float32), kind)
+        Cv = rng.uniform(-1, 1, (1, N)).astype(np.float32)
+        A, Bm, C = bits_to_dev(ab, kind), bits_to_dev(bb, kind), torch.from_numpy(Cv).cuda()
+        ref, S = oracle.gemm(av, bv, Cv, 1.0, 1.0, 0, transB, relu=False, want_scale=True)
+        got = lib.onnx_gemm_lp(A, Bm, C, transB=transB, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        launch = lib.onnx_last_launch()
+        assert launch.startswith("gemm_lp 64x64") and "ksplit=1 " not in launch, launch
+        g = got.cpu().numpy()
+        assert rel_err(g, ref) <= REL_TOL and within_rounding_bound(g, ref, S, K + 2)
+        got2 = lp_to_host(lib.onnx_gemm_lp(A, Bm, C, transB=transB, act=1), kind)
+        assert "ksplit=1 " not in lib.onnx_last_launch()
+        want = np.maximum(ref, 0)
+        assert (np.abs(got2 - want) <= u * np.abs(want) + (K + 5) * 2.0 ** -24 * (S + 1.0) + 1e-7).all()
+    # MatMul with a batch, small integers: every partial sum exact, so the shares must add up bit for bit
+    a = rng.integers(-4, 5, (3, 70, 1024)).astype(np.float32)
+    b = rng.integers(-4, 5, (1024, 72)).astype(np.float32)
+    got = lib.onnx_matmul_lp(bits_to_dev(encode(a, kind)[0], kind), bits_to_dev(encode(b, kind)[0], kind), out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert "ksplit=1 " not in lib.onnx_last_launch(), lib.onnx_last_launch()
+    assert np.array_equal(got.cpu().numpy().astype(np.float64), oracle.matmul(a, b))
+    # 1x1 convolution on one image with a residual: 16-bit result from the finishing kernel
+    xb, xv = encode(rng.uniform(-1, 1, (1, 1024, 14, 14)).astype(np.float32), kind)
+    wb, wv = encode(rng.uniform(-1, 1, (256, 1024, 1, 1)).astype(np.float32), kind)
+    rb, rv = encode(rng.uniform(-1, 1, (1, 256, 14, 14)).astype(np.float32), kind)
+    z4, o2 = (0, 0, 0, 0), (1, 1)
+    ref, S = oracle.conv(xv, wv, None, z4, o2, o2, 1, residual=rv, relu=False, want_scale=True)
+    got = lp_to_host(lib.onnx_conv_lp(bits_to_dev(xb, kind), bits_to_dev(wb, kind), None, z4, o2, o2, 1, residual=bits_to_dev(rb, kind), act=1), kind)
+    assert "ksplit=1 " not in lib.onnx_last_launch(), lib.onnx_last_launch()
+    want = np.maximum(ref, 0)
+    assert (np.abs(got - want) <= u * np.abs(want) + (1024 + 5) * 2.0 ** -24 * (S + 1.0) + 1e-7).all()
+
+
 def test_conv3x3_16bit_workspace_too_small_or_channels_not_16(lib, lp_workspace):
     """The LDS-patch kernel needs room for the rewritten filter bank and 16 | channels per group; otherwise the
     general kernel runs, with the same result up to summation order."""
