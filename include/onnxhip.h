@@ -322,6 +322,14 @@ onnx_status onnx_avgpool_lp(const void* X, const int64_t x_dims[4], const int64_
                             onnx_dtype type, void* stream);
 
 /*
+ * ONNX LeakyRelu on a 16-bit tensor (Section 3.1: the operator's definition lists F16 among its
+ * element types): Y[i] = X[i] for X[i] >= 0, alpha * X[i] otherwise, the product taken in fp32 and
+ * rounded to the type (nearest even); alpha = 0 is Relu.  `count` elements of `type` (ONNX_F16 or
+ * ONNX_BF16); Y must not overlap X.
+ */
+onnx_status onnx_leakyrelu_lp(const void* X, int64_t count, float alpha, void* Y, onnx_dtype type, void* stream);
+
+/*
  * ONNX LSTM (named among the supported operators, Section 4.1), layout 0, default activations
  * (sigmoid, tanh, tanh), no peepholes, every sequence of full length.  X [seq, batch, input];
  * W [dirs, 4H, input] and R [dirs, 4H, H] with the gate blocks in the order i, o, f, c;

@@ -52,6 +52,8 @@ _lib.onnx_maxpool.argtypes = [_vp, _i64p, _i64p, _i64p, _i64p, _i64p, _ci, _vp, 
 _lib.onnx_avgpool.argtypes = [_vp, _i64p, _i64p, _i64p, _i64p, _ci, _ci, _vp, _i64p, _vp]
 _lib.onnx_maxpool_lp.argtypes = [_vp, _i64p, _i64p, _i64p, _i64p, _i64p, _ci, _vp, _i64p, _ci, _vp]
 _lib.onnx_avgpool_lp.argtypes = [_vp, _i64p, _i64p, _i64p, _i64p, _ci, _ci, _vp, _i64p, _ci, _vp]
+_lib.onnx_leakyrelu_lp.argtypes = [_vp, _c64, _cf, _vp, _ci, _vp]
+_lib.onnx_leakyrelu_lp.restype = _ci
 for _f in (_lib.onnx_conv_infer, _lib.onnx_pool_infer, _lib.onnx_matmul_infer, _lib.onnx_conv,
            _lib.onnx_gemm, _lib.onnx_matmul, _lib.onnx_maxpool, _lib.onnx_avgpool, _lib.onnx_maxpool_lp,
            _lib.onnx_avgpool_lp):
@@ -413,6 +415,14 @@ def onnx_conv_lp_taps(X, packed, B=None, pads=(0, 0, 0, 0), strides=(1, 1), dila
     _check(_lib.onnx_conv_lp_taps(_ptr(X), dims(X.shape), _ptr(packed), dims(packed.shape), _ptr(B), dims(pads), dims(strides),
                                   dims(dilations), int(group), _ptr(residual), int(act), _ptr(Y), dims(Y.shape),
                                   _LP_TYPES[X.dtype], ot, _stream(stream)))
+    return Y
+
+
+def onnx_leakyrelu_lp(X, alpha=0.01, out=None, stream=None):
+    """LeakyRelu on a float16 / bfloat16 CUDA tensor (alpha = 0: Relu); the result has the same type."""
+    X = _lp(X, "X")
+    Y, _ = _lp_out(out, X.shape, X.dtype, X)
+    _check(_lib.onnx_leakyrelu_lp(_ptr(X), X.numel(), float(alpha), _ptr(Y), _LP_TYPES[X.dtype], _stream(stream)))
     return Y
 
 

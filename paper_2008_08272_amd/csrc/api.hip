@@ -748,6 +748,15 @@ onnx_status onnx_maxpool_lp(const void* X, const int64_t x_dims[4], const int64_
     return maxpool_any(X, x_dims, kernel, pads, strides, dilations, ceil_mode, Y, nullptr, y_dims, type, stream);
 }
 
+onnx_status onnx_leakyrelu_lp(const void* X, int64_t count, float alpha, void* Y, onnx_dtype type, void* stream) {
+    if (type != ONNX_F16 && type != ONNX_BF16) return fail(ONNX_ERR_ATTR, "leakyrelu_lp: type must be ONNX_F16 or ONNX_BF16");
+    if (count < 0) return fail(ONNX_ERR_SHAPE, "leakyrelu_lp: negative element count");
+    if (count == 0) return ONNX_OK;
+    if (!X || !Y) return fail(ONNX_ERR_NULL, "leakyrelu_lp: X and Y must not be NULL");
+    if (overlaps(Y, count * 2, X, count * 2)) return fail(ONNX_ERR_ALIAS, "leakyrelu_lp: Y overlaps X");
+    return device_status(launch_leakyrelu_lp(X, Y, count, alpha, (int)type, static_cast<hipStream_t>(stream)), "leakyrelu_lp");
+}
+
 onnx_status onnx_avgpool_lp(const void* X, const int64_t x_dims[4], const int64_t* kernel, const int64_t* pads,
                             const int64_t* strides, int ceil_mode, int count_include_pad, void* Y,
                             const int64_t y_dims[4], onnx_dtype type, void* stream) {

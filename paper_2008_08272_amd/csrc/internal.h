@@ -131,5 +131,6 @@ hipError_t launch_global_avgpool(const float* X, float* Y, int64_t planes, int H
 hipError_t launch_maxpool_lp(const void* X, void* Y, const WindowGeom& g, int type, hipStream_t stream);
 hipError_t launch_avgpool_lp(const void* X, void* Y, const WindowGeom& g, int count_include_pad, int type, hipStream_t stream);
 hipError_t launch_global_avgpool_lp(const void* X, void* Y, int64_t planes, int HW, int type, hipStream_t stream);
+hipError_t launch_leakyrelu_lp(const void* X, void* Y, int64_t count, float alpha, int type, hipStream_t stream);
 
 }  // namespace onnxhip

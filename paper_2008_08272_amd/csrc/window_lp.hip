@@ -1,4 +1,4 @@
-// MaxPool / AveragePool / GlobalAveragePool on 16-bit tensors (IEEE half or bfloat16): what a
+// MaxPool / AveragePool / GlobalAveragePool and LeakyRelu on 16-bit tensors (IEEE half or bfloat16): what a
 // network whose contractions run on 16-bit inputs (gemm_lp.h, conv_window_lp.hip) needs between
 // them so that its activations never leave the 16-bit type.  Same ONNX semantics as the fp32
 // pools (Section 4.1 of the paper lists pooling among the supported operators): the maximum is
@@ -87,7 +87,48 @@ __global__ __launch_bounds__(256) void global_avgpool_lp_kernel(const uint16_t* 
     if (lane == 0) Y[plane] = to_lp<DT>(acc / (float)HW);
 }
 
+// LeakyRelu (Section 3.1 of the paper: its operator definition lists F16 among the element types; Relu is
+// alpha = 0): y = x for x >= 0, alpha * x otherwise, the product rounded to fp32 and then to the type.
+// VEC = 8: one 16-byte load and store per thread; VEC = 1: any alignment and the tail.
+template <int DT, int VEC>
+__global__ __launch_bounds__(256) void leakyrelu_lp_kernel(const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, int64_t count,
+                                                          float alpha) {
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * VEC;
+    if (i >= count) return;
+    auto one = [&](uint32_t bits) -> uint32_t {
+        const float x = from_lp<DT>(bits);
+        return x >= 0.f ? bits : to_lp<DT>(alpha * x);           // x >= 0 (and -0 only through the product) keeps its bits; NaN goes through the product
+    };
+    if constexpr (VEC == 8) {
+        const uintx4 v = *reinterpret_cast<const uintx4*>(X + i);
+        uintx4 o;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = one(v[k] & 0xffffu) | (one(v[k] >> 16) << 16);
+        *reinterpret_cast<uintx4*>(Y + i) = o;
+    } else {
+        Y[i] = (uint16_t)one(X[i]);
+    }
+}
+
 }  // namespace
+
+hipError_t launch_leakyrelu_lp(const void* X, void* Y, int64_t count, float alpha, int type, hipStream_t stream) {
+    const uint16_t* x = static_cast<const uint16_t*>(X);
+    uint16_t* y = static_cast<uint16_t*>(Y);
+    const bool wide = count % 8 == 0 && ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(Y)) & 15u) == 0;
+    const int64_t threads = wide ? count / 8 : count;
+    const int64_t blocks = (threads + 255) / 256;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks), block(256);
+    if (type == LP_BF16) {
+        if (wide) hipLaunchKernelGGL((leakyrelu_lp_kernel<LP_BF16, 8>), grid, block, 0, stream, x, y, count, alpha);
+        else hipLaunchKernelGGL((leakyrelu_lp_kernel<LP_BF16, 1>), grid, block, 0, stream, x, y, count, alpha);
+    } else {
+        if (wide) hipLaunchKernelGGL((leakyrelu_lp_kernel<LP_F16, 8>), grid, block, 0, stream, x, y, count, alpha);
+        else hipLaunchKernelGGL((leakyrelu_lp_kernel<LP_F16, 1>), grid, block, 0, stream, x, y, count, alpha);
+    }
+    return hipGetLastError();
+}
 
 // X, Y: 16-bit tensors of `type` (LP_F16 / LP_BF16).  The caller has checked that N*C*OH*OW < 2^31.
 hipError_t launch_maxpool_lp(const void* X, void* Y, const WindowGeom& g, int type, hipStream_t stream) {

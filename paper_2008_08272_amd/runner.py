@@ -10,7 +10,7 @@ instead.  All arithmetic happens inside the library's kernels; this module only 
 argument lists.
 
 With ``dtype=torch.float16`` or ``torch.bfloat16`` a graph of Conv / MaxPool / AveragePool / Reshape /
-Gemm / MatMul nodes runs on 16-bit tensors (the operator definitions admit them, Section 3.1):
+Gemm / MatMul / Relu / LeakyRelu nodes runs on 16-bit tensors (the operator definitions admit them, Section 3.1):
 inputs and weights are rounded to the type once, on upload, the biases stay fp32, every
 activation is stored in the type (fp32 accumulation inside each operator), and the node that
 produces the model's output stores fp32.
@@ -138,9 +138,9 @@ class GraphRunner:
         code = B.F16 if dt == torch.float16 else B.BF16
         fp32_names = set()                         # the additive operands, which the 16-bit operators take in fp32
         for nd in model["graph"]:
-            if nd["op"] not in ("conv", "maxpool", "avgpool", "reshape", "gemm", "matmul"):
-                raise NotImplementedError("node %r (%s): the 16-bit runner takes Conv, MaxPool, AveragePool, Reshape, Gemm "
-                                          "and MatMul nodes" % (nd["y"], nd["op"]))
+            if nd["op"] not in ("conv", "maxpool", "avgpool", "reshape", "gemm", "matmul", "relu", "leakyrelu"):
+                raise NotImplementedError("node %r (%s): the 16-bit runner takes Conv, MaxPool, AveragePool, Reshape, Gemm, "
+                                          "MatMul, Relu and LeakyRelu nodes" % (nd["y"], nd["op"]))
             if nd["op"] == "conv" and nd["b"]:
                 fp32_names.add(nd["b"])
             if nd["op"] == "gemm" and nd["c"]:
@@ -214,6 +214,11 @@ class GraphRunner:
                         float(nd["alpha"]), float(nd["beta"]), int(nd["transA"]), int(nd["transB"]),
                         B.ACT_RELU if nd["relu"] else B.ACT_NONE, B._ptr(y), B.dims(y.shape), code, ycode, None]
                 self.calls.append((lib.onnx_gemm_lp, args))
+            elif op in ("relu", "leakyrelu"):
+                x = self.t[nd["x"]]
+                y = self._new(nd["y"], x.shape, dt)
+                alpha = float(nd["alpha"]) if op == "leakyrelu" else 0.0
+                self.calls.append((lib.onnx_leakyrelu_lp, [B._ptr(x), x.numel(), alpha, B._ptr(y), code, None]))
             else:                                  # matmul
                 a, b = self.t[nd["a"]], self.t[nd["b"]]
                 yd = B.onnx_matmul_infer(a.shape, b.shape)

@@ -658,6 +658,58 @@ def test_pools_16bit_match_oracle(lib, case, kind):
     assert (np.abs(g - want) <= u * np.abs(want) + H * W * 2.0 ** -22).all()
 
 
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+def test_leakyrelu_16bit_bit_exact(lib, kind):
+    """LeakyRelu on 16-bit tensors (the paper's operator definition lists F16): x >= 0 keeps its bits, otherwise the
+    fp32 product alpha * x rounded to the type.  Both sides round the same way, so kept elements agree bit for bit and
+    products value for value (a zero product may carry either sign): 16-byte and element-wise forms, special values,
+    and through the runner's 16-bit mode behind a convolution."""
+    announce("leakyrelu_lp", kind)
+    rng = np.random.default_rng(17)
+    special = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1e-40, -1e-40, -6e-8, 6e-8, -65504.0, 65504.0, -1.0, 1.0], dtype=np.float32)
+    for count, off in ((8192, 0), (8200, 0), (1003, 0), (8192, 1), (13, 0), (0, 0)):
+        x = rng.standard_normal(count).astype(np.float32) * 3
+        x[:min(count, special.size)] = special[:min(count, special.size)]
+        xb, xv = encode(x, kind)
+        buf = torch.empty(count + 16, dtype=TORCH_T[kind], device="cuda")
+        X = buf[off:off + count]
+        if count:
+            X.copy_(bits_to_dev(xb, kind))
+        for alpha in (0.0, 0.01, 0.3, -1.5):
+            got = lib.onnx_leakyrelu_lp(X, alpha)
+            torch.cuda.synchronize()
+            assert got.dtype == TORCH_T[kind] and got.shape == (count,)
+            if count == 0:
+                continue
+            with np.errstate(all="ignore"):
+                want64 = np.where(xv.astype(np.float64) >= 0.0, xv.astype(np.float64), float(np.float32(alpha)) * xv.astype(np.float64))
+                _, wv = encode(want64.astype(np.float32), kind)
+            gb = got.view(torch.int16).cpu().numpy().view(np.uint16)
+            gv = lp_to_host(got, kind)
+            keep = xv >= 0                                  # kept elements carry the input's bits
+            nan = np.isnan(xv)
+            assert np.array_equal(gb[keep], xb[keep]), (count, off, alpha)
+            # the products: equal values (a zero product may carry either sign)
+            assert np.array_equal(gv[~keep & ~nan], wv[~keep & ~nan], equal_nan=True), (count, off, alpha)
+            assert np.isnan(gv[nan]).all()
+    # through the runner: Conv -> LeakyRelu -> Relu on 16-bit tensors
+    from paper_2008_08272_amd.runner import GraphRunner
+    conv = dict(op="conv", x="x", w="w", b="b", pads=(1, 1, 1, 1), strides=(1, 1), dilations=(1, 1), group=1, residual=None,
+                relu=False, y="c")
+    m = dict(inputs={"x": rng.standard_normal((2, 16, 9, 9)).astype(np.float32)},
+             weights={"w": (rng.standard_normal((24, 16, 3, 3)) * 0.1).astype(np.float32), "b": rng.standard_normal(24).astype(np.float32)},
+             graph=[conv, dict(op="leakyrelu", x="c", alpha=0.2, y="l"), dict(op="relu", x="l", y="r")], output="r")
+    r = GraphRunner(m, dtype=TORCH_T[kind])
+    r.run()
+    torch.cuda.synchronize()
+    c = r.t["c"].float().cpu().numpy().astype(np.float64)
+    want_l = encode(np.where(c >= 0, c, float(np.float32(0.2)) * c).astype(np.float32), kind)[1]
+    assert np.array_equal(r.t["l"].float().cpu().numpy(), want_l)
+    assert np.array_equal(r.t["r"].float().cpu().numpy(), np.maximum(want_l, 0))
+    with pytest.raises(NotImplementedError):
+        GraphRunner(dict(m, graph=[conv, dict(op="softmax", x="c", axis=1, y="r")]), dtype=TORCH_T[kind])
+
+
 def test_pools_16bit_errors(lib):
     announce("pool_lp errors")
     import ctypes
