@@ -44,6 +44,48 @@ __global__ __launch_bounds__(256) void maxpool_lp_kernel(const uint16_t* __restr
     Y[idx] = best_bits;
 }
 
+// MaxPool with 3 columns per window, horizontal stride 2 and left pad 1 (ResNet-50's pool behind the stem) on
+// rows of even length: a thread computes the outputs (ow, ow + 1) for even ow.  Their windows cover the input
+// columns 2*ow - 1 .. 2*ow + 3, which lie in three 4-byte aligned pairs starting at column 2*ow - 2: three loads
+// per input row for two outputs instead of six 2-byte ones.  Same scan order and first-maximum rule as above.
+template <int DT>
+__global__ __launch_bounds__(256) void maxpool_lp_pairs_kernel(const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, WindowGeom g,
+                                                              PoolIndex d, uint32_t total_pairs) {
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;            // (plane, oh, pair of output columns)
+    if (idx >= total_pairs) return;
+    uint32_t q, op, plane, oh;
+    d.OW.divmod(idx, q, op);                                         // d.OW divides by the pairs per output row
+    d.OH.divmod(q, plane, oh);
+    const int ow = 2 * (int)op;
+    const int ih0 = (int)oh * g.sH - g.pT;
+    const uint16_t* xc = X + (int64_t)plane * g.H * g.W;
+    bool found[2] = {false, false};
+    float best[2] = {0.f, 0.f};
+    uint16_t best_bits[2] = {0, 0};
+    auto offer = [&](int o, uint32_t bits) {
+        const float v = from_lp<DT>(bits);
+        if (!found[o] || v > best[o]) { best[o] = v; best_bits[o] = (uint16_t)bits; found[o] = true; }
+    };
+    for (int kh = 0; kh < g.kH; ++kh) {
+        const int ih = ih0 + kh * g.dH;
+        if (ih < 0 || ih >= g.H) continue;
+        const uint32_t* row = reinterpret_cast<const uint32_t*>(xc + ih * g.W);      // W even, X 4-byte aligned
+        const int c0 = 2 * ow - 2;                                                   // even; pairs at c0, c0 + 2, c0 + 4
+        const uint32_t p0 = c0 >= 0 ? row[c0 >> 1] : 0u;
+        const uint32_t p1 = row[(c0 + 2) >> 1];                                      // columns 2*ow, 2*ow + 1: always inside
+        const uint32_t p2 = c0 + 4 < g.W ? row[(c0 + 4) >> 1] : 0u;
+        // output ow: columns 2*ow - 1, 2*ow, 2*ow + 1; output ow + 1: columns 2*ow + 1, 2*ow + 2, 2*ow + 3
+        if (c0 >= 0) offer(0, p0 >> 16);
+        offer(0, p1 & 0xffffu);
+        offer(0, p1 >> 16);
+        offer(1, p1 >> 16);
+        if (c0 + 4 < g.W) { offer(1, p2 & 0xffffu); offer(1, p2 >> 16); }
+    }
+    const int64_t o = ((int64_t)plane * g.OH + oh) * g.OW + ow;
+    Y[o] = best_bits[0];
+    if (ow + 1 < g.OW) Y[o + 1] = best_bits[1];
+}
+
 template <int DT>
 __global__ __launch_bounds__(256) void avgpool_lp_kernel(const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, WindowGeom g,
                                                         int count_include_pad, PoolIndex d, uint32_t total) {
@@ -137,6 +179,17 @@ hipError_t launch_maxpool_lp(const void* X, void* Y, const WindowGeom& g, int ty
     const dim3 grid((total + 255u) / 256u), block(256);
     const uint16_t* x = static_cast<const uint16_t*>(X);
     uint16_t* y = static_cast<uint16_t*>(Y);
+    // pairs of outputs from 4-byte loads: the window of output ow + 1 must end inside the pair at column 2*ow + 2, and the
+    // last output's middle pair inside the row
+    if (g.kW == 3 && g.sW == 2 && g.dW == 1 && g.pL == 1 && g.W % 2 == 0 && 2 * g.OW <= g.W && (reinterpret_cast<uintptr_t>(X) & 3u) == 0) {
+        const int pairs_per_row = (g.OW + 1) / 2;
+        const uint32_t total_pairs = (uint32_t)((int64_t)g.N * g.C * g.OH * pairs_per_row);
+        const PoolIndex dp = {FastDiv::make((uint32_t)pairs_per_row), FastDiv::make((uint32_t)g.OH)};
+        const dim3 pgrid((total_pairs + 255u) / 256u);
+        if (type == LP_BF16) hipLaunchKernelGGL(maxpool_lp_pairs_kernel<LP_BF16>, pgrid, block, 0, stream, x, y, g, dp, total_pairs);
+        else hipLaunchKernelGGL(maxpool_lp_pairs_kernel<LP_F16>, pgrid, block, 0, stream, x, y, g, dp, total_pairs);
+        return hipGetLastError();
+    }
     if (type == LP_BF16) hipLaunchKernelGGL(maxpool_lp_kernel<LP_BF16>, grid, block, 0, stream, x, y, g, d, total);
     else hipLaunchKernelGGL(maxpool_lp_kernel<LP_F16>, grid, block, 0, stream, x, y, g, d, total);
     return hipGetLastError();

@@ -621,7 +621,10 @@ POOL_LP_CASES = [
     (2, 2, 11, 11, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 1),
     (1, 3, 12, 9, (3, 2), (0, 0, 0, 0), (3, 2), (2, 2), 0),
     (2, 5, 13, 10, (3, 2), (2, 0, 1, 1), (1, 2), (1, 1), 0),
-    (3, 64, 56, 56, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),
+    (3, 64, 56, 56, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),      # 3 columns, stride 2, left pad 1, even rows: two outputs per thread
+    (1, 2, 9, 10, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),        # the same with an odd number of output columns
+    (1, 2, 12, 10, (2, 3), (0, 1, 0, 1), (1, 2), (1, 1), 0),       # two rows per window, vertical stride 1
+    (2, 2, 9, 12, (3, 3), (1, 1, 0, 0), (2, 2), (1, 1), 1),        # ceil_mode: a last window past the row, one output per thread
     (4, 1, 1, 1, (1, 1), (0, 0, 0, 0), (1, 1), (1, 1), 0),
     (0, 3, 8, 8, (2, 2), (0, 0, 0, 0), (2, 2), (1, 1), 0),
 ]
@@ -644,6 +647,10 @@ def test_pools_16bit_match_oracle(lib, case, kind):
         return
     ref = oracle.maxpool(xv, k, pads, st, dl, ceil, want_indices=False)
     assert np.array_equal(lp_to_host(got, kind), ref)
+    # the same tensor two bytes off a 4-byte boundary (no 4-byte loads then)
+    buf = torch.empty(X.numel() + 8, dtype=X.dtype, device="cuda")
+    buf[1:1 + X.numel()].copy_(X.reshape(-1))
+    assert np.array_equal(lp_to_host(lib.onnx_maxpool_lp(buf[1:1 + X.numel()].view(X.shape), k, pads, st, dl, ceil), kind), ref)
     u = 2.0 ** -PRECISION[kind]
     if dl == (1, 1):
         for cip in (0, 1):
