@@ -251,6 +251,47 @@ def test_fixed_scratch_conv_validates_like_conv_and_enforces_its_maximum(B):
     assert "#define ONNX_CONV_FIXED_SCRATCH_MAX_OUTPUTS (1 << 21)" in text and B.CONV_FIXED_SCRATCH_MAX_OUTPUTS == 1 << 21
 
 
+def test_16bit_entry_points_validate_before_touching_the_device(B):
+    """The 16-bit pools, LeakyRelu and the filter rewriting check types, shapes and pointers on the host: every
+    refusal below returns without device work."""
+    lib = B.raw()
+    d = B.dims
+    fake, fake2 = ctypes.c_void_p(4096), ctypes.c_void_p(1 << 20)
+    # element type must be one of the two 16-bit types
+    assert lib.onnx_leakyrelu_lp(fake, 16, 0.1, fake2, 0, None) == 4
+    assert lib.onnx_maxpool_lp(fake, d((1, 1, 4, 4)), d((2, 2)), d((0, 0, 0, 0)), d((1, 1)), d((1, 1)), 0, fake2, d((1, 1, 3, 3)), 0, None) == 4
+    assert lib.onnx_avgpool_lp(fake, d((1, 1, 4, 4)), d((2, 2)), d((0, 0, 0, 0)), d((1, 1)), 0, 0, fake2, d((1, 1, 3, 3)), 7, None) == 4
+    # LeakyRelu: counts and pointers
+    assert lib.onnx_leakyrelu_lp(fake, -1, 0.1, fake2, B.BF16, None) == 3
+    assert lib.onnx_leakyrelu_lp(None, 0, 0.1, None, B.BF16, None) == 0
+    assert lib.onnx_leakyrelu_lp(None, 8, 0.1, fake2, B.F16, None) == 1
+    assert lib.onnx_leakyrelu_lp(fake, 8, 0.1, ctypes.c_void_p(4100), B.F16, None) == 6       # Y inside X
+    # pools: inferred shape, window against the padded image, pads against the window
+    assert lib.onnx_maxpool_lp(fake, d((1, 1, 4, 4)), d((2, 2)), d((0, 0, 0, 0)), d((1, 1)), d((1, 1)), 0, fake2, d((1, 1, 2, 2)), B.BF16, None) == 3
+    assert lib.onnx_maxpool_lp(fake, d((1, 1, 4, 4)), d((2, 2)), d((2, 2, 2, 2)), d((1, 1)), d((1, 1)), 0, fake2, d((1, 1, 7, 7)), B.F16, None) == 4
+    assert lib.onnx_avgpool_lp(fake, d((1, 1, 4, 4)), d((5, 5)), d((0, 0, 0, 0)), d((1, 1)), 0, 0, fake2, d((1, 1, 1, 1)), B.F16, None) != 0
+    assert lib.onnx_avgpool_lp(fake, d((2, 3, 4, 4)), None, None, None, 0, 0, fake2, d((2, 3, 2, 2)), B.BF16, None) == 3   # global: {N,C,1,1}
+    assert lib.onnx_maxpool_lp(None, d((0, 3, 4, 4)), d((2, 2)), d((0, 0, 0, 0)), d((1, 1)), d((1, 1)), 0, None, d((0, 3, 3, 3)), B.BF16, None) == 0
+    # filter rewriting: 3x3 windows, channels per group a multiple of 16, aligned destination
+    assert lib.onnx_conv_lp_filter_taps(fake, d((8, 16, 5, 5)), fake2, None) == 5
+    assert lib.onnx_conv_lp_filter_taps(fake, d((8, 24, 3, 3)), fake2, None) == 5
+    assert lib.onnx_conv_lp_filter_taps(fake, d((8, 16, 3, 3)), ctypes.c_void_p((1 << 20) + 2), None) == 4
+    assert lib.onnx_conv_lp_filter_taps(fake, d((8, 16, 3, 3)), None, None) == 1
+    assert lib.onnx_conv_lp_filter_taps(None, d((0, 16, 3, 3)), None, None) == 0
+    assert lib.onnx_conv_lp_filter_taps(fake, d((8, 16, 3, 3)), ctypes.c_void_p(4096 + 16), None) == 6            # packed inside W
+    # the convolution on rewritten filters: types, alignment, shapes like onnx_conv_lp
+    args = [fake, d((1, 16, 8, 8)), fake2, d((8, 16, 3, 3)), None, d((1, 1, 1, 1)), d((1, 1)), d((1, 1)), 1, None, 0,
+            ctypes.c_void_p(1 << 22), d((1, 8, 8, 8)), 0, 0, None]
+    assert lib.onnx_conv_lp_taps(*args) == 4                                                        # in_type fp32
+    args[13] = B.BF16; args[14] = B.F16
+    assert lib.onnx_conv_lp_taps(*args) == 4                                                        # out_type neither fp32 nor in_type
+    args[14] = B.BF16; args[2] = ctypes.c_void_p((1 << 20) + 8)
+    assert lib.onnx_conv_lp_taps(*args) == 4                                                        # bank not 16-byte aligned
+    args[2] = fake2; args[12] = d((1, 8, 8, 7))
+    assert lib.onnx_conv_lp_taps(*args) == 3
+    assert "conv" in B.onnx_last_error()
+
+
 def test_workspace_setting_checks_its_arguments(B):
     lib = B.raw()
     assert lib.onnx_set_workspace(ctypes.c_void_p(1 << 20), 1 << 19) == 4         # below 1 MiB
