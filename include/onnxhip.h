@@ -330,6 +330,17 @@ onnx_status onnx_avgpool_lp(const void* X, const int64_t x_dims[4], const int64_
 onnx_status onnx_leakyrelu_lp(const void* X, int64_t count, float alpha, void* Y, onnx_dtype type, void* stream);
 
 /*
+ * ONNX Add and Abs on 16-bit tensors (Section 3: Add is the running example; Section 3.4: Abs is
+ * one of the two operators ReduceL1 decomposes into; `type` ONNX_F16 or ONNX_BF16 for every
+ * operand).  Add: shapes, broadcasting, y_dims and errors as for onnx_add; every sum is taken in
+ * fp32 and rounded to the type (nearest even), which for two 16-bit addends is the correctly
+ * rounded sum.  Abs clears the sign bit (of a NaN too).  Y must not overlap an input.
+ */
+onnx_status onnx_add_lp(const void* A, const int64_t* a_dims, int a_rank, const void* B, const int64_t* b_dims,
+                        int b_rank, void* Y, const int64_t* y_dims, int y_rank, onnx_dtype type, void* stream);
+onnx_status onnx_abs_lp(const void* X, int64_t count, void* Y, onnx_dtype type, void* stream);
+
+/*
  * ONNX LSTM (named among the supported operators, Section 4.1), layout 0, default activations
  * (sigmoid, tanh, tanh), no peepholes, every sequence of full length.  X [seq, batch, input];
  * W [dirs, 4H, input] and R [dirs, 4H, H] with the gate blocks in the order i, o, f, c;

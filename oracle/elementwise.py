@@ -20,6 +20,29 @@ def add(a, b):
     return _f64(a) + _f64(b)
 
 
+def round_to_16bit(v, kind):
+    """The values of the 16-bit type ("f16": IEEE half, 11 significant bits, exponents -14..15;
+    "bf16": bfloat16, 8 significant bits, exponents -126..127) nearest to the doubles `v`, ties to
+    the even significand, overflow to infinity: one rounding, straight from the double.  Returned
+    as doubles (each exactly representable in the type)."""
+    v = np.asarray(v, dtype=np.float64)
+    bits, emin, emax = (11, -14, 15) if kind == "f16" else (8, -126, 127)
+    with np.errstate(all="ignore"):
+        m, e = np.frexp(v)                                   # v = m 2^e, 0.5 <= |m| < 1
+        e = np.maximum(e, emin + 1)                          # below the normal range the spacing stays 2^(emin - bits + 1)
+        q = np.rint(np.ldexp(v, bits - e))                   # rint rounds halves to even; |q| <= 2^bits
+        r = np.ldexp(q, e - bits)
+        big = np.ldexp(2.0 - 2.0 ** (1 - bits), emax)        # largest finite value of the type
+        r = np.where(np.abs(r) > big, np.sign(v) * np.inf, r)
+    return np.where(np.isfinite(v), r, v)
+
+
+def add_16bit(a, b, kind):
+    """ONNX Add on tensors of a 16-bit type: the exact sum (two 16-bit addends: exact in double)
+    rounded once to the type."""
+    return round_to_16bit(np.asarray(a, dtype=np.float64) + np.asarray(b, dtype=np.float64), kind)
+
+
 def relu(x):
     """ONNX Relu: y = max(0, x)."""
     x = _f64(x)

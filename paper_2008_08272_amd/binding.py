@@ -54,6 +54,10 @@ _lib.onnx_maxpool_lp.argtypes = [_vp, _i64p, _i64p, _i64p, _i64p, _i64p, _ci, _v
 _lib.onnx_avgpool_lp.argtypes = [_vp, _i64p, _i64p, _i64p, _i64p, _ci, _ci, _vp, _i64p, _ci, _vp]
 _lib.onnx_leakyrelu_lp.argtypes = [_vp, _c64, _cf, _vp, _ci, _vp]
 _lib.onnx_leakyrelu_lp.restype = _ci
+_lib.onnx_add_lp.argtypes = [_vp, _i64p, _ci, _vp, _i64p, _ci, _vp, _i64p, _ci, _ci, _vp]
+_lib.onnx_add_lp.restype = _ci
+_lib.onnx_abs_lp.argtypes = [_vp, _c64, _vp, _ci, _vp]
+_lib.onnx_abs_lp.restype = _ci
 for _f in (_lib.onnx_conv_infer, _lib.onnx_pool_infer, _lib.onnx_matmul_infer, _lib.onnx_conv,
            _lib.onnx_gemm, _lib.onnx_matmul, _lib.onnx_maxpool, _lib.onnx_avgpool, _lib.onnx_maxpool_lp,
            _lib.onnx_avgpool_lp):
@@ -423,6 +427,25 @@ def onnx_leakyrelu_lp(X, alpha=0.01, out=None, stream=None):
     X = _lp(X, "X")
     Y, _ = _lp_out(out, X.shape, X.dtype, X)
     _check(_lib.onnx_leakyrelu_lp(_ptr(X), X.numel(), float(alpha), _ptr(Y), _LP_TYPES[X.dtype], _stream(stream)))
+    return Y
+
+
+def onnx_add_lp(A, B, out=None, stream=None):
+    """Add with numpy-style broadcasting on two float16 / bfloat16 CUDA tensors of one type; the result has that type."""
+    A, B = _lp(A, "A"), _lp(B, "B")
+    if A.dtype != B.dtype:
+        raise TypeError("A and B must have the same 16-bit type")
+    Y, _ = _lp_out(out, onnx_broadcast_infer(A.shape, B.shape), A.dtype, A)
+    _check(_lib.onnx_add_lp(_ptr(A), dims(A.shape), A.dim(), _ptr(B), dims(B.shape), B.dim(), _ptr(Y), dims(Y.shape),
+                            Y.dim(), _LP_TYPES[A.dtype], _stream(stream)))
+    return Y
+
+
+def onnx_abs_lp(X, out=None, stream=None):
+    """Abs on a float16 / bfloat16 CUDA tensor; the result has the same type."""
+    X = _lp(X, "X")
+    Y, _ = _lp_out(out, X.shape, X.dtype, X)
+    _check(_lib.onnx_abs_lp(_ptr(X), X.numel(), _ptr(Y), _LP_TYPES[X.dtype], _stream(stream)))
     return Y
 
 

@@ -340,13 +340,13 @@ hipError_t launch_instance(ContractionParams& p, int nz, const SplitSpace& space
     p.tail_split = 1;
     const unsigned gz = nz < 32768 ? (unsigned)nz : 32768u;
     const unsigned gy = ((unsigned)nz + gz - 1) / gz;
-    if (tiles > 0x7fffffffLL || gy * (unsigned)p.ksplit > 65535u) return hipErrorInvalidValue;
+    if (tiles * (WM * WN) > 0x7fffffffLL || gy * (unsigned)p.ksplit > 65535u) return hipErrorInvalidValue;
     hipLaunchKernelGGL((conv_window_lp_kernel<BM, BN, WM, WN, DT, LP_OUT, PAIR, NPU>), dim3((unsigned)tiles, gy * (unsigned)p.ksplit, gz),
                        dim3(64 * WM * WN), 0, stream, p);
     hipError_t e = hipGetLastError();
     if constexpr (kMaySplit) {
         if (e == hipSuccess && p.ksplit > 1) {
-            hipLaunchKernelGGL((lp_finish_kernel<BM, BN, WM, WN, DT, LP_OUT>), dim3((unsigned)tiles, gy, gz), dim3(64 * WM * WN), 0,
+            hipLaunchKernelGGL((lp_finish_kernel<BM, BN, WM, WN, DT, LP_OUT>), dim3((unsigned)tiles * (WM * WN), gy, gz), dim3(64), 0,
                                stream, p);
             e = hipGetLastError();
         }

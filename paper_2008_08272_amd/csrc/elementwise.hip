@@ -7,6 +7,7 @@
 #include <stdio.h>
 
 #include "../../include/onnxhip.h"
+#include "gemm_lp.h"
 #include "internal.h"
 
 using namespace onnxhip;
@@ -79,6 +80,21 @@ onnx_status run_unary(const char* name, const float* X, int64_t count, float alp
     return device_status(hipGetLastError(), name);
 }
 
+// Abs on 16-bit elements of either type: the sign bit cleared, 8 elements per 16-byte access (VEC = 8) or one.
+template <int VEC>
+__global__ __launch_bounds__(256) void abs_lp_kernel(const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, int64_t count) {
+    for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * VEC; i < count; i += (int64_t)gridDim.x * 256 * VEC) {
+        if constexpr (VEC == 8) {
+            uintx4 v = *reinterpret_cast<const uintx4*>(X + i);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[k] &= 0x7fff7fffu;
+            *reinterpret_cast<uintx4*>(Y + i) = v;
+        } else {
+            Y[i] = X[i] & 0x7fffu;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------- broadcasting Add
 
 // Output index space after merging: up to EW_MAX_DIMS extents, row-major, with the element
@@ -115,6 +131,40 @@ __global__ __launch_bounds__(256) void add_kernel(const float* __restrict__ A, c
             *reinterpret_cast<floatx4*>(Y + (int64_t)gidx * 4) = y;
         } else {
             Y[gidx] = A[oa] + B[ob];
+        }
+    }
+}
+
+// The same on 16-bit tensors (DT: LP_F16 / LP_BF16): groups of 8 innermost outputs through 16-byte
+// accesses (VEC = 8) or single elements; the sum is taken in fp32 and rounded to the type.
+template <int DT, int VEC>
+__global__ __launch_bounds__(256) void add_lp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
+                                                     uint16_t* __restrict__ Y, uint32_t groups, BroadcastMap m) {
+    for (uint32_t gidx = blockIdx.x * 256u + threadIdx.x; gidx < groups; gidx += gridDim.x * 256u) {
+        uint32_t rest = gidx, i;
+        int64_t oa = 0, ob = 0;
+        for (int d = m.nd - 1; d >= 0; --d) {
+            m.dim[d].divmod(rest, rest, i);
+            const int64_t step = (d == m.nd - 1) ? (int64_t)i * VEC : (int64_t)i;
+            oa += step * m.sa[d];
+            ob += step * m.sb[d];
+        }
+        if constexpr (VEC == 8) {
+            const bool ca = m.sa[m.nd - 1] != 0, cb = m.sb[m.nd - 1] != 0;
+            uintx4 a, b, y;
+            if (ca) a = *reinterpret_cast<const uintx4*>(A + oa);
+            else { const uint32_t v = A[oa]; a[0] = a[1] = a[2] = a[3] = v | (v << 16); }
+            if (cb) b = *reinterpret_cast<const uintx4*>(B + ob);
+            else { const uint32_t v = B[ob]; b[0] = b[1] = b[2] = b[3] = v | (v << 16); }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t lo = to_lp<DT>(from_lp<DT>(a[k] & 0xffffu) + from_lp<DT>(b[k] & 0xffffu));
+                const uint32_t hi = to_lp<DT>(from_lp<DT>(a[k] >> 16) + from_lp<DT>(b[k] >> 16));
+                y[k] = lo | (hi << 16);
+            }
+            *reinterpret_cast<uintx4*>(Y + (int64_t)gidx * 8) = y;
+        } else {
+            Y[gidx] = to_lp<DT>(from_lp<DT>(A[oa]) + from_lp<DT>(B[ob]));
         }
     }
 }
@@ -324,6 +374,22 @@ onnx_status onnx_abs(const float* X, int64_t count, float* Y, void* stream) {
     return run_unary<UN_ABS>("abs", X, count, 0.f, Y, stream);
 }
 
+onnx_status onnx_abs_lp(const void* X, int64_t count, void* Y, onnx_dtype type, void* stream) {
+    if (type != ONNX_F16 && type != ONNX_BF16) return fail(ONNX_ERR_ATTR, "abs_lp: type must be ONNX_F16 or ONNX_BF16");
+    if (count < 0) return fail(ONNX_ERR_SHAPE, "abs_lp: negative element count");
+    if (count == 0) return ONNX_OK;
+    if (!X || !Y) return fail(ONNX_ERR_NULL, "abs_lp: X and Y must not be NULL");
+    if (overlaps(Y, count * 2, X, count * 2)) return fail(ONNX_ERR_ALIAS, "abs_lp: Y overlaps X");
+    const uint16_t* x = static_cast<const uint16_t*>(X);
+    uint16_t* y = static_cast<uint16_t*>(Y);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (count % 8 == 0 && aligned16(X) && aligned16(Y))
+        hipLaunchKernelGGL((abs_lp_kernel<8>), dim3(blocks_for(count / 8)), dim3(256), 0, s, x, y, count);
+    else
+        hipLaunchKernelGGL((abs_lp_kernel<1>), dim3(blocks_for(count)), dim3(256), 0, s, x, y, count);
+    return device_status(hipGetLastError(), "abs_lp");
+}
+
 onnx_status onnx_broadcast_infer(const int64_t* a_dims, int a_rank, const int64_t* b_dims, int b_rank,
                                  int64_t* y_dims, int* y_rank) {
     if (a_rank < 0 || a_rank > ONNX_MAX_RANK || b_rank < 0 || b_rank > ONNX_MAX_RANK)
@@ -336,8 +402,10 @@ onnx_status onnx_broadcast_infer(const int64_t* a_dims, int a_rank, const int64_
     return ONNX_OK;
 }
 
-onnx_status onnx_add(const float* A, const int64_t* a_dims, int a_rank, const float* B, const int64_t* b_dims,
-                     int b_rank, float* Y, const int64_t* y_dims, int y_rank, void* stream) {
+// Add on fp32 (type 0) or 16-bit (LP_F16 / LP_BF16) tensors: checks, the merged index space, the launch.
+static onnx_status add_any(const void* A, const int64_t* a_dims, int a_rank, const void* B, const int64_t* b_dims, int b_rank,
+                           void* Y, const int64_t* y_dims, int y_rank, int type, void* stream) {
+    const int64_t esz = type == 0 ? 4 : 2, vecw = 16 / esz;
     int64_t yd[ONNX_MAX_RANK];
     int r = 0;
     const onnx_status st = onnx_broadcast_infer(a_dims, a_rank, b_dims, b_rank, yd, &r);
@@ -354,7 +422,7 @@ onnx_status onnx_add(const float* A, const int64_t* a_dims, int a_rank, const fl
     for (int d = 0; d < b_rank; ++d) nb *= b_dims[d];
     if (ny == 0) return ONNX_OK;
     if (!A || !B || !Y) return fail(ONNX_ERR_NULL, "add: A, B and Y must not be NULL");
-    if (overlaps(Y, ny * 4, A, na * 4) || overlaps(Y, ny * 4, B, nb * 4)) return fail(ONNX_ERR_ALIAS, "add: Y overlaps an input");
+    if (overlaps(Y, ny * esz, A, na * esz) || overlaps(Y, ny * esz, B, nb * esz)) return fail(ONNX_ERR_ALIAS, "add: Y overlaps an input");
     // per-dimension strides (0 = broadcast), unit extents dropped, neighbours merged when both
     // operands walk them like one longer extent
     int64_t dim[ONNX_MAX_RANK], sa[ONNX_MAX_RANK], sb[ONNX_MAX_RANK];
@@ -380,21 +448,48 @@ onnx_status onnx_add(const float* A, const int64_t* a_dims, int a_rank, const fl
         }
         if (nd == 0) { dim[0] = 1; sa[0] = 0; sb[0] = 0; nd = 1; }
     }
-    const bool vec = dim[nd - 1] % 4 == 0 && aligned16(A) && aligned16(B) && aligned16(Y);
+    // wide accesses: an operand walked with stride 1 needs 16-byte aligned groups (its other strides then are multiples
+    // of the group too, the innermost extent being one); a broadcast one is read element by element
+    const bool vec = dim[nd - 1] % vecw == 0 && (sa[nd - 1] == 0 || aligned16(A)) && (sb[nd - 1] == 0 || aligned16(B)) && aligned16(Y);
     BroadcastMap m;
     m.nd = nd;
     for (int d = 0; d < nd; ++d) {
-        m.dim[d] = FastDiv::make((uint32_t)((d == nd - 1 && vec) ? dim[d] / 4 : dim[d]));
+        m.dim[d] = FastDiv::make((uint32_t)((d == nd - 1 && vec) ? dim[d] / vecw : dim[d]));
         m.sa[d] = sa[d]; m.sb[d] = sb[d];
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (vec) {
-        const uint32_t groups = (uint32_t)(ny / 4);
-        hipLaunchKernelGGL((add_kernel<4>), dim3(blocks_for(groups)), dim3(256), 0, s, A, B, Y, groups, m);
+    const uint32_t groups = (uint32_t)(vec ? ny / vecw : ny);
+    const dim3 grid(blocks_for(groups)), block(256);
+    if (type == 0) {
+        const float* a = static_cast<const float*>(A);
+        const float* b = static_cast<const float*>(B);
+        float* y = static_cast<float*>(Y);
+        if (vec) hipLaunchKernelGGL((add_kernel<4>), grid, block, 0, s, a, b, y, groups, m);
+        else hipLaunchKernelGGL((add_kernel<1>), grid, block, 0, s, a, b, y, groups, m);
     } else {
-        hipLaunchKernelGGL((add_kernel<1>), dim3(blocks_for(ny)), dim3(256), 0, s, A, B, Y, (uint32_t)ny, m);
+        const uint16_t* a = static_cast<const uint16_t*>(A);
+        const uint16_t* b = static_cast<const uint16_t*>(B);
+        uint16_t* y = static_cast<uint16_t*>(Y);
+        if (type == LP_BF16) {
+            if (vec) hipLaunchKernelGGL((add_lp_kernel<LP_BF16, 8>), grid, block, 0, s, a, b, y, groups, m);
+            else hipLaunchKernelGGL((add_lp_kernel<LP_BF16, 1>), grid, block, 0, s, a, b, y, groups, m);
+        } else {
+            if (vec) hipLaunchKernelGGL((add_lp_kernel<LP_F16, 8>), grid, block, 0, s, a, b, y, groups, m);
+            else hipLaunchKernelGGL((add_lp_kernel<LP_F16, 1>), grid, block, 0, s, a, b, y, groups, m);
+        }
     }
     return device_status(hipGetLastError(), "add");
+}
+
+onnx_status onnx_add(const float* A, const int64_t* a_dims, int a_rank, const float* B, const int64_t* b_dims,
+                     int b_rank, float* Y, const int64_t* y_dims, int y_rank, void* stream) {
+    return add_any(A, a_dims, a_rank, B, b_dims, b_rank, Y, y_dims, y_rank, 0, stream);
+}
+
+onnx_status onnx_add_lp(const void* A, const int64_t* a_dims, int a_rank, const void* B, const int64_t* b_dims, int b_rank,
+                        void* Y, const int64_t* y_dims, int y_rank, onnx_dtype type, void* stream) {
+    if (type != ONNX_F16 && type != ONNX_BF16) return fail(ONNX_ERR_ATTR, "add_lp: type must be ONNX_F16 or ONNX_BF16");
+    return add_any(A, a_dims, a_rank, B, b_dims, b_rank, Y, y_dims, y_rank, type == ONNX_F16 ? LP_F16 : LP_BF16, stream);
 }
 
 onnx_status onnx_reduce_infer(const int64_t* x_dims, int rank, const int64_t* axes, int naxes, int keepdims,

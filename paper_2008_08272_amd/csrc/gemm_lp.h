@@ -489,10 +489,13 @@ __device__ __forceinline__ void park_partial_tile(const floatx16 (&acc)[TM][TN],
 }
 
 // Second half of a product whose K range was split over several workgroups per tile (park_partial_tile
-// below): the thread-to-accumulator mapping of the kernel that parked the shares; the shares of a tile are added in split order (four requested at a time, a share
-// past the last one being an out-of-range offset that returns 0), then the same epilogues.
+// above).  One wavefront per workgroup, WM * WN workgroups per tile (these launches have few tiles: as one
+// workgroup per tile they took half as long again), each with the thread-to-accumulator mapping of the
+// wavefront that parked its part of the shares; the shares of a tile are added in split order (four
+// requested at a time, a share past the last one being an out-of-range offset that returns 0), then the
+// same epilogues.  Grid: (tiles * WM * WN, z-slices).
 template <int BM, int BN, int WM, int WN, int DT, bool LP_OUT>
-__global__ __launch_bounds__(64 * WM * WN) void lp_finish_kernel(const ContractionParams cp) {
+__global__ __launch_bounds__(64) void lp_finish_kernel(const ContractionParams cp) {
     constexpr int NT = 64 * WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -502,13 +505,15 @@ __global__ __launch_bounds__(64 * WM * WN) void lp_finish_kernel(const Contracti
     w.zslice = blockIdx.y * gridDim.z + blockIdx.z;
     if (w.zslice >= cp.nz) return;
     const int ntiles = cp.tiles_m * cp.tiles_n;
+    const int tile = blockIdx.x / (WM * WN), wave = blockIdx.x % (WM * WN);
     w.ksplit = 1; w.split = 0; w.slot = 0;
-    tile_origin(cp, xcd_contiguous(blockIdx.x, ntiles), BM, BN, w.m0, w.n0);
+    tile_origin(cp, xcd_contiguous(tile, ntiles), BM, BN, w.m0, w.n0);
     w.m0 = scalar(w.m0); w.n0 = scalar(w.n0); w.zslice = scalar(w.zslice);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x;
+    const int tid = wave * 64 + lane;                // this thread's index in the workgroup that parked the shares
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, h = lane >> 5;
-    const int64_t first_slot = ((int64_t)w.zslice * ntiles + blockIdx.x) * cp.ksplit;
+    const int64_t first_slot = ((int64_t)w.zslice * ntiles + tile) * cp.ksplit;
     const __amdgpu_buffer_rsrc_t rp = tile_rsrc(cp.ws_partial + first_slot * TILE);
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -525,7 +530,7 @@ __global__ __launch_bounds__(64 * WM * WN) void lp_finish_kernel(const Contracti
                 float v[AHEAD][16];
 #pragma unroll
                 for (int u = 0; u < AHEAD; ++u) {
-                    const uint32_t share = s0 + u < cp.ksplit ? (uint32_t)threadIdx.x * 4u : OOB;
+                    const uint32_t share = s0 + u < cp.ksplit ? (uint32_t)tid * 4u : OOB;
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
                         v[u][r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(

@@ -27,7 +27,7 @@ hipError_t launch_instance(ContractionParams& p, int nz, const Workspace& ws, hi
     p.ws_partial = ws.partial;
     const unsigned gz = nz < 32768 ? (unsigned)nz : 32768u;
     const unsigned gy = ((unsigned)nz + gz - 1) / gz;
-    if (tiles > 0x7fffffffLL || gy * (unsigned)p.ksplit > 65535u) return hipErrorInvalidValue;
+    if (tiles * (WM * WN) > 0x7fffffffLL || gy * (unsigned)p.ksplit > 65535u) return hipErrorInvalidValue;
     p.tail_begin = (int)tiles;
     p.tail_split = 1;
     hipLaunchKernelGGL((gemm_lp_kernel<BM, BN, BK, WM, WN, DT, LP_OUT, PF, BKIND, BVEC>), dim3((unsigned)tiles, gy * (unsigned)p.ksplit, gz),
@@ -35,7 +35,7 @@ hipError_t launch_instance(ContractionParams& p, int nz, const Workspace& ws, hi
     hipError_t e = hipGetLastError();
     if constexpr (kMaySplit) {
         if (e == hipSuccess && p.ksplit > 1) {
-            hipLaunchKernelGGL((lp_finish_kernel<BM, BN, WM, WN, DT, LP_OUT>), dim3((unsigned)tiles, gy, gz), dim3(64 * WM * WN), 0, stream, p);
+            hipLaunchKernelGGL((lp_finish_kernel<BM, BN, WM, WN, DT, LP_OUT>), dim3((unsigned)tiles * (WM * WN), gy, gz), dim3(64), 0, stream, p);
             e = hipGetLastError();
         }
     }

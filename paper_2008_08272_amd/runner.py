@@ -138,9 +138,9 @@ class GraphRunner:
         code = B.F16 if dt == torch.float16 else B.BF16
         fp32_names = set()                         # the additive operands, which the 16-bit operators take in fp32
         for nd in model["graph"]:
-            if nd["op"] not in ("conv", "maxpool", "avgpool", "reshape", "gemm", "matmul", "relu", "leakyrelu"):
+            if nd["op"] not in ("conv", "maxpool", "avgpool", "reshape", "gemm", "matmul", "relu", "leakyrelu", "add", "abs"):
                 raise NotImplementedError("node %r (%s): the 16-bit runner takes Conv, MaxPool, AveragePool, Reshape, Gemm, "
-                                          "MatMul, Relu and LeakyRelu nodes" % (nd["y"], nd["op"]))
+                                          "MatMul, Relu, LeakyRelu, Add and Abs nodes" % (nd["y"], nd["op"]))
             if nd["op"] == "conv" and nd["b"]:
                 fp32_names.add(nd["b"])
             if nd["op"] == "gemm" and nd["c"]:
@@ -219,6 +219,16 @@ class GraphRunner:
                 y = self._new(nd["y"], x.shape, dt)
                 alpha = float(nd["alpha"]) if op == "leakyrelu" else 0.0
                 self.calls.append((lib.onnx_leakyrelu_lp, [B._ptr(x), x.numel(), alpha, B._ptr(y), code, None]))
+            elif op == "add":
+                a, b = self.t[nd["a"]], self.t[nd["b"]]
+                y = self._new(nd["y"], B.onnx_broadcast_infer(a.shape, b.shape), dt)
+                args = [B._ptr(a), B.dims(a.shape), a.dim(), B._ptr(b), B.dims(b.shape), b.dim(), B._ptr(y),
+                        B.dims(y.shape), y.dim(), code, None]
+                self.calls.append((lib.onnx_add_lp, args))
+            elif op == "abs":
+                x = self.t[nd["x"]]
+                y = self._new(nd["y"], x.shape, dt)
+                self.calls.append((lib.onnx_abs_lp, [B._ptr(x), x.numel(), B._ptr(y), code, None]))
             else:                                  # matmul
                 a, b = self.t[nd["a"]], self.t[nd["b"]]
                 yd = B.onnx_matmul_infer(a.shape, b.shape)

@@ -252,7 +252,7 @@ def test_fixed_scratch_conv_validates_like_conv_and_enforces_its_maximum(B):
 
 
 def test_16bit_entry_points_validate_before_touching_the_device(B):
-    """The 16-bit pools, LeakyRelu and the filter rewriting check types, shapes and pointers on the host: every
+    """The 16-bit pools, LeakyRelu, Add, Abs and the filter rewriting check types, shapes and pointers on the host: every
     refusal below returns without device work."""
     lib = B.raw()
     d = B.dims
@@ -266,6 +266,19 @@ def test_16bit_entry_points_validate_before_touching_the_device(B):
     assert lib.onnx_leakyrelu_lp(None, 0, 0.1, None, B.BF16, None) == 0
     assert lib.onnx_leakyrelu_lp(None, 8, 0.1, fake2, B.F16, None) == 1
     assert lib.onnx_leakyrelu_lp(fake, 8, 0.1, ctypes.c_void_p(4100), B.F16, None) == 6       # Y inside X
+    # Add and Abs: type, broadcast, result shape, pointers, overlap
+    add = lambda a, ad, b, bd, y, yd, t: lib.onnx_add_lp(a, d(ad), len(ad), b, d(bd), len(bd), y, d(yd), len(yd), t, None)
+    assert add(fake, (4, 8), fake2, (8,), ctypes.c_void_p(1 << 21), (4, 8), 0) == 4
+    assert add(fake, (4, 8), fake2, (3,), ctypes.c_void_p(1 << 21), (4, 8), B.BF16) == 3
+    assert add(fake, (4, 8), fake2, (8,), ctypes.c_void_p(1 << 21), (4, 4), B.F16) == 3
+    assert add(fake, (4, 8), None, (8,), ctypes.c_void_p(1 << 21), (4, 8), B.F16) == 1
+    assert add(fake, (4, 8), fake2, (8,), ctypes.c_void_p(4096 + 62), (4, 8), B.F16) == 6          # Y starts on A's last element
+    assert add(None, (0, 8), None, (8,), None, (0, 8), B.BF16) == 0
+    assert lib.onnx_abs_lp(fake, 8, fake2, 5, None) == 4
+    assert lib.onnx_abs_lp(fake, -2, fake2, B.F16, None) == 3
+    assert lib.onnx_abs_lp(None, 8, fake2, B.F16, None) == 1
+    assert lib.onnx_abs_lp(fake, 8, ctypes.c_void_p(4110), B.BF16, None) == 6
+    assert lib.onnx_abs_lp(None, 0, None, B.BF16, None) == 0
     # pools: inferred shape, window against the padded image, pads against the window
     assert lib.onnx_maxpool_lp(fake, d((1, 1, 4, 4)), d((2, 2)), d((0, 0, 0, 0)), d((1, 1)), d((1, 1)), 0, fake2, d((1, 1, 2, 2)), B.BF16, None) == 3
     assert lib.onnx_maxpool_lp(fake, d((1, 1, 4, 4)), d((2, 2)), d((2, 2, 2, 2)), d((1, 1)), d((1, 1)), 0, fake2, d((1, 1, 7, 7)), B.F16, None) == 4

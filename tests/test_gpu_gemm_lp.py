@@ -717,6 +717,82 @@ def test_leakyrelu_16bit_bit_exact(lib, kind):
         GraphRunner(dict(m, graph=[conv, dict(op="softmax", x="c", axis=1, y="r")]), dtype=TORCH_T[kind])
 
 
+ADD_LP_CASES = [((4, 24, 14, 16), (4, 24, 14, 16), 0), ((4, 24, 14, 16), (24, 1, 1), 0), ((2, 3, 7, 40), (40,), 0), ((5, 1, 48), (1, 9, 1), 0),
+                ((3, 5, 7), (3, 5, 7), 0), ((6, 33), (1,), 0), ((6, 32), (6, 1), 0), ((2, 16, 8), (2, 16, 8), 1), ((4, 8), (8,), 3),
+                ((1,), (7, 3, 8), 0), ((0, 5), (5,), 0), ((2, 2, 2, 2, 2, 3, 8), (2, 1, 2, 1, 2, 1, 8), 0)]
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("sa,sb,off", ADD_LP_CASES)
+def test_add_abs_16bit_bit_exact(lib, sa, sb, off, kind):
+    """Add on 16-bit tensors (Section 3's running example in the type Section 3.1 also lists): the fp32 sum of two 16-bit
+    values rounded to the type is the correctly rounded sum, so the result equals the oracle's value for value (zeros
+    with their sign, NaN where infinities cancel): same-shape, per-channel, row, column, scalar and two-sided
+    broadcasts, element-wise forms for misaligned views and short rows, an empty tensor.  Abs: the sign bit cleared."""
+    announce("add_lp", kind, sa, sb, off)
+    from oracle import elementwise as ew
+    rng = np.random.default_rng(abs(hash((sa, sb, off))) % 1000)
+    special = np.array([0.0, -0.0, np.inf, -np.inf, 65504.0, -65504.0, 6e-8, -6e-8, 1e-40, 40000.0, 40000.0, 1.0], dtype=np.float32)
+
+    def operand(shape):
+        n = int(np.prod(shape))
+        x = (rng.standard_normal(n) * 10.0 ** rng.integers(-3, 3, n)).astype(np.float32)
+        k = min(n, special.size)
+        x[:k] = rng.permutation(special)[:k]
+        bits, vals = encode(x, kind)
+        buf = torch.empty(n + 16, dtype=TORCH_T[kind], device="cuda")
+        t = buf[off:off + n]
+        if n:
+            t.copy_(bits_to_dev(bits, kind))
+        return t.view(shape), vals.reshape(shape).astype(np.float64)
+
+    A, av = operand(sa)
+    B, bv = operand(sb)
+    got = lib.onnx_add_lp(A, B)
+    torch.cuda.synchronize()
+    with np.errstate(all="ignore"):
+        want = ew.add_16bit(av, bv, kind)
+    assert got.dtype == TORCH_T[kind] and tuple(got.shape) == want.shape
+    g = lp_to_host(got, kind).astype(np.float64).reshape(want.shape)
+    assert np.array_equal(g, want, equal_nan=True)
+    assert np.array_equal(np.signbit(g)[want == 0], np.signbit(want)[want == 0])
+    # Abs of the first operand: the same bits without the sign
+    ab = lib.onnx_abs_lp(A)
+    torch.cuda.synchronize()
+    assert np.array_equal(ab.view(torch.int16).cpu().numpy().view(np.uint16), A.contiguous().view(torch.int16).cpu().numpy().view(np.uint16) & 0x7fff)
+    assert np.array_equal(lp_to_host(ab, kind).astype(np.float64), ew.absolute(av.astype(np.float32)), equal_nan=True)
+
+
+def test_add_abs_16bit_errors_and_runner(lib):
+    announce("add_lp errors and runner nodes")
+    x = torch.zeros((4, 8), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(TypeError):
+        lib.onnx_add_lp(x, x.half())
+    with pytest.raises(lib.OnnxHipError):
+        lib.onnx_add_lp(x, torch.zeros((3,), dtype=torch.bfloat16, device="cuda"))
+    with pytest.raises(lib.OnnxHipError):
+        lib.onnx_add_lp(x, x, out=x)                               # the result may not overlap an input
+    with pytest.raises(lib.OnnxHipError):
+        lib.onnx_abs_lp(x, out=x)
+    # through the runner's 16-bit mode: Conv -> Add (with the input, unfused) -> Abs
+    from oracle import elementwise as ew
+    from paper_2008_08272_amd.runner import GraphRunner
+    rng = np.random.default_rng(5)
+    conv = dict(op="conv", x="x", w="w", b="b", pads=(1, 1, 1, 1), strides=(1, 1), dilations=(1, 1), group=1, residual=None,
+                relu=False, y="c")
+    m = dict(inputs={"x": rng.standard_normal((2, 16, 9, 9)).astype(np.float32)},
+             weights={"w": (rng.standard_normal((16, 16, 3, 3)) * 0.1).astype(np.float32), "b": rng.standard_normal(16).astype(np.float32)},
+             graph=[conv, dict(op="add", a="c", b="x", y="s"), dict(op="abs", x="s", y="r")], output="r")
+    for kind in ("f16", "bf16"):
+        r = GraphRunner(m, dtype=TORCH_T[kind])
+        r.run()
+        torch.cuda.synchronize()
+        c, xin = r.t["c"].double().cpu().numpy(), r.t["x"].double().cpu().numpy()
+        want = ew.add_16bit(c, xin, kind)
+        assert np.array_equal(r.t["s"].double().cpu().numpy(), want)
+        assert np.array_equal(r.t["r"].double().cpu().numpy(), np.abs(want))
+
+
 def test_pools_16bit_errors(lib):
     announce("pool_lp errors")
     import ctypes

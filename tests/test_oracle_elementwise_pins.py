@@ -122,3 +122,56 @@ def test_against_torch_float64():
     assert np.allclose(ew.leakyrelu(x, 0.2), torch.nn.functional.leaky_relu(t, float(np.float32(0.2))).numpy(), rtol=1e-15)
     b = rng.standard_normal((5, 1, 6)).astype(np.float32)
     assert np.array_equal(ew.add(x, b), (t + torch.from_numpy(b).double()).numpy())
+
+
+def test_round_to_16bit_half_matches_numpy_and_bfloat16_matches_torch():
+    """The oracle's one-step rounding to a 16-bit type against two library conversions that round once: numpy's
+    double -> float16, and torch's float32 -> bfloat16 on doubles that are float32 values."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(21)
+    v = np.concatenate([rng.standard_normal(4000) * 10.0 ** rng.integers(-9, 6, 4000),
+                        np.ldexp(rng.integers(-3000, 3000, 500).astype(np.float64), -25),       # half's subnormals and their ties
+                        np.array([0.0, -0.0, 65504.0, 65519.9, 65520.0, -65520.0, 1e9, np.inf, -np.inf, 2.0 ** -24, 2.0 ** -25, 3 * 2.0 ** -25])])
+    with np.errstate(over="ignore"):
+        want = v.astype(np.float16).astype(np.float64)
+    got = ew.round_to_16bit(v, "f16")
+    assert np.array_equal(got, want) and np.array_equal(np.signbit(got), np.signbit(want))
+    assert np.isnan(ew.round_to_16bit(np.array([np.nan]), "f16"))[0]
+    f = np.concatenate([(rng.standard_normal(4000) * 10.0 ** rng.integers(-30, 30, 4000)).astype(np.float32),
+                        np.array([3.3895314e38, 3.4e38, -3.4e38, 1e-40, -1e-40, 9.1e-41, 0.0], dtype=np.float32)])
+    want = torch.from_numpy(f).to(torch.bfloat16).double().numpy()
+    assert np.array_equal(ew.round_to_16bit(f.astype(np.float64), "bf16"), want)
+
+
+def test_round_to_16bit_ties_and_error_bound():
+    """Hand-worked ties (to the even significand) and, over random doubles, the definition itself in exact rational
+    arithmetic: the result is within half a spacing of the input, and on the even neighbour when exactly half away."""
+    from fractions import Fraction
+    cases = [(1 + 2.0 ** -8, 1.0), (1 + 3 * 2.0 ** -8, 1 + 2.0 ** -6), (1 + 2.0 ** -8 + 2.0 ** -30, 1 + 2.0 ** -7),
+             (2.0 ** -134, 0.0), (3 * 2.0 ** -134, 2.0 ** -132), (-(1 + 2.0 ** -8), -1.0), (3.39e38, 3.3895313892515355e38),
+             (3.3962e38, np.inf)]
+    for v, want in cases:
+        assert ew.round_to_16bit(np.array([v]), "bf16")[0] == want, v
+    assert ew.round_to_16bit(np.array([1 + 2.0 ** -11]), "f16")[0] == 1.0
+    assert ew.round_to_16bit(np.array([1 + 3 * 2.0 ** -11]), "f16")[0] == 1 + 2.0 ** -9
+    rng = np.random.default_rng(22)
+    for kind, bits, emin in (("f16", 11, -14), ("bf16", 8, -126)):
+        v = rng.standard_normal(300) * 10.0 ** rng.integers(-4, 4, 300)
+        v[:40] = np.ldexp(rng.integers(1, 1 << 12, 40).astype(np.float64), rng.integers(-20, 5, 40) - 12)   # many exact ties
+        r = ew.round_to_16bit(v, kind)
+        for x, y in zip(v.tolist(), r.tolist()):
+            e = max(math.frexp(x)[1], emin + 1)
+            spacing = Fraction(2) ** (e - bits)
+            err = abs(Fraction(y) - Fraction(x))
+            q = Fraction(y) / spacing
+            assert q.denominator == 1 and abs(q) <= 2 ** bits, (kind, x, y)          # a value of the type
+            assert err * 2 <= spacing, (kind, x, y)
+            if err * 2 == spacing:
+                assert q.numerator % 2 == 0, (kind, x, y)
+
+
+def test_add_16bit_is_the_rounded_exact_sum():
+    a = np.array([1.0, 1.0, 256.0, -3.0, 65504.0, 0.0], dtype=np.float64)
+    b = np.array([2.0 ** -8, 3 * 2.0 ** -8, 1.0, 3.0, 65504.0, -0.0], dtype=np.float64)
+    assert ew.add_16bit(a, b, "bf16").tolist() == [1.0, 1 + 2.0 ** -6, 256.0, 0.0, 131072.0, 0.0]      # 257 ties to 256
+    assert ew.add_16bit(a, b, "f16").tolist() == [1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 257.0, 0.0, np.inf, 0.0]
