@@ -500,6 +500,26 @@ def main():
             y = torch.empty(8, 256, 56, 56, device=dev)
             return lambda: lib.onnx_conv(x, w, b, (1, 1, 1, 1), (1, 1), (1, 1), 256, out=y)
 
+        # the same operators on bfloat16 tensors (half the bytes)
+        def rnd16(*sh):
+            return torch.randn(*sh, device=dev).to(torch.bfloat16)
+
+        def mk_add16():
+            a, b, y = rnd16(*shape), rnd16(*shape), torch.empty(shape, device=dev, dtype=torch.bfloat16)
+            return lambda: lib.onnx_add_lp(a, b, out=y)
+
+        def mk_bias16():
+            a, b, y = rnd16(*shape), rnd16(256, 1, 1), torch.empty(shape, device=dev, dtype=torch.bfloat16)
+            return lambda: lib.onnx_add_lp(a, b, out=y)
+
+        def mk_leaky16():
+            a, y = rnd16(*shape), torch.empty(shape, device=dev, dtype=torch.bfloat16)
+            return lambda: lib.onnx_leakyrelu_lp(a, 0.01, out=y)
+
+        def mk_maxpool16():
+            x, y = rnd16(32, 64, 112, 112), torch.empty(32, 64, 56, 56, device=dev, dtype=torch.bfloat16)
+            return lambda: lib.onnx_maxpool_lp(x, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0, out=y)
+
         hbm("hbm_add_32x256x56x56", 3 * nb, mk_add)
         hbm("hbm_add_channel_bias_32x256x56x56", 2 * nb, mk_bias)
         hbm("hbm_relu_32x256x56x56", 2 * nb, mk_relu)
@@ -509,6 +529,10 @@ def main():
         hbm("hbm_softmax_8192x1000", 8.0 * 8192 * 1000, mk_softmax)
         hbm("hbm_maxpool_3x3s2_32x64x112x112", 4.0 * (32 * 64 * 112 * 112 + 32 * 64 * 56 * 56), mk_maxpool)
         hbm("hbm_depthwise_3x3_8x256x56x56", 4.0 * 2 * 8 * 256 * 56 * 56, mk_depthwise)
+        hbm("hbm_add_bf16_32x256x56x56", 1.5 * nb, mk_add16)
+        hbm("hbm_add_channel_bias_bf16_32x256x56x56", nb, mk_bias16)
+        hbm("hbm_leakyrelu_bf16_32x256x56x56", nb, mk_leaky16)
+        hbm("hbm_maxpool_bf16_3x3s2_32x64x112x112", 2.0 * (32 * 64 * 112 * 112 + 32 * 64 * 56 * 56), mk_maxpool16)
 
     # ---- CPU oracle beside it (a reported baseline, not the target) ---------------------------
     cpu = None

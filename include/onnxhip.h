@@ -341,6 +341,19 @@ onnx_status onnx_add_lp(const void* A, const int64_t* a_dims, int a_rank, const 
 onnx_status onnx_abs_lp(const void* X, int64_t count, void* Y, onnx_dtype type, void* stream);
 
 /*
+ * ONNX ReduceSum and Softmax on 16-bit tensors (`type` ONNX_F16 or ONNX_BF16 for X and Y): shapes,
+ * axes, keepdims, y_dims, the optional workspace and errors as for onnx_reducesum / onnx_softmax
+ * (Section 3.4: ReduceSum is the other half of the ReduceL1 decomposition).  Sums, the maximum,
+ * the exponentials and the division are fp32; only the result is rounded to the type (nearest
+ * even).  Y must not overlap X.
+ */
+onnx_status onnx_reducesum_lp(const void* X, const int64_t* x_dims, int rank, const int64_t* axes, int naxes,
+                              int keepdims, void* Y, const int64_t* y_dims, int y_rank, onnx_dtype type,
+                              void* stream);
+onnx_status onnx_softmax_lp(const void* X, const int64_t* x_dims, int rank, int axis, void* Y, onnx_dtype type,
+                            void* stream);
+
+/*
  * ONNX LSTM (named among the supported operators, Section 4.1), layout 0, default activations
  * (sigmoid, tanh, tanh), no peepholes, every sequence of full length.  X [seq, batch, input];
  * W [dirs, 4H, input] and R [dirs, 4H, H] with the gate blocks in the order i, o, f, c;

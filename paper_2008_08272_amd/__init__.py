@@ -13,7 +13,7 @@ import importlib
 
 _BINDING_NAMES = (
     "OnnxHipError", "lib_path", "onnx_chain", "chain_shapes", "onnx_abs", "onnx_add", "onnx_avgpool", "onnx_broadcast_infer", "onnx_conv",
-    "onnx_conv_fixed_scratch", "onnx_conv_lp", "onnx_conv_lp_taps", "onnx_conv_lp_filter_taps", "onnx_maxpool_lp", "onnx_leakyrelu_lp", "onnx_add_lp", "onnx_abs_lp", "onnx_avgpool_lp", "onnx_last_launch", "onnx_matmul_lp",
+    "onnx_conv_fixed_scratch", "onnx_conv_lp", "onnx_conv_lp_taps", "onnx_conv_lp_filter_taps", "onnx_maxpool_lp", "onnx_leakyrelu_lp", "onnx_add_lp", "onnx_abs_lp", "onnx_reducesum_lp", "onnx_softmax_lp", "onnx_avgpool_lp", "onnx_last_launch", "onnx_matmul_lp",
     "onnx_conv_infer", "onnx_gemm", "onnx_gemm_lp", "onnx_last_error", "onnx_leakyrelu", "onnx_lstm", "onnx_matmul",
     "onnx_matmul_infer", "onnx_maxpool", "onnx_pool_infer", "onnx_reduce_infer", "onnx_reducesum", "onnx_relu",
     "onnx_set_workspace", "onnx_softmax",

@@ -58,6 +58,10 @@ _lib.onnx_add_lp.argtypes = [_vp, _i64p, _ci, _vp, _i64p, _ci, _vp, _i64p, _ci, 
 _lib.onnx_add_lp.restype = _ci
 _lib.onnx_abs_lp.argtypes = [_vp, _c64, _vp, _ci, _vp]
 _lib.onnx_abs_lp.restype = _ci
+_lib.onnx_reducesum_lp.argtypes = [_vp, _i64p, _ci, _i64p, _ci, _ci, _vp, _i64p, _ci, _ci, _vp]
+_lib.onnx_reducesum_lp.restype = _ci
+_lib.onnx_softmax_lp.argtypes = [_vp, _i64p, _ci, _ci, _vp, _ci, _vp]
+_lib.onnx_softmax_lp.restype = _ci
 for _f in (_lib.onnx_conv_infer, _lib.onnx_pool_infer, _lib.onnx_matmul_infer, _lib.onnx_conv,
            _lib.onnx_gemm, _lib.onnx_matmul, _lib.onnx_maxpool, _lib.onnx_avgpool, _lib.onnx_maxpool_lp,
            _lib.onnx_avgpool_lp):
@@ -446,6 +450,24 @@ def onnx_abs_lp(X, out=None, stream=None):
     X = _lp(X, "X")
     Y, _ = _lp_out(out, X.shape, X.dtype, X)
     _check(_lib.onnx_abs_lp(_ptr(X), X.numel(), _ptr(Y), _LP_TYPES[X.dtype], _stream(stream)))
+    return Y
+
+
+def onnx_reducesum_lp(X, axes=None, keepdims=1, out=None, stream=None):
+    """ReduceSum on a float16 / bfloat16 CUDA tensor (fp32 sums); the result has the same type."""
+    X = _lp(X, "X")
+    axes = [] if axes is None else list(axes)
+    Y, _ = _lp_out(out, onnx_reduce_infer(X.shape, axes, keepdims), X.dtype, X)
+    _check(_lib.onnx_reducesum_lp(_ptr(X), dims(X.shape), X.dim(), dims(axes), len(axes), int(keepdims), _ptr(Y),
+                                  dims(Y.shape), Y.dim(), _LP_TYPES[X.dtype], _stream(stream)))
+    return Y
+
+
+def onnx_softmax_lp(X, axis=-1, out=None, stream=None):
+    """Softmax on a float16 / bfloat16 CUDA tensor (fp32 arithmetic); the result has the same type."""
+    X = _lp(X, "X")
+    Y, _ = _lp_out(out, X.shape, X.dtype, X)
+    _check(_lib.onnx_softmax_lp(_ptr(X), dims(X.shape), X.dim(), int(axis), _ptr(Y), _LP_TYPES[X.dtype], _stream(stream)))
     return Y
 
 

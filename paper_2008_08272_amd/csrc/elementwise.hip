@@ -29,8 +29,24 @@ unsigned blocks_for(int64_t work_items, int per_block = 256, unsigned cap = 256u
     return (unsigned)(b < 1 ? 1 : (b > cap ? cap : b));
 }
 
-__global__ __launch_bounds__(256) void fill_kernel(float* __restrict__ Y, int64_t n, float v) {
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) Y[i] = v;
+// Storage types of the reductions and of Softmax: DT = 0 is fp32, LP_F16 / LP_BF16 the 16-bit types; arithmetic is
+// fp32 for all of them, a 16-bit result rounded once on the way out.
+template <int DT>
+struct Elem {
+    typedef uint16_t type;
+    static __device__ inline float load(const uint16_t* p) { return from_lp<DT>(*p); }
+    static __device__ inline void store(uint16_t* p, float v) { *p = to_lp<DT>(v); }
+};
+template <>
+struct Elem<0> {
+    typedef float type;
+    static __device__ inline float load(const float* p) { return *p; }
+    static __device__ inline void store(float* p, float v) { *p = v; }
+};
+
+template <int DT>
+__global__ __launch_bounds__(256) void fill_kernel(typename Elem<DT>::type* __restrict__ Y, int64_t n, float v) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) Elem<DT>::store(Y + i, v);
 }
 
 // ---------------------------------------------------------------------------- unary
@@ -204,66 +220,87 @@ __device__ inline int64_t offset_of(uint32_t idx, int n, const FastDiv* dims, co
 // chunk of the reduced index space together (coalesced along the innermost extent), each
 // keeps a private fp32 sum, and a butterfly adds the 64 of them.  `chunks` > 1 is the first
 // stage of a two-stage reduction: it writes chunk sums, chunk-minor, for a second launch.
-__global__ __launch_bounds__(256) void reduce_inner_kernel(const float* __restrict__ X, float* __restrict__ Y,
-                                                           ReduceMap m, uint32_t chunks, uint32_t per_chunk) {
+// DTI / DTO: storage types of X and Y (the chunk sums of a two-stage reduction are fp32 whatever the tensors are).
+template <int DTI, int DTO>
+__global__ __launch_bounds__(256) void reduce_inner_kernel(const typename Elem<DTI>::type* __restrict__ X,
+                                                           typename Elem<DTO>::type* __restrict__ Y, ReduceMap m, uint32_t chunks,
+                                                           uint32_t per_chunk) {
+    typedef typename Elem<DTI>::type in_t;
     const uint32_t wave = blockIdx.x * 4u + (threadIdx.x >> 6);
     if (wave >= m.outputs * chunks) return;
     const uint32_t out = wave / chunks, chunk = wave - out * chunks;
     const int lane = threadIdx.x & 63;
-    const float* base = X + offset_of(out, m.nk, m.kdim, m.ks);
+    const in_t* base = X + offset_of(out, m.nk, m.kdim, m.ks);
     const uint32_t r0 = chunk * per_chunk;
     const uint32_t r1 = min(m.reduced, r0 + per_chunk);
     float acc = 0.f;
     if (m.nr == 1 && m.rs[0] == 1) {
-        // contiguous run: scalar head up to a 16-byte boundary, 16-byte loads with four
+        // contiguous run: scalar head up to a 16-byte boundary, 16-byte loads (EPV elements each) with four
         // independent partial sums per lane (four loads in flight), scalar tail
-        const float* p = base + r0;
+        constexpr uint32_t EPV = 16 / sizeof(in_t);
+        const in_t* p = base + r0;
         const uint32_t n = r1 > r0 ? r1 - r0 : 0u;
-        uint32_t head = (uint32_t)((16u - (uint32_t)(reinterpret_cast<uintptr_t>(p) & 15u)) & 15u) >> 2;
+        uint32_t head = (uint32_t)((16u - (uint32_t)(reinterpret_cast<uintptr_t>(p) & 15u)) & 15u) / (uint32_t)sizeof(in_t);
         if (head > n) head = n;
-        if ((uint32_t)lane < head) acc += p[lane];
-        const floatx4* p4 = reinterpret_cast<const floatx4*>(p + head);
-        const uint32_t n4 = (n - head) >> 2;
+        if ((uint32_t)lane < head) acc += Elem<DTI>::load(p + lane);
+        const uint32_t nv = (n - head) / EPV;
         float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
         uint32_t j = lane;
-        for (; j + 192 < n4; j += 256) {
-            const floatx4 v0 = p4[j], v1 = p4[j + 64], v2 = p4[j + 128], v3 = p4[j + 192];
-            a0 += (v0.x + v0.y) + (v0.z + v0.w);
-            a1 += (v1.x + v1.y) + (v1.z + v1.w);
-            a2 += (v2.x + v2.y) + (v2.z + v2.w);
-            a3 += (v3.x + v3.y) + (v3.z + v3.w);
-        }
-        for (; j < n4; j += 64) {
-            const floatx4 v = p4[j];
-            a0 += (v.x + v.y) + (v.z + v.w);
+        if constexpr (DTI == 0) {
+            const floatx4* p4 = reinterpret_cast<const floatx4*>(p + head);
+            for (; j + 192 < nv; j += 256) {
+                const floatx4 v0 = p4[j], v1 = p4[j + 64], v2 = p4[j + 128], v3 = p4[j + 192];
+                a0 += (v0.x + v0.y) + (v0.z + v0.w);
+                a1 += (v1.x + v1.y) + (v1.z + v1.w);
+                a2 += (v2.x + v2.y) + (v2.z + v2.w);
+                a3 += (v3.x + v3.y) + (v3.z + v3.w);
+            }
+            for (; j < nv; j += 64) {
+                const floatx4 v = p4[j];
+                a0 += (v.x + v.y) + (v.z + v.w);
+            }
+        } else {
+            const uintx4* p8 = reinterpret_cast<const uintx4*>(p + head);
+            auto sum8 = [](const uintx4& v) {
+                float t[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) t[k] = from_lp<DTI>(v[k] & 0xffffu) + from_lp<DTI>(v[k] >> 16);
+                return (t[0] + t[1]) + (t[2] + t[3]);
+            };
+            for (; j + 192 < nv; j += 256) {
+                const uintx4 v0 = p8[j], v1 = p8[j + 64], v2 = p8[j + 128], v3 = p8[j + 192];
+                a0 += sum8(v0); a1 += sum8(v1); a2 += sum8(v2); a3 += sum8(v3);
+            }
+            for (; j < nv; j += 64) a0 += sum8(p8[j]);
         }
         acc += (a0 + a1) + (a2 + a3);
-        for (uint32_t t = head + (n4 << 2) + lane; t < n; t += 64) acc += p[t];
+        for (uint32_t t = head + nv * EPV + lane; t < n; t += 64) acc += Elem<DTI>::load(p + t);
     } else if (m.nr == 1) {
-        for (uint32_t r = r0 + lane; r < r1; r += 64) acc += base[(int64_t)r * m.rs[0]];
+        for (uint32_t r = r0 + lane; r < r1; r += 64) acc += Elem<DTI>::load(base + (int64_t)r * m.rs[0]);
     } else {
-        for (uint32_t r = r0 + lane; r < r1; r += 64) acc += base[offset_of(r, m.nr, m.rdim, m.rs)];
+        for (uint32_t r = r0 + lane; r < r1; r += 64) acc += Elem<DTI>::load(base + offset_of(r, m.nr, m.rdim, m.rs));
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-    if (lane == 0) Y[wave] = acc;
+    if (lane == 0) Elem<DTO>::store(Y + wave, acc);
 }
 
 // The innermost extent of X is kept: one thread per output, neighbouring threads on
 // neighbouring innermost positions, each walks the reduced index space on its own (every step
 // is a coalesced row read across the threads).
-__global__ __launch_bounds__(256) void reduce_outer_kernel(const float* __restrict__ X, float* __restrict__ Y,
-                                                           ReduceMap m) {
+template <int DT>
+__global__ __launch_bounds__(256) void reduce_outer_kernel(const typename Elem<DT>::type* __restrict__ X,
+                                                           typename Elem<DT>::type* __restrict__ Y, ReduceMap m) {
     const uint32_t out = blockIdx.x * 256u + threadIdx.x;
     if (out >= m.outputs) return;
-    const float* base = X + offset_of(out, m.nk, m.kdim, m.ks);
+    const typename Elem<DT>::type* base = X + offset_of(out, m.nk, m.kdim, m.ks);
     float acc = 0.f;
     if (m.nr == 1) {
-        for (uint32_t r = 0; r < m.reduced; ++r) acc += base[(int64_t)r * m.rs[0]];
+        for (uint32_t r = 0; r < m.reduced; ++r) acc += Elem<DT>::load(base + (int64_t)r * m.rs[0]);
     } else {
-        for (uint32_t r = 0; r < m.reduced; ++r) acc += base[offset_of(r, m.nr, m.rdim, m.rs)];
+        for (uint32_t r = 0; r < m.reduced; ++r) acc += Elem<DT>::load(base + offset_of(r, m.nr, m.rdim, m.rs));
     }
-    Y[out] = acc;
+    Elem<DT>::store(Y + out, acc);
 }
 
 // Normalises `axes` (negative values count from the end; none = all) into a per-dimension flag.
@@ -299,20 +336,21 @@ __device__ inline float wave_sum(float v) {
     return v;
 }
 
-__global__ __launch_bounds__(256) void softmax_rows_kernel(const float* __restrict__ X, float* __restrict__ Y,
-                                                           uint32_t rows, uint32_t L) {
+template <int DT>
+__global__ __launch_bounds__(256) void softmax_rows_kernel(const typename Elem<DT>::type* __restrict__ X,
+                                                           typename Elem<DT>::type* __restrict__ Y, uint32_t rows, uint32_t L) {
     const uint32_t row = blockIdx.x * 4u + (threadIdx.x >> 6);
     if (row >= rows) return;
     const int lane = threadIdx.x & 63;
-    const float* x = X + (int64_t)row * L;
-    float* y = Y + (int64_t)row * L;
+    const typename Elem<DT>::type* x = X + (int64_t)row * L;
+    typename Elem<DT>::type* y = Y + (int64_t)row * L;
     if (L <= 64u * ROW_REGS) {
         float v[ROW_REGS];
         float mx = -__builtin_inff();
 #pragma unroll
         for (int i = 0; i < ROW_REGS; ++i) {
             const uint32_t j = lane + 64u * i;
-            v[i] = j < L ? x[j] : -__builtin_inff();
+            v[i] = j < L ? Elem<DT>::load(x + j) : -__builtin_inff();
             mx = fmaxf(mx, v[i]);
         }
         mx = wave_max(mx);
@@ -326,36 +364,150 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(const float* __restri
 #pragma unroll
         for (int i = 0; i < ROW_REGS; ++i) {
             const uint32_t j = lane + 64u * i;
-            if (j < L) y[j] = v[i] * inv;
+            if (j < L) Elem<DT>::store(y + j, v[i] * inv);
         }
     } else {
         float mx = -__builtin_inff();
-        for (uint32_t j = lane; j < L; j += 64) mx = fmaxf(mx, x[j]);
+        for (uint32_t j = lane; j < L; j += 64) mx = fmaxf(mx, Elem<DT>::load(x + j));
         mx = wave_max(mx);
         float sum = 0.f;
-        for (uint32_t j = lane; j < L; j += 64) sum += expf(x[j] - mx);
+        for (uint32_t j = lane; j < L; j += 64) sum += expf(Elem<DT>::load(x + j) - mx);
         const float inv = 1.0f / wave_sum(sum);
-        for (uint32_t j = lane; j < L; j += 64) y[j] = expf(x[j] - mx) * inv;
+        for (uint32_t j = lane; j < L; j += 64) Elem<DT>::store(y + j, expf(Elem<DT>::load(x + j) - mx) * inv);
     }
 }
 
 // inner > 1: one thread per (outer, inner) column, neighbouring threads on neighbouring inner
 // positions; three passes over the column (each step a coalesced read across the threads).
-__global__ __launch_bounds__(256) void softmax_cols_kernel(const float* __restrict__ X, float* __restrict__ Y,
-                                                           uint32_t cols, uint32_t L, FastDiv innerd) {
+template <int DT>
+__global__ __launch_bounds__(256) void softmax_cols_kernel(const typename Elem<DT>::type* __restrict__ X,
+                                                           typename Elem<DT>::type* __restrict__ Y, uint32_t cols, uint32_t L, FastDiv innerd) {
     const uint32_t c = blockIdx.x * 256u + threadIdx.x;
     if (c >= cols) return;
     uint32_t outer, in;
     innerd.divmod(c, outer, in);
     const int64_t inner = innerd.d;
-    const float* x = X + (int64_t)outer * L * inner + in;
-    float* y = Y + (int64_t)outer * L * inner + in;
+    const typename Elem<DT>::type* x = X + (int64_t)outer * L * inner + in;
+    typename Elem<DT>::type* y = Y + (int64_t)outer * L * inner + in;
     float mx = -__builtin_inff();
-    for (uint32_t j = 0; j < L; ++j) mx = fmaxf(mx, x[(int64_t)j * inner]);
+    for (uint32_t j = 0; j < L; ++j) mx = fmaxf(mx, Elem<DT>::load(x + (int64_t)j * inner));
     float sum = 0.f;
-    for (uint32_t j = 0; j < L; ++j) sum += expf(x[(int64_t)j * inner] - mx);
+    for (uint32_t j = 0; j < L; ++j) sum += expf(Elem<DT>::load(x + (int64_t)j * inner) - mx);
     const float inv = 1.0f / sum;
-    for (uint32_t j = 0; j < L; ++j) y[(int64_t)j * inner] = expf(x[(int64_t)j * inner] - mx) * inv;
+    for (uint32_t j = 0; j < L; ++j) Elem<DT>::store(y + (int64_t)j * inner, expf(Elem<DT>::load(x + (int64_t)j * inner) - mx) * inv);
+}
+
+// ReduceSum on tensors of storage type DT (0: fp32): checks, the merged index spaces, the launches.
+template <int DT>
+onnx_status reducesum_impl(const typename Elem<DT>::type* X, const int64_t* x_dims, int rank, const int64_t* axes, int naxes,
+                           int keepdims, typename Elem<DT>::type* Y, const int64_t* y_dims, int y_rank, void* stream) {
+    constexpr int64_t esz = sizeof(typename Elem<DT>::type);
+    int64_t yd[ONNX_MAX_RANK];
+    int r = 0;
+    onnx_status st = onnx_reduce_infer(x_dims, rank, axes, naxes, keepdims, yd, &r);
+    if (st != ONNX_OK) return st;
+    if (y_rank != r || (r && !y_dims)) return fail(ONNX_ERR_SHAPE, "reducesum: y_rank %d but the inferred rank is %d", y_rank, r);
+    for (int d = 0; d < r; ++d)
+        if (y_dims[d] != yd[d])
+            return fail(ONNX_ERR_SHAPE, "reducesum: y_dims[%d]=%lld but the inferred extent is %lld", d, (long long)y_dims[d], (long long)yd[d]);
+    bool red[ONNX_MAX_RANK];
+    reduce_flags("reducesum", rank, axes, naxes, red);
+    int64_t nx = 1, ny = 1, nred = 1;
+    for (int d = 0; d < rank; ++d) {
+        if (x_dims[d] != 0 && nx > kMaxElems / x_dims[d]) return fail(ONNX_ERR_UNSUPPORTED, "reducesum: more than 2^31-1 input elements");
+        nx *= x_dims[d];
+        if (red[d]) nred *= x_dims[d]; else ny *= x_dims[d];
+    }
+    if (ny == 0) return ONNX_OK;
+    if (!Y || (nx != 0 && !X)) return fail(ONNX_ERR_NULL, "reducesum: X and Y must not be NULL");
+    if (overlaps(Y, ny * esz, X, nx * esz)) return fail(ONNX_ERR_ALIAS, "reducesum: Y overlaps X");
+    // merged kept / reduced extents with their strides in X (unit extents dropped)
+    ReduceMap m;
+    m.nk = m.nr = 0;
+    int64_t kd[ONNX_MAX_RANK], rd[ONNX_MAX_RANK];
+    {
+        int64_t stride[ONNX_MAX_RANK], sacc = 1;
+        for (int d = rank - 1; d >= 0; --d) { stride[d] = sacc; sacc *= x_dims[d]; }
+        int last = -1;                                   // 0 = kept, 1 = reduced: kind of the previous extent
+        for (int d = 0; d < rank; ++d) {
+            if (x_dims[d] == 1) continue;
+            const int kind = red[d] ? 1 : 0;
+            if (kind == last) {                          // adjacent extents of one kind: one longer extent
+                if (kind) { rd[m.nr - 1] *= x_dims[d]; m.rs[m.nr - 1] = stride[d]; }
+                else { kd[m.nk - 1] *= x_dims[d]; m.ks[m.nk - 1] = stride[d]; }
+            } else if (kind) { rd[m.nr] = x_dims[d]; m.rs[m.nr] = stride[d]; ++m.nr; }
+            else { kd[m.nk] = x_dims[d]; m.ks[m.nk] = stride[d]; ++m.nk; }
+            last = kind;
+        }
+        if (m.nr == 0) { rd[0] = nred; m.rs[0] = 0; m.nr = 1; }     // nothing (or only unit extents) to add up
+        for (int i = 0; i < m.nk; ++i) m.kdim[i] = FastDiv::make((uint32_t)kd[i]);
+        for (int i = 0; i < m.nr; ++i) m.rdim[i] = FastDiv::make((uint32_t)rd[i]);
+        m.outputs = (uint32_t)ny;
+        m.reduced = (uint32_t)nred;
+        // which kind is innermost in memory
+        int inner_kind = 0;
+        for (int d = rank - 1; d >= 0; --d) if (x_dims[d] != 1) { inner_kind = red[d] ? 1 : 0; break; }
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        if (nred == 0) {                                 // empty sum: every output is 0
+            hipLaunchKernelGGL(fill_kernel<DT>, dim3(blocks_for(ny)), dim3(256), 0, s, Y, ny, 0.f);
+            return device_status(hipGetLastError(), "reducesum");
+        }
+        if (inner_kind == 1 || ny < 64) {
+            // few outputs and a long sum: cut the reduced range into chunks when a workspace can hold the chunk sums
+            const Workspace& w = workspace();
+            uint32_t chunks = 1;
+            if (w.partial && ny < 2048 && nred >= 32768) {
+                int64_t c = nred / 8192;
+                const int64_t cap = 4096 / ny > 1 ? 4096 / ny : 1;
+                if (c > cap) c = cap;
+                if (c >= 2 && ny * c <= w.partial_floats) chunks = (uint32_t)c;
+            }
+            if (chunks > 1) {
+                const uint32_t per = (uint32_t)((nred + chunks - 1) / chunks);
+                hipLaunchKernelGGL((reduce_inner_kernel<DT, 0>), dim3((unsigned)((ny * chunks + 3) / 4)), dim3(256), 0, s, X, w.partial, m, chunks, per);
+                ReduceMap m2;
+                m2.nk = 1; m2.nr = 1;
+                m2.kdim[0] = FastDiv::make((uint32_t)ny); m2.ks[0] = chunks;
+                m2.rdim[0] = FastDiv::make(chunks); m2.rs[0] = 1;
+                m2.outputs = (uint32_t)ny; m2.reduced = chunks;
+                hipLaunchKernelGGL((reduce_inner_kernel<0, DT>), dim3((unsigned)((ny + 3) / 4)), dim3(256), 0, s, static_cast<const float*>(w.partial), Y, m2, 1u, chunks);
+            } else {
+                hipLaunchKernelGGL((reduce_inner_kernel<DT, DT>), dim3((unsigned)((ny + 3) / 4)), dim3(256), 0, s, X, Y, m, 1u, (uint32_t)nred);
+            }
+        } else {
+            hipLaunchKernelGGL(reduce_outer_kernel<DT>, dim3((unsigned)((ny + 255) / 256)), dim3(256), 0, s, X, Y, m);
+        }
+    }
+    return device_status(hipGetLastError(), "reducesum");
+}
+
+// Softmax on tensors of storage type DT (0: fp32).
+template <int DT>
+onnx_status softmax_impl(const typename Elem<DT>::type* X, const int64_t* x_dims, int rank, int axis, typename Elem<DT>::type* Y, void* stream) {
+    constexpr int64_t esz = sizeof(typename Elem<DT>::type);
+    if (rank < 1 || rank > ONNX_MAX_RANK) return fail(ONNX_ERR_RANK, "softmax: rank %d outside 1..%d", rank, ONNX_MAX_RANK);
+    if (!x_dims) return fail(ONNX_ERR_NULL, "softmax: NULL dims");
+    if (axis < -rank || axis >= rank) return fail(ONNX_ERR_ATTR, "softmax: axis %d out of range for rank %d", axis, rank);
+    if (axis < 0) axis += rank;
+    int64_t outer = 1, inner = 1, n = 1;
+    for (int d = 0; d < rank; ++d) {
+        if (x_dims[d] < 0) return fail(ONNX_ERR_SHAPE, "softmax: negative extent");
+        if (x_dims[d] != 0 && n > kMaxElems / x_dims[d]) return fail(ONNX_ERR_UNSUPPORTED, "softmax: more than 2^31-1 elements");
+        n *= x_dims[d];
+        if (d < axis) outer *= x_dims[d];
+        if (d > axis) inner *= x_dims[d];
+    }
+    const int64_t L = x_dims[axis];
+    if (n == 0) return ONNX_OK;
+    if (!X || !Y) return fail(ONNX_ERR_NULL, "softmax: X and Y must not be NULL");
+    if (overlaps(Y, n * esz, X, n * esz)) return fail(ONNX_ERR_ALIAS, "softmax: Y overlaps X");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (inner == 1)
+        hipLaunchKernelGGL(softmax_rows_kernel<DT>, dim3((unsigned)((outer + 3) / 4)), dim3(256), 0, s, X, Y, (uint32_t)outer, (uint32_t)L);
+    else
+        hipLaunchKernelGGL(softmax_cols_kernel<DT>, dim3((unsigned)((outer * inner + 255) / 256)), dim3(256), 0, s, X, Y,
+                           (uint32_t)(outer * inner), (uint32_t)L, FastDiv::make((uint32_t)inner));
+    return device_status(hipGetLastError(), "softmax");
 }
 
 }  // namespace
@@ -510,109 +662,28 @@ onnx_status onnx_reduce_infer(const int64_t* x_dims, int rank, const int64_t* ax
 
 onnx_status onnx_reducesum(const float* X, const int64_t* x_dims, int rank, const int64_t* axes, int naxes,
                            int keepdims, float* Y, const int64_t* y_dims, int y_rank, void* stream) {
-    int64_t yd[ONNX_MAX_RANK];
-    int r = 0;
-    onnx_status st = onnx_reduce_infer(x_dims, rank, axes, naxes, keepdims, yd, &r);
-    if (st != ONNX_OK) return st;
-    if (y_rank != r || (r && !y_dims)) return fail(ONNX_ERR_SHAPE, "reducesum: y_rank %d but the inferred rank is %d", y_rank, r);
-    for (int d = 0; d < r; ++d)
-        if (y_dims[d] != yd[d])
-            return fail(ONNX_ERR_SHAPE, "reducesum: y_dims[%d]=%lld but the inferred extent is %lld", d, (long long)y_dims[d], (long long)yd[d]);
-    bool red[ONNX_MAX_RANK];
-    reduce_flags("reducesum", rank, axes, naxes, red);
-    int64_t nx = 1, ny = 1, nred = 1;
-    for (int d = 0; d < rank; ++d) {
-        if (x_dims[d] != 0 && nx > kMaxElems / x_dims[d]) return fail(ONNX_ERR_UNSUPPORTED, "reducesum: more than 2^31-1 input elements");
-        nx *= x_dims[d];
-        if (red[d]) nred *= x_dims[d]; else ny *= x_dims[d];
-    }
-    if (ny == 0) return ONNX_OK;
-    if (!Y || (nx != 0 && !X)) return fail(ONNX_ERR_NULL, "reducesum: X and Y must not be NULL");
-    if (overlaps(Y, ny * 4, X, nx * 4)) return fail(ONNX_ERR_ALIAS, "reducesum: Y overlaps X");
-    // merged kept / reduced extents with their strides in X (unit extents dropped)
-    ReduceMap m;
-    m.nk = m.nr = 0;
-    int64_t kd[ONNX_MAX_RANK], rd[ONNX_MAX_RANK];
-    {
-        int64_t stride[ONNX_MAX_RANK], sacc = 1;
-        for (int d = rank - 1; d >= 0; --d) { stride[d] = sacc; sacc *= x_dims[d]; }
-        int last = -1;                                   // 0 = kept, 1 = reduced: kind of the previous extent
-        for (int d = 0; d < rank; ++d) {
-            if (x_dims[d] == 1) continue;
-            const int kind = red[d] ? 1 : 0;
-            if (kind == last) {                          // adjacent extents of one kind: one longer extent
-                if (kind) { rd[m.nr - 1] *= x_dims[d]; m.rs[m.nr - 1] = stride[d]; }
-                else { kd[m.nk - 1] *= x_dims[d]; m.ks[m.nk - 1] = stride[d]; }
-            } else if (kind) { rd[m.nr] = x_dims[d]; m.rs[m.nr] = stride[d]; ++m.nr; }
-            else { kd[m.nk] = x_dims[d]; m.ks[m.nk] = stride[d]; ++m.nk; }
-            last = kind;
-        }
-        if (m.nr == 0) { rd[0] = nred; m.rs[0] = 0; m.nr = 1; }     // nothing (or only unit extents) to add up
-        for (int i = 0; i < m.nk; ++i) m.kdim[i] = FastDiv::make((uint32_t)kd[i]);
-        for (int i = 0; i < m.nr; ++i) m.rdim[i] = FastDiv::make((uint32_t)rd[i]);
-        m.outputs = (uint32_t)ny;
-        m.reduced = (uint32_t)nred;
-        // which kind is innermost in memory
-        int inner_kind = 0;
-        for (int d = rank - 1; d >= 0; --d) if (x_dims[d] != 1) { inner_kind = red[d] ? 1 : 0; break; }
-        hipStream_t s = static_cast<hipStream_t>(stream);
-        if (nred == 0) {                                 // empty sum: every output is 0
-            hipLaunchKernelGGL(fill_kernel, dim3(blocks_for(ny)), dim3(256), 0, s, Y, ny, 0.f);
-            return device_status(hipGetLastError(), "reducesum");
-        }
-        if (inner_kind == 1 || ny < 64) {
-            // few outputs and a long sum: cut the reduced range into chunks when a workspace can hold the chunk sums
-            const Workspace& w = workspace();
-            uint32_t chunks = 1;
-            if (w.partial && ny < 2048 && nred >= 32768) {
-                int64_t c = nred / 8192;
-                const int64_t cap = 4096 / ny > 1 ? 4096 / ny : 1;
-                if (c > cap) c = cap;
-                if (c >= 2 && ny * c <= w.partial_floats) chunks = (uint32_t)c;
-            }
-            if (chunks > 1) {
-                const uint32_t per = (uint32_t)((nred + chunks - 1) / chunks);
-                hipLaunchKernelGGL(reduce_inner_kernel, dim3((unsigned)((ny * chunks + 3) / 4)), dim3(256), 0, s, X, w.partial, m, chunks, per);
-                ReduceMap m2;
-                m2.nk = 1; m2.nr = 1;
-                m2.kdim[0] = FastDiv::make((uint32_t)ny); m2.ks[0] = chunks;
-                m2.rdim[0] = FastDiv::make(chunks); m2.rs[0] = 1;
-                m2.outputs = (uint32_t)ny; m2.reduced = chunks;
-                hipLaunchKernelGGL(reduce_inner_kernel, dim3((unsigned)((ny + 3) / 4)), dim3(256), 0, s, w.partial, Y, m2, 1u, chunks);
-            } else {
-                hipLaunchKernelGGL(reduce_inner_kernel, dim3((unsigned)((ny + 3) / 4)), dim3(256), 0, s, X, Y, m, 1u, (uint32_t)nred);
-            }
-        } else {
-            hipLaunchKernelGGL(reduce_outer_kernel, dim3((unsigned)((ny + 255) / 256)), dim3(256), 0, s, X, Y, m);
-        }
-    }
-    return device_status(hipGetLastError(), "reducesum");
+    return reducesum_impl<0>(X, x_dims, rank, axes, naxes, keepdims, Y, y_dims, y_rank, stream);
+}
+
+onnx_status onnx_reducesum_lp(const void* X, const int64_t* x_dims, int rank, const int64_t* axes, int naxes, int keepdims,
+                              void* Y, const int64_t* y_dims, int y_rank, onnx_dtype type, void* stream) {
+    const uint16_t* x = static_cast<const uint16_t*>(X);
+    uint16_t* y = static_cast<uint16_t*>(Y);
+    if (type == ONNX_F16) return reducesum_impl<LP_F16>(x, x_dims, rank, axes, naxes, keepdims, y, y_dims, y_rank, stream);
+    if (type == ONNX_BF16) return reducesum_impl<LP_BF16>(x, x_dims, rank, axes, naxes, keepdims, y, y_dims, y_rank, stream);
+    return fail(ONNX_ERR_ATTR, "reducesum_lp: type must be ONNX_F16 or ONNX_BF16");
 }
 
 onnx_status onnx_softmax(const float* X, const int64_t* x_dims, int rank, int axis, float* Y, void* stream) {
-    if (rank < 1 || rank > ONNX_MAX_RANK) return fail(ONNX_ERR_RANK, "softmax: rank %d outside 1..%d", rank, ONNX_MAX_RANK);
-    if (!x_dims) return fail(ONNX_ERR_NULL, "softmax: NULL dims");
-    if (axis < -rank || axis >= rank) return fail(ONNX_ERR_ATTR, "softmax: axis %d out of range for rank %d", axis, rank);
-    if (axis < 0) axis += rank;
-    int64_t outer = 1, inner = 1, n = 1;
-    for (int d = 0; d < rank; ++d) {
-        if (x_dims[d] < 0) return fail(ONNX_ERR_SHAPE, "softmax: negative extent");
-        if (x_dims[d] != 0 && n > kMaxElems / x_dims[d]) return fail(ONNX_ERR_UNSUPPORTED, "softmax: more than 2^31-1 elements");
-        n *= x_dims[d];
-        if (d < axis) outer *= x_dims[d];
-        if (d > axis) inner *= x_dims[d];
-    }
-    const int64_t L = x_dims[axis];
-    if (n == 0) return ONNX_OK;
-    if (!X || !Y) return fail(ONNX_ERR_NULL, "softmax: X and Y must not be NULL");
-    if (overlaps(Y, n * 4, X, n * 4)) return fail(ONNX_ERR_ALIAS, "softmax: Y overlaps X");
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (inner == 1)
-        hipLaunchKernelGGL(softmax_rows_kernel, dim3((unsigned)((outer + 3) / 4)), dim3(256), 0, s, X, Y, (uint32_t)outer, (uint32_t)L);
-    else
-        hipLaunchKernelGGL(softmax_cols_kernel, dim3((unsigned)((outer * inner + 255) / 256)), dim3(256), 0, s, X, Y,
-                           (uint32_t)(outer * inner), (uint32_t)L, FastDiv::make((uint32_t)inner));
-    return device_status(hipGetLastError(), "softmax");
+    return softmax_impl<0>(X, x_dims, rank, axis, Y, stream);
+}
+
+onnx_status onnx_softmax_lp(const void* X, const int64_t* x_dims, int rank, int axis, void* Y, onnx_dtype type, void* stream) {
+    const uint16_t* x = static_cast<const uint16_t*>(X);
+    uint16_t* y = static_cast<uint16_t*>(Y);
+    if (type == ONNX_F16) return softmax_impl<LP_F16>(x, x_dims, rank, axis, y, stream);
+    if (type == ONNX_BF16) return softmax_impl<LP_BF16>(x, x_dims, rank, axis, y, stream);
+    return fail(ONNX_ERR_ATTR, "softmax_lp: type must be ONNX_F16 or ONNX_BF16");
 }
 
 }  // extern "C"

@@ -138,9 +138,10 @@ class GraphRunner:
         code = B.F16 if dt == torch.float16 else B.BF16
         fp32_names = set()                         # the additive operands, which the 16-bit operators take in fp32
         for nd in model["graph"]:
-            if nd["op"] not in ("conv", "maxpool", "avgpool", "reshape", "gemm", "matmul", "relu", "leakyrelu", "add", "abs"):
+            if nd["op"] not in ("conv", "maxpool", "avgpool", "reshape", "gemm", "matmul", "relu", "leakyrelu", "add", "abs", "reducesum",
+                                "softmax"):
                 raise NotImplementedError("node %r (%s): the 16-bit runner takes Conv, MaxPool, AveragePool, Reshape, Gemm, "
-                                          "MatMul, Relu, LeakyRelu, Add and Abs nodes" % (nd["y"], nd["op"]))
+                                          "MatMul, Relu, LeakyRelu, Add, Abs, ReduceSum and Softmax nodes" % (nd["y"], nd["op"]))
             if nd["op"] == "conv" and nd["b"]:
                 fp32_names.add(nd["b"])
             if nd["op"] == "gemm" and nd["c"]:
@@ -229,6 +230,17 @@ class GraphRunner:
                 x = self.t[nd["x"]]
                 y = self._new(nd["y"], x.shape, dt)
                 self.calls.append((lib.onnx_abs_lp, [B._ptr(x), x.numel(), B._ptr(y), code, None]))
+            elif op == "reducesum":
+                x = self.t[nd["x"]]
+                axes = [] if nd["axes"] is None else list(nd["axes"])
+                y = self._new(nd["y"], B.onnx_reduce_infer(x.shape, axes, nd["keepdims"]), dt)
+                args = [B._ptr(x), B.dims(x.shape), x.dim(), B.dims(axes), len(axes), int(nd["keepdims"]), B._ptr(y),
+                        B.dims(y.shape), y.dim(), code, None]
+                self.calls.append((lib.onnx_reducesum_lp, args))
+            elif op == "softmax":
+                x = self.t[nd["x"]]
+                y = self._new(nd["y"], x.shape, dt)
+                self.calls.append((lib.onnx_softmax_lp, [B._ptr(x), B.dims(x.shape), x.dim(), int(nd["axis"]), B._ptr(y), code, None]))
             else:                                  # matmul
                 a, b = self.t[nd["a"]], self.t[nd["b"]]
                 yd = B.onnx_matmul_infer(a.shape, b.shape)

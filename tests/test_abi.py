@@ -252,7 +252,7 @@ def test_fixed_scratch_conv_validates_like_conv_and_enforces_its_maximum(B):
 
 
 def test_16bit_entry_points_validate_before_touching_the_device(B):
-    """The 16-bit pools, LeakyRelu, Add, Abs and the filter rewriting check types, shapes and pointers on the host: every
+    """The 16-bit pools, LeakyRelu, Add, Abs, ReduceSum, Softmax and the filter rewriting check types, shapes and pointers on the host: every
     refusal below returns without device work."""
     lib = B.raw()
     d = B.dims
@@ -279,6 +279,18 @@ def test_16bit_entry_points_validate_before_touching_the_device(B):
     assert lib.onnx_abs_lp(None, 8, fake2, B.F16, None) == 1
     assert lib.onnx_abs_lp(fake, 8, ctypes.c_void_p(4110), B.BF16, None) == 6
     assert lib.onnx_abs_lp(None, 0, None, B.BF16, None) == 0
+    # ReduceSum and Softmax: type, axes, result shape, pointers
+    red = lambda x, xd, ax, keep, y, yd, t: lib.onnx_reducesum_lp(x, d(xd), len(xd), d(ax), len(ax), keep, y, d(yd), len(yd), t, None)
+    assert red(fake, (4, 8), (1,), 1, fake2, (4, 1), 0) == 4
+    assert red(fake, (4, 8), (2,), 1, fake2, (4, 1), B.F16) == 4
+    assert red(fake, (4, 8), (1,), 1, fake2, (4, 8), B.F16) == 3
+    assert red(None, (4, 8), (1,), 1, fake2, (4, 1), B.BF16) == 1
+    assert red(fake, (4, 8), (1,), 0, ctypes.c_void_p(4096 + 32), (4,), B.BF16) == 6
+    assert lib.onnx_softmax_lp(fake, d((4, 8)), 2, 1, fake2, 3, None) == 4
+    assert lib.onnx_softmax_lp(fake, d((4, 8)), 2, 2, fake2, B.F16, None) == 4
+    assert lib.onnx_softmax_lp(fake, d((4, 8)), 2, 1, None, B.F16, None) == 1
+    assert lib.onnx_softmax_lp(fake, d((4, 8)), 2, 1, ctypes.c_void_p(4096 + 8), B.BF16, None) == 6
+    assert lib.onnx_softmax_lp(None, d((0, 8)), 2, 1, None, B.BF16, None) == 0
     # pools: inferred shape, window against the padded image, pads against the window
     assert lib.onnx_maxpool_lp(fake, d((1, 1, 4, 4)), d((2, 2)), d((0, 0, 0, 0)), d((1, 1)), d((1, 1)), 0, fake2, d((1, 1, 2, 2)), B.BF16, None) == 3
     assert lib.onnx_maxpool_lp(fake, d((1, 1, 4, 4)), d((2, 2)), d((2, 2, 2, 2)), d((1, 1)), d((1, 1)), 0, fake2, d((1, 1, 7, 7)), B.F16, None) == 4

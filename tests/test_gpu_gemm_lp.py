@@ -714,7 +714,7 @@ def test_leakyrelu_16bit_bit_exact(lib, kind):
     assert np.array_equal(r.t["l"].float().cpu().numpy(), want_l)
     assert np.array_equal(r.t["r"].float().cpu().numpy(), np.maximum(want_l, 0))
     with pytest.raises(NotImplementedError):
-        GraphRunner(dict(m, graph=[conv, dict(op="softmax", x="c", axis=1, y="r")]), dtype=TORCH_T[kind])
+        GraphRunner(dict(m, graph=[conv, dict(op="batchnorm", x="c", y="r")]), dtype=TORCH_T[kind])
 
 
 ADD_LP_CASES = [((4, 24, 14, 16), (4, 24, 14, 16), 0), ((4, 24, 14, 16), (24, 1, 1), 0), ((2, 3, 7, 40), (40,), 0), ((5, 1, 48), (1, 9, 1), 0),
@@ -791,6 +791,82 @@ def test_add_abs_16bit_errors_and_runner(lib):
         want = ew.add_16bit(c, xin, kind)
         assert np.array_equal(r.t["s"].double().cpu().numpy(), want)
         assert np.array_equal(r.t["r"].double().cpu().numpy(), np.abs(want))
+
+
+REDUCE_LP_CASES = [((4, 6, 10, 12), [2, 3], 1), ((4, 6, 10, 12), [1], 0), ((3, 70000), [1], 1), ((5, 7, 9), None, 0), ((64, 33), [0], 1),
+                   ((9, 1, 40), [0, 2], 0), ((2, 100003), [1], 0), ((3, 5, 4099), [2], 1), ((0, 4), [0], 0), ((1, 300000), None, 1)]
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("use_ws", [False, True])
+@pytest.mark.parametrize("shape,axes,keep", REDUCE_LP_CASES)
+def test_reducesum_16bit_matches_oracle(lib, shape, axes, keep, use_ws, kind):
+    """ReduceSum on 16-bit tensors: fp32 partial sums in an unspecified order, one rounding to the type at the end.
+    Small integers (every partial sum exact, the result a value of the type) must come out exactly; for random data
+    the result is within (count + 2) 2^-24 sum|x| of the exact sum, plus half a unit of the type in the last place."""
+    announce("reducesum_lp", kind, shape, axes, keep, use_ws)
+    from oracle import elementwise as ew
+    ws = torch.empty(8 << 20, dtype=torch.uint8, device="cuda") if use_ws else None
+    lib.onnx_set_workspace(ws)
+    try:
+        rng = np.random.default_rng(31)
+        u = 2.0 ** -11 if kind == "f16" else 2.0 ** -8
+        tiny = 2.0 ** -25 if kind == "f16" else 2.0 ** -134
+        n = int(np.prod(shape))
+        # values in {-1, 0, 1}: partial sums are small integers, and so is every result for the short sums; the long ones
+        # are bounded by the tolerance test below
+        x = rng.integers(-1, 2, shape).astype(np.float32)
+        bits, vals = encode(x, kind)
+        X = bits_to_dev(bits.reshape(-1), kind).view(shape) if n else torch.empty(shape, dtype=TORCH_T[kind], device="cuda")
+        Y = lib.onnx_reducesum_lp(X, axes, keep)
+        ref = ew.reducesum(vals, axes, keep)
+        assert tuple(Y.shape) == ref.shape and Y.dtype == TORCH_T[kind]
+        got = lp_to_host(Y.reshape(-1), kind).astype(np.float64).reshape(ref.shape)
+        assert np.array_equal(got, ew.round_to_16bit(ref, kind))
+        if n == 0:
+            return
+        x = (rng.standard_normal(shape) * 4).astype(np.float32)
+        bits, vals = encode(x, kind)
+        X = bits_to_dev(bits.reshape(-1), kind).view(shape)
+        got = lp_to_host(lib.onnx_reducesum_lp(X, axes, keep).reshape(-1), kind).astype(np.float64)
+        ref = ew.reducesum(vals, axes, keep).reshape(-1)
+        scale = ew.reducel1(vals, axes, keep).reshape(-1)
+        count = n // max(ref.size, 1)
+        assert (np.abs(got - ref) <= (count + 2) * 2.0 ** -24 * scale * (1 + u) + u * np.abs(ref) + tiny).all()
+    finally:
+        torch.cuda.synchronize()
+        lib.onnx_set_workspace(None)
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("shape,axis", [((1, 5), 1), ((32, 1000), 1), ((32, 1000), 0), ((7, 1025), -1), ((3, 5000), 1), ((4, 9, 6), 1),
+                                        ((2, 3, 4, 5), 2), ((513,), 0), ((6, 1), 1), ((0, 7), 1)])
+def test_softmax_16bit_matches_oracle(lib, shape, axis, kind):
+    """Softmax on 16-bit tensors: the fp32 kernel's arithmetic on the 16-bit values (the bound of the fp32 test), then one
+    rounding to the type."""
+    announce("softmax_lp", kind, shape, axis)
+    from oracle import elementwise as ew
+    rng = np.random.default_rng(32)
+    u = 2.0 ** -11 if kind == "f16" else 2.0 ** -8
+    tiny = 2.0 ** -25 if kind == "f16" else 2.0 ** -134
+    for scale in (1.0, 8.0):
+        x = (rng.standard_normal(shape) * scale).astype(np.float32)
+        bits, vals = encode(x, kind)
+        if x.size == 0:
+            assert lib.onnx_softmax_lp(torch.empty(shape, dtype=TORCH_T[kind], device="cuda"), axis).shape == shape
+            continue
+        X = bits_to_dev(bits.reshape(-1), kind).view(shape)
+        got = lp_to_host(lib.onnx_softmax_lp(X, axis), kind).astype(np.float64)
+        ref = ew.softmax(vals, axis)
+        assert got.shape == ref.shape
+        depth = np.abs(vals.astype(np.float64) - vals.astype(np.float64).max(axis=axis, keepdims=True))
+        assert (np.abs(got - ref) <= ((depth * 2.0 ** -23 + 4e-6) * (1 + u) + u) * ref + tiny).all()
+    big = bits_to_dev(encode(np.array([1000.0, 1000.0, -1000.0], np.float32), kind)[0], kind).view(1, 3)
+    assert lp_to_host(lib.onnx_softmax_lp(big, 1), kind).tolist() == [[0.5, 0.5, 0.0]]
+    with pytest.raises(lib.OnnxHipError):
+        lib.onnx_softmax_lp(big, 2)
+    with pytest.raises(lib.OnnxHipError):
+        lib.onnx_reducesum_lp(big, [3])
 
 
 def test_pools_16bit_errors(lib):
