@@ -86,6 +86,74 @@ __global__ __launch_bounds__(256) void maxpool_lp_pairs_kernel(const uint16_t* _
     if (ow + 1 < g.OW) Y[o + 1] = best_bits[1];
 }
 
+// The same windows on rows whose length is a multiple of 8 with exactly W / 2 outputs: a thread computes four
+// neighbouring outputs of one output row from one 16-byte load per input row (columns 8c .. 8c + 7) and the
+// column left of it (a 2-byte load that hits the cache line of the previous thread's load), and stores them as one
+// 8-byte word.  Output 4c + j reads columns 8c + 2j - 1 .. 8c + 2j + 1; same scan order and
+// first-maximum rule as above.
+template <int DT>
+__global__ __launch_bounds__(256) void maxpool_lp_quads_kernel(const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, WindowGeom g,
+                                                              PoolIndex d, uint32_t total_quads) {
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;            // (plane, oh, group of four output columns)
+    if (idx >= total_quads) return;
+    uint32_t q, c, plane, oh;
+    d.OW.divmod(idx, q, c);                                          // d.OW divides by the groups per output row
+    d.OH.divmod(q, plane, oh);
+    const int ih0 = (int)oh * g.sH - g.pT;
+    const uint16_t* xc = X + (int64_t)plane * g.H * g.W;
+    bool found[4] = {false, false, false, false};
+    float best[4] = {0.f, 0.f, 0.f, 0.f};
+    uint32_t best_bits[4] = {0, 0, 0, 0};
+    auto offer = [&](int o, uint32_t bits) {
+        const float v = from_lp<DT>(bits);
+        if (!found[o] || v > best[o]) { best[o] = v; best_bits[o] = bits; found[o] = true; }
+    };
+    // one input row's eight columns and the column left of them, in scan order
+    auto offer_row = [&](const uintx4& v, uint32_t left) {
+        if (c > 0) offer(0, left);
+        uint32_t e[8];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { e[2 * k] = v[k] & 0xffffu; e[2 * k + 1] = v[k] >> 16; }
+        offer(0, e[0]);
+        offer(0, e[1]);
+#pragma unroll
+        for (int j = 1; j < 4; ++j) {
+            offer(j, e[2 * j - 1]);
+            offer(j, e[2 * j]);
+            offer(j, e[2 * j + 1]);
+        }
+    };
+    // W a multiple of 8 and X 16-byte aligned: every load below is aligned and inside its row
+    if (g.kH == 3) {
+        // all six loads of the three rows requested before the first comparison (a row outside the image reads row 0
+        // instead and is skipped afterwards)
+        uintx4 v[3];
+        uint32_t left[3];
+        bool inside[3];
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh) {
+            const int ih = ih0 + kh * g.dH;
+            inside[kh] = ih >= 0 && ih < g.H;
+            const uint16_t* row = xc + (inside[kh] ? ih : 0) * g.W + 8 * (int)c;
+            v[kh] = *reinterpret_cast<const uintx4*>(row);
+            left[kh] = c > 0 ? row[-1] : 0u;
+        }
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh)
+            if (inside[kh]) offer_row(v[kh], left[kh]);
+    } else {
+        for (int kh = 0; kh < g.kH; ++kh) {
+            const int ih = ih0 + kh * g.dH;
+            if (ih < 0 || ih >= g.H) continue;
+            const uint16_t* row = xc + ih * g.W + 8 * (int)c;
+            offer_row(*reinterpret_cast<const uintx4*>(row), c > 0 ? row[-1] : 0u);
+        }
+    }
+    typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
+    const uintx2 out = {best_bits[0] | (best_bits[1] << 16), best_bits[2] | (best_bits[3] << 16)};
+    *reinterpret_cast<uintx2*>(Y + ((int64_t)plane * g.OH + oh) * g.OW + 4 * (int)c) = out;
+}
+
 template <int DT>
 __global__ __launch_bounds__(256) void avgpool_lp_kernel(const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, WindowGeom g,
                                                         int count_include_pad, PoolIndex d, uint32_t total) {
@@ -181,6 +249,17 @@ hipError_t launch_maxpool_lp(const void* X, void* Y, const WindowGeom& g, int ty
     uint16_t* y = static_cast<uint16_t*>(Y);
     // pairs of outputs from 4-byte loads: the window of output ow + 1 must end inside the pair at column 2*ow + 2, and the
     // last output's middle pair inside the row
+    // four outputs per thread from 16-byte loads: rows a multiple of 8 long with W / 2 outputs each
+    if (g.kW == 3 && g.sW == 2 && g.dW == 1 && g.pL == 1 && g.W % 8 == 0 && 2 * g.OW == g.W && (reinterpret_cast<uintptr_t>(X) & 15u) == 0 &&
+        (reinterpret_cast<uintptr_t>(Y) & 7u) == 0) {
+        const int quads_per_row = g.OW / 4;
+        const uint32_t total_quads = (uint32_t)((int64_t)g.N * g.C * g.OH * quads_per_row);
+        const PoolIndex dq = {FastDiv::make((uint32_t)quads_per_row), FastDiv::make((uint32_t)g.OH)};
+        const dim3 qgrid((total_quads + 255u) / 256u);
+        if (type == LP_BF16) hipLaunchKernelGGL(maxpool_lp_quads_kernel<LP_BF16>, qgrid, block, 0, stream, x, y, g, dq, total_quads);
+        else hipLaunchKernelGGL(maxpool_lp_quads_kernel<LP_F16>, qgrid, block, 0, stream, x, y, g, dq, total_quads);
+        return hipGetLastError();
+    }
     if (g.kW == 3 && g.sW == 2 && g.dW == 1 && g.pL == 1 && g.W % 2 == 0 && 2 * g.OW <= g.W && (reinterpret_cast<uintptr_t>(X) & 3u) == 0) {
         const int pairs_per_row = (g.OW + 1) / 2;
         const uint32_t total_pairs = (uint32_t)((int64_t)g.N * g.C * g.OH * pairs_per_row);

@@ -621,8 +621,12 @@ POOL_LP_CASES = [
     (2, 2, 11, 11, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 1),
     (1, 3, 12, 9, (3, 2), (0, 0, 0, 0), (3, 2), (2, 2), 0),
     (2, 5, 13, 10, (3, 2), (2, 0, 1, 1), (1, 2), (1, 1), 0),
-    (3, 64, 56, 56, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),      # 3 columns, stride 2, left pad 1, even rows: two outputs per thread
+    (3, 64, 56, 56, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),      # 3 columns, stride 2, left pad 1, rows of 56: four outputs per thread
     (1, 2, 9, 10, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),        # the same with an odd number of output columns
+    (2, 4, 17, 24, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),       # rows a multiple of 8 long: four outputs per thread from 16-byte loads
+    (1, 3, 10, 16, (2, 3), (0, 1, 0, 1), (1, 2), (1, 1), 0),       # the same with two rows per window at vertical stride 1
+    (1, 2, 11, 16, (3, 3), (2, 1, 2, 1), (3, 2), (2, 1), 0),       # the same with vertical dilation, stride 3 and pads of 2
+    (2, 2, 9, 20, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),        # rows of 20: even but not a multiple of 8, two outputs per thread
     (1, 2, 12, 10, (2, 3), (0, 1, 0, 1), (1, 2), (1, 1), 0),       # two rows per window, vertical stride 1
     (2, 2, 9, 12, (3, 3), (1, 1, 0, 0), (2, 2), (1, 1), 1),        # ceil_mode: a last window past the row, one output per thread
     (4, 1, 1, 1, (1, 1), (0, 0, 0, 0), (1, 1), (1, 1), 0),
