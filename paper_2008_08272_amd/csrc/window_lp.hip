@@ -197,6 +197,31 @@ __global__ __launch_bounds__(256) void global_avgpool_lp_kernel(const uint16_t* 
     if (lane == 0) Y[plane] = to_lp<DT>(acc / (float)HW);
 }
 
+// Planes of at most 64 values (the 7 x 7 planes in front of a classifier): a wavefront takes eight neighbouring
+// planes, one value per lane and plane, all eight loads requested together; the same butterfly per plane (the
+// same order of additions as above), lanes 0..7 store the eight means.
+template <int DT>
+__global__ __launch_bounds__(256) void global_avgpool_lp_small_kernel(const uint16_t* __restrict__ X, uint16_t* __restrict__ Y,
+                                                                     int64_t planes, int HW) {
+    const int lane = threadIdx.x & 63;
+    const int64_t first = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 8;
+    if (first >= planes) return;
+    float acc[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int64_t plane = first + k < planes ? first + k : planes - 1;
+        acc[k] = lane < HW ? from_lp<DT>(X[plane * HW + lane]) : 0.f;
+    }
+    float mine = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) acc[k] += __shfl_xor(acc[k], off, 64);
+        if (lane == k) mine = acc[k];
+    }
+    if (lane < 8 && first + lane < planes) Y[first + lane] = to_lp<DT>(mine / (float)HW);
+}
+
 // LeakyRelu (Section 3.1 of the paper: its operator definition lists F16 among the element types; Relu is
 // alpha = 0): y = x for x >= 0, alpha * x otherwise, the product rounded to fp32 and then to the type.
 // VEC = 8: one 16-byte load and store per thread; VEC = 1: any alignment and the tail.
@@ -290,6 +315,12 @@ hipError_t launch_global_avgpool_lp(const void* X, void* Y, int64_t planes, int 
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const uint16_t* x = static_cast<const uint16_t*>(X);
     uint16_t* y = static_cast<uint16_t*>(Y);
+    if (HW <= 64 && planes >= 64) {
+        const dim3 grid((unsigned)((planes + 31) / 32)), block(256);
+        if (type == LP_BF16) hipLaunchKernelGGL(global_avgpool_lp_small_kernel<LP_BF16>, grid, block, 0, stream, x, y, planes, HW);
+        else hipLaunchKernelGGL(global_avgpool_lp_small_kernel<LP_F16>, grid, block, 0, stream, x, y, planes, HW);
+        return hipGetLastError();
+    }
     if (type == LP_BF16) hipLaunchKernelGGL(global_avgpool_lp_kernel<LP_BF16>, dim3((unsigned)blocks), dim3(256), 0, stream, x, y, planes, HW);
     else hipLaunchKernelGGL(global_avgpool_lp_kernel<LP_F16>, dim3((unsigned)blocks), dim3(256), 0, stream, x, y, planes, HW);
     return hipGetLastError();

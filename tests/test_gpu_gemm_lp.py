@@ -630,6 +630,8 @@ POOL_LP_CASES = [
     (1, 2, 12, 10, (2, 3), (0, 1, 0, 1), (1, 2), (1, 1), 0),       # two rows per window, vertical stride 1
     (2, 2, 9, 12, (3, 3), (1, 1, 0, 0), (2, 2), (1, 1), 1),        # ceil_mode: a last window past the row, one output per thread
     (4, 1, 1, 1, (1, 1), (0, 0, 0, 0), (1, 1), (1, 1), 0),
+    (5, 13, 7, 7, (2, 2), (0, 0, 0, 0), (1, 1), (1, 1), 0),        # 65 planes of 49 values: the global mean takes eight planes per wavefront, one left over
+    (4, 16, 8, 8, (3, 3), (1, 1, 1, 1), (2, 2), (1, 1), 0),        # 64 planes of 64 values
     (0, 3, 8, 8, (2, 2), (0, 0, 0, 0), (2, 2), (1, 1), 0),
 ]
 
