@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libonnxhip.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-SOURCES = ("api.hip", "contraction.hip", "conv_window.hip", "conv_window_lp.hip", "conv_resident.hip", "window_kernels.hip", "window_lp.hip", "elementwise.hip", "gemm_lp.hip", "lp_generic.hip", "lp_layout.hip", "lstm.hip", "chain.hip")
+SOURCES = ("api.hip", "contraction.hip", "conv_window.hip", "conv_window_lp.hip", "conv_stem_lp.hip", "conv_resident.hip", "window_kernels.hip", "window_lp.hip", "elementwise.hip", "gemm_lp.hip", "lp_generic.hip", "lp_layout.hip", "lstm.hip", "chain.hip")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -239,6 +239,12 @@ onnx_status conv_with_workspace(const float* X, const int64_t x_dims[4], const f
             return device_status(launch_lp_tuned(p, LOAD_RC, bvec, (int)group, (int)in_type, (int)out_type,
                                                  Workspace{ws_bytes > 0 ? reinterpret_cast<float*>(ws_free) : nullptr, ws_bytes / 4}, s),
                                  "conv (16-bit)");
+        if (!pw && !filters_in_tap_order) {
+            hipError_t e = hipSuccess;
+            if (launch_conv_stem_lp(X, W, B, Y, g, (int)M, (int)Cg, (int)group, residual != nullptr, act == ONNX_ACT_RELU, (int)in_type,
+                                    (int)out_type, s, &e))
+                return device_status(e, "conv (16-bit, stem)");
+        }
         if (!pw) {
             hipError_t e = hipSuccess;
             if (launch_conv_window_lp(p, (int)kH, (int)kW, (int)OH, (int)OW, (int)Cg, (int)group, (int)in_type, (int)out_type,

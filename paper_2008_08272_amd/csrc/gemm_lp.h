@@ -38,9 +38,7 @@ __device__ inline floatx16 mfma16(const floatx4& a, const floatx4& b, const floa
 template <int DT>
 __device__ inline uint16_t to_lp(float v) {
     if (DT == LP_F16) return __builtin_bit_cast(uint16_t, (_Float16)v);
-    const uint32_t u = __builtin_bit_cast(uint32_t, v);
-    const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-    return (uint16_t)((u & 0x7fffffffu) > 0x7f800000u ? (u >> 16) | 0x40u : rounded);      // NaN stays NaN
+    return __builtin_bit_cast(uint16_t, (__bf16)v);          // the hardware conversion (v_cvt_pk_bf16_f32): nearest even, NaN stays NaN
 }
 
 // K-contiguous tile loader for 16-bit elements: ROWS x BK values, 16-byte chunks of 8.

@@ -117,6 +117,12 @@ struct WindowGeom {
 bool launch_conv_resident(const float* X, const float* W, const float* B, const float* residual, float* Y,
                           const WindowGeom& g, int M, int Cg, int relu, hipStream_t stream, hipError_t* status);
 
+// The 7x7 stride-2 convolution on 3 channels into 64 feature maps with pads of 3 (ResNet50's stem) on 16-bit tensors
+// (conv_stem_lp.hip).  Returns false for every other shape (the caller then uses the general kernel); otherwise
+// enqueues the kernel and stores the launch status in *status.  in_type / out_type as for launch_lp_generic.
+bool launch_conv_stem_lp(const void* X, const void* W, const float* B, void* Y, const WindowGeom& g, int M, int Cg, int group,
+                         bool has_residual, int relu, int in_type, int out_type, hipStream_t stream, hipError_t* status);
+
 // Direct (one thread per output) convolution for shapes the matrix cores cannot use well:
 // depthwise and other tiny-K / tiny-M groups.
 hipError_t launch_conv_direct(const float* X, const float* W, const float* B, const float* residual,

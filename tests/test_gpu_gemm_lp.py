@@ -279,7 +279,7 @@ def test_16bit_tuned_kernel_random_sweep(lib):
 CONV_LP_CASES = [
     # N, C, H, W, M, kH, kW, pads, strides, dilations, group
     (2, 16, 19, 23, 40, 3, 3, (1, 1, 1, 1), (1, 1), (1, 1), 1),
-    (2, 3, 37, 41, 64, 7, 7, (3, 3, 3, 3), (2, 2), (1, 1), 1),
+    (2, 3, 37, 41, 48, 7, 7, (3, 3, 3, 3), (2, 2), (1, 1), 1),            # 48 filters: not the stem kernel (64)
     (2, 32, 20, 20, 48, 3, 3, (2, 0, 1, 3), (2, 3), (2, 1), 2),
     (2, 64, 12, 12, 96, 1, 1, (0, 0, 0, 0), (1, 1), (1, 1), 1),          # pointwise: row-contiguous input, chunks of 8 positions
     (2, 64, 9, 7, 96, 1, 1, (0, 0, 0, 0), (1, 1), (1, 1), 1),            # pointwise, 63 positions per image: general kernel
@@ -444,6 +444,82 @@ def test_conv3x3_16bit_lds_patch_operands_off_alignment(lib, lp_workspace):
             assert launch.startswith("conv_window_lp 64x64x144") and "B=IM2COL/%d " % cols in launch, launch
             gth = got.cpu().numpy()
             assert rel_err(gth, ref) <= REL_TOL and within_rounding_bound(gth, ref, S, C * 9 + 1)
+
+
+STEM_LP_CASES = [
+    # N, H, W, runs the stem kernel
+    (2, 32, 32, True),        # 16 x 16 outputs: one tile of 16 rows per image
+    (1, 224, 224, True),      # ResNet50's: 112 x 112 outputs, tiles of two rows
+    (3, 30, 34, True),        # 15 x 17 outputs: rows that end inside a wavefront, a last tile with fewer rows
+    (2, 17, 23, True),        # odd extents: the last window column lies past the image
+    (1, 9, 300, True),        # 150 outputs per row: one row per tile, five wavefronts, three idle
+    (1, 20, 80, True),        # 40 outputs per row: patch rows of two 64-column pieces
+    (2, 12, 150, True),       # 75 outputs per row: three pieces
+    (1, 7, 520, False),       # 260 outputs per row: more than a tile holds, the general kernel
+]
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("case", STEM_LP_CASES)
+def test_conv_stem_16bit_matches_oracle(lib, case, kind):
+    """The 7x7 stride-2 convolution of 3 channels into 64 feature maps (ResNet50's first layer, Section 4.2) on 16-bit
+    tensors: its own kernel, with and without bias and Relu, fp32 and 16-bit results; other 7x7 shapes keep the
+    general kernel."""
+    N, H, W, stem = case
+    announce("conv_lp stem", kind, case)
+    rng = np.random.default_rng([N, H, W])
+    pads, st, dl = (3, 3, 3, 3), (2, 2), (1, 1)
+    xb, xv = encode(rng.uniform(-1, 1, (N, 3, H, W)).astype(np.float32), kind)
+    wb, wv = encode(rng.uniform(-1, 1, (64, 3, 7, 7)).astype(np.float32), kind)
+    Bv = rng.uniform(-1, 1, (64,)).astype(np.float32)
+    K = 147
+    X, Wt = bits_to_dev(xb, kind), bits_to_dev(wb, kind)
+    family = "conv_stem_lp" if stem else "lp_generic"
+    ref, S = oracle.conv(xv, wv, Bv, pads, st, dl, 1, want_scale=True)
+    got = lib.onnx_conv_lp(X, Wt, torch.from_numpy(Bv).cuda(), pads, st, dl, 1, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert lib.onnx_last_launch().startswith(family), lib.onnx_last_launch()
+    gth = got.cpu().numpy()
+    assert gth.shape == ref.shape
+    assert rel_err(gth, ref) <= REL_TOL
+    assert within_rounding_bound(gth, ref, S, K + 1)
+    # 16-bit result, no bias, Relu
+    ref2, S2 = oracle.conv(xv, wv, None, pads, st, dl, 1, relu=False, want_scale=True)
+    got2 = lp_to_host(lib.onnx_conv_lp(X, Wt, None, pads, st, dl, 1, act=1), kind)
+    assert lib.onnx_last_launch().startswith(family)
+    u = 2.0 ** -PRECISION[kind]
+    want = np.maximum(ref2, 0)
+    assert (np.abs(got2 - want) <= u * np.abs(want) + (K + 5) * 2.0 ** -24 * (S2 + 1.0) + 1e-7).all()
+    assert (got2 >= 0).all()
+    # small integers: every product and partial sum exact, so the bits must agree; an infinity in one pixel must reach
+    # exactly the windows that contain it (the zero taps that pad K see neighbouring pixels)
+    Xi = rng.integers(-4, 5, (N, 3, H, W)).astype(np.float32)
+    Wi = rng.integers(-4, 5, (64, 3, 7, 7)).astype(np.float32)
+    refi = oracle.conv(Xi, Wi, None, pads, st, dl, 1)
+    Xd, Wd = bits_to_dev(encode(Xi, kind)[0], kind), bits_to_dev(encode(Wi, kind)[0], kind)
+    goti = lib.onnx_conv_lp(Xd, Wd, None, pads, st, dl, 1, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert np.array_equal(goti.cpu().numpy().astype(np.float64), refi)
+    Wpos = np.abs(Wi) + 1
+    Xinf = Xi.copy()
+    Xinf[0, 1, H // 2, W // 2] = np.inf
+    gotf = lib.onnx_conv_lp(bits_to_dev(encode(Xinf, kind)[0], kind), bits_to_dev(encode(Wpos, kind)[0], kind), None, pads, st, dl, 1,
+                            out_dtype=torch.float32).cpu().numpy()
+    hit = np.zeros(gotf.shape[2:], dtype=bool)
+    for oh in range(gotf.shape[2]):
+        for ow in range(gotf.shape[3]):
+            hit[oh, ow] = 0 <= H // 2 - (2 * oh - 3) < 7 and 0 <= W // 2 - (2 * ow - 3) < 7
+    assert np.isposinf(gotf[0][:, hit]).all() and np.isfinite(gotf[0][:, ~hit]).all() and np.isfinite(gotf[1:]).all()
+    # a residual, another filter count or other pads: not this kernel
+    res = torch.zeros(got.shape, dtype=TORCH_T[kind], device="cuda")
+    lib.onnx_conv_lp(X, Wt, None, pads, st, dl, 1, residual=res)
+    assert lib.onnx_last_launch().startswith("lp_generic")
+    lib.onnx_conv_lp(X, Wt[:32].contiguous(), None, pads, st, dl, 1)
+    assert lib.onnx_last_launch().startswith("lp_generic")
+    if H >= 9:
+        lib.onnx_conv_lp(X, Wt, None, (2, 3, 3, 3), st, dl, 1)
+        assert lib.onnx_last_launch().startswith("lp_generic")
+    torch.cuda.synchronize()
 
 
 CONV1X1_LAYOUT_CASES = [
