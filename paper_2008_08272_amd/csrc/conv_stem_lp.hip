@@ -96,26 +96,28 @@ __global__ __launch_bounds__(STEM_NT) __attribute__((amdgpu_waves_per_eu(4, 4)))
     const int first_row = scalar(wave * sp.rows_per_wave);
     uint32_t first_c, first_pr;
     sp.PRd.divmod((uint32_t)first_row, first_c, first_pr);
-    uint32_t parked[(ROWS * CHUNKS + 1) / 2];
+    typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+    u16x2 parked[(ROWS * CHUNKS + 1) / 2];
     auto fetch = [&](int tile) {
         uint32_t n, band;
         sp.bandsd.divmod((uint32_t)tile, n, band);
         const int ih_first = 2 * (int)band * sp.R - 3;
-        const uint16_t* xn = sp.X + (int64_t)n * STEM_C * sp.H * sp.Wd;
+        // loads through a buffer resource on the image: a value outside it (or of a row this wavefront does not own) is
+        // an out-of-range offset, which reads 0 without a branch, so that all of a tile's loads are in flight together
+        const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>(sp.X) + (int64_t)scalar((int)n) * STEM_C * sp.H * sp.Wd, 0, (int)OOB, RSRC_FLAGS);
         int c = (int)first_c, pr = (int)first_pr;
 #pragma unroll
         for (int ri = 0; ri < ROWS; ++ri) {
             const int ih = ih_first + pr;
             const bool row_ok = ri < sp.rows_per_wave && first_row + ri < rows_total && ih >= 0 && ih < sp.H;      // uniform
-            const uint16_t* src = xn + ((int64_t)c * sp.H + (row_ok ? ih : 0)) * sp.Wd - 3;
+            const int row_first = (c * sp.H + ih) * sp.Wd;                  // element of (c, ih, 0) in the image
 #pragma unroll
             for (int k = 0; k < CHUNKS; ++k) {
-                const int j = lane + 64 * k, iw = j - 3;
-                uint32_t v = 0u;
-                if (row_ok && iw >= 0 && iw < sp.Wd) v = src[j];
+                const int iw = lane + 64 * k - 3;
+                const uint32_t off = (row_ok && iw >= 0 && iw < sp.Wd) ? (uint32_t)(row_first + iw) * 2u : OOB;
                 const int i = ri * CHUNKS + k;
-                if (i & 1) parked[i / 2] |= v << 16;
-                else parked[i / 2] = v;
+                parked[i / 2][i & 1] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rx, (int)off, 0, 0);
             }
             if (++pr == sp.PR) { pr = 0; ++c; }
         }
@@ -128,7 +130,7 @@ __global__ __launch_bounds__(STEM_NT) __attribute__((amdgpu_waves_per_eu(4, 4)))
 #pragma unroll
             for (int k = 0; k < CHUNKS; ++k) {
                 const int j = lane + 64 * k, i = ri * CHUNKS + k;
-                if (row_ok && j < sp.PW) patch[row * sp.PW + j] = (uint16_t)((i & 1) ? parked[i / 2] >> 16 : parked[i / 2] & 0xffffu);
+                if (row_ok && j < sp.PW) patch[row * sp.PW + j] = parked[i / 2][i & 1];
             }
         }
     };
@@ -225,6 +227,7 @@ bool launch_conv_stem_lp(const void* X, const void* W, const float* B, void* Y, 
         g.sW != 2 || g.dH != 1 || g.dW != 1 || g.pT != 3 || g.pL != 3 || g.pB != 3 || g.pR != 3)
         return false;
     if (g.OW < 1 || g.OW > 256 || g.OH < 1 || (int64_t)g.N * g.OH > 0x7fffffffLL) return false;
+    if ((int64_t)STEM_C * g.H * g.W * 2 >= 0x7fffffffLL) return false;          // 32-bit byte offsets inside an image
     StemParams sp;
     sp.X = static_cast<const uint16_t*>(X);
     sp.W = static_cast<const uint16_t*>(W);
