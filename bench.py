@@ -368,13 +368,14 @@ def main():
         t3 = time_call(lambda: lib.onnx_matmul_lp(A16, B16, out=Y16), iters=20, warm=5)
         details["matmul_bf16_proj_8x512x768_x_768x3072"] = dict(timing(t3), tflops=round(2.0 * 8 * 512 * 768 * 3072 / (t3[0] * 1e-3) / 1e12, 1))
         del A16, B16, Y16
-        for cname, xs, ws_, pads in (("conv_bf16_3x3_32x128x28x28", (32, 128, 28, 28), (128, 128, 3, 3), (1, 1, 1, 1)),
-                                     ("conv_bf16_1x1_32x1024x14x14", (32, 1024, 14, 14), (256, 1024, 1, 1), (0, 0, 0, 0))):
+        for cname, xs, ws_, pads, st in (("conv_bf16_3x3_32x128x28x28", (32, 128, 28, 28), (128, 128, 3, 3), (1, 1, 1, 1), (1, 1)),
+                                         ("conv_bf16_1x1_32x1024x14x14", (32, 1024, 14, 14), (256, 1024, 1, 1), (0, 0, 0, 0), (1, 1)),
+                                         ("conv_bf16_stem_7x7s2_32x3x224x224", (32, 3, 224, 224), (64, 3, 7, 7), (3, 3, 3, 3), (2, 2))):
             X16 = torch.randn(*xs, device=dev).to(torch.bfloat16)
             W16 = (torch.randn(*ws_, device=dev) * 0.05).to(torch.bfloat16)
-            yd = lib.onnx_conv_infer(xs, ws_, pads)
+            yd = lib.onnx_conv_infer(xs, ws_, pads, st)
             Y16 = torch.empty(yd, device=dev, dtype=torch.bfloat16)
-            t3 = time_call(lambda: lib.onnx_conv_lp(X16, W16, None, pads, act=1, out=Y16), iters=20, warm=5)
+            t3 = time_call(lambda: lib.onnx_conv_lp(X16, W16, None, pads, st, act=1, out=Y16), iters=20, warm=5)
             fl = 2.0 * Y16.numel() * ws_[1] * ws_[2] * ws_[3]
             details[cname] = dict(timing(t3), tflops=round(fl / (t3[0] * 1e-3) / 1e12, 1))
             del X16, W16, Y16
