@@ -275,9 +275,12 @@ onnx_status onnx_matmul_lp(const void* A, const int64_t* a_dims, int a_rank, con
  * multiple of 16 runs through a kernel that stages the input patch of a tile in LDS, provided
  * the workspace of onnx_set_workspace can hold a rewritten copy of the filter bank
  * (M * C/group * 9 16-bit values; a small kernel ahead of the convolution writes it on every
- * call, so calls that share the workspace on different streams race, as for split-K).  Every
- * other shape runs through one general kernel that gathers the input element by element and
- * uses no workspace.
+ * call, so calls that share the workspace on different streams race, as for split-K).  With a
+ * workspace, strided 1x1 convolutions and pointwise ones whose H*W is not a multiple of 4 are
+ * first copied into a layout the tuned kernel reads.  The first layer of ResNet50 (Section 4.2:
+ * 7x7, stride 2, pads 3, 3 -> 64 channels, no residual, at most 157 output columns) has a
+ * kernel of its own that needs no workspace.  Every other shape runs through one general kernel
+ * that gathers the input element by element and uses no workspace.
  */
 onnx_status onnx_conv_lp(const void* X, const int64_t x_dims[4], const void* W, const int64_t w_dims[4],
                          const float* B, const int64_t pads[4], const int64_t strides[2],
