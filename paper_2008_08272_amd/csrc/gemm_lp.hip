@@ -50,7 +50,11 @@ hipError_t launch_tile(ContractionParams& p, int nz, const Workspace& ws, hipStr
     const double t256 = (double)((p.M + 255) / 256) * (double)((p.N + 255) / 256) * nz;
     const double t128 = (double)((p.M + 127) / 128) * (double)((p.N + 127) / 128) * nz;
     const double c256 = (double)(int64_t)((t256 + cus - 1) / cus) * 65536.0 / 1.0;
-    const double c128 = (t128 / cus < 1.0 ? 1.0 : t128 / cus) * 16384.0 / 0.85;
+    // (1x1 convolutions with K <= 256 are bound by their stores, and the 128 x 128 tile's are the less efficient ones:
+    // ResNet-50's 64 -> 256 at 56 x 56 and 128 / 256 -> 512 at 28 x 28 take 33.6 / 20.0 us on 256 x 256 tiles against
+    // 37.1 / 22.9-23.8)
+    const double eff128 = (p.col_images && p.K <= 256) ? 0.75 : 0.85;
+    const double c128 = (t128 / cus < 1.0 ? 1.0 : t128 / cus) * 16384.0 / eff128;
     // at most 64 rows: a larger tile would be half empty (ResNet-50's 1x1 layers with 64 filters at batch 32: 18.6 -> 12.4
     // and 25.6 -> 18.4 us)
     if (p.M <= 64) return launch_instance<64, 64, 64, 2, 2, DT, LP_OUT, 2, BKIND, BVEC>(p, nz, ws, stream);
